@@ -1,0 +1,351 @@
+"""Pins of the CPU oracle against things other than itself.
+
+The paper prints no worked numeric example for its Eq. (7)-(12), so every pin
+is a closed form, an invariant, a special case that reduces to a textbook or
+library routine, or brute force on tiny inputs.  They are chosen so that a
+plausible slip in the oracle (a dropped term, n instead of n-1, a transposed
+operand, a wrong head mapping, an off-by-one in the key set) fails one of them.
+"""
+import math
+
+import numpy as np
+import pytest
+import scipy.special
+import scipy.stats
+from scipy.spatial.distance import cosine as scipy_cosine_distance
+
+from oracle import actqkv_oracle as orc
+
+RNG = np.random.default_rng(7)
+
+
+# ---------------------------------------------------------------- Sec. 4.1
+def test_hand_example_eq7_to_eq9():
+    # One channel, three queries 0, 1, 2: mean 1, unbiased variance 1,
+    # biases 1, 0, 1, weights 1/2, 0, 1/2, probe = 1.
+    q = np.array([[0.0], [1.0], [2.0]])
+    z, s2 = orc.running_stats_literal(q)
+    assert z[0] == 1.0 and s2[0] == 1.0
+    phi = orc.activation_bias(q, z, s2)
+    assert phi[:, 0].tolist() == [1.0, 0.0, 1.0]
+    probe, w = orc.probe_query(q, phi)
+    assert w.tolist() == [0.5, 0.0, 0.5] and probe[0] == 1.0
+    # Two channels with different spread: the division is per channel.
+    q = np.array([[0.0, 0.0], [2.0, 20.0], [4.0, 10.0]])
+    z, s2 = orc.running_stats_literal(q)
+    assert z.tolist() == [2.0, 10.0] and s2.tolist() == [4.0, 100.0]
+    phi = orc.activation_bias(q, z, s2)
+    assert np.allclose(phi, [[1.0, 1.0], [0.0, 1.0], [1.0, 0.0]])
+    probe, w = orc.probe_query(q, phi)
+    assert np.allclose(w, [0.5, 0.25, 0.25])
+    assert np.allclose(probe, [0.5 * 0 + 0.25 * 2 + 0.25 * 4, 0.25 * 20 + 0.25 * 10])
+
+
+def test_p1_weights_sum_to_one():
+    q = RNG.normal(size=(37, 24))
+    z, s2 = orc.running_stats_literal(q)
+    _, w = orc.probe_query(q, orc.activation_bias(q, z, s2))
+    assert (w >= 0).all() and abs(w.sum() - 1.0) < 1e-14
+
+
+def test_p2_first_window_bias_mass():
+    # At t = 1 every channel's biases sum to m - 1 (unbiased variance), so the
+    # entrywise L1 norm of Phi is (m - 1) * d.  n instead of n - 1 gives m * d.
+    m, d = 29, 12
+    q = RNG.normal(size=(m, d)) * RNG.uniform(0.1, 9.0, size=d) + RNG.normal(size=d)
+    z, s2 = orc.running_stats_literal(q)
+    phi = orc.activation_bias(q, z, s2)
+    assert np.allclose(phi.sum(axis=0), m - 1, rtol=1e-12)
+    assert math.isclose(np.abs(phi).sum(), (m - 1) * d, rel_tol=1e-12)
+
+
+def test_p3_equal_bias_is_mean_pooling():
+    q = RNG.normal(size=(2, 16))
+    z, s2 = orc.running_stats_literal(q)
+    probe, w = orc.probe_query(q, orc.activation_bias(q, z, s2))
+    assert np.allclose(w, 0.5) and np.allclose(probe, q.mean(axis=0))
+    # all-zero bias (identical queries): uniform weights
+    q = np.tile(RNG.normal(size=(1, 8)), (5, 1))
+    z, s2 = orc.running_stats_literal(q)
+    probe, w = orc.probe_query(q, orc.activation_bias(q, z, s2))
+    assert np.allclose(w, 0.2) and np.allclose(probe, q[0])
+
+
+def test_p4_affine_invariance_of_weights():
+    q = RNG.normal(size=(21, 10))
+    alpha = RNG.uniform(0.5, 4.0, size=10) * RNG.choice([-1.0, 1.0], size=10)
+    beta = RNG.normal(size=10) * 3
+    w = []
+    for x in (q, q * alpha + beta):
+        z, s2 = orc.running_stats_literal(x)
+        w.append(orc.probe_query(x, orc.activation_bias(x, z, s2))[1])
+    assert np.allclose(w[0], w[1], rtol=1e-10)
+
+
+def test_outlier_token_dominates_probe():
+    # A token far from the mean gets the largest weight (Eq. (6)'s intent).
+    q = RNG.normal(size=(64, 8))
+    q[17] += 25.0
+    z, s2 = orc.running_stats_literal(q)
+    _, w = orc.probe_query(q, orc.activation_bias(q, z, s2))
+    assert int(np.argmax(w)) == 17 and w[17] > 0.4
+
+
+def test_p5_streaming_stats_match_two_pass():
+    d = 9
+    wins = [RNG.normal(size=(n, d)) * 3 + 5 for n in (16, 16, 16, 7)]
+    st = orc.RunningStats(d)
+    for i, w in enumerate(wins):
+        z, s2 = st.update(w)
+        cat = np.concatenate(wins[: i + 1], axis=0)
+        z_l, s2_l = orc.running_stats_literal(cat)
+        assert np.allclose(z, z_l, rtol=1e-12) and np.allclose(s2, s2_l, rtol=1e-12)
+        assert np.allclose(z_l, np.mean(cat, axis=0))
+        assert np.allclose(s2_l, np.var(cat, axis=0, ddof=1))
+
+
+# ---------------------------------------------------------------- Eq. (10)
+def test_p6_cosine():
+    a, b = RNG.normal(size=40), RNG.normal(size=40)
+    c = orc.cosine(a, b)
+    assert math.isclose(c, 1.0 - scipy_cosine_distance(a, b), rel_tol=1e-12)
+    assert -1.0 <= c <= 1.0
+    assert math.isclose(orc.cosine(3.5 * a, 0.2 * b), c, rel_tol=1e-12)
+    assert math.isclose(orc.cosine(a, -b), -c, rel_tol=1e-12)
+    assert orc.cosine(a, np.zeros(40)) == 0.0
+    assert orc.cosine([1, 0, 0], [0, 2, 0]) == 0.0
+
+
+def test_p6_block_scores_group_mapping():
+    hk, g, d, nb, r = 3, 4, 8, 5, 2
+    rep = RNG.normal(size=(nb, r, hk, d))
+    probe = RNG.normal(size=(hk * g, d))
+    s = orc.block_scores(probe.reshape(-1), rep, g)
+    # independent expansion: query head h reads KV head h // g
+    for b in range(nb):
+        acc = 0.0
+        for j in range(r):
+            k_hat = np.stack([rep[b, j, h // g] for h in range(hk * g)])
+            acc += 1.0 - scipy_cosine_distance(probe.reshape(-1), k_hat.reshape(-1))
+        assert math.isclose(s[b], acc / r, rel_tol=1e-12)
+    assert (np.abs(s) <= 1.0).all()
+    # probe equal across the heads of a group and keys proportional to it: score 1
+    base = RNG.normal(size=(hk, d))
+    probe1 = np.repeat(base, g, axis=0).reshape(-1)
+    rep1 = np.stack([np.stack([base * c for c in (0.5, 7.0)])])
+    assert math.isclose(orc.block_scores(probe1, rep1, g)[0], 1.0, rel_tol=1e-12)
+    # G = 1 is the plain cosine
+    s1 = orc.block_scores(probe[:hk].reshape(-1), rep, 1)
+    assert math.isclose(s1[2], np.mean([1.0 - scipy_cosine_distance(probe[:hk].ravel(),
+                                                                   rep[2, j].ravel())
+                                        for j in range(r)]), rel_tol=1e-12)
+
+
+# ---------------------------------------------------------------- Eq. (11), (12)
+def test_p7_information_density():
+    n = 46
+    assert math.isclose(orc.information_density(np.full(n, 0.3)), math.log(n), rel_tol=1e-13)
+    s = RNG.uniform(-1, 1, size=n)
+    th = orc.information_density(s)
+    assert math.isclose(th, scipy.stats.entropy(scipy.special.softmax(s)), rel_tol=1e-12)
+    assert th < math.log(n) and math.exp(th) <= n
+    # spreading the scores out around their mean lowers the density
+    wide = s.mean() + 3.0 * (s - s.mean())
+    assert orc.information_density(wide) < th
+    # shift invariance
+    assert math.isclose(orc.information_density(s + 0.25), th, rel_tol=1e-12)
+
+
+def test_p8_budgets_telescope():
+    L, k_bar = 32, 46
+    theta = RNG.uniform(2.0, 4.0, size=L)
+    b_kv = float(L * k_bar)
+    budgets = []
+    for l in range(L):
+        rest = float(theta[l + 1:].sum())          # exact driver: mean density = the layer's own
+        b = orc.layer_budget(float(theta[l]), rest, b_kv)
+        budgets.append(b)
+        b_kv -= b
+    budgets = np.array(budgets)
+    assert np.allclose(budgets, L * k_bar * theta / theta.sum(), rtol=1e-10)
+    assert math.isclose(budgets.sum(), L * k_bar, rel_tol=1e-12) and abs(b_kv) < 1e-9
+    # equal densities: every layer gets k_bar
+    b_kv = float(L * k_bar)
+    for l in range(L):
+        b = orc.layer_budget(3.0, 3.0 * (L - 1 - l), b_kv)
+        assert math.isclose(b, k_bar, rel_tol=1e-10)
+        b_kv -= b
+
+
+def test_p9_budget_monotone_in_density():
+    thetas = np.linspace(0.01, 7.0, 200)
+    b = [orc.layer_budget(float(t), 90.0, 640.0) for t in thetas]
+    assert all(x < y for x, y in zip(b, b[1:]))
+    e = [orc.cutoff_count(x, 32, 1000) for x in b]
+    assert all(x <= y for x, y in zip(e, e[1:]))
+    assert orc.cutoff_count(0.2, 32, 1000) == 1          # never fewer than one block
+    assert orc.cutoff_count(99.0, 32, 1000) == 32        # capacity
+    assert orc.cutoff_count(99.0, 32, 5) == 5            # not more than there are
+    assert orc.cutoff_count(6.5, 32, 1000) == 7 and orc.cutoff_count(6.49, 32, 1000) == 6
+
+
+def test_p10_selection_is_a_stable_sort_prefix():
+    for trial in range(50):
+        n = int(RNG.integers(1, 12))
+        s = RNG.integers(0, 4, size=n) / 4.0               # many ties
+        ids = sorted(RNG.choice(100, size=n, replace=False).tolist())
+        # brute force: repeatedly take the best remaining, lowest id on ties
+        remaining = list(zip(s.tolist(), ids))
+        expect = []
+        while remaining:
+            best = max(x[0] for x in remaining)
+            pick = min(i for (v, i) in remaining if v == best)
+            expect.append(pick)
+            remaining = [x for x in remaining if x[1] != pick]
+        for count in range(0, n + 1):
+            assert orc.select_blocks(s, ids, count) == expect[:count]
+    assert sorted(orc.select_blocks(RNG.normal(size=6), list(range(3, 9)), 6)) == list(range(3, 9))
+
+
+# ---------------------------------------------------------------- geometry
+@pytest.mark.parametrize("n_init,n_local,block", [(128, 256, 128), (128, 512, 128), (64, 96, 32),
+                                                  (0, 64, 32), (64, 0, 32)])
+def test_key_set_partition(n_init, n_local, block):
+    # With every eligible block selected, the visible positions of the query at
+    # p are exactly 0..p, each once.
+    for w0 in list(range(0, 9 * block, block)) + [5, block + 3, 7 * block + 17, 2000]:
+        elig = orc.eligible_blocks(w0, n_init, n_local, block)
+        l0 = orc.local_start(w0, n_init, n_local, block)
+        assert min(n_init, w0) <= l0 <= w0
+        assert w0 - l0 < n_local + block or l0 == min(n_init, w0)
+        if w0 - n_local >= n_init:
+            assert w0 - l0 >= n_local
+        for p in (w0, w0 + 1, w0 + block + 1):
+            pos = orc.key_positions(w0, p, elig, n_init, n_local, block)
+            assert sorted(pos) == list(range(p + 1))
+
+
+# ---------------------------------------------------------------- attention
+def _dense_causal_attention(q, k, v):
+    """Textbook causal attention, one query at a time: q [N][H][D], k, v [N][Hk][D]."""
+    n, h_n, d = q.shape
+    g = h_n // k.shape[1]
+    out = np.zeros((n, h_n, d))
+    for p in range(n):
+        for h in range(h_n):
+            logits = np.array([np.dot(q[p, h], k[i, h // g]) for i in range(p + 1)]) / math.sqrt(d)
+            pr = scipy.special.softmax(logits)
+            out[p, h] = sum(pr[i] * v[i, h // g] for i in range(p + 1))
+    return out
+
+
+@pytest.mark.parametrize("fast", [False, True])
+def test_p11_select_all_is_dense_causal_attention(fast):
+    n, h_n, hk, d, m, block, n_init, n_local, r = 96, 4, 2, 8, 16, 8, 8, 16, 2
+    q = RNG.normal(size=(n, h_n, d))
+    k = RNG.normal(size=(n, hk, d))
+    v = RNG.normal(size=(n, hk, d))
+    rep = k[: (n // block) * block].reshape(n // block, block, hk, d)[:, :r]
+    res = orc.prefill_layer(q, k, v, rep, m, n_init, n_local, block, k_cap=10 ** 6,
+                            fast_attention=fast)
+    got = np.concatenate([w["out"] for w in res], axis=0)
+    want = _dense_causal_attention(q, k, v)
+    assert np.abs(got - want).max() < 1e-13
+    # the last windows do have eligible blocks, and all of them were taken
+    assert res[-1]["idx"] and sorted(res[-1]["idx"]) == res[-1]["eligible"]
+
+
+def test_p11_decode_select_all_is_last_row_of_dense():
+    n, h_n, hk, d, block, n_init, n_local, r = 75, 4, 2, 8, 8, 8, 16, 2
+    q = RNG.normal(size=(n, h_n, d))
+    k = RNG.normal(size=(n, hk, d))
+    v = RNG.normal(size=(n, hk, d))
+    rep = k[: (n // block) * block].reshape(n // block, block, hk, d)[:, :r]
+    res = orc.decode_step(q[-1], k, v, rep, n, n_init, n_local, block, k_cap=10 ** 6)
+    want = _dense_causal_attention(q, k, v)[-1]
+    assert np.abs(res["out"] - want).max() < 1e-13
+
+
+def test_p12_attention_rows():
+    n, hk, d = 40, 2, 8
+    k = RNG.normal(size=(n, hk, d))
+    v = RNG.normal(size=(n, hk, d))
+    q = RNG.normal(size=(3, 4, d))
+    # one visible key: the output is its value
+    o = orc.attention_rows(q, k, v, [11], group=2)
+    assert np.allclose(o[:, 0], v[11, 0]) and np.allclose(o[:, 3], v[11, 1])
+    # constant values: probabilities sum to one
+    vc = np.tile(RNG.normal(size=(1, hk, d)), (n, 1, 1))
+    o = orc.attention_rows(q, k, vc, list(range(n)), group=2)
+    assert np.allclose(o[:, 1], vc[0, 0]) and np.allclose(o[:, 2], vc[0, 1])
+    # the order of the gathered keys does not matter
+    a = orc.attention_rows(q, k, v, [3, 4, 5, 20, 21], group=2)
+    b = orc.attention_rows(q, k, v, [21, 3, 20, 5, 4], group=2)
+    assert np.allclose(a, b, rtol=1e-12)
+    # a key with a much larger logit takes all the mass
+    k2 = k.copy()
+    k2[7, 0] = 200.0 * q[0, 0] / np.linalg.norm(q[0, 0])
+    o = orc.attention_rows(q[:1], k2, v, list(range(n)), group=2)
+    assert np.allclose(o[0, 0], v[7, 0], atol=1e-9)
+
+
+def test_window_attention_forms_agree_with_selection():
+    n, h_n, hk, d, m, block, n_init, n_local = 160, 4, 2, 8, 16, 8, 8, 16
+    q = RNG.normal(size=(n, h_n, d))
+    k = RNG.normal(size=(n, hk, d))
+    v = RNG.normal(size=(n, hk, d))
+    w0 = 128
+    sel = [9, 3, 5]
+    a = orc.retrieval_attention(q[w0:w0 + m], k, v, w0, sel, n_init, n_local, block, 2)
+    b = orc.retrieval_attention_window(q[w0:w0 + m], k, v, w0, sel, n_init, n_local, block, 2)
+    assert np.abs(a - b).max() < 1e-13
+    # hidden blocks really are hidden: changing an unselected, non-local block changes nothing
+    k2, v2 = k.copy(), v.copy()
+    k2[4 * block:5 * block] += 3.0
+    v2[4 * block:5 * block] -= 2.0
+    c = orc.retrieval_attention(q[w0:w0 + m], k2, v2, w0, sel, n_init, n_local, block, 2)
+    assert np.abs(a - c).max() == 0.0
+
+
+# ---------------------------------------------------------------- end to end
+def test_p13_planted_blocks_are_retrieved():
+    n, h_n, hk, d, m, block, n_init, n_local, r = 2048, 4, 2, 16, 64, 32, 32, 64, 4
+    g = h_n // hk
+    u = RNG.normal(size=(hk, d))
+    u /= np.linalg.norm(u)
+    q = RNG.normal(size=(n, h_n, d))
+    k = RNG.normal(size=(n, hk, d))
+    v = RNG.normal(size=(n, hk, d))
+    outl = RNG.uniform(size=n) < 0.05
+    q[outl] += 12.0 * np.repeat(u, g, axis=0)
+    planted = [3, 11, 17, 30]
+    for b in planted:
+        k[b * block:(b + 1) * block] += 4.0 * u
+    rep = k.reshape(n // block, block, hk, d)[:, :r]
+    res = orc.prefill_layer(q, k, v, rep, m, n_init, n_local, block, k_cap=4, attend=[])
+    last = res[-1]
+    assert sorted(last["idx"]) == planted
+    assert last["theta"] < math.log(len(last["eligible"]))
+
+
+def test_cutoff_path_and_budget_bookkeeping():
+    n, h_n, hk, d, m, block, n_init, n_local, r = 1024, 4, 2, 16, 64, 32, 32, 64, 2
+    q = RNG.normal(size=(n, h_n, d))
+    k = RNG.normal(size=(n, hk, d))
+    v = RNG.normal(size=(n, hk, d))
+    rep = k.reshape(n // block, block, hk, d)[:, :r]
+    cut = [(40.0, 30.0)] * (n // m)
+    res = orc.prefill_layer(q, k, v, rep, m, n_init, n_local, block, k_cap=8, cutoffs=cut,
+                            attend=[])
+    for w in res:
+        ne = len(w["eligible"])
+        if ne == 0:
+            assert w["count"] == 0 and w["idx"] == []
+            continue
+        b = w["theta"] / (w["theta"] + 30.0) * 40.0
+        assert math.isclose(w["budget"], b, rel_tol=1e-12)
+        assert math.isclose(w["b_kv_after"], 40.0 - b, rel_tol=1e-12)
+        assert w["count"] == min(8, ne, max(1, math.floor(b + 0.5))) == len(w["idx"])
+        top = np.sort(w["scores"])[::-1][: w["count"]]
+        got = [w["scores"][w["eligible"].index(i)] for i in w["idx"]]
+        assert np.allclose(got, top)
