@@ -1,0 +1,185 @@
+/*
+ * actqkv.h - C ABI of the ActQKV per-layer retrieval-attention path for MI355X (gfx950).
+ *
+ * One layer, one context window (prefill) or one new token (decode) per call chain:
+ *
+ *   actqkv_build_probe   Activation Bias and probe-Query      (Sec. 4.1, Eq. (7)-(9))
+ *   actqkv_score_blocks  cosine scores of the KV blocks       (Sec. 3.2 Eq. (5), Sec. 4.2 Eq. (10))
+ *   actqkv_select        information density, budget, top-E   (Sec. 4.2 Eq. (11)-(12), Alg. 1)
+ *   actqkv_retrieval_attention  attention over initial tokens, retrieved blocks,
+ *                        local span and the window itself     (Sec. 3.1 Eq. (2)-(3))
+ *
+ * Conventions shared by every call
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or keeps a pointer beyond the call; scratch memory
+ *     comes from the caller's workspace (actqkv_workspace_bytes sizes it).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A
+ *     call only enqueues kernels: no device synchronisation, no read-back.  The
+ *     number of selected blocks, their indices and the cut-off budget stay on
+ *     the device between the calls.
+ *   - Pointers to q, the caches, rep_keys, stats, probe, probe_kv, out and the
+ *     workspace must be 16-byte aligned (they are read with 16-byte loads);
+ *     per-sequence arrays (n_ctx, nb_end, n_sel, idx, scores, theta, budget,
+ *     probe_norm, weights, lse) need 4-byte and cutoff 8-byte alignment.
+ *   - Return value: ACTQKV_OK, or a negative error code.  Arguments are checked
+ *     on the host before anything is launched; on error nothing has been
+ *     enqueued.  actqkv_last_error() gives a thread-local message.  Nothing
+ *     throws or aborts across this boundary.
+ *   - Values that live on the device (n_ctx, nb_end, idx, n_sel) cannot be
+ *     checked by the host; kernels clamp them to the stated capacities, so a
+ *     wrong value gives a wrong result but no out-of-bounds access.
+ *   - Layouts are row-major with the last index fastest.  "storage dtype" is
+ *     shape->dtype: fp32, or bf16 with fp32 accumulation.
+ *
+ * Blocked KV cache (per sequence; block b holds tokens [b*Bs, (b+1)*Bs)):
+ *     k_cache  [nb_capacity][Hk][Bs][D]     keys, token-major inside a block
+ *     v_cache  [nb_capacity][Hk][D][Bs]     values, TRANSPOSED inside a block
+ *     rep_keys [nb_capacity][r][Hk][D]      r representative keys per block
+ *   Values are stored channel-major so that a block's tile is a ready matrix-core
+ *   operand for P*V without any transposition on the hot path.  Cache memory
+ *   past the last valid token of a partial block must hold finite numbers
+ *   (zero-fill the cache once); it is masked, never trusted.
+ */
+#ifndef ACTQKV_H
+#define ACTQKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ACTQKV_VERSION 100
+
+enum {
+  ACTQKV_OK = 0,
+  ACTQKV_EINVAL = -1,     /* null pointer, negative or inconsistent argument */
+  ACTQKV_ESHAPE = -2,     /* H/Hk/D/Bs/r/m/k_cap combination not supported   */
+  ACTQKV_EALIGN = -3,     /* a tensor pointer is not 16-byte aligned          */
+  ACTQKV_EWORKSPACE = -4, /* workspace missing or too small                   */
+  ACTQKV_EHIP = -5        /* a HIP call or kernel launch failed               */
+};
+
+enum { ACTQKV_F32 = 0, ACTQKV_BF16 = 1 };
+
+/* Limits checked by every call (ACTQKV_ESHAPE otherwise):
+ *   head_dim in {64, 128}; n_q_heads a multiple of n_kv_heads, group size
+ *   n_q_heads/n_kv_heads in {1, 2, 4, 8}; block_size == 128; 1 <= n_rep <= 16;
+ *   n_init and n_local multiples of block_size (0 allowed);
+ *   1 <= k_cap <= 64; at most 8192 blocks take part in one selection. */
+typedef struct actqkv_shape {
+  int32_t n_q_heads;     /* H                                              */
+  int32_t n_kv_heads;    /* Hk                                             */
+  int32_t head_dim;      /* D                                              */
+  int32_t block_size;    /* Bs, tokens per KV block                        */
+  int32_t n_rep;         /* r, representative keys per block               */
+  int32_t n_init;        /* initial tokens that are always attended        */
+  int32_t n_local;       /* tokens before the window that are always attended */
+  int32_t dtype;         /* ACTQKV_F32 or ACTQKV_BF16 (storage of q, k, v, rep_keys, out) */
+  float softmax_scale;   /* 0 means 1/sqrt(D)                              */
+  float var_eps;         /* floor of the variance in Eq. (7); 0 means 1e-12 */
+} actqkv_shape;
+
+/* Dynamic cut-off state of one sequence (device memory, Sec. 4.2):
+ *   budget_remaining  B_kv, in blocks; actqkv_select subtracts B^l from it
+ *   theta_rest_sum    R = sum over the layers still to come of their mean density */
+typedef struct actqkv_cutoff {
+  float budget_remaining;
+  float theta_rest_sum;
+} actqkv_cutoff;
+
+/* Number of floats of running statistics per sequence: {n, pad[3], mean[d], m2[d]},
+ * d = H*D.  n is the number of queries seen, mean their per-channel mean, m2 the
+ * per-channel sum of squared deviations from it (Eq. (8) is mean and m2/(n-1)).
+ * Zero-fill it before the first window. */
+size_t actqkv_stats_floats(const actqkv_shape* shape);
+
+/* Bytes of workspace that any of the calls below may need for these sizes.  The
+ * workspace must be zero-filled once after allocation (the kernels leave the
+ * counters it holds at zero); calls sharing one workspace must be ordered on
+ * one stream. */
+size_t actqkv_workspace_bytes(const actqkv_shape* shape, int batch, int m, int nb_capacity,
+                              int k_cap);
+
+/* Activation Bias and probe-Query of one window per sequence (Sec. 4.1).
+ *   q_win   [batch][m][H][D], storage dtype: the window's queries.
+ *   stats   [batch][actqkv_stats_floats] fp32.  update_stats != 0: the window is
+ *           merged into it first, so mean and variance cover every query up to
+ *           and including this window (Eq. (8)); == 0: used as it is.
+ *   For each token j: phi_j = (q_j - mean)^2 / max(var, eps) per channel (Eq. (7));
+ *   weight_j = |phi_j|_1 / sum_j |phi_j|_1 (uniform if the sum is 0);
+ *   probe = sum_j weight_j q_j (Eq. (9)).  m == 1 gives probe = q (Sec. 4.2, decode).
+ * Outputs (fp32):
+ *   probe      [batch][H*D]
+ *   probe_kv   [batch][Hk*D]  probe summed over the G query heads of each KV head
+ *   probe_norm [batch]        L2 norm of probe
+ *   weights    [batch][m]     may be NULL
+ * Errors: EINVAL (null, batch < 1, m < 1), ESHAPE, EALIGN, EWORKSPACE. */
+int actqkv_build_probe(const actqkv_shape* shape, int batch, int m, const void* q_win,
+                       float* stats, int update_stats, float* probe, float* probe_kv,
+                       float* probe_norm, float* weights, void* workspace, size_t ws_bytes,
+                       void* stream);
+
+/* Block scores (Eq. (10), applied to a block's representative keys; Eq. (5)).
+ *   rep_keys  [batch][nb_capacity][r][Hk][D], storage dtype; seq_stride = elements
+ *             between two sequences.
+ *   nb_end    device int32 [batch]: blocks nb_begin <= b < nb_end[s] are scored
+ *             (clamped to nb_capacity); other entries of `scores` are left alone.
+ *   scores    [batch][score_stride] fp32, score_stride >= nb_capacity:
+ *             scores[s][b] = mean over the r keys of cos(probe, key repeated to the
+ *             H query heads) = mean_j  <probe_kv, k_j> / (probe_norm * sqrt(G) * |k_j|),
+ *             0 where a norm is 0. */
+int actqkv_score_blocks(const actqkv_shape* shape, int batch, const float* probe_kv,
+                        const float* probe_norm, const void* rep_keys, int64_t seq_stride,
+                        int nb_capacity, int nb_begin, const int32_t* nb_end, float* scores,
+                        int64_t score_stride, void* stream);
+
+/* Information density, budget and selection (Eq. (11), (12), Alg. 1) over the
+ * eligible blocks nb_begin <= b < nb_end[s] of each sequence.
+ *   theta = entropy (natural log) of softmax(scores over the eligible blocks).
+ *   cutoff == NULL: E = min(k_cap, n_eligible); budget is reported as E.
+ *   cutoff != NULL (device, [batch]): B = theta / (theta + theta_rest_sum) * budget_remaining
+ *           (B = budget_remaining if the denominator is 0);
+ *           E = min(k_cap, n_eligible, max(1, floor(B + 0.5)));
+ *           budget_remaining -= B.
+ *   idx     [batch][k_cap] int32: the E best blocks, best first, equal scores by
+ *           ascending block index; unused entries are -1.
+ *   n_sel   [batch] int32 = E (0 when nothing is eligible; theta and budget are 0 then
+ *           and budget_remaining is left alone).
+ *   theta, budget  [batch] fp32, may be NULL. */
+int actqkv_select(int batch, const float* scores, int64_t score_stride, int nb_capacity,
+                  int nb_begin, const int32_t* nb_end, int k_cap, actqkv_cutoff* cutoff,
+                  int32_t* idx, int32_t* n_sel, float* theta, float* budget, void* stream);
+
+/* Attention of a window over [current window, selected cache] (Eq. (2); Eq. (3) for m == 1).
+ *   q        [batch][m][H][D], storage dtype.
+ *   k_cache, v_cache  blocked caches (layouts above), seq_stride = elements between
+ *            two sequences; they already hold the window's own keys and values.
+ *   n_ctx    device int32 [batch]: valid tokens in the cache, the m current ones
+ *            included; the window is [w0, w0+m) with w0 = n_ctx - m.
+ *   idx, n_sel  from actqkv_select ([batch][k_cap], [batch]); entries outside
+ *            [0, nb_capacity) are ignored.  The caller keeps selected blocks disjoint
+ *            from the initial tokens and the local span (actqkv_select on the
+ *            eligible range guarantees it).
+ *   The query at position p sees: tokens [0, min(n_init, w0)); the selected blocks;
+ *   [l0, p] with l0 = max(min(n_init, w0), (w0 - n_local) rounded down to a block
+ *   boundary).  Query head h reads KV head h / G.  out = softmax(q K^T scale) V.
+ *   out      [batch][m][H][D], storage dtype.
+ *   lse      [batch][H][m] fp32, natural-log sum of exp of the scaled logits; may be NULL. */
+int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, const void* q,
+                               const void* k_cache, const void* v_cache, int64_t seq_stride,
+                               int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
+                               const int32_t* n_sel, int k_cap, void* out, float* lse,
+                               void* workspace, size_t ws_bytes, void* stream);
+
+/* Message of the last error on this thread ("" if none). */
+const char* actqkv_last_error(void);
+
+/* ACTQKV_VERSION of the built library. */
+int actqkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ACTQKV_H */

@@ -1,0 +1,158 @@
+"""Thin ctypes binding of libactqkv.so: same names as the C ABI, argument
+marshalling only.  Tensors are torch tensors on the GPU (torch is used for
+device memory and streams, nothing else); every step runs in the library's
+kernels.  There is no fallback: if the library is missing or a call fails, an
+exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+from .synth import LayerShape
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libactqkv.so")
+
+ACTQKV_F32, ACTQKV_BF16 = 0, 1
+ERROR_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EALIGN", -4: "EWORKSPACE", -5: "EHIP"}
+
+
+class ActQKVError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"actqkv error {ERROR_NAMES.get(code, code)}: {message}")
+        self.code = code
+
+
+class CShape(ctypes.Structure):
+    _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32),
+                ("n_rep", ctypes.c_int32), ("n_init", ctypes.c_int32),
+                ("n_local", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float), ("var_eps", ctypes.c_float)]
+
+
+def c_shape(s: LayerShape, softmax_scale: float = 0.0, var_eps: float = 0.0) -> CShape:
+    return CShape(s.n_q_heads, s.n_kv_heads, s.head_dim, s.block_size, s.n_rep, s.n_init,
+                  s.n_local, ACTQKV_F32 if s.dtype == "fp32" else ACTQKV_BF16,
+                  softmax_scale, var_eps)
+
+
+_lib = None
+
+_vp, _i, _i64, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+_shp = ctypes.POINTER(CShape)
+SIGNATURES = {
+    "actqkv_stats_floats": (_sz, [_shp]),
+    "actqkv_workspace_bytes": (_sz, [_shp, _i, _i, _i, _i]),
+    "actqkv_build_probe": (_i, [_shp, _i, _i, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "actqkv_score_blocks": (_i, [_shp, _i, _vp, _vp, _vp, _i64, _i, _i, _vp, _vp, _i64, _vp]),
+    "actqkv_select": (_i, [_i, _vp, _i64, _i, _i, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "actqkv_retrieval_attention": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
+                                        _vp, _vp, _vp, _sz, _vp]),
+    "actqkv_last_error": (ctypes.c_char_p, []),
+    "actqkv_version": (_i, []),
+}
+
+
+def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
+    """Loads libactqkv.so (building it first if it has never been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise FileNotFoundError(LIB_PATH)
+        from .build import build
+        build()
+    lib = ctypes.CDLL(LIB_PATH)
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise ActQKVError(rc, load_library().actqkv_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ActQKVError(-1, "tensor is not on the GPU")
+    if not t.is_contiguous():
+        raise ActQKVError(-1, "tensor is not contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ActQKVError(-1, f"tensor dtype {t.dtype}, expected {dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def version() -> int:
+    return load_library().actqkv_version()
+
+
+def last_error() -> str:
+    return load_library().actqkv_last_error().decode()
+
+
+def stats_floats(shape: CShape) -> int:
+    return load_library().actqkv_stats_floats(ctypes.byref(shape))
+
+
+def workspace_bytes(shape: CShape, batch: int, m: int, nb_capacity: int, k_cap: int) -> int:
+    n = load_library().actqkv_workspace_bytes(ctypes.byref(shape), batch, m, nb_capacity, k_cap)
+    if n == 0:
+        raise ActQKVError(-1, last_error())
+    return n
+
+
+def build_probe(shape: CShape, batch: int, m: int, q_win, stats, update_stats: bool, probe, probe_kv,
+                probe_norm, weights, workspace, stream=None) -> None:
+    st = torch.float32 if shape.dtype == ACTQKV_F32 else torch.bfloat16
+    _check(load_library().actqkv_build_probe(
+        ctypes.byref(shape), batch, m, _ptr(q_win, st), _ptr(stats, torch.float32),
+        int(bool(update_stats)), _ptr(probe, torch.float32), _ptr(probe_kv, torch.float32),
+        _ptr(probe_norm, torch.float32), _ptr(weights, torch.float32), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def score_blocks(shape: CShape, batch: int, probe_kv, probe_norm, rep_keys, seq_stride: int,
+                 nb_capacity: int, nb_begin: int, nb_end, scores, score_stride: int,
+                 stream=None) -> None:
+    st = torch.float32 if shape.dtype == ACTQKV_F32 else torch.bfloat16
+    _check(load_library().actqkv_score_blocks(
+        ctypes.byref(shape), batch, _ptr(probe_kv, torch.float32), _ptr(probe_norm, torch.float32),
+        _ptr(rep_keys, st), seq_stride, nb_capacity, nb_begin, _ptr(nb_end, torch.int32),
+        _ptr(scores, torch.float32), score_stride, _stream(stream)))
+
+
+def select(batch: int, scores, score_stride: int, nb_capacity: int, nb_begin: int, nb_end,
+           k_cap: int, cutoff, idx, n_sel, theta=None, budget=None, stream=None) -> None:
+    _check(load_library().actqkv_select(
+        batch, _ptr(scores, torch.float32), score_stride, nb_capacity, nb_begin,
+        _ptr(nb_end, torch.int32), k_cap, _ptr(cutoff, torch.float32), _ptr(idx, torch.int32),
+        _ptr(n_sel, torch.int32), _ptr(theta, torch.float32), _ptr(budget, torch.float32),
+        _stream(stream)))
+
+
+def retrieval_attention(shape: CShape, batch: int, m: int, q, k_cache, v_cache, seq_stride: int,
+                        nb_capacity: int, n_ctx, idx, n_sel, k_cap: int, out, lse, workspace,
+                        stream=None) -> None:
+    st = torch.float32 if shape.dtype == ACTQKV_F32 else torch.bfloat16
+    _check(load_library().actqkv_retrieval_attention(
+        ctypes.byref(shape), batch, m, _ptr(q, st), _ptr(k_cache, st), _ptr(v_cache, st),
+        seq_stride, nb_capacity, _ptr(n_ctx, torch.int32), _ptr(idx, torch.int32),
+        _ptr(n_sel, torch.int32), k_cap, _ptr(out, st), _ptr(lse, torch.float32),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))

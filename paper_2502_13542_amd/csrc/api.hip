@@ -1,0 +1,262 @@
+// C ABI of the library: host-side argument checks, then one launcher per entry point.
+// The checks need no GPU, so every error path can be exercised on a CPU-only machine.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "launch.h"
+
+namespace actqkv {
+
+static thread_local char g_error[512] = "";
+
+int set_error(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int hip_status(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return ACTQKV_OK;
+  return set_error(ACTQKV_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int check_shape(const actqkv_shape* sh) {
+  if (sh == nullptr) return set_error(ACTQKV_EINVAL, "shape is NULL");
+  if (sh->n_q_heads < 1 || sh->n_kv_heads < 1 || sh->head_dim < 1 || sh->n_rep < 1 ||
+      sh->n_init < 0 || sh->n_local < 0)
+    return set_error(ACTQKV_EINVAL, "shape has a non-positive field");
+  if (sh->dtype != ACTQKV_F32 && sh->dtype != ACTQKV_BF16)
+    return set_error(ACTQKV_EINVAL, "dtype %d is neither ACTQKV_F32 nor ACTQKV_BF16", sh->dtype);
+  if (!(sh->softmax_scale >= 0.f) || !(sh->var_eps >= 0.f))
+    return set_error(ACTQKV_EINVAL, "softmax_scale and var_eps must be >= 0");
+  if (sh->head_dim != 64 && sh->head_dim != 128)
+    return set_error(ACTQKV_ESHAPE, "head_dim %d not supported (64 or 128)", sh->head_dim);
+  if (sh->n_q_heads % sh->n_kv_heads != 0)
+    return set_error(ACTQKV_ESHAPE, "n_q_heads %d is not a multiple of n_kv_heads %d", sh->n_q_heads,
+                     sh->n_kv_heads);
+  const int g = sh->n_q_heads / sh->n_kv_heads;
+  if (g != 1 && g != 2 && g != 4 && g != 8)
+    return set_error(ACTQKV_ESHAPE, "group size %d not supported (1, 2, 4, 8)", g);
+  if (sh->block_size != 128)
+    return set_error(ACTQKV_ESHAPE, "block_size %d not supported (128)", sh->block_size);
+  if (sh->n_rep > 16) return set_error(ACTQKV_ESHAPE, "n_rep %d not supported (1..16)", sh->n_rep);
+  if (sh->n_init % sh->block_size != 0 || sh->n_local % sh->block_size != 0)
+    return set_error(ACTQKV_ESHAPE, "n_init and n_local must be multiples of block_size");
+  if (sh->n_q_heads * sh->head_dim > 16384)
+    return set_error(ACTQKV_ESHAPE, "H*D = %d not supported (at most 16384)",
+                     sh->n_q_heads * sh->head_dim);
+  return ACTQKV_OK;
+}
+
+static int check_batch(int batch) {
+  if (batch < 1) return set_error(ACTQKV_EINVAL, "batch %d < 1", batch);
+  if (batch > kMaxBatch) return set_error(ACTQKV_ESHAPE, "batch %d > %d", batch, kMaxBatch);
+  return ACTQKV_OK;
+}
+
+static int check_blocks(int nb_capacity, int nb_begin, int k_cap, bool use_k) {
+  if (nb_capacity < 0 || nb_begin < 0)
+    return set_error(ACTQKV_EINVAL, "nb_capacity %d or nb_begin %d negative", nb_capacity, nb_begin);
+  if (use_k && (k_cap < 1 || k_cap > 64))
+    return set_error(ACTQKV_ESHAPE, "k_cap %d not supported (1..64)", k_cap);
+  if (nb_capacity - nb_begin > 8192)
+    return set_error(ACTQKV_ESHAPE, "%d blocks in one selection (at most 8192)",
+                     nb_capacity - nb_begin);
+  return ACTQKV_OK;
+}
+
+#define ACTQKV_REQUIRE_PTR(p)                                                       \
+  do {                                                                              \
+    if ((p) == nullptr) return set_error(ACTQKV_EINVAL, #p " is NULL");             \
+    if (!aligned16(p)) return set_error(ACTQKV_EALIGN, #p " is not 16-byte aligned"); \
+  } while (0)
+#define ACTQKV_REQUIRE_SMALL(p, a)                                                          \
+  do {                                                                                      \
+    if ((p) == nullptr) return set_error(ACTQKV_EINVAL, #p " is NULL");                     \
+    if ((reinterpret_cast<uintptr_t>(p) & ((a)-1)) != 0)                                    \
+      return set_error(ACTQKV_EALIGN, #p " is not %d-byte aligned", int(a));                \
+  } while (0)
+#define ACTQKV_OPTIONAL_SMALL(p, a)                                                         \
+  do {                                                                                      \
+    if ((p) != nullptr && (reinterpret_cast<uintptr_t>(p) & ((a)-1)) != 0)                  \
+      return set_error(ACTQKV_EALIGN, #p " is not %d-byte aligned", int(a));                \
+  } while (0)
+#define ACTQKV_OPTIONAL_PTR(p)                                                                   \
+  do {                                                                                           \
+    if ((p) != nullptr && !aligned16(p)) return set_error(ACTQKV_EALIGN, #p " is not 16-byte aligned"); \
+  } while (0)
+#define ACTQKV_TRY(expr)      \
+  do {                        \
+    int rc_ = (expr);         \
+    if (rc_ != ACTQKV_OK) return rc_; \
+  } while (0)
+
+int prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap) {
+  (void)sh; (void)batch; (void)m; (void)k_cap;
+  return 1;
+}
+int decode_splits(const actqkv_shape& sh, int batch, int k_cap) {
+  (void)sh; (void)batch; (void)k_cap;
+  return 1;
+}
+
+size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap) {
+  (void)nb_capacity;
+  size_t probe = size_t(batch) * probe_scratch_floats(sh, m) * sizeof(float);
+  int splits = m == 1 ? decode_splits(sh, batch, k_cap) : prefill_splits(sh, batch, m, k_cap);
+  size_t attn = attn_scratch_floats(sh, batch, m, splits) * sizeof(float);
+  return kCounterBytes + align_up(probe > attn ? probe : attn, 256);
+}
+
+int launch_attention_rows(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
+                          const void* v_cache, int64_t seq_stride, int nb_capacity,
+                          const int32_t* n_ctx, const int32_t* idx, const int32_t* n_sel, int k_cap,
+                          void* out, float* lse, float scale, hipStream_t stream);
+
+int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
+                     const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
+                     const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
+                     const Workspace& ws, hipStream_t stream) {
+  (void)ws;
+  const float scale = sh.softmax_scale > 0.f ? sh.softmax_scale : 1.f / std::sqrt(float(sh.head_dim));
+  return launch_attention_rows(sh, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx,
+                               n_sel, k_cap, out, lse, scale, stream);
+}
+
+}  // namespace actqkv
+
+using namespace actqkv;
+
+extern "C" {
+
+size_t actqkv_stats_floats(const actqkv_shape* shape) {
+  if (check_shape(shape) != ACTQKV_OK) return 0;
+  return stats_floats(*shape);
+}
+
+size_t actqkv_workspace_bytes(const actqkv_shape* shape, int batch, int m, int nb_capacity, int k_cap) {
+  if (check_shape(shape) != ACTQKV_OK) return 0;
+  if (batch < 1 || batch > kMaxBatch || m < 1 || nb_capacity < 0 || k_cap < 1 || k_cap > 64) {
+    set_error(ACTQKV_EINVAL, "workspace_bytes: bad batch/m/nb_capacity/k_cap");
+    return 0;
+  }
+  return workspace_bytes(*shape, batch, m, nb_capacity, k_cap);
+}
+
+int actqkv_build_probe(const actqkv_shape* shape, int batch, int m, const void* q_win, float* stats,
+                       int update_stats, float* probe, float* probe_kv, float* probe_norm,
+                       float* weights, void* workspace, size_t ws_bytes, void* stream) {
+  ACTQKV_TRY(check_shape(shape));
+  ACTQKV_TRY(check_batch(batch));
+  if (m < 1) return set_error(ACTQKV_EINVAL, "m %d < 1", m);
+  if (m > 65536) return set_error(ACTQKV_ESHAPE, "m %d > 65536", m);
+  ACTQKV_REQUIRE_PTR(q_win);
+  ACTQKV_REQUIRE_PTR(probe);
+  ACTQKV_REQUIRE_PTR(probe_kv);
+  ACTQKV_REQUIRE_SMALL(probe_norm, 4);
+  ACTQKV_OPTIONAL_SMALL(weights, 4);
+  if (m > 1 || update_stats) ACTQKV_REQUIRE_PTR(stats);
+  if (workspace == nullptr || !aligned16(workspace))
+    return set_error(ACTQKV_EWORKSPACE, "workspace is NULL or not 16-byte aligned");
+  size_t need = kCounterBytes + size_t(batch) * probe_scratch_floats(*shape, m) * sizeof(float);
+  if (ws_bytes < need)
+    return set_error(ACTQKV_EWORKSPACE, "workspace has %zu bytes, build_probe needs %zu", ws_bytes, need);
+  Workspace ws{workspace, ws_bytes};
+  return launch_probe(*shape, batch, m, q_win, stats, update_stats, probe, probe_kv, probe_norm,
+                      weights, ws, static_cast<hipStream_t>(stream));
+}
+
+int actqkv_score_blocks(const actqkv_shape* shape, int batch, const float* probe_kv,
+                        const float* probe_norm, const void* rep_keys, int64_t seq_stride,
+                        int nb_capacity, int nb_begin, const int32_t* nb_end, float* scores,
+                        int64_t score_stride, void* stream) {
+  ACTQKV_TRY(check_shape(shape));
+  ACTQKV_TRY(check_batch(batch));
+  ACTQKV_TRY(check_blocks(nb_capacity, nb_begin, 1, false));
+  ACTQKV_REQUIRE_PTR(probe_kv);
+  ACTQKV_REQUIRE_SMALL(probe_norm, 4);
+  ACTQKV_REQUIRE_PTR(rep_keys);
+  ACTQKV_REQUIRE_SMALL(nb_end, 4);
+  ACTQKV_REQUIRE_SMALL(scores, 4);
+  if (score_stride < nb_capacity)
+    return set_error(ACTQKV_EINVAL, "score_stride %lld < nb_capacity %d", (long long)score_stride,
+                     nb_capacity);
+  const int64_t per_seq = int64_t(nb_capacity) * shape->n_rep * shape->n_kv_heads * shape->head_dim;
+  if (batch > 1 && seq_stride < per_seq)
+    return set_error(ACTQKV_EINVAL, "seq_stride %lld < one sequence's representative keys %lld",
+                     (long long)seq_stride, (long long)per_seq);
+  if (seq_stride % 8 != 0) return set_error(ACTQKV_EALIGN, "seq_stride must be a multiple of 8 elements");
+  return launch_score(*shape, batch, probe_kv, probe_norm, rep_keys, seq_stride, nb_capacity, nb_begin,
+                      nb_end, scores, score_stride, static_cast<hipStream_t>(stream));
+}
+
+int actqkv_select(int batch, const float* scores, int64_t score_stride, int nb_capacity, int nb_begin,
+                  const int32_t* nb_end, int k_cap, actqkv_cutoff* cutoff, int32_t* idx,
+                  int32_t* n_sel, float* theta, float* budget, void* stream) {
+  ACTQKV_TRY(check_batch(batch));
+  ACTQKV_TRY(check_blocks(nb_capacity, nb_begin, k_cap, true));
+  ACTQKV_REQUIRE_SMALL(scores, 4);
+  ACTQKV_REQUIRE_SMALL(nb_end, 4);
+  ACTQKV_REQUIRE_SMALL(idx, 4);
+  ACTQKV_REQUIRE_SMALL(n_sel, 4);
+  ACTQKV_OPTIONAL_SMALL(cutoff, 8);
+  ACTQKV_OPTIONAL_SMALL(theta, 4);
+  ACTQKV_OPTIONAL_SMALL(budget, 4);
+  if (score_stride < nb_capacity)
+    return set_error(ACTQKV_EINVAL, "score_stride %lld < nb_capacity %d", (long long)score_stride,
+                     nb_capacity);
+  return launch_select(batch, scores, score_stride, nb_capacity, nb_begin, nb_end, k_cap, cutoff, idx,
+                       n_sel, theta, budget, static_cast<hipStream_t>(stream));
+}
+
+int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, const void* q,
+                               const void* k_cache, const void* v_cache, int64_t seq_stride,
+                               int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
+                               const int32_t* n_sel, int k_cap, void* out, float* lse, void* workspace,
+                               size_t ws_bytes, void* stream) {
+  ACTQKV_TRY(check_shape(shape));
+  ACTQKV_TRY(check_batch(batch));
+  if (m < 1) return set_error(ACTQKV_EINVAL, "m %d < 1", m);
+  if (m > 65536) return set_error(ACTQKV_ESHAPE, "m %d > 65536", m);
+  ACTQKV_TRY(check_blocks(nb_capacity, 0, k_cap, true));
+  if (nb_capacity < 1) return set_error(ACTQKV_EINVAL, "nb_capacity %d < 1", nb_capacity);
+  if (int64_t(nb_capacity) * shape->block_size < m)
+    return set_error(ACTQKV_EINVAL, "cache of %d blocks cannot hold a window of %d tokens", nb_capacity, m);
+  if (int64_t(nb_capacity) * shape->block_size > (int64_t(1) << 30))
+    return set_error(ACTQKV_ESHAPE, "cache of %d blocks exceeds 2^30 tokens", nb_capacity);
+  ACTQKV_REQUIRE_PTR(q);
+  ACTQKV_REQUIRE_PTR(k_cache);
+  ACTQKV_REQUIRE_PTR(v_cache);
+  ACTQKV_REQUIRE_SMALL(n_ctx, 4);
+  ACTQKV_REQUIRE_SMALL(idx, 4);
+  ACTQKV_REQUIRE_SMALL(n_sel, 4);
+  ACTQKV_REQUIRE_PTR(out);
+  ACTQKV_OPTIONAL_SMALL(lse, 4);
+  const int64_t per_seq = int64_t(nb_capacity) * shape->n_kv_heads * shape->block_size * shape->head_dim;
+  if (batch > 1 && seq_stride < per_seq)
+    return set_error(ACTQKV_EINVAL, "seq_stride %lld < one sequence's cache %lld", (long long)seq_stride,
+                     (long long)per_seq);
+  if (seq_stride % 8 != 0) return set_error(ACTQKV_EALIGN, "seq_stride must be a multiple of 8 elements");
+  if (workspace == nullptr || !aligned16(workspace))
+    return set_error(ACTQKV_EWORKSPACE, "workspace is NULL or not 16-byte aligned");
+  size_t need = workspace_bytes(*shape, batch, m, nb_capacity, k_cap);
+  if (ws_bytes < need)
+    return set_error(ACTQKV_EWORKSPACE, "workspace has %zu bytes, retrieval_attention needs %zu", ws_bytes,
+                     need);
+  Workspace ws{workspace, ws_bytes};
+  return launch_attention(*shape, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx,
+                          n_sel, k_cap, out, lse, ws, static_cast<hipStream_t>(stream));
+}
+
+const char* actqkv_last_error(void) { return g_error; }
+
+int actqkv_version(void) { return ACTQKV_VERSION; }
+
+}  // extern "C"

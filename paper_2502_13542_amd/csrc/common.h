@@ -1,0 +1,170 @@
+// Shared device helpers for the gfx950 kernels of the retrieval-attention path.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/actqkv.h"
+
+namespace actqkv {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 128;  // tokens per KV block (the only supported block size)
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+// ---- bf16 <-> fp32 (bf16 is the upper half of an fp32) ---------------------
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) {
+  return __uint_as_float(packed & 0xffff0000u);
+}
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// ---- 16-byte vector loads of VEC consecutive elements widened to fp32 ------
+template <typename T> struct Vec;  // T = float: 4 elements; T = uint16_t (bf16 bits): 8 elements
+template <> struct Vec<float> {
+  static constexpr int N = 4;
+  __device__ static __forceinline__ void load(const float* p, float (&out)[4]) {
+    f32x4 v = *reinterpret_cast<const f32x4*>(p);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+  }
+};
+template <> struct Vec<uint16_t> {
+  static constexpr int N = 8;
+  __device__ static __forceinline__ void load(const uint16_t* p, float (&out)[8]) {
+    u32x4 v = *reinterpret_cast<const u32x4*>(p);
+    out[0] = bf16_lo(v.x); out[1] = bf16_hi(v.x); out[2] = bf16_lo(v.y); out[3] = bf16_hi(v.y);
+    out[4] = bf16_lo(v.z); out[5] = bf16_hi(v.z); out[6] = bf16_lo(v.w); out[7] = bf16_hi(v.w);
+  }
+};
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(uint16_t x) { return __uint_as_float(uint32_t(x) << 16); }
+__device__ __forceinline__ void store_elem(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_elem(uint16_t* p, float v) { *p = uint16_t(f32_to_bf16_bits(v)); }
+
+// ---- wave / workgroup reductions ------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// Sum over the workgroup; every thread gets the result.  `red` holds >= 32 floats of LDS.
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  v = wave_sum(v);
+  __syncthreads();
+  if (lane == 0) red[w] = v;
+  __syncthreads();
+  float t = 0.f;
+  for (int i = 0; i < nw; ++i) t += red[i];
+  return t;
+}
+__device__ __forceinline__ float block_max(float v, float* red) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  v = wave_max(v);
+  __syncthreads();
+  if (lane == 0) red[w] = v;
+  __syncthreads();
+  float t = red[0];
+  for (int i = 1; i < nw; ++i) t = fmaxf(t, red[i]);
+  return t;
+}
+
+// "Last workgroup done" ticket: returns true in every thread of the workgroup
+// that arrives last out of `total` at `counter`, after making this workgroup's
+// global writes visible and the others' visible to it.  The last one resets
+// the counter, so a zero-filled counter stays reusable.  `flag` is one int of LDS.
+__device__ __forceinline__ bool last_block_done(unsigned int* counter, unsigned int total, int* flag) {
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned int t = atomicAdd(counter, 1u);
+    int last = (t == total - 1u);
+    if (last) *counter = 0u;
+    *flag = last;
+  }
+  __syncthreads();
+  bool last = (*flag != 0);
+  if (last) __threadfence();
+  return last;
+}
+
+// ---- window geometry -------------------------------------------------------
+// Tokens [0, i0) are the visible initial tokens; the local span starts at l0.
+struct WindowGeom {
+  int w0, i0, l0;
+};
+__host__ __device__ __forceinline__ WindowGeom window_geom(int n_ctx, int m, int n_init, int n_local) {
+  WindowGeom g;
+  g.w0 = n_ctx - m;
+  if (g.w0 < 0) g.w0 = 0;
+  g.i0 = n_init < g.w0 ? n_init : g.w0;
+  int a = g.w0 - n_local;
+  a = a > 0 ? (a / kBlock) * kBlock : 0;
+  g.l0 = a > g.i0 ? a : g.i0;
+  return g;
+}
+
+// The list of key tiles one query tile walks through: initial tokens, selected
+// blocks, then the local span and the window itself up to the tile's last query.
+// Tile t covers key positions [lo, hi) of cache block `block` (hi <= lo: empty).
+struct TileList {
+  int n_init_tiles, n_sel, n_tail_tiles, tail_block0;
+  int i0, l0, q_hi;
+  const int32_t* idx;
+  int nb_capacity;
+  __device__ __forceinline__ int count() const { return n_init_tiles + n_sel + n_tail_tiles; }
+  __device__ __forceinline__ void get(int t, int& block, int& lo, int& hi) const {
+    if (t < n_init_tiles) {
+      block = t;
+      lo = t * kBlock;
+      hi = min(lo + kBlock, i0);
+    } else if (t < n_init_tiles + n_sel) {
+      int b = idx[t - n_init_tiles];
+      bool ok = (b >= 0) && (b < nb_capacity);
+      block = ok ? b : 0;
+      lo = block * kBlock;
+      hi = ok ? lo + kBlock : lo;
+    } else {
+      block = tail_block0 + (t - n_init_tiles - n_sel);
+      lo = max(block * kBlock, l0);
+      hi = min(block * kBlock + kBlock, q_hi + 1);
+    }
+  }
+};
+// q_hi: position of the last query of the tile.  n_ctx is clamped by the caller.
+__device__ __forceinline__ TileList make_tile_list(const WindowGeom& g, int q_hi, const int32_t* idx,
+                                                   int n_sel, int k_cap, int nb_capacity) {
+  TileList tl;
+  tl.i0 = g.i0;
+  tl.l0 = g.l0;
+  tl.q_hi = q_hi;
+  tl.n_init_tiles = (g.i0 + kBlock - 1) / kBlock;
+  tl.n_sel = n_sel < 0 ? 0 : (n_sel > k_cap ? k_cap : n_sel);
+  tl.tail_block0 = g.l0 / kBlock;
+  tl.n_tail_tiles = q_hi / kBlock - tl.tail_block0 + 1;
+  tl.idx = idx;
+  tl.nb_capacity = nb_capacity;
+  return tl;
+}
+
+}  // namespace actqkv

@@ -1,0 +1,72 @@
+// Host-side plumbing shared by the C ABI and the kernel launchers: workspace
+// layout, launch declarations, error reporting.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/actqkv.h"
+
+namespace actqkv {
+
+// ---- error reporting -------------------------------------------------------
+int set_error(int code, const char* fmt, ...);
+// Turns the last HIP launch error, if any, into ACTQKV_EHIP.
+int hip_status(const char* what);
+
+// ---- sizes -----------------------------------------------------------------
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline size_t stats_floats(const actqkv_shape& sh) {
+  return 4 + 2 * size_t(sh.n_q_heads) * sh.head_dim;
+}
+inline int probe_stat_splits(int m) {
+  int s = (m + 63) / 64;
+  return s < 1 ? 1 : (s > 8 ? 8 : s);
+}
+__host__ __device__ inline size_t probe_a_floats(int m) { return (size_t(m) + 3) / 4 * 4; }
+// per sequence: mean[d], inv_var[d], a[m], partial sums [8][2][d]
+inline size_t probe_scratch_floats(const actqkv_shape& sh, int m) {
+  size_t d = size_t(sh.n_q_heads) * sh.head_dim;
+  return 2 * d + probe_a_floats(m) + 8 * 2 * d;
+}
+
+// Key-tile splits of the prefill attention and of the decode attention.
+constexpr int kMaxSplits = 16;
+int prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap);
+int decode_splits(const actqkv_shape& sh, int batch, int k_cap);
+// per (sequence, query row, head, split): D partial outputs + running max + running sum
+inline size_t attn_scratch_floats(const actqkv_shape& sh, int batch, int m, int splits) {
+  return size_t(batch) * m * sh.n_q_heads * splits * (size_t(sh.head_dim) + 2);
+}
+
+constexpr size_t kCounterBytes = 4096;  // 1024 uint32 tickets at the head of the workspace
+constexpr int kMaxBatch = 1024;
+
+size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap);
+
+struct Workspace {
+  void* base;
+  size_t bytes;
+  unsigned int* counters() const { return static_cast<unsigned int*>(base); }
+  float* scratch_f32() const {
+    return reinterpret_cast<float*>(static_cast<char*>(base) + kCounterBytes);
+  }
+};
+
+// ---- launchers (one per entry point; arguments already validated) ----------
+int launch_probe(const actqkv_shape& sh, int batch, int m, const void* q_win, float* stats,
+                 int update_stats, float* probe, float* probe_kv, float* probe_norm, float* weights,
+                 const Workspace& ws, hipStream_t stream);
+int launch_score(const actqkv_shape& sh, int batch, const float* probe_kv, const float* probe_norm,
+                 const void* rep_keys, int64_t seq_stride, int nb_capacity, int nb_begin,
+                 const int32_t* nb_end, float* scores, int64_t score_stride, hipStream_t stream);
+int launch_select(int batch, const float* scores, int64_t score_stride, int nb_capacity, int nb_begin,
+                  const int32_t* nb_end, int k_cap, actqkv_cutoff* cutoff, int32_t* idx,
+                  int32_t* n_sel, float* theta, float* budget, hipStream_t stream);
+int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
+                     const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
+                     const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
+                     const Workspace& ws, hipStream_t stream);
+
+}  // namespace actqkv

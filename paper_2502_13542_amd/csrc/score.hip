@@ -1,0 +1,83 @@
+// Block scores (Sec. 4.2, Eq. (10), applied to the r representative keys of a block;
+// the objective of Sec. 3.2, Eq. (5) ranks blocks by the sum of these cosines).
+//
+// HBM-bound streaming kernel: every representative key is read exactly once with
+// 16-byte loads.  One wavefront scores one block; each group of 16 lanes walks one
+// representative key (consecutive lanes read consecutive 16-byte chunks), so a
+// wavefront keeps four keys in flight.  The group-summed probe sits in LDS.
+#include "common.h"
+#include "launch.h"
+
+namespace actqkv {
+
+template <typename T>
+__global__ __launch_bounds__(256) void score_blocks_kernel(
+    const float* __restrict__ probe_kv, const float* __restrict__ probe_norm,
+    const T* __restrict__ rep_keys, int64_t seq_stride, int nb_capacity, int nb_begin,
+    const int32_t* __restrict__ nb_end, float* __restrict__ scores, int64_t score_stride, int n_rep,
+    int key_len, float inv_sqrt_g) {
+  constexpr int V = Vec<T>::N;
+  extern __shared__ float probe_lds[];  // [key_len]
+  const int s = blockIdx.y;
+  for (int i = threadIdx.x; i < key_len; i += 256) probe_lds[i] = probe_kv[size_t(s) * key_len + i];
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int end = min(nb_end[s], nb_capacity);
+  const int b = nb_begin + blockIdx.x * 4 + wave;
+  if (b >= end) return;
+  const float pn = probe_norm[s];
+  const int gq = lane >> 4, l16 = lane & 15;
+  const int chunks = key_len / V;
+  const T* block_keys = rep_keys + size_t(s) * seq_stride + size_t(b) * n_rep * key_len;
+  float total = 0.f;
+  for (int j0 = 0; j0 < n_rep; j0 += 4) {
+    const int j = j0 + gq;
+    float dot = 0.f, nrm = 0.f;
+    if (j < n_rep) {
+      const T* key = block_keys + size_t(j) * key_len;
+#pragma unroll 4
+      for (int c = l16; c < chunks; c += 16) {
+        float k[V];
+        Vec<T>::load(key + c * V, k);
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+          dot += probe_lds[c * V + v] * k[v];
+          nrm += k[v] * k[v];
+        }
+      }
+    }
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) {
+      dot += __shfl_xor(dot, o, 64);
+      nrm += __shfl_xor(nrm, o, 64);
+    }
+    // cosine of the probe with the key repeated to the G query heads of each KV head
+    float c = (j < n_rep && nrm > 0.f && pn > 0.f) ? dot * inv_sqrt_g / (pn * sqrtf(nrm)) : 0.f;
+    c += __shfl_xor(c, 16, 64);
+    c += __shfl_xor(c, 32, 64);
+    total += c;
+  }
+  if (lane == 0) scores[size_t(s) * score_stride + b] = total / float(n_rep);
+}
+
+int launch_score(const actqkv_shape& sh, int batch, const float* probe_kv, const float* probe_norm,
+                 const void* rep_keys, int64_t seq_stride, int nb_capacity, int nb_begin,
+                 const int32_t* nb_end, float* scores, int64_t score_stride, hipStream_t stream) {
+  const int n = nb_capacity - nb_begin;
+  if (n <= 0) return ACTQKV_OK;
+  const int key_len = sh.n_kv_heads * sh.head_dim;
+  const float inv_sqrt_g = 1.f / sqrtf(float(sh.n_q_heads / sh.n_kv_heads));
+  dim3 grid((n + 3) / 4, batch);
+  const size_t lds = size_t(key_len) * sizeof(float);
+  if (sh.dtype == ACTQKV_F32)
+    hipLaunchKernelGGL(score_blocks_kernel<float>, grid, dim3(256), lds, stream, probe_kv, probe_norm,
+                       static_cast<const float*>(rep_keys), seq_stride, nb_capacity, nb_begin, nb_end,
+                       scores, score_stride, sh.n_rep, key_len, inv_sqrt_g);
+  else
+    hipLaunchKernelGGL(score_blocks_kernel<uint16_t>, grid, dim3(256), lds, stream, probe_kv,
+                       probe_norm, static_cast<const uint16_t*>(rep_keys), seq_stride, nb_capacity,
+                       nb_begin, nb_end, scores, score_stride, sh.n_rep, key_len, inv_sqrt_g);
+  return hip_status("score_blocks");
+}
+
+}  // namespace actqkv

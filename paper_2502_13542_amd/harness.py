@@ -1,0 +1,154 @@
+"""Host-side driver around the library: cache layout conversion, window
+bookkeeping and the window-by-window / step-by-step loops of Sec. 3.1.  It only
+allocates, converts layouts and calls the four entry points in order; every
+arithmetic step of the path runs inside libactqkv.so.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import torch
+
+from . import binding as B
+from .synth import LayerShape
+
+
+# ---------------------------------------------------------------- geometry
+def local_start(shape: LayerShape, w0: int) -> int:
+    """First token of the local span of a window that starts at w0 (same rule as the kernels)."""
+    i0 = min(shape.n_init, w0)
+    a = w0 - shape.n_local
+    a = (a // shape.block_size) * shape.block_size if a > 0 else 0
+    return max(i0, a)
+
+
+def eligible_range(shape: LayerShape, w0: int) -> Tuple[int, int]:
+    """[nb_begin, nb_end): blocks wholly between the initial tokens and the local span."""
+    nb_begin = shape.n_init // shape.block_size
+    return nb_begin, max(nb_begin, local_start(shape, w0) // shape.block_size)
+
+
+# ---------------------------------------------------------------- layouts
+def blocked_k(k: torch.Tensor, shape: LayerShape, nb_capacity: Optional[int] = None) -> torch.Tensor:
+    """[N][Hk][D] -> k_cache [nb][Hk][Bs][D], zero-padded to whole blocks."""
+    n, hk, d = k.shape
+    bs = shape.block_size
+    nb = (n + bs - 1) // bs if nb_capacity is None else nb_capacity
+    out = torch.zeros(nb, hk, bs, d, dtype=k.dtype, device=k.device)
+    full = n // bs
+    out[:full] = k[: full * bs].reshape(full, bs, hk, d).permute(0, 2, 1, 3)
+    if n > full * bs:
+        out[full, :, : n - full * bs] = k[full * bs:].permute(1, 0, 2)
+    return out
+
+
+def blocked_vt(v: torch.Tensor, shape: LayerShape, nb_capacity: Optional[int] = None) -> torch.Tensor:
+    """[N][Hk][D] -> v_cache [nb][Hk][D][Bs] (values transposed inside a block), zero-padded."""
+    n, hk, d = v.shape
+    bs = shape.block_size
+    nb = (n + bs - 1) // bs if nb_capacity is None else nb_capacity
+    out = torch.zeros(nb, hk, d, bs, dtype=v.dtype, device=v.device)
+    full = n // bs
+    out[:full] = v[: full * bs].reshape(full, bs, hk, d).permute(0, 2, 3, 1)
+    if n > full * bs:
+        out[full, :, :, : n - full * bs] = v[full * bs:].permute(1, 2, 0)
+    return out
+
+
+# ---------------------------------------------------------------- one layer of one (batch of) sequence(s)
+class LayerRunner:
+    """Device buffers of one layer and the call sequence of one window / step."""
+
+    def __init__(self, shape: LayerShape, batch: int, m: int, nb_capacity: int, k_cap: int,
+                 device="cuda"):
+        self.shape, self.batch, self.m, self.nb_capacity, self.k_cap = shape, batch, m, nb_capacity, k_cap
+        self.cs = B.c_shape(shape)
+        self.device = device
+        d, dk = shape.d_model, shape.n_kv_heads * shape.head_dim
+        f32 = dict(dtype=torch.float32, device=device)
+        i32 = dict(dtype=torch.int32, device=device)
+        self.stats = torch.zeros(batch, B.stats_floats(self.cs), **f32)
+        self.probe = torch.empty(batch, d, **f32)
+        self.probe_kv = torch.empty(batch, dk, **f32)
+        self.probe_norm = torch.empty(batch, **f32)
+        self.weights = torch.empty(batch, m, **f32)
+        self.score_stride = (nb_capacity + 3) // 4 * 4
+        self.scores = torch.zeros(batch, self.score_stride, **f32)
+        self.idx = torch.full((batch, k_cap), -1, **i32)
+        self.n_sel = torch.zeros(batch, **i32)
+        self.theta = torch.zeros(batch, **f32)
+        self.budget = torch.zeros(batch, **f32)
+        ws = B.workspace_bytes(self.cs, batch, m, nb_capacity, k_cap)
+        self.workspace = torch.zeros(ws, dtype=torch.uint8, device=device)
+
+    def reset(self) -> None:
+        self.stats.zero_()
+
+    def step(self, q_win: torch.Tensor, k_cache, v_cache, rep_keys, n_ctx: torch.Tensor,
+             nb_end: torch.Tensor, nb_end_max: int, out: torch.Tensor, cutoff: Optional[torch.Tensor],
+             update_stats: bool = True, m: Optional[int] = None, lse=None, stream=None) -> None:
+        """probe -> scores -> selection -> attention for one window (or decode step).
+        nb_end_max: host-side upper bound of nb_end, sizes the scoring launch."""
+        sh, cs, bt = self.shape, self.cs, self.batch
+        m = self.m if m is None else m
+        nb_begin = sh.n_init // sh.block_size
+        cache_stride = k_cache.stride(0) if k_cache.dim() == 5 else 0
+        rep_stride = rep_keys.stride(0) if rep_keys.dim() == 5 else 0
+        B.build_probe(cs, bt, m, q_win, self.stats, update_stats, self.probe, self.probe_kv,
+                      self.probe_norm, self.weights, self.workspace, stream)
+        nb_cap = min(max(nb_end_max, nb_begin), self.nb_capacity)
+        B.score_blocks(cs, bt, self.probe_kv, self.probe_norm, rep_keys, rep_stride, nb_cap, nb_begin,
+                       nb_end, self.scores, self.score_stride, stream)
+        B.select(bt, self.scores, self.score_stride, nb_cap, nb_begin, nb_end, self.k_cap, cutoff,
+                 self.idx, self.n_sel, self.theta, self.budget, stream)
+        B.retrieval_attention(cs, bt, m, q_win, k_cache, v_cache, cache_stride, self.nb_capacity, n_ctx,
+                              self.idx, self.n_sel, self.k_cap, out, lse, self.workspace, stream)
+
+
+@dataclass
+class PrefillPlan:
+    """Per-window device scalars of a single-sequence prefill, uploaded once."""
+    n_windows: int
+    w0: List[int]
+    rows: List[int]
+    nb_end_host: List[int]
+    n_ctx: torch.Tensor      # int32 [T]
+    nb_end: torch.Tensor     # int32 [T]
+    cutoff: Optional[torch.Tensor]   # float32 [T][2] or None
+
+
+def make_prefill_plan(shape: LayerShape, n_ctx: int, m: int,
+                      cutoffs: Optional[Sequence[Tuple[float, float]]], device="cuda") -> PrefillPlan:
+    w0s = list(range(0, n_ctx, m))
+    rows = [min(m, n_ctx - w) for w in w0s]
+    nb_end = [eligible_range(shape, w)[1] for w in w0s]
+    nctx = [w + r for w, r in zip(w0s, rows)]
+    cut = None
+    if cutoffs is not None:
+        cut = torch.tensor([[c[0], c[1]] for c in cutoffs], dtype=torch.float32, device=device)
+    return PrefillPlan(len(w0s), w0s, rows, nb_end,
+                       torch.tensor(nctx, dtype=torch.int32, device=device),
+                       torch.tensor(nb_end, dtype=torch.int32, device=device), cut)
+
+
+def prefill_layer(runner: LayerRunner, plan: PrefillPlan, q: torch.Tensor, k_cache, v_cache, rep_keys,
+                  out: torch.Tensor, record: Optional[Sequence[int]] = None,
+                  windows: Optional[Sequence[int]] = None) -> Dict[int, Dict[str, torch.Tensor]]:
+    """Runs the windows of one sequence in order.  q, out [N][H][D].  `record` lists the
+    windows whose intermediate results are copied out (for parity checks)."""
+    rec: Dict[int, Dict[str, torch.Tensor]] = {}
+    m = runner.m
+    for t in (range(plan.n_windows) if windows is None else windows):
+        w0, rows = plan.w0[t], plan.rows[t]
+        cut = None if plan.cutoff is None else plan.cutoff[t:t + 1]
+        runner.step(q[w0:w0 + rows], k_cache, v_cache, rep_keys, plan.n_ctx[t:t + 1],
+                    plan.nb_end[t:t + 1], plan.nb_end_host[t], out[w0:w0 + rows], cut, True, rows)
+        if record is not None and t in record:
+            rec[t] = dict(probe=runner.probe[0].clone(), probe_kv=runner.probe_kv[0].clone(),
+                          probe_norm=runner.probe_norm[0].clone(),
+                          weights=runner.weights[0, :rows].clone(), scores=runner.scores[0].clone(),
+                          idx=runner.idx[0].clone(), n_sel=runner.n_sel[0].clone(),
+                          theta=runner.theta[0].clone(), budget=runner.budget[0].clone(),
+                          cutoff_after=None if cut is None else cut[0].clone())
+    return rec

@@ -1,0 +1,96 @@
+"""Host-side checks of the C ABI that need no GPU: the library builds and loads, exports
+every symbol the header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2502_13542_amd import binding as B
+from paper_2502_13542_amd.synth import LayerShape
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LLAMA = LayerShape(32, 8, 128, 128, 4, 128, 512, "bf16")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return B.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    text = open(os.path.join(ROOT, "include", "actqkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(actqkv_[a-z_]+)\s*\(", text))
+    assert {"actqkv_build_probe", "actqkv_score_blocks", "actqkv_select",
+            "actqkv_retrieval_attention"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in actqkv.h but not exported"
+    assert declared == set(B.SIGNATURES), "binding and header disagree"
+    assert lib.actqkv_version() == int(re.search(r"#define ACTQKV_VERSION (\d+)", text).group(1))
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(B.CShape) == 40
+    assert B.CShape.softmax_scale.offset == 32 and B.CShape.var_eps.offset == 36
+
+
+def test_sizes(lib):
+    cs = B.c_shape(LLAMA)
+    assert B.stats_floats(cs) == 4 + 2 * 4096
+    ws = B.workspace_bytes(cs, 1, 512, 1024, 32)
+    assert ws >= 4096 and ws % 256 == 0
+    assert B.workspace_bytes(cs, 16, 1, 520, 32) >= 4096
+
+
+A16 = 0x10000  # fake, aligned, never dereferenced: every check below fails before a launch
+
+
+def _probe(lib, cs, **kw):
+    a = dict(batch=1, m=512, q=A16, stats=A16, upd=1, probe=A16, pkv=A16, pn=A16, w=None, ws=A16,
+             wsb=1 << 30)
+    a.update(kw)
+    return lib.actqkv_build_probe(ctypes.byref(cs), a["batch"], a["m"], a["q"], a["stats"], a["upd"],
+                                  a["probe"], a["pkv"], a["pn"], a["w"], a["ws"], a["wsb"], None)
+
+
+def test_build_probe_rejects(lib):
+    cs = B.c_shape(LLAMA)
+    assert _probe(lib, cs, batch=0) == -1
+    assert _probe(lib, cs, m=0) == -1
+    assert _probe(lib, cs, q=None) == -1 and b"q_win" in lib.actqkv_last_error()
+    assert _probe(lib, cs, q=A16 + 4) == -3
+    assert _probe(lib, cs, ws=None) == -4
+    assert _probe(lib, cs, wsb=100) == -4 and b"needs" in lib.actqkv_last_error()
+    assert lib.actqkv_build_probe(None, 1, 1, A16, A16, 0, A16, A16, A16, None, A16, 1 << 20, None) == -1
+
+
+@pytest.mark.parametrize("field,value,code", [("head_dim", 96, -2), ("n_kv_heads", 5, -2),
+                                              ("block_size", 64, -2), ("n_rep", 17, -2),
+                                              ("n_init", 100, -2), ("dtype", 7, -1),
+                                              ("n_q_heads", 0, -1), ("softmax_scale", -1.0, -1)])
+def test_shape_rejects(lib, field, value, code):
+    cs = B.c_shape(LLAMA)
+    setattr(cs, field, value)
+    assert _probe(lib, cs) == code
+    assert B.stats_floats(cs) == 0
+
+
+def test_score_select_attention_reject(lib):
+    cs = B.c_shape(LLAMA)
+    sb = lambda **k: lib.actqkv_score_blocks(ctypes.byref(cs), k.get("batch", 1), A16, A16,
+                                             k.get("rep", A16), k.get("stride", 0), k.get("cap", 64), 1,
+                                             A16, A16, k.get("ss", 64), None)
+    assert sb(rep=None) == -1 and sb(rep=A16 + 8) == -3 and sb(ss=10) == -1 and sb(cap=-1) == -1
+    assert sb(batch=2, stride=8) == -1 and sb(stride=4) == -3 and sb(cap=9000, ss=9000) == -2
+    se = lambda **k: lib.actqkv_select(1, A16, 64, 64, 1, A16, k.get("k_cap", 32), k.get("cut"),
+                                       k.get("idx", A16), A16, None, None, None)
+    assert se(k_cap=0) == -2 and se(k_cap=65) == -2 and se(idx=None) == -1 and se(cut=A16 + 4) == -3
+    at = lambda **k: lib.actqkv_retrieval_attention(ctypes.byref(cs), 1, k.get("m", 512), A16,
+                                                    k.get("kc", A16), A16, 0, k.get("cap", 64), A16, A16,
+                                                    A16, 32, k.get("out", A16), None, k.get("ws", A16),
+                                                    k.get("wsb", 1 << 30), None)
+    assert at(kc=None) == -1 and at(out=A16 + 2) == -3 and at(ws=None) == -4 and at(wsb=8) == -4
+    assert at(m=0) == -1 and at(cap=2) == -1 and at(cap=0) == -1
+    with pytest.raises(B.ActQKVError):
+        B._check(at(wsb=8))
