@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libactqkv.so")
 
-SOURCES = ["api.hip", "probe.hip", "score.hip", "select.hip", "attn_rows.hip"]
+SOURCES = ["api.hip", "probe.hip", "score.hip", "select.hip", "attn_rows.hip",
+           "attn_prefill_mfma.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed fp32 instructions are kept out of the generated code

@@ -98,9 +98,21 @@ static int check_blocks(int nb_capacity, int nb_begin, int k_cap, bool use_k) {
     if (rc_ != ACTQKV_OK) return rc_; \
   } while (0)
 
+bool prefill_mfma_supported(const actqkv_shape& sh, int m);
+int prefill_mfma_qtiles(const actqkv_shape& sh, int m);
+int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, const void* q,
+                                  const void* k_cache, const void* v_cache, int64_t seq_stride,
+                                  int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
+                                  const int32_t* n_sel, int k_cap, void* out, float* lse, int splits,
+                                  float* scratch, float scale, hipStream_t stream);
+
+// Enough key splits to give every compute unit a workgroup, never more than 8.
 int prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap) {
-  (void)sh; (void)batch; (void)m; (void)k_cap;
-  return 1;
+  (void)k_cap;
+  if (!prefill_mfma_supported(sh, m)) return 1;
+  const int base = batch * sh.n_kv_heads * prefill_mfma_qtiles(sh, m);
+  int s = 256 / (base > 0 ? base : 1);
+  return s < 1 ? 1 : (s > 8 ? 8 : s);
 }
 int decode_splits(const actqkv_shape& sh, int batch, int k_cap) {
   (void)sh; (void)batch; (void)k_cap;
@@ -112,6 +124,10 @@ size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity
   size_t probe = size_t(batch) * probe_scratch_floats(sh, m) * sizeof(float);
   int splits = m == 1 ? decode_splits(sh, batch, k_cap) : prefill_splits(sh, batch, m, k_cap);
   size_t attn = attn_scratch_floats(sh, batch, m, splits) * sizeof(float);
+  if (prefill_mfma_supported(sh, m)) {
+    size_t groups = size_t(batch) * sh.n_kv_heads * prefill_mfma_qtiles(sh, m);
+    attn = groups * splits * kPfPartialFloats * sizeof(float);
+  }
   return kCounterBytes + align_up(probe > attn ? probe : attn, 256);
 }
 
@@ -124,8 +140,12 @@ int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, co
                      const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
                      const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
                      const Workspace& ws, hipStream_t stream) {
-  (void)ws;
   const float scale = sh.softmax_scale > 0.f ? sh.softmax_scale : 1.f / std::sqrt(float(sh.head_dim));
+  if (prefill_mfma_supported(sh, m))
+    return launch_attention_prefill_mfma(sh, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity,
+                                         n_ctx, idx, n_sel, k_cap, out, lse,
+                                         prefill_splits(sh, batch, m, k_cap), ws.scratch_f32(), scale,
+                                         stream);
   return launch_attention_rows(sh, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx,
                                n_sel, k_cap, out, lse, scale, stream);
 }
@@ -156,7 +176,7 @@ int actqkv_build_probe(const actqkv_shape* shape, int batch, int m, const void* 
   ACTQKV_TRY(check_shape(shape));
   ACTQKV_TRY(check_batch(batch));
   if (m < 1) return set_error(ACTQKV_EINVAL, "m %d < 1", m);
-  if (m > 65536) return set_error(ACTQKV_ESHAPE, "m %d > 65536", m);
+  if (m > kMaxWindow) return set_error(ACTQKV_ESHAPE, "m %d > %d", m, kMaxWindow);
   ACTQKV_REQUIRE_PTR(q_win);
   ACTQKV_REQUIRE_PTR(probe);
   ACTQKV_REQUIRE_PTR(probe_kv);
@@ -168,6 +188,13 @@ int actqkv_build_probe(const actqkv_shape* shape, int batch, int m, const void* 
   size_t need = kCounterBytes + size_t(batch) * probe_scratch_floats(*shape, m) * sizeof(float);
   if (ws_bytes < need)
     return set_error(ACTQKV_EWORKSPACE, "workspace has %zu bytes, build_probe needs %zu", ws_bytes, need);
+  if (update_stats) {
+    const int vec = shape->dtype == ACTQKV_F32 ? 4 : 8;
+    const int n_slabs = (shape->n_q_heads * shape->head_dim + 64 * vec - 1) / (64 * vec);
+    if (batch * (n_slabs + 1) > 1024)
+      return set_error(ACTQKV_ESHAPE, "batch %d too large for a statistics update of %d channels", batch,
+                       shape->n_q_heads * shape->head_dim);
+  }
   Workspace ws{workspace, ws_bytes};
   return launch_probe(*shape, batch, m, q_win, stats, update_stats, probe, probe_kv, probe_norm,
                       weights, ws, static_cast<hipStream_t>(stream));
@@ -224,7 +251,7 @@ int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, cons
   ACTQKV_TRY(check_shape(shape));
   ACTQKV_TRY(check_batch(batch));
   if (m < 1) return set_error(ACTQKV_EINVAL, "m %d < 1", m);
-  if (m > 65536) return set_error(ACTQKV_ESHAPE, "m %d > 65536", m);
+  if (m > kMaxWindow) return set_error(ACTQKV_ESHAPE, "m %d > %d", m, kMaxWindow);
   ACTQKV_TRY(check_blocks(nb_capacity, 0, k_cap, true));
   if (nb_capacity < 1) return set_error(ACTQKV_EINVAL, "nb_capacity %d < 1", nb_capacity);
   if (int64_t(nb_capacity) * shape->block_size < m)

@@ -1,0 +1,377 @@
+// Retrieval attention of a prefill window on the matrix cores
+// (Sec. 3.1, Eq. (2): O^t = Attention(Q^t, [K^t, K*], [V^t, V*]); bf16 storage, fp32 accumulation).
+//
+// Work split.  A workgroup of 8 wavefronts owns 256 query rows that share one KV
+// head: all G query heads of the group times 256/G consecutive window positions;
+// each wavefront owns 32 rows (one head, 32 positions).  The key tiles of the
+// window - initial tokens, the blocks chosen by actqkv_select (read from device
+// memory), the local span and the causal part of the window - form one list of
+// 128-key blocks; it is cut into `splits` contiguous pieces, one workgroup each,
+// so that a 512-token window still fills all 256 compute units; a short second
+// kernel merges the pieces.  Workgroups of one
+// KV head sit on one XCD (blockIdx % Hk picks the head), so that head's gathered
+// tiles stay in that XCD's L2.
+//
+// Data flow per tile.  K [128 keys][D] and V^T [D][128 keys] go global -> registers
+// -> LDS (double buffered, rows padded to 272 bytes so that 16-byte reads of 16
+// consecutive rows hit all 64 banks).  Each wavefront computes S^T = K Q^T with
+// v_mfma_f32_32x32x16_bf16 (A = K rows from LDS, B = Q^T kept in registers), so a
+// lane ends up holding scores of ONE query: the softmax needs no cross-lane work
+// except one exchange between the two half-waves, and the probabilities are
+// already in the register layout the next product wants as its B operand:
+// O^T += V^T P^T (A = V^T rows from LDS).  To make that work the K rows are fed in
+// a permuted order (bits 2 and 3 of the row index swapped); the permutation is
+// undone for free because a lane's 8 consecutive accumulator registers then hold
+// 8 consecutive keys.
+#include "common.h"
+#include "launch.h"
+
+namespace actqkv {
+
+constexpr int kPfThreads = 512;
+constexpr int kPfWaves = 8;
+constexpr int kPfD = 128;
+constexpr int kRowPad = 136;                         // bf16 elements per padded LDS row (272 bytes)
+constexpr int kTileElems = kBlock * kRowPad;         // one K or V^T tile in LDS
+constexpr int kPfLdsBytes = 2 * 2 * kTileElems * 2;  // 2 stages x (K, V^T) x bf16
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// 8 fp32 -> 8 bf16 (round to nearest even), packed as an MFMA operand
+__device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, float a4, float a5,
+                                        float a6, float a7) {
+  typedef __attribute__((ext_vector_type(8))) float f32x8;
+  f32x8 v = {a0, a1, a2, a3, a4, a5, a6, a7};
+  return __builtin_convertvector(v, bf16x8);
+}
+
+// MFMA row -> key row inside a 32-key group: swap bits 2 and 3.
+__device__ __forceinline__ int perm_row(int i) {
+  return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
+}
+
+struct PfParams {
+  const uint16_t* q;
+  const uint16_t* k_cache;
+  const uint16_t* v_cache;
+  int64_t seq_stride;
+  int nb_capacity;
+  const int32_t* n_ctx;
+  const int32_t* idx;
+  const int32_t* n_sel;
+  int k_cap;
+  uint16_t* out;
+  float* lse;
+  float* part;             // [workgroup][split][wave][64 registers + max + sum][64 lanes]
+  int m, n_q_heads, n_kv_heads, n_init, n_local;
+  int splits, n_qtiles;
+  float scale_log2e;
+};
+
+// Final normalisation and store of one lane's share of a query row:
+// acc_o[db][4j + r] is channel d = db*32 + 8j + 4*half + r.
+__device__ __forceinline__ void store_rows(const PfParams& p, const f32x16 (&acc_o)[4], float m_run,
+                                           float l_tot, int s, int my_row, int head, int half) {
+  const size_t grow = (size_t(s) * p.m + my_row) * p.n_q_heads + head;
+  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  uint16_t* op = p.out + grow * kPfD;
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      u32x2 v;
+      v.x = pack_bf16x2(acc_o[db][4 * j + 0] * inv, acc_o[db][4 * j + 1] * inv);
+      v.y = pack_bf16x2(acc_o[db][4 * j + 2] * inv, acc_o[db][4 * j + 3] * inv);
+      *reinterpret_cast<u32x2*>(op + db * 32 + 8 * j + 4 * half) = v;
+    }
+  if (p.lse != nullptr && half == 0)
+    p.lse[(size_t(s) * p.n_q_heads + head) * p.m + my_row] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+}
+
+__global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 31, half = lane >> 5;
+  const int group = p.n_q_heads / p.n_kv_heads;
+  const int waves_per_head = kPfWaves / group;
+  const int pos_per_wg = 32 * waves_per_head;
+
+  // blockIdx.x = ((split * n_qtiles + qtile) * Hk + hk): consecutive ids differ in hk,
+  // and ids are dealt round-robin to the XCDs, so each XCD serves few KV heads.
+  int bid = blockIdx.x;
+  const int hk = bid % p.n_kv_heads;
+  bid /= p.n_kv_heads;
+  const int qtile = bid % p.n_qtiles;
+  const int split = bid / p.n_qtiles;
+  const int s = blockIdx.y;
+
+  const int n_ctx = min(max(p.n_ctx[s], p.m), p.nb_capacity * kBlock);
+  const WindowGeom g = window_geom(n_ctx, p.m, p.n_init, p.n_local);
+  const int row0 = qtile * pos_per_wg;                       // first window row of the workgroup
+  const int row_hi = min(row0 + pos_per_wg, p.m) - 1;
+  const TileList tl = make_tile_list(g, g.w0 + row_hi, p.idx + size_t(s) * p.k_cap, p.n_sel[s],
+                                     p.k_cap, p.nb_capacity);
+  const int n_tiles = tl.count();
+  const int per = (n_tiles + p.splits - 1) / p.splits;
+  const int t_begin = split * per, t_end = min(n_tiles, t_begin + per);
+
+  const int head = hk * group + wave / waves_per_head;
+  const int wrow0 = row0 + (wave % waves_per_head) * 32;     // first window row of this wavefront
+  const int my_row = wrow0 + n;
+  const bool row_ok = my_row < p.m;
+  const int my_pos = g.w0 + my_row;                          // this lane's query position
+
+  // Q^T as B operand: lane (n, half) holds d = ks*16 + 8*half .. +7 of query row n
+  bf16x8 qreg[kPfD / 16];
+  {
+    const int r = min(my_row, p.m - 1);
+    const uint16_t* qp = p.q + ((size_t(s) * p.m + r) * p.n_q_heads + head) * kPfD + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < kPfD / 16; ++ks)
+      qreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4*>(qp + ks * 16));
+  }
+
+  f32x16 acc_o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc_o[i][j] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;   // running max (log2 units), this lane's share of the sum
+
+  const uint16_t* kc = p.k_cache + size_t(s) * p.seq_stride;
+  const uint16_t* vc = p.v_cache + size_t(s) * p.seq_stride;
+  const size_t tile_elems = size_t(kBlock) * kPfD;
+
+  // global -> register staging of one tile: 4 K chunks + 4 V^T chunks of 16 bytes per thread
+  u32x4 stage_k[4], stage_v[4];
+  auto load_tile = [&](int t) {
+    int block, lo, hi;
+    tl.get(t, block, lo, hi);
+    const uint16_t* kt = kc + (size_t(block) * p.n_kv_heads + hk) * tile_elems;
+    const uint16_t* vt = vc + (size_t(block) * p.n_kv_heads + hk) * tile_elems;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = tid + kPfThreads * i;
+      stage_k[i] = *reinterpret_cast<const u32x4*>(kt + size_t(c) * 8);
+      stage_v[i] = *reinterpret_cast<const u32x4*>(vt + size_t(c) * 8);
+    }
+  };
+  auto store_tile = [&](int stage) {
+    uint16_t* ks_ = lds + stage * 2 * kTileElems;
+    uint16_t* vs_ = ks_ + kTileElems;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = tid + kPfThreads * i;
+      const int r = c >> 4, col = (c & 15) * 8;
+      *reinterpret_cast<u32x4*>(ks_ + r * kRowPad + col) = stage_k[i];
+      *reinterpret_cast<u32x4*>(vs_ + r * kRowPad + col) = stage_v[i];
+    }
+  };
+
+  if (t_begin < t_end) {
+    load_tile(t_begin);
+    store_tile(0);
+  }
+  __syncthreads();
+
+  const int a_row = perm_row(n);
+  for (int t = t_begin; t < t_end; ++t) {
+    const int stage = (t - t_begin) & 1;
+    if (t + 1 < t_end) load_tile(t + 1);
+
+    int block, lo, hi;
+    tl.get(t, block, lo, hi);
+    const int kpos0 = block * kBlock;
+    // the wavefront skips tiles none of its rows can see; it masks tiles that are
+    // clipped or that reach past its first row's position
+    const bool visible = hi > lo && lo <= g.w0 + min(wrow0 + 31, p.m - 1);
+    const bool masked = lo > kpos0 || hi < kpos0 + kBlock || hi - 1 > g.w0 + wrow0;
+    if (visible) {
+      const uint16_t* ks_ = lds + stage * 2 * kTileElems;
+      const uint16_t* vs_ = ks_ + kTileElems;
+      // ---- S^T = K Q^T : 4 groups of 32 keys
+      f32x16 acc_s[4];
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc_s[kb][j] = 0.f;
+        const uint16_t* arow = ks_ + (kb * 32 + a_row) * kRowPad + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < kPfD / 16; ++ks) {
+          bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(arow + ks * 16));
+          acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], acc_s[kb], 0, 0, 0);
+        }
+      }
+      // register i of group kb holds key kpos0 + kb*32 + 16*(i/8) + 8*half + (i%8)
+      if (masked) {
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int kp = kpos0 + kb * 32 + 16 * (i >> 3) + 8 * half + (i & 7);
+            const bool ok = kp >= lo && kp < hi && kp <= my_pos;
+            acc_s[kb][i] = ok ? acc_s[kb][i] : -INFINITY;
+          }
+      }
+      // ---- online softmax, one query per lane (two lanes share a query: n and n+32)
+      float mx = acc_s[0][0];
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc_s[kb][i]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx * p.scale_log2e);
+      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+      m_run = m_new;
+      float psum = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float pv = __builtin_amdgcn_exp2f(acc_s[kb][i] * p.scale_log2e - m_safe);
+          acc_s[kb][i] = pv;
+          psum += pv;
+        }
+      l_run = l_run * alpha + psum;
+      if (!__all(alpha == 1.f)) {
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc_o[db][i] *= alpha;
+      }
+      // ---- O^T += V^T P^T
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb) {
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8 pb = pack8(acc_s[kb][8 * s2 + 0], acc_s[kb][8 * s2 + 1], acc_s[kb][8 * s2 + 2],
+                                  acc_s[kb][8 * s2 + 3], acc_s[kb][8 * s2 + 4], acc_s[kb][8 * s2 + 5],
+                                  acc_s[kb][8 * s2 + 6], acc_s[kb][8 * s2 + 7]);
+          const uint16_t* vrow = vs_ + n * kRowPad + kb * 32 + 16 * s2 + 8 * half;
+#pragma unroll
+          for (int db = 0; db < 4; ++db) {
+            bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(vrow + db * 32 * kRowPad));
+            acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, acc_o[db], 0, 0, 0);
+          }
+        }
+      }
+    }
+    if (t + 1 < t_end) store_tile(stage ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (p.splits > 1) {
+    // The split stores its accumulators exactly as the registers hold them (register-major,
+    // lane-minor: every store is one contiguous 256-byte row); attn_combine_kernel merges them.
+    const size_t group_id = (size_t(s) * p.n_qtiles + qtile) * p.n_kv_heads + hk;
+    float* mine = p.part + ((group_id * p.splits + split) * kPfWaves + wave) * (66 * 64);
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mine[(db * 16 + i) * 64 + lane] = acc_o[db][i];
+    mine[64 * 64 + lane] = m_run;
+    mine[65 * 64 + lane] = l_tot;
+    return;
+  }
+  if (row_ok) store_rows(p, acc_o, m_run, l_tot, s, my_row, head, half);
+}
+
+// Merges the partial results of the key splits: one wavefront per (workgroup, wavefront) of
+// the main kernel, same register layout, so every load is a contiguous 256-byte row.
+//   out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s
+__global__ __launch_bounds__(256) void attn_combine_kernel(PfParams p) {
+  const int lane = threadIdx.x & 63;
+  const int n = lane & 31, half = lane >> 5;
+  const size_t gw = size_t(blockIdx.x) * 4 + (threadIdx.x >> 6);   // (group, wave)
+  const int wave = int(gw % kPfWaves);
+  const size_t group_id = gw / kPfWaves;
+  const int hk = int(group_id % p.n_kv_heads);
+  const int qtile = int((group_id / p.n_kv_heads) % p.n_qtiles);
+  const int s = int(group_id / (size_t(p.n_kv_heads) * p.n_qtiles));
+  const int group = p.n_q_heads / p.n_kv_heads;
+  const int waves_per_head = kPfWaves / group;
+  const int head = hk * group + wave / waves_per_head;
+  const int my_row = qtile * 32 * waves_per_head + (wave % waves_per_head) * 32 + n;
+
+  f32x16 acc_o[4];
+  float m_run = -INFINITY, l_tot = 0.f;
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc_o[db][i] = 0.f;
+  for (int s2 = 0; s2 < p.splits; ++s2) {
+    const float* other = p.part + ((group_id * p.splits + s2) * kPfWaves + wave) * (66 * 64);
+    float tmp[66];
+#pragma unroll
+    for (int k = 0; k < 66; ++k) tmp[k] = other[k * 64 + lane];   // all loads first: they overlap
+    const float m_o = tmp[64], l_o = tmp[65];
+    const float m_new = fmaxf(m_run, m_o);
+    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+    const float wa = __builtin_amdgcn_exp2f(m_run - m_safe), wb = __builtin_amdgcn_exp2f(m_o - m_safe);
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc_o[db][i] = acc_o[db][i] * wa + tmp[db * 16 + i] * wb;
+    l_tot = l_tot * wa + l_o * wb;
+    m_run = m_new;
+  }
+  if (my_row < p.m) store_rows(p, acc_o, m_run, l_tot, s, my_row, head, half);
+}
+
+bool prefill_mfma_supported(const actqkv_shape& sh, int m) {
+  const int g = sh.n_q_heads / sh.n_kv_heads;
+  return sh.dtype == ACTQKV_BF16 && sh.head_dim == kPfD && m > 1 && g <= 8;
+}
+
+int prefill_mfma_qtiles(const actqkv_shape& sh, int m) {
+  const int g = sh.n_q_heads / sh.n_kv_heads;
+  const int pos_per_wg = 32 * (kPfWaves / g);
+  return (m + pos_per_wg - 1) / pos_per_wg;
+}
+
+int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, const void* q,
+                                  const void* k_cache, const void* v_cache, int64_t seq_stride,
+                                  int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
+                                  const int32_t* n_sel, int k_cap, void* out, float* lse, int splits,
+                                  float* scratch, float scale, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_mfma_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes);
+    if (e != hipSuccess) return set_error(ACTQKV_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+    attr_set = true;
+  }
+  PfParams p;
+  p.q = static_cast<const uint16_t*>(q);
+  p.k_cache = static_cast<const uint16_t*>(k_cache);
+  p.v_cache = static_cast<const uint16_t*>(v_cache);
+  p.seq_stride = seq_stride;
+  p.nb_capacity = nb_capacity;
+  p.n_ctx = n_ctx;
+  p.idx = idx;
+  p.n_sel = n_sel;
+  p.k_cap = k_cap;
+  p.out = static_cast<uint16_t*>(out);
+  p.lse = lse;
+  p.part = scratch;
+  p.m = m;
+  p.n_q_heads = sh.n_q_heads;
+  p.n_kv_heads = sh.n_kv_heads;
+  p.n_init = sh.n_init;
+  p.n_local = sh.n_local;
+  p.splits = splits;
+  p.n_qtiles = prefill_mfma_qtiles(sh, m);
+  p.scale_log2e = scale * 1.4426950408889634f;
+  dim3 grid(p.n_qtiles * sh.n_kv_heads * splits, batch);
+  hipLaunchKernelGGL(attn_prefill_mfma_kernel, grid, dim3(kPfThreads), kPfLdsBytes, stream, p);
+  if (splits > 1) {
+    const unsigned groups = unsigned(batch) * p.n_qtiles * sh.n_kv_heads;
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(groups * kPfWaves / 4), dim3(256), 0, stream, p);
+  }
+  return hip_status("attention (prefill, matrix cores)");
+}
+
+}  // namespace actqkv

@@ -89,25 +89,6 @@ __device__ __forceinline__ float block_max(float v, float* red) {
   return t;
 }
 
-// "Last workgroup done" ticket: returns true in every thread of the workgroup
-// that arrives last out of `total` at `counter`, after making this workgroup's
-// global writes visible and the others' visible to it.  The last one resets
-// the counter, so a zero-filled counter stays reusable.  `flag` is one int of LDS.
-__device__ __forceinline__ bool last_block_done(unsigned int* counter, unsigned int total, int* flag) {
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    unsigned int t = atomicAdd(counter, 1u);
-    int last = (t == total - 1u);
-    if (last) *counter = 0u;
-    *flag = last;
-  }
-  __syncthreads();
-  bool last = (*flag != 0);
-  if (last) __threadfence();
-  return last;
-}
-
 // ---- window geometry -------------------------------------------------------
 // Tokens [0, i0) are the visible initial tokens; the local span starts at l0.
 struct WindowGeom {

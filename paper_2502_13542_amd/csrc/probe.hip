@@ -1,110 +1,138 @@
 // Activation Bias and probe-Query (Sec. 4.1, Eq. (7)-(9)).
 //
-// Three phases, each bounded by one pass over the window's queries Q^t [m][d]:
-//   stats   per-channel sums of the window, merged into the running
-//           (n, mean, M2) of Eq. (8) by the last workgroup to finish;
-//   bias    a_j = sum_c (q_jc - mean_c)^2 / var_c = |phi_j|_1 of Eq. (7), one row per token;
-//   reduce  probe = sum_j (a_j / sum a) q_j of Eq. (9), column slabs in parallel, then
-//           the last workgroup adds the norm and the per-KV-head sum of the probe.
+// Each phase needs a result over the whole window from the phase before, so the
+// call is a chain of five short kernels over the window's queries Q^t [m][d]
+// (a kernel boundary is the cheapest grid-wide dependency on this chip: device-scope
+// fences inside a kernel write back and invalidate the whole L2):
+//   stats     per-channel partial sums of the window, 32 rows per workgroup;
+//   merge     the partial sums are merged into the running (n, mean, M2) of Eq. (8);
+//   bias      a_j = sum_c (q_jc - mean_c)^2 / var_c = |phi_j|_1 of Eq. (7), one row per token;
+//   reduce    partial sums of a_j q_j over row slices, column slabs in parallel;
+//   finish    probe = sum_j (a_j / sum a) q_j of Eq. (9), its norm and its per-KV-head sum.
 // All sums are fp32 and are taken in a fixed order, so results are reproducible.
 #include "common.h"
 #include "launch.h"
 
 namespace actqkv {
 
-constexpr int kStatsThreads = 1024;  // 64 column lanes x 16 row lanes
-constexpr int kStatsRowLanes = 16;
+constexpr int kStatsThreads = 256;   // 64 column lanes x 4 row lanes
+constexpr int kStatsRowLanes = 4;
+constexpr int kStatsRowsPerThread = 8;
+constexpr int kStatsRowsPerWG = kStatsRowLanes * kStatsRowsPerThread;  // 32
 
+// grid (column slabs of 64*V channels, row splits of 32 rows, batch): partial sums of
+// (q - shift) and (q - shift)^2 per channel, shift = the old mean (or the window's first
+// query when there is no history), which keeps the squares free of cancellation.
 template <typename T>
 __global__ __launch_bounds__(kStatsThreads) void probe_stats_kernel(
-    const T* __restrict__ q_win, float* __restrict__ stats, float* __restrict__ scratch,
-    unsigned int* __restrict__ counters, int m, int d, float eps, size_t stats_stride,
-    size_t scratch_stride) {
+    const T* __restrict__ q_win, const float* __restrict__ stats, float* __restrict__ scratch, int m,
+    int d, size_t stats_stride, size_t scratch_stride) {
   constexpr int V = Vec<T>::N;
-  __shared__ float red[kStatsRowLanes][64 * V];
-  __shared__ int flag;
-  const int s = blockIdx.z;
+  constexpr int SLAB = 64 * V;
+  __shared__ float red[2][kStatsRowLanes][SLAB];
+  const int s = blockIdx.z, slab = blockIdx.x;
   const T* q = q_win + size_t(s) * m * d;
-  float* st = stats + size_t(s) * stats_stride;
-  float* sc = scratch + size_t(s) * scratch_stride;
-  float* sc_mean = sc;
-  float* sc_inv = sc + d;
-  float* part = sc + 2 * size_t(d) + probe_a_floats(m);  // [splits][2][d]
-  const int splits = gridDim.y;
+  const float* st = stats + size_t(s) * stats_stride;
+  float* part = scratch + size_t(s) * scratch_stride + 2 * size_t(d) + probe_a_floats(m);
   const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
-  const int ch0 = (blockIdx.x * 64 + cl) * V;
+  const int ch0 = slab * SLAB + cl * V;
   const float n_old = st[0];
   const float* mean_old = st + 4;
 
-  // shift: the old mean, or the window's first query when there is no history
   float c[V], s1[V], s2[V];
-  const bool active = ch0 < d;
-  if (active) {
+#pragma unroll
+  for (int v = 0; v < V; ++v) c[v] = s1[v] = s2[v] = 0.f;
+  if (ch0 < d) {
     if (n_old > 0.f) {
 #pragma unroll
       for (int v = 0; v < V; ++v) c[v] = mean_old[ch0 + v];
     } else {
       Vec<T>::load(q + ch0, c);
     }
-  }
+    const int r0 = blockIdx.y * kStatsRowsPerWG + rl;
+    float x[kStatsRowsPerThread][V];
 #pragma unroll
-  for (int v = 0; v < V; ++v) s1[v] = s2[v] = 0.f;
-  const int rows_per = (m + splits - 1) / splits;
-  const int r0 = blockIdx.y * rows_per, r1 = min(m, r0 + rows_per);
-  if (active) {
-    for (int r = r0 + rl; r < r1; r += kStatsRowLanes) {
-      float x[V];
-      Vec<T>::load(q + size_t(r) * d + ch0, x);
+    for (int i = 0; i < kStatsRowsPerThread; ++i) {   // all loads first: they overlap
+      const int r = r0 + i * kStatsRowLanes;
+      Vec<T>::load(q + size_t(r < m ? r : 0) * d + ch0, x[i]);
+    }
 #pragma unroll
-      for (int v = 0; v < V; ++v) {
-        float t = x[v] - c[v];
-        s1[v] += t;
-        s2[v] += t * t;
+    for (int i = 0; i < kStatsRowsPerThread; ++i) {
+      if (r0 + i * kStatsRowLanes < m) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+          float t = x[i][v] - c[v];
+          s1[v] += t;
+          s2[v] += t * t;
+        }
       }
     }
   }
-  // reduce over the 16 row lanes, first the sums, then the sums of squares
-  for (int pass = 0; pass < 2; ++pass) {
-    __syncthreads();
 #pragma unroll
-    for (int v = 0; v < V; ++v) red[rl][cl * V + v] = pass == 0 ? s1[v] : s2[v];
-    __syncthreads();
-    for (int col = threadIdx.x; col < 64 * V; col += kStatsThreads) {
-      int ch = blockIdx.x * 64 * V + col;
-      if (ch < d) {
-        float t = 0.f;
-#pragma unroll
-        for (int i = 0; i < kStatsRowLanes; ++i) t += red[i][col];
-        part[(size_t(blockIdx.y) * 2 + pass) * d + ch] = t;
-      }
-    }
-  }
-
-  if (!last_block_done(counters + s, gridDim.x * gridDim.y, &flag)) return;
-
-  // merge the window into the running statistics (pairwise update of Eq. (8))
-  const float nb = float(m), n_new = n_old + nb;
-  for (int ch = threadIdx.x; ch < d; ch += kStatsThreads) {
-    float t1 = 0.f, t2 = 0.f;
-    for (int i = 0; i < splits; ++i) {
-      t1 += part[(size_t(i) * 2 + 0) * d + ch];
-      t2 += part[(size_t(i) * 2 + 1) * d + ch];
-    }
-    float mean_a = mean_old[ch];
-    float shift = n_old > 0.f ? mean_a : to_f32(q[ch]);
-    float mean_b = shift + t1 / nb;
-    float m2_b = fmaxf(t2 - t1 * t1 / nb, 0.f);
-    float delta = mean_b - mean_a;
-    float mean = n_old > 0.f ? mean_a + delta * (nb / n_new) : mean_b;
-    float m2 = n_old > 0.f ? st[4 + d + ch] + m2_b + delta * delta * (n_old * nb / n_new) : m2_b;
-    st[4 + ch] = mean;
-    st[4 + d + ch] = m2;
-    float var = n_new > 1.f ? m2 / (n_new - 1.f) : 0.f;
-    sc_mean[ch] = mean;
-    sc_inv[ch] = 1.f / fmaxf(var, eps);
+  for (int v = 0; v < V; ++v) {
+    red[0][rl][cl * V + v] = s1[v];
+    red[1][rl][cl * V + v] = s2[v];
   }
   __syncthreads();
-  if (threadIdx.x == 0) st[0] = n_new;
+  for (int i = threadIdx.x; i < 2 * SLAB; i += kStatsThreads) {
+    const int pass = i / SLAB, col = i % SLAB, ch = slab * SLAB + col;
+    if (ch < d) {
+      float t = 0.f;
+#pragma unroll
+      for (int k = 0; k < kStatsRowLanes; ++k) t += red[pass][k][col];
+      part[(size_t(blockIdx.y) * 2 + pass) * d + ch] = t;
+    }
+  }
+}
+
+// One thread per channel: the window's partial sums are merged into the running
+// statistics (pairwise update of the mean and the squared deviations of Eq. (8)), and
+// mean and 1/variance are put where the bias phase reads them.
+template <typename T>
+__global__ __launch_bounds__(256) void probe_merge_kernel(const T* __restrict__ q_win,
+                                                          float* __restrict__ stats,
+                                                          float* __restrict__ scratch, int m, int d,
+                                                          int splits, float eps, size_t stats_stride,
+                                                          size_t scratch_stride) {
+  const int s = blockIdx.y;
+  const int ch = blockIdx.x * 256 + threadIdx.x;
+  float* st = stats + size_t(s) * stats_stride;
+  float* sc = scratch + size_t(s) * scratch_stride;
+  const float* part = sc + 2 * size_t(d) + probe_a_floats(m);
+  const float n_old = st[0];
+  const float nb = float(m), n_new = n_old + nb;
+  if (ch < d) {
+    float t1 = 0.f, t2 = 0.f;
+    for (int i0 = 0; i0 < splits; i0 += 16) {
+      float a1[16], a2[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {              // all loads first: they overlap
+        const int k = i0 + i < splits ? i0 + i : i0;
+        a1[i] = part[(size_t(k) * 2 + 0) * d + ch];
+        a2[i] = part[(size_t(k) * 2 + 1) * d + ch];
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        if (i0 + i < splits) {
+          t1 += a1[i];
+          t2 += a2[i];
+        }
+      }
+    }
+    const float mean_a = st[4 + ch];
+    const float shift = n_old > 0.f ? mean_a : to_f32(q_win[size_t(s) * m * d + ch]);
+    const float mean_b = shift + t1 / nb;
+    const float m2_b = fmaxf(t2 - t1 * t1 / nb, 0.f);
+    const float delta = mean_b - mean_a;
+    const float mean = n_old > 0.f ? mean_a + delta * (nb / n_new) : mean_b;
+    const float m2 = n_old > 0.f ? st[4 + d + ch] + m2_b + delta * delta * (n_old * nb / n_new) : m2_b;
+    st[4 + ch] = mean;
+    st[4 + d + ch] = m2;
+    const float var = n_new > 1.f ? m2 / (n_new - 1.f) : 0.f;
+    sc[ch] = mean;
+    sc[d + ch] = 1.f / fmaxf(var, eps);
+  }
+  // the count is published by the kernel that follows (every thread here reads the old one)
 }
 
 // Statistics used as they are: only mean and 1/var are put where the next phase reads them.
@@ -126,8 +154,10 @@ constexpr int kBiasRows = 4;
 
 template <typename T>
 __global__ __launch_bounds__(256) void probe_bias_kernel(const T* __restrict__ q_win,
-                                                         float* __restrict__ scratch, int m, int d,
-                                                         size_t scratch_stride) {
+                                                         float* __restrict__ scratch,
+                                                         float* __restrict__ stats, int add_count, int m,
+                                                         int d, size_t scratch_stride,
+                                                         size_t stats_stride) {
   constexpr int V = Vec<T>::N;
   __shared__ float red[4][kBiasRows];
   const int s = blockIdx.y;
@@ -137,6 +167,7 @@ __global__ __launch_bounds__(256) void probe_bias_kernel(const T* __restrict__ q
   const float* inv = sc + d;
   float* a = sc + 2 * size_t(d);
   const int r0 = blockIdx.x * kBiasRows;
+  if (add_count && blockIdx.x == 0 && threadIdx.x == 0) stats[size_t(s) * stats_stride] += float(m);
   float acc[kBiasRows];
 #pragma unroll
   for (int i = 0; i < kBiasRows; ++i) acc[i] = 0.f;
@@ -149,14 +180,16 @@ __global__ __launch_bounds__(256) void probe_bias_kernel(const T* __restrict__ q
       mu[v] = a4.x; mu[v + 1] = a4.y; mu[v + 2] = a4.z; mu[v + 3] = a4.w;
       iv[v] = b4.x; iv[v + 1] = b4.y; iv[v + 2] = b4.z; iv[v + 3] = b4.w;
     }
+    float x[kBiasRows][V];
+#pragma unroll
+    for (int i = 0; i < kBiasRows; ++i)          // all loads first: they overlap
+      Vec<T>::load(q + size_t(r0 + i < m ? r0 + i : r0) * d + ch, x[i]);
 #pragma unroll
     for (int i = 0; i < kBiasRows; ++i) {
       if (r0 + i < m) {
-        float x[V];
-        Vec<T>::load(q + size_t(r0 + i) * d + ch, x);
 #pragma unroll
         for (int v = 0; v < V; ++v) {
-          float t = x[v] - mu[v];
+          float t = x[i][v] - mu[v];
           acc[i] += t * t * iv[v];
         }
       }
@@ -191,40 +224,51 @@ __device__ __forceinline__ void probe_finish(const float* probe, float* probe_kv
   }
 }
 
+constexpr int kReduceRowSplits = 4;
+
+// grid (column slabs of 16*V channels, kReduceRowSplits, batch); 256 threads = 16 column
+// lanes x 16 row lanes.  Partial weighted sums sum_j w_j q_j over a slice of the rows.
 template <typename T>
-__global__ __launch_bounds__(256) void probe_reduce_kernel(
-    const T* __restrict__ q_win, const float* __restrict__ scratch, unsigned int* __restrict__ counters,
-    float* __restrict__ probe_out, float* __restrict__ probe_kv_out, float* __restrict__ probe_norm_out,
-    float* __restrict__ weights_out, int m, int n_q_heads, int n_kv_heads, int head_dim,
-    size_t scratch_stride) {
+__global__ __launch_bounds__(256) void probe_reduce_kernel(const T* __restrict__ q_win,
+                                                           float* __restrict__ scratch,
+                                                           float* __restrict__ weights_out, int m,
+                                                           int d, size_t scratch_stride) {
   constexpr int V = Vec<T>::N;
   __shared__ float red[32];
   __shared__ float buf[16][16 * V];
-  __shared__ int flag;
-  const int d = n_q_heads * head_dim;
-  const int s = blockIdx.y;
+  const int s = blockIdx.z;
   const T* q = q_win + size_t(s) * m * d;
-  const float* a = scratch + size_t(s) * scratch_stride + 2 * size_t(d);
-  float* probe = probe_out + size_t(s) * d;
+  float* sc = scratch + size_t(s) * scratch_stride;
+  const float* a = sc + 2 * size_t(d);
+  float* part = sc + 2 * size_t(d) + probe_a_floats(m);   // [kReduceRowSplits][d]
 
-  float part = 0.f;
-  for (int j = threadIdx.x; j < m; j += 256) part += a[j];
-  const float total = block_sum(part, red);          // |Phi|_1
+  float tsum = 0.f;
+  for (int j = threadIdx.x; j < m; j += 256) tsum += a[j];
+  const float total = block_sum(tsum, red);          // |Phi|_1
   const float inv_total = total > 0.f ? 1.f / total : 0.f;
   const float uniform = 1.f / float(m);
 
   const int cl = threadIdx.x & 15, rl = threadIdx.x >> 4;
   const int ch0 = (blockIdx.x * 16 + cl) * V;
+  const int rows_per = (m + kReduceRowSplits - 1) / kReduceRowSplits;
+  const int r_begin = blockIdx.y * rows_per, r_end = min(m, r_begin + rows_per);
   float acc[V];
 #pragma unroll
   for (int v = 0; v < V; ++v) acc[v] = 0.f;
   if (ch0 < d) {
-    for (int j = rl; j < m; j += 16) {
-      float w = total > 0.f ? a[j] * inv_total : uniform;
-      float x[V];
-      Vec<T>::load(q + size_t(j) * d + ch0, x);
+    for (int j0 = r_begin + rl; j0 < r_end; j0 += 16 * 8) {
+      float x[8][V], w[8];
 #pragma unroll
-      for (int v = 0; v < V; ++v) acc[v] += w * x[v];
+      for (int i = 0; i < 8; ++i) {                    // 8 independent loads in flight
+        const int j = j0 + 16 * i;
+        const int jj = j < r_end ? j : r_begin;
+        Vec<T>::load(q + size_t(jj) * d + ch0, x[i]);
+        w[i] = j < r_end ? (total > 0.f ? a[jj] * inv_total : uniform) : 0.f;
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[v] += w[i] * x[i][v];
     }
   }
 #pragma unroll
@@ -236,14 +280,34 @@ __global__ __launch_bounds__(256) void probe_reduce_kernel(
       float t = 0.f;
 #pragma unroll
       for (int i = 0; i < 16; ++i) t += buf[i][threadIdx.x];
-      probe[ch] = t;
+      part[size_t(blockIdx.y) * d + ch] = t;
     }
   }
-  if (blockIdx.x == 0 && weights_out != nullptr) {
+  if (blockIdx.x == 0 && blockIdx.y == 0 && weights_out != nullptr) {
     for (int j = threadIdx.x; j < m; j += 256)
       weights_out[size_t(s) * m + j] = total > 0.f ? a[j] * inv_total : uniform;
   }
-  if (!last_block_done(counters + s, gridDim.x, &flag)) return;
+}
+
+// One workgroup per sequence: adds the row slices up in a fixed order and finishes the probe.
+__global__ __launch_bounds__(1024) void probe_finish_kernel(const float* __restrict__ scratch,
+                                                            float* __restrict__ probe_out,
+                                                            float* __restrict__ probe_kv_out,
+                                                            float* __restrict__ probe_norm_out, int m,
+                                                            int n_q_heads, int n_kv_heads, int head_dim,
+                                                            size_t scratch_stride) {
+  __shared__ float red[32];
+  const int d = n_q_heads * head_dim;
+  const int s = blockIdx.x;
+  const float* part = scratch + size_t(s) * scratch_stride + 2 * size_t(d) + probe_a_floats(m);
+  float* probe = probe_out + size_t(s) * d;
+  for (int ch = threadIdx.x * 4; ch < d; ch += 1024 * 4) {
+    f32x4 t = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < kReduceRowSplits; ++i) t += *reinterpret_cast<const f32x4*>(part + size_t(i) * d + ch);
+    *reinterpret_cast<f32x4*>(probe + ch) = t;
+  }
+  __syncthreads();
   probe_finish(probe, probe_kv_out + size_t(s) * n_kv_heads * head_dim, probe_norm_out + s,
                n_q_heads, n_kv_heads, head_dim, red);
 }
@@ -251,12 +315,13 @@ __global__ __launch_bounds__(256) void probe_reduce_kernel(
 // A window of one token (decode): Eq. (9) has a single weight, 1, so the probe is the query.
 template <typename T>
 __global__ __launch_bounds__(256) void probe_identity_kernel(
-    const T* __restrict__ q_win, float* __restrict__ probe_out, float* __restrict__ probe_kv_out,
-    float* __restrict__ probe_norm_out, float* __restrict__ weights_out, int n_q_heads,
-    int n_kv_heads, int head_dim) {
+    const T* __restrict__ q_win, float* __restrict__ stats, int add_count, size_t stats_stride,
+    float* __restrict__ probe_out, float* __restrict__ probe_kv_out, float* __restrict__ probe_norm_out,
+    float* __restrict__ weights_out, int n_q_heads, int n_kv_heads, int head_dim) {
   __shared__ float red[32];
   const int d = n_q_heads * head_dim;
   const int s = blockIdx.x;
+  if (add_count && threadIdx.x == 0) stats[size_t(s) * stats_stride] += 1.f;
   float* probe = probe_out + size_t(s) * d;
   for (int ch = threadIdx.x; ch < d; ch += 256) probe[ch] = to_f32(q_win[size_t(s) * d + ch]);
   __syncthreads();
@@ -277,29 +342,35 @@ static int launch_probe_t(const actqkv_shape& sh, int batch, int m, const T* q_w
   float* scratch = ws.scratch_f32();
   const int splits = probe_stat_splits(m);
   if (update_stats) {
-    dim3 grid((d + 64 * V - 1) / (64 * V), splits, batch);
+    const int n_slabs = (d + 64 * V - 1) / (64 * V);
+    dim3 grid(n_slabs, splits, batch);
     hipLaunchKernelGGL(probe_stats_kernel<T>, grid, dim3(kStatsThreads), 0, stream, q_win, stats,
-                       scratch, ws.counters(), m, d, eps, stats_stride, scratch_stride);
+                       scratch, m, d, stats_stride, scratch_stride);
+    hipLaunchKernelGGL(probe_merge_kernel<T>, dim3((d + 255) / 256, batch), dim3(256), 0, stream, q_win,
+                       stats, scratch, m, d, splits, eps, stats_stride, scratch_stride);
   } else if (m > 1) {
     dim3 grid((d + 255) / 256, batch);
     hipLaunchKernelGGL(probe_prepare_kernel, grid, dim3(256), 0, stream, stats, scratch, d, eps,
                        stats_stride, scratch_stride);
   }
   if (m == 1) {
-    hipLaunchKernelGGL(probe_identity_kernel<T>, dim3(batch), dim3(256), 0, stream, q_win, probe,
-                       probe_kv, probe_norm, weights, sh.n_q_heads, sh.n_kv_heads, sh.head_dim);
+    hipLaunchKernelGGL(probe_identity_kernel<T>, dim3(batch), dim3(256), 0, stream, q_win, stats,
+                       update_stats, stats_stride, probe, probe_kv, probe_norm, weights, sh.n_q_heads,
+                       sh.n_kv_heads, sh.head_dim);
     return hip_status("probe");
   }
   {
     dim3 grid((m + kBiasRows - 1) / kBiasRows, batch);
-    hipLaunchKernelGGL(probe_bias_kernel<T>, grid, dim3(256), 0, stream, q_win, scratch, m, d,
-                       scratch_stride);
+    hipLaunchKernelGGL(probe_bias_kernel<T>, grid, dim3(256), 0, stream, q_win, scratch, stats,
+                       update_stats, m, d, scratch_stride, stats_stride);
   }
   {
-    dim3 grid((d + 16 * V - 1) / (16 * V), batch);
-    hipLaunchKernelGGL(probe_reduce_kernel<T>, grid, dim3(256), 0, stream, q_win, scratch,
-                       ws.counters(), probe, probe_kv, probe_norm, weights, m, sh.n_q_heads,
-                       sh.n_kv_heads, sh.head_dim, scratch_stride);
+    dim3 grid((d + 16 * V - 1) / (16 * V), kReduceRowSplits, batch);
+    hipLaunchKernelGGL(probe_reduce_kernel<T>, grid, dim3(256), 0, stream, q_win, scratch, weights, m,
+                       d, scratch_stride);
+    hipLaunchKernelGGL(probe_finish_kernel, dim3(batch), dim3(1024), 0, stream, scratch, probe,
+                       probe_kv, probe_norm, m, sh.n_q_heads, sh.n_kv_heads, sh.head_dim,
+                       scratch_stride);
   }
   return hip_status("probe");
 }

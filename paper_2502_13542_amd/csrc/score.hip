@@ -10,6 +10,8 @@
 
 namespace actqkv {
 
+constexpr int kScoreBatch = 8;  // 16-byte loads a lane keeps in flight
+
 template <typename T>
 __global__ __launch_bounds__(256) void score_blocks_kernel(
     const float* __restrict__ probe_kv, const float* __restrict__ probe_norm,
@@ -35,14 +37,23 @@ __global__ __launch_bounds__(256) void score_blocks_kernel(
     float dot = 0.f, nrm = 0.f;
     if (j < n_rep) {
       const T* key = block_keys + size_t(j) * key_len;
-#pragma unroll 4
-      for (int c = l16; c < chunks; c += 16) {
-        float k[V];
-        Vec<T>::load(key + c * V, k);
+      for (int c0 = l16; c0 < chunks; c0 += 16 * kScoreBatch) {
+        float k[kScoreBatch][V];
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-          dot += probe_lds[c * V + v] * k[v];
-          nrm += k[v] * k[v];
+        for (int i = 0; i < kScoreBatch; ++i) {   // all loads of the batch first: they overlap
+          const int c = c0 + 16 * i;
+          Vec<T>::load(key + (c < chunks ? c : l16) * V, k[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < kScoreBatch; ++i) {
+          const int c = c0 + 16 * i;
+          if (c < chunks) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+              dot += probe_lds[c * V + v] * k[i][v];
+              nrm += k[i][v] * k[i][v];
+            }
+          }
         }
       }
     }

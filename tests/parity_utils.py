@@ -82,5 +82,6 @@ def check_selection(gpu_idx: Sequence[int], gpu_count: int, res: Dict, k_cap: in
 def oracle_windows(q, k, v, rep, shape: LayerShape, m: int, k_cap: int, cutoffs=None,
                    attend: Optional[Sequence[int]] = None) -> List[Dict]:
     """The oracle's prefill over CPU copies of the tensors."""
-    return orc.prefill_layer(f64(q), f64(k), f64(v), f64(rep), m, shape.n_init, shape.n_local,
+    f32 = lambda t: t.detach().float().cpu().numpy()   # exact for bf16 and fp32; widened per window
+    return orc.prefill_layer(f32(q), f32(k), f32(v), f64(rep), m, shape.n_init, shape.n_local,
                              shape.block_size, k_cap, cutoffs, attend)

@@ -106,6 +106,17 @@ def test_llama_shape_bf16_cutoff_ragged():
     run_prefill_case(w, attend=[0, 3, 16])
 
 
+def test_c2_32k_full_size_sampled_windows():
+    # configs[1] at full size, in the launch configuration bench.py uses; the oracle checks the
+    # probe and the selection of every window and the attention of a spread of windows
+    run_prefill_case(synth.WORKLOADS["c2_32k"], attend=[0, 1, 7, 31, 63])
+
+
+def test_c3_128k_full_size_sampled_windows():
+    # configs[2] (the benchmarked workload) at full size with the dynamic cut-off
+    run_prefill_case(synth.WORKLOADS["c3_128k"], attend=[2, 64, 255])
+
+
 @pytest.mark.parametrize("n_init,n_local", [(0, 256), (128, 0), (256, 128)])
 def test_geometry_variants(n_init, n_local):
     sh = LayerShape(4, 2, 64, 128, 2, n_init, n_local, "fp32")
