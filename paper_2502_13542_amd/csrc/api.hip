@@ -188,13 +188,6 @@ int actqkv_build_probe(const actqkv_shape* shape, int batch, int m, const void* 
   size_t need = kCounterBytes + size_t(batch) * probe_scratch_floats(*shape, m) * sizeof(float);
   if (ws_bytes < need)
     return set_error(ACTQKV_EWORKSPACE, "workspace has %zu bytes, build_probe needs %zu", ws_bytes, need);
-  if (update_stats) {
-    const int vec = shape->dtype == ACTQKV_F32 ? 4 : 8;
-    const int n_slabs = (shape->n_q_heads * shape->head_dim + 64 * vec - 1) / (64 * vec);
-    if (batch * (n_slabs + 1) > 1024)
-      return set_error(ACTQKV_ESHAPE, "batch %d too large for a statistics update of %d channels", batch,
-                       shape->n_q_heads * shape->head_dim);
-  }
   Workspace ws{workspace, ws_bytes};
   return launch_probe(*shape, batch, m, q_win, stats, update_stats, probe, probe_kv, probe_norm,
                       weights, ws, static_cast<hipStream_t>(stream));

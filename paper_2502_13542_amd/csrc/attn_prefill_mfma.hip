@@ -34,6 +34,8 @@ constexpr int kPfD = 128;
 constexpr int kRowPad = 136;                         // bf16 elements per padded LDS row (272 bytes)
 constexpr int kTileElems = kBlock * kRowPad;         // one K or V^T tile in LDS
 constexpr int kPfLdsBytes = 2 * 2 * kTileElems * 2;  // 2 stages x (K, V^T) x bf16
+constexpr int kPfPartWords = 34;                     // per lane: 32 bf16 pairs + max + sum
+constexpr int kMaxPfSplits = 8;
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -62,7 +64,7 @@ struct PfParams {
   int k_cap;
   uint16_t* out;
   float* lse;
-  float* part;             // [workgroup][split][wave][64 registers + max + sum][64 lanes]
+  float* part;             // [workgroup][split][wave][32 bf16 pairs + max + sum][64 lanes]
   int m, n_q_heads, n_kv_heads, n_init, n_local;
   int splits, n_qtiles;
   float scale_log2e;
@@ -264,16 +266,20 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
   // ---- epilogue
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (p.splits > 1) {
-    // The split stores its accumulators exactly as the registers hold them (register-major,
-    // lane-minor: every store is one contiguous 256-byte row); attn_combine_kernel merges them.
+    // The split stores its normalised output as bf16 pairs in the order the registers hold
+    // them (register-major, lane-minor: every store is one contiguous 256-byte row), plus its
+    // running max and sum; attn_combine_kernel merges the splits.
     const size_t group_id = (size_t(s) * p.n_qtiles + qtile) * p.n_kv_heads + hk;
-    float* mine = p.part + ((group_id * p.splits + split) * kPfWaves + wave) * (66 * 64);
+    uint32_t* mine = reinterpret_cast<uint32_t*>(p.part) +
+                     ((group_id * p.splits + split) * kPfWaves + wave) * (kPfPartWords * 64);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) mine[(db * 16 + i) * 64 + lane] = acc_o[db][i];
-    mine[64 * 64 + lane] = m_run;
-    mine[65 * 64 + lane] = l_tot;
+      for (int i = 0; i < 8; ++i)
+        mine[(db * 8 + i) * 64 + lane] = pack_bf16x2(acc_o[db][2 * i] * inv, acc_o[db][2 * i + 1] * inv);
+    mine[32 * 64 + lane] = __float_as_uint(m_run);
+    mine[33 * 64 + lane] = __float_as_uint(l_tot);
     return;
   }
   if (row_ok) store_rows(p, acc_o, m_run, l_tot, s, my_row, head, half);
@@ -296,27 +302,42 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(PfParams p) {
   const int head = hk * group + wave / waves_per_head;
   const int my_row = qtile * 32 * waves_per_head + (wave % waves_per_head) * 32 + n;
 
+  // out = sum_s w_s o_s / sum_s w_s with w_s = l_s 2^(m_s - M), M = max_s m_s
+  uint32_t raw[kMaxPfSplits][kPfPartWords];
+#pragma unroll
+  for (int s2 = 0; s2 < kMaxPfSplits; ++s2) {
+    if (s2 < p.splits) {
+      const uint32_t* other = reinterpret_cast<const uint32_t*>(p.part) +
+                              ((group_id * p.splits + s2) * kPfWaves + wave) * (kPfPartWords * 64);
+#pragma unroll
+      for (int k = 0; k < kPfPartWords; ++k) raw[s2][k] = other[k * 64 + lane];  // loads first
+    }
+  }
+  float m_run = -INFINITY;
+#pragma unroll
+  for (int s2 = 0; s2 < kMaxPfSplits; ++s2)
+    if (s2 < p.splits) m_run = fmaxf(m_run, __uint_as_float(raw[s2][32]));
+  const float m_safe = m_run == -INFINITY ? 0.f : m_run;
   f32x16 acc_o[4];
-  float m_run = -INFINITY, l_tot = 0.f;
+  float l_tot = 0.f;
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc_o[db][i] = 0.f;
-  for (int s2 = 0; s2 < p.splits; ++s2) {
-    const float* other = p.part + ((group_id * p.splits + s2) * kPfWaves + wave) * (66 * 64);
-    float tmp[66];
 #pragma unroll
-    for (int k = 0; k < 66; ++k) tmp[k] = other[k * 64 + lane];   // all loads first: they overlap
-    const float m_o = tmp[64], l_o = tmp[65];
-    const float m_new = fmaxf(m_run, m_o);
-    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-    const float wa = __builtin_amdgcn_exp2f(m_run - m_safe), wb = __builtin_amdgcn_exp2f(m_o - m_safe);
+  for (int s2 = 0; s2 < kMaxPfSplits; ++s2) {
+    if (s2 < p.splits) {
+      const float w = __uint_as_float(raw[s2][33]) *
+                      __builtin_amdgcn_exp2f(__uint_as_float(raw[s2][32]) - m_safe);
+      l_tot += w;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+      for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc_o[db][i] = acc_o[db][i] * wa + tmp[db * 16 + i] * wb;
-    l_tot = l_tot * wa + l_o * wb;
-    m_run = m_new;
+        for (int i = 0; i < 8; ++i) {
+          acc_o[db][2 * i] += w * bf16_lo(raw[s2][db * 8 + i]);
+          acc_o[db][2 * i + 1] += w * bf16_hi(raw[s2][db * 8 + i]);
+        }
+    }
   }
   if (my_row < p.m) store_rows(p, acc_o, m_run, l_tot, s, my_row, head, half);
 }

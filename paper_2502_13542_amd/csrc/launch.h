@@ -20,13 +20,11 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline size_t stats_floats(const actqkv_shape& sh) {
   return 4 + 2 * size_t(sh.n_q_heads) * sh.head_dim;
 }
-inline int probe_stat_splits(int m) { return (m + 31) / 32; }
 __host__ __device__ inline size_t probe_a_floats(int m) { return (size_t(m) + 3) / 4 * 4; }
-// per sequence: mean[d], inv_var[d], a[m], partial sums [row splits][2][d]
+// per sequence: mean[d], inv_var[d], a[m], partial weighted sums [4 row slices][d]
 inline size_t probe_scratch_floats(const actqkv_shape& sh, int m) {
   size_t d = size_t(sh.n_q_heads) * sh.head_dim;
-  size_t splits = size_t(probe_stat_splits(m) > 4 ? probe_stat_splits(m) : 4);
-  return 2 * d + probe_a_floats(m) + splits * 2 * d;
+  return 2 * d + probe_a_floats(m) + 4 * d;
 }
 
 // Key-tile splits of the prefill attention and of the decode attention.
@@ -37,9 +35,9 @@ int decode_splits(const actqkv_shape& sh, int batch, int k_cap);
 inline size_t attn_scratch_floats(const actqkv_shape& sh, int batch, int m, int splits) {
   return size_t(batch) * m * sh.n_q_heads * splits * (size_t(sh.head_dim) + 2);
 }
-// prefill on the matrix cores: per workgroup and split, 8 wavefronts x (64 accumulator
-// registers + max + sum) x 64 lanes
-constexpr size_t kPfPartialFloats = 8 * (64 + 2) * 64;
+// prefill on the matrix cores: per workgroup and split, 8 wavefronts x (32 bf16 pairs of
+// normalised output + max + sum) x 64 lanes
+constexpr size_t kPfPartialFloats = 8 * (32 + 2) * 64;
 constexpr int kMaxWindow = 8192;
 
 constexpr size_t kCounterBytes = 4096;  // 1024 uint32 tickets at the head of the workspace

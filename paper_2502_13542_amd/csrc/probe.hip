@@ -1,11 +1,10 @@
 // Activation Bias and probe-Query (Sec. 4.1, Eq. (7)-(9)).
 //
 // Each phase needs a result over the whole window from the phase before, so the
-// call is a chain of five short kernels over the window's queries Q^t [m][d]
+// call is a chain of four short kernels over the window's queries Q^t [m][d]
 // (a kernel boundary is the cheapest grid-wide dependency on this chip: device-scope
 // fences inside a kernel write back and invalidate the whole L2):
-//   stats     per-channel partial sums of the window, 32 rows per workgroup;
-//   merge     the partial sums are merged into the running (n, mean, M2) of Eq. (8);
+//   stats     per-channel sums of the window, merged into the running (n, mean, M2) of Eq. (8);
 //   bias      a_j = sum_c (q_jc - mean_c)^2 / var_c = |phi_j|_1 of Eq. (7), one row per token;
 //   reduce    partial sums of a_j q_j over row slices, column slabs in parallel;
 //   finish    probe = sum_j (a_j / sum a) q_j of Eq. (9), its norm and its per-KV-head sum.
@@ -15,29 +14,32 @@
 
 namespace actqkv {
 
-constexpr int kStatsThreads = 256;   // 64 column lanes x 4 row lanes
-constexpr int kStatsRowLanes = 4;
-constexpr int kStatsRowsPerThread = 8;
-constexpr int kStatsRowsPerWG = kStatsRowLanes * kStatsRowsPerThread;  // 32
+constexpr int kStatsBatch = 8;   // 16-byte loads a thread keeps in flight
+constexpr int kStatsColLanes = 8, kStatsRowLanes = 32;
 
-// grid (column slabs of 64*V channels, row splits of 32 rows, batch): partial sums of
-// (q - shift) and (q - shift)^2 per channel, shift = the old mean (or the window's first
-// query when there is no history), which keeps the squares free of cancellation.
+// Running statistics of Eq. (8).  grid (column slabs of 8*V channels, batch); 256 threads
+// = 8 column lanes x 32 row lanes.  A workgroup owns its channels for ALL rows of the
+// window, so it can merge them into the running (mean, M2) itself (pairwise update) and no
+// second pass over partial sums is needed.  Sums are taken of (q - shift), shift = the old
+// mean (or the window's first query when there is no history), which keeps the squares
+// free of cancellation.  The count n is published by the next kernel of the chain (every
+// workgroup here reads the old one).
 template <typename T>
-__global__ __launch_bounds__(kStatsThreads) void probe_stats_kernel(
-    const T* __restrict__ q_win, const float* __restrict__ stats, float* __restrict__ scratch, int m,
-    int d, size_t stats_stride, size_t scratch_stride) {
+__global__ __launch_bounds__(256) void probe_stats_kernel(const T* __restrict__ q_win,
+                                                          float* __restrict__ stats,
+                                                          float* __restrict__ scratch, int m, int d,
+                                                          float eps, size_t stats_stride,
+                                                          size_t scratch_stride) {
   constexpr int V = Vec<T>::N;
-  constexpr int SLAB = 64 * V;
+  constexpr int SLAB = kStatsColLanes * V;
   __shared__ float red[2][kStatsRowLanes][SLAB];
-  const int s = blockIdx.z, slab = blockIdx.x;
+  const int s = blockIdx.y;
   const T* q = q_win + size_t(s) * m * d;
-  const float* st = stats + size_t(s) * stats_stride;
-  float* part = scratch + size_t(s) * scratch_stride + 2 * size_t(d) + probe_a_floats(m);
-  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
-  const int ch0 = slab * SLAB + cl * V;
+  float* st = stats + size_t(s) * stats_stride;
+  float* sc = scratch + size_t(s) * scratch_stride;
+  const int cl = threadIdx.x % kStatsColLanes, rl = threadIdx.x / kStatsColLanes;
+  const int ch0 = blockIdx.x * SLAB + cl * V;
   const float n_old = st[0];
-  const float* mean_old = st + 4;
 
   float c[V], s1[V], s2[V];
 #pragma unroll
@@ -45,25 +47,26 @@ __global__ __launch_bounds__(kStatsThreads) void probe_stats_kernel(
   if (ch0 < d) {
     if (n_old > 0.f) {
 #pragma unroll
-      for (int v = 0; v < V; ++v) c[v] = mean_old[ch0 + v];
+      for (int v = 0; v < V; ++v) c[v] = st[4 + ch0 + v];
     } else {
       Vec<T>::load(q + ch0, c);
     }
-    const int r0 = blockIdx.y * kStatsRowsPerWG + rl;
-    float x[kStatsRowsPerThread][V];
+    for (int r0 = rl; r0 < m; r0 += kStatsRowLanes * kStatsBatch) {
+      float x[kStatsBatch][V];
 #pragma unroll
-    for (int i = 0; i < kStatsRowsPerThread; ++i) {   // all loads first: they overlap
-      const int r = r0 + i * kStatsRowLanes;
-      Vec<T>::load(q + size_t(r < m ? r : 0) * d + ch0, x[i]);
-    }
+      for (int i = 0; i < kStatsBatch; ++i) {   // all loads first: they overlap
+        const int r = r0 + kStatsRowLanes * i;
+        Vec<T>::load(q + size_t(r < m ? r : 0) * d + ch0, x[i]);
+      }
 #pragma unroll
-    for (int i = 0; i < kStatsRowsPerThread; ++i) {
-      if (r0 + i * kStatsRowLanes < m) {
+      for (int i = 0; i < kStatsBatch; ++i) {
+        if (r0 + kStatsRowLanes * i < m) {
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-          float t = x[i][v] - c[v];
-          s1[v] += t;
-          s2[v] += t * t;
+          for (int v = 0; v < V; ++v) {
+            float t = x[i][v] - c[v];
+            s1[v] += t;
+            s2[v] += t * t;
+          }
         }
       }
     }
@@ -74,53 +77,17 @@ __global__ __launch_bounds__(kStatsThreads) void probe_stats_kernel(
     red[1][rl][cl * V + v] = s2[v];
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < 2 * SLAB; i += kStatsThreads) {
-    const int pass = i / SLAB, col = i % SLAB, ch = slab * SLAB + col;
-    if (ch < d) {
-      float t = 0.f;
-#pragma unroll
-      for (int k = 0; k < kStatsRowLanes; ++k) t += red[pass][k][col];
-      part[(size_t(blockIdx.y) * 2 + pass) * d + ch] = t;
-    }
-  }
-}
-
-// One thread per channel: the window's partial sums are merged into the running
-// statistics (pairwise update of the mean and the squared deviations of Eq. (8)), and
-// mean and 1/variance are put where the bias phase reads them.
-template <typename T>
-__global__ __launch_bounds__(256) void probe_merge_kernel(const T* __restrict__ q_win,
-                                                          float* __restrict__ stats,
-                                                          float* __restrict__ scratch, int m, int d,
-                                                          int splits, float eps, size_t stats_stride,
-                                                          size_t scratch_stride) {
-  const int s = blockIdx.y;
-  const int ch = blockIdx.x * 256 + threadIdx.x;
-  float* st = stats + size_t(s) * stats_stride;
-  float* sc = scratch + size_t(s) * scratch_stride;
-  const float* part = sc + 2 * size_t(d) + probe_a_floats(m);
-  const float n_old = st[0];
-  const float nb = float(m), n_new = n_old + nb;
-  if (ch < d) {
+  const int col = threadIdx.x, ch = blockIdx.x * SLAB + col;
+  if (col < SLAB && ch < d) {
     float t1 = 0.f, t2 = 0.f;
-    for (int i0 = 0; i0 < splits; i0 += 16) {
-      float a1[16], a2[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {              // all loads first: they overlap
-        const int k = i0 + i < splits ? i0 + i : i0;
-        a1[i] = part[(size_t(k) * 2 + 0) * d + ch];
-        a2[i] = part[(size_t(k) * 2 + 1) * d + ch];
-      }
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        if (i0 + i < splits) {
-          t1 += a1[i];
-          t2 += a2[i];
-        }
-      }
+    for (int k = 0; k < kStatsRowLanes; ++k) {
+      t1 += red[0][k][col];
+      t2 += red[1][k][col];
     }
+    const float nb = float(m), n_new = n_old + nb;
     const float mean_a = st[4 + ch];
-    const float shift = n_old > 0.f ? mean_a : to_f32(q_win[size_t(s) * m * d + ch]);
+    const float shift = n_old > 0.f ? mean_a : to_f32(q[ch]);
     const float mean_b = shift + t1 / nb;
     const float m2_b = fmaxf(t2 - t1 * t1 / nb, 0.f);
     const float delta = mean_b - mean_a;
@@ -132,7 +99,6 @@ __global__ __launch_bounds__(256) void probe_merge_kernel(const T* __restrict__ 
     sc[ch] = mean;
     sc[d + ch] = 1.f / fmaxf(var, eps);
   }
-  // the count is published by the kernel that follows (every thread here reads the old one)
 }
 
 // Statistics used as they are: only mean and 1/var are put where the next phase reads them.
@@ -340,14 +306,10 @@ static int launch_probe_t(const actqkv_shape& sh, int batch, int m, const T* q_w
   const size_t stats_stride = stats_floats(sh);
   const size_t scratch_stride = probe_scratch_floats(sh, m);
   float* scratch = ws.scratch_f32();
-  const int splits = probe_stat_splits(m);
   if (update_stats) {
-    const int n_slabs = (d + 64 * V - 1) / (64 * V);
-    dim3 grid(n_slabs, splits, batch);
-    hipLaunchKernelGGL(probe_stats_kernel<T>, grid, dim3(kStatsThreads), 0, stream, q_win, stats,
-                       scratch, m, d, stats_stride, scratch_stride);
-    hipLaunchKernelGGL(probe_merge_kernel<T>, dim3((d + 255) / 256, batch), dim3(256), 0, stream, q_win,
-                       stats, scratch, m, d, splits, eps, stats_stride, scratch_stride);
+    dim3 grid((d + kStatsColLanes * V - 1) / (kStatsColLanes * V), batch);
+    hipLaunchKernelGGL(probe_stats_kernel<T>, grid, dim3(256), 0, stream, q_win, stats, scratch, m, d,
+                       eps, stats_stride, scratch_stride);
   } else if (m > 1) {
     dim3 grid((d + 255) / 256, batch);
     hipLaunchKernelGGL(probe_prepare_kernel, grid, dim3(256), 0, stream, stats, scratch, d, eps,

@@ -19,54 +19,82 @@ __global__ __launch_bounds__(256) void score_blocks_kernel(
     const int32_t* __restrict__ nb_end, float* __restrict__ scores, int64_t score_stride, int n_rep,
     int key_len, float inv_sqrt_g) {
   constexpr int V = Vec<T>::N;
-  extern __shared__ float probe_lds[];  // [key_len]
+  extern __shared__ __attribute__((aligned(16))) float probe_lds[];  // [key_len]
   const int s = blockIdx.y;
-  for (int i = threadIdx.x; i < key_len; i += 256) probe_lds[i] = probe_kv[size_t(s) * key_len + i];
-  __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int end = min(nb_end[s], nb_capacity);
-  const int b = nb_begin + blockIdx.x * 4 + wave;
-  if (b >= end) return;
-  const float pn = probe_norm[s];
   const int gq = lane >> 4, l16 = lane & 15;
   const int chunks = key_len / V;
-  const T* block_keys = rep_keys + size_t(s) * seq_stride + size_t(b) * n_rep * key_len;
-  float total = 0.f;
-  for (int j0 = 0; j0 < n_rep; j0 += 4) {
-    const int j = j0 + gq;
-    float dot = 0.f, nrm = 0.f;
-    if (j < n_rep) {
-      const T* key = block_keys + size_t(j) * key_len;
-      for (int c0 = l16; c0 < chunks; c0 += 16 * kScoreBatch) {
-        float k[kScoreBatch][V];
+  const int end = min(nb_end[s], nb_capacity);
+  const int b = nb_begin + blockIdx.x * 4 + wave;
+  const bool live = b < end;
+  const T* block_keys = rep_keys + size_t(s) * seq_stride + size_t(live ? b : nb_begin) * n_rep * key_len;
+
+  // kScoreBatch chunks of key j, starting at chunk c0: all loads are issued before any is used
+  auto load_batch = [&](int j, int c0, float (&k)[kScoreBatch][V]) {
+    const T* key = block_keys + size_t(j < n_rep ? j : 0) * key_len;
 #pragma unroll
-        for (int i = 0; i < kScoreBatch; ++i) {   // all loads of the batch first: they overlap
-          const int c = c0 + 16 * i;
-          Vec<T>::load(key + (c < chunks ? c : l16) * V, k[i]);
-        }
+    for (int i = 0; i < kScoreBatch; ++i) {
+      const int c = c0 + 16 * i;
+      Vec<T>::load(key + (c < chunks ? c : l16) * V, k[i]);
+    }
+  };
+  auto accumulate = [&](int j, int c0, const float (&k)[kScoreBatch][V], float& dot, float& nrm) {
 #pragma unroll
-        for (int i = 0; i < kScoreBatch; ++i) {
-          const int c = c0 + 16 * i;
-          if (c < chunks) {
+    for (int i = 0; i < kScoreBatch; ++i) {
+      const int c = c0 + 16 * i;
+      if (c < chunks && j < n_rep) {
 #pragma unroll
-            for (int v = 0; v < V; ++v) {
-              dot += probe_lds[c * V + v] * k[i][v];
-              nrm += k[i][v] * k[i][v];
-            }
-          }
+        for (int v = 0; v < V; ++v) {
+          dot += probe_lds[c * V + v] * k[i][v];
+          nrm += k[i][v] * k[i][v];
         }
       }
     }
+  };
+  // cosine of the probe with key j repeated to the G query heads, summed over the 4 lane groups
+  auto finish_keys = [&](int j, float dot, float nrm, float pn) {
 #pragma unroll
     for (int o = 8; o > 0; o >>= 1) {
       dot += __shfl_xor(dot, o, 64);
       nrm += __shfl_xor(nrm, o, 64);
     }
-    // cosine of the probe with the key repeated to the G query heads of each KV head
     float c = (j < n_rep && nrm > 0.f && pn > 0.f) ? dot * inv_sqrt_g / (pn * sqrtf(nrm)) : 0.f;
     c += __shfl_xor(c, 16, 64);
     c += __shfl_xor(c, 32, 64);
-    total += c;
+    return c;
+  };
+
+  // the first batch of key loads is in flight while the probe goes to LDS
+  float k0[kScoreBatch][V];
+  load_batch(gq, l16, k0);
+  {
+    const float* src = probe_kv + size_t(s) * key_len;
+    for (int i = threadIdx.x * 4; i < key_len; i += 256 * 4)
+      *reinterpret_cast<f32x4*>(probe_lds + i) = *reinterpret_cast<const f32x4*>(src + i);
+  }
+  __syncthreads();
+  if (!live) return;
+  const float pn = probe_norm[s];
+  float total = 0.f;
+  {
+    float dot = 0.f, nrm = 0.f;
+    accumulate(gq, l16, k0, dot, nrm);
+    for (int c0 = l16 + 16 * kScoreBatch; c0 < chunks; c0 += 16 * kScoreBatch) {
+      float kk[kScoreBatch][V];
+      load_batch(gq, c0, kk);
+      accumulate(gq, c0, kk, dot, nrm);
+    }
+    total += finish_keys(gq, dot, nrm, pn);
+  }
+  for (int j0 = 4; j0 < n_rep; j0 += 4) {
+    const int j = j0 + gq;
+    float dot = 0.f, nrm = 0.f;
+    for (int c0 = l16; c0 < chunks; c0 += 16 * kScoreBatch) {
+      float kk[kScoreBatch][V];
+      load_batch(j, c0, kk);
+      accumulate(j, c0, kk, dot, nrm);
+    }
+    total += finish_keys(j, dot, nrm, pn);
   }
   if (lane == 0) scores[size_t(s) * score_stride + b] = total / float(n_rep);
 }
