@@ -1,17 +1,27 @@
 #!/usr/bin/env python3
 """Benchmark of the retrieval-attention hot path on one MI355X.
 
-A step is one whole single-layer windowed prefill of the workload's context: for every
-window, actqkv_build_probe -> actqkv_score_blocks -> actqkv_select ->
-actqkv_retrieval_attention, in order, on one stream, with all inputs resident in HBM.
-The default workload is the benchmark's configs[2] (LLaMA3-8B layer, 128K tokens, window
-512, top-k 32 with the dynamic cut-off): the one its metric "tokens/s per layer @128K"
-is quoted on.  Prints ONE JSON line.
+Prefill (the headline).  A step is one whole single-layer windowed prefill of the
+workload's context: for every window, actqkv_build_probe -> actqkv_score_blocks ->
+actqkv_select -> actqkv_retrieval_attention, in order, on one stream, with all inputs
+resident in HBM.  The default workload is the benchmark's configs[2] (LLaMA3-8B layer,
+128K tokens, window 512, top-k 32 with the dynamic cut-off): the one its metric
+"tokens/s per layer @128K" is quoted on.  The step's launches are captured once in a HIP
+graph (checked against the eager result on several replays) and the timed region replays
+it; then one eager pass of the same step brackets every attention launch with HIP events
+on its stream for the roofline figure (a graph cannot hold timing events).
+
+Decode (second part of the metric).  configs[3]: 16 sequences x 32 layers x 64K cached
+tokens, one new token per sequence per step, per-layer dynamic cut-off; a step is all 32
+layers; reported as us/step with the HBM roofline of the decode attention kernel.
+
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -22,6 +32,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
 PEAK_HBM_GBS = 8000.0
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
 def attention_flops(shape, w0: int, rows: int, n_sel: int, l0: int) -> float:
@@ -67,6 +81,252 @@ def cpu_baseline(w, q, k, v, rep, cutoffs, sample):
                       f"{t_total:.1f} s of numpy fp64"}
 
 
+def capture_graph(torch, step_fn, check_tensor, log_name):
+    """Captures step_fn in a HIP graph and checks three replays, with eager work in between,
+    against the eager result.  Returns the graph, or None if capture or the check failed."""
+    try:
+        step_fn()
+        torch.cuda.synchronize()
+        want = check_tensor.clone()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step_fn()
+        for i in range(3):
+            check_tensor.zero_()
+            g.replay()
+            torch.cuda.synchronize()
+            if not torch.equal(check_tensor, want):
+                log(f"{log_name}: graph replay {i} differs from the eager result; timing eagerly")
+                return None
+            step_fn()                      # eager work between replays
+            torch.cuda.synchronize()
+        return g
+    except Exception as e:  # capture not possible: time the eager loop instead
+        log(f"{log_name}: graph capture failed ({e}); timing eagerly")
+        return None
+
+
+def bench_prefill(args, torch, B, H, synth):
+    dev = "cuda:0"
+    w = synth.WORKLOADS[args.workload]
+    if args.n_ctx:
+        w = synth.scaled(w, n_ctx=args.n_ctx)
+    sh = w.shape
+    log(f"prefill {w.name}: generating inputs on the device")
+    q, k, v = synth.gen_layer(w, dev)
+    rep = synth.pick_rep_keys(k, sh.block_size, sh.n_rep)
+    kc, vc = H.blocked_k(k, sh, w.n_blocks), H.blocked_vt(v, sh, w.n_blocks)
+    repd = torch.zeros(w.n_blocks, sh.n_rep, sh.n_kv_heads, sh.head_dim, dtype=rep.dtype, device=dev)
+    repd[: rep.shape[0]] = rep
+    cutoffs = None
+    if w.cutoff:
+        cutoffs = []
+        for t in range(w.n_windows):
+            b, e = H.eligible_range(sh, t * w.window)
+            cutoffs.append(synth.cutoff_state(w, e - b, t, 0))
+    runner = H.LayerRunner(sh, 1, w.window, w.n_blocks, w.k_cap, dev)
+    plan = H.make_prefill_plan(sh, w.n_ctx, w.window, cutoffs, dev)
+    bud0 = None if plan.budget is None else plan.budget.clone()
+    out = torch.zeros_like(q)
+    n_win = plan.n_windows
+    nsel_log = torch.zeros(n_win, dtype=torch.int32, device=dev)
+    nb_begin = sh.n_init // sh.block_size
+
+    def one_step(events=None):
+        runner.stats.zero_()
+        if bud0 is not None:
+            plan.budget.copy_(bud0)
+        for t in range(n_win):
+            w0, rows = plan.w0[t], plan.rows[t]
+            qw = q[w0:w0 + rows]
+            bud = None if plan.budget is None else plan.budget[t:t + 1]
+            rest = None if plan.rest is None else plan.rest[t:t + 1]
+            nb_cap = min(max(plan.nb_end_host[t], nb_begin), runner.nb_capacity)
+            B.build_probe(runner.cs, 1, rows, qw, runner.stats, True, runner.probe, runner.probe_kv,
+                          runner.probe_norm, None, runner.workspace)
+            B.score_blocks(runner.cs, 1, runner.probe_kv, runner.probe_norm, repd, 0, nb_cap, nb_begin,
+                           plan.nb_end[t:t + 1], runner.scores, runner.score_stride)
+            B.select(1, runner.scores, runner.score_stride, nb_cap, nb_begin, plan.nb_end[t:t + 1],
+                     w.k_cap, bud, rest, runner.idx, nsel_log[t:t + 1], None, None)
+            if events is not None:
+                events[t][0].record()
+            B.retrieval_attention(runner.cs, 1, rows, qw, kc, vc, 0, runner.nb_capacity,
+                                  plan.n_ctx[t:t + 1], runner.idx, nsel_log[t:t + 1], w.k_cap,
+                                  out[w0:w0 + rows], None, runner.workspace)
+            if events is not None:
+                events[t][1].record()
+
+    graph = None if args.eager else capture_graph(torch, one_step, out, "prefill")
+    run = graph.replay if graph is not None else one_step
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    # ---- roofline of the dominant kernel: the prefill attention launch, one eager pass
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_win)]
+    one_step(ev)
+    torch.cuda.synchronize()
+    n_sel = nsel_log.cpu().tolist()
+    flops = sum(attention_flops(sh, plan.w0[t], plan.rows[t], n_sel[t], H.local_start(sh, plan.w0[t]))
+                for t in range(n_win))
+    attn_ms = sum(a.elapsed_time(b) for (a, b) in ev)
+    achieved = flops / (attn_ms * 1e-3) / 1e12
+    res = {
+        "metric": "prefill retrieval-attn tokens/s per layer @128K" if not args.n_ctx and
+                  args.workload == "c3_128k" else f"prefill retrieval-attn tokens/s per layer ({w.name})",
+        "value": w.n_ctx * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": elapsed * 1e3 / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: 1 sequence, 1 layer, H{sh.n_q_heads}/Hk{sh.n_kv_heads}/D{sh.head_dim}, "
+                               f"{w.n_ctx} tokens, window {w.window}, block {sh.block_size} x {sh.n_rep} rep keys, "
+                               f"n_init {sh.n_init}, n_local {sh.n_local}, k_cap {w.k_cap}, "
+                               f"cut-off {'on' if w.cutoff else 'off'}",
+                   "windows": n_win, "mean_blocks_selected": sum(n_sel) / max(n_win, 1),
+                   "launch": "hip graph replay" if graph is not None else "eager"},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "actqkv_retrieval_attention launch (attn_prefill_mfma_kernel + attn_combine_kernel)",
+                     "avg_launch_us": attn_ms * 1e3 / n_win,
+                     "algorithmic_gflop_per_launch": flops / n_win / 1e9,
+                     "timing": "HIP events around every attention launch of one eager pass of the step"},
+    }
+    if not args.no_cpu_baseline:
+        T = n_win
+        sample = sorted({max(T // 4, 0), T // 2, (3 * T) // 4, T - 1})
+        log("cpu_baseline: timing the oracle on sampled windows")
+        res["cpu_baseline"] = cpu_baseline(w, q, k, v, rep, cutoffs, sample)
+    return res
+
+
+def bench_decode(args, torch, B, H, synth):
+    """configs[3]: batch 16 x 32 layers x 64K cached tokens, `decode_steps` steps."""
+    dev = "cuda:0"
+    w = synth.WORKLOADS["c4_decode"]
+    if args.decode_layers:
+        w = synth.scaled(w, n_layers=args.decode_layers)
+    sh, L, bt = w.shape, w.n_layers, w.batch
+    steps = args.decode_steps
+    n0 = w.n_ctx                                     # cached tokens before the first step
+    nb_cap = (n0 + steps + sh.block_size - 1) // sh.block_size
+    hk, D, bs = sh.n_kv_heads, sh.head_dim, sh.block_size
+    gb = 2 * L * bt * nb_cap * hk * bs * D * 2 / 1e9
+    log(f"decode {w.name}: generating {gb:.0f} GB of KV cache on the device")
+    kc = torch.empty(L, bt, nb_cap, hk, bs, D, dtype=torch.bfloat16, device=dev)
+    vc = torch.empty(L, bt, nb_cap, hk, D, bs, dtype=torch.bfloat16, device=dev)
+    rep = torch.empty(L, bt, nb_cap, sh.n_rep, hk, D, dtype=torch.bfloat16, device=dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    u = synth.direction(w, 0, 0, dev)                # [Hk][D]
+    for l in range(L):
+        kc[l].normal_(generator=gen)
+        vc[l].normal_(generator=gen)
+        planted = torch.stack([torch.tensor(synth.planted_blocks(w, l, s)) for s in range(bt)]).to(dev)
+        sidx = torch.arange(bt, device=dev)[:, None].expand_as(planted)
+        kc[l][sidx, planted] += (w.shift * u)[None, None, :, None, :].to(torch.bfloat16)
+        # representative keys: the r tokens of a block with the largest key norm over all KV heads
+        norms = kc[l].float().pow(2).sum(dim=(2, 4))                      # [bt][nb][Bs]
+        top = torch.sort(norms, dim=2, descending=True, stable=True).indices[:, :, : sh.n_rep]
+        top = torch.sort(top, dim=2).values
+        src = kc[l].permute(0, 1, 3, 2, 4)                                # [bt][nb][Bs][Hk][D]
+        rep[l] = torch.gather(src, 2, top[:, :, :, None, None].expand(bt, nb_cap, sh.n_rep, hk, D))
+        del norms, top
+    u_hat = u.repeat_interleave(sh.group, dim=0)
+    q_all = torch.randn(steps, L, bt, 1, sh.n_q_heads, D, generator=gen, device=dev) + w.alpha * u_hat
+    q_all = q_all.to(torch.bfloat16)
+    out = torch.zeros(L, bt, 1, sh.n_q_heads, D, dtype=torch.bfloat16, device=dev)
+    runner = H.LayerRunner(sh, bt, 1, nb_cap, w.k_cap, dev)
+    nb_begin = sh.n_init // bs
+    # per-step device scalars
+    n_ctx_all = torch.tensor([[n0 + 1 + t] * bt for t in range(steps)], dtype=torch.int32, device=dev)
+    nb_end_host = [H.eligible_range(sh, n0 + t)[1] for t in range(steps)]
+    nb_end_all = torch.tensor([[e] * bt for e in nb_end_host], dtype=torch.int32, device=dev)
+    b_init, rest = synth.decode_cutoff_profile(w, nb_end_host[0] - nb_begin)
+    rest_all = torch.tensor([[r] * bt for r in rest], dtype=torch.float32, device=dev)     # [L][bt]
+    budget = torch.zeros(bt, dtype=torch.float32, device=dev)
+    nsel_log = torch.zeros(L, bt, dtype=torch.int32, device=dev)
+    q_step = torch.zeros(L, bt, 1, sh.n_q_heads, D, dtype=torch.bfloat16, device=dev)
+    step_no = torch.zeros(1, dtype=torch.int64, device=dev)
+    n_ctx_cur = torch.zeros(bt, dtype=torch.int32, device=dev)
+    nb_end_cur = torch.zeros(bt, dtype=torch.int32, device=dev)
+    cache_stride, rep_stride = kc[0].stride(0), rep[0].stride(0)
+
+    def load_step(t):
+        """Per-step inputs (new queries, lengths): device copies outside the library."""
+        q_step.copy_(q_all[t])
+        n_ctx_cur.copy_(n_ctx_all[t])
+        nb_end_cur.copy_(nb_end_all[t])
+
+    def one_step(events=None):
+        budget.fill_(b_init)                          # B_kv is reset at the start of every step
+        for l in range(L):
+            B.build_probe(runner.cs, bt, 1, q_step[l], None, False, runner.probe, runner.probe_kv,
+                          runner.probe_norm, None, runner.workspace)
+            B.score_blocks(runner.cs, bt, runner.probe_kv, runner.probe_norm, rep[l], rep_stride,
+                           nb_end_host[-1], nb_begin, nb_end_cur, runner.scores, runner.score_stride)
+            B.select(bt, runner.scores, runner.score_stride, nb_end_host[-1], nb_begin, nb_end_cur,
+                     w.k_cap, budget, rest_all[l], runner.idx, nsel_log[l], None, None)
+            if events is not None:
+                events[l][0].record()
+            B.retrieval_attention(runner.cs, bt, 1, q_step[l], kc[l], vc[l], cache_stride, nb_cap,
+                                  n_ctx_cur, runner.idx, nsel_log[l], w.k_cap, out[l], None,
+                                  runner.workspace)
+            if events is not None:
+                events[l][1].record()
+
+    load_step(0)
+    graph = None if args.eager else capture_graph(torch, one_step, out, "decode")
+    run = graph.replay if graph is not None else one_step
+    for t in range(min(8, steps)):
+        load_step(t)
+        run()
+    torch.cuda.synchronize()
+    times = []
+    t_all0 = time.perf_counter()
+    for t in range(steps):
+        load_step(t)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run()
+        torch.cuda.synchronize()
+        times.append(time.perf_counter() - t0)
+    t_all = time.perf_counter() - t_all0
+    times.sort()
+    # roofline of the decode attention kernel: one eager step with events
+    load_step(steps - 1)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
+    one_step(ev)
+    torch.cuda.synchronize()
+    n_sel = nsel_log.cpu()
+    n_ctx_last = n0 + steps
+    l0 = H.local_start(sh, n_ctx_last - 1)
+    keys = min(sh.n_init, n_ctx_last - 1) + (n_ctx_last - l0)
+    byt = float(((n_sel.sum().item() * bs) + keys * L * bt) * hk * D * 2 * 2)       # K and V, bf16
+    attn_ms = sum(a.elapsed_time(b) for (a, b) in ev)
+    score_bytes = float((nb_end_host[-1] - nb_begin) * sh.n_rep * hk * D * 2 * L * bt)
+    achieved = byt / (attn_ms * 1e-3) / 1e9
+    mean_us = sum(times) / len(times) * 1e6
+    return {
+        "metric": "decode step us", "value": mean_us, "unit": "us/step", "p50_us": times[len(times) // 2] * 1e6,
+        "higher_is_better": False, "steps": steps, "wall_s_incl_input_copies": t_all,
+        "config": {"workload": f"{w.name}: batch {bt}, {L} layers, {n0} cached tokens, k_cap {w.k_cap}, "
+                               f"per-layer dynamic cut-off, KV cache {gb:.0f} GB bf16 in HBM",
+                   "mean_blocks_selected": float(n_sel.float().mean()),
+                   "launch": "hip graph replay" if graph is not None else "eager"},
+        "algorithmic_bytes_per_step": byt + score_bytes,
+        "hbm_frac_of_step": (byt + score_bytes) / (mean_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                     "kernel": "actqkv_retrieval_attention launch, m = 1 (attn_decode_kernel + attn_decode_combine_kernel)",
+                     "avg_launch_us": attn_ms * 1e3 / L, "algorithmic_mb_per_launch": byt / L / 1e6,
+                     "timing": "HIP events around every attention launch of one eager step"},
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -75,6 +335,11 @@ def main() -> int:
     ap.add_argument("--workload", default="c3_128k")
     ap.add_argument("--n-ctx", type=int, default=0, help="override the context length (testing)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="do not use HIP graphs")
+    ap.add_argument("--skip-decode", action="store_true")
+    ap.add_argument("--skip-prefill", action="store_true")
+    ap.add_argument("--decode-steps", type=int, default=256)
+    ap.add_argument("--decode-layers", type=int, default=0, help="override the layer count (testing)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -90,99 +355,17 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     B.load_library()
-    dev = "cuda:0"
     torch.cuda.set_device(0)
-    w = synth.WORKLOADS[args.workload]
-    if args.n_ctx:
-        w = synth.scaled(w, n_ctx=args.n_ctx)
-    sh = w.shape
-
-    # ---- inputs, generated on the device and resident in HBM before timing starts
-    q, k, v = synth.gen_layer(w, dev)
-    rep = synth.pick_rep_keys(k, sh.block_size, sh.n_rep)
-    kc, vc = H.blocked_k(k, sh, w.n_blocks), H.blocked_vt(v, sh, w.n_blocks)
-    repd = torch.zeros(w.n_blocks, sh.n_rep, sh.n_kv_heads, sh.head_dim, dtype=rep.dtype, device=dev)
-    repd[: rep.shape[0]] = rep
-    cutoffs = None
-    if w.cutoff:
-        cutoffs = []
-        for t in range(w.n_windows):
-            b, e = H.eligible_range(sh, t * w.window)
-            cutoffs.append(synth.cutoff_state(w, e - b, t, 0))
-    runner = H.LayerRunner(sh, 1, w.window, w.n_blocks, w.k_cap, dev)
-    plan = H.make_prefill_plan(sh, w.n_ctx, w.window, cutoffs, dev)
-    cut0 = None if plan.cutoff is None else plan.cutoff.clone()
-    out = torch.zeros_like(q)
-    n_win = plan.n_windows
-    nsel_log = torch.zeros(n_win, dtype=torch.int32, device=dev)
-
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           for _ in range(n_win)] for _ in range(args.steps)]
-
-    def one_step(events=None):
-        runner.reset()
-        if cut0 is not None:
-            plan.cutoff.copy_(cut0)
-        nb_begin = sh.n_init // sh.block_size
-        for t in range(n_win):
-            w0, rows = plan.w0[t], plan.rows[t]
-            qw = q[w0:w0 + rows]
-            cut = None if plan.cutoff is None else plan.cutoff[t:t + 1]
-            nb_cap = min(max(plan.nb_end_host[t], nb_begin), runner.nb_capacity)
-            B.build_probe(runner.cs, 1, rows, qw, runner.stats, True, runner.probe, runner.probe_kv,
-                          runner.probe_norm, None, runner.workspace)
-            B.score_blocks(runner.cs, 1, runner.probe_kv, runner.probe_norm, repd, 0, nb_cap, nb_begin,
-                           plan.nb_end[t:t + 1], runner.scores, runner.score_stride)
-            B.select(1, runner.scores, runner.score_stride, nb_cap, nb_begin, plan.nb_end[t:t + 1],
-                     w.k_cap, cut, runner.idx, nsel_log[t:t + 1], None, None)
-            if events is not None:
-                events[t][0].record()
-            B.retrieval_attention(runner.cs, 1, rows, qw, kc, vc, 0, runner.nb_capacity,
-                                  plan.n_ctx[t:t + 1], runner.idx, nsel_log[t:t + 1], w.k_cap,
-                                  out[w0:w0 + rows], None, runner.workspace)
-            if events is not None:
-                events[t][1].record()
-
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        one_step(ev[i])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-
-    # ---- roofline of the dominant kernel: the prefill attention launch
-    n_sel = nsel_log.cpu().tolist()
-    flops = 0.0
-    for t in range(n_win):
-        flops += attention_flops(sh, plan.w0[t], plan.rows[t], n_sel[t], H.local_start(sh, plan.w0[t]))
-    attn_ms = sum(a.elapsed_time(b) for step in ev for (a, b) in step)
-    n_launch = args.steps * n_win
-    avg_us = attn_ms * 1e3 / n_launch
-    achieved = (flops * args.steps) / (attn_ms * 1e-3) / 1e12
-    tokens_per_s = w.n_ctx * args.steps / elapsed
-    res = {
-        "metric": "prefill retrieval-attn tokens/s per layer @128K" if not args.n_ctx and
-                  args.workload == "c3_128k" else f"prefill retrieval-attn tokens/s per layer ({w.name})",
-        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": elapsed * 1e3 / args.steps, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype, "data": "synthetic",
-        "config": {"workload": f"{w.name}: 1 sequence, 1 layer, H{sh.n_q_heads}/Hk{sh.n_kv_heads}/D{sh.head_dim}, "
-                               f"{w.n_ctx} tokens, window {w.window}, block {sh.block_size} x {sh.n_rep} rep keys, "
-                               f"n_init {sh.n_init}, n_local {sh.n_local}, k_cap {w.k_cap}, "
-                               f"cut-off {'on' if w.cutoff else 'off'}",
-                   "windows": n_win, "mean_blocks_selected": sum(n_sel) / max(n_win, 1)},
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
-                     "kernel": "actqkv_retrieval_attention launch (attn_prefill_mfma_kernel + split combine)",
-                     "avg_launch_us": avg_us, "algorithmic_gflop_per_launch": flops / n_win / 1e9,
-                     "attention_share_of_step": attn_ms / 1e3 / elapsed},
-    }
-    if not args.no_cpu_baseline:
-        T = n_win
-        sample = sorted({max(T // 4, 0), T // 2, (3 * T) // 4, T - 1})
-        res["cpu_baseline"] = cpu_baseline(w, q, k, v, rep, cutoffs, sample)
+    res = {}
+    if not args.skip_prefill:
+        res = bench_prefill(args, torch, B, H, synth)
+        torch.cuda.empty_cache()
+    if not args.skip_decode:
+        dec = bench_decode(args, torch, B, H, synth)
+        if res:
+            res["decode"] = dec
+        else:
+            res = dec
     print(json.dumps(res))
     return 0
 

@@ -20,7 +20,7 @@
  *   - Pointers to q, the caches, rep_keys, stats, probe, probe_kv, out and the
  *     workspace must be 16-byte aligned (they are read with 16-byte loads);
  *     per-sequence arrays (n_ctx, nb_end, n_sel, idx, scores, theta, budget,
- *     probe_norm, weights, lse) need 4-byte and cutoff 8-byte alignment.
+ *     probe_norm, weights, lse, budget_remaining, theta_rest_sum) need 4-byte alignment.
  *   - Return value: ACTQKV_OK, or a negative error code.  Arguments are checked
  *     on the host before anything is launched; on error nothing has been
  *     enqueued.  actqkv_last_error() gives a thread-local message.  Nothing
@@ -81,14 +81,6 @@ typedef struct actqkv_shape {
   float var_eps;         /* floor of the variance in Eq. (7); 0 means 1e-12 */
 } actqkv_shape;
 
-/* Dynamic cut-off state of one sequence (device memory, Sec. 4.2):
- *   budget_remaining  B_kv, in blocks; actqkv_select subtracts B^l from it
- *   theta_rest_sum    R = sum over the layers still to come of their mean density */
-typedef struct actqkv_cutoff {
-  float budget_remaining;
-  float theta_rest_sum;
-} actqkv_cutoff;
-
 /* Number of floats of running statistics per sequence: {n, pad[3], mean[d], m2[d]},
  * d = H*D.  n is the number of queries seen, mean their per-channel mean, m2 the
  * per-channel sum of squared deviations from it (Eq. (8) is mean and m2/(n-1)).
@@ -138,19 +130,24 @@ int actqkv_score_blocks(const actqkv_shape* shape, int batch, const float* probe
 /* Information density, budget and selection (Eq. (11), (12), Alg. 1) over the
  * eligible blocks nb_begin <= b < nb_end[s] of each sequence.
  *   theta = entropy (natural log) of softmax(scores over the eligible blocks).
- *   cutoff == NULL: E = min(k_cap, n_eligible); budget is reported as E.
- *   cutoff != NULL (device, [batch]): B = theta / (theta + theta_rest_sum) * budget_remaining
- *           (B = budget_remaining if the denominator is 0);
- *           E = min(k_cap, n_eligible, max(1, floor(B + 0.5)));
- *           budget_remaining -= B.
+ *   Dynamic cut-off state (device memory, Sec. 4.2), both pointers or neither:
+ *     budget_remaining [batch] fp32  B_kv, in blocks; B^l is subtracted from it, so the same
+ *                                    array is handed from layer to layer within a step
+ *     theta_rest_sum   [batch] fp32  R = sum over the layers still to come of their mean density
+ *   Without it: E = min(k_cap, n_eligible); budget is reported as E.
+ *   With it:    B = theta / (theta + R) * B_kv   (B = B_kv if the denominator is 0);
+ *               E = min(k_cap, n_eligible, max(1, floor(B + 0.5)));  B_kv -= B.
  *   idx     [batch][k_cap] int32: the E best blocks, best first, equal scores by
  *           ascending block index; unused entries are -1.
  *   n_sel   [batch] int32 = E (0 when nothing is eligible; theta and budget are 0 then
  *           and budget_remaining is left alone).
- *   theta, budget  [batch] fp32, may be NULL. */
+ *   theta, budget  [batch] fp32, may be NULL.
+ * Errors: EINVAL (null, one cut-off pointer without the other), ESHAPE (k_cap, more than
+ * 8192 blocks), EALIGN. */
 int actqkv_select(int batch, const float* scores, int64_t score_stride, int nb_capacity,
-                  int nb_begin, const int32_t* nb_end, int k_cap, actqkv_cutoff* cutoff,
-                  int32_t* idx, int32_t* n_sel, float* theta, float* budget, void* stream);
+                  int nb_begin, const int32_t* nb_end, int k_cap, float* budget_remaining,
+                  const float* theta_rest_sum, int32_t* idx, int32_t* n_sel, float* theta,
+                  float* budget, void* stream);
 
 /* Attention of a window over [current window, selected cache] (Eq. (2); Eq. (3) for m == 1).
  *   q        [batch][m][H][D], storage dtype.

@@ -50,7 +50,7 @@ SIGNATURES = {
     "actqkv_workspace_bytes": (_sz, [_shp, _i, _i, _i, _i]),
     "actqkv_build_probe": (_i, [_shp, _i, _i, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "actqkv_score_blocks": (_i, [_shp, _i, _vp, _vp, _vp, _i64, _i, _i, _vp, _vp, _i64, _vp]),
-    "actqkv_select": (_i, [_i, _vp, _i64, _i, _i, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "actqkv_select": (_i, [_i, _vp, _i64, _i, _i, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_retrieval_attention": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
                                         _vp, _vp, _vp, _sz, _vp]),
     "actqkv_last_error": (ctypes.c_char_p, []),
@@ -139,10 +139,12 @@ def score_blocks(shape: CShape, batch: int, probe_kv, probe_norm, rep_keys, seq_
 
 
 def select(batch: int, scores, score_stride: int, nb_capacity: int, nb_begin: int, nb_end,
-           k_cap: int, cutoff, idx, n_sel, theta=None, budget=None, stream=None) -> None:
+           k_cap: int, budget_remaining, theta_rest_sum, idx, n_sel, theta=None, budget=None,
+           stream=None) -> None:
     _check(load_library().actqkv_select(
         batch, _ptr(scores, torch.float32), score_stride, nb_capacity, nb_begin,
-        _ptr(nb_end, torch.int32), k_cap, _ptr(cutoff, torch.float32), _ptr(idx, torch.int32),
+        _ptr(nb_end, torch.int32), k_cap, _ptr(budget_remaining, torch.float32),
+        _ptr(theta_rest_sum, torch.float32), _ptr(idx, torch.int32),
         _ptr(n_sel, torch.int32), _ptr(theta, torch.float32), _ptr(budget, torch.float32),
         _stream(stream)))
 

@@ -114,16 +114,20 @@ int prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap) {
   int s = 256 / (base > 0 ? base : 1);
   return s < 1 ? 1 : (s > 8 ? 8 : s);
 }
-int decode_splits(const actqkv_shape& sh, int batch, int k_cap) {
-  (void)sh; (void)batch; (void)k_cap;
-  return 1;
-}
+bool decode_mfma_supported(const actqkv_shape& sh, int m);
+size_t decode_mfma_scratch_floats(const actqkv_shape& sh, int batch, int k_cap);
+int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* q, const void* k_cache,
+                                 const void* v_cache, int64_t seq_stride, int nb_capacity,
+                                 const int32_t* n_ctx, const int32_t* idx, const int32_t* n_sel,
+                                 int k_cap, void* out, float* lse, float* scratch, float scale,
+                                 hipStream_t stream);
 
 size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap) {
   (void)nb_capacity;
   size_t probe = size_t(batch) * probe_scratch_floats(sh, m) * sizeof(float);
-  int splits = m == 1 ? decode_splits(sh, batch, k_cap) : prefill_splits(sh, batch, m, k_cap);
-  size_t attn = attn_scratch_floats(sh, batch, m, splits) * sizeof(float);
+  int splits = prefill_splits(sh, batch, m, k_cap);
+  size_t attn = 0;
+  if (decode_mfma_supported(sh, m)) attn = decode_mfma_scratch_floats(sh, batch, k_cap) * sizeof(float);
   if (prefill_mfma_supported(sh, m)) {
     size_t groups = size_t(batch) * sh.n_kv_heads * prefill_mfma_qtiles(sh, m);
     attn = groups * splits * kPfPartialFloats * sizeof(float);
@@ -141,6 +145,9 @@ int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, co
                      const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
                      const Workspace& ws, hipStream_t stream) {
   const float scale = sh.softmax_scale > 0.f ? sh.softmax_scale : 1.f / std::sqrt(float(sh.head_dim));
+  if (decode_mfma_supported(sh, m))
+    return launch_attention_decode_mfma(sh, batch, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx,
+                                        idx, n_sel, k_cap, out, lse, ws.scratch_f32(), scale, stream);
   if (prefill_mfma_supported(sh, m))
     return launch_attention_prefill_mfma(sh, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity,
                                          n_ctx, idx, n_sel, k_cap, out, lse,
@@ -218,22 +225,26 @@ int actqkv_score_blocks(const actqkv_shape* shape, int batch, const float* probe
 }
 
 int actqkv_select(int batch, const float* scores, int64_t score_stride, int nb_capacity, int nb_begin,
-                  const int32_t* nb_end, int k_cap, actqkv_cutoff* cutoff, int32_t* idx,
-                  int32_t* n_sel, float* theta, float* budget, void* stream) {
+                  const int32_t* nb_end, int k_cap, float* budget_remaining,
+                  const float* theta_rest_sum, int32_t* idx, int32_t* n_sel, float* theta,
+                  float* budget, void* stream) {
   ACTQKV_TRY(check_batch(batch));
   ACTQKV_TRY(check_blocks(nb_capacity, nb_begin, k_cap, true));
   ACTQKV_REQUIRE_SMALL(scores, 4);
   ACTQKV_REQUIRE_SMALL(nb_end, 4);
   ACTQKV_REQUIRE_SMALL(idx, 4);
   ACTQKV_REQUIRE_SMALL(n_sel, 4);
-  ACTQKV_OPTIONAL_SMALL(cutoff, 8);
+  if ((budget_remaining == nullptr) != (theta_rest_sum == nullptr))
+    return set_error(ACTQKV_EINVAL, "budget_remaining and theta_rest_sum must be given together");
+  ACTQKV_OPTIONAL_SMALL(budget_remaining, 4);
+  ACTQKV_OPTIONAL_SMALL(theta_rest_sum, 4);
   ACTQKV_OPTIONAL_SMALL(theta, 4);
   ACTQKV_OPTIONAL_SMALL(budget, 4);
   if (score_stride < nb_capacity)
     return set_error(ACTQKV_EINVAL, "score_stride %lld < nb_capacity %d", (long long)score_stride,
                      nb_capacity);
-  return launch_select(batch, scores, score_stride, nb_capacity, nb_begin, nb_end, k_cap, cutoff, idx,
-                       n_sel, theta, budget, static_cast<hipStream_t>(stream));
+  return launch_select(batch, scores, score_stride, nb_capacity, nb_begin, nb_end, k_cap, budget_remaining,
+                       theta_rest_sum, idx, n_sel, theta, budget, static_cast<hipStream_t>(stream));
 }
 
 int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, const void* q,

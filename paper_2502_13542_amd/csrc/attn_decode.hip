@@ -1,0 +1,275 @@
+// Retrieval attention of a decode step (Sec. 3.1, Eq. (3): one query token per sequence
+// over [k^t, K*]; bf16 storage, fp32 accumulation).  HBM-bound: every selected key and
+// value byte is read exactly once, by exactly one wavefront.
+//
+// One wavefront owns one 128-key tile of one (sequence, KV head): initial tokens, the
+// blocks chosen by actqkv_select (read from device memory) or the local span up to the new
+// token.  The G query heads of the KV head ride along as columns of a 16-wide matrix-core
+// tile, so a key or value byte is loaded once for all of them, straight from global memory
+// into MFMA operands (no LDS staging: nothing is shared between wavefronts):
+//   S^T[key][head] = K[key][:] Q^T        v_mfma_f32_16x16x32_bf16, A = 16 keys x 32 channels
+//   O^T[d][head]  += V^T[d][keys] P^T     A = 16 channels x 32 keys of the transposed V block
+// A lane of an A operand reads 16 contiguous bytes and four lanes cover 64 contiguous
+// bytes of a row.  Keys enter S^T in a permuted row order such that each lane's accumulator
+// registers hold 8 consecutive keys of every 32-key step, which is exactly the B-operand
+// layout of the second product; no cross-lane traffic is needed apart from two shuffles
+// for the row maximum.  The four wavefronts of a workgroup (four consecutive tiles) merge
+// their (max, sum, O) through LDS and write one partial; attn_decode_combine_kernel merges
+// the partials of a (sequence, head).
+#include "common.h"
+#include "launch.h"
+
+namespace actqkv {
+
+constexpr int kDcD = 128;
+constexpr int kDcWaves = 4;
+
+struct DcParams {
+  const uint16_t* q;
+  const uint16_t* k_cache;
+  const uint16_t* v_cache;
+  int64_t seq_stride;
+  int nb_capacity;
+  const int32_t* n_ctx;
+  const int32_t* idx;
+  const int32_t* n_sel;
+  int k_cap;
+  uint16_t* out;
+  float* lse;
+  float* part;  // [batch][Hk][n_wg][G][D + 2]
+  int n_q_heads, n_kv_heads, n_init, n_local;
+  int n_wg;     // workgroups (partials) per (sequence, KV head)
+  float scale_log2e;
+};
+
+__device__ __forceinline__ bf16x8 dc_as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__global__ __launch_bounds__(kDcWaves * 64) void attn_decode_kernel(DcParams p) {
+  __shared__ float red_ml[kDcWaves][8][2];
+  __shared__ float red_o[kDcWaves][8][kDcD];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 15, kq = lane >> 4;       // MFMA column (query head) and lane quarter
+  const int wg = blockIdx.x, hk = blockIdx.y, s = blockIdx.z;
+  const int group = p.n_q_heads / p.n_kv_heads;
+
+  const int n_ctx = min(max(p.n_ctx[s], 1), p.nb_capacity * kBlock);
+  const WindowGeom g = window_geom(n_ctx, 1, p.n_init, p.n_local);
+  const TileList tl = make_tile_list(g, n_ctx - 1, p.idx + size_t(s) * p.k_cap, p.n_sel[s], p.k_cap,
+                                     p.nb_capacity);
+  const int t = wg * kDcWaves + wave;
+  int block = 0, lo = 0, hi = 0;
+  if (t < tl.count()) tl.get(t, block, lo, hi);
+  const bool live = hi > lo;                     // wave-uniform
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 acc_o[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc_o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  if (live) {
+    const size_t tile_elems = size_t(kBlock) * kDcD;
+    const uint16_t* kt = p.k_cache + size_t(s) * p.seq_stride + (size_t(block) * p.n_kv_heads + hk) * tile_elems;
+    const uint16_t* vt = p.v_cache + size_t(s) * p.seq_stride + (size_t(block) * p.n_kv_heads + hk) * tile_elems;
+    const int kpos0 = block * kBlock;
+
+    // A operands of S^T: MFMA row r of sub-tile h of 32-key step st is key 32*st + 8*(r/4) + 4*h + r%4,
+    // so that lane quarter kq ends up with keys 32*st + 8*kq + 4*h + i in register i.
+    u32x4 ka[32];
+    {
+      const int r = n;   // A-operand row of this lane
+      const uint16_t* base = kt + size_t(8 * (r >> 2) + (r & 3)) * kDcD + 8 * kq;
+#pragma unroll
+      for (int st = 0; st < 4; ++st)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks)   // 32 loads in flight
+            ka[(st * 2 + h) * 4 + ks] =
+                *reinterpret_cast<const u32x4*>(base + size_t(32 * st + 4 * h) * kDcD + ks * 32);
+    }
+    // Q^T as B operand: lane (n, kq) holds channels ks*32 + 8*kq .. +7 of head n (zero for n >= G)
+    bf16x8 qb[4];
+    {
+      const uint16_t* qp = p.q + (size_t(s) * p.n_q_heads + hk * group + min(n, group - 1)) * kDcD + 8 * kq;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        u32x4 v = *reinterpret_cast<const u32x4*>(qp + ks * 32);
+        if (n >= group) v = u32x4{0u, 0u, 0u, 0u};
+        qb[ks] = dc_as_bf16x8(v);
+      }
+    }
+    f32x4 sc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      sc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        sc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dc_as_bf16x8(ka[j * 4 + ks]), qb[ks], sc[j], 0, 0, 0);
+    }
+    // V^T A operands: lane (row = channel within a group of 16, kq) reads keys 32*st + 8*kq .. +7
+    u32x4 va[32];
+    {
+      const uint16_t* base = vt + size_t(n) * kBlock + 8 * kq;
+#pragma unroll
+      for (int dg = 0; dg < 8; ++dg)
+#pragma unroll
+        for (int st = 0; st < 4; ++st)
+          va[dg * 4 + st] = *reinterpret_cast<const u32x4*>(base + size_t(16 * dg) * kBlock + 32 * st);
+    }
+    // mask and softmax of this tile: sc[2*st + h][i] is key kpos0 + 32*st + 8*kq + 4*h + i
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int kp = kpos0 + 32 * (j >> 1) + 8 * kq + 4 * (j & 1) + i;
+        const float v = (kp >= lo && kp < hi) ? sc[j][i] : -INFINITY;
+        sc[j][i] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    m_run = mx * p.scale_log2e;                  // finite: a live tile has a visible key
+    float psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float pv = __builtin_amdgcn_exp2f(sc[j][i] * p.scale_log2e - m_run);
+        sc[j][i] = pv;
+        psum += pv;
+      }
+    psum += __shfl_xor(psum, 16, 64);
+    psum += __shfl_xor(psum, 32, 64);
+    l_run = psum;
+    // O^T += V^T P^T
+    typedef __attribute__((ext_vector_type(8))) float f32x8;
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      f32x8 pf = {sc[2 * st][0], sc[2 * st][1], sc[2 * st][2], sc[2 * st][3],
+                  sc[2 * st + 1][0], sc[2 * st + 1][1], sc[2 * st + 1][2], sc[2 * st + 1][3]};
+      const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
+#pragma unroll
+      for (int dg = 0; dg < 8; ++dg)
+        acc_o[dg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dc_as_bf16x8(va[dg * 4 + st]), pb, acc_o[dg], 0, 0, 0);
+    }
+  }
+
+  // merge the four wavefronts: lane (n < G, kq) holds channels 16*dg + 4*kq + i of head n
+  if (n < group) {
+    if (kq == 0) {
+      red_ml[wave][n][0] = m_run;
+      red_ml[wave][n][1] = l_run;
+    }
+#pragma unroll
+    for (int dg = 0; dg < 8; ++dg)
+      *reinterpret_cast<f32x4*>(&red_o[wave][n][16 * dg + 4 * kq]) = acc_o[dg];
+  }
+  __syncthreads();
+  // thread = (head, channel pair): 256 threads cover up to 8 heads x 128 channels in two halves
+  float* part = p.part + ((size_t(s) * p.n_kv_heads + hk) * p.n_wg + wg) * group * (kDcD + 2);
+  for (int e = threadIdx.x; e < group * kDcD; e += kDcWaves * 64) {
+    const int h = e / kDcD, d = e - h * kDcD;
+    float mm = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kDcWaves; ++w) mm = fmaxf(mm, red_ml[w][h][0]);
+    const float m_safe = mm == -INFINITY ? 0.f : mm;
+    float l = 0.f, o = 0.f;
+#pragma unroll
+    for (int w = 0; w < kDcWaves; ++w) {
+      const float sc_w = __builtin_amdgcn_exp2f(red_ml[w][h][0] - m_safe);
+      l += sc_w * red_ml[w][h][1];
+      o += sc_w * red_o[w][h][d];
+    }
+    part[size_t(h) * (kDcD + 2) + d] = o;
+    if (d == 0) {
+      part[size_t(h) * (kDcD + 2) + kDcD] = mm;
+      part[size_t(h) * (kDcD + 2) + kDcD + 1] = l;
+    }
+  }
+}
+
+// out[s][head][:] = sum_w 2^(m_w - M) O_w / sum_w 2^(m_w - M) l_w over the n_wg partials.
+// One workgroup of 128 threads per (sequence, head); thread = channel.
+__global__ __launch_bounds__(kDcD) void attn_decode_combine_kernel(DcParams p) {
+  const int head = blockIdx.x, s = blockIdx.y, d = threadIdx.x;
+  const int group = p.n_q_heads / p.n_kv_heads;
+  const int hk = head / group, h = head - hk * group;
+  const float* part = p.part + (size_t(s) * p.n_kv_heads + hk) * p.n_wg * group * (kDcD + 2) +
+                      size_t(h) * (kDcD + 2);
+  const size_t stride = size_t(group) * (kDcD + 2);
+  constexpr int kB = 16;
+  float mm = -INFINITY, l = 0.f, o = 0.f;
+  for (int w0 = 0; w0 < p.n_wg; w0 += kB) {
+    float pm[kB], pl[kB], po[kB];
+#pragma unroll
+    for (int i = 0; i < kB; ++i) {               // all loads first: they overlap
+      const int w = w0 + i < p.n_wg ? w0 + i : w0;
+      pm[i] = part[w * stride + kDcD];
+      pl[i] = part[w * stride + kDcD + 1];
+      po[i] = part[w * stride + d];
+    }
+#pragma unroll
+    for (int i = 0; i < kB; ++i) {
+      if (w0 + i < p.n_wg) {
+        const float m_new = fmaxf(mm, pm[i]);
+        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+        const float wa = __builtin_amdgcn_exp2f(mm - m_safe), wb = __builtin_amdgcn_exp2f(pm[i] - m_safe);
+        l = l * wa + pl[i] * wb;
+        o = o * wa + po[i] * wb;
+        mm = m_new;
+      }
+    }
+  }
+  const float inv = l > 0.f ? 1.f / l : 0.f;
+  p.out[(size_t(s) * p.n_q_heads + head) * kDcD + d] = uint16_t(f32_to_bf16_bits(o * inv));
+  if (p.lse != nullptr && d == 0)
+    p.lse[size_t(s) * p.n_q_heads + head] = (mm + log2f(l)) * 0.6931471805599453f;
+}
+
+bool decode_mfma_supported(const actqkv_shape& sh, int m) {
+  const int g = sh.n_q_heads / sh.n_kv_heads;
+  return sh.dtype == ACTQKV_BF16 && sh.head_dim == kDcD && m == 1 && g <= 8;
+}
+
+// Workgroups per (sequence, KV head): enough wavefronts for the longest possible tile list.
+int decode_mfma_workgroups(const actqkv_shape& sh, int k_cap) {
+  const int tiles = (sh.n_init + kBlock - 1) / kBlock + k_cap + sh.n_local / kBlock + 2;
+  return (tiles + kDcWaves - 1) / kDcWaves;
+}
+
+size_t decode_mfma_scratch_floats(const actqkv_shape& sh, int batch, int k_cap) {
+  return size_t(batch) * sh.n_q_heads * decode_mfma_workgroups(sh, k_cap) * (kDcD + 2);
+}
+
+int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* q, const void* k_cache,
+                                 const void* v_cache, int64_t seq_stride, int nb_capacity,
+                                 const int32_t* n_ctx, const int32_t* idx, const int32_t* n_sel,
+                                 int k_cap, void* out, float* lse, float* scratch, float scale,
+                                 hipStream_t stream) {
+  DcParams p;
+  p.q = static_cast<const uint16_t*>(q);
+  p.k_cache = static_cast<const uint16_t*>(k_cache);
+  p.v_cache = static_cast<const uint16_t*>(v_cache);
+  p.seq_stride = seq_stride;
+  p.nb_capacity = nb_capacity;
+  p.n_ctx = n_ctx;
+  p.idx = idx;
+  p.n_sel = n_sel;
+  p.k_cap = k_cap;
+  p.out = static_cast<uint16_t*>(out);
+  p.lse = lse;
+  p.part = scratch;
+  p.n_q_heads = sh.n_q_heads;
+  p.n_kv_heads = sh.n_kv_heads;
+  p.n_init = sh.n_init;
+  p.n_local = sh.n_local;
+  p.n_wg = decode_mfma_workgroups(sh, k_cap);
+  p.scale_log2e = scale * 1.4426950408889634f;
+  hipLaunchKernelGGL(attn_decode_kernel, dim3(p.n_wg, sh.n_kv_heads, batch), dim3(kDcWaves * 64), 0,
+                     stream, p);
+  hipLaunchKernelGGL(attn_decode_combine_kernel, dim3(sh.n_q_heads, batch), dim3(kDcD), 0, stream, p);
+  return hip_status("attention (decode)");
+}
+
+}  // namespace actqkv

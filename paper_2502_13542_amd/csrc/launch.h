@@ -27,14 +27,8 @@ inline size_t probe_scratch_floats(const actqkv_shape& sh, int m) {
   return 2 * d + probe_a_floats(m) + 4 * d;
 }
 
-// Key-tile splits of the prefill attention and of the decode attention.
-constexpr int kMaxSplits = 16;
+// Key-tile splits of the prefill attention.
 int prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap);
-int decode_splits(const actqkv_shape& sh, int batch, int k_cap);
-// per (sequence, query row, head, split): D partial outputs + running max + running sum
-inline size_t attn_scratch_floats(const actqkv_shape& sh, int batch, int m, int splits) {
-  return size_t(batch) * m * sh.n_q_heads * splits * (size_t(sh.head_dim) + 2);
-}
 // prefill on the matrix cores: per workgroup and split, 8 wavefronts x (32 bf16 pairs of
 // normalised output + max + sum) x 64 lanes
 constexpr size_t kPfPartialFloats = 8 * (32 + 2) * 64;
@@ -62,8 +56,9 @@ int launch_score(const actqkv_shape& sh, int batch, const float* probe_kv, const
                  const void* rep_keys, int64_t seq_stride, int nb_capacity, int nb_begin,
                  const int32_t* nb_end, float* scores, int64_t score_stride, hipStream_t stream);
 int launch_select(int batch, const float* scores, int64_t score_stride, int nb_capacity, int nb_begin,
-                  const int32_t* nb_end, int k_cap, actqkv_cutoff* cutoff, int32_t* idx,
-                  int32_t* n_sel, float* theta, float* budget, hipStream_t stream);
+                  const int32_t* nb_end, int k_cap, float* budget_remaining,
+                  const float* theta_rest_sum, int32_t* idx, int32_t* n_sel, float* theta,
+                  float* budget, hipStream_t stream);
 int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
                      const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
                      const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,

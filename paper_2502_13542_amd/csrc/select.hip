@@ -57,8 +57,8 @@ __device__ __forceinline__ unsigned long long bitonic_sort_desc(unsigned long lo
 
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     const float* __restrict__ scores, int64_t score_stride, int nb_capacity, int nb_begin,
-    const int32_t* __restrict__ nb_end, int k_cap, actqkv_cutoff* __restrict__ cutoff,
-    int32_t* __restrict__ idx, int32_t* __restrict__ n_sel, float* __restrict__ theta_out,
+    const int32_t* __restrict__ nb_end, int k_cap, float* __restrict__ budget_remaining,
+    const float* __restrict__ theta_rest_sum, int32_t* __restrict__ idx, int32_t* __restrict__ n_sel, float* __restrict__ theta_out,
     float* __restrict__ budget_out) {
   __shared__ float red[32];
   __shared__ unsigned long long lists[kSelectWaves][64];
@@ -94,14 +94,14 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     float theta = fmaxf(logf(z) + mx - t / z, 0.f);
     float b_l;
     int e;
-    if (cutoff != nullptr) {
+    if (budget_remaining != nullptr) {
       // Eq. (12) and the budget update that follows it
-      float b_kv = cutoff[s].budget_remaining, rest = cutoff[s].theta_rest_sum;
+      float b_kv = budget_remaining[s], rest = theta_rest_sum[s];
       float den = theta + rest;
       b_l = den > 0.f ? theta / den * b_kv : b_kv;
       float r = fminf(fmaxf(floorf(b_l + 0.5f), 1.f), float(k_cap));
       e = min(int(r), n);
-      cutoff[s].budget_remaining = b_kv - b_l;
+      budget_remaining[s] = b_kv - b_l;
     } else {
       e = min(k_cap, n);
       b_l = float(e);
@@ -141,11 +141,12 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
 }
 
 int launch_select(int batch, const float* scores, int64_t score_stride, int nb_capacity, int nb_begin,
-                  const int32_t* nb_end, int k_cap, actqkv_cutoff* cutoff, int32_t* idx,
-                  int32_t* n_sel, float* theta, float* budget, hipStream_t stream) {
+                  const int32_t* nb_end, int k_cap, float* budget_remaining,
+                  const float* theta_rest_sum, int32_t* idx, int32_t* n_sel, float* theta,
+                  float* budget, hipStream_t stream) {
   hipLaunchKernelGGL(select_kernel, dim3(batch), dim3(kSelectThreads), 0, stream, scores,
-                     score_stride, nb_capacity, nb_begin, nb_end, k_cap, cutoff, idx, n_sel, theta,
-                     budget);
+                     score_stride, nb_capacity, nb_begin, nb_end, k_cap, budget_remaining, theta_rest_sum, idx,
+                     n_sel, theta, budget);
   return hip_status("select");
 }
 

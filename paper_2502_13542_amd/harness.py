@@ -86,10 +86,13 @@ class LayerRunner:
         self.stats.zero_()
 
     def step(self, q_win: torch.Tensor, k_cache, v_cache, rep_keys, n_ctx: torch.Tensor,
-             nb_end: torch.Tensor, nb_end_max: int, out: torch.Tensor, cutoff: Optional[torch.Tensor],
-             update_stats: bool = True, m: Optional[int] = None, lse=None, stream=None) -> None:
+             nb_end: torch.Tensor, nb_end_max: int, out: torch.Tensor,
+             budget_remaining: Optional[torch.Tensor] = None,
+             theta_rest_sum: Optional[torch.Tensor] = None, update_stats: bool = True,
+             m: Optional[int] = None, lse=None, stream=None) -> None:
         """probe -> scores -> selection -> attention for one window (or decode step).
-        nb_end_max: host-side upper bound of nb_end, sizes the scoring launch."""
+        nb_end_max: host-side upper bound of nb_end, sizes the scoring launch.
+        budget_remaining / theta_rest_sum: [batch] fp32 cut-off state, or None."""
         sh, cs, bt = self.shape, self.cs, self.batch
         m = self.m if m is None else m
         nb_begin = sh.n_init // sh.block_size
@@ -100,8 +103,8 @@ class LayerRunner:
         nb_cap = min(max(nb_end_max, nb_begin), self.nb_capacity)
         B.score_blocks(cs, bt, self.probe_kv, self.probe_norm, rep_keys, rep_stride, nb_cap, nb_begin,
                        nb_end, self.scores, self.score_stride, stream)
-        B.select(bt, self.scores, self.score_stride, nb_cap, nb_begin, nb_end, self.k_cap, cutoff,
-                 self.idx, self.n_sel, self.theta, self.budget, stream)
+        B.select(bt, self.scores, self.score_stride, nb_cap, nb_begin, nb_end, self.k_cap, budget_remaining,
+                 theta_rest_sum, self.idx, self.n_sel, self.theta, self.budget, stream)
         B.retrieval_attention(cs, bt, m, q_win, k_cache, v_cache, cache_stride, self.nb_capacity, n_ctx,
                               self.idx, self.n_sel, self.k_cap, out, lse, self.workspace, stream)
 
@@ -115,7 +118,8 @@ class PrefillPlan:
     nb_end_host: List[int]
     n_ctx: torch.Tensor      # int32 [T]
     nb_end: torch.Tensor     # int32 [T]
-    cutoff: Optional[torch.Tensor]   # float32 [T][2] or None
+    budget: Optional[torch.Tensor]   # float32 [T]: B_kv handed to each window, or None
+    rest: Optional[torch.Tensor]     # float32 [T]: R of each window, or None
 
 
 def make_prefill_plan(shape: LayerShape, n_ctx: int, m: int,
@@ -124,12 +128,13 @@ def make_prefill_plan(shape: LayerShape, n_ctx: int, m: int,
     rows = [min(m, n_ctx - w) for w in w0s]
     nb_end = [eligible_range(shape, w)[1] for w in w0s]
     nctx = [w + r for w, r in zip(w0s, rows)]
-    cut = None
+    budget = rest = None
     if cutoffs is not None:
-        cut = torch.tensor([[c[0], c[1]] for c in cutoffs], dtype=torch.float32, device=device)
+        budget = torch.tensor([c[0] for c in cutoffs], dtype=torch.float32, device=device)
+        rest = torch.tensor([c[1] for c in cutoffs], dtype=torch.float32, device=device)
     return PrefillPlan(len(w0s), w0s, rows, nb_end,
                        torch.tensor(nctx, dtype=torch.int32, device=device),
-                       torch.tensor(nb_end, dtype=torch.int32, device=device), cut)
+                       torch.tensor(nb_end, dtype=torch.int32, device=device), budget, rest)
 
 
 def prefill_layer(runner: LayerRunner, plan: PrefillPlan, q: torch.Tensor, k_cache, v_cache, rep_keys,
@@ -141,14 +146,15 @@ def prefill_layer(runner: LayerRunner, plan: PrefillPlan, q: torch.Tensor, k_cac
     m = runner.m
     for t in (range(plan.n_windows) if windows is None else windows):
         w0, rows = plan.w0[t], plan.rows[t]
-        cut = None if plan.cutoff is None else plan.cutoff[t:t + 1]
+        bud = None if plan.budget is None else plan.budget[t:t + 1]
+        rest = None if plan.rest is None else plan.rest[t:t + 1]
         runner.step(q[w0:w0 + rows], k_cache, v_cache, rep_keys, plan.n_ctx[t:t + 1],
-                    plan.nb_end[t:t + 1], plan.nb_end_host[t], out[w0:w0 + rows], cut, True, rows)
+                    plan.nb_end[t:t + 1], plan.nb_end_host[t], out[w0:w0 + rows], bud, rest, True, rows)
         if record is not None and t in record:
             rec[t] = dict(probe=runner.probe[0].clone(), probe_kv=runner.probe_kv[0].clone(),
                           probe_norm=runner.probe_norm[0].clone(),
                           weights=runner.weights[0, :rows].clone(), scores=runner.scores[0].clone(),
                           idx=runner.idx[0].clone(), n_sel=runner.n_sel[0].clone(),
                           theta=runner.theta[0].clone(), budget=runner.budget[0].clone(),
-                          cutoff_after=None if cut is None else cut[0].clone())
+                          budget_after=None if bud is None else bud[0].clone())
     return rec

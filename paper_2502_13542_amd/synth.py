@@ -292,3 +292,22 @@ def cutoff_state(w: Workload, n_eligible: int, step: int, layer: int = 0, seq: i
     rest = remaining * th * (0.8 + 0.4 * float(r[1]))
     budget = target_e * (th + rest) / th + (float(r[2]) - 0.5) * 0.25
     return float(budget), float(rest)
+
+
+def decode_cutoff_profile(w: Workload, n_eligible: int, step: int = 0) -> Tuple[float, List[float]]:
+    """Seeded cut-off inputs of one decode step over all layers: the initial budget B_kv
+    and, per layer, R = the summed mean densities of the layers still to come.
+
+    Per-layer target block counts b_l are drawn in e_frac * k_cap; R_l is set so that a
+    layer whose density is close to ln(n_eligible) (near-uniform scores) is granted about
+    b_l blocks out of what is left: R_l = ln(n_e) * sum_{j>l} b_j / b_l.  This stands in for
+    the density profile a full model would have accumulated over earlier steps."""
+    g = _gen("cpu", w.seed, _TENSOR_ID["cutoff"], 1 << 20, step)
+    r = torch.rand(w.n_layers, generator=g, dtype=torch.float64)
+    b = [(w.e_frac[0] + (w.e_frac[1] - w.e_frac[0]) * float(x)) * w.k_cap for x in r]
+    th = math.log(max(n_eligible, 2))
+    rest = []
+    for l in range(w.n_layers):
+        tail = sum(b[l + 1:])
+        rest.append(th * tail / b[l])
+    return float(sum(b)), rest

@@ -83,9 +83,10 @@ def test_score_select_attention_reject(lib):
                                              A16, A16, k.get("ss", 64), None)
     assert sb(rep=None) == -1 and sb(rep=A16 + 8) == -3 and sb(ss=10) == -1 and sb(cap=-1) == -1
     assert sb(batch=2, stride=8) == -1 and sb(stride=4) == -3 and sb(cap=9000, ss=9000) == -2
-    se = lambda **k: lib.actqkv_select(1, A16, 64, 64, 1, A16, k.get("k_cap", 32), k.get("cut"),
-                                       k.get("idx", A16), A16, None, None, None)
-    assert se(k_cap=0) == -2 and se(k_cap=65) == -2 and se(idx=None) == -1 and se(cut=A16 + 4) == -3
+    se = lambda **k: lib.actqkv_select(1, A16, 64, 64, 1, A16, k.get("k_cap", 32), k.get("bud"),
+                                       k.get("rest"), k.get("idx", A16), A16, None, None, None)
+    assert se(k_cap=0) == -2 and se(k_cap=65) == -2 and se(idx=None) == -1
+    assert se(bud=A16 + 2, rest=A16) == -3 and se(bud=A16) == -1 and se(rest=A16) == -1
     at = lambda **k: lib.actqkv_retrieval_attention(ctypes.byref(cs), 1, k.get("m", 512), A16,
                                                     k.get("kc", A16), A16, 0, k.get("cap", 64), A16, A16,
                                                     A16, 32, k.get("out", A16), None, k.get("ws", A16),

@@ -65,7 +65,7 @@ def run_prefill_case(w: synth.Workload, attend=None, use_cutoff=None, layer=0):
             assert abs(float(g["theta"]) - res["theta"]) < TOL_THETA, f"theta, window {t}"
             assert abs(float(g["budget"]) - res["budget"]) <= TOL_BUDGET * max(1.0, abs(res["budget"]))
             if cutoffs is not None:
-                assert abs(float(g["cutoff_after"][0]) - res["b_kv_after"]) <= TOL_BUDGET * max(
+                assert abs(float(g["budget_after"]) - res["b_kv_after"]) <= TOL_BUDGET * max(
                     1.0, abs(cutoffs[t][0]))
         gi = g["idx"].cpu().tolist()
         gn = int(g["n_sel"])
@@ -142,7 +142,10 @@ def _select_case(scores: np.ndarray, nb_begin: int, k_cap: int, cutoff):
     theta = torch.zeros(1, dtype=torch.float32, device=DEV)
     budget = torch.zeros(1, dtype=torch.float32, device=DEV)
     cut = None if cutoff is None else torch.tensor([list(cutoff)], dtype=torch.float32, device=DEV)
-    B.select(1, sc, n + nb_begin, n + nb_begin, nb_begin, nb_end, k_cap, cut, idx, n_sel, theta, budget)
+    bud = None if cut is None else cut[0, 0:1]
+    rest = None if cut is None else cut[0, 1:2]
+    B.select(1, sc, n + nb_begin, n + nb_begin, nb_begin, nb_end, k_cap, bud, rest, idx, n_sel, theta,
+             budget)
     torch.cuda.synchronize()
     s32 = scores.astype(np.float32).astype(np.float64)
     ids = list(range(nb_begin, nb_begin + n))
@@ -234,10 +237,11 @@ def test_decode_step_batch(dtype):
     runner = H.LayerRunner(sh, bt, 1, nb_cap, w.k_cap, DEV)
     nb_ends = [H.eligible_range(sh, n - 1)[1] for n in n_ctxs]
     cuts = [synth.cutoff_state(w, e - 1, 0, 3, s) for s, e in enumerate(nb_ends)]
-    cut = torch.tensor(cuts, dtype=torch.float32, device=DEV)
+    bud = torch.tensor([c[0] for c in cuts], dtype=torch.float32, device=DEV)
+    rest = torch.tensor([c[1] for c in cuts], dtype=torch.float32, device=DEV)
     out = torch.zeros_like(qd)
     runner.step(qd, kc, vc, repd, torch.tensor(n_ctxs, dtype=torch.int32, device=DEV),
-                torch.tensor(nb_ends, dtype=torch.int32, device=DEV), max(nb_ends), out, cut,
+                torch.tensor(nb_ends, dtype=torch.int32, device=DEV), max(nb_ends), out, bud, rest,
                 update_stats=False, m=1)
     torch.cuda.synchronize()
     for s, n in enumerate(n_ctxs):
