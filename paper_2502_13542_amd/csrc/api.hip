@@ -99,7 +99,7 @@ static int check_blocks(int nb_capacity, int nb_begin, int k_cap, bool use_k) {
   } while (0)
 
 bool prefill_mfma_supported(const actqkv_shape& sh, int m);
-int prefill_mfma_qtiles(const actqkv_shape& sh, int m);
+int prefill_mfma_workgroups(const actqkv_shape& sh, int m);
 int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, const void* q,
                                   const void* k_cache, const void* v_cache, int64_t seq_stride,
                                   int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
@@ -110,7 +110,7 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
 int prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap) {
   (void)k_cap;
   if (!prefill_mfma_supported(sh, m)) return 1;
-  const int base = batch * sh.n_kv_heads * prefill_mfma_qtiles(sh, m);
+  const int base = batch * prefill_mfma_workgroups(sh, m);
   int s = 256 / (base > 0 ? base : 1);
   return s < 1 ? 1 : (s > 8 ? 8 : s);
 }
@@ -129,7 +129,7 @@ size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity
   size_t attn = 0;
   if (decode_mfma_supported(sh, m)) attn = decode_mfma_scratch_floats(sh, batch, k_cap) * sizeof(float);
   if (prefill_mfma_supported(sh, m)) {
-    size_t groups = size_t(batch) * sh.n_kv_heads * prefill_mfma_qtiles(sh, m);
+    size_t groups = size_t(batch) * prefill_mfma_workgroups(sh, m);
     attn = groups * splits * kPfPartialFloats * sizeof(float);
   }
   return kCounterBytes + align_up(probe > attn ? probe : attn, 256);

@@ -2,7 +2,7 @@
 // over [k^t, K*]; bf16 storage, fp32 accumulation).  HBM-bound: every selected key and
 // value byte is read exactly once, by exactly one wavefront.
 //
-// One wavefront owns one 128-key tile of one (sequence, KV head): initial tokens, the
+// A wavefront owns whole 128-key tiles of one (sequence, KV head): initial tokens, the
 // blocks chosen by actqkv_select (read from device memory) or the local span up to the new
 // token.  The G query heads of the KV head ride along as columns of a 16-wide matrix-core
 // tile, so a key or value byte is loaded once for all of them, straight from global memory
@@ -13,16 +13,16 @@
 // bytes of a row.  Keys enter S^T in a permuted row order such that each lane's accumulator
 // registers hold 8 consecutive keys of every 32-key step, which is exactly the B-operand
 // layout of the second product; no cross-lane traffic is needed apart from two shuffles
-// for the row maximum.  The four wavefronts of a workgroup (four consecutive tiles) merge
-// their (max, sum, O) through LDS and write one partial; attn_decode_combine_kernel merges
-// the partials of a (sequence, head).
+// for the row maximum.  The 8 wavefronts of a workgroup merge their (max, sum, O) through
+// LDS.  If one workgroup covers a whole (sequence, KV head) it writes the output itself;
+// otherwise the workgroups write partials and attn_decode_combine_kernel merges them.
 #include "common.h"
 #include "launch.h"
 
 namespace actqkv {
 
 constexpr int kDcD = 128;
-constexpr int kDcWaves = 4;
+constexpr int kDcMaxWaves = 8;   // 512 threads: the register budget stays at 256 per lane
 
 struct DcParams {
   const uint16_t* q;
@@ -38,66 +38,71 @@ struct DcParams {
   float* lse;
   float* part;  // [batch][Hk][n_wg][G][D + 2]
   int n_q_heads, n_kv_heads, n_init, n_local;
-  int n_wg;     // workgroups (partials) per (sequence, KV head)
+  int n_wg;     // workgroups per (sequence, KV head); 1: the workgroup writes the output itself
   float scale_log2e;
 };
 
 __device__ __forceinline__ bf16x8 dc_as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-__global__ __launch_bounds__(kDcWaves * 64) void attn_decode_kernel(DcParams p) {
-  __shared__ float red_ml[kDcWaves][8][2];
-  __shared__ float red_o[kDcWaves][8][kDcD];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+// grid (n_wg, Hk, batch); blockDim = 64 * (wavefronts per workgroup).  Wavefront w of
+// workgroup g walks tiles g*W + w, g*W + w + n_wg*W, ...
+__global__ __launch_bounds__(kDcMaxWaves * 64) void attn_decode_kernel(DcParams p) {
+  extern __shared__ __attribute__((aligned(16))) float dc_lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
   const int n = lane & 15, kq = lane >> 4;       // MFMA column (query head) and lane quarter
   const int wg = blockIdx.x, hk = blockIdx.y, s = blockIdx.z;
   const int group = p.n_q_heads / p.n_kv_heads;
+  float* red_ml = dc_lds;                        // [n_waves][group][2]
+  float* red_o = dc_lds + n_waves * group * 2;   // [n_waves][group][D]
 
   const int n_ctx = min(max(p.n_ctx[s], 1), p.nb_capacity * kBlock);
   const WindowGeom g = window_geom(n_ctx, 1, p.n_init, p.n_local);
   const TileList tl = make_tile_list(g, n_ctx - 1, p.idx + size_t(s) * p.k_cap, p.n_sel[s], p.k_cap,
                                      p.nb_capacity);
-  const int t = wg * kDcWaves + wave;
-  int block = 0, lo = 0, hi = 0;
-  if (t < tl.count()) tl.get(t, block, lo, hi);
-  const bool live = hi > lo;                     // wave-uniform
+  const int n_tiles = tl.count();
 
+  // Q^T as B operand: lane (n, kq) holds channels ks*32 + 8*kq .. +7 of head n (zero for n >= G)
+  bf16x8 qb[4];
+  {
+    const uint16_t* qp = p.q + (size_t(s) * p.n_q_heads + hk * group + min(n, group - 1)) * kDcD + 8 * kq;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      u32x4 v = *reinterpret_cast<const u32x4*>(qp + ks * 32);
+      if (n >= group) v = u32x4{0u, 0u, 0u, 0u};
+      qb[ks] = dc_as_bf16x8(v);
+    }
+  }
   float m_run = -INFINITY, l_run = 0.f;
   f32x4 acc_o[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc_o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const size_t tile_elems = size_t(kBlock) * kDcD;
+  const uint16_t* kc = p.k_cache + size_t(s) * p.seq_stride;
+  const uint16_t* vc = p.v_cache + size_t(s) * p.seq_stride;
 
-  if (live) {
-    const size_t tile_elems = size_t(kBlock) * kDcD;
-    const uint16_t* kt = p.k_cache + size_t(s) * p.seq_stride + (size_t(block) * p.n_kv_heads + hk) * tile_elems;
-    const uint16_t* vt = p.v_cache + size_t(s) * p.seq_stride + (size_t(block) * p.n_kv_heads + hk) * tile_elems;
+  for (int t = wg * n_waves + wave; t < n_tiles; t += p.n_wg * n_waves) {
+    int block, lo, hi;
+    tl.get(t, block, lo, hi);
+    if (hi <= lo) continue;                      // wave-uniform
+    const uint16_t* kt = kc + (size_t(block) * p.n_kv_heads + hk) * tile_elems;
+    const uint16_t* vt = vc + (size_t(block) * p.n_kv_heads + hk) * tile_elems;
     const int kpos0 = block * kBlock;
 
     // A operands of S^T: MFMA row r of sub-tile h of 32-key step st is key 32*st + 8*(r/4) + 4*h + r%4,
     // so that lane quarter kq ends up with keys 32*st + 8*kq + 4*h + i in register i.
     u32x4 ka[32];
     {
-      const int r = n;   // A-operand row of this lane
-      const uint16_t* base = kt + size_t(8 * (r >> 2) + (r & 3)) * kDcD + 8 * kq;
+      const uint16_t* base = kt + size_t(8 * (n >> 2) + (n & 3)) * kDcD + 8 * kq;
 #pragma unroll
       for (int st = 0; st < 4; ++st)
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
-          for (int ks = 0; ks < 4; ++ks)   // 32 loads in flight
+          for (int ks = 0; ks < 4; ++ks)
             ka[(st * 2 + h) * 4 + ks] =
                 *reinterpret_cast<const u32x4*>(base + size_t(32 * st + 4 * h) * kDcD + ks * 32);
     }
-    // Q^T as B operand: lane (n, kq) holds channels ks*32 + 8*kq .. +7 of head n (zero for n >= G)
-    bf16x8 qb[4];
-    {
-      const uint16_t* qp = p.q + (size_t(s) * p.n_q_heads + hk * group + min(n, group - 1)) * kDcD + 8 * kq;
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        u32x4 v = *reinterpret_cast<const u32x4*>(qp + ks * 32);
-        if (n >= group) v = u32x4{0u, 0u, 0u, 0u};
-        qb[ks] = dc_as_bf16x8(v);
-      }
-    }
+    __builtin_amdgcn_sched_barrier(0);   // all 32 key loads are in flight before the first MFMA
     f32x4 sc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -116,7 +121,8 @@ __global__ __launch_bounds__(kDcWaves * 64) void attn_decode_kernel(DcParams p) 
         for (int st = 0; st < 4; ++st)
           va[dg * 4 + st] = *reinterpret_cast<const u32x4*>(base + size_t(16 * dg) * kBlock + 32 * st);
     }
-    // mask and softmax of this tile: sc[2*st + h][i] is key kpos0 + 32*st + 8*kq + 4*h + i
+    __builtin_amdgcn_sched_barrier(0);   // all 32 value loads are in flight during the softmax
+    // mask and online softmax: sc[2*st + h][i] is key kpos0 + 32*st + 8*kq + 4*h + i
     float mx = -INFINITY;
 #pragma unroll
     for (int j = 0; j < 8; ++j)
@@ -129,19 +135,23 @@ __global__ __launch_bounds__(kDcWaves * 64) void attn_decode_kernel(DcParams p) 
       }
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    m_run = mx * p.scale_log2e;                  // finite: a live tile has a visible key
+    const float m_new = fmaxf(m_run, mx * p.scale_log2e);   // finite: the tile has a visible key
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
     float psum = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float pv = __builtin_amdgcn_exp2f(sc[j][i] * p.scale_log2e - m_run);
+        const float pv = __builtin_amdgcn_exp2f(sc[j][i] * p.scale_log2e - m_new);
         sc[j][i] = pv;
         psum += pv;
       }
     psum += __shfl_xor(psum, 16, 64);
     psum += __shfl_xor(psum, 32, 64);
-    l_run = psum;
+    l_run = l_run * alpha + psum;
+#pragma unroll
+    for (int dg = 0; dg < 8; ++dg) acc_o[dg] *= alpha;
     // O^T += V^T P^T
     typedef __attribute__((ext_vector_type(8))) float f32x8;
 #pragma unroll
@@ -155,36 +165,40 @@ __global__ __launch_bounds__(kDcWaves * 64) void attn_decode_kernel(DcParams p) 
     }
   }
 
-  // merge the four wavefronts: lane (n < G, kq) holds channels 16*dg + 4*kq + i of head n
+  // merge the wavefronts: lane (n < G, kq) holds channels 16*dg + 4*kq + i of head n
   if (n < group) {
     if (kq == 0) {
-      red_ml[wave][n][0] = m_run;
-      red_ml[wave][n][1] = l_run;
+      red_ml[(wave * group + n) * 2 + 0] = m_run;
+      red_ml[(wave * group + n) * 2 + 1] = l_run;
     }
 #pragma unroll
     for (int dg = 0; dg < 8; ++dg)
-      *reinterpret_cast<f32x4*>(&red_o[wave][n][16 * dg + 4 * kq]) = acc_o[dg];
+      *reinterpret_cast<f32x4*>(&red_o[(wave * group + n) * kDcD + 16 * dg + 4 * kq]) = acc_o[dg];
   }
   __syncthreads();
-  // thread = (head, channel pair): 256 threads cover up to 8 heads x 128 channels in two halves
   float* part = p.part + ((size_t(s) * p.n_kv_heads + hk) * p.n_wg + wg) * group * (kDcD + 2);
-  for (int e = threadIdx.x; e < group * kDcD; e += kDcWaves * 64) {
+  for (int e = threadIdx.x; e < group * kDcD; e += blockDim.x) {
     const int h = e / kDcD, d = e - h * kDcD;
     float mm = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < kDcWaves; ++w) mm = fmaxf(mm, red_ml[w][h][0]);
+    for (int w = 0; w < n_waves; ++w) mm = fmaxf(mm, red_ml[(w * group + h) * 2]);
     const float m_safe = mm == -INFINITY ? 0.f : mm;
     float l = 0.f, o = 0.f;
-#pragma unroll
-    for (int w = 0; w < kDcWaves; ++w) {
-      const float sc_w = __builtin_amdgcn_exp2f(red_ml[w][h][0] - m_safe);
-      l += sc_w * red_ml[w][h][1];
-      o += sc_w * red_o[w][h][d];
+    for (int w = 0; w < n_waves; ++w) {
+      const float sc_w = __builtin_amdgcn_exp2f(red_ml[(w * group + h) * 2] - m_safe);
+      l += sc_w * red_ml[(w * group + h) * 2 + 1];
+      o += sc_w * red_o[(w * group + h) * kDcD + d];
     }
-    part[size_t(h) * (kDcD + 2) + d] = o;
-    if (d == 0) {
-      part[size_t(h) * (kDcD + 2) + kDcD] = mm;
-      part[size_t(h) * (kDcD + 2) + kDcD + 1] = l;
+    if (p.n_wg == 1) {
+      const int head = hk * group + h;
+      p.out[(size_t(s) * p.n_q_heads + head) * kDcD + d] = uint16_t(f32_to_bf16_bits(l > 0.f ? o / l : 0.f));
+      if (p.lse != nullptr && d == 0)
+        p.lse[size_t(s) * p.n_q_heads + head] = (mm + log2f(l)) * 0.6931471805599453f;
+    } else {
+      part[size_t(h) * (kDcD + 2) + d] = o;
+      if (d == 0) {
+        part[size_t(h) * (kDcD + 2) + kDcD] = mm;
+        part[size_t(h) * (kDcD + 2) + kDcD + 1] = l;
+      }
     }
   }
 }
@@ -232,14 +246,22 @@ bool decode_mfma_supported(const actqkv_shape& sh, int m) {
   return sh.dtype == ACTQKV_BF16 && sh.head_dim == kDcD && m == 1 && g <= 8;
 }
 
-// Workgroups per (sequence, KV head): enough wavefronts for the longest possible tile list.
-int decode_mfma_workgroups(const actqkv_shape& sh, int k_cap) {
-  const int tiles = (sh.n_init + kBlock - 1) / kBlock + k_cap + sh.n_local / kBlock + 2;
-  return (tiles + kDcWaves - 1) / kDcWaves;
+// Launch shape: workgroups of 8 wavefronts; about 2048 wavefronts in total (two per SIMD,
+// each with a whole tile's loads in flight) unless the tile list is shorter than that.
+// One workgroup per (sequence, KV head) writes the output itself; with more,
+// attn_decode_combine_kernel merges the partials.
+static int decode_tiles_max(const actqkv_shape& sh, int k_cap) {
+  return (sh.n_init + kBlock - 1) / kBlock + k_cap + sh.n_local / kBlock + 2;
+}
+int decode_mfma_workgroups(const actqkv_shape& sh, int batch, int k_cap) {
+  const int pairs = batch * sh.n_kv_heads;
+  const int want = (2048 + pairs * kDcMaxWaves - 1) / (pairs * kDcMaxWaves);
+  const int most = (decode_tiles_max(sh, k_cap) + kDcMaxWaves - 1) / kDcMaxWaves;
+  return want < 1 ? 1 : (want > most ? most : want);
 }
 
 size_t decode_mfma_scratch_floats(const actqkv_shape& sh, int batch, int k_cap) {
-  return size_t(batch) * sh.n_q_heads * decode_mfma_workgroups(sh, k_cap) * (kDcD + 2);
+  return size_t(batch) * sh.n_q_heads * decode_mfma_workgroups(sh, batch, k_cap) * (kDcD + 2);
 }
 
 int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* q, const void* k_cache,
@@ -264,11 +286,15 @@ int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* 
   p.n_kv_heads = sh.n_kv_heads;
   p.n_init = sh.n_init;
   p.n_local = sh.n_local;
-  p.n_wg = decode_mfma_workgroups(sh, k_cap);
+  p.n_wg = decode_mfma_workgroups(sh, batch, k_cap);
   p.scale_log2e = scale * 1.4426950408889634f;
-  hipLaunchKernelGGL(attn_decode_kernel, dim3(p.n_wg, sh.n_kv_heads, batch), dim3(kDcWaves * 64), 0,
+  const int group = sh.n_q_heads / sh.n_kv_heads;
+  const int n_waves = kDcMaxWaves;
+  const size_t lds = size_t(n_waves) * group * (kDcD + 2) * sizeof(float);
+  hipLaunchKernelGGL(attn_decode_kernel, dim3(p.n_wg, sh.n_kv_heads, batch), dim3(n_waves * 64), lds,
                      stream, p);
-  hipLaunchKernelGGL(attn_decode_combine_kernel, dim3(sh.n_q_heads, batch), dim3(kDcD), 0, stream, p);
+  if (p.n_wg > 1)
+    hipLaunchKernelGGL(attn_decode_combine_kernel, dim3(sh.n_q_heads, batch), dim3(kDcD), 0, stream, p);
   return hip_status("attention (decode)");
 }
 

@@ -12,9 +12,12 @@
 // KV head sit on one XCD (blockIdx % Hk picks the head), so that head's gathered
 // tiles stay in that XCD's L2.
 //
-// Data flow per tile.  K [128 keys][D] and V^T [D][128 keys] go global -> registers
-// -> LDS (double buffered, rows padded to 272 bytes so that 16-byte reads of 16
-// consecutive rows hit all 64 banks).  Each wavefront computes S^T = K Q^T with
+// Data flow per tile.  K [128 keys][D] and V^T [D][128 keys] go from HBM straight into
+// LDS (global_load_lds_dwordx4, double buffered, 16-byte chunks XOR-swizzled with the row
+// index so that operand reads of 16 consecutive rows hit all 64 banks).  A 16x16x32 tiling
+// with one wavefront per SIMD and no key splits was measured and rejected: one wavefront
+// can only issue a 1 KB LDS operand read every ~35 cycles, which caps a 16-cycle MFMA per
+// read at ~40 % and left that variant at 0.4 PFLOP/s.  Each wavefront computes S^T = K Q^T with
 // v_mfma_f32_32x32x16_bf16 (A = K rows from LDS, B = Q^T kept in registers), so a
 // lane ends up holding scores of ONE query: the softmax needs no cross-lane work
 // except one exchange between the two half-waves, and the probabilities are
@@ -31,9 +34,10 @@ namespace actqkv {
 constexpr int kPfThreads = 512;
 constexpr int kPfWaves = 8;
 constexpr int kPfD = 128;
-constexpr int kRowPad = 136;                         // bf16 elements per padded LDS row (272 bytes)
+constexpr int kRowPad = 128;                         // bf16 elements per LDS row (16 chunks of 16 bytes)
 constexpr int kTileElems = kBlock * kRowPad;         // one K or V^T tile in LDS
-constexpr int kPfLdsBytes = 2 * 2 * kTileElems * 2;  // 2 stages x (K, V^T) x bf16
+constexpr int kPfMaxTiles = 96;                      // initial + selected (<= 64) + local + window
+constexpr int kPfLdsBytes = 2 * 2 * kTileElems * 2 + kPfMaxTiles * 12;  // 2 stages x (K, V^T) + tile table
 constexpr int kPfPartWords = 34;                     // per lane: 32 bf16 pairs + max + sum
 constexpr int kMaxPfSplits = 8;
 
@@ -140,49 +144,59 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
     for (int j = 0; j < 16; ++j) acc_o[i][j] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;   // running max (log2 units), this lane's share of the sum
 
-  const uint16_t* kc = p.k_cache + size_t(s) * p.seq_stride;
-  const uint16_t* vc = p.v_cache + size_t(s) * p.seq_stride;
-  const size_t tile_elems = size_t(kBlock) * kPfD;
-
-  // global -> register staging of one tile: 4 K chunks + 4 V^T chunks of 16 bytes per thread
-  u32x4 stage_k[4], stage_v[4];
-  auto load_tile = [&](int t) {
+  const char* kc = reinterpret_cast<const char*>(p.k_cache + size_t(s) * p.seq_stride);
+  const char* vc = reinterpret_cast<const char*>(p.v_cache + size_t(s) * p.seq_stride);
+  constexpr uint32_t kTileBytes = kBlock * kPfD * 2;     // one (block, KV head) tile in HBM
+  constexpr uint32_t kSlotBytes = kTileElems * 2;        // one tile in LDS
+  char* lds_b = reinterpret_cast<char*>(lds);
+  // LDS: stage s holds K at (2s) * kSlotBytes and V^T at (2s + 1) * kSlotBytes; behind the
+  // stages sits the table {block, lo, hi} of this workgroup's tiles (the selected indices
+  // are read from global memory once, not once per use).
+  int* tile_tab = reinterpret_cast<int*>(lds_b + 4 * kSlotBytes);
+  for (int i = tid; i < t_end - t_begin; i += kPfThreads) {
     int block, lo, hi;
-    tl.get(t, block, lo, hi);
-    const uint16_t* kt = kc + (size_t(block) * p.n_kv_heads + hk) * tile_elems;
-    const uint16_t* vt = vc + (size_t(block) * p.n_kv_heads + hk) * tile_elems;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = tid + kPfThreads * i;
-      stage_k[i] = *reinterpret_cast<const u32x4*>(kt + size_t(c) * 8);
-      stage_v[i] = *reinterpret_cast<const u32x4*>(vt + size_t(c) * 8);
-    }
-  };
-  auto store_tile = [&](int stage) {
-    uint16_t* ks_ = lds + stage * 2 * kTileElems;
-    uint16_t* vs_ = ks_ + kTileElems;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = tid + kPfThreads * i;
-      const int r = c >> 4, col = (c & 15) * 8;
-      *reinterpret_cast<u32x4*>(ks_ + r * kRowPad + col) = stage_k[i];
-      *reinterpret_cast<u32x4*>(vs_ + r * kRowPad + col) = stage_v[i];
-    }
-  };
-
-  if (t_begin < t_end) {
-    load_tile(t_begin);
-    store_tile(0);
+    tl.get(t_begin + i, block, lo, hi);
+    tile_tab[3 * i + 0] = block;
+    tile_tab[3 * i + 1] = lo;
+    tile_tab[3 * i + 2] = hi;
   }
   __syncthreads();
 
-  const int a_row = perm_row(n);
-  for (int t = t_begin; t < t_end; ++t) {
-    const int stage = (t - t_begin) & 1;
-    if (t + 1 < t_end) load_tile(t + 1);
+  // Tiles go from HBM straight into LDS (global_load_lds_dwordx4: lane i of a wavefront
+  // fills the i-th 16-byte chunk of a contiguous 1 KB piece of LDS, i.e. 4 rows; no staging
+  // registers, no ds_write).  Wavefront w fills rows 16*w .. 16*w + 15 of a K and of a V^T
+  // tile with 4 such loads each.  The 16 chunks of an LDS row are XOR-swizzled with
+  // (row % 16), so that the 16 rows an MFMA operand load touches hit all 64 banks; the
+  // swizzle is applied on the global side: the lane that fills chunk c' of row r fetches
+  // chunk c' ^ (r % 16) of that row.
+  const int lq = lane >> 4, c16 = lane & 15;
+  const uint32_t g_row = uint32_t(16 * wave + lq) * (kPfD * 2);          // + 4*i rows per load
+  const uint32_t g_chunk = uint32_t(c16 ^ lq) << 4;                      // ^ (i << 6)
+  auto fetch_tile = [&](int u, int stage) {
+    const int block = __builtin_amdgcn_readfirstlane(tile_tab[3 * u]);
+    const size_t off = (size_t(block) * p.n_kv_heads + hk) * kTileBytes;
+    char* dst = lds_b + stage * 2 * kSlotBytes + wave * (16 * kRowPad * 2);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t go = g_row + i * 4 * (kPfD * 2) + (g_chunk ^ (uint32_t(i) << 6));
+      __builtin_amdgcn_global_load_lds(kc + off + go, dst + i * 4 * (kRowPad * 2), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(vc + off + go, dst + kSlotBytes + i * 4 * (kRowPad * 2), 16, 0, 0);
+    }
+  };
 
-    int block, lo, hi;
-    tl.get(t, block, lo, hi);
+  if (t_begin < t_end) fetch_tile(0, 0);
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+
+  const int a_row = perm_row(n);
+  const uint32_t sw = uint32_t(a_row & 15);   // swizzle key of every row this lane reads (K and V^T)
+  for (int t = t_begin; t < t_end; ++t) {
+    const int u = t - t_begin, stage = u & 1;
+    if (t + 1 < t_end) fetch_tile(u + 1, stage ^ 1);   // lands while this tile is computed
+
+    const int block = __builtin_amdgcn_readfirstlane(tile_tab[3 * u]);
+    const int lo = __builtin_amdgcn_readfirstlane(tile_tab[3 * u + 1]);
+    const int hi = __builtin_amdgcn_readfirstlane(tile_tab[3 * u + 2]);
     const int kpos0 = block * kBlock;
     // the wavefront skips tiles none of its rows can see; it masks tiles that are
     // clipped or that reach past its first row's position
@@ -197,10 +211,10 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
       for (int kb = 0; kb < 4; ++kb) {
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc_s[kb][j] = 0.f;
-        const uint16_t* arow = ks_ + (kb * 32 + a_row) * kRowPad + 8 * half;
+        const uint16_t* arow = ks_ + (kb * 32 + a_row) * kRowPad;
 #pragma unroll
         for (int ks = 0; ks < kPfD / 16; ++ks) {
-          bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(arow + ks * 16));
+          bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(arow + (((2 * ks + half) ^ sw) << 3)));
           acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], acc_s[kb], 0, 0, 0);
         }
       }
@@ -250,7 +264,8 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
           const bf16x8 pb = pack8(acc_s[kb][8 * s2 + 0], acc_s[kb][8 * s2 + 1], acc_s[kb][8 * s2 + 2],
                                   acc_s[kb][8 * s2 + 3], acc_s[kb][8 * s2 + 4], acc_s[kb][8 * s2 + 5],
                                   acc_s[kb][8 * s2 + 6], acc_s[kb][8 * s2 + 7]);
-          const uint16_t* vrow = vs_ + n * kRowPad + kb * 32 + 16 * s2 + 8 * half;
+          // V^T row db*32 + n (swizzle key n % 16), chunk 4*kb + 2*s2 + half
+          const uint16_t* vrow = vs_ + n * kRowPad + (((4 * kb + 2 * s2 + half) ^ (n & 15)) << 3);
 #pragma unroll
           for (int db = 0; db < 4; ++db) {
             bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(vrow + db * 32 * kRowPad));
@@ -259,7 +274,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
         }
       }
     }
-    if (t + 1 < t_end) store_tile(stage ^ 1);
+    __builtin_amdgcn_s_waitcnt(0);   // this wavefront's pieces of the next tile have landed in LDS
     __syncthreads();
   }
 
@@ -344,13 +359,20 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(PfParams p) {
 
 bool prefill_mfma_supported(const actqkv_shape& sh, int m) {
   const int g = sh.n_q_heads / sh.n_kv_heads;
-  return sh.dtype == ACTQKV_BF16 && sh.head_dim == kPfD && m > 1 && g <= 8;
+  // longest possible tile list: initial + selected + local + window (+ 2 partial blocks)
+  const int tiles = sh.n_init / kBlock + 64 + sh.n_local / kBlock + (m + kBlock - 1) / kBlock + 2;
+  return sh.dtype == ACTQKV_BF16 && sh.head_dim == kPfD && m > 1 && g <= 8 && tiles <= kPfMaxTiles;
 }
 
 int prefill_mfma_qtiles(const actqkv_shape& sh, int m) {
   const int g = sh.n_q_heads / sh.n_kv_heads;
   const int pos_per_wg = 32 * (kPfWaves / g);
   return (m + pos_per_wg - 1) / pos_per_wg;
+}
+
+// workgroups per (sequence, split): query tiles x KV heads
+int prefill_mfma_workgroups(const actqkv_shape& sh, int m) {
+  return prefill_mfma_qtiles(sh, m) * sh.n_kv_heads;
 }
 
 int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, const void* q,

@@ -216,11 +216,14 @@ def test_scores_zero_norms_and_determinism():
 
 
 # ---------------------------------------------------------------- decode
-@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
-def test_decode_step_batch(dtype):
-    sh = LayerShape(8, 2, 128 if dtype == "bf16" else 64, 128, 4, 128, 256, dtype)
-    w = synth.Workload("decode_small", sh, 3000, 1, 6, True, 2024, n_planted=4, batch=3)
-    n_ctxs = [3000, 2817, 1100]                               # ragged, one just past a block boundary
+@pytest.mark.parametrize("dtype,hq,hkv,n_ctxs", [
+    ("fp32", 8, 2, [3000, 2817, 1100]),                       # ragged, one just past a block boundary
+    ("bf16", 8, 2, [3000, 2817, 1100]),                       # few (sequence, head) pairs: split + combine
+    ("bf16", 32, 8, [2900, 2817, 1100, 700, 3000, 129, 2048, 1]),  # 64 pairs: one workgroup per pair
+])
+def test_decode_step_batch(dtype, hq, hkv, n_ctxs):
+    sh = LayerShape(hq, hkv, 128 if dtype == "bf16" else 64, 128, 4, 128, 256, dtype)
+    w = synth.Workload("decode_small", sh, 3000, 1, 6, True, 2024, n_planted=4, batch=len(n_ctxs))
     nb_cap = 24
     bt = len(n_ctxs)
     ks, vs, reps, qs = [], [], [], []
