@@ -106,6 +106,43 @@ def capture_graph(torch, step_fn, check_tensor, log_name):
         return None
 
 
+PMC_COPY_BYTES = 256 << 20
+
+
+def pmc_pass(torch, B, one_step, info):
+    """One eager pass of the step for a hardware-counter run (rocprofv3 --pmc FETCH_SIZE or
+    WRITE_SIZE), after a plain copy of known size that calibrates the counter."""
+    src = torch.ones(PMC_COPY_BYTES, dtype=torch.uint8, device="cuda:0")
+    dst = torch.zeros_like(src)
+    torch.cuda.synchronize()
+    B.copy_bytes(dst, src)
+    torch.cuda.synchronize()
+    one_step()
+    torch.cuda.synchronize()
+    return dict(info, pmc_pass=True, copy_bytes=PMC_COPY_BYTES)
+
+
+def measured_traffic(workload):
+    """HBM bytes per attention launch from the committed counter runs, or None."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2502_13542_amd",
+                        "traffic_measured.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload)
+    except (OSError, ValueError):
+        return None
+
+
+def traffic_fields(workload):
+    t = measured_traffic(workload)
+    if not t:
+        return {"traffic": None}
+    return {"traffic": t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"],
+            "traffic_detail": dict(t, unit="bytes per attention launch",
+                                   source="rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of bench.py --pmc-pass, "
+                                          "scaled by a 256 MiB copy kernel; summaries under profiles/")}
+
+
 def bench_prefill(args, torch, B, H, synth):
     dev = "cuda:0"
     w = synth.WORKLOADS[args.workload]
@@ -156,6 +193,8 @@ def bench_prefill(args, torch, B, H, synth):
             if events is not None:
                 events[t][1].record()
 
+    if args.pmc_pass:
+        return pmc_pass(torch, B, one_step, {"workload": w.name, "launches": n_win})
     graph = None if args.eager else capture_graph(torch, one_step, out, "prefill")
     run = graph.replay if graph is not None else one_step
     for _ in range(args.warmup):
@@ -189,7 +228,7 @@ def bench_prefill(args, torch, B, H, synth):
                    "windows": n_win, "mean_blocks_selected": sum(n_sel) / max(n_win, 1),
                    "launch": "hip graph replay" if graph is not None else "eager"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, **traffic_fields(w.name),
                      "kernel": "actqkv_retrieval_attention launch (attn_prefill_mfma_kernel + attn_combine_kernel)",
                      "avg_launch_us": attn_ms * 1e3 / n_win,
                      "algorithmic_gflop_per_launch": flops / n_win / 1e9,
@@ -279,6 +318,8 @@ def bench_decode(args, torch, B, H, synth):
                 events[l][1].record()
 
     load_step(0)
+    if args.pmc_pass:
+        return pmc_pass(torch, B, one_step, {"workload": w.name, "launches": L})
     graph = None if args.eager else capture_graph(torch, one_step, out, "decode")
     run = graph.replay if graph is not None else one_step
     for t in range(min(8, steps)):
@@ -320,7 +361,7 @@ def bench_decode(args, torch, B, H, synth):
         "algorithmic_bytes_per_step": byt + score_bytes,
         "hbm_frac_of_step": (byt + score_bytes) / (mean_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                     "frac": achieved / PEAK_HBM_GBS, **traffic_fields(w.name),
                      "kernel": "actqkv_retrieval_attention launch, m = 1 (attn_decode_kernel + attn_decode_combine_kernel)",
                      "avg_launch_us": attn_ms * 1e3 / L, "algorithmic_mb_per_launch": byt / L / 1e6,
                      "timing": "HIP events around every attention launch of one eager step"},
@@ -340,6 +381,8 @@ def main() -> int:
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--decode-layers", type=int, default=0, help="override the layer count (testing)")
+    ap.add_argument("--pmc-pass", action="store_true",
+                    help="one calibration copy and one eager pass, for a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "

@@ -170,6 +170,12 @@ int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, cons
                                const int32_t* n_sel, int k_cap, void* out, float* lse,
                                void* workspace, size_t ws_bytes, void* stream);
 
+/* Measurement aid, not a step of the method: a plain copy of `bytes` bytes (a multiple
+ * of 16; both pointers device memory, 16-byte aligned, not overlapping) done by one
+ * kernel with 16-byte loads and stores.  It reads and writes exactly `bytes` bytes of
+ * HBM, which calibrates the hardware traffic counters against a known size. */
+int actqkv_copy_bytes(void* dst, const void* src, size_t bytes, void* stream);
+
 /* Message of the last error on this thread ("" if none). */
 const char* actqkv_last_error(void);
 

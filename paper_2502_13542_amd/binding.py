@@ -53,6 +53,7 @@ SIGNATURES = {
     "actqkv_select": (_i, [_i, _vp, _i64, _i, _i, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_retrieval_attention": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
                                         _vp, _vp, _vp, _sz, _vp]),
+    "actqkv_copy_bytes": (_i, [_vp, _vp, _sz, _vp]),
     "actqkv_last_error": (ctypes.c_char_p, []),
     "actqkv_version": (_i, []),
 }
@@ -116,6 +117,14 @@ def workspace_bytes(shape: CShape, batch: int, m: int, nb_capacity: int, k_cap: 
     if n == 0:
         raise ActQKVError(-1, last_error())
     return n
+
+
+def copy_bytes(dst, src, stream=None) -> None:
+    """Plain device copy of src into dst by one kernel (traffic-counter calibration)."""
+    n = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != n:
+        raise ActQKVError(-1, "copy_bytes: sizes differ")
+    _check(load_library().actqkv_copy_bytes(_ptr(dst), _ptr(src), n, _stream(stream)))
 
 
 def build_probe(shape: CShape, batch: int, m: int, q_win, stats, update_stats: bool, probe, probe_kv,

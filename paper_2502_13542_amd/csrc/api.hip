@@ -1,10 +1,12 @@
 // C ABI of the library: host-side argument checks, then one launcher per entry point.
 // The checks need no GPU, so every error path can be exercised on a CPU-only machine.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
 
+#include "common.h"
 #include "launch.h"
 
 namespace actqkv {
@@ -161,6 +163,15 @@ int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, co
 
 using namespace actqkv;
 
+namespace actqkv {
+// Grid-stride copy of n 16-byte words (traffic-counter calibration).
+__global__ __launch_bounds__(256) void copy_bytes_kernel(u32x4* __restrict__ dst,
+                                                         const u32x4* __restrict__ src, size_t n) {
+  for (size_t i = size_t(blockIdx.x) * 256 + threadIdx.x; i < n; i += size_t(gridDim.x) * 256)
+    dst[i] = src[i];
+}
+}  // namespace actqkv
+
 extern "C" {
 
 size_t actqkv_stats_floats(const actqkv_shape* shape) {
@@ -284,6 +295,19 @@ int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, cons
   Workspace ws{workspace, ws_bytes};
   return launch_attention(*shape, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx,
                           n_sel, k_cap, out, lse, ws, static_cast<hipStream_t>(stream));
+}
+
+int actqkv_copy_bytes(void* dst, const void* src, size_t bytes, void* stream) {
+  if (dst == nullptr || src == nullptr) return set_error(ACTQKV_EINVAL, "copy_bytes: null pointer");
+  if (bytes % 16 != 0) return set_error(ACTQKV_EINVAL, "copy_bytes: %zu bytes is not a multiple of 16", bytes);
+  if (reinterpret_cast<uintptr_t>(dst) % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0)
+    return set_error(ACTQKV_EALIGN, "copy_bytes: pointers must be 16-byte aligned");
+  if (bytes == 0) return ACTQKV_OK;
+  const size_t n = bytes / 16;
+  const unsigned blocks = unsigned(std::min<size_t>((n + 255) / 256, 256 * 16));
+  hipLaunchKernelGGL(copy_bytes_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n);
+  return hip_status("copy_bytes");
 }
 
 const char* actqkv_last_error(void) { return g_error; }

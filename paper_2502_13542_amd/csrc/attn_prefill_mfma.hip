@@ -142,7 +142,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc_o[i][j] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;   // running max (log2 units), this lane's share of the sum
+  float m_run = -INFINITY;                // running max (log2 units)
 
   const char* kc = reinterpret_cast<const char*>(p.k_cache + size_t(s) * p.seq_stride);
   const char* vc = reinterpret_cast<const char*>(p.v_cache + size_t(s) * p.seq_stride);
@@ -189,7 +189,19 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
   __syncthreads();
 
   const int a_row = perm_row(n);
-  const uint32_t sw = uint32_t(a_row & 15);   // swizzle key of every row this lane reads (K and V^T)
+  // byte offsets of this lane's MFMA A operands inside a K / V^T slot; the 32-row blocks
+  // (kb, db) add a compile-time constant.  K: row perm(n), chunk 2*ks + half, swizzle key
+  // perm(n) % 16.  V^T: row n, chunk c = 4*kb + 2*s2 + half, swizzle key n % 16.
+  uint32_t a_off[8], v_off[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    a_off[c] = uint32_t(a_row) * (kRowPad * 2) + (uint32_t((2 * c + half) ^ (a_row & 15)) << 4);
+    v_off[c] = uint32_t(n) * (kRowPad * 2) + (uint32_t((2 * c + half) ^ (n & 15)) << 4);
+  }
+  const bf16x8 ones = as_bf16x8(u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
+  f32x16 acc_l;                                // every register: the running sum of the lane's query row
+#pragma unroll
+  for (int j = 0; j < 16; ++j) acc_l[j] = 0.f;
   for (int t = t_begin; t < t_end; ++t) {
     const int u = t - t_begin, stage = u & 1;
     if (t + 1 < t_end) fetch_tile(u + 1, stage ^ 1);   // lands while this tile is computed
@@ -203,19 +215,17 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
     const bool visible = hi > lo && lo <= g.w0 + min(wrow0 + 31, p.m - 1);
     const bool masked = lo > kpos0 || hi < kpos0 + kBlock || hi - 1 > g.w0 + wrow0;
     if (visible) {
-      const uint16_t* ks_ = lds + stage * 2 * kTileElems;
-      const uint16_t* vs_ = ks_ + kTileElems;
+      const char* ks_ = lds_b + stage * 2 * kSlotBytes;
+      const char* vs_ = ks_ + kSlotBytes;
       // ---- S^T = K Q^T : 4 groups of 32 keys
       f32x16 acc_s[4];
+      const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb) {
 #pragma unroll
-        for (int j = 0; j < 16; ++j) acc_s[kb][j] = 0.f;
-        const uint16_t* arow = ks_ + (kb * 32 + a_row) * kRowPad;
-#pragma unroll
         for (int ks = 0; ks < kPfD / 16; ++ks) {
-          bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(arow + (((2 * ks + half) ^ sw) << 3)));
-          acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], acc_s[kb], 0, 0, 0);
+          bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(ks_ + a_off[ks] + kb * 32 * (kRowPad * 2)));
+          acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], ks == 0 ? zero16 : acc_s[kb], 0, 0, 0);
         }
       }
       // register i of group kb holds key kpos0 + kb*32 + 16*(i/8) + 8*half + (i%8)
@@ -240,23 +250,22 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
       const float m_safe = m_new == -INFINITY ? 0.f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
       m_run = m_new;
-      float psum = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float pv = __builtin_amdgcn_exp2f(acc_s[kb][i] * p.scale_log2e - m_safe);
-          acc_s[kb][i] = pv;
-          psum += pv;
-        }
-      l_run = l_run * alpha + psum;
+        for (int i = 0; i < 16; ++i)
+          acc_s[kb][i] = __builtin_amdgcn_exp2f(acc_s[kb][i] * p.scale_log2e - m_safe);
       if (!__all(alpha == 1.f)) {
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
           for (int i = 0; i < 16; ++i) acc_o[db][i] *= alpha;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc_l[i] *= alpha;
       }
-      // ---- O^T += V^T P^T
+      // ---- O^T += V^T P^T; the row sums of P come from one more MFMA per 16 keys against an
+      // all-ones A operand (64 additions per tile less on the vector ALU, and exactly the
+      // bf16 probabilities that multiply V are summed)
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb) {
 #pragma unroll
@@ -264,11 +273,10 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
           const bf16x8 pb = pack8(acc_s[kb][8 * s2 + 0], acc_s[kb][8 * s2 + 1], acc_s[kb][8 * s2 + 2],
                                   acc_s[kb][8 * s2 + 3], acc_s[kb][8 * s2 + 4], acc_s[kb][8 * s2 + 5],
                                   acc_s[kb][8 * s2 + 6], acc_s[kb][8 * s2 + 7]);
-          // V^T row db*32 + n (swizzle key n % 16), chunk 4*kb + 2*s2 + half
-          const uint16_t* vrow = vs_ + n * kRowPad + (((4 * kb + 2 * s2 + half) ^ (n & 15)) << 3);
+          acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pb, acc_l, 0, 0, 0);
 #pragma unroll
           for (int db = 0; db < 4; ++db) {
-            bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(vrow + db * 32 * kRowPad));
+            bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(vs_ + v_off[2 * kb + s2] + db * 32 * (kRowPad * 2)));
             acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, acc_o[db], 0, 0, 0);
           }
         }
@@ -279,7 +287,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
   }
 
   // ---- epilogue
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float l_tot = acc_l[0];
   if (p.splits > 1) {
     // The split stores its normalised output as bf16 pairs in the order the registers hold
     // them (register-major, lane-minor: every store is one contiguous 256-byte row), plus its

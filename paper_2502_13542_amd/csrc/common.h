@@ -37,18 +37,22 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 template <typename T> struct Vec;  // T = float: 4 elements; T = uint16_t (bf16 bits): 8 elements
 template <> struct Vec<float> {
   static constexpr int N = 4;
-  __device__ static __forceinline__ void load(const float* p, float (&out)[4]) {
-    f32x4 v = *reinterpret_cast<const f32x4*>(p);
+  typedef f32x4 raw;
+  __device__ static __forceinline__ raw load_raw(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
+  __device__ static __forceinline__ void widen(const raw& v, float (&out)[4]) {
     out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
   }
+  __device__ static __forceinline__ void load(const float* p, float (&out)[4]) { widen(load_raw(p), out); }
 };
 template <> struct Vec<uint16_t> {
   static constexpr int N = 8;
-  __device__ static __forceinline__ void load(const uint16_t* p, float (&out)[8]) {
-    u32x4 v = *reinterpret_cast<const u32x4*>(p);
+  typedef u32x4 raw;
+  __device__ static __forceinline__ raw load_raw(const uint16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
+  __device__ static __forceinline__ void widen(const raw& v, float (&out)[8]) {
     out[0] = bf16_lo(v.x); out[1] = bf16_hi(v.x); out[2] = bf16_lo(v.y); out[3] = bf16_hi(v.y);
     out[4] = bf16_lo(v.z); out[5] = bf16_hi(v.z); out[6] = bf16_lo(v.w); out[7] = bf16_hi(v.w);
   }
+  __device__ static __forceinline__ void load(const uint16_t* p, float (&out)[8]) { widen(load_raw(p), out); }
 };
 
 __device__ __forceinline__ float to_f32(float x) { return x; }

@@ -20,11 +20,16 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline size_t stats_floats(const actqkv_shape& sh) {
   return 4 + 2 * size_t(sh.n_q_heads) * sh.head_dim;
 }
-__host__ __device__ inline size_t probe_a_floats(int m) { return (size_t(m) + 3) / 4 * 4; }
-// per sequence: mean[d], inv_var[d], a[m], partial weighted sums [4 row slices][d]
+// The probe kernels cut the d channels into slabs of 128 bytes of a query row.
+constexpr int kProbeSlabBytes = 128;
+inline int probe_slabs(const actqkv_shape& sh) {
+  int per = kProbeSlabBytes / (sh.dtype == ACTQKV_F32 ? 4 : 2);
+  return (sh.n_q_heads * sh.head_dim + per - 1) / per;
+}
+inline size_t probe_a_floats(int m) { return (size_t(m) + 15) / 16 * 16; }
+// per sequence: partial |phi_j|_1 [slabs][m rounded up to 16]
 inline size_t probe_scratch_floats(const actqkv_shape& sh, int m) {
-  size_t d = size_t(sh.n_q_heads) * sh.head_dim;
-  return 2 * d + probe_a_floats(m) + 4 * d;
+  return size_t(probe_slabs(sh)) * probe_a_floats(m);
 }
 
 // Key-tile splits of the prefill attention.

@@ -1,176 +1,171 @@
 // Activation Bias and probe-Query (Sec. 4.1, Eq. (7)-(9)).
 //
-// Each phase needs a result over the whole window from the phase before, so the
-// call is a chain of four short kernels over the window's queries Q^t [m][d]
-// (a kernel boundary is the cheapest grid-wide dependency on this chip: device-scope
-// fences inside a kernel write back and invalidate the whole L2):
-//   stats     per-channel sums of the window, merged into the running (n, mean, M2) of Eq. (8);
-//   bias      a_j = sum_c (q_jc - mean_c)^2 / var_c = |phi_j|_1 of Eq. (7), one row per token;
-//   reduce    partial sums of a_j q_j over row slices, column slabs in parallel;
-//   finish    probe = sum_j (a_j / sum a) q_j of Eq. (9), its norm and its per-KV-head sum.
+// The statistics of Eq. (8) reduce over the rows of the window and the weights of Eq. (9)
+// over the channels, so the call is a chain of three short kernels over the window's
+// queries Q^t [m][d] (a kernel boundary is the cheapest grid-wide dependency on this chip:
+// device-scope fences inside a kernel write back and invalidate the whole L2):
+//   stats_bias  a workgroup owns a slab of channels for ALL rows: merges the window into the
+//               running (n, mean, M2) of Eq. (8), then sums phi of Eq. (7) over its channels,
+//               one partial |phi_j|_1 per row and slab;
+//   weigh       adds the slabs' partials to a_j = |phi_j|_1, w_j = a_j / sum a, and forms its
+//               slab of probe = sum_j w_j q_j of Eq. (9);
+//   finish      norm of the probe and its per-KV-head sum.
 // All sums are fp32 and are taken in a fixed order, so results are reproducible.
 #include "common.h"
 #include "launch.h"
 
 namespace actqkv {
 
-constexpr int kStatsBatch = 8;   // 16-byte loads a thread keeps in flight
-constexpr int kStatsColLanes = 8, kStatsRowLanes = 32;
+constexpr int kColLanes = 8;      // 16-byte column lanes of a slab
+constexpr int kRowsPerThread = 16;   // 16-byte loads a thread keeps in flight
+constexpr int kStatsRowLanes = 32;
+constexpr int kStatsRowsPerPass = kStatsRowLanes * kRowsPerThread;
 
-// Running statistics of Eq. (8).  grid (column slabs of 8*V channels, batch); 256 threads
-// = 8 column lanes x 32 row lanes.  A workgroup owns its channels for ALL rows of the
-// window, so it can merge them into the running (mean, M2) itself (pairwise update) and no
-// second pass over partial sums is needed.  Sums are taken of (q - shift), shift = the old
-// mean (or the window's first query when there is no history), which keeps the squares
-// free of cancellation.  The count n is published by the next kernel of the chain (every
-// workgroup here reads the old one).
+// grid (column slabs of 8*V channels, batch); 256 threads = 8 column lanes x 32 row lanes;
+// row lane rl takes rows rl*16 .. rl*16+15 of every pass of 512 rows.
+// Pass 1 (update != 0): sums of (q - shift), shift = the old mean (or the window's first
+// query when there is no history), which keeps the squares free of cancellation; pairwise
+// merge into the running mean and M2.  The count n is published by the next kernel of the
+// chain (every workgroup here reads the old one).
+// Pass 2 (m > 1): apart[slab][j] = sum over the slab's channels of (q_jc - mean_c)^2 / var_c.
+// A window of at most 512 rows stays in registers between the passes.
 template <typename T>
-__global__ __launch_bounds__(256) void probe_stats_kernel(const T* __restrict__ q_win,
-                                                          float* __restrict__ stats,
-                                                          float* __restrict__ scratch, int m, int d,
-                                                          float eps, size_t stats_stride,
-                                                          size_t scratch_stride) {
+__global__ __launch_bounds__(256) void probe_stats_bias_kernel(const T* __restrict__ q_win,
+                                                               float* __restrict__ stats,
+                                                               float* __restrict__ scratch, int update,
+                                                               int m, int m_pad, int d, float eps,
+                                                               size_t stats_stride,
+                                                               size_t scratch_stride) {
   constexpr int V = Vec<T>::N;
-  constexpr int SLAB = kStatsColLanes * V;
+  constexpr int SLAB = kColLanes * V;
+  typedef typename Vec<T>::raw raw_t;
   __shared__ float red[2][kStatsRowLanes][SLAB];
+  __shared__ float mu_lds[SLAB], iv_lds[SLAB];
   const int s = blockIdx.y;
   const T* q = q_win + size_t(s) * m * d;
   float* st = stats + size_t(s) * stats_stride;
-  float* sc = scratch + size_t(s) * scratch_stride;
-  const int cl = threadIdx.x % kStatsColLanes, rl = threadIdx.x / kStatsColLanes;
+  float* apart = scratch + size_t(s) * scratch_stride + size_t(blockIdx.x) * m_pad;
+  const int cl = threadIdx.x % kColLanes, rl = threadIdx.x / kColLanes;
   const int ch0 = blockIdx.x * SLAB + cl * V;
+  const bool col_ok = ch0 < d;
   const float n_old = st[0];
+  const int n_pass = (m + kStatsRowsPerPass - 1) / kStatsRowsPerPass;
 
-  float c[V], s1[V], s2[V];
+  raw_t x[kRowsPerThread];
+  auto load_pass = [&](int pass) {
 #pragma unroll
-  for (int v = 0; v < V; ++v) c[v] = s1[v] = s2[v] = 0.f;
-  if (ch0 < d) {
-    if (n_old > 0.f) {
-#pragma unroll
-      for (int v = 0; v < V; ++v) c[v] = st[4 + ch0 + v];
-    } else {
-      Vec<T>::load(q + ch0, c);
+    for (int i = 0; i < kRowsPerThread; ++i) {   // all loads first: they overlap
+      const int r = pass * kStatsRowsPerPass + rl * kRowsPerThread + i;
+      x[i] = Vec<T>::load_raw(q + size_t(r < m ? r : 0) * d + (col_ok ? ch0 : 0));
     }
-    for (int r0 = rl; r0 < m; r0 += kStatsRowLanes * kStatsBatch) {
-      float x[kStatsBatch][V];
+  };
+  load_pass(0);
+
+  if (update) {
+    float c[V], s1[V], s2[V];
 #pragma unroll
-      for (int i = 0; i < kStatsBatch; ++i) {   // all loads first: they overlap
-        const int r = r0 + kStatsRowLanes * i;
-        Vec<T>::load(q + size_t(r < m ? r : 0) * d + ch0, x[i]);
+    for (int v = 0; v < V; ++v) c[v] = s1[v] = s2[v] = 0.f;
+    if (col_ok) {
+      if (n_old > 0.f) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) c[v] = st[4 + ch0 + v];
+      } else {
+        Vec<T>::load(q + ch0, c);
       }
+    }
+    for (int pass = 0; pass < n_pass; ++pass) {
+      if (pass > 0) load_pass(pass);
 #pragma unroll
-      for (int i = 0; i < kStatsBatch; ++i) {
-        if (r0 + kStatsRowLanes * i < m) {
+      for (int i = 0; i < kRowsPerThread; ++i) {
+        if (pass * kStatsRowsPerPass + rl * kRowsPerThread + i < m) {
+          float f[V];
+          Vec<T>::widen(x[i], f);
 #pragma unroll
           for (int v = 0; v < V; ++v) {
-            float t = x[i][v] - c[v];
+            float t = f[v] - c[v];
             s1[v] += t;
             s2[v] += t * t;
           }
         }
       }
     }
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      red[0][rl][cl * V + v] = s1[v];
+      red[1][rl][cl * V + v] = s2[v];
+    }
+    __syncthreads();
   }
+  {
+    const int col = threadIdx.x, ch = blockIdx.x * SLAB + col;
+    if (col < SLAB && ch >= d) mu_lds[col] = iv_lds[col] = 0.f;
+    if (col < SLAB && ch < d) {
+      float mean, m2, n_new;
+      if (update) {
+        float t1 = 0.f, t2 = 0.f;
+#pragma unroll
+        for (int k = 0; k < kStatsRowLanes; ++k) {
+          t1 += red[0][k][col];
+          t2 += red[1][k][col];
+        }
+        const float nb = float(m);
+        n_new = n_old + nb;
+        const float mean_a = st[4 + ch];
+        const float shift = n_old > 0.f ? mean_a : to_f32(q[ch]);
+        const float mean_b = shift + t1 / nb;
+        const float m2_b = fmaxf(t2 - t1 * t1 / nb, 0.f);
+        const float delta = mean_b - mean_a;
+        mean = n_old > 0.f ? mean_a + delta * (nb / n_new) : mean_b;
+        m2 = n_old > 0.f ? st[4 + d + ch] + m2_b + delta * delta * (n_old * nb / n_new) : m2_b;
+        st[4 + ch] = mean;
+        st[4 + d + ch] = m2;
+      } else {
+        n_new = n_old;
+        mean = st[4 + ch];
+        m2 = st[4 + d + ch];
+      }
+      const float var = n_new > 1.f ? m2 / (n_new - 1.f) : 0.f;
+      mu_lds[col] = mean;
+      iv_lds[col] = 1.f / fmaxf(var, eps);
+    }
+  }
+  if (m == 1) return;   // a single token is its own probe: no weights needed
+  __syncthreads();
+
+  float mu[V], iv[V];
 #pragma unroll
   for (int v = 0; v < V; ++v) {
-    red[0][rl][cl * V + v] = s1[v];
-    red[1][rl][cl * V + v] = s2[v];
+    mu[v] = mu_lds[cl * V + v];
+    iv[v] = iv_lds[cl * V + v];
   }
-  __syncthreads();
-  const int col = threadIdx.x, ch = blockIdx.x * SLAB + col;
-  if (col < SLAB && ch < d) {
-    float t1 = 0.f, t2 = 0.f;
+  for (int pass = 0; pass < n_pass; ++pass) {
+    if (n_pass > 1) load_pass(pass);
+    const int r0 = pass * kStatsRowsPerPass + rl * kRowsPerThread;
+    float a[kRowsPerThread];
 #pragma unroll
-    for (int k = 0; k < kStatsRowLanes; ++k) {
-      t1 += red[0][k][col];
-      t2 += red[1][k][col];
+    for (int i = 0; i < kRowsPerThread; ++i) {
+      float f[V];
+      Vec<T>::widen(x[i], f);
+      float t = 0.f;
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        float e = f[v] - mu[v];
+        t += e * e * iv[v];
+      }
+      // the 8 column lanes of a row are neighbouring lanes of one wave
+      t += __shfl_xor(t, 1, 64);
+      t += __shfl_xor(t, 2, 64);
+      t += __shfl_xor(t, 4, 64);
+      a[i] = r0 + i < m ? t : 0.f;
     }
-    const float nb = float(m), n_new = n_old + nb;
-    const float mean_a = st[4 + ch];
-    const float shift = n_old > 0.f ? mean_a : to_f32(q[ch]);
-    const float mean_b = shift + t1 / nb;
-    const float m2_b = fmaxf(t2 - t1 * t1 / nb, 0.f);
-    const float delta = mean_b - mean_a;
-    const float mean = n_old > 0.f ? mean_a + delta * (nb / n_new) : mean_b;
-    const float m2 = n_old > 0.f ? st[4 + d + ch] + m2_b + delta * delta * (n_old * nb / n_new) : m2_b;
-    st[4 + ch] = mean;
-    st[4 + d + ch] = m2;
-    const float var = n_new > 1.f ? m2 / (n_new - 1.f) : 0.f;
-    sc[ch] = mean;
-    sc[d + ch] = 1.f / fmaxf(var, eps);
-  }
-}
-
-// Statistics used as they are: only mean and 1/var are put where the next phase reads them.
-__global__ void probe_prepare_kernel(const float* __restrict__ stats, float* __restrict__ scratch,
-                                     int d, float eps, size_t stats_stride, size_t scratch_stride) {
-  const int s = blockIdx.y;
-  const float* st = stats + size_t(s) * stats_stride;
-  float* sc = scratch + size_t(s) * scratch_stride;
-  const float n = st[0];
-  int ch = blockIdx.x * blockDim.x + threadIdx.x;
-  if (ch < d) {
-    float var = n > 1.f ? st[4 + d + ch] / (n - 1.f) : 0.f;
-    sc[ch] = st[4 + ch];
-    sc[d + ch] = 1.f / fmaxf(var, eps);
-  }
-}
-
-constexpr int kBiasRows = 4;
-
-template <typename T>
-__global__ __launch_bounds__(256) void probe_bias_kernel(const T* __restrict__ q_win,
-                                                         float* __restrict__ scratch,
-                                                         float* __restrict__ stats, int add_count, int m,
-                                                         int d, size_t scratch_stride,
-                                                         size_t stats_stride) {
-  constexpr int V = Vec<T>::N;
-  __shared__ float red[4][kBiasRows];
-  const int s = blockIdx.y;
-  const T* q = q_win + size_t(s) * m * d;
-  float* sc = scratch + size_t(s) * scratch_stride;
-  const float* mean = sc;
-  const float* inv = sc + d;
-  float* a = sc + 2 * size_t(d);
-  const int r0 = blockIdx.x * kBiasRows;
-  if (add_count && blockIdx.x == 0 && threadIdx.x == 0) stats[size_t(s) * stats_stride] += float(m);
-  float acc[kBiasRows];
+    if (cl == 0 && r0 < m_pad) {
 #pragma unroll
-  for (int i = 0; i < kBiasRows; ++i) acc[i] = 0.f;
-  for (int ch = threadIdx.x * V; ch < d; ch += 256 * V) {
-    float mu[V], iv[V];
-#pragma unroll
-    for (int v = 0; v < V; v += 4) {
-      f32x4 a4 = *reinterpret_cast<const f32x4*>(mean + ch + v);
-      f32x4 b4 = *reinterpret_cast<const f32x4*>(inv + ch + v);
-      mu[v] = a4.x; mu[v + 1] = a4.y; mu[v + 2] = a4.z; mu[v + 3] = a4.w;
-      iv[v] = b4.x; iv[v + 1] = b4.y; iv[v + 2] = b4.z; iv[v + 3] = b4.w;
-    }
-    float x[kBiasRows][V];
-#pragma unroll
-    for (int i = 0; i < kBiasRows; ++i)          // all loads first: they overlap
-      Vec<T>::load(q + size_t(r0 + i < m ? r0 + i : r0) * d + ch, x[i]);
-#pragma unroll
-    for (int i = 0; i < kBiasRows; ++i) {
-      if (r0 + i < m) {
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-          float t = x[i][v] - mu[v];
-          acc[i] += t * t * iv[v];
-        }
+      for (int i = 0; i < kRowsPerThread; i += 4) {
+        f32x4 o = {a[i], a[i + 1], a[i + 2], a[i + 3]};
+        *reinterpret_cast<f32x4*>(apart + r0 + i) = o;
       }
     }
   }
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-#pragma unroll
-  for (int i = 0; i < kBiasRows; ++i) {
-    float t = wave_sum(acc[i]);
-    if (lane == 0) red[w][i] = t;
-  }
-  __syncthreads();
-  if (threadIdx.x < kBiasRows && r0 + threadIdx.x < m)
-    a[r0 + threadIdx.x] = red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] +
-                          red[3][threadIdx.x];
 }
 
 // probe_kv and the norm of the probe; run by one workgroup that sees the whole probe.
@@ -190,92 +185,120 @@ __device__ __forceinline__ void probe_finish(const float* probe, float* probe_kv
   }
 }
 
-constexpr int kReduceRowSplits = 4;
+constexpr int kWeighRowLanes = 64;
+constexpr int kWeighRows = 8;    // rows a thread takes per pass
+constexpr int kWeighRowsPerPass = kWeighRowLanes * kWeighRows;
+constexpr int kWeighSlabBatch = 16;
 
-// grid (column slabs of 16*V channels, kReduceRowSplits, batch); 256 threads = 16 column
-// lanes x 16 row lanes.  Partial weighted sums sum_j w_j q_j over a slice of the rows.
+// grid (column slabs of 8*V channels, batch); 512 threads = 8 column lanes x 64 row lanes.
+// Every workgroup adds the slabs' partials up to a_j (slab order), turns them into the
+// weights of Eq. (9) and sums w_j q_j over all rows for its channels.  The queries of the
+// first pass are requested before the partials, so both are in flight together.
 template <typename T>
-__global__ __launch_bounds__(256) void probe_reduce_kernel(const T* __restrict__ q_win,
-                                                           float* __restrict__ scratch,
-                                                           float* __restrict__ weights_out, int m,
-                                                           int d, size_t scratch_stride) {
+__global__ __launch_bounds__(512) void probe_weigh_kernel(const T* __restrict__ q_win,
+                                                          const float* __restrict__ scratch,
+                                                          float* __restrict__ stats, int add_count,
+                                                          float* __restrict__ probe_out,
+                                                          float* __restrict__ weights_out, int m,
+                                                          int m_pad, int n_slabs, int d,
+                                                          size_t scratch_stride, size_t stats_stride) {
   constexpr int V = Vec<T>::N;
+  constexpr int SLAB = kColLanes * V;
+  typedef typename Vec<T>::raw raw_t;
   __shared__ float red[32];
-  __shared__ float buf[16][16 * V];
-  const int s = blockIdx.z;
+  __shared__ float w_lds[kMaxWindow];
+  __shared__ float buf[8][SLAB];
+  const int s = blockIdx.y;
   const T* q = q_win + size_t(s) * m * d;
-  float* sc = scratch + size_t(s) * scratch_stride;
-  const float* a = sc + 2 * size_t(d);
-  float* part = sc + 2 * size_t(d) + probe_a_floats(m);   // [kReduceRowSplits][d]
+  const float* apart = scratch + size_t(s) * scratch_stride;
+  const int cl = threadIdx.x % kColLanes, rl = threadIdx.x / kColLanes;
+  const int ch0 = blockIdx.x * SLAB + cl * V;
+  const bool col_ok = ch0 < d;
+  if (add_count && blockIdx.x == 0 && threadIdx.x == 0) stats[size_t(s) * stats_stride] += float(m);
+
+  raw_t x[kWeighRows];
+  auto load_pass = [&](int pass) {
+#pragma unroll
+    for (int i = 0; i < kWeighRows; ++i) {
+      const int r = pass * kWeighRowsPerPass + rl * kWeighRows + i;
+      x[i] = Vec<T>::load_raw(q + size_t(r < m ? r : 0) * d + (col_ok ? ch0 : 0));
+    }
+  };
+  load_pass(0);
 
   float tsum = 0.f;
-  for (int j = threadIdx.x; j < m; j += 256) tsum += a[j];
-  const float total = block_sum(tsum, red);          // |Phi|_1
+  for (int j = threadIdx.x; j < m; j += 512) {
+    float t = 0.f;
+    for (int s0 = 0; s0 < n_slabs; s0 += kWeighSlabBatch) {
+      float p[kWeighSlabBatch];
+#pragma unroll
+      for (int i = 0; i < kWeighSlabBatch; ++i)   // all loads first: they overlap
+        p[i] = apart[size_t(s0 + i < n_slabs ? s0 + i : s0) * m_pad + j];
+#pragma unroll
+      for (int i = 0; i < kWeighSlabBatch; ++i) t += s0 + i < n_slabs ? p[i] : 0.f;
+    }
+    w_lds[j] = t;
+    tsum += t;
+  }
+  const float total = block_sum(tsum, red);          // |Phi|_1; orders the LDS writes as well
   const float inv_total = total > 0.f ? 1.f / total : 0.f;
   const float uniform = 1.f / float(m);
 
-  const int cl = threadIdx.x & 15, rl = threadIdx.x >> 4;
-  const int ch0 = (blockIdx.x * 16 + cl) * V;
-  const int rows_per = (m + kReduceRowSplits - 1) / kReduceRowSplits;
-  const int r_begin = blockIdx.y * rows_per, r_end = min(m, r_begin + rows_per);
   float acc[V];
 #pragma unroll
   for (int v = 0; v < V; ++v) acc[v] = 0.f;
-  if (ch0 < d) {
-    for (int j0 = r_begin + rl; j0 < r_end; j0 += 16 * 8) {
-      float x[8][V], w[8];
+  const int n_pass = (m + kWeighRowsPerPass - 1) / kWeighRowsPerPass;
+  for (int pass = 0; pass < n_pass; ++pass) {
+    if (pass > 0) load_pass(pass);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {                    // 8 independent loads in flight
-        const int j = j0 + 16 * i;
-        const int jj = j < r_end ? j : r_begin;
-        Vec<T>::load(q + size_t(jj) * d + ch0, x[i]);
-        w[i] = j < r_end ? (total > 0.f ? a[jj] * inv_total : uniform) : 0.f;
-      }
+    for (int i = 0; i < kWeighRows; ++i) {
+      const int r = pass * kWeighRowsPerPass + rl * kWeighRows + i;
+      const float w = r < m ? (total > 0.f ? w_lds[r] * inv_total : uniform) : 0.f;
+      float f[V];
+      Vec<T>::widen(x[i], f);
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int v = 0; v < V; ++v) acc[v] += w[i] * x[i][v];
+      for (int v = 0; v < V; ++v) acc[v] += w * f[v];
     }
   }
+  // the 8 row lanes of a wave first, then the 8 waves through LDS
 #pragma unroll
-  for (int v = 0; v < V; ++v) buf[rl][cl * V + v] = acc[v];
+  for (int v = 0; v < V; ++v) {
+    acc[v] += __shfl_xor(acc[v], 8, 64);
+    acc[v] += __shfl_xor(acc[v], 16, 64);
+    acc[v] += __shfl_xor(acc[v], 32, 64);
+  }
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  if (lane < kColLanes) {
+#pragma unroll
+    for (int v = 0; v < V; ++v) buf[wv][cl * V + v] = acc[v];
+  }
   __syncthreads();
-  if (threadIdx.x < 16 * V) {
-    int ch = blockIdx.x * 16 * V + threadIdx.x;
+  if (threadIdx.x < SLAB) {
+    const int ch = blockIdx.x * SLAB + threadIdx.x;
     if (ch < d) {
       float t = 0.f;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) t += buf[i][threadIdx.x];
-      part[size_t(blockIdx.y) * d + ch] = t;
+      for (int i = 0; i < 8; ++i) t += buf[i][threadIdx.x];
+      probe_out[size_t(s) * d + ch] = t;
     }
   }
-  if (blockIdx.x == 0 && blockIdx.y == 0 && weights_out != nullptr) {
-    for (int j = threadIdx.x; j < m; j += 256)
-      weights_out[size_t(s) * m + j] = total > 0.f ? a[j] * inv_total : uniform;
+  if (blockIdx.x == 0 && weights_out != nullptr) {
+    for (int j = threadIdx.x; j < m; j += 512)
+      weights_out[size_t(s) * m + j] = total > 0.f ? w_lds[j] * inv_total : uniform;
   }
 }
 
-// One workgroup per sequence: adds the row slices up in a fixed order and finishes the probe.
-__global__ __launch_bounds__(1024) void probe_finish_kernel(const float* __restrict__ scratch,
-                                                            float* __restrict__ probe_out,
+// One workgroup per sequence that sees the whole probe.
+__global__ __launch_bounds__(1024) void probe_finish_kernel(const float* __restrict__ probe,
                                                             float* __restrict__ probe_kv_out,
-                                                            float* __restrict__ probe_norm_out, int m,
-                                                            int n_q_heads, int n_kv_heads, int head_dim,
-                                                            size_t scratch_stride) {
+                                                            float* __restrict__ probe_norm_out,
+                                                            int n_q_heads, int n_kv_heads,
+                                                            int head_dim) {
   __shared__ float red[32];
-  const int d = n_q_heads * head_dim;
   const int s = blockIdx.x;
-  const float* part = scratch + size_t(s) * scratch_stride + 2 * size_t(d) + probe_a_floats(m);
-  float* probe = probe_out + size_t(s) * d;
-  for (int ch = threadIdx.x * 4; ch < d; ch += 1024 * 4) {
-    f32x4 t = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < kReduceRowSplits; ++i) t += *reinterpret_cast<const f32x4*>(part + size_t(i) * d + ch);
-    *reinterpret_cast<f32x4*>(probe + ch) = t;
-  }
-  __syncthreads();
-  probe_finish(probe, probe_kv_out + size_t(s) * n_kv_heads * head_dim, probe_norm_out + s,
-               n_q_heads, n_kv_heads, head_dim, red);
+  probe_finish(probe + size_t(s) * n_q_heads * head_dim,
+               probe_kv_out + size_t(s) * n_kv_heads * head_dim, probe_norm_out + s, n_q_heads,
+               n_kv_heads, head_dim, red);
 }
 
 // A window of one token (decode): Eq. (9) has a single weight, 1, so the probe is the query.
@@ -333,15 +356,13 @@ static int launch_probe_t(const actqkv_shape& sh, int batch, int m, const T* q_w
   const float eps = sh.var_eps > 0.f ? sh.var_eps : 1e-12f;
   const size_t stats_stride = stats_floats(sh);
   const size_t scratch_stride = probe_scratch_floats(sh, m);
+  const int m_pad = int(probe_a_floats(m));
+  const int n_slabs = probe_slabs(sh);
+  static_assert(kColLanes * 8 == kProbeSlabBytes / 2 && kColLanes * 4 == kProbeSlabBytes / 4, "slab width");
   float* scratch = ws.scratch_f32();
-  if (update_stats) {
-    dim3 grid((d + kStatsColLanes * V - 1) / (kStatsColLanes * V), batch);
-    hipLaunchKernelGGL(probe_stats_kernel<T>, grid, dim3(256), 0, stream, q_win, stats, scratch, m, d,
-                       eps, stats_stride, scratch_stride);
-  } else if (m > 1) {
-    dim3 grid((d + 255) / 256, batch);
-    hipLaunchKernelGGL(probe_prepare_kernel, grid, dim3(256), 0, stream, stats, scratch, d, eps,
-                       stats_stride, scratch_stride);
+  if (update_stats || m > 1) {
+    hipLaunchKernelGGL(probe_stats_bias_kernel<T>, dim3(n_slabs, batch), dim3(256), 0, stream, q_win,
+                       stats, scratch, update_stats, m, m_pad, d, eps, stats_stride, scratch_stride);
   }
   if (m == 1) {
     hipLaunchKernelGGL(probe_identity_kernel<T>, dim3(batch), dim3(1024), size_t(d) * sizeof(float),
@@ -350,19 +371,12 @@ static int launch_probe_t(const actqkv_shape& sh, int batch, int m, const T* q_w
                        sh.n_kv_heads, sh.head_dim);
     return hip_status("probe");
   }
-  {
-    dim3 grid((m + kBiasRows - 1) / kBiasRows, batch);
-    hipLaunchKernelGGL(probe_bias_kernel<T>, grid, dim3(256), 0, stream, q_win, scratch, stats,
-                       update_stats, m, d, scratch_stride, stats_stride);
-  }
-  {
-    dim3 grid((d + 16 * V - 1) / (16 * V), kReduceRowSplits, batch);
-    hipLaunchKernelGGL(probe_reduce_kernel<T>, grid, dim3(256), 0, stream, q_win, scratch, weights, m,
-                       d, scratch_stride);
-    hipLaunchKernelGGL(probe_finish_kernel, dim3(batch), dim3(1024), 0, stream, scratch, probe,
-                       probe_kv, probe_norm, m, sh.n_q_heads, sh.n_kv_heads, sh.head_dim,
-                       scratch_stride);
-  }
+  hipLaunchKernelGGL(probe_weigh_kernel<T>, dim3(n_slabs, batch), dim3(512), 0, stream, q_win, scratch,
+                     stats, update_stats, probe, weights, m, m_pad, n_slabs, d, scratch_stride,
+                     stats_stride);
+  hipLaunchKernelGGL(probe_finish_kernel, dim3(batch), dim3(1024), 0, stream, probe, probe_kv,
+                     probe_norm, sh.n_q_heads, sh.n_kv_heads, sh.head_dim);
+  (void)V;
   return hip_status("probe");
 }
 
