@@ -229,7 +229,7 @@ def bench_prefill(args, torch, B, H, synth):
                    "launch": "hip graph replay" if graph is not None else "eager"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, **traffic_fields(w.name),
-                     "kernel": "actqkv_retrieval_attention launch (attn_prefill_mfma_kernel + attn_combine_kernel)",
+                     "kernel": "actqkv_retrieval_attention launch (attn_prefill_mfma_kernel)",
                      "avg_launch_us": attn_ms * 1e3 / n_win,
                      "algorithmic_gflop_per_launch": flops / n_win / 1e9,
                      "timing": "HIP events around every attention launch of one eager pass of the step"},
@@ -362,7 +362,7 @@ def bench_decode(args, torch, B, H, synth):
         "hbm_frac_of_step": (byt + score_bytes) / (mean_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBS, **traffic_fields(w.name),
-                     "kernel": "actqkv_retrieval_attention launch, m = 1 (attn_decode_kernel + attn_decode_combine_kernel)",
+                     "kernel": "actqkv_retrieval_attention launch, m = 1 (attn_decode_kernel)",
                      "avg_launch_us": attn_ms * 1e3 / L, "algorithmic_mb_per_launch": byt / L / 1e6,
                      "timing": "HIP events around every attention launch of one eager step"},
     }

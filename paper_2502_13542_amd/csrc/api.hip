@@ -106,7 +106,8 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
                                   const void* k_cache, const void* v_cache, int64_t seq_stride,
                                   int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
                                   const int32_t* n_sel, int k_cap, void* out, float* lse, int splits,
-                                  float* scratch, float scale, hipStream_t stream);
+                                  float* scratch, unsigned int* counters, float scale,
+                                  hipStream_t stream);
 
 // Enough key splits to give every compute unit a workgroup, never more than 8.
 int prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap) {
@@ -121,8 +122,8 @@ size_t decode_mfma_scratch_floats(const actqkv_shape& sh, int batch, int k_cap);
 int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* q, const void* k_cache,
                                  const void* v_cache, int64_t seq_stride, int nb_capacity,
                                  const int32_t* n_ctx, const int32_t* idx, const int32_t* n_sel,
-                                 int k_cap, void* out, float* lse, float* scratch, float scale,
-                                 hipStream_t stream);
+                                 int k_cap, void* out, float* lse, float* scratch,
+                                 unsigned int* counters, float scale, hipStream_t stream);
 
 size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap) {
   (void)nb_capacity;
@@ -149,12 +150,13 @@ int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, co
   const float scale = sh.softmax_scale > 0.f ? sh.softmax_scale : 1.f / std::sqrt(float(sh.head_dim));
   if (decode_mfma_supported(sh, m))
     return launch_attention_decode_mfma(sh, batch, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx,
-                                        idx, n_sel, k_cap, out, lse, ws.scratch_f32(), scale, stream);
+                                        idx, n_sel, k_cap, out, lse, ws.scratch_f32(), ws.counters(), scale,
+                                        stream);
   if (prefill_mfma_supported(sh, m))
     return launch_attention_prefill_mfma(sh, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity,
                                          n_ctx, idx, n_sel, k_cap, out, lse,
-                                         prefill_splits(sh, batch, m, k_cap), ws.scratch_f32(), scale,
-                                         stream);
+                                         prefill_splits(sh, batch, m, k_cap), ws.scratch_f32(),
+                                         ws.counters(), scale, stream);
   return launch_attention_rows(sh, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx,
                                n_sel, k_cap, out, lse, scale, stream);
 }

@@ -15,7 +15,7 @@
 // layout of the second product; no cross-lane traffic is needed apart from two shuffles
 // for the row maximum.  The 8 wavefronts of a workgroup merge their (max, sum, O) through
 // LDS.  If one workgroup covers a whole (sequence, KV head) it writes the output itself;
-// otherwise the workgroups write partials and attn_decode_combine_kernel merges them.
+// otherwise the workgroups store partials and the one that finishes last merges them.
 #include "common.h"
 #include "launch.h"
 
@@ -36,7 +36,8 @@ struct DcParams {
   int k_cap;
   uint16_t* out;
   float* lse;
-  float* part;  // [batch][Hk][n_wg][G][D + 2]
+  uint32_t* part;           // [batch][Hk][n_wg][G][D + 2] fp32 bits
+  unsigned int* counters;   // one ticket counter per (sequence, KV head), zero between launches
   int n_q_heads, n_kv_heads, n_init, n_local;
   int n_wg;     // workgroups per (sequence, KV head); 1: the workgroup writes the output itself
   float scale_log2e;
@@ -176,7 +177,8 @@ __global__ __launch_bounds__(kDcMaxWaves * 64) void attn_decode_kernel(DcParams 
       *reinterpret_cast<f32x4*>(&red_o[(wave * group + n) * kDcD + 16 * dg + 4 * kq]) = acc_o[dg];
   }
   __syncthreads();
-  float* part = p.part + ((size_t(s) * p.n_kv_heads + hk) * p.n_wg + wg) * group * (kDcD + 2);
+  uint32_t* pair_part = p.part + (size_t(s) * p.n_kv_heads + hk) * p.n_wg * group * (kDcD + 2);
+  uint32_t* part = pair_part + size_t(wg) * group * (kDcD + 2);
   for (int e = threadIdx.x; e < group * kDcD; e += blockDim.x) {
     const int h = e / kDcD, d = e - h * kDcD;
     float mm = -INFINITY;
@@ -194,51 +196,53 @@ __global__ __launch_bounds__(kDcMaxWaves * 64) void attn_decode_kernel(DcParams 
       if (p.lse != nullptr && d == 0)
         p.lse[size_t(s) * p.n_q_heads + head] = (mm + log2f(l)) * 0.6931471805599453f;
     } else {
-      part[size_t(h) * (kDcD + 2) + d] = o;
+      st_agent(part + size_t(h) * (kDcD + 2) + d, __float_as_uint(o));
       if (d == 0) {
-        part[size_t(h) * (kDcD + 2) + kDcD] = mm;
-        part[size_t(h) * (kDcD + 2) + kDcD + 1] = l;
+        st_agent(part + size_t(h) * (kDcD + 2) + kDcD, __float_as_uint(mm));
+        st_agent(part + size_t(h) * (kDcD + 2) + kDcD + 1, __float_as_uint(l));
       }
     }
   }
-}
+  if (p.n_wg == 1) return;
+  __shared__ int last_flag;
+  if (!last_of_group(p.counters + size_t(s) * p.n_kv_heads + hk, unsigned(p.n_wg), &last_flag)) return;
 
-// out[s][head][:] = sum_w 2^(m_w - M) O_w / sum_w 2^(m_w - M) l_w over the n_wg partials.
-// One workgroup of 128 threads per (sequence, head); thread = channel.
-__global__ __launch_bounds__(kDcD) void attn_decode_combine_kernel(DcParams p) {
-  const int head = blockIdx.x, s = blockIdx.y, d = threadIdx.x;
-  const int group = p.n_q_heads / p.n_kv_heads;
-  const int hk = head / group, h = head - hk * group;
-  const float* part = p.part + (size_t(s) * p.n_kv_heads + hk) * p.n_wg * group * (kDcD + 2) +
-                      size_t(h) * (kDcD + 2);
+  // ---- the workgroup that finished last merges the partials, in workgroup order:
+  //   out[head][:] = sum_w 2^(m_w - M) O_w / sum_w 2^(m_w - M) l_w
   const size_t stride = size_t(group) * (kDcD + 2);
-  constexpr int kB = 16;
-  float mm = -INFINITY, l = 0.f, o = 0.f;
-  for (int w0 = 0; w0 < p.n_wg; w0 += kB) {
-    float pm[kB], pl[kB], po[kB];
+  constexpr int kB = 8;
+  for (int e = threadIdx.x; e < group * kDcD; e += blockDim.x) {
+    const int h = e / kDcD, d = e - h * kDcD;
+    const uint32_t* src = pair_part + size_t(h) * (kDcD + 2);
+    float mm = -INFINITY, l = 0.f, o = 0.f;
+    for (int w0 = 0; w0 < p.n_wg; w0 += kB) {
+      uint32_t pm[kB], pl[kB], po[kB];
 #pragma unroll
-    for (int i = 0; i < kB; ++i) {               // all loads first: they overlap
-      const int w = w0 + i < p.n_wg ? w0 + i : w0;
-      pm[i] = part[w * stride + kDcD];
-      pl[i] = part[w * stride + kDcD + 1];
-      po[i] = part[w * stride + d];
-    }
+      for (int i = 0; i < kB; ++i) {               // all loads first: they overlap
+        const int w = w0 + i < p.n_wg ? w0 + i : w0;
+        pm[i] = ld_agent(src + w * stride + kDcD);
+        pl[i] = ld_agent(src + w * stride + kDcD + 1);
+        po[i] = ld_agent(src + w * stride + d);
+      }
 #pragma unroll
-    for (int i = 0; i < kB; ++i) {
-      if (w0 + i < p.n_wg) {
-        const float m_new = fmaxf(mm, pm[i]);
-        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-        const float wa = __builtin_amdgcn_exp2f(mm - m_safe), wb = __builtin_amdgcn_exp2f(pm[i] - m_safe);
-        l = l * wa + pl[i] * wb;
-        o = o * wa + po[i] * wb;
-        mm = m_new;
+      for (int i = 0; i < kB; ++i) {
+        if (w0 + i < p.n_wg) {
+          const float pmf = __uint_as_float(pm[i]);
+          const float m_new = fmaxf(mm, pmf);
+          const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+          const float wa = __builtin_amdgcn_exp2f(mm - m_safe), wb = __builtin_amdgcn_exp2f(pmf - m_safe);
+          l = l * wa + __uint_as_float(pl[i]) * wb;
+          o = o * wa + __uint_as_float(po[i]) * wb;
+          mm = m_new;
+        }
       }
     }
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    const int head = hk * group + h;
+    p.out[(size_t(s) * p.n_q_heads + head) * kDcD + d] = uint16_t(f32_to_bf16_bits(o * inv));
+    if (p.lse != nullptr && d == 0)
+      p.lse[size_t(s) * p.n_q_heads + head] = (mm + log2f(l)) * 0.6931471805599453f;
   }
-  const float inv = l > 0.f ? 1.f / l : 0.f;
-  p.out[(size_t(s) * p.n_q_heads + head) * kDcD + d] = uint16_t(f32_to_bf16_bits(o * inv));
-  if (p.lse != nullptr && d == 0)
-    p.lse[size_t(s) * p.n_q_heads + head] = (mm + log2f(l)) * 0.6931471805599453f;
 }
 
 bool decode_mfma_supported(const actqkv_shape& sh, int m) {
@@ -248,8 +252,8 @@ bool decode_mfma_supported(const actqkv_shape& sh, int m) {
 
 // Launch shape: workgroups of 8 wavefronts; about 2048 wavefronts in total (two per SIMD,
 // each with a whole tile's loads in flight) unless the tile list is shorter than that.
-// One workgroup per (sequence, KV head) writes the output itself; with more,
-// attn_decode_combine_kernel merges the partials.
+// One workgroup per (sequence, KV head) writes the output itself; with more, the one that
+// finishes last merges the partials.
 static int decode_tiles_max(const actqkv_shape& sh, int k_cap) {
   return (sh.n_init + kBlock - 1) / kBlock + k_cap + sh.n_local / kBlock + 2;
 }
@@ -267,8 +271,8 @@ size_t decode_mfma_scratch_floats(const actqkv_shape& sh, int batch, int k_cap) 
 int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* q, const void* k_cache,
                                  const void* v_cache, int64_t seq_stride, int nb_capacity,
                                  const int32_t* n_ctx, const int32_t* idx, const int32_t* n_sel,
-                                 int k_cap, void* out, float* lse, float* scratch, float scale,
-                                 hipStream_t stream) {
+                                 int k_cap, void* out, float* lse, float* scratch,
+                                 unsigned int* counters, float scale, hipStream_t stream) {
   DcParams p;
   p.q = static_cast<const uint16_t*>(q);
   p.k_cache = static_cast<const uint16_t*>(k_cache);
@@ -281,7 +285,8 @@ int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* 
   p.k_cap = k_cap;
   p.out = static_cast<uint16_t*>(out);
   p.lse = lse;
-  p.part = scratch;
+  p.part = reinterpret_cast<uint32_t*>(scratch);
+  p.counters = counters;
   p.n_q_heads = sh.n_q_heads;
   p.n_kv_heads = sh.n_kv_heads;
   p.n_init = sh.n_init;
@@ -291,10 +296,10 @@ int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* 
   const int group = sh.n_q_heads / sh.n_kv_heads;
   const int n_waves = kDcMaxWaves;
   const size_t lds = size_t(n_waves) * group * (kDcD + 2) * sizeof(float);
+  if (p.n_wg > 1 && size_t(batch) * sh.n_kv_heads * sizeof(unsigned int) > kCounterBytes)
+    return set_error(ACTQKV_EINVAL, "decode attention: more split (sequence, KV head) pairs than ticket counters");
   hipLaunchKernelGGL(attn_decode_kernel, dim3(p.n_wg, sh.n_kv_heads, batch), dim3(n_waves * 64), lds,
                      stream, p);
-  if (p.n_wg > 1)
-    hipLaunchKernelGGL(attn_decode_combine_kernel, dim3(sh.n_q_heads, batch), dim3(kDcD), 0, stream, p);
   return hip_status("attention (decode)");
 }
 

@@ -7,8 +7,8 @@
 // window - initial tokens, the blocks chosen by actqkv_select (read from device
 // memory), the local span and the causal part of the window - form one list of
 // 128-key blocks; it is cut into `splits` contiguous pieces, one workgroup each,
-// so that a 512-token window still fills all 256 compute units; a short second
-// kernel merges the pieces.  Workgroups of one
+// so that a 512-token window still fills all 256 compute units; the workgroup that
+// finishes last among the pieces of a query tile merges them.  Workgroups of one
 // KV head sit on one XCD (blockIdx % Hk picks the head), so that head's gathered
 // tiles stay in that XCD's L2.
 //
@@ -38,7 +38,7 @@ constexpr int kRowPad = 128;                         // bf16 elements per LDS ro
 constexpr int kTileElems = kBlock * kRowPad;         // one K or V^T tile in LDS
 constexpr int kPfMaxTiles = 96;                      // initial + selected (<= 64) + local + window
 constexpr int kPfLdsBytes = 2 * 2 * kTileElems * 2 + kPfMaxTiles * 12;  // 2 stages x (K, V^T) + tile table
-constexpr int kPfPartWords = 34;                     // per lane: 32 bf16 pairs + max + sum
+constexpr int kPfPartWords = 17;                     // 64-bit words per lane: 16 x 4 bf16 + (max, sum)
 constexpr int kMaxPfSplits = 8;
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -68,7 +68,8 @@ struct PfParams {
   int k_cap;
   uint16_t* out;
   float* lse;
-  float* part;             // [workgroup][split][wave][32 bf16 pairs + max + sum][64 lanes]
+  uint64_t* part;          // [workgroup][split][wave][16 x 4 bf16 + (max, sum)][64 lanes]
+  unsigned int* counters;  // one ticket counter per (sequence, query tile, KV head), zero between launches
   int m, n_q_heads, n_kv_heads, n_init, n_local;
   int splits, n_qtiles;
   float scale_log2e;
@@ -288,81 +289,85 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
 
   // ---- epilogue
   const float l_tot = acc_l[0];
-  if (p.splits > 1) {
-    // The split stores its normalised output as bf16 pairs in the order the registers hold
-    // them (register-major, lane-minor: every store is one contiguous 256-byte row), plus its
-    // running max and sum; attn_combine_kernel merges the splits.
-    const size_t group_id = (size_t(s) * p.n_qtiles + qtile) * p.n_kv_heads + hk;
-    uint32_t* mine = reinterpret_cast<uint32_t*>(p.part) +
-                     ((group_id * p.splits + split) * kPfWaves + wave) * (kPfPartWords * 64);
+  if (p.splits == 1) {
+    if (row_ok) store_rows(p, acc_o, m_run, l_tot, s, my_row, head, half);
+    return;
+  }
+  // The split stores its normalised output as bf16 in the order the registers hold it
+  // (register-major, lane-minor: every store instruction writes one contiguous 512-byte
+  // row), plus its running max and sum.
+  __shared__ int last_flag;
+  const size_t group_id = (size_t(s) * p.n_qtiles + qtile) * p.n_kv_heads + hk;
+  uint64_t* group_part = p.part + group_id * p.splits * kPfWaves * (kPfPartWords * 64);
+  {
+    uint64_t* mine = group_part + (size_t(split) * kPfWaves + wave) * (kPfPartWords * 64);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
-        mine[(db * 8 + i) * 64 + lane] = pack_bf16x2(acc_o[db][2 * i] * inv, acc_o[db][2 * i + 1] * inv);
-    mine[32 * 64 + lane] = __float_as_uint(m_run);
-    mine[33 * 64 + lane] = __float_as_uint(l_tot);
-    return;
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t lo = pack_bf16x2(acc_o[db][4 * i] * inv, acc_o[db][4 * i + 1] * inv);
+        const uint32_t hi = pack_bf16x2(acc_o[db][4 * i + 2] * inv, acc_o[db][4 * i + 3] * inv);
+        st_agent(mine + (db * 4 + i) * 64 + lane, uint64_t(lo) | (uint64_t(hi) << 32));
+      }
+    st_agent(mine + 16 * 64 + lane, uint64_t(__float_as_uint(m_run)) | (uint64_t(__float_as_uint(l_tot)) << 32));
   }
-  if (row_ok) store_rows(p, acc_o, m_run, l_tot, s, my_row, head, half);
-}
+  if (!last_of_group(p.counters + group_id, unsigned(p.splits), &last_flag)) return;
 
-// Merges the partial results of the key splits: one wavefront per (workgroup, wavefront) of
-// the main kernel, same register layout, so every load is a contiguous 256-byte row.
-//   out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s
-__global__ __launch_bounds__(256) void attn_combine_kernel(PfParams p) {
-  const int lane = threadIdx.x & 63;
-  const int n = lane & 31, half = lane >> 5;
-  const size_t gw = size_t(blockIdx.x) * 4 + (threadIdx.x >> 6);   // (group, wave)
-  const int wave = int(gw % kPfWaves);
-  const size_t group_id = gw / kPfWaves;
-  const int hk = int(group_id % p.n_kv_heads);
-  const int qtile = int((group_id / p.n_kv_heads) % p.n_qtiles);
-  const int s = int(group_id / (size_t(p.n_kv_heads) * p.n_qtiles));
-  const int group = p.n_q_heads / p.n_kv_heads;
-  const int waves_per_head = kPfWaves / group;
-  const int head = hk * group + wave / waves_per_head;
-  const int my_row = qtile * 32 * waves_per_head + (wave % waves_per_head) * 32 + n;
-
-  // out = sum_s w_s o_s / sum_s w_s with w_s = l_s 2^(m_s - M), M = max_s m_s
-  uint32_t raw[kMaxPfSplits][kPfPartWords];
+  // ---- the last split of the query tile merges all of them, in split order:
+  //   out = sum_s w_s o_s / sum_s w_s with w_s = l_s 2^(m_s - M), M = max_s m_s
+  // (its own piece is read back like the others, so the result does not depend on who is last)
+  const uint64_t* piece0 = group_part + size_t(wave) * (kPfPartWords * 64) + lane;
+  const size_t piece_stride = size_t(kPfWaves) * (kPfPartWords * 64);
+  float w_s[kMaxPfSplits];
+  float m_all = -INFINITY;
+  {
+    uint64_t ml[kMaxPfSplits];
 #pragma unroll
-  for (int s2 = 0; s2 < kMaxPfSplits; ++s2) {
-    if (s2 < p.splits) {
-      const uint32_t* other = reinterpret_cast<const uint32_t*>(p.part) +
-                              ((group_id * p.splits + s2) * kPfWaves + wave) * (kPfPartWords * 64);
+    for (int s2 = 0; s2 < kMaxPfSplits; ++s2)
+      ml[s2] = s2 < p.splits ? ld_agent(piece0 + s2 * piece_stride + 16 * 64) : 0;
 #pragma unroll
-      for (int k = 0; k < kPfPartWords; ++k) raw[s2][k] = other[k * 64 + lane];  // loads first
-    }
+    for (int s2 = 0; s2 < kMaxPfSplits; ++s2)
+      if (s2 < p.splits) m_all = fmaxf(m_all, __uint_as_float(uint32_t(ml[s2])));
+    const float m_safe = m_all == -INFINITY ? 0.f : m_all;
+#pragma unroll
+    for (int s2 = 0; s2 < kMaxPfSplits; ++s2)
+      w_s[s2] = s2 < p.splits ? __uint_as_float(uint32_t(ml[s2] >> 32)) *
+                                    __builtin_amdgcn_exp2f(__uint_as_float(uint32_t(ml[s2])) - m_safe)
+                              : 0.f;
   }
-  float m_run = -INFINITY;
-#pragma unroll
-  for (int s2 = 0; s2 < kMaxPfSplits; ++s2)
-    if (s2 < p.splits) m_run = fmaxf(m_run, __uint_as_float(raw[s2][32]));
-  const float m_safe = m_run == -INFINITY ? 0.f : m_run;
-  f32x16 acc_o[4];
-  float l_tot = 0.f;
+  float l_all = 0.f;
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc_o[db][i] = 0.f;
 #pragma unroll
-  for (int s2 = 0; s2 < kMaxPfSplits; ++s2) {
-    if (s2 < p.splits) {
-      const float w = __uint_as_float(raw[s2][33]) *
-                      __builtin_amdgcn_exp2f(__uint_as_float(raw[s2][32]) - m_safe);
-      l_tot += w;
+  for (int b0 = 0; b0 < kMaxPfSplits; b0 += 2) {
+    if (b0 < p.splits) {
+      uint64_t raw[2][16];
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
+      for (int j = 0; j < 2; ++j)                     // loads first: they overlap
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          acc_o[db][2 * i] += w * bf16_lo(raw[s2][db * 8 + i]);
-          acc_o[db][2 * i + 1] += w * bf16_hi(raw[s2][db * 8 + i]);
-        }
+        for (int k = 0; k < 16; ++k)
+          raw[j][k] = b0 + j < p.splits ? ld_agent(piece0 + (b0 + j) * piece_stride + k * 64) : 0;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const float w = w_s[b0 + j];
+        l_all += w;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = uint32_t(raw[j][db * 4 + i]), hi = uint32_t(raw[j][db * 4 + i] >> 32);
+            acc_o[db][4 * i + 0] += w * bf16_lo(lo);
+            acc_o[db][4 * i + 1] += w * bf16_hi(lo);
+            acc_o[db][4 * i + 2] += w * bf16_lo(hi);
+            acc_o[db][4 * i + 3] += w * bf16_hi(hi);
+          }
+      }
     }
   }
-  if (my_row < p.m) store_rows(p, acc_o, m_run, l_tot, s, my_row, head, half);
+  if (row_ok) store_rows(p, acc_o, m_all, l_all, s, my_row, head, half);
 }
 
 bool prefill_mfma_supported(const actqkv_shape& sh, int m) {
@@ -387,7 +392,8 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
                                   const void* k_cache, const void* v_cache, int64_t seq_stride,
                                   int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
                                   const int32_t* n_sel, int k_cap, void* out, float* lse, int splits,
-                                  float* scratch, float scale, hipStream_t stream) {
+                                  float* scratch, unsigned int* counters, float scale,
+                                  hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_mfma_kernel),
@@ -407,7 +413,8 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
   p.k_cap = k_cap;
   p.out = static_cast<uint16_t*>(out);
   p.lse = lse;
-  p.part = scratch;
+  p.part = reinterpret_cast<uint64_t*>(scratch);
+  p.counters = counters;
   p.m = m;
   p.n_q_heads = sh.n_q_heads;
   p.n_kv_heads = sh.n_kv_heads;
@@ -417,11 +424,9 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
   p.n_qtiles = prefill_mfma_qtiles(sh, m);
   p.scale_log2e = scale * 1.4426950408889634f;
   dim3 grid(p.n_qtiles * sh.n_kv_heads * splits, batch);
+  if (splits > 1 && size_t(batch) * p.n_qtiles * sh.n_kv_heads * sizeof(unsigned int) > kCounterBytes)
+    return set_error(ACTQKV_EINVAL, "prefill attention: more split query tiles than ticket counters");
   hipLaunchKernelGGL(attn_prefill_mfma_kernel, grid, dim3(kPfThreads), kPfLdsBytes, stream, p);
-  if (splits > 1) {
-    const unsigned groups = unsigned(batch) * p.n_qtiles * sh.n_kv_heads;
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(groups * kPfWaves / 4), dim3(256), 0, stream, p);
-  }
   return hip_status("attention (prefill, matrix cores)");
 }
 

@@ -93,6 +93,43 @@ __device__ __forceinline__ float block_max(float v, float* red) {
   return t;
 }
 
+// ---- merging the partial results of several workgroups inside one kernel ----------------
+// The workgroups of a group store their partials with agent-scope relaxed atomic stores
+// (write-through: the data leaves the XCD's L2, which other XCDs do not see), wait until
+// these are acknowledged and take a ticket; the one that draws the last ticket reads all
+// partials back with agent-scope atomic loads (which do not hit stale L2 lines) and writes
+// the result.  No device-scope fence is involved: on this chip such a fence writes back and
+// invalidates a whole L2 and costs more than a kernel boundary.  Nobody waits for anybody,
+// so every wavefront runs to its end whatever the others do.
+__device__ __forceinline__ void st_agent(uint64_t* p, uint64_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(uint32_t* p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t ld_agent(const uint64_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// True in every thread of the workgroup that arrives last out of `total` at `counter`
+// (zero before the first arrival; the last one puts it back to zero).  Called by all
+// threads after their st_agent stores; `flag` is one int of LDS.
+__device__ __forceinline__ bool last_of_group(unsigned int* counter, unsigned int total, int* flag) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);       // this wavefront's stores have been acknowledged
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned int t = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = t == total - 1u;
+    if (last) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *flag = last;
+  }
+  __syncthreads();
+  return *flag != 0;
+}
+
 // ---- window geometry -------------------------------------------------------
 // Tokens [0, i0) are the visible initial tokens; the local span starts at l0.
 struct WindowGeom {

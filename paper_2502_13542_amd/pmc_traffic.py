@@ -18,8 +18,8 @@ import os
 from collections import defaultdict
 
 ATTENTION = {
-    "c3_128k": ("attn_prefill_mfma_kernel", ["attn_prefill_mfma_kernel", "attn_combine_kernel"]),
-    "c4_decode": ("attn_decode_kernel", ["attn_decode_kernel", "attn_decode_combine_kernel"]),
+    "c3_128k": ("attn_prefill_mfma_kernel", ["attn_prefill_mfma_kernel"]),
+    "c4_decode": ("attn_decode_kernel", ["attn_decode_kernel"]),
 }
 
 
