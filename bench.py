@@ -166,45 +166,45 @@ def bench_prefill(args, torch, B, H, synth):
     bud0 = None if plan.budget is None else plan.budget.clone()
     out = torch.zeros_like(q)
     n_win = plan.n_windows
-    nsel_log = torch.zeros(n_win, dtype=torch.int32, device=dev)
-    nb_begin = sh.n_init // sh.block_size
 
-    def one_step(events=None):
+    # Two dependency chains (see PrefillPipeline): with overlap, the attention of window t runs
+    # on a second stream beside the probe / score / select chain of window t+1.
+    pipe = H.PrefillPipeline(runner, plan)
+    nsel_log = pipe.n_sel
+
+    def one_step(events=None, overlap=False):
         runner.stats.zero_()
         if bud0 is not None:
             plan.budget.copy_(bud0)
-        for t in range(n_win):
-            w0, rows = plan.w0[t], plan.rows[t]
-            qw = q[w0:w0 + rows]
-            bud = None if plan.budget is None else plan.budget[t:t + 1]
-            rest = None if plan.rest is None else plan.rest[t:t + 1]
-            nb_cap = min(max(plan.nb_end_host[t], nb_begin), runner.nb_capacity)
-            B.build_probe(runner.cs, 1, rows, qw, runner.stats, True, runner.probe, runner.probe_kv,
-                          runner.probe_norm, None, runner.workspace)
-            B.score_blocks(runner.cs, 1, runner.probe_kv, runner.probe_norm, repd, 0, nb_cap, nb_begin,
-                           plan.nb_end[t:t + 1], runner.scores, runner.score_stride)
-            B.select(1, runner.scores, runner.score_stride, nb_cap, nb_begin, plan.nb_end[t:t + 1],
-                     w.k_cap, bud, rest, runner.idx, nsel_log[t:t + 1], None, None)
-            if events is not None:
-                events[t][0].record()
-            B.retrieval_attention(runner.cs, 1, rows, qw, kc, vc, 0, runner.nb_capacity,
-                                  plan.n_ctx[t:t + 1], runner.idx, nsel_log[t:t + 1], w.k_cap,
-                                  out[w0:w0 + rows], None, runner.workspace)
-            if events is not None:
-                events[t][1].record()
+        pipe.run(q, kc, vc, repd, out, overlap, events)
 
     if args.pmc_pass:
         return pmc_pass(torch, B, one_step, {"workload": w.name, "launches": n_win})
-    graph = None if args.eager else capture_graph(torch, one_step, out, "prefill")
-    run = graph.replay if graph is not None else one_step
-    for _ in range(args.warmup):
-        run()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    def timed(run, steps):
+        for _ in range(args.warmup):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    # strictly in window order (one stream): reported beside the headline number
+    graph_serial = None if args.eager else capture_graph(torch, one_step, out, "prefill (window order)")
+    serial_s = timed(graph_serial.replay if graph_serial is not None else one_step, min(args.steps, 3))
+    overlap = not args.no_overlap
+    if overlap:
+        B.set_attention_cus(args.attention_cus)     # the rest serves the chain of the next window
+        step_fn = lambda: one_step(overlap=True)
+        graph = None if args.eager else capture_graph(torch, step_fn, out, "prefill (two streams)")
+        run = graph.replay if graph is not None else step_fn
+        elapsed = timed(run, args.steps) * args.steps
+        B.set_attention_cus(256)
+    else:
+        graph, elapsed = graph_serial, serial_s * args.steps
+        if args.steps > 3:
+            elapsed = timed(graph_serial.replay if graph_serial is not None else one_step, args.steps) * args.steps
 
     # ---- roofline of the dominant kernel: the prefill attention launch, one eager pass
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_win)]
@@ -226,7 +226,11 @@ def bench_prefill(args, torch, B, H, synth):
                                f"n_init {sh.n_init}, n_local {sh.n_local}, k_cap {w.k_cap}, "
                                f"cut-off {'on' if w.cutoff else 'off'}",
                    "windows": n_win, "mean_blocks_selected": sum(n_sel) / max(n_win, 1),
-                   "launch": "hip graph replay" if graph is not None else "eager"},
+                   "launch": ("hip graph replay" if graph is not None else "eager") +
+                             (", attention of window t on a second stream beside the probe/score/select "
+                              f"chain of window t+1, attention on {args.attention_cus} of 256 CUs" if overlap
+                              else ", one stream, window order"),
+                   "ms_per_step_window_order": serial_s * 1e3},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, **traffic_fields(w.name),
                      "kernel": "actqkv_retrieval_attention launch (attn_prefill_mfma_kernel)",
@@ -381,6 +385,10 @@ def main() -> int:
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--decode-layers", type=int, default=0, help="override the layer count (testing)")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="prefill: one stream, strictly in window order")
+    ap.add_argument("--attention-cus", type=int, default=192,
+                    help="prefill, two streams: compute units the attention may fill")
     ap.add_argument("--pmc-pass", action="store_true",
                     help="one calibration copy and one eager pass, for a rocprofv3 --pmc run")
     args = ap.parse_args()

@@ -170,6 +170,16 @@ int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, cons
                                const int32_t* n_sel, int k_cap, void* out, float* lse,
                                void* workspace, size_t ws_bytes, void* stream);
 
+/* Launch-shape hint for callers that run other kernels beside the prefill attention (for
+ * instance the probe / score / select chain of the next window on a second stream, which
+ * depends on the previous selection but not on the previous attention): the prefill
+ * attention then cuts its key tiles into only as many pieces as fill `cus` of the chip's
+ * 256 compute units and leaves the others to the concurrent work.  Process-wide, default
+ * 256; takes effect for later calls, including actqkv_workspace_bytes (a workspace sized
+ * under one setting may be too small under a larger one, which the calls report as
+ * ACTQKV_EWORKSPACE).  Results do not depend on it beyond the order of floating-point sums. */
+int actqkv_set_attention_cus(int cus);
+
 /* Measurement aid, not a step of the method: a plain copy of `bytes` bytes (a multiple
  * of 16; both pointers device memory, 16-byte aligned, not overlapping) done by one
  * kernel with 16-byte loads and stores.  It reads and writes exactly `bytes` bytes of

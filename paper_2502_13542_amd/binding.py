@@ -53,6 +53,7 @@ SIGNATURES = {
     "actqkv_select": (_i, [_i, _vp, _i64, _i, _i, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_retrieval_attention": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
                                         _vp, _vp, _vp, _sz, _vp]),
+    "actqkv_set_attention_cus": (_i, [_i]),
     "actqkv_copy_bytes": (_i, [_vp, _vp, _sz, _vp]),
     "actqkv_last_error": (ctypes.c_char_p, []),
     "actqkv_version": (_i, []),
@@ -64,12 +65,13 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
+    path = os.environ.get("ACTQKV_LIB") or LIB_PATH    # another build of the library, for comparisons
+    if path == LIB_PATH and not os.path.exists(LIB_PATH):
         if not build_if_missing:
             raise FileNotFoundError(LIB_PATH)
         from .build import build
         build()
-    lib = ctypes.CDLL(LIB_PATH)
+    lib = ctypes.CDLL(path)
     for name, (res, args) in SIGNATURES.items():
         fn = getattr(lib, name)
         fn.restype, fn.argtypes = res, args
@@ -117,6 +119,11 @@ def workspace_bytes(shape: CShape, batch: int, m: int, nb_capacity: int, k_cap: 
     if n == 0:
         raise ActQKVError(-1, last_error())
     return n
+
+
+def set_attention_cus(cus: int) -> None:
+    """Compute units the prefill attention may fill (256 = all); see the header."""
+    _check(load_library().actqkv_set_attention_cus(int(cus)))
 
 
 def copy_bytes(dst, src, stream=None) -> None:

@@ -1,6 +1,7 @@
 // C ABI of the library: host-side argument checks, then one launcher per entry point.
 // The checks need no GPU, so every error path can be exercised on a CPU-only machine.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -109,12 +110,15 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
                                   float* scratch, unsigned int* counters, float scale,
                                   hipStream_t stream);
 
-// Enough key splits to give every compute unit a workgroup, never more than 8.
+// Compute units the prefill attention may fill (actqkv_set_attention_cus).
+static std::atomic<int> g_attention_cus{256};
+
+// Enough key splits to give every compute unit it may fill a workgroup, never more than 8.
 int prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap) {
   (void)k_cap;
   if (!prefill_mfma_supported(sh, m)) return 1;
   const int base = batch * prefill_mfma_workgroups(sh, m);
-  int s = 256 / (base > 0 ? base : 1);
+  int s = g_attention_cus.load(std::memory_order_relaxed) / (base > 0 ? base : 1);
   return s < 1 ? 1 : (s > 8 ? 8 : s);
 }
 bool decode_mfma_supported(const actqkv_shape& sh, int m);
@@ -310,6 +314,12 @@ int actqkv_copy_bytes(void* dst, const void* src, size_t bytes, void* stream) {
   hipLaunchKernelGGL(copy_bytes_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n);
   return hip_status("copy_bytes");
+}
+
+int actqkv_set_attention_cus(int cus) {
+  if (cus < 1 || cus > 256) return set_error(ACTQKV_EINVAL, "set_attention_cus: %d not in 1..256", cus);
+  g_attention_cus.store(cus, std::memory_order_relaxed);
+  return ACTQKV_OK;
 }
 
 const char* actqkv_last_error(void) { return g_error; }

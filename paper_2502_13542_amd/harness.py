@@ -158,3 +158,56 @@ def prefill_layer(runner: LayerRunner, plan: PrefillPlan, q: torch.Tensor, k_cac
                           theta=runner.theta[0].clone(), budget=runner.budget[0].clone(),
                           budget_after=None if bud is None else bud[0].clone())
     return rec
+
+
+class PrefillPipeline:
+    """The windows of one layer as two dependency chains.  The probe / score / select chain
+    of a window depends on the windows before it (running statistics of Eq. (8), the budget of
+    Eq. (12)); the attention of a window depends only on that window's own selection.  With
+    overlap=True the attention calls go to a second stream, so the chain of window t+1 runs
+    beside the attention of window t; every window keeps its own selection, and the two
+    streams use separate workspaces.  The results are those of window order."""
+
+    def __init__(self, runner: LayerRunner, plan: PrefillPlan):
+        self.runner, self.plan = runner, plan
+        dev = runner.device
+        self.idx = torch.full((plan.n_windows, runner.k_cap), -1, dtype=torch.int32, device=dev)
+        self.n_sel = torch.zeros(plan.n_windows, dtype=torch.int32, device=dev)
+        self.ws_attn = torch.zeros_like(runner.workspace)
+        self.side = torch.cuda.Stream(device=dev)
+
+    def run(self, q: torch.Tensor, k_cache, v_cache, rep_keys, out: torch.Tensor, overlap: bool = True,
+            events=None) -> None:
+        """q, out [N][H][D].  events: optional per-window (start, end) event pairs recorded around
+        the attention call (window order only)."""
+        r, plan = self.runner, self.plan
+        sh, cs = r.shape, r.cs
+        nb_begin = sh.n_init // sh.block_size
+        cur = torch.cuda.current_stream()
+        if overlap:
+            self.side.wait_stream(cur)
+        for t in range(plan.n_windows):
+            w0, rows = plan.w0[t], plan.rows[t]
+            qw = q[w0:w0 + rows]
+            bud = None if plan.budget is None else plan.budget[t:t + 1]
+            rest = None if plan.rest is None else plan.rest[t:t + 1]
+            nb_cap = min(max(plan.nb_end_host[t], nb_begin), r.nb_capacity)
+            B.build_probe(cs, 1, rows, qw, r.stats, True, r.probe, r.probe_kv, r.probe_norm, None,
+                          r.workspace)
+            B.score_blocks(cs, 1, r.probe_kv, r.probe_norm, rep_keys, 0, nb_cap, nb_begin,
+                           plan.nb_end[t:t + 1], r.scores, r.score_stride)
+            B.select(1, r.scores, r.score_stride, nb_cap, nb_begin, plan.nb_end[t:t + 1], r.k_cap, bud,
+                     rest, self.idx[t], self.n_sel[t:t + 1], None, None)
+            if overlap:
+                done = torch.cuda.Event()
+                done.record(cur)
+                self.side.wait_event(done)
+            elif events is not None:
+                events[t][0].record()
+            B.retrieval_attention(cs, 1, rows, qw, k_cache, v_cache, 0, r.nb_capacity,
+                                  plan.n_ctx[t:t + 1], self.idx[t], self.n_sel[t:t + 1], r.k_cap,
+                                  out[w0:w0 + rows], None, self.ws_attn, self.side if overlap else None)
+            if not overlap and events is not None:
+                events[t][1].record()
+        if overlap:
+            cur.wait_stream(self.side)

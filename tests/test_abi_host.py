@@ -95,3 +95,25 @@ def test_score_select_attention_reject(lib):
     assert at(m=0) == -1 and at(cap=2) == -1 and at(cap=0) == -1
     with pytest.raises(B.ActQKVError):
         B._check(at(wsb=8))
+
+
+def test_set_attention_cus(lib):
+    cs = B.c_shape(LLAMA)
+    full = B.workspace_bytes(cs, 1, 512, 1024, 32)
+    assert lib.actqkv_set_attention_cus(0) == -1
+    assert lib.actqkv_set_attention_cus(257) == -1
+    assert "set_attention_cus" in B.last_error()
+    try:
+        assert lib.actqkv_set_attention_cus(192) == 0
+        assert B.workspace_bytes(cs, 1, 512, 1024, 32) <= full     # fewer pieces, fewer partials
+    finally:
+        assert lib.actqkv_set_attention_cus(256) == 0
+    assert B.workspace_bytes(cs, 1, 512, 1024, 32) == full
+
+
+def test_copy_bytes_rejects(lib):
+    assert lib.actqkv_copy_bytes(None, A16, 1024, None) == -1
+    assert lib.actqkv_copy_bytes(A16, None, 1024, None) == -1
+    assert lib.actqkv_copy_bytes(A16, A16 + 4096, 1000, None) == -1      # not a multiple of 16
+    assert lib.actqkv_copy_bytes(A16 + 4, A16 + 4096, 1024, None) == -3  # alignment
+    assert lib.actqkv_copy_bytes(A16, A16 + 4096, 0, None) == 0          # nothing to do, nothing launched

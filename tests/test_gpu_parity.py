@@ -117,6 +117,61 @@ def test_c3_128k_full_size_sampled_windows():
     run_prefill_case(synth.WORKLOADS["c3_128k"], attend=[2, 64, 255])
 
 
+def test_c3_128k_two_stream_pipeline_as_benchmarked():
+    """configs[2] at full size the way bench.py times it: attention on a second stream with
+    192 of the 256 compute units, the selection chain of the next window beside it.  Every
+    window's selection must equal the one found in window order; the attention of sampled
+    windows is checked against the oracle and all rows against the window-order result."""
+    w = synth.WORKLOADS["c3_128k"]
+    sh = w.shape
+    _say(f"[case] {w.name} two streams N={w.n_ctx} seed={w.seed}")
+    q, k, v = synth.gen_layer(w, "cpu", 0)
+    rep = synth.pick_rep_keys(k, sh.block_size, sh.n_rep)
+    cutoffs = []
+    for t in range(w.n_windows):
+        b, e = H.eligible_range(sh, t * w.window)
+        cutoffs.append(synth.cutoff_state(w, e - b, t, 0))
+    qd, kc, vc = q.to(DEV), H.blocked_k(k.to(DEV), sh, w.n_blocks), H.blocked_vt(v.to(DEV), sh, w.n_blocks)
+    repd = torch.zeros(w.n_blocks, sh.n_rep, sh.n_kv_heads, sh.head_dim, dtype=rep.dtype, device=DEV)
+    repd[: rep.shape[0]] = rep.to(DEV)
+    runner = H.LayerRunner(sh, 1, w.window, w.n_blocks, w.k_cap, DEV)
+    plan = H.make_prefill_plan(sh, w.n_ctx, w.window, cutoffs, DEV)
+    bud0 = plan.budget.clone()
+    pipe = H.PrefillPipeline(runner, plan)
+    out_order, out_two = torch.zeros_like(qd), torch.zeros_like(qd)
+    pipe.run(qd, kc, vc, repd, out_order, overlap=False)
+    torch.cuda.synchronize()
+    idx_order, nsel_order = pipe.idx.clone(), pipe.n_sel.clone()
+    runner.reset()
+    plan.budget.copy_(bud0)
+    pipe.idx.fill_(-1)
+    B.set_attention_cus(192)
+    try:
+        pipe.run(qd, kc, vc, repd, out_two, overlap=True)
+        torch.cuda.synchronize()
+    finally:
+        B.set_attention_cus(256)
+    assert torch.equal(pipe.idx, idx_order) and torch.equal(pipe.n_sel, nsel_order)
+    diff = (out_two.float() - out_order.float()).abs().max().item()
+    scale = out_order.float().abs().max().item()
+    assert diff <= TOL_OUT["bf16"] * scale, f"two streams vs window order: {diff}"
+    attend = [3, 130, 255]
+    want = oracle_windows(q, k, v, rep, sh, w.window, w.k_cap, cutoffs, attend)
+    worst = 0.0
+    for t in attend:
+        res = want[t]
+        gi, gn = pipe.idx[t].cpu().tolist(), int(pipe.n_sel[t])
+        ref = res["out"]
+        if not check_selection(gi, gn, res, w.k_cap):
+            ref = orc.retrieval_attention_window(f64(q[res["w0"]:res["w0"] + w.window]), f64(k), f64(v),
+                                                 res["w0"], gi[:gn], sh.n_init, sh.n_local,
+                                                 sh.block_size, sh.group)
+        err = out_error(out_two[res["w0"]:res["w0"] + ref.shape[0]], ref)
+        worst = max(worst, err)
+        assert err < TOL_OUT["bf16"], f"attention output, window {t}: {err}"
+    _say(f"[case] {w.name} two streams: selections equal, max |two - order| {diff:.3e}, worst out err {worst:.3e}")
+
+
 @pytest.mark.parametrize("n_init,n_local", [(0, 256), (128, 0), (256, 128)])
 def test_geometry_variants(n_init, n_local):
     sh = LayerShape(4, 2, 64, 128, 2, n_init, n_local, "fp32")
@@ -129,6 +184,14 @@ def test_context_shorter_than_init():
     sh = LayerShape(4, 2, 64, 128, 2, 128, 128, "fp32")
     w = synth.Workload("tiny", sh, 100, 128, 4, False, 5, outlier_kind="boost", n_planted=0)
     run_prefill_case(w)
+
+
+def test_copy_bytes():
+    src = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device=DEV)
+    dst = torch.zeros_like(src)
+    B.copy_bytes(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
 
 
 # ---------------------------------------------------------------- select alone: ties, cut-off, sizes
