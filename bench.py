@@ -77,8 +77,8 @@ def cpu_baseline(w, q, k, v, rep, cutoffs, sample):
         t_total += time.perf_counter() - t0
         tokens += qw.shape[0]
     return {"value": tokens / t_total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"windows {list(sample)} of {w.n_windows} (all steps of the path, all rows), "
-                      f"{t_total:.1f} s of numpy fp64"}
+            "sample": f"{len(sample)} windows spread evenly over the {w.n_windows} (first {sample[0]}, last "
+                      f"{sample[-1]}; all steps of the path, all rows), {t_total:.1f} s of numpy fp64"}
 
 
 def capture_graph(torch, step_fn, check_tensor, log_name):
@@ -176,7 +176,7 @@ def bench_prefill(args, torch, B, H, synth):
         runner.stats.zero_()
         if bud0 is not None:
             plan.budget.copy_(bud0)
-        pipe.run(q, kc, vc, repd, out, overlap, events)
+        pipe.run(q, kc, vc, repd, out, overlap, events, args.chunk)
 
     if args.pmc_pass:
         return pmc_pass(torch, B, one_step, {"workload": w.name, "launches": n_win})
@@ -227,8 +227,9 @@ def bench_prefill(args, torch, B, H, synth):
                                f"cut-off {'on' if w.cutoff else 'off'}",
                    "windows": n_win, "mean_blocks_selected": sum(n_sel) / max(n_win, 1),
                    "launch": ("hip graph replay" if graph is not None else "eager") +
-                             (", attention of window t on a second stream beside the probe/score/select "
-                              f"chain of window t+1, attention on {args.attention_cus} of 256 CUs" if overlap
+                             (f", attention on a second stream ({args.attention_cus} of 256 CUs, {args.chunk} windows "
+                              "per hand-over) beside the probe/score/select chain of the following windows"
+                              if overlap
                               else ", one stream, window order"),
                    "ms_per_step_window_order": serial_s * 1e3},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
@@ -240,7 +241,8 @@ def bench_prefill(args, torch, B, H, synth):
     }
     if not args.no_cpu_baseline:
         T = n_win
-        sample = sorted({max(T // 4, 0), T // 2, (3 * T) // 4, T - 1})
+        stride = max(T // 48, 1)                  # about 48 windows, 10-20 s of oracle time
+        sample = sorted(set(range(stride // 2, T, stride)) | {T - 1})
         log("cpu_baseline: timing the oracle on sampled windows")
         res["cpu_baseline"] = cpu_baseline(w, q, k, v, rep, cutoffs, sample)
     return res
@@ -387,6 +389,8 @@ def main() -> int:
     ap.add_argument("--decode-layers", type=int, default=0, help="override the layer count (testing)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="prefill: one stream, strictly in window order")
+    ap.add_argument("--chunk", type=int, default=8,
+                    help="prefill, two streams: windows per hand-over between the streams")
     ap.add_argument("--attention-cus", type=int, default=192,
                     help="prefill, two streams: compute units the attention may fill")
     ap.add_argument("--pmc-pass", action="store_true",

@@ -103,23 +103,37 @@ static int check_blocks(int nb_capacity, int nb_begin, int k_cap, bool use_k) {
 
 bool prefill_mfma_supported(const actqkv_shape& sh, int m);
 int prefill_mfma_workgroups(const actqkv_shape& sh, int m);
+int prefill_mfma_qtiles(const actqkv_shape& sh, int m);
 int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, const void* q,
                                   const void* k_cache, const void* v_cache, int64_t seq_stride,
                                   int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
-                                  const int32_t* n_sel, int k_cap, void* out, float* lse, int splits,
-                                  float* scratch, unsigned int* counters, float scale,
-                                  hipStream_t stream);
+                                  const int32_t* n_sel, int k_cap, void* out, float* lse,
+                                  const PfSplits& splits, float* scratch, unsigned int* counters,
+                                  float scale, hipStream_t stream);
 
 // Compute units the prefill attention may fill (actqkv_set_attention_cus).
 static std::atomic<int> g_attention_cus{256};
 
-// Enough key splits to give every compute unit it may fill a workgroup, never more than 8.
-int prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap) {
+// Enough key splits to give every compute unit it may fill a workgroup, never more than 8
+// per query tile; what does not divide evenly goes to the last query tiles of the window.
+PfSplits prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap) {
   (void)k_cap;
-  if (!prefill_mfma_supported(sh, m)) return 1;
-  const int base = batch * prefill_mfma_workgroups(sh, m);
-  int s = g_attention_cus.load(std::memory_order_relaxed) / (base > 0 ? base : 1);
-  return s < 1 ? 1 : (s > 8 ? 8 : s);
+  PfSplits r{1, 0, 1};
+  if (!prefill_mfma_supported(sh, m)) return r;
+  const int n_qtiles = prefill_mfma_qtiles(sh, m);
+  const int pairs = batch * sh.n_kv_heads;                   // each has n_qtiles query tiles
+  const int cus = g_attention_cus.load(std::memory_order_relaxed);
+  int per_pair = cus / (pairs > 0 ? pairs : 1);              // workgroups one pair may have
+  if (per_pair < n_qtiles) per_pair = n_qtiles;
+  r.s_lo = per_pair / n_qtiles;
+  if (r.s_lo >= 8) {
+    r.s_lo = 8;
+    r.rem = 0;
+  } else {
+    r.rem = per_pair - r.s_lo * n_qtiles;
+  }
+  r.slots = r.s_lo * n_qtiles + r.rem;
+  return r;
 }
 bool decode_mfma_supported(const actqkv_shape& sh, int m);
 size_t decode_mfma_scratch_floats(const actqkv_shape& sh, int batch, int k_cap);
@@ -132,12 +146,11 @@ int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* 
 size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap) {
   (void)nb_capacity;
   size_t probe = size_t(batch) * probe_scratch_floats(sh, m) * sizeof(float);
-  int splits = prefill_splits(sh, batch, m, k_cap);
+  const PfSplits splits = prefill_splits(sh, batch, m, k_cap);
   size_t attn = 0;
   if (decode_mfma_supported(sh, m)) attn = decode_mfma_scratch_floats(sh, batch, k_cap) * sizeof(float);
   if (prefill_mfma_supported(sh, m)) {
-    size_t groups = size_t(batch) * prefill_mfma_workgroups(sh, m);
-    attn = groups * splits * kPfPartialFloats * sizeof(float);
+    attn = size_t(batch) * sh.n_kv_heads * splits.slots * kPfPartialFloats * sizeof(float);
   }
   return kCounterBytes + align_up(probe > attn ? probe : attn, 256);
 }

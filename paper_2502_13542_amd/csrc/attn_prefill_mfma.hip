@@ -71,7 +71,7 @@ struct PfParams {
   uint64_t* part;          // [workgroup][split][wave][16 x 4 bf16 + (max, sum)][64 lanes]
   unsigned int* counters;  // one ticket counter per (sequence, query tile, KV head), zero between launches
   int m, n_q_heads, n_kv_heads, n_init, n_local;
-  int splits, n_qtiles;
+  int s_lo, rem, slots, n_qtiles;   // pieces per query tile (PfSplits)
   float scale_log2e;
 };
 
@@ -103,13 +103,23 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
   const int waves_per_head = kPfWaves / group;
   const int pos_per_wg = 32 * waves_per_head;
 
-  // blockIdx.x = ((split * n_qtiles + qtile) * Hk + hk): consecutive ids differ in hk,
-  // and ids are dealt round-robin to the XCDs, so each XCD serves few KV heads.
-  int bid = blockIdx.x;
-  const int hk = bid % p.n_kv_heads;
-  bid /= p.n_kv_heads;
-  const int qtile = bid % p.n_qtiles;
-  const int split = bid / p.n_qtiles;
+  // blockIdx.x = slot * Hk + hk: consecutive ids differ in hk, and ids are dealt round-robin
+  // to the XCDs, so each XCD serves few KV heads.  The slots of a (sequence, KV head) are the
+  // pieces of its query tiles, in order.
+  const int hk = blockIdx.x % p.n_kv_heads;
+  const int slot = blockIdx.x / p.n_kv_heads;
+  const int n_lo = p.n_qtiles - p.rem;
+  int qtile, split, splits;
+  if (slot < n_lo * p.s_lo) {
+    qtile = slot / p.s_lo;
+    split = slot - qtile * p.s_lo;
+    splits = p.s_lo;
+  } else {
+    const int r = slot - n_lo * p.s_lo;
+    splits = p.s_lo + 1;
+    qtile = n_lo + r / splits;
+    split = r - (qtile - n_lo) * splits;
+  }
   const int s = blockIdx.y;
 
   const int n_ctx = min(max(p.n_ctx[s], p.m), p.nb_capacity * kBlock);
@@ -119,7 +129,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
   const TileList tl = make_tile_list(g, g.w0 + row_hi, p.idx + size_t(s) * p.k_cap, p.n_sel[s],
                                      p.k_cap, p.nb_capacity);
   const int n_tiles = tl.count();
-  const int per = (n_tiles + p.splits - 1) / p.splits;
+  const int per = (n_tiles + splits - 1) / splits;
   const int t_begin = split * per, t_end = min(n_tiles, t_begin + per);
 
   const int head = hk * group + wave / waves_per_head;
@@ -289,7 +299,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
 
   // ---- epilogue
   const float l_tot = acc_l[0];
-  if (p.splits == 1) {
+  if (splits == 1) {
     if (row_ok) store_rows(p, acc_o, m_run, l_tot, s, my_row, head, half);
     return;
   }
@@ -298,7 +308,8 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
   // row), plus its running max and sum.
   __shared__ int last_flag;
   const size_t group_id = (size_t(s) * p.n_qtiles + qtile) * p.n_kv_heads + hk;
-  uint64_t* group_part = p.part + group_id * p.splits * kPfWaves * (kPfPartWords * 64);
+  uint64_t* group_part = p.part + ((size_t(s) * p.n_kv_heads + hk) * p.slots + (slot - split)) *
+                                      (kPfWaves * (kPfPartWords * 64));
   {
     uint64_t* mine = group_part + (size_t(split) * kPfWaves + wave) * (kPfPartWords * 64);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
@@ -312,7 +323,7 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
       }
     st_agent(mine + 16 * 64 + lane, uint64_t(__float_as_uint(m_run)) | (uint64_t(__float_as_uint(l_tot)) << 32));
   }
-  if (!last_of_group(p.counters + group_id, unsigned(p.splits), &last_flag)) return;
+  if (!last_of_group(p.counters + group_id, unsigned(splits), &last_flag)) return;
 
   // ---- the last split of the query tile merges all of them, in split order:
   //   out = sum_s w_s o_s / sum_s w_s with w_s = l_s 2^(m_s - M), M = max_s m_s
@@ -325,14 +336,14 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
     uint64_t ml[kMaxPfSplits];
 #pragma unroll
     for (int s2 = 0; s2 < kMaxPfSplits; ++s2)
-      ml[s2] = s2 < p.splits ? ld_agent(piece0 + s2 * piece_stride + 16 * 64) : 0;
+      ml[s2] = s2 < splits ? ld_agent(piece0 + s2 * piece_stride + 16 * 64) : 0;
 #pragma unroll
     for (int s2 = 0; s2 < kMaxPfSplits; ++s2)
-      if (s2 < p.splits) m_all = fmaxf(m_all, __uint_as_float(uint32_t(ml[s2])));
+      if (s2 < splits) m_all = fmaxf(m_all, __uint_as_float(uint32_t(ml[s2])));
     const float m_safe = m_all == -INFINITY ? 0.f : m_all;
 #pragma unroll
     for (int s2 = 0; s2 < kMaxPfSplits; ++s2)
-      w_s[s2] = s2 < p.splits ? __uint_as_float(uint32_t(ml[s2] >> 32)) *
+      w_s[s2] = s2 < splits ? __uint_as_float(uint32_t(ml[s2] >> 32)) *
                                     __builtin_amdgcn_exp2f(__uint_as_float(uint32_t(ml[s2])) - m_safe)
                               : 0.f;
   }
@@ -343,13 +354,13 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
     for (int i = 0; i < 16; ++i) acc_o[db][i] = 0.f;
 #pragma unroll
   for (int b0 = 0; b0 < kMaxPfSplits; b0 += 2) {
-    if (b0 < p.splits) {
+    if (b0 < splits) {
       uint64_t raw[2][16];
 #pragma unroll
       for (int j = 0; j < 2; ++j)                     // loads first: they overlap
 #pragma unroll
         for (int k = 0; k < 16; ++k)
-          raw[j][k] = b0 + j < p.splits ? ld_agent(piece0 + (b0 + j) * piece_stride + k * 64) : 0;
+          raw[j][k] = b0 + j < splits ? ld_agent(piece0 + (b0 + j) * piece_stride + k * 64) : 0;
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const float w = w_s[b0 + j];
@@ -391,9 +402,9 @@ int prefill_mfma_workgroups(const actqkv_shape& sh, int m) {
 int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, const void* q,
                                   const void* k_cache, const void* v_cache, int64_t seq_stride,
                                   int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
-                                  const int32_t* n_sel, int k_cap, void* out, float* lse, int splits,
-                                  float* scratch, unsigned int* counters, float scale,
-                                  hipStream_t stream) {
+                                  const int32_t* n_sel, int k_cap, void* out, float* lse,
+                                  const PfSplits& splits, float* scratch, unsigned int* counters,
+                                  float scale, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_mfma_kernel),
@@ -420,11 +431,15 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
   p.n_kv_heads = sh.n_kv_heads;
   p.n_init = sh.n_init;
   p.n_local = sh.n_local;
-  p.splits = splits;
+  p.s_lo = splits.s_lo;
+  p.rem = splits.rem;
+  p.slots = splits.slots;
   p.n_qtiles = prefill_mfma_qtiles(sh, m);
   p.scale_log2e = scale * 1.4426950408889634f;
-  dim3 grid(p.n_qtiles * sh.n_kv_heads * splits, batch);
-  if (splits > 1 && size_t(batch) * p.n_qtiles * sh.n_kv_heads * sizeof(unsigned int) > kCounterBytes)
+  if (splits.slots < p.n_qtiles || splits.slots != splits.s_lo * p.n_qtiles + splits.rem)
+    return set_error(ACTQKV_EINVAL, "prefill attention: inconsistent split of the key tiles");
+  dim3 grid(splits.slots * sh.n_kv_heads, batch);
+  if (splits.slots > p.n_qtiles && size_t(batch) * p.n_qtiles * sh.n_kv_heads * sizeof(unsigned int) > kCounterBytes)
     return set_error(ACTQKV_EINVAL, "prefill attention: more split query tiles than ticket counters");
   hipLaunchKernelGGL(attn_prefill_mfma_kernel, grid, dim3(kPfThreads), kPfLdsBytes, stream, p);
   return hip_status("attention (prefill, matrix cores)");

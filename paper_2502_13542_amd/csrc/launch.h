@@ -33,7 +33,12 @@ inline size_t probe_scratch_floats(const actqkv_shape& sh, int m) {
 }
 
 // Key-tile splits of the prefill attention.
-int prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap);
+// The first n_qtiles - rem query tiles of a sequence are cut into s_lo pieces, the last rem
+// (which see more of the causal window) into s_lo + 1; slots = pieces per (sequence, KV head).
+struct PfSplits {
+  int s_lo, rem, slots;
+};
+PfSplits prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap);
 // prefill on the matrix cores: per workgroup and split, 8 wavefronts x (32 bf16 pairs of
 // normalised output + max + sum) x 64 lanes
 constexpr size_t kPfPartialFloats = 8 * (32 + 2) * 64;

@@ -13,7 +13,7 @@ namespace actqkv {
 constexpr int kScoreBatch = 8;  // 16-byte loads a lane keeps in flight
 
 template <typename T>
-__global__ __launch_bounds__(256) void score_blocks_kernel(
+__global__ __launch_bounds__(1024) void score_blocks_kernel(
     const float* __restrict__ probe_kv, const float* __restrict__ probe_norm,
     const T* __restrict__ rep_keys, int64_t seq_stride, int nb_capacity, int nb_begin,
     const int32_t* __restrict__ nb_end, float* __restrict__ scores, int64_t score_stride, int n_rep,
@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256) void score_blocks_kernel(
   const int gq = lane >> 4, l16 = lane & 15;
   const int chunks = key_len / V;
   const int end = min(nb_end[s], nb_capacity);
-  const int b = nb_begin + blockIdx.x * 4 + wave;
+  const int b = nb_begin + blockIdx.x * int(blockDim.x >> 6) + wave;
   const bool live = b < end;
   const T* block_keys = rep_keys + size_t(s) * seq_stride + size_t(live ? b : nb_begin) * n_rep * key_len;
 
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void score_blocks_kernel(
   load_batch(gq, l16, k0);
   {
     const float* src = probe_kv + size_t(s) * key_len;
-    for (int i = threadIdx.x * 4; i < key_len; i += 256 * 4)
+    for (int i = threadIdx.x * 4; i < key_len; i += int(blockDim.x) * 4)
       *reinterpret_cast<f32x4*>(probe_lds + i) = *reinterpret_cast<const f32x4*>(src + i);
   }
   __syncthreads();
@@ -106,14 +106,20 @@ int launch_score(const actqkv_shape& sh, int batch, const float* probe_kv, const
   if (n <= 0) return ACTQKV_OK;
   const int key_len = sh.n_kv_heads * sh.head_dim;
   const float inv_sqrt_g = 1.f / sqrtf(float(sh.n_q_heads / sh.n_kv_heads));
-  dim3 grid((n + 3) / 4, batch);
+  // One wavefront per block.  A single long sequence (prefill) gets at most 64 workgroups,
+  // so that the kernel fits beside a prefill attention that leaves 64 compute units free.
+  int waves = 4;
+  if (batch == 1) {
+    while (waves < 16 && (n + waves - 1) / waves > 64) waves *= 2;
+  }
+  dim3 grid((n + waves - 1) / waves, batch), block(64 * waves);
   const size_t lds = size_t(key_len) * sizeof(float);
   if (sh.dtype == ACTQKV_F32)
-    hipLaunchKernelGGL(score_blocks_kernel<float>, grid, dim3(256), lds, stream, probe_kv, probe_norm,
+    hipLaunchKernelGGL(score_blocks_kernel<float>, grid, block, lds, stream, probe_kv, probe_norm,
                        static_cast<const float*>(rep_keys), seq_stride, nb_capacity, nb_begin, nb_end,
                        scores, score_stride, sh.n_rep, key_len, inv_sqrt_g);
   else
-    hipLaunchKernelGGL(score_blocks_kernel<uint16_t>, grid, dim3(256), lds, stream, probe_kv,
+    hipLaunchKernelGGL(score_blocks_kernel<uint16_t>, grid, block, lds, stream, probe_kv,
                        probe_norm, static_cast<const uint16_t*>(rep_keys), seq_stride, nb_capacity,
                        nb_begin, nb_end, scores, score_stride, sh.n_rep, key_len, inv_sqrt_g);
   return hip_status("score_blocks");

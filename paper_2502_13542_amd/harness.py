@@ -164,8 +164,8 @@ class PrefillPipeline:
     """The windows of one layer as two dependency chains.  The probe / score / select chain
     of a window depends on the windows before it (running statistics of Eq. (8), the budget of
     Eq. (12)); the attention of a window depends only on that window's own selection.  With
-    overlap=True the attention calls go to a second stream, so the chain of window t+1 runs
-    beside the attention of window t; every window keeps its own selection, and the two
+    overlap=True the attention calls go to a second stream, so the chain of later windows runs
+    beside the attention of earlier ones; every window keeps its own selection, and the two
     streams use separate workspaces.  The results are those of window order."""
 
     def __init__(self, runner: LayerRunner, plan: PrefillPlan):
@@ -177,15 +177,25 @@ class PrefillPipeline:
         self.side = torch.cuda.Stream(device=dev)
 
     def run(self, q: torch.Tensor, k_cache, v_cache, rep_keys, out: torch.Tensor, overlap: bool = True,
-            events=None) -> None:
+            events=None, chunk: int = 8) -> None:
         """q, out [N][H][D].  events: optional per-window (start, end) event pairs recorded around
-        the attention call (window order only)."""
+        the attention call (window order only).  chunk: with overlap, the second stream picks up
+        the attention calls of `chunk` windows at a time, once the last of them has its selection
+        (one dependency between the streams per chunk, not per window)."""
         r, plan = self.runner, self.plan
         sh, cs = r.shape, r.cs
         nb_begin = sh.n_init // sh.block_size
         cur = torch.cuda.current_stream()
+
+        def attend(t, stream):
+            w0, rows = plan.w0[t], plan.rows[t]
+            B.retrieval_attention(cs, 1, rows, q[w0:w0 + rows], k_cache, v_cache, 0, r.nb_capacity,
+                                  plan.n_ctx[t:t + 1], self.idx[t], self.n_sel[t:t + 1], r.k_cap,
+                                  out[w0:w0 + rows], None, self.ws_attn, stream)
+
         if overlap:
             self.side.wait_stream(cur)
+        pending = []
         for t in range(plan.n_windows):
             w0, rows = plan.w0[t], plan.rows[t]
             qw = q[w0:w0 + rows]
@@ -198,16 +208,20 @@ class PrefillPipeline:
                            plan.nb_end[t:t + 1], r.scores, r.score_stride)
             B.select(1, r.scores, r.score_stride, nb_cap, nb_begin, plan.nb_end[t:t + 1], r.k_cap, bud,
                      rest, self.idx[t], self.n_sel[t:t + 1], None, None)
-            if overlap:
+            if not overlap:
+                if events is not None:
+                    events[t][0].record()
+                attend(t, None)
+                if events is not None:
+                    events[t][1].record()
+                continue
+            pending.append(t)
+            if len(pending) == chunk or t == plan.n_windows - 1:
                 done = torch.cuda.Event()
                 done.record(cur)
                 self.side.wait_event(done)
-            elif events is not None:
-                events[t][0].record()
-            B.retrieval_attention(cs, 1, rows, qw, k_cache, v_cache, 0, r.nb_capacity,
-                                  plan.n_ctx[t:t + 1], self.idx[t], self.n_sel[t:t + 1], r.k_cap,
-                                  out[w0:w0 + rows], None, self.ws_attn, self.side if overlap else None)
-            if not overlap and events is not None:
-                events[t][1].record()
+                for u in pending:
+                    attend(u, self.side)
+                pending = []
         if overlap:
             cur.wait_stream(self.side)
