@@ -106,12 +106,12 @@ __global__ __launch_bounds__(kDcMaxWaves * 64) void attn_decode_kernel(DcParams 
     __builtin_amdgcn_sched_barrier(0);   // all 32 key loads are in flight before the first MFMA
     f32x4 sc[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      sc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < 8; ++j) sc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
+    for (int ks = 0; ks < 4; ++ks)       // the 8 sub-tiles take turns: no MFMA waits for the one before it
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
         sc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dc_as_bf16x8(ka[j * 4 + ks]), qb[ks], sc[j], 0, 0, 0);
-    }
     // V^T A operands: lane (row = channel within a group of 16, kq) reads keys 32*st + 8*kq .. +7
     u32x4 va[32];
     {

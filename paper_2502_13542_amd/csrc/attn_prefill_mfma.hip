@@ -122,12 +122,18 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
   }
   const int s = blockIdx.y;
 
-  const int n_ctx = min(max(p.n_ctx[s], p.m), p.nb_capacity * kBlock);
+  // the selected block indices are requested together with the two scalars they are used
+  // with, not after them (one memory round trip less before the first tile can be fetched)
+  __shared__ int32_t idx_lds[64];
+  const int32_t my_idx = tid < p.k_cap ? p.idx[size_t(s) * p.k_cap + tid] : -1;
+  const int n_ctx_raw = p.n_ctx[s], n_sel_raw = p.n_sel[s];
+  if (tid < 64) idx_lds[tid] = my_idx;
+  __syncthreads();
+  const int n_ctx = min(max(n_ctx_raw, p.m), p.nb_capacity * kBlock);
   const WindowGeom g = window_geom(n_ctx, p.m, p.n_init, p.n_local);
   const int row0 = qtile * pos_per_wg;                       // first window row of the workgroup
   const int row_hi = min(row0 + pos_per_wg, p.m) - 1;
-  const TileList tl = make_tile_list(g, g.w0 + row_hi, p.idx + size_t(s) * p.k_cap, p.n_sel[s],
-                                     p.k_cap, p.nb_capacity);
+  const TileList tl = make_tile_list(g, g.w0 + row_hi, idx_lds, n_sel_raw, p.k_cap, p.nb_capacity);
   const int n_tiles = tl.count();
   const int per = (n_tiles + splits - 1) / splits;
   const int t_begin = split * per, t_end = min(n_tiles, t_begin + per);
@@ -231,14 +237,27 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
       // ---- S^T = K Q^T : 4 groups of 32 keys
       f32x16 acc_s[4];
       const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      // the four key groups take turns, so that an MFMA never waits for the one just before it
+      // (a dependent 32x32x16 MFMA issues only about 90 cycles after its producer, an
+      // independent one after 32)
 #pragma unroll
-      for (int kb = 0; kb < 4; ++kb) {
+      for (int ks = 0; ks < kPfD / 16; ++ks) {
 #pragma unroll
-        for (int ks = 0; ks < kPfD / 16; ++ks) {
+        for (int kb = 0; kb < 4; ++kb) {
           bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(ks_ + a_off[ks] + kb * 32 * (kRowPad * 2)));
           acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], ks == 0 ? zero16 : acc_s[kb], 0, 0, 0);
         }
       }
+      // issue order: 8 operand reads ahead of the first MFMA, then one read per MFMA, so that an
+      // operand is requested about 8 MFMAs before it is needed (0x100 = LDS read, 0x008 = MFMA)
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+      for (int i = 0; i < 24; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      __builtin_amdgcn_sched_barrier(0);
       // register i of group kb holds key kpos0 + kb*32 + 16*(i/8) + 8*half + (i%8)
       if (masked) {
 #pragma unroll
@@ -330,39 +349,45 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
   // (its own piece is read back like the others, so the result does not depend on who is last)
   const uint64_t* piece0 = group_part + size_t(wave) * (kPfPartWords * 64) + lane;
   const size_t piece_stride = size_t(kPfWaves) * (kPfPartWords * 64);
-  float w_s[kMaxPfSplits];
+  // the loads of the first pieces go out together with the (max, sum) words of all pieces
+  constexpr int kMergeBatch = 3;
+  uint64_t ml[kMaxPfSplits], raw[kMergeBatch][16];
+#pragma unroll
+  for (int s2 = 0; s2 < kMaxPfSplits; ++s2)
+    ml[s2] = s2 < splits ? ld_agent(piece0 + s2 * piece_stride + 16 * 64) : 0;
+#pragma unroll
+  for (int j = 0; j < kMergeBatch; ++j)
+#pragma unroll
+    for (int k = 0; k < 16; ++k) raw[j][k] = j < splits ? ld_agent(piece0 + j * piece_stride + k * 64) : 0;
+  __builtin_amdgcn_sched_barrier(0);
+  float w_s[kMaxPfSplits + kMergeBatch];
   float m_all = -INFINITY;
-  {
-    uint64_t ml[kMaxPfSplits];
 #pragma unroll
-    for (int s2 = 0; s2 < kMaxPfSplits; ++s2)
-      ml[s2] = s2 < splits ? ld_agent(piece0 + s2 * piece_stride + 16 * 64) : 0;
+  for (int s2 = 0; s2 < kMaxPfSplits; ++s2)
+    if (s2 < splits) m_all = fmaxf(m_all, __uint_as_float(uint32_t(ml[s2])));
+  const float m_safe = m_all == -INFINITY ? 0.f : m_all;
 #pragma unroll
-    for (int s2 = 0; s2 < kMaxPfSplits; ++s2)
-      if (s2 < splits) m_all = fmaxf(m_all, __uint_as_float(uint32_t(ml[s2])));
-    const float m_safe = m_all == -INFINITY ? 0.f : m_all;
-#pragma unroll
-    for (int s2 = 0; s2 < kMaxPfSplits; ++s2)
-      w_s[s2] = s2 < splits ? __uint_as_float(uint32_t(ml[s2] >> 32)) *
-                                    __builtin_amdgcn_exp2f(__uint_as_float(uint32_t(ml[s2])) - m_safe)
-                              : 0.f;
-  }
+  for (int s2 = 0; s2 < kMaxPfSplits + kMergeBatch; ++s2)
+    w_s[s2] = s2 < splits ? __uint_as_float(uint32_t(ml[s2 < kMaxPfSplits ? s2 : 0] >> 32)) *
+                                  __builtin_amdgcn_exp2f(__uint_as_float(uint32_t(ml[s2 < kMaxPfSplits ? s2 : 0])) - m_safe)
+                            : 0.f;
   float l_all = 0.f;
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc_o[db][i] = 0.f;
 #pragma unroll
-  for (int b0 = 0; b0 < kMaxPfSplits; b0 += 2) {
+  for (int b0 = 0; b0 < kMaxPfSplits; b0 += kMergeBatch) {
     if (b0 < splits) {
-      uint64_t raw[2][16];
+      if (b0 > 0) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j)                     // loads first: they overlap
+        for (int j = 0; j < kMergeBatch; ++j)
 #pragma unroll
-        for (int k = 0; k < 16; ++k)
-          raw[j][k] = b0 + j < splits ? ld_agent(piece0 + (b0 + j) * piece_stride + k * 64) : 0;
+          for (int k = 0; k < 16; ++k)
+            raw[j][k] = b0 + j < splits ? ld_agent(piece0 + (b0 + j) * piece_stride + k * 64) : 0;
+      }
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < kMergeBatch; ++j) {
         const float w = w_s[b0 + j];
         l_all += w;
 #pragma unroll
