@@ -170,6 +170,26 @@ int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, cons
                                const int32_t* n_sel, int k_cap, void* out, float* lse,
                                void* workspace, size_t ws_bytes, void* stream);
 
+/* Cache update (Sec. 3.1, Eq. (4): the cache after a step is the cache before it with the
+ * step's keys and values appended), written in the blocked layouts above, and the
+ * representative keys of every block the new tokens complete.
+ *   k_new, v_new  [batch][m][Hk][D], storage dtype: keys and values of the m new tokens.
+ *   pos0     device int32 [batch]: tokens already in the sequence's cache; the new tokens take
+ *            positions pos0 .. pos0 + m - 1.  Tokens that would fall behind block
+ *            nb_capacity - 1 are dropped.
+ *   k_cache, v_cache  as in actqkv_retrieval_attention; only the new positions are written.
+ *   rep_keys [nb_capacity][r][Hk][D] per sequence, or NULL.  For every block that is complete
+ *            after the call and was not before, its r entries are written: the keys of the r
+ *            tokens of the block whose key over all KV heads together has the largest L2
+ *            norm (squares summed in fp32; equal norms: the lower position), in position
+ *            order.  The paper leaves this choice to the block-retrieval work it builds on.
+ *   cache_seq_stride, rep_seq_stride  elements between two sequences (multiples of 8).
+ * The call reads tokens older than pos0 of a completed block from k_cache, so earlier appends
+ * to the same cache must be ordered before it on the stream. */
+int actqkv_append_kv(const actqkv_shape* shape, int batch, int m, const void* k_new, const void* v_new,
+                     const int32_t* pos0, void* k_cache, void* v_cache, int64_t cache_seq_stride,
+                     void* rep_keys, int64_t rep_seq_stride, int nb_capacity, void* stream);
+
 /* Launch-shape hint for callers that run other kernels beside the prefill attention (for
  * instance the probe / score / select chain of the next window on a second stream, which
  * depends on the previous selection but not on the previous attention): the prefill

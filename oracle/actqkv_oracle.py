@@ -32,6 +32,10 @@ in the design notes of the repository):
     of eligible blocks; B_kv is decremented by the real-valued B^l.
   * Sorting by the softmax of the scores is sorting by the scores; equal
     scores keep the lower block index first.
+  * Cache update (Eq. (4)): concatenation.  Which tokens represent a block is
+    not stated in the paper (it builds on earlier block-retrieval work); the
+    rule taken: the r tokens whose key over all KV heads together has the
+    largest L2 norm, ties to the lower position, kept in position order.
   * Attention (Eq. (2), (3)): scale 1/sqrt(D); the first n_init tokens and the
     n_local tokens before the window (start rounded down to a block boundary)
     are always visible; the window itself is causal; queries and keys are
@@ -356,3 +360,34 @@ def decode_step(q_tok, k, v, rep_keys, n_ctx: int, n_init: int, n_local: int, bl
     res["out"] = retrieval_attention(q_tok[None], k[:n_ctx], v[:n_ctx], w0, res["idx"],
                                      n_init, n_local, block, group)[0]
     return res
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.1, Eq. (4): cache update; representatives of a finished block
+# --------------------------------------------------------------------------
+def append_cache(k_cache, v_cache, k_new, v_new) -> Tuple[np.ndarray, np.ndarray]:
+    """Eq. (4): the cache after a step is the cache before it with the step's keys and
+    values appended.  All arrays [tokens][Hk][D]."""
+    return (np.concatenate([np.asarray(k_cache), np.asarray(k_new)], axis=0),
+            np.concatenate([np.asarray(v_cache), np.asarray(v_new)], axis=0))
+
+
+def representative_tokens(k_block, r: int) -> List[int]:
+    """Positions (inside the block, ascending) of the r tokens of k_block [Bs][Hk][D] whose
+    key, all KV heads taken together, has the largest L2 norm; equal norms: lower position."""
+    kb = _f64(k_block)
+    norms = [math.sqrt(float((kb[j] * kb[j]).sum())) for j in range(kb.shape[0])]
+    order = sorted(range(len(norms)), key=lambda j: (-norms[j], j))
+    return sorted(order[:r])
+
+
+def representative_keys(k_all, block: int, r: int) -> np.ndarray:
+    """[NB][r][Hk][D] for the complete blocks of k_all [N][Hk][D] (same bits as stored)."""
+    k_all = np.asarray(k_all)
+    nb = k_all.shape[0] // block
+    out = np.zeros((nb, r) + k_all.shape[1:], dtype=k_all.dtype)
+    for b in range(nb):
+        kb = k_all[b * block:(b + 1) * block]
+        for slot, j in enumerate(representative_tokens(kb, r)):
+            out[b, slot] = kb[j]
+    return out

@@ -53,6 +53,7 @@ SIGNATURES = {
     "actqkv_select": (_i, [_i, _vp, _i64, _i, _i, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_retrieval_attention": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
                                         _vp, _vp, _vp, _sz, _vp]),
+    "actqkv_append_kv": (_i, [_shp, _i, _i, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _vp]),
     "actqkv_set_attention_cus": (_i, [_i]),
     "actqkv_copy_bytes": (_i, [_vp, _vp, _sz, _vp]),
     "actqkv_last_error": (ctypes.c_char_p, []),
@@ -119,6 +120,15 @@ def workspace_bytes(shape: CShape, batch: int, m: int, nb_capacity: int, k_cap: 
     if n == 0:
         raise ActQKVError(-1, last_error())
     return n
+
+
+def append_kv(shape: CShape, batch: int, m: int, k_new, v_new, pos0, k_cache, v_cache,
+              cache_seq_stride: int, rep_keys, rep_seq_stride: int, nb_capacity: int, stream=None) -> None:
+    st = torch.float32 if shape.dtype == ACTQKV_F32 else torch.bfloat16
+    _check(load_library().actqkv_append_kv(
+        ctypes.byref(shape), batch, m, _ptr(k_new, st), _ptr(v_new, st), _ptr(pos0, torch.int32),
+        _ptr(k_cache, st), _ptr(v_cache, st), cache_seq_stride, _ptr(rep_keys, st), rep_seq_stride,
+        nb_capacity, _stream(stream)))
 
 
 def set_attention_cus(cus: int) -> None:

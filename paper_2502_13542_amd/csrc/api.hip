@@ -329,6 +329,36 @@ int actqkv_copy_bytes(void* dst, const void* src, size_t bytes, void* stream) {
   return hip_status("copy_bytes");
 }
 
+int actqkv_append_kv(const actqkv_shape* shape, int batch, int m, const void* k_new, const void* v_new,
+                     const int32_t* pos0, void* k_cache, void* v_cache, int64_t cache_seq_stride,
+                     void* rep_keys, int64_t rep_seq_stride, int nb_capacity, void* stream) {
+  ACTQKV_TRY(check_shape(shape));
+  ACTQKV_TRY(check_batch(batch));
+  if (m < 1) return set_error(ACTQKV_EINVAL, "m %d < 1", m);
+  if (m > kMaxWindow) return set_error(ACTQKV_ESHAPE, "m %d > %d", m, kMaxWindow);
+  if (nb_capacity < 1) return set_error(ACTQKV_EINVAL, "nb_capacity %d < 1", nb_capacity);
+  if (int64_t(nb_capacity) * shape->block_size > (int64_t(1) << 30))
+    return set_error(ACTQKV_ESHAPE, "cache of %d blocks exceeds 2^30 tokens", nb_capacity);
+  ACTQKV_REQUIRE_PTR(k_new);
+  ACTQKV_REQUIRE_PTR(v_new);
+  ACTQKV_REQUIRE_SMALL(pos0, 4);
+  ACTQKV_REQUIRE_PTR(k_cache);
+  ACTQKV_REQUIRE_PTR(v_cache);
+  ACTQKV_OPTIONAL_PTR(rep_keys);
+  const int64_t per_seq = int64_t(nb_capacity) * shape->n_kv_heads * shape->block_size * shape->head_dim;
+  const int64_t rep_per_seq = int64_t(nb_capacity) * shape->n_rep * shape->n_kv_heads * shape->head_dim;
+  if (batch > 1 && cache_seq_stride < per_seq)
+    return set_error(ACTQKV_EINVAL, "cache_seq_stride %lld < one sequence's cache %lld",
+                     (long long)cache_seq_stride, (long long)per_seq);
+  if (batch > 1 && rep_keys != nullptr && rep_seq_stride < rep_per_seq)
+    return set_error(ACTQKV_EINVAL, "rep_seq_stride %lld < one sequence's representative keys %lld",
+                     (long long)rep_seq_stride, (long long)rep_per_seq);
+  if (cache_seq_stride % 8 != 0 || rep_seq_stride % 8 != 0)
+    return set_error(ACTQKV_EALIGN, "sequence strides must be multiples of 8 elements");
+  return launch_append(*shape, batch, m, k_new, v_new, pos0, k_cache, v_cache, cache_seq_stride, rep_keys,
+                       rep_seq_stride, nb_capacity, static_cast<hipStream_t>(stream));
+}
+
 int actqkv_set_attention_cus(int cus) {
   if (cus < 1 || cus > 256) return set_error(ACTQKV_EINVAL, "set_attention_cus: %d not in 1..256", cus);
   g_attention_cus.store(cus, std::memory_order_relaxed);

@@ -74,4 +74,8 @@ int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, co
                      const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
                      const Workspace& ws, hipStream_t stream);
 
+int launch_append(const actqkv_shape& sh, int batch, int m, const void* k_new, const void* v_new,
+                  const int32_t* pos0, void* k_cache, void* v_cache, int64_t cache_stride,
+                  void* rep_keys, int64_t rep_stride, int nb_capacity, hipStream_t stream);
+
 }  // namespace actqkv

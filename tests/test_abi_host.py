@@ -117,3 +117,15 @@ def test_copy_bytes_rejects(lib):
     assert lib.actqkv_copy_bytes(A16, A16 + 4096, 1000, None) == -1      # not a multiple of 16
     assert lib.actqkv_copy_bytes(A16 + 4, A16 + 4096, 1024, None) == -3  # alignment
     assert lib.actqkv_copy_bytes(A16, A16 + 4096, 0, None) == 0          # nothing to do, nothing launched
+
+
+def test_append_kv_rejects(lib):
+    cs = B.c_shape(LLAMA)
+    call = lambda **kw: lib.actqkv_append_kv(ctypes.byref(cs), kw.get("batch", 1), kw.get("m", 512),
+                                             kw.get("k", A16), kw.get("v", A16), kw.get("pos0", A16),
+                                             kw.get("kc", A16), kw.get("vc", A16), kw.get("cs", 0),
+                                             kw.get("rep", A16), kw.get("rs", 0), kw.get("nb", 8), None)
+    assert call(m=0) == -1 and call(batch=0) == -1 and call(nb=0) == -1
+    assert call(k=None) == -1 and call(pos0=None) == -1 and call(vc=None) == -1
+    assert call(k=A16 + 2) == -3 and call(cs=12) == -3
+    assert call(batch=2, cs=8) == -1                       # stride smaller than one sequence's cache

@@ -321,3 +321,105 @@ def test_decode_step_batch(dtype, hq, hkv, n_ctxs):
                                           sh.n_init, sh.n_local, 128, sh.group)[0]
         assert out_error(out[s, 0], ref) < TOL_OUT[dtype], f"decode output, sequence {s}"
         assert rel_to_max(runner.probe[s], f64(qs[s]).reshape(-1)) == 0.0   # probe is the query itself
+
+
+# ---------------------------------------------------------------- cache update and representatives
+def _logical_from_blocked(kc, vc, n):
+    """[nb][Hk][Bs][D], [nb][Hk][D][Bs] -> K, V [n][Hk][D]."""
+    nb, hk, bs, d = kc.shape
+    k = kc.permute(0, 2, 1, 3).reshape(nb * bs, hk, d)[:n]
+    v = vc.permute(0, 3, 1, 2).reshape(nb * bs, hk, d)[:n]
+    return k, v
+
+
+def _check_reps(rep_gpu, k_all_cpu, sh, n_tokens):
+    """Representative keys of all complete blocks against the oracle: bit-equal, unless the
+    fp32 norms that decide on the GPU tie within rounding with the fp64 ones of the oracle."""
+    want = orc.representative_keys(k_all_cpu.float().numpy(), sh.block_size, sh.n_rep)
+    got = rep_gpu[: want.shape[0]].float().cpu().numpy()
+    for b in range(want.shape[0]):
+        if np.array_equal(got[b], want[b]):
+            continue
+        kb = f64(k_all_cpu[b * sh.block_size:(b + 1) * sh.block_size])
+        norms = np.sqrt((kb ** 2).sum(axis=(1, 2)))
+        order = np.sort(norms)[::-1]
+        gap = order[sh.n_rep - 1] - order[sh.n_rep]
+        assert gap < 1e-5 * order[0], f"block {b}: representatives differ with a norm gap of {gap}"
+        rows = {tuple(r.reshape(-1)) for r in kb.astype(np.float32)}
+        assert all(tuple(r.reshape(-1)) in rows for r in got[b]), f"block {b}: not keys of the block"
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d,chunks", [
+    ("bf16", 32, 8, 128, [512, 512, 512, 77]),          # aligned windows and a ragged tail
+    ("bf16", 32, 8, 128, [100, 1, 1, 300, 27, 1]),      # unaligned pieces, single tokens
+    ("fp32", 8, 2, 64, [256, 256, 130]),
+])
+def test_append_kv_builds_the_cache_and_the_representatives(dtype, hq, hkv, d, chunks):
+    sh = LayerShape(hq, hkv, d, 128, 4, 128, 256, dtype)
+    cs = B.c_shape(sh)
+    tdt = torch.float32 if dtype == "fp32" else torch.bfloat16
+    n = sum(chunks)
+    nb_cap = (n + 127) // 128 + 1
+    g = torch.Generator().manual_seed(1234 + n)
+    k = torch.randn(n, hkv, d, generator=g).to(tdt)
+    v = torch.randn(n, hkv, d, generator=g).to(tdt)
+    _say(f"[append] {dtype} H{hq}/Hk{hkv}/D{d} chunks={chunks}")
+    kc = torch.zeros(nb_cap, hkv, 128, d, dtype=tdt, device=DEV)
+    vc = torch.zeros(nb_cap, hkv, d, 128, dtype=tdt, device=DEV)
+    rep = torch.zeros(nb_cap, sh.n_rep, hkv, d, dtype=tdt, device=DEV)
+    pos = 0
+    for m in chunks:
+        pos0 = torch.tensor([pos], dtype=torch.int32, device=DEV)
+        B.append_kv(cs, 1, m, k[pos:pos + m].to(DEV), v[pos:pos + m].to(DEV), pos0, kc, vc, 0, rep, 0, nb_cap)
+        pos += m
+    torch.cuda.synchronize()
+    # byte moves: bit-exact, and nothing written behind the last token
+    assert torch.equal(kc.cpu(), H.blocked_k(k, sh, nb_cap)) and torch.equal(vc.cpu(), H.blocked_vt(v, sh, nb_cap))
+    kl, vl = _logical_from_blocked(kc.cpu(), vc.cpu(), n)
+    k_or, v_or = orc.append_cache(k[:0].float().numpy(), v[:0].float().numpy(), k.float().numpy(), v.float().numpy())
+    assert np.array_equal(kl.float().numpy(), k_or) and np.array_equal(vl.float().numpy(), v_or)
+    _check_reps(rep, k, sh, n)
+    assert not rep[n // 128:].any(), "representatives of an incomplete block were written"
+
+
+def test_append_kv_batch_of_decode_steps():
+    """Three sequences at different lengths take single tokens; two of them finish a block."""
+    sh = LayerShape(32, 8, 128, 128, 4, 128, 256, "bf16")
+    cs = B.c_shape(sh)
+    lens = [126, 255, 300]
+    steps, nb_cap = 3, 4
+    g = torch.Generator().manual_seed(99)
+    ks = [torch.randn(l + steps, 8, 128, generator=g).to(torch.bfloat16) for l in lens]
+    vs = [torch.randn(l + steps, 8, 128, generator=g).to(torch.bfloat16) for l in lens]
+    kc = torch.stack([H.blocked_k(k[:l], sh, nb_cap) for k, l in zip(ks, lens)]).to(DEV)
+    vc = torch.stack([H.blocked_vt(v[:l], sh, nb_cap) for v, l in zip(vs, lens)]).to(DEV)
+    rep = torch.zeros(3, nb_cap, 4, 8, 128, dtype=torch.bfloat16, device=DEV)
+    for t in range(steps):
+        pos0 = torch.tensor([l + t for l in lens], dtype=torch.int32, device=DEV)
+        kn = torch.stack([k[l + t:l + t + 1] for k, l in zip(ks, lens)]).to(DEV)
+        vn = torch.stack([v[l + t:l + t + 1] for v, l in zip(vs, lens)]).to(DEV)
+        B.append_kv(cs, 3, 1, kn, vn, pos0, kc, vc, kc.stride(0), rep, rep.stride(0), nb_cap)
+    torch.cuda.synchronize()
+    for i, l in enumerate(lens):
+        assert torch.equal(kc[i].cpu(), H.blocked_k(ks[i], sh, nb_cap))
+        assert torch.equal(vc[i].cpu(), H.blocked_vt(vs[i], sh, nb_cap))
+        want = orc.representative_keys(ks[i].float().numpy(), 128, 4)
+        newly = [b for b in range(want.shape[0]) if b * 128 + 128 > l]     # finished during the steps
+        for b in range(nb_cap):
+            if b in newly:
+                assert np.array_equal(rep[i, b].float().cpu().numpy(), want[b]), f"seq {i} block {b}"
+            else:
+                assert not rep[i, b].any()
+
+
+def test_append_kv_drops_tokens_behind_the_capacity():
+    sh = LayerShape(8, 2, 64, 128, 4, 128, 256, "fp32")
+    cs = B.c_shape(sh)
+    k = torch.randn(200, 2, 64); v = torch.randn(200, 2, 64)
+    kc = torch.zeros(1, 2, 128, 64, device=DEV); vc = torch.zeros(1, 2, 64, 128, device=DEV)
+    guard_k, guard_v = torch.full((4096,), 7.0, device=DEV), torch.full((4096,), 7.0, device=DEV)
+    pos0 = torch.tensor([0], dtype=torch.int32, device=DEV)
+    B.append_kv(cs, 1, 200, k.to(DEV), v.to(DEV), pos0, kc, vc, 0, None, 0, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(kc.cpu(), H.blocked_k(k[:128], sh, 1)) and torch.equal(vc.cpu(), H.blocked_vt(v[:128], sh, 1))
+    assert bool((guard_k == 7).all()) and bool((guard_v == 7).all())

@@ -349,3 +349,48 @@ def test_cutoff_path_and_budget_bookkeeping():
         top = np.sort(w["scores"])[::-1][: w["count"]]
         got = [w["scores"][w["eligible"].index(i)] for i in w["idx"]]
         assert np.allclose(got, top)
+
+
+# ---------------------------------------------------------------- Eq. (4) and the representatives
+def test_append_is_concatenation_and_blocks_are_stable():
+    rng = np.random.default_rng(7)
+    k = rng.standard_normal((300, 2, 8)); v = rng.standard_normal((300, 2, 8))
+    kc, vc = k[:0], v[:0]
+    for a, b in [(0, 130), (130, 131), (131, 300)]:       # a window, one token, a ragged rest
+        kc, vc = orc.append_cache(kc, vc, k[a:b], v[a:b])
+    assert np.array_equal(kc, k) and np.array_equal(vc, v)
+    # representatives of a finished block do not change when later tokens arrive
+    r1 = orc.representative_keys(k[:140], 128, 4)
+    r2 = orc.representative_keys(k, 128, 4)
+    assert r1.shape == (1, 4, 2, 8) and r2.shape == (2, 4, 2, 8) and np.array_equal(r1[0], r2[0])
+
+
+def test_representative_tokens_hand_example_with_tie():
+    # norms over both heads: token0 5, token1 5 (tie with token0), token2 1, token3 13, token4 0
+    kb = np.zeros((5, 2, 2))
+    kb[0, 0] = [3, 0]; kb[0, 1] = [0, 4]
+    kb[1, 0] = [0, 5]
+    kb[2, 1] = [1, 0]
+    kb[3, 0] = [5, 0]; kb[3, 1] = [12, 0]
+    assert orc.representative_tokens(kb, 1) == [3]
+    assert orc.representative_tokens(kb, 2) == [0, 3]          # the tie goes to the lower position
+    assert orc.representative_tokens(kb, 3) == [0, 1, 3]
+    assert orc.representative_tokens(kb, 5) == [0, 1, 2, 3, 4]
+
+
+def test_representative_tokens_against_brute_force_and_torch_recipe():
+    import itertools
+    import torch
+    from paper_2502_13542_amd import synth
+    rng = np.random.default_rng(11)
+    kb = rng.standard_normal((9, 2, 4))
+    norms = np.sqrt((kb ** 2).sum(axis=(1, 2)))
+    for r in (1, 3, 4):
+        # the chosen set maximises the sum of norms over all r-subsets (distinct norms: unique)
+        best = max(itertools.combinations(range(9), r), key=lambda c: norms[list(c)].sum())
+        assert orc.representative_tokens(kb, r) == sorted(best)
+    # an independent implementation (torch stable sort) on a few blocks
+    k = torch.randn(3 * 128 + 17, 4, 16, generator=torch.Generator().manual_seed(3))
+    want = synth.pick_rep_keys(k, 128, 4).numpy()
+    got = orc.representative_keys(k.numpy(), 128, 4)
+    assert got.shape == want.shape and np.array_equal(got, want)
