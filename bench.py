@@ -283,6 +283,9 @@ def bench_decode(args, torch, B, H, synth):
     u_hat = u.repeat_interleave(sh.group, dim=0)
     q_all = torch.randn(steps, L, bt, 1, sh.n_q_heads, D, generator=gen, device=dev) + w.alpha * u_hat
     q_all = q_all.to(torch.bfloat16)
+    # keys and values of the tokens generated during the run, appended layer by layer (Eq. (4))
+    k_all = torch.randn(steps, L, bt, 1, hk, D, generator=gen, device=dev).to(torch.bfloat16)
+    v_all = torch.randn(steps, L, bt, 1, hk, D, generator=gen, device=dev).to(torch.bfloat16)
     out = torch.zeros(L, bt, 1, sh.n_q_heads, D, dtype=torch.bfloat16, device=dev)
     runner = H.LayerRunner(sh, bt, 1, nb_cap, w.k_cap, dev)
     nb_begin = sh.n_init // bs
@@ -297,18 +300,26 @@ def bench_decode(args, torch, B, H, synth):
     q_step = torch.zeros(L, bt, 1, sh.n_q_heads, D, dtype=torch.bfloat16, device=dev)
     step_no = torch.zeros(1, dtype=torch.int64, device=dev)
     n_ctx_cur = torch.zeros(bt, dtype=torch.int32, device=dev)
+    pos_cur = torch.zeros(bt, dtype=torch.int32, device=dev)
+    k_step = torch.zeros(L, bt, 1, hk, D, dtype=torch.bfloat16, device=dev)
+    v_step = torch.zeros(L, bt, 1, hk, D, dtype=torch.bfloat16, device=dev)
     nb_end_cur = torch.zeros(bt, dtype=torch.int32, device=dev)
     cache_stride, rep_stride = kc[0].stride(0), rep[0].stride(0)
 
     def load_step(t):
         """Per-step inputs (new queries, lengths): device copies outside the library."""
         q_step.copy_(q_all[t])
+        k_step.copy_(k_all[t])
+        v_step.copy_(v_all[t])
         n_ctx_cur.copy_(n_ctx_all[t])
+        torch.sub(n_ctx_cur, 1, out=pos_cur)
         nb_end_cur.copy_(nb_end_all[t])
 
     def one_step(events=None):
         budget.fill_(b_init)                          # B_kv is reset at the start of every step
         for l in range(L):
+            B.append_kv(runner.cs, bt, 1, k_step[l], v_step[l], pos_cur, kc[l], vc[l], cache_stride,
+                        rep[l], rep_stride, nb_cap)
             B.build_probe(runner.cs, bt, 1, q_step[l], None, False, runner.probe, runner.probe_kv,
                           runner.probe_norm, None, runner.workspace)
             B.score_blocks(runner.cs, bt, runner.probe_kv, runner.probe_norm, rep[l], rep_stride,
@@ -361,7 +372,7 @@ def bench_decode(args, torch, B, H, synth):
         "metric": "decode step us", "value": mean_us, "unit": "us/step", "p50_us": times[len(times) // 2] * 1e6,
         "higher_is_better": False, "steps": steps, "wall_s_incl_input_copies": t_all,
         "config": {"workload": f"{w.name}: batch {bt}, {L} layers, {n0} cached tokens, k_cap {w.k_cap}, "
-                               f"per-layer dynamic cut-off, KV cache {gb:.0f} GB bf16 in HBM",
+                               f"per-layer dynamic cut-off, new token appended per layer, KV cache {gb:.0f} GB bf16 in HBM",
                    "mean_blocks_selected": float(n_sel.float().mean()),
                    "launch": "hip graph replay" if graph is not None else "eager"},
         "algorithmic_bytes_per_step": byt + score_bytes,
