@@ -293,8 +293,13 @@ def bench_decode(args, torch, B, H, synth):
     n_ctx_all = torch.tensor([[n0 + 1 + t] * bt for t in range(steps)], dtype=torch.int32, device=dev)
     nb_end_host = [H.eligible_range(sh, n0 + t)[1] for t in range(steps)]
     nb_end_all = torch.tensor([[e] * bt for e in nb_end_host], dtype=torch.int32, device=dev)
-    b_init, rest = synth.decode_cutoff_profile(w, nb_end_host[0] - nb_begin)
-    rest_all = torch.tensor([[r] * bt for r in rest], dtype=torch.float32, device=dev)     # [L][bt]
+    # Alg. 1 across layers and steps: the history of the layers' densities lives on the device
+    b_init, _ = synth.decode_cutoff_profile(w, nb_end_host[0] - nb_begin)
+    k_mean, theta_prior = b_init / L, math.log(max(nb_end_host[0] - nb_begin, 2))
+    theta_sum = torch.zeros(bt, L, dtype=torch.float32, device=dev)
+    hist_steps = torch.zeros(bt, dtype=torch.float32, device=dev)
+    theta_step = torch.zeros(L, bt, dtype=torch.float32, device=dev)
+    rest_all = torch.zeros(L, bt, dtype=torch.float32, device=dev)
     budget = torch.zeros(bt, dtype=torch.float32, device=dev)
     nsel_log = torch.zeros(L, bt, dtype=torch.int32, device=dev)
     q_step = torch.zeros(L, bt, 1, sh.n_q_heads, D, dtype=torch.bfloat16, device=dev)
@@ -316,7 +321,8 @@ def bench_decode(args, torch, B, H, synth):
         nb_end_cur.copy_(nb_end_all[t])
 
     def one_step(events=None):
-        budget.fill_(b_init)                          # B_kv is reset at the start of every step
+        # folds the step before into the history; B_kv = L * k again; R^l for every layer
+        B.cutoff_next_step(bt, L, k_mean, theta_prior, theta_step, theta_sum, hist_steps, budget, rest_all)
         for l in range(L):
             B.append_kv(runner.cs, bt, 1, k_step[l], v_step[l], pos_cur, kc[l], vc[l], cache_stride,
                         rep[l], rep_stride, nb_cap)
@@ -325,7 +331,7 @@ def bench_decode(args, torch, B, H, synth):
             B.score_blocks(runner.cs, bt, runner.probe_kv, runner.probe_norm, rep[l], rep_stride,
                            nb_end_host[-1], nb_begin, nb_end_cur, runner.scores, runner.score_stride)
             B.select(bt, runner.scores, runner.score_stride, nb_end_host[-1], nb_begin, nb_end_cur,
-                     w.k_cap, budget, rest_all[l], runner.idx, nsel_log[l], None, None)
+                     w.k_cap, budget, rest_all[l], runner.idx, nsel_log[l], theta_step[l], None)
             if events is not None:
                 events[l][0].record()
             B.retrieval_attention(runner.cs, bt, 1, q_step[l], kc[l], vc[l], cache_stride, nb_cap,
@@ -335,6 +341,15 @@ def bench_decode(args, torch, B, H, synth):
                 events[l][1].record()
 
     load_step(0)
+    # the first step has no history: the prior stands in for every layer's mean density
+    B.cutoff_next_step(bt, L, k_mean, theta_prior, None, theta_sum, hist_steps, budget, rest_all)
+    for l in range(L):
+        B.build_probe(runner.cs, bt, 1, q_step[l], None, False, runner.probe, runner.probe_kv,
+                      runner.probe_norm, None, runner.workspace)
+        B.score_blocks(runner.cs, bt, runner.probe_kv, runner.probe_norm, rep[l], rep_stride,
+                       nb_end_host[-1], nb_begin, nb_end_cur, runner.scores, runner.score_stride)
+        B.select(bt, runner.scores, runner.score_stride, nb_end_host[-1], nb_begin, nb_end_cur,
+                 w.k_cap, budget, rest_all[l], runner.idx, nsel_log[l], theta_step[l], None)
     if args.pmc_pass:
         return pmc_pass(torch, B, one_step, {"workload": w.name, "launches": L})
     graph = None if args.eager else capture_graph(torch, one_step, out, "decode")
@@ -372,7 +387,7 @@ def bench_decode(args, torch, B, H, synth):
         "metric": "decode step us", "value": mean_us, "unit": "us/step", "p50_us": times[len(times) // 2] * 1e6,
         "higher_is_better": False, "steps": steps, "wall_s_incl_input_copies": t_all,
         "config": {"workload": f"{w.name}: batch {bt}, {L} layers, {n0} cached tokens, k_cap {w.k_cap}, "
-                               f"per-layer dynamic cut-off, new token appended per layer, KV cache {gb:.0f} GB bf16 in HBM",
+                               f"dynamic cut-off with the density history on the device, new token appended per layer, KV cache {gb:.0f} GB bf16 in HBM",
                    "mean_blocks_selected": float(n_sel.float().mean()),
                    "launch": "hip graph replay" if graph is not None else "eager"},
         "algorithmic_bytes_per_step": byt + score_bytes,

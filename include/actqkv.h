@@ -190,6 +190,23 @@ int actqkv_append_kv(const actqkv_shape* shape, int batch, int m, const void* k_
                      const int32_t* pos0, void* k_cache, void* v_cache, int64_t cache_seq_stride,
                      void* rep_keys, int64_t rep_seq_stride, int nb_capacity, void* stream);
 
+/* Start of a step of the dynamic cut-off (Sec. 4.2, Eq. (12); Alg. 1): keeps the history of
+ * the layers' information densities on the device and prepares the two cut-off inputs of
+ * actqkv_select for all layers of the step that begins.
+ *   theta_prev  device [n_layers][batch] fp32: the densities actqkv_select reported for the
+ *               layers of the step before (its `theta` output, one row per layer), or NULL
+ *               for the first step; they are added to the history.
+ *   theta_sum   device [batch][n_layers], n_steps device [batch], fp32: the history (sum of the
+ *               densities per layer, number of steps), zero before the first step; updated.
+ *   budget_remaining  device [batch]: set to n_layers * k_mean, the step's budget B_kv.
+ *   theta_rest_sum    device [n_layers][batch]: row l = sum over the layers j > l of the mean
+ *               density of layer j so far (theta_prior for every layer while there is no
+ *               history); pass row l to actqkv_select in layer l.
+ * One short kernel; nothing is read back. */
+int actqkv_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_prior,
+                            const float* theta_prev, float* theta_sum, float* n_steps,
+                            float* budget_remaining, float* theta_rest_sum, void* stream);
+
 /* Launch-shape hint for callers that run other kernels beside the prefill attention (for
  * instance the probe / score / select chain of the next window on a second stream, which
  * depends on the previous selection but not on the previous attention): the prefill

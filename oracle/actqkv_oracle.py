@@ -391,3 +391,42 @@ def representative_keys(k_all, block: int, r: int) -> np.ndarray:
         for slot, j in enumerate(representative_tokens(kb, r)):
             out[b, slot] = kb[j]
     return out
+
+
+# --------------------------------------------------------------------------
+# Sec. 4.2, Eq. (12) / Alg. 1 across the layers of a step and across steps
+# --------------------------------------------------------------------------
+class CutoffHistory:
+    """The means of the layers' information densities over the steps so far, which stand in
+    for the layers a step has not reached yet (Eq. (12): the sum over j > l of the mean
+    density of layer j)."""
+
+    def __init__(self, n_layers: int, theta_prior: float):
+        self.sums = [0.0] * n_layers
+        self.steps = 0
+        self.prior = float(theta_prior)
+
+    def means(self) -> List[float]:
+        return [x / self.steps if self.steps > 0 else self.prior for x in self.sums]
+
+    def rest_sums(self) -> List[float]:
+        """R^l = sum of the mean densities of the layers after l, for every l."""
+        mean = self.means()
+        return [math.fsum(mean[l + 1:]) for l in range(len(mean))]
+
+    def add_step(self, thetas: Sequence[float]) -> None:
+        for l, th in enumerate(thetas):
+            self.sums[l] += float(th)
+        self.steps += 1
+
+
+def step_budgets(thetas: Sequence[float], rest_sums: Sequence[float], k_mean: float) -> List[float]:
+    """Second loop of Alg. 1 for one step: B_kv starts at L * k; layer l takes
+    B^l = Theta^l / (Theta^l + R^l) * B_kv and leaves the rest."""
+    b_kv = len(thetas) * float(k_mean)
+    out = []
+    for th, rest in zip(thetas, rest_sums):
+        b_l = layer_budget(float(th), float(rest), b_kv)
+        out.append(b_l)
+        b_kv -= b_l
+    return out

@@ -54,6 +54,7 @@ SIGNATURES = {
     "actqkv_retrieval_attention": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
                                         _vp, _vp, _vp, _sz, _vp]),
     "actqkv_append_kv": (_i, [_shp, _i, _i, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _vp]),
+    "actqkv_cutoff_next_step": (_i, [_i, _i, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_set_attention_cus": (_i, [_i]),
     "actqkv_copy_bytes": (_i, [_vp, _vp, _sz, _vp]),
     "actqkv_last_error": (ctypes.c_char_p, []),
@@ -129,6 +130,14 @@ def append_kv(shape: CShape, batch: int, m: int, k_new, v_new, pos0, k_cache, v_
         ctypes.byref(shape), batch, m, _ptr(k_new, st), _ptr(v_new, st), _ptr(pos0, torch.int32),
         _ptr(k_cache, st), _ptr(v_cache, st), cache_seq_stride, _ptr(rep_keys, st), rep_seq_stride,
         nb_capacity, _stream(stream)))
+
+
+def cutoff_next_step(batch: int, n_layers: int, k_mean: float, theta_prior: float, theta_prev,
+                     theta_sum, n_steps, budget_remaining, theta_rest_sum, stream=None) -> None:
+    f = torch.float32
+    _check(load_library().actqkv_cutoff_next_step(
+        batch, n_layers, k_mean, theta_prior, _ptr(theta_prev, f), _ptr(theta_sum, f), _ptr(n_steps, f),
+        _ptr(budget_remaining, f), _ptr(theta_rest_sum, f), _stream(stream)))
 
 
 def set_attention_cus(cus: int) -> None:

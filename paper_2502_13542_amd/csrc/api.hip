@@ -359,6 +359,23 @@ int actqkv_append_kv(const actqkv_shape* shape, int batch, int m, const void* k_
                        rep_seq_stride, nb_capacity, static_cast<hipStream_t>(stream));
 }
 
+int actqkv_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_prior,
+                            const float* theta_prev, float* theta_sum, float* n_steps,
+                            float* budget_remaining, float* theta_rest_sum, void* stream) {
+  ACTQKV_TRY(check_batch(batch));
+  if (n_layers < 1 || n_layers > 1024)
+    return set_error(ACTQKV_ESHAPE, "n_layers %d not supported (1..1024)", n_layers);
+  if (!(k_mean > 0.f)) return set_error(ACTQKV_EINVAL, "k_mean must be positive");
+  if (!(theta_prior >= 0.f)) return set_error(ACTQKV_EINVAL, "theta_prior must not be negative");
+  ACTQKV_OPTIONAL_SMALL(theta_prev, 4);
+  ACTQKV_REQUIRE_SMALL(theta_sum, 4);
+  ACTQKV_REQUIRE_SMALL(n_steps, 4);
+  ACTQKV_REQUIRE_SMALL(budget_remaining, 4);
+  ACTQKV_REQUIRE_SMALL(theta_rest_sum, 4);
+  return launch_cutoff_next_step(batch, n_layers, k_mean, theta_prior, theta_prev, theta_sum, n_steps,
+                                 budget_remaining, theta_rest_sum, static_cast<hipStream_t>(stream));
+}
+
 int actqkv_set_attention_cus(int cus) {
   if (cus < 1 || cus > 256) return set_error(ACTQKV_EINVAL, "set_attention_cus: %d not in 1..256", cus);
   g_attention_cus.store(cus, std::memory_order_relaxed);

@@ -78,4 +78,8 @@ int launch_append(const actqkv_shape& sh, int batch, int m, const void* k_new, c
                   const int32_t* pos0, void* k_cache, void* v_cache, int64_t cache_stride,
                   void* rep_keys, int64_t rep_stride, int nb_capacity, hipStream_t stream);
 
+int launch_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_prior,
+                            const float* theta_prev, float* theta_sum, float* n_steps,
+                            float* budget_remaining, float* theta_rest_sum, hipStream_t stream);
+
 }  // namespace actqkv

@@ -129,3 +129,12 @@ def test_append_kv_rejects(lib):
     assert call(k=None) == -1 and call(pos0=None) == -1 and call(vc=None) == -1
     assert call(k=A16 + 2) == -3 and call(cs=12) == -3
     assert call(batch=2, cs=8) == -1                       # stride smaller than one sequence's cache
+
+
+def test_cutoff_next_step_rejects(lib):
+    f = ctypes.c_float
+    call = lambda batch=2, L=32, k=8.0, prior=6.0, prev=A16, ts=A16, ns=A16, b=A16, r=A16: \
+        lib.actqkv_cutoff_next_step(batch, L, f(k), f(prior), prev, ts, ns, b, r, None)
+    assert call(batch=0) == -1 and call(k=0.0) == -1 and call(prior=-1.0) == -1
+    assert call(L=0) == -2 and call(L=2000) == -2
+    assert call(ts=None) == -1 and call(b=None) == -1 and call(r=A16 + 2) == -3

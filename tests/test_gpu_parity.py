@@ -423,3 +423,46 @@ def test_append_kv_drops_tokens_behind_the_capacity():
     torch.cuda.synchronize()
     assert torch.equal(kc.cpu(), H.blocked_k(k[:128], sh, 1)) and torch.equal(vc.cpu(), H.blocked_vt(v[:128], sh, 1))
     assert bool((guard_k == 7).all()) and bool((guard_v == 7).all())
+
+
+# ---------------------------------------------------------------- cut-off across layers and steps
+def test_cutoff_history_across_layers_and_steps():
+    """Alg. 1 with the history of densities kept on the device: every step, every layer's
+    budget, count and selection against the oracle, for three sequences with different scores."""
+    L, bt, steps, k_cap, k_mean, n = 6, 3, 5, 16, 5.0, 200
+    prior = math.log(n)
+    rng = np.random.default_rng(77)
+    sharp = rng.uniform(0.5, 12.0, size=(L, bt))            # how peaked each layer's scores are
+    theta_sum = torch.zeros(bt, L, device=DEV); n_steps = torch.zeros(bt, device=DEV)
+    budget = torch.zeros(bt, device=DEV); rest = torch.zeros(L, bt, device=DEV)
+    theta_step = torch.zeros(L, bt, device=DEV)
+    idx = torch.zeros(bt, k_cap, dtype=torch.int32, device=DEV)
+    n_sel = torch.zeros(L, bt, dtype=torch.int32, device=DEV)
+    b_out = torch.zeros(L, bt, device=DEV)
+    nb_end = torch.full((bt,), n, dtype=torch.int32, device=DEV)
+    hists = [orc.CutoffHistory(L, prior) for _ in range(bt)]
+    for t in range(steps):
+        B.cutoff_next_step(bt, L, k_mean, prior, theta_step if t > 0 else None, theta_sum, n_steps, budget, rest)
+        torch.cuda.synchronize()
+        want_rest = np.array([h.rest_sums() for h in hists]).T                      # [L][bt]
+        assert np.allclose(rest.cpu().numpy(), want_rest, rtol=1e-5, atol=1e-6), f"rest sums, step {t}"
+        assert np.allclose(budget.cpu().numpy(), L * k_mean)
+        scores = rng.standard_normal((L, bt, n)).astype(np.float32) * 0.05
+        scores[:, :, :8] += (sharp[:, :, None] * rng.uniform(0.5, 1.0, size=(L, bt, 8))).astype(np.float32) * 0.1
+        sd = torch.from_numpy(scores).to(DEV)
+        for l in range(L):
+            B.select(bt, sd[l], n, n, 0, nb_end, k_cap, budget, rest[l], idx, n_sel[l], theta_step[l], b_out[l])
+        torch.cuda.synchronize()
+        for s in range(bt):
+            thetas = [orc.information_density(f64(scores[l, s])) for l in range(L)]
+            assert np.allclose(theta_step[:, s].cpu().numpy(), thetas, atol=TOL_THETA)
+            b_want = orc.step_budgets(thetas, hists[s].rest_sums(), k_mean)
+            assert np.allclose(b_out[:, s].cpu().numpy(), b_want, rtol=TOL_BUDGET, atol=TOL_BUDGET)
+            for l in range(L):
+                if abs(b_want[l] + 0.5 - round(b_want[l] + 0.5)) > 1e-3:            # not at a rounding edge
+                    assert int(n_sel[l, s]) == orc.cutoff_count(b_want[l], k_cap, n), f"E, step {t} layer {l} seq {s}"
+            hists[s].add_step(thetas)
+    B.cutoff_next_step(bt, L, k_mean, prior, theta_step, theta_sum, n_steps, budget, rest)
+    torch.cuda.synchronize()
+    assert np.allclose(n_steps.cpu().numpy(), steps)
+    assert np.allclose(theta_sum.cpu().numpy() / steps, np.array([h.means() for h in hists]), rtol=1e-5)

@@ -394,3 +394,33 @@ def test_representative_tokens_against_brute_force_and_torch_recipe():
     want = synth.pick_rep_keys(k, 128, 4).numpy()
     got = orc.representative_keys(k.numpy(), 128, 4)
     assert got.shape == want.shape and np.array_equal(got, want)
+
+
+# ---------------------------------------------------------------- Eq. (12) across layers and steps
+def test_cutoff_history_means_rest_sums_and_budgets():
+    rng = np.random.default_rng(5)
+    L, T, k = 6, 9, 4.0
+    th = rng.uniform(1.0, 6.0, size=(T, L))
+    hist = orc.CutoffHistory(L, theta_prior=2.5)
+    assert hist.rest_sums() == pytest.approx([2.5 * (L - 1 - l) for l in range(L)])   # no history: the prior
+    for t in range(T):
+        rest = hist.rest_sums()
+        if t > 0:
+            mean = th[:t].mean(axis=0)
+            want = np.concatenate([np.cumsum(mean[::-1])[::-1][1:], [0.0]])           # suffix sums by numpy
+            assert rest == pytest.approx(want, rel=1e-12)
+        b = orc.step_budgets(th[t], rest, k)
+        assert sum(b) == pytest.approx(L * k, rel=1e-12)      # the last layer takes what is left
+        assert all(x > 0 for x in b)
+        hist.add_step(th[t])
+    assert hist.means() == pytest.approx(th.mean(axis=0), rel=1e-12)
+
+
+def test_cutoff_constant_density_gives_every_layer_k():
+    # equal densities in all layers and steps: B^l = B_kv_left / (L - l) = k for every layer
+    L, k = 8, 5.0
+    hist = orc.CutoffHistory(L, theta_prior=3.0)
+    for _ in range(3):
+        b = orc.step_budgets([3.0] * L, hist.rest_sums(), k)
+        assert b == pytest.approx([k] * L, rel=1e-12)
+        hist.add_step([3.0] * L)
