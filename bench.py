@@ -179,7 +179,10 @@ def bench_prefill(args, torch, B, H, synth):
         pipe.run(q, kc, vc, repd, out, overlap, events, args.chunk)
 
     if args.pmc_pass:
-        return pmc_pass(torch, B, one_step, {"workload": w.name, "launches": n_win})
+        if not args.no_overlap:
+            B.set_attention_cus(args.attention_cus)
+        return pmc_pass(torch, B, lambda: one_step(overlap=not args.no_overlap),
+                        {"workload": w.name, "windows": n_win, "windows_per_launch": args.chunk})
     def timed(run, steps):
         for _ in range(args.warmup):
             run()
@@ -206,14 +209,21 @@ def bench_prefill(args, torch, B, H, synth):
         if args.steps > 3:
             elapsed = timed(graph_serial.replay if graph_serial is not None else one_step, args.steps) * args.steps
 
-    # ---- roofline of the dominant kernel: the prefill attention launch, one eager pass
+    # ---- roofline of the dominant kernel: the prefill attention launches of one eager pass in
+    # the schedule that was timed, events on the stream the attention runs on
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_win)]
-    one_step(ev)
+    if overlap:
+        B.set_attention_cus(args.attention_cus)
+    one_step(ev, overlap)
     torch.cuda.synchronize()
+    if overlap:
+        B.set_attention_cus(256)
     n_sel = nsel_log.cpu().tolist()
     flops = sum(attention_flops(sh, plan.w0[t], plan.rows[t], n_sel[t], H.local_start(sh, plan.w0[t]))
                 for t in range(n_win))
-    attn_ms = sum(a.elapsed_time(b) for (a, b) in ev)
+    starts = list(range(0, n_win, args.chunk)) if overlap else list(range(n_win))
+    attn_ms = sum(ev[t][0].elapsed_time(ev[t][1]) for t in starts)
+    n_launch = len(starts)
     achieved = flops / (attn_ms * 1e-3) / 1e12
     res = {
         "metric": "prefill retrieval-attn tokens/s per layer @128K" if not args.n_ctx and
@@ -234,10 +244,14 @@ def bench_prefill(args, torch, B, H, synth):
                    "ms_per_step_window_order": serial_s * 1e3},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, **traffic_fields(w.name),
-                     "kernel": "actqkv_retrieval_attention launch (attn_prefill_mfma_kernel)",
-                     "avg_launch_us": attn_ms * 1e3 / n_win,
-                     "algorithmic_gflop_per_launch": flops / n_win / 1e9,
-                     "timing": "HIP events around every attention launch of one eager pass of the step"},
+                     "kernel": ("actqkv_retrieval_attention launch of %d windows (attn_prefill_mfma_queued_kernel)"
+                                % args.chunk) if overlap else
+                               "actqkv_retrieval_attention launch (attn_prefill_mfma_kernel)",
+                     "avg_launch_us": attn_ms * 1e3 / n_launch,
+                     "windows_per_launch": n_win / n_launch,
+                     "algorithmic_gflop_per_launch": flops / n_launch / 1e9,
+                     "timing": "HIP events, on the stream the attention runs on, around every attention "
+                               "launch of one eager pass of the step in the timed schedule"},
     }
     if not args.no_cpu_baseline:
         T = n_win
@@ -415,7 +429,7 @@ def main() -> int:
     ap.add_argument("--decode-layers", type=int, default=0, help="override the layer count (testing)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="prefill: one stream, strictly in window order")
-    ap.add_argument("--chunk", type=int, default=8,
+    ap.add_argument("--chunk", type=int, default=16,
                     help="prefill, two streams: windows per hand-over between the streams")
     ap.add_argument("--attention-cus", type=int, default=192,
                     help="prefill, two streams: compute units the attention may fill")

@@ -153,6 +153,9 @@ int actqkv_select(int batch, const float* scores, int64_t score_stride, int nb_c
  *   q        [batch][m][H][D], storage dtype.
  *   k_cache, v_cache  blocked caches (layouts above), seq_stride = elements between
  *            two sequences; they already hold the window's own keys and values.
+ *            seq_stride = 0 makes all batch entries read the same cache: the entries are then
+ *            several windows of one sequence (each with its own n_ctx, idx, n_sel, q and out),
+ *            whose attentions do not depend on each other.
  *   n_ctx    device int32 [batch]: valid tokens in the cache, the m current ones
  *            included; the window is [w0, w0+m) with w0 = n_ctx - m.
  *   idx, n_sel  from actqkv_select ([batch][k_cap], [batch]); entries outside

@@ -113,6 +113,7 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
 
 // Compute units the prefill attention may fill (actqkv_set_attention_cus).
 static std::atomic<int> g_attention_cus{256};
+int attention_cus() { return g_attention_cus.load(std::memory_order_relaxed); }
 
 // Enough key splits to give every compute unit it may fill a workgroup, never more than 8
 // per query tile; what does not divide evenly goes to the last query tiles of the window.
@@ -301,7 +302,8 @@ int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, cons
   ACTQKV_REQUIRE_PTR(out);
   ACTQKV_OPTIONAL_SMALL(lse, 4);
   const int64_t per_seq = int64_t(nb_capacity) * shape->n_kv_heads * shape->block_size * shape->head_dim;
-  if (batch > 1 && seq_stride < per_seq)
+  // seq_stride 0: all batch entries read one cache (several windows of one sequence)
+  if (batch > 1 && seq_stride != 0 && seq_stride < per_seq)
     return set_error(ACTQKV_EINVAL, "seq_stride %lld < one sequence's cache %lld", (long long)seq_stride,
                      (long long)per_seq);
   if (seq_stride % 8 != 0) return set_error(ACTQKV_EALIGN, "seq_stride must be a multiple of 8 elements");

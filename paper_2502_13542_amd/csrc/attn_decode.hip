@@ -296,7 +296,7 @@ int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* 
   const int group = sh.n_q_heads / sh.n_kv_heads;
   const int n_waves = kDcMaxWaves;
   const size_t lds = size_t(n_waves) * group * (kDcD + 2) * sizeof(float);
-  if (p.n_wg > 1 && size_t(batch) * sh.n_kv_heads * sizeof(unsigned int) > kCounterBytes)
+  if (p.n_wg > 1 && size_t(batch) * sh.n_kv_heads > kTicketCounters)
     return set_error(ACTQKV_EINVAL, "decode attention: more split (sequence, KV head) pairs than ticket counters");
   hipLaunchKernelGGL(attn_decode_kernel, dim3(p.n_wg, sh.n_kv_heads, batch), dim3(n_waves * 64), lds,
                      stream, p);

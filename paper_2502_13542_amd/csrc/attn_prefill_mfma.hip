@@ -26,6 +26,8 @@
 // a permuted order (bits 2 and 3 of the row index swapped); the permutation is
 // undone for free because a lane's 8 consecutive accumulator registers then hold
 // 8 consecutive keys.
+#include <algorithm>
+
 #include "common.h"
 #include "launch.h"
 
@@ -40,6 +42,7 @@ constexpr int kPfMaxTiles = 96;                      // initial + selected (<= 6
 constexpr int kPfLdsBytes = 2 * 2 * kTileElems * 2 + kPfMaxTiles * 12;  // 2 stages x (K, V^T) + tile table
 constexpr int kPfPartWords = 17;                     // 64-bit words per lane: 16 x 4 bf16 + (max, sum)
 constexpr int kMaxPfSplits = 8;
+constexpr int kPfQueueDone = 128;                    // index of the "left" counter behind the per-head queue counters
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -72,6 +75,8 @@ struct PfParams {
   unsigned int* counters;  // one ticket counter per (sequence, query tile, KV head), zero between launches
   int m, n_q_heads, n_kv_heads, n_init, n_local;
   int s_lo, rem, slots, n_qtiles;   // pieces per query tile (PfSplits)
+  int items_per_head, wgs_per_head; // work items and workgroups of one KV head
+  unsigned int* queue;              // per KV head: items handed out beyond the first round; [kPfQueueDone]: workgroups that left
   float scale_log2e;
 };
 
@@ -95,19 +100,20 @@ __device__ __forceinline__ void store_rows(const PfParams& p, const f32x16 (&acc
     p.lse[(size_t(s) * p.n_q_heads + head) * p.m + my_row] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
 }
 
-__global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams p) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// One work item: piece `slot` of the query tiles of (sequence s, KV head hk).
+template <bool kInLoop>
+__device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* lds, int hk, int slot, int s) {
+  // (inside an item loop the thread index is made opaque, so that nothing derived from it is
+  // hoisted out of the loop and kept in registers across the whole item)
+  int tid = threadIdx.x;
+  if (kInLoop) asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, half = lane >> 5;
   const int group = p.n_q_heads / p.n_kv_heads;
   const int waves_per_head = kPfWaves / group;
   const int pos_per_wg = 32 * waves_per_head;
 
-  // blockIdx.x = slot * Hk + hk: consecutive ids differ in hk, and ids are dealt round-robin
-  // to the XCDs, so each XCD serves few KV heads.  The slots of a (sequence, KV head) are the
-  // pieces of its query tiles, in order.
-  const int hk = blockIdx.x % p.n_kv_heads;
-  const int slot = blockIdx.x / p.n_kv_heads;
+  // The slots of a (sequence, KV head) are the pieces of its query tiles, in order.
   const int n_lo = p.n_qtiles - p.rem;
   int qtile, split, splits;
   if (slot < n_lo * p.s_lo) {
@@ -120,7 +126,6 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
     qtile = n_lo + r / splits;
     split = r - (qtile - n_lo) * splits;
   }
-  const int s = blockIdx.y;
 
   // the selected block indices are requested together with the two scalars they are used
   // with, not after them (one memory round trip less before the first tile can be fetched)
@@ -406,6 +411,46 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams 
   if (row_ok) store_rows(p, acc_o, m_all, l_all, s, my_row, head, half);
 }
 
+// blockIdx.x = w * Hk + hk: consecutive ids differ in hk, and ids are dealt round-robin to the
+// XCDs, so each XCD serves few KV heads and that head's tiles stay in its L2.  The items of a
+// KV head are its (sequence, slot) pairs.  If there are no more of them than workgroups, each
+// workgroup takes one.  Otherwise (several windows in one call, fewer compute units than
+// items) the workgroups of a head draw the remaining items from a counter: windows differ in
+// how many blocks they retrieve, and a fixed assignment would wait for the unluckiest
+// workgroup.  Nobody waits for anybody: a workgroup leaves when the counter runs out, and the
+// last one to leave puts the counters back to zero for the next launch.
+__global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_kernel(PfParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+  const int item = blockIdx.x / p.n_kv_heads, s = item / p.slots;
+  attn_prefill_item<false>(p, lds, blockIdx.x % p.n_kv_heads, item - s * p.slots, s);
+}
+
+__global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_queued_kernel(PfParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+  __shared__ int next_item;
+  const int hk = blockIdx.x % p.n_kv_heads;
+  int item = blockIdx.x / p.n_kv_heads;
+  while (item < p.items_per_head) {
+    const int s = item / p.slots;
+    attn_prefill_item<true>(p, lds, hk, item - s * p.slots, s);
+    __syncthreads();                         // everybody is done with the LDS tiles of this item
+    if (threadIdx.x == 0)
+      next_item = p.wgs_per_head + int(__hip_atomic_fetch_add(p.queue + hk, 1u, __ATOMIC_RELAXED,
+                                                              __HIP_MEMORY_SCOPE_AGENT));
+    __syncthreads();
+    item = next_item;
+  }
+  if (threadIdx.x == 0) {
+    unsigned int* done = p.queue + kPfQueueDone;
+    const unsigned int t = __hip_atomic_fetch_add(done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (t == gridDim.x - 1u) {
+      for (int h = 0; h < p.n_kv_heads; ++h)
+        __hip_atomic_store(p.queue + h, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
 bool prefill_mfma_supported(const actqkv_shape& sh, int m) {
   const int g = sh.n_q_heads / sh.n_kv_heads;
   // longest possible tile list: initial + selected + local + window (+ 2 partial blocks)
@@ -434,6 +479,9 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_mfma_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_mfma_queued_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes);
     if (e != hipSuccess) return set_error(ACTQKV_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
     attr_set = true;
   }
@@ -463,10 +511,18 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
   p.scale_log2e = scale * 1.4426950408889634f;
   if (splits.slots < p.n_qtiles || splits.slots != splits.s_lo * p.n_qtiles + splits.rem)
     return set_error(ACTQKV_EINVAL, "prefill attention: inconsistent split of the key tiles");
-  dim3 grid(splits.slots * sh.n_kv_heads, batch);
-  if (splits.slots > p.n_qtiles && size_t(batch) * p.n_qtiles * sh.n_kv_heads * sizeof(unsigned int) > kCounterBytes)
+  if (splits.slots > p.n_qtiles && size_t(batch) * p.n_qtiles * sh.n_kv_heads > kTicketCounters)
     return set_error(ACTQKV_EINVAL, "prefill attention: more split query tiles than ticket counters");
-  hipLaunchKernelGGL(attn_prefill_mfma_kernel, grid, dim3(kPfThreads), kPfLdsBytes, stream, p);
+  if (sh.n_kv_heads > kPfQueueDone)
+    return set_error(ACTQKV_ESHAPE, "prefill attention: more than %d KV heads", kPfQueueDone);
+  p.items_per_head = splits.slots * batch;
+  p.wgs_per_head = std::min(p.items_per_head, std::max(1, attention_cus() / sh.n_kv_heads));
+  p.queue = counters + kTicketCounters;
+  dim3 grid(p.wgs_per_head * sh.n_kv_heads);
+  if (p.items_per_head > p.wgs_per_head)
+    hipLaunchKernelGGL(attn_prefill_mfma_queued_kernel, grid, dim3(kPfThreads), kPfLdsBytes, stream, p);
+  else
+    hipLaunchKernelGGL(attn_prefill_mfma_kernel, grid, dim3(kPfThreads), kPfLdsBytes, stream, p);
   return hip_status("attention (prefill, matrix cores)");
 }
 

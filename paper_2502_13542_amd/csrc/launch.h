@@ -44,7 +44,10 @@ PfSplits prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap);
 constexpr size_t kPfPartialFloats = 8 * (32 + 2) * 64;
 constexpr int kMaxWindow = 8192;
 
-constexpr size_t kCounterBytes = 4096;  // 1024 uint32 tickets at the head of the workspace
+// head of the workspace: 1024 uint32 tickets, then the work queue counters of the prefill attention
+constexpr size_t kTicketCounters = 1024;
+constexpr size_t kCounterBytes = 8192;
+int attention_cus();   // compute units the prefill attention may fill (actqkv_set_attention_cus)
 constexpr int kMaxBatch = 1024;
 
 size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap);

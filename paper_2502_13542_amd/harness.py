@@ -168,24 +168,31 @@ class PrefillPipeline:
     beside the attention of earlier ones; every window keeps its own selection, and the two
     streams use separate workspaces.  The results are those of window order."""
 
+    MAX_CHUNK = 16
+
     def __init__(self, runner: LayerRunner, plan: PrefillPlan):
         self.runner, self.plan = runner, plan
         dev = runner.device
         self.idx = torch.full((plan.n_windows, runner.k_cap), -1, dtype=torch.int32, device=dev)
         self.n_sel = torch.zeros(plan.n_windows, dtype=torch.int32, device=dev)
-        self.ws_attn = torch.zeros_like(runner.workspace)
+        ws = B.workspace_bytes(runner.cs, self.MAX_CHUNK, runner.m, runner.nb_capacity, runner.k_cap)
+        self.ws_attn = torch.zeros(ws, dtype=torch.uint8, device=dev)
         self.side = torch.cuda.Stream(device=dev)
 
     def run(self, q: torch.Tensor, k_cache, v_cache, rep_keys, out: torch.Tensor, overlap: bool = True,
-            events=None, chunk: int = 8) -> None:
+            events=None, chunk: int = 16) -> None:
         """q, out [N][H][D].  events: optional per-window (start, end) event pairs recorded around
-        the attention call (window order only).  chunk: with overlap, the second stream picks up
-        the attention calls of `chunk` windows at a time, once the last of them has its selection
-        (one dependency between the streams per chunk, not per window)."""
+        the attention call of a window; with overlap, the pair of a chunk's first window brackets
+        the chunk's one call, on the stream it runs on.  chunk: with overlap, the second stream picks up
+        the attention of `chunk` windows at a time, once the last of them has its selection:
+        one dependency between the streams per chunk, and ONE attention call for the chunk (the
+        windows are batch entries that share the cache; with that many query tiles in a launch
+        the key tiles need not be cut into pieces, so nothing has to be merged)."""
         r, plan = self.runner, self.plan
         sh, cs = r.shape, r.cs
         nb_begin = sh.n_init // sh.block_size
         cur = torch.cuda.current_stream()
+        chunk = max(1, min(chunk, self.MAX_CHUNK))
 
         def attend(t, stream):
             w0, rows = plan.w0[t], plan.rows[t]
@@ -220,8 +227,20 @@ class PrefillPipeline:
                 done = torch.cuda.Event()
                 done.record(cur)
                 self.side.wait_event(done)
-                for u in pending:
-                    attend(u, self.side)
+                t0, n_p = pending[0], len(pending)
+                if events is not None:
+                    events[t0][0].record(self.side)
+                if n_p > 1 and all(plan.rows[u] == r.m for u in pending):
+                    w0 = plan.w0[t0]
+                    B.retrieval_attention(cs, n_p, r.m, q[w0:w0 + n_p * r.m], k_cache, v_cache, 0,
+                                          r.nb_capacity, plan.n_ctx[t0:t0 + n_p], self.idx[t0:t0 + n_p],
+                                          self.n_sel[t0:t0 + n_p], r.k_cap, out[w0:w0 + n_p * r.m], None,
+                                          self.ws_attn, self.side)
+                else:
+                    for u in pending:
+                        attend(u, self.side)
+                if events is not None:
+                    events[t0][1].record(self.side)
                 pending = []
         if overlap:
             cur.wait_stream(self.side)
