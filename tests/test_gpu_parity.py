@@ -323,6 +323,68 @@ def test_decode_step_batch(dtype, hq, hkv, n_ctxs):
         assert rel_to_max(runner.probe[s], f64(qs[s]).reshape(-1)) == 0.0   # probe is the query itself
 
 
+def test_decode_full_size_layer_as_benchmarked():
+    """One layer of configs[3] at full size in the launch configuration bench.py times: 16
+    sequences with 65536 cached tokens each (4.3 GB of keys and values), a new token appended,
+    k_cap 32 with the cut-off; the selection and the output of sampled sequences against the
+    oracle, the whole batch for finiteness and for equality between two runs."""
+    w = synth.WORKLOADS["c4_decode"]
+    sh, bt = w.shape, w.batch
+    n0 = w.n_ctx
+    nb_cap = (n0 + 256 + 127) // 128
+    hk, D = sh.n_kv_heads, sh.head_dim
+    _say(f"[case] {w.name} one layer, batch {bt}, {n0} cached tokens")
+    gen = torch.Generator(device=DEV); gen.manual_seed(w.seed)
+    kc = torch.empty(bt, nb_cap, hk, 128, D, dtype=torch.bfloat16, device=DEV).normal_(generator=gen)
+    vc = torch.empty(bt, nb_cap, hk, D, 128, dtype=torch.bfloat16, device=DEV).normal_(generator=gen)
+    u = synth.direction(w, 0, 0, DEV)
+    planted = torch.stack([torch.tensor(synth.planted_blocks(w, 0, s)) for s in range(bt)]).to(DEV)
+    sidx = torch.arange(bt, device=DEV)[:, None].expand_as(planted)
+    kc[sidx, planted] += (w.shift * u)[None, None, :, None, :].to(torch.bfloat16)
+    cs = B.c_shape(sh)
+    # representative keys of the cached blocks: largest key norm over all KV heads, position order
+    rep = torch.zeros(bt, nb_cap, sh.n_rep, hk, D, dtype=torch.bfloat16, device=DEV)
+    src = kc.permute(0, 1, 3, 2, 4)                                   # [bt][nb][Bs][Hk][D] view
+    norms = kc.float().pow(2).sum(dim=(2, 4))                         # [bt][nb][Bs]
+    top = torch.sort(torch.sort(norms, dim=2, descending=True, stable=True).indices[:, :, : sh.n_rep], dim=2).values
+    rep.copy_(torch.gather(src, 2, top[:, :, :, None, None].expand(bt, nb_cap, sh.n_rep, hk, D)))
+    del norms, src
+    q = (torch.randn(bt, 1, sh.n_q_heads, D, generator=gen, device=DEV) +
+         w.alpha * u.repeat_interleave(sh.group, dim=0)).to(torch.bfloat16)
+    k_new = torch.randn(bt, 1, hk, D, generator=gen, device=DEV).to(torch.bfloat16)
+    v_new = torch.randn(bt, 1, hk, D, generator=gen, device=DEV).to(torch.bfloat16)
+    pos0 = torch.full((bt,), n0, dtype=torch.int32, device=DEV)
+    n_ctx = torch.full((bt,), n0 + 1, dtype=torch.int32, device=DEV)
+    nb_begin, nb_end_h = H.eligible_range(sh, n0)
+    nb_end = torch.full((bt,), nb_end_h, dtype=torch.int32, device=DEV)
+    cut = synth.cutoff_state(w, nb_end_h - nb_begin, 0, 5, 0)
+    runner = H.LayerRunner(sh, bt, 1, nb_cap, w.k_cap, DEV)
+    outs = []
+    for rep_run in range(2):
+        bud = torch.full((bt,), cut[0], dtype=torch.float32, device=DEV)
+        rest = torch.full((bt,), cut[1], dtype=torch.float32, device=DEV)
+        out = torch.zeros_like(q)
+        B.append_kv(cs, bt, 1, k_new, v_new, pos0, kc, vc, kc.stride(0), rep, rep.stride(0), nb_cap)
+        runner.step(q, kc, vc, rep, n_ctx, nb_end, nb_end_h, out, bud, rest, update_stats=False, m=1)
+        torch.cuda.synchronize()
+        outs.append(out)
+    assert torch.equal(outs[0], outs[1]) and bool(torch.isfinite(outs[0].float()).all())
+    for s in (0, 7, 15):
+        k_log, v_log = _logical_from_blocked(kc[s].cpu(), vc[s].cpu(), n0 + 1)
+        assert torch.equal(k_log[n0], k_new[s, 0].cpu()) and torch.equal(v_log[n0], v_new[s, 0].cpu())
+        rep_s = rep[s, : (n0 + 1) // 128].cpu()
+        res = orc.decode_step(f64(q[s, 0]), k_log.float().numpy(), v_log.float().numpy(), f64(rep_s), n0 + 1,
+                              sh.n_init, sh.n_local, 128, w.k_cap, cut)
+        gi, gn = runner.idx[s].cpu().tolist(), int(runner.n_sel[s])
+        ref = res["out"]
+        if not check_selection(gi, gn, res, w.k_cap):
+            ref = orc.retrieval_attention(f64(q[s, 0])[None], k_log.float().numpy(), v_log.float().numpy(), n0,
+                                          gi[:gn], sh.n_init, sh.n_local, 128, sh.group)[0]
+        err = out_error(outs[0][s, 0], ref)
+        _say(f"[case] {w.name} sequence {s}: E = {gn}, output error {err:.3e}")
+        assert err < TOL_OUT["bf16"], f"decode output, sequence {s}"
+
+
 # ---------------------------------------------------------------- cache update and representatives
 def _logical_from_blocked(kc, vc, n):
     """[nb][Hk][Bs][D], [nb][Hk][D][Bs] -> K, V [n][Hk][D]."""
