@@ -221,7 +221,7 @@ def bench_prefill(args, torch, B, H, synth):
     n_sel = nsel_log.cpu().tolist()
     flops = sum(attention_flops(sh, plan.w0[t], plan.rows[t], n_sel[t], H.local_start(sh, plan.w0[t]))
                 for t in range(n_win))
-    starts = list(range(0, n_win, args.chunk)) if overlap else list(range(n_win))
+    starts = list(pipe.chunk_starts)
     attn_ms = sum(ev[t][0].elapsed_time(ev[t][1]) for t in starts)
     n_launch = len(starts)
     achieved = flops / (attn_ms * 1e-3) / 1e12
@@ -237,15 +237,15 @@ def bench_prefill(args, torch, B, H, synth):
                                f"cut-off {'on' if w.cutoff else 'off'}",
                    "windows": n_win, "mean_blocks_selected": sum(n_sel) / max(n_win, 1),
                    "launch": ("hip graph replay" if graph is not None else "eager") +
-                             (f", attention on a second stream ({args.attention_cus} of 256 CUs, {args.chunk} windows "
+                             (f", attention on a second stream ({args.attention_cus} of 256 CUs, up to {args.chunk} windows "
                               "per hand-over) beside the probe/score/select chain of the following windows"
                               if overlap
                               else ", one stream, window order"),
                    "ms_per_step_window_order": serial_s * 1e3},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, **traffic_fields(w.name),
-                     "kernel": ("actqkv_retrieval_attention launch of %d windows (attn_prefill_mfma_queued_kernel)"
-                                % args.chunk) if overlap else
+                     "kernel": ("actqkv_retrieval_attention launches of up to %d windows "
+                                "(attn_prefill_mfma_queued_kernel)" % args.chunk) if overlap else
                                "actqkv_retrieval_attention launch (attn_prefill_mfma_kernel)",
                      "avg_launch_us": attn_ms * 1e3 / n_launch,
                      "windows_per_launch": n_win / n_launch,

@@ -203,6 +203,7 @@ class PrefillPipeline:
         if overlap:
             self.side.wait_stream(cur)
         pending = []
+        self.chunk_starts = []          # first window of every attention call of this run
         for t in range(plan.n_windows):
             w0, rows = plan.w0[t], plan.rows[t]
             qw = q[w0:w0 + rows]
@@ -216,6 +217,7 @@ class PrefillPipeline:
             B.select(1, r.scores, r.score_stride, nb_cap, nb_begin, plan.nb_end[t:t + 1], r.k_cap, bud,
                      rest, self.idx[t], self.n_sel[t:t + 1], None, None)
             if not overlap:
+                self.chunk_starts.append(t)
                 if events is not None:
                     events[t][0].record()
                 attend(t, None)
@@ -228,6 +230,7 @@ class PrefillPipeline:
                 done.record(cur)
                 self.side.wait_event(done)
                 t0, n_p = pending[0], len(pending)
+                self.chunk_starts.append(t0)
                 if events is not None:
                     events[t0][0].record(self.side)
                 if n_p > 1 and all(plan.rows[u] == r.m for u in pending):
