@@ -176,7 +176,7 @@ def bench_prefill(args, torch, B, H, synth):
         runner.stats.zero_()
         if bud0 is not None:
             plan.budget.copy_(bud0)
-        pipe.run(q, kc, vc, repd, out, overlap, events, args.chunk)
+        pipe.run(q, kc, vc, repd, out, overlap, events, args.chunk, args.score_chunk)
 
     if args.pmc_pass:
         if not args.no_overlap:
@@ -237,8 +237,11 @@ def bench_prefill(args, torch, B, H, synth):
                                f"cut-off {'on' if w.cutoff else 'off'}",
                    "windows": n_win, "mean_blocks_selected": sum(n_sel) / max(n_win, 1),
                    "launch": ("hip graph replay" if graph is not None else "eager") +
-                             (f", attention on a second stream ({args.attention_cus} of 256 CUs, up to {args.chunk} windows "
-                              "per hand-over) beside the probe/score/select chain of the following windows"
+                             (f", three streams: probes, then scoring and selection ({args.score_chunk} windows per "
+                              f"hand-over), then attention ({args.attention_cus} of 256 CUs, up to {args.chunk} "
+                              "windows per launch)" if overlap and args.score_chunk > 0 else
+                              f", attention on a second stream ({args.attention_cus} of 256 CUs, up to {args.chunk} "
+                              "windows per hand-over) beside the probe/score/select chain of the following windows"
                               if overlap
                               else ", one stream, window order"),
                    "ms_per_step_window_order": serial_s * 1e3},
@@ -431,6 +434,9 @@ def main() -> int:
                     help="prefill: one stream, strictly in window order")
     ap.add_argument("--chunk", type=int, default=16,
                     help="prefill, two streams: windows per hand-over between the streams")
+    ap.add_argument("--score-chunk", type=int, default=16,
+                    help="prefill: > 0 puts scoring and selection on a stream of their own, this many "
+                         "windows behind the probe chain per hand-over")
     ap.add_argument("--attention-cus", type=int, default=192,
                     help="prefill, two streams: compute units the attention may fill")
     ap.add_argument("--pmc-pass", action="store_true",

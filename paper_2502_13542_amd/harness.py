@@ -168,7 +168,7 @@ class PrefillPipeline:
     beside the attention of earlier ones; every window keeps its own selection, and the two
     streams use separate workspaces.  The results are those of window order."""
 
-    MAX_CHUNK = 16
+    MAX_CHUNK = 32
 
     def __init__(self, runner: LayerRunner, plan: PrefillPlan):
         self.runner, self.plan = runner, plan
@@ -178,21 +178,30 @@ class PrefillPipeline:
         ws = B.workspace_bytes(runner.cs, self.MAX_CHUNK, runner.m, runner.nb_capacity, runner.k_cap)
         self.ws_attn = torch.zeros(ws, dtype=torch.uint8, device=dev)
         self.side = torch.cuda.Stream(device=dev)
+        # the probe of every window, for the schedule that scores behind the probe chain
+        dk = runner.shape.n_kv_heads * runner.shape.head_dim
+        self.probe_kv = torch.empty(plan.n_windows, dk, dtype=torch.float32, device=dev)
+        self.probe_norm = torch.empty(plan.n_windows, dtype=torch.float32, device=dev)
+        self.side_score = torch.cuda.Stream(device=dev)
 
     def run(self, q: torch.Tensor, k_cache, v_cache, rep_keys, out: torch.Tensor, overlap: bool = True,
-            events=None, chunk: int = 16) -> None:
+            events=None, chunk: int = 16, score_chunk: int = 16) -> None:
         """q, out [N][H][D].  events: optional per-window (start, end) event pairs recorded around
         the attention call of a window; with overlap, the pair of a chunk's first window brackets
         the chunk's one call, on the stream it runs on.  chunk: with overlap, the second stream picks up
         the attention of `chunk` windows at a time, once the last of them has its selection:
         one dependency between the streams per chunk, and ONE attention call for the chunk (the
         windows are batch entries that share the cache; with that many query tiles in a launch
-        the key tiles need not be cut into pieces, so nothing has to be merged)."""
+        the key tiles need not be cut into pieces, so nothing has to be merged).  score_chunk > 0
+        (with overlap) also moves scoring and selection to a stream of their own, that many
+        windows behind the probes (see _run_three_streams); 0 keeps them on the current stream."""
         r, plan = self.runner, self.plan
         sh, cs = r.shape, r.cs
         nb_begin = sh.n_init // sh.block_size
         cur = torch.cuda.current_stream()
         chunk = max(1, min(chunk, self.MAX_CHUNK))
+        if overlap and score_chunk > 0:
+            return self._run_three_streams(q, k_cache, v_cache, rep_keys, out, events, chunk, score_chunk)
 
         def attend(t, stream):
             w0, rows = plan.w0[t], plan.rows[t]
@@ -247,3 +256,68 @@ class PrefillPipeline:
                 pending = []
         if overlap:
             cur.wait_stream(self.side)
+
+    def _run_three_streams(self, q, k_cache, v_cache, rep_keys, out, events, chunk, score_chunk) -> None:
+        """The selection chain cut in two as well.  The probe of a window (statistics, bias,
+        weights) depends only on the statistics of the window before; scoring and selection
+        depend on the window's probe and on the budget the window before left.  So the probes run
+        ahead on the current stream, scoring and selection follow on a second stream
+        `score_chunk` windows at a time, and the attention on a third, `chunk` windows at a time."""
+        r, plan = self.runner, self.plan
+        sh, cs = r.shape, r.cs
+        nb_begin = sh.n_init // sh.block_size
+        cur, mid, last = torch.cuda.current_stream(), self.side_score, self.side
+        mid.wait_stream(cur)
+        last.wait_stream(cur)
+        self.chunk_starts = []
+        to_score, to_attend = [], []
+        for t in range(plan.n_windows):
+            w0, rows = plan.w0[t], plan.rows[t]
+            B.build_probe(cs, 1, rows, q[w0:w0 + rows], r.stats, True, r.probe, self.probe_kv[t],
+                          self.probe_norm[t:t + 1], None, r.workspace)
+            to_score.append(t)
+            final = t == plan.n_windows - 1
+            if len(to_score) < score_chunk and not final:
+                continue
+            probed = torch.cuda.Event()
+            probed.record(cur)
+            mid.wait_event(probed)
+            for u in to_score:
+                bud = None if plan.budget is None else plan.budget[u:u + 1]
+                rest = None if plan.rest is None else plan.rest[u:u + 1]
+                nb_cap = min(max(plan.nb_end_host[u], nb_begin), r.nb_capacity)
+                B.score_blocks(cs, 1, self.probe_kv[u], self.probe_norm[u:u + 1], rep_keys, 0, nb_cap,
+                               nb_begin, plan.nb_end[u:u + 1], r.scores, r.score_stride, mid)
+                B.select(1, r.scores, r.score_stride, nb_cap, nb_begin, plan.nb_end[u:u + 1], r.k_cap, bud,
+                         rest, self.idx[u], self.n_sel[u:u + 1], None, None, mid)
+            to_attend += to_score
+            to_score = []
+            if len(to_attend) < chunk and not final:
+                continue
+            selected = torch.cuda.Event()
+            selected.record(mid)
+            last.wait_event(selected)
+            for a0 in range(0, len(to_attend), chunk):
+                piece = to_attend[a0:a0 + chunk]
+                t0, n_p = piece[0], len(piece)
+                self.chunk_starts.append(t0)
+                if events is not None:
+                    events[t0][0].record(last)
+                if n_p > 1 and all(plan.rows[u] == r.m for u in piece):
+                    w0 = plan.w0[t0]
+                    B.retrieval_attention(cs, n_p, r.m, q[w0:w0 + n_p * r.m], k_cache, v_cache, 0,
+                                          r.nb_capacity, plan.n_ctx[t0:t0 + n_p], self.idx[t0:t0 + n_p],
+                                          self.n_sel[t0:t0 + n_p], r.k_cap, out[w0:w0 + n_p * r.m], None,
+                                          self.ws_attn, last)
+                else:
+                    for u in piece:
+                        w0, rows = plan.w0[u], plan.rows[u]
+                        B.retrieval_attention(cs, 1, rows, q[w0:w0 + rows], k_cache, v_cache, 0,
+                                              r.nb_capacity, plan.n_ctx[u:u + 1], self.idx[u],
+                                              self.n_sel[u:u + 1], r.k_cap, out[w0:w0 + rows], None,
+                                              self.ws_attn, last)
+                if events is not None:
+                    events[t0][1].record(last)
+            to_attend = []
+        cur.wait_stream(mid)
+        cur.wait_stream(last)

@@ -118,10 +118,11 @@ def test_c3_128k_full_size_sampled_windows():
 
 
 def test_c3_128k_two_stream_pipeline_as_benchmarked():
-    """configs[2] at full size the way bench.py times it: attention on a second stream with
-    192 of the 256 compute units, the selection chain of the next window beside it.  Every
-    window's selection must equal the one found in window order; the attention of sampled
-    windows is checked against the oracle and all rows against the window-order result."""
+    """configs[2] at full size the way bench.py times it: the probes on one stream, scoring and
+    selection 16 windows behind them on a second, the attention of 16 windows per launch on a
+    third with 192 of the 256 compute units.  Every window's selection must equal the one found
+    in window order; the attention of sampled windows is checked against the oracle and all
+    rows against the window-order result.  The two-stream schedule is checked the same way."""
     w = synth.WORKLOADS["c3_128k"]
     sh = w.shape
     _say(f"[case] {w.name} two streams N={w.n_ctx} seed={w.seed}")
@@ -152,6 +153,19 @@ def test_c3_128k_two_stream_pipeline_as_benchmarked():
     finally:
         B.set_attention_cus(256)
     assert torch.equal(pipe.idx, idx_order) and torch.equal(pipe.n_sel, nsel_order)
+    # the same with scoring and selection kept on the probes' stream
+    out_b = torch.zeros_like(qd)
+    runner.reset()
+    plan.budget.copy_(bud0)
+    pipe.idx.fill_(-1)
+    B.set_attention_cus(192)
+    try:
+        pipe.run(qd, kc, vc, repd, out_b, overlap=True, score_chunk=0)
+        torch.cuda.synchronize()
+    finally:
+        B.set_attention_cus(256)
+    assert torch.equal(pipe.idx, idx_order) and torch.equal(pipe.n_sel, nsel_order)
+    assert torch.equal(out_b, out_two)
     diff = (out_two.float() - out_order.float()).abs().max().item()
     scale = out_order.float().abs().max().item()
     assert diff <= TOL_OUT["bf16"] * scale, f"two streams vs window order: {diff}"
