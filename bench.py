@@ -437,7 +437,7 @@ def main() -> int:
     ap.add_argument("--score-chunk", type=int, default=16,
                     help="prefill: > 0 puts scoring and selection on a stream of their own, this many "
                          "windows behind the probe chain per hand-over")
-    ap.add_argument("--attention-cus", type=int, default=192,
+    ap.add_argument("--attention-cus", type=int, default=224,
                     help="prefill, two streams: compute units the attention may fill")
     ap.add_argument("--pmc-pass", action="store_true",
                     help="one calibration copy and one eager pass, for a rocprofv3 --pmc run")

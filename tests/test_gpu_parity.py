@@ -120,7 +120,7 @@ def test_c3_128k_full_size_sampled_windows():
 def test_c3_128k_two_stream_pipeline_as_benchmarked():
     """configs[2] at full size the way bench.py times it: the probes on one stream, scoring and
     selection 16 windows behind them on a second, the attention of 16 windows per launch on a
-    third with 192 of the 256 compute units.  Every window's selection must equal the one found
+    third with 224 of the 256 compute units.  Every window's selection must equal the one found
     in window order; the attention of sampled windows is checked against the oracle and all
     rows against the window-order result.  The two-stream schedule is checked the same way."""
     w = synth.WORKLOADS["c3_128k"]
@@ -146,7 +146,7 @@ def test_c3_128k_two_stream_pipeline_as_benchmarked():
     runner.reset()
     plan.budget.copy_(bud0)
     pipe.idx.fill_(-1)
-    B.set_attention_cus(192)
+    B.set_attention_cus(224)
     try:
         pipe.run(qd, kc, vc, repd, out_two, overlap=True)
         torch.cuda.synchronize()
@@ -158,7 +158,7 @@ def test_c3_128k_two_stream_pipeline_as_benchmarked():
     runner.reset()
     plan.budget.copy_(bud0)
     pipe.idx.fill_(-1)
-    B.set_attention_cus(192)
+    B.set_attention_cus(224)
     try:
         pipe.run(qd, kc, vc, repd, out_b, overlap=True, score_chunk=0)
         torch.cuda.synchronize()
