@@ -424,3 +424,42 @@ def test_cutoff_constant_density_gives_every_layer_k():
         b = orc.step_budgets([3.0] * L, hist.rest_sums(), k)
         assert b == pytest.approx([k] * L, rel=1e-12)
         hist.add_step([3.0] * L)
+
+
+# ---------------------------------------------------------------- tests/golden: hand-worked cases
+def _fixture(name):
+    import os
+    out = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", name)):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, val = line.split(":", 1)
+        rows = [[float(x) for x in row.split()] for row in val.split(";")]
+        out[key.strip()] = np.array(rows if len(rows) > 1 else rows[0])
+    return out
+
+
+def test_golden_fixtures():
+    f = _fixture("eq7_9_probe.txt")
+    z, s2 = orc.running_stats_literal(f["q"])
+    assert np.array_equal(z, f["mean"]) and np.array_equal(s2, f["var"])
+    phi = orc.activation_bias(f["q"], z, s2)
+    assert np.allclose(phi, f["phi"], rtol=0, atol=1e-15)
+    probe, w = orc.probe_query(f["q"], phi)
+    assert np.allclose(w, f["weights"], rtol=0, atol=1e-15) and np.allclose(probe, f["probe"], rtol=0, atol=1e-14)
+    st = orc.RunningStats(2)                                  # the streaming form gives the same
+    z2, s22 = st.update(f["q"])
+    assert np.allclose(z2, f["mean"]) and np.allclose(s22, f["var"])
+
+    g = _fixture("eq11_12_cutoff.txt")
+    theta = orc.information_density(np.log(g["scores_ln"]))
+    assert theta == pytest.approx(float(g["theta_over_ln2"][0]) * math.log(2.0), rel=1e-14)
+    budgets = orc.step_budgets(g["densities"], g["rest"], float(g["k"][0]))
+    assert budgets == pytest.approx(g["budgets"].tolist(), rel=1e-14)
+    b_kv = len(budgets) * float(g["k"][0])
+    for th, rest, want in zip(g["densities"], g["rest"], g["budgets"]):
+        assert orc.layer_budget(float(th), float(rest), b_kv) == pytest.approx(want, rel=1e-14)
+        b_kv -= want
+    counts = [orc.cutoff_count(b, int(g["k_cap"][0]), 40) for b in budgets]
+    assert counts == [int(c) for c in g["counts"]]
