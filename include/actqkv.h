@@ -65,7 +65,7 @@ enum { ACTQKV_F32 = 0, ACTQKV_BF16 = 1 };
 
 /* Limits checked by every call (ACTQKV_ESHAPE otherwise):
  *   head_dim in {64, 128}; n_q_heads a multiple of n_kv_heads, group size
- *   n_q_heads/n_kv_heads in {1, 2, 4, 8}; block_size == 128; 1 <= n_rep <= 16;
+ *   n_q_heads/n_kv_heads in 1..8; block_size == 128; 1 <= n_rep <= 16;
  *   n_init and n_local multiples of block_size (0 allowed);
  *   1 <= k_cap <= 64; at most 8192 blocks take part in one selection. */
 typedef struct actqkv_shape {

@@ -45,8 +45,7 @@ static int check_shape(const actqkv_shape* sh) {
     return set_error(ACTQKV_ESHAPE, "n_q_heads %d is not a multiple of n_kv_heads %d", sh->n_q_heads,
                      sh->n_kv_heads);
   const int g = sh->n_q_heads / sh->n_kv_heads;
-  if (g != 1 && g != 2 && g != 4 && g != 8)
-    return set_error(ACTQKV_ESHAPE, "group size %d not supported (1, 2, 4, 8)", g);
+  if (g < 1 || g > 8) return set_error(ACTQKV_ESHAPE, "group size %d not supported (1..8)", g);
   if (sh->block_size != 128)
     return set_error(ACTQKV_ESHAPE, "block_size %d not supported (128)", sh->block_size);
   if (sh->n_rep > 16) return set_error(ACTQKV_ESHAPE, "n_rep %d not supported (1..16)", sh->n_rep);

@@ -54,6 +54,8 @@ __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, 
   return __builtin_convertvector(v, bf16x8);
 }
 
+__host__ __device__ __forceinline__ int padded_group(int g) { return g <= 1 ? 1 : (g <= 2 ? 2 : (g <= 4 ? 4 : 8)); }
+
 // MFMA row -> key row inside a 32-key group: swap bits 2 and 3.
 __device__ __forceinline__ int perm_row(int i) {
   return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
@@ -110,7 +112,9 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
   const int lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, half = lane >> 5;
   const int group = p.n_q_heads / p.n_kv_heads;
-  const int waves_per_head = kPfWaves / group;
+  // a group size that does not divide 8 (7 heads per KV head, say) is rounded up to the next
+  // power of two: the surplus wavefronts help to fetch tiles and otherwise idle
+  const int waves_per_head = kPfWaves / padded_group(group);
   const int pos_per_wg = 32 * waves_per_head;
 
   // The slots of a (sequence, KV head) are the pieces of its query tiles, in order.
@@ -143,10 +147,12 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
   const int per = (n_tiles + splits - 1) / splits;
   const int t_begin = split * per, t_end = min(n_tiles, t_begin + per);
 
-  const int head = hk * group + wave / waves_per_head;
+  const int head_in_group = wave / waves_per_head;
+  const bool head_ok = head_in_group < group;
+  const int head = hk * group + min(head_in_group, group - 1);
   const int wrow0 = row0 + (wave % waves_per_head) * 32;     // first window row of this wavefront
   const int my_row = wrow0 + n;
-  const bool row_ok = my_row < p.m;
+  const bool row_ok = my_row < p.m && head_ok;
   const int my_pos = g.w0 + my_row;                          // this lane's query position
 
   // Q^T as B operand: lane (n, half) holds d = ks*16 + 8*half .. +7 of query row n
@@ -234,7 +240,7 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
     const int kpos0 = block * kBlock;
     // the wavefront skips tiles none of its rows can see; it masks tiles that are
     // clipped or that reach past its first row's position
-    const bool visible = hi > lo && lo <= g.w0 + min(wrow0 + 31, p.m - 1);
+    const bool visible = head_ok && hi > lo && lo <= g.w0 + min(wrow0 + 31, p.m - 1);
     const bool masked = lo > kpos0 || hi < kpos0 + kBlock || hi - 1 > g.w0 + wrow0;
     if (visible) {
       const char* ks_ = lds_b + stage * 2 * kSlotBytes;
@@ -460,7 +466,7 @@ bool prefill_mfma_supported(const actqkv_shape& sh, int m) {
 
 int prefill_mfma_qtiles(const actqkv_shape& sh, int m) {
   const int g = sh.n_q_heads / sh.n_kv_heads;
-  const int pos_per_wg = 32 * (kPfWaves / g);
+  const int pos_per_wg = 32 * (kPfWaves / padded_group(g));
   return (m + pos_per_wg - 1) / pos_per_wg;
 }
 

@@ -186,6 +186,16 @@ def test_c3_128k_two_stream_pipeline_as_benchmarked():
     _say(f"[case] {w.name} two streams: selections equal, max |two - order| {diff:.3e}, worst out err {worst:.3e}")
 
 
+@pytest.mark.parametrize("hq,hkv,d,dtype", [(28, 4, 128, "bf16"), (6, 2, 64, "fp32"), (12, 4, 128, "bf16")])
+def test_group_sizes_that_do_not_divide_eight(hq, hkv, d, dtype):
+    """7 query heads per KV head (the second model of Sec. 5.1 has 28 and 4), and 3."""
+    sh = LayerShape(hq, hkv, d, 128, 4, 128, 256, dtype)
+    w = synth.Workload(f"group_{hq // hkv}", sh, 3072 + 100, 512 if dtype == "bf16" else 256, 6, True,
+                       4242 + hq, outlier_rate=0.02, outlier_kind="boost" if dtype == "fp32" else "student_t",
+                       n_planted=4)
+    run_prefill_case(w, attend=[0, 2, 6])
+
+
 @pytest.mark.parametrize("n_init,n_local", [(0, 256), (128, 0), (256, 128)])
 def test_geometry_variants(n_init, n_local):
     sh = LayerShape(4, 2, 64, 128, 2, n_init, n_local, "fp32")
@@ -297,6 +307,7 @@ def test_scores_zero_norms_and_determinism():
     ("fp32", 8, 2, [3000, 2817, 1100]),                       # ragged, one just past a block boundary
     ("bf16", 8, 2, [3000, 2817, 1100]),                       # few (sequence, head) pairs: split + combine
     ("bf16", 32, 8, [2900, 2817, 1100, 700, 3000, 129, 2048, 1]),  # 64 pairs: one workgroup per pair
+    ("bf16", 28, 4, [2900, 1100, 129]),                       # 7 query heads per KV head
 ])
 def test_decode_step_batch(dtype, hq, hkv, n_ctxs):
     sh = LayerShape(hq, hkv, 128 if dtype == "bf16" else 64, 128, 4, 128, 256, dtype)
