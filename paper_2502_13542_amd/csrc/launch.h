@@ -39,8 +39,8 @@ struct PfSplits {
   int s_lo, rem, slots;
 };
 PfSplits prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap);
-// prefill on the matrix cores: per workgroup and split, 8 wavefronts x (32 bf16 pairs of
-// normalised output + max + sum) x 64 lanes
+// prefill on the matrix cores: per workgroup and piece, 8 wavefronts x (16 eight-byte words of
+// four bf16 of normalised output + one word (max, sum)) x 64 lanes, counted in floats
 constexpr size_t kPfPartialFloats = 8 * (32 + 2) * 64;
 constexpr int kMaxWindow = 8192;
 

@@ -305,7 +305,7 @@ def test_scores_zero_norms_and_determinism():
 # ---------------------------------------------------------------- decode
 @pytest.mark.parametrize("dtype,hq,hkv,n_ctxs", [
     ("fp32", 8, 2, [3000, 2817, 1100]),                       # ragged, one just past a block boundary
-    ("bf16", 8, 2, [3000, 2817, 1100]),                       # few (sequence, head) pairs: split + combine
+    ("bf16", 8, 2, [3000, 2817, 1100]),                       # few (sequence, head) pairs: several workgroups per pair, merged by the last one
     ("bf16", 32, 8, [2900, 2817, 1100, 700, 3000, 129, 2048, 1]),  # 64 pairs: one workgroup per pair
     ("bf16", 28, 4, [2900, 1100, 129]),                       # 7 query heads per KV head
 ])
