@@ -150,7 +150,9 @@ size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity
   size_t attn = 0;
   if (decode_mfma_supported(sh, m)) attn = decode_mfma_scratch_floats(sh, batch, k_cap) * sizeof(float);
   if (prefill_mfma_supported(sh, m)) {
-    attn = size_t(batch) * sh.n_kv_heads * splits.slots * kPfPartialFloats * sizeof(float);
+    // partial results exist only where a query tile's key tiles are cut into pieces
+    if (splits.slots > prefill_mfma_qtiles(sh, m))
+      attn = size_t(batch) * sh.n_kv_heads * splits.slots * kPfPartialFloats * sizeof(float);
   }
   return kCounterBytes + align_up(probe > attn ? probe : attn, 256);
 }

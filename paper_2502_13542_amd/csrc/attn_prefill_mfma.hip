@@ -54,6 +54,15 @@ __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, 
   return __builtin_convertvector(v, bf16x8);
 }
 
+// A pointer that is the same in all lanes, pinned to scalar registers (so that adding a
+// 32-bit lane offset to it becomes the scalar-base addressing mode of the load).
+__device__ __forceinline__ const char* uniform_ptr(const char* ptr) {
+  const uint64_t v = reinterpret_cast<uint64_t>(ptr);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(v));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(uint32_t(v >> 32));
+  return reinterpret_cast<const char*>((uint64_t(hi) << 32) | lo);
+}
+
 __host__ __device__ __forceinline__ int padded_group(int g) { return g <= 1 ? 1 : (g <= 2 ? 2 : (g <= 4 ? 4 : 8)); }
 
 // MFMA row -> key row inside a 32-key group: swap bits 2 and 3.
@@ -200,15 +209,22 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
   const int lq = lane >> 4, c16 = lane & 15;
   const uint32_t g_row = uint32_t(16 * wave + lq) * (kPfD * 2);          // + 4*i rows per load
   const uint32_t g_chunk = uint32_t(c16 ^ lq) << 4;                      // ^ (i << 6)
+  // per-lane byte offsets inside a tile, one per load; the tile's base and the LDS
+  // destination are the same for all lanes and stay in scalar registers
+  uint32_t go[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) go[i] = g_row + i * 4 * (kPfD * 2) + (g_chunk ^ (uint32_t(i) << 6));
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   auto fetch_tile = [&](int u, int stage) {
     const int block = __builtin_amdgcn_readfirstlane(tile_tab[3 * u]);
     const size_t off = (size_t(block) * p.n_kv_heads + hk) * kTileBytes;
-    char* dst = lds_b + stage * 2 * kSlotBytes + wave * (16 * kRowPad * 2);
+    const char* kt = uniform_ptr(kc + off);
+    const char* vt = uniform_ptr(vc + off);
+    char* dst = lds_b + stage * 2 * kSlotBytes + wave_s * (16 * kRowPad * 2);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint32_t go = g_row + i * 4 * (kPfD * 2) + (g_chunk ^ (uint32_t(i) << 6));
-      __builtin_amdgcn_global_load_lds(kc + off + go, dst + i * 4 * (kRowPad * 2), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(vc + off + go, dst + kSlotBytes + i * 4 * (kRowPad * 2), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(kt + go[i], dst + i * 4 * (kRowPad * 2), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(vt + go[i], dst + kSlotBytes + i * 4 * (kRowPad * 2), 16, 0, 0);
     }
   };
 
