@@ -175,7 +175,10 @@ class PrefillPipeline:
         dev = runner.device
         self.idx = torch.full((plan.n_windows, runner.k_cap), -1, dtype=torch.int32, device=dev)
         self.n_sel = torch.zeros(plan.n_windows, dtype=torch.int32, device=dev)
-        ws = B.workspace_bytes(runner.cs, self.MAX_CHUNK, runner.m, runner.nb_capacity, runner.k_cap)
+        # one workspace for the attention stream: calls of up to MAX_CHUNK windows, and of a single
+        # (ragged) window, whose key tiles are cut into pieces and need room for the partials
+        ws = max(B.workspace_bytes(runner.cs, n, runner.m, runner.nb_capacity, runner.k_cap)
+                 for n in (1, 2, self.MAX_CHUNK))
         self.ws_attn = torch.zeros(ws, dtype=torch.uint8, device=dev)
         self.side = torch.cuda.Stream(device=dev)
         # the probe of every window, for the schedule that scores behind the probe chain

@@ -553,3 +553,43 @@ def test_cutoff_history_across_layers_and_steps():
     torch.cuda.synchronize()
     assert np.allclose(n_steps.cpu().numpy(), steps)
     assert np.allclose(theta_sum.cpu().numpy() / steps, np.array([h.means() for h in hists]), rtol=1e-5)
+
+
+def test_pipeline_with_ragged_last_window_and_short_context():
+    """The three-stream schedule on a context that is not a multiple of the window (the last
+    window goes out as a call of its own) and on one shorter than a chunk."""
+    for n_ctx in (512 * 5 + 77, 700):
+        w = synth.scaled(synth.WORKLOADS["c3_128k"], n_ctx=n_ctx, k_cap=8, name=f"pipe_{n_ctx}")
+        sh = w.shape
+        q, k, v = synth.gen_layer(w, "cpu", 0)
+        rep = synth.pick_rep_keys(k, sh.block_size, sh.n_rep)
+        cutoffs = []
+        for t in range(w.n_windows):
+            b, e = H.eligible_range(sh, t * w.window)
+            cutoffs.append(synth.cutoff_state(w, e - b, t, 0))
+        qd, kc, vc = q.to(DEV), H.blocked_k(k.to(DEV), sh, w.n_blocks), H.blocked_vt(v.to(DEV), sh, w.n_blocks)
+        repd = torch.zeros(w.n_blocks, sh.n_rep, sh.n_kv_heads, sh.head_dim, dtype=rep.dtype, device=DEV)
+        repd[: rep.shape[0]] = rep.to(DEV)
+        runner = H.LayerRunner(sh, 1, w.window, w.n_blocks, w.k_cap, DEV)
+        plan = H.make_prefill_plan(sh, w.n_ctx, w.window, cutoffs, DEV)
+        bud0 = plan.budget.clone()
+        pipe = H.PrefillPipeline(runner, plan)
+        outs = []
+        for overlap in (False, True):
+            runner.reset()
+            plan.budget.copy_(bud0)
+            out = torch.zeros_like(qd)
+            B.set_attention_cus(224 if overlap else 256)
+            try:
+                pipe.run(qd, kc, vc, repd, out, overlap=overlap, chunk=4, score_chunk=4)
+                torch.cuda.synchronize()
+            finally:
+                B.set_attention_cus(256)
+            outs.append((out, pipe.idx.clone(), pipe.n_sel.clone()))
+        assert torch.equal(outs[0][1], outs[1][1]) and torch.equal(outs[0][2], outs[1][2])
+        diff = (outs[0][0].float() - outs[1][0].float()).abs().max().item()
+        assert diff <= TOL_OUT["bf16"] * outs[0][0].float().abs().max().item()
+        want = oracle_windows(q, k, v, rep, sh, w.window, w.k_cap, cutoffs, [w.n_windows - 1])
+        res = want[w.n_windows - 1]
+        err = out_error(outs[1][0][res["w0"]:res["w0"] + res["out"].shape[0]], res["out"])
+        assert err < TOL_OUT["bf16"], f"last window of {n_ctx}: {err}"
