@@ -63,6 +63,12 @@ enum {
 
 enum { ACTQKV_F32 = 0, ACTQKV_BF16 = 1 };
 
+/* Bits of the update_stats argument of actqkv_build_probe. */
+enum {
+  ACTQKV_STATS_UPDATE = 1,        /* merge the window into the running statistics first */
+  ACTQKV_PROBE_MEAN_POOLING = 2   /* ablation baseline (Sec. 5.3): every token weighs 1/m */
+};
+
 /* Limits checked by every call (ACTQKV_ESHAPE otherwise):
  *   head_dim in {64, 128}; n_q_heads a multiple of n_kv_heads, group size
  *   n_q_heads/n_kv_heads in 1..8; block_size == 128; 1 <= n_rep <= 16;
@@ -96,9 +102,12 @@ size_t actqkv_workspace_bytes(const actqkv_shape* shape, int batch, int m, int n
 
 /* Activation Bias and probe-Query of one window per sequence (Sec. 4.1).
  *   q_win   [batch][m][H][D], storage dtype: the window's queries.
- *   stats   [batch][actqkv_stats_floats] fp32.  update_stats != 0: the window is
- *           merged into it first, so mean and variance cover every query up to
- *           and including this window (Eq. (8)); == 0: used as it is.
+ *   stats   [batch][actqkv_stats_floats] fp32.  update_stats & ACTQKV_STATS_UPDATE: the
+ *           window is merged into it first, so mean and variance cover every query up to
+ *           and including this window (Eq. (8)); otherwise it is used as it is.
+ *           update_stats & ACTQKV_PROBE_MEAN_POOLING: the weights of Eq. (9) are replaced by
+ *           1/m (the probe is the mean of the window's queries; the statistics are still
+ *           maintained if asked for).
  *   For each token j: phi_j = (q_j - mean)^2 / max(var, eps) per channel (Eq. (7));
  *   weight_j = |phi_j|_1 / sum_j |phi_j|_1 (uniform if the sum is 0);
  *   probe = sum_j weight_j q_j (Eq. (9)).  m == 1 gives probe = q (Sec. 4.2, decode).

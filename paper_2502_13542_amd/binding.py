@@ -18,6 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libactqkv.so")
 
 ACTQKV_F32, ACTQKV_BF16 = 0, 1
+STATS_UPDATE, PROBE_MEAN_POOLING = 1, 2      # bits of build_probe's update_stats
 ERROR_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EALIGN", -4: "EWORKSPACE", -5: "EHIP"}
 
 
@@ -153,12 +154,12 @@ def copy_bytes(dst, src, stream=None) -> None:
     _check(load_library().actqkv_copy_bytes(_ptr(dst), _ptr(src), n, _stream(stream)))
 
 
-def build_probe(shape: CShape, batch: int, m: int, q_win, stats, update_stats: bool, probe, probe_kv,
+def build_probe(shape: CShape, batch: int, m: int, q_win, stats, update_stats, probe, probe_kv,
                 probe_norm, weights, workspace, stream=None) -> None:
     st = torch.float32 if shape.dtype == ACTQKV_F32 else torch.bfloat16
     _check(load_library().actqkv_build_probe(
         ctypes.byref(shape), batch, m, _ptr(q_win, st), _ptr(stats, torch.float32),
-        int(bool(update_stats)), _ptr(probe, torch.float32), _ptr(probe_kv, torch.float32),
+        int(update_stats), _ptr(probe, torch.float32), _ptr(probe_kv, torch.float32),
         _ptr(probe_norm, torch.float32), _ptr(weights, torch.float32), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))
 

@@ -198,6 +198,7 @@ template <typename T>
 __global__ __launch_bounds__(512) void probe_weigh_kernel(const T* __restrict__ q_win,
                                                           const float* __restrict__ scratch,
                                                           float* __restrict__ stats, int add_count,
+                                                          int mean_pooling,
                                                           float* __restrict__ probe_out,
                                                           float* __restrict__ weights_out, int m,
                                                           int m_pad, int n_slabs, int d,
@@ -227,7 +228,7 @@ __global__ __launch_bounds__(512) void probe_weigh_kernel(const T* __restrict__ 
   load_pass(0);
 
   float tsum = 0.f;
-  for (int j = threadIdx.x; j < m; j += 512) {
+  for (int j = threadIdx.x; j < m && !mean_pooling; j += 512) {
     float t = 0.f;
     for (int s0 = 0; s0 < n_slabs; s0 += kWeighSlabBatch) {
       float p[kWeighSlabBatch];
@@ -360,7 +361,9 @@ static int launch_probe_t(const actqkv_shape& sh, int batch, int m, const T* q_w
   const int n_slabs = probe_slabs(sh);
   static_assert(kColLanes * 8 == kProbeSlabBytes / 2 && kColLanes * 4 == kProbeSlabBytes / 4, "slab width");
   float* scratch = ws.scratch_f32();
-  if (update_stats || m > 1) {
+  const int mean_pooling = (update_stats & ACTQKV_PROBE_MEAN_POOLING) != 0;
+  update_stats &= ACTQKV_STATS_UPDATE;
+  if (update_stats || (m > 1 && !mean_pooling)) {
     hipLaunchKernelGGL(probe_stats_bias_kernel<T>, dim3(n_slabs, batch), dim3(256), 0, stream, q_win,
                        stats, scratch, update_stats, m, m_pad, d, eps, stats_stride, scratch_stride);
   }
@@ -372,7 +375,7 @@ static int launch_probe_t(const actqkv_shape& sh, int batch, int m, const T* q_w
     return hip_status("probe");
   }
   hipLaunchKernelGGL(probe_weigh_kernel<T>, dim3(n_slabs, batch), dim3(512), 0, stream, q_win, scratch,
-                     stats, update_stats, probe, weights, m, m_pad, n_slabs, d, scratch_stride,
+                     stats, update_stats, mean_pooling, probe, weights, m, m_pad, n_slabs, d, scratch_stride,
                      stats_stride);
   hipLaunchKernelGGL(probe_finish_kernel, dim3(batch), dim3(1024), 0, stream, probe, probe_kv,
                      probe_norm, sh.n_q_heads, sh.n_kv_heads, sh.head_dim);

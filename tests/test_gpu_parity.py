@@ -593,3 +593,30 @@ def test_pipeline_with_ragged_last_window_and_short_context():
         res = want[w.n_windows - 1]
         err = out_error(outs[1][0][res["w0"]:res["w0"] + res["out"].shape[0]], res["out"])
         assert err < TOL_OUT["bf16"], f"last window of {n_ctx}: {err}"
+
+
+def test_mean_pooling_probe_variant():
+    """The ablation baseline: every token of the window weighs 1/m, the statistics are still kept."""
+    sh = LayerShape(32, 8, 128, 128, 4, 128, 512, "bf16")
+    cs = B.c_shape(sh)
+    m, d = 512, 32 * 128
+    g = torch.Generator().manual_seed(321)
+    q = (torch.randn(2, m, 32, 128, generator=g) * 1.5 + 0.3).to(torch.bfloat16)
+    qd = q.to(DEV)
+    runs = {}
+    for name, flags in (("probe", B.STATS_UPDATE), ("mean", B.STATS_UPDATE | B.PROBE_MEAN_POOLING)):
+        r = H.LayerRunner(sh, 2, m, 8, 4, DEV)
+        w = torch.zeros(2, m, device=DEV)
+        B.build_probe(cs, 2, m, qd, r.stats, flags, r.probe, r.probe_kv, r.probe_norm, w, r.workspace)
+        torch.cuda.synchronize()
+        runs[name] = (r.probe.cpu(), r.probe_kv.cpu(), r.probe_norm.cpu(), w.cpu(), r.stats.cpu())
+    assert torch.equal(runs["probe"][4], runs["mean"][4])            # same statistics either way
+    for s in range(2):
+        want, wts = orc.probe_query(f64(q[s]).reshape(m, d), np.ones((m, d)))
+        assert np.allclose(wts, 1.0 / m)
+        assert rel_to_max(runs["mean"][0][s], want) < TOL_PROBE
+        assert np.allclose(runs["mean"][3][s].numpy(), 1.0 / m, rtol=1e-6)
+        assert abs(float(runs["mean"][2][s]) - np.linalg.norm(want)) < TOL_PROBE * np.linalg.norm(want)
+        kv = want.reshape(8, 4, 128).sum(axis=1).reshape(-1)
+        assert rel_to_max(runs["mean"][1][s], kv) < TOL_PROBE
+        assert rel_to_max(runs["probe"][0][s], want) > 10 * TOL_PROBE   # the activation-aware probe differs
