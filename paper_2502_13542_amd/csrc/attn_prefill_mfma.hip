@@ -42,6 +42,7 @@ constexpr int kPfMaxTiles = 96;                      // initial + selected (<= 6
 constexpr int kPfLdsBytes = 2 * 2 * kTileElems * 2 + kPfMaxTiles * 12;  // 2 stages x (K, V^T) + tile table
 constexpr int kPfPartWords = 17;                     // 64-bit words per lane: 16 x 4 bf16 + (max, sum)
 constexpr int kMaxPfSplits = 8;
+constexpr float kLazyMaxLog2 = 8.f;                  // how far a tile's maximum may exceed the reference one
 constexpr int kPfQueueDone = 128;                    // index of the "left" counter behind the per-head queue counters
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -303,7 +304,11 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
 #pragma unroll
         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc_s[kb][i]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx * p.scale_log2e);
+      // the reference maximum follows the true one lazily: it moves only when a tile exceeds
+      // it by more than 2^8, so the rescaling of the accumulators below is rare after the first
+      // tiles; probabilities up to 2^8 are as exact in bf16 and fp32 as those up to 1
+      const float m_tile = mx * p.scale_log2e;
+      const float m_new = m_tile - m_run > kLazyMaxLog2 ? m_tile : m_run;
       const float m_safe = m_new == -INFINITY ? 0.f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
       m_run = m_new;
