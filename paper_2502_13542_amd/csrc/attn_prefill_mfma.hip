@@ -249,7 +249,6 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
   for (int j = 0; j < 16; ++j) acc_l[j] = 0.f;
   for (int t = t_begin; t < t_end; ++t) {
     const int u = t - t_begin, stage = u & 1;
-    if (t + 1 < t_end) fetch_tile(u + 1, stage ^ 1);   // lands while this tile is computed
 
     const int block = __builtin_amdgcn_readfirstlane(tile_tab[3 * u]);
     const int lo = __builtin_amdgcn_readfirstlane(tile_tab[3 * u + 1]);
@@ -259,11 +258,11 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
     // clipped or that reach past its first row's position
     const bool visible = head_ok && hi > lo && lo <= g.w0 + min(wrow0 + 31, p.m - 1);
     const bool masked = lo > kpos0 || hi < kpos0 + kBlock || hi - 1 > g.w0 + wrow0;
+    const char* ks_ = lds_b + stage * 2 * kSlotBytes;
+    const char* vs_ = ks_ + kSlotBytes;
+    f32x16 acc_s[4];
     if (visible) {
-      const char* ks_ = lds_b + stage * 2 * kSlotBytes;
-      const char* vs_ = ks_ + kSlotBytes;
       // ---- S^T = K Q^T : 4 groups of 32 keys
-      f32x16 acc_s[4];
       const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       // the four key groups take turns, so that an MFMA never waits for the one just before it
       // (a dependent 32x32x16 MFMA issues only about 90 cycles after its producer, an
@@ -286,6 +285,14 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
       __builtin_amdgcn_sched_barrier(0);
+    }
+    // The next tile is requested here, after the score MFMAs and not at the top of the
+    // iteration: while an LDS-direct load (a FLAT-encoded instruction) is in flight the
+    // compiler must treat LDS operations as completing out of order and waits for ALL
+    // outstanding operand reads before each use, which stalled the score phase every 8 MFMAs.
+    // It still has the softmax and the value phase of this tile to land.
+    if (t + 1 < t_end) fetch_tile(u + 1, stage ^ 1);
+    if (visible) {
       // register i of group kb holds key kpos0 + kb*32 + 16*(i/8) + 8*half + (i%8)
       if (masked) {
 #pragma unroll
