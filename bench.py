@@ -176,7 +176,7 @@ def bench_prefill(args, torch, B, H, synth):
         runner.stats.zero_()
         if bud0 is not None:
             plan.budget.copy_(bud0)
-        pipe.run(q, kc, vc, repd, out, overlap, events, args.chunk, args.score_chunk)
+        pipe.run(q, kc, vc, repd, out, overlap, events, args.chunk, args.score_chunk, not args.per_window_selection)
 
     if args.pmc_pass:
         if not args.no_overlap:
@@ -237,7 +237,10 @@ def bench_prefill(args, torch, B, H, synth):
                                f"cut-off {'on' if w.cutoff else 'off'}",
                    "windows": n_win, "mean_blocks_selected": sum(n_sel) / max(n_win, 1),
                    "launch": ("hip graph replay" if graph is not None else "eager") +
-                             (f", three streams: probes, then scoring and selection ({args.score_chunk} windows per "
+                             (f", two streams, {args.chunk} windows per call: probes, scores and selection of chunk "
+                              f"c + 1 beside the attention of chunk c ({args.attention_cus} of 256 CUs)"
+                              if overlap and not args.per_window_selection else
+                              f", three streams: probes, then scoring and selection ({args.score_chunk} windows per "
                               f"hand-over), then attention ({args.attention_cus} of 256 CUs, up to {args.chunk} "
                               "windows per launch)" if overlap and args.score_chunk > 0 else
                               f", attention on a second stream ({args.attention_cus} of 256 CUs, up to {args.chunk} "
@@ -437,6 +440,9 @@ def main() -> int:
     ap.add_argument("--score-chunk", type=int, default=16,
                     help="prefill: > 0 puts scoring and selection on a stream of their own, this many "
                          "windows behind the probe chain per hand-over")
+    ap.add_argument("--per-window-selection", action="store_true",
+                    help="prefill, with overlap: probe, score and select calls of one window each (three "
+                         "streams) instead of one call per chunk of windows")
     ap.add_argument("--attention-cus", type=int, default=224,
                     help="prefill, two streams: compute units the attention may fill")
     ap.add_argument("--pmc-pass", action="store_true",

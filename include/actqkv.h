@@ -66,7 +66,8 @@ enum { ACTQKV_F32 = 0, ACTQKV_BF16 = 1 };
 /* Bits of the update_stats argument of actqkv_build_probe. */
 enum {
   ACTQKV_STATS_UPDATE = 1,        /* merge the window into the running statistics first */
-  ACTQKV_PROBE_MEAN_POOLING = 2   /* ablation baseline (Sec. 5.3): every token weighs 1/m */
+  ACTQKV_PROBE_MEAN_POOLING = 2,  /* ablation baseline (Sec. 5.3): every token weighs 1/m */
+  ACTQKV_PROBE_WINDOW_CHAIN = 4   /* the batch entries are consecutive windows of ONE sequence */
 };
 
 /* Limits checked by every call (ACTQKV_ESHAPE otherwise):
@@ -108,6 +109,11 @@ size_t actqkv_workspace_bytes(const actqkv_shape* shape, int batch, int m, int n
  *           update_stats & ACTQKV_PROBE_MEAN_POOLING: the weights of Eq. (9) are replaced by
  *           1/m (the probe is the mean of the window's queries; the statistics are still
  *           maintained if asked for).
+ *           update_stats & ACTQKV_PROBE_WINDOW_CHAIN (needs ACTQKV_STATS_UPDATE and m >= 2):
+ *           the batch entries are `batch` consecutive windows of one sequence and stats is
+ *           that sequence's single record.  Entry b gets the probe that batch calls of one
+ *           window each, in order, would give it (statistics over every query up to and
+ *           including window b, Eq. (8)); stats ends as after the last window.
  *   For each token j: phi_j = (q_j - mean)^2 / max(var, eps) per channel (Eq. (7));
  *   weight_j = |phi_j|_1 / sum_j |phi_j|_1 (uniform if the sum is 0);
  *   probe = sum_j weight_j q_j (Eq. (9)).  m == 1 gives probe = q (Sec. 4.2, decode).
@@ -124,7 +130,8 @@ int actqkv_build_probe(const actqkv_shape* shape, int batch, int m, const void* 
 
 /* Block scores (Eq. (10), applied to a block's representative keys; Eq. (5)).
  *   rep_keys  [batch][nb_capacity][r][Hk][D], storage dtype; seq_stride = elements
- *             between two sequences.
+ *             between two sequences; 0 = all entries score the same keys (the entries
+ *             are then windows of one sequence, each with its own probe and nb_end).
  *   nb_end    device int32 [batch]: blocks nb_begin <= b < nb_end[s] are scored
  *             (clamped to nb_capacity); other entries of `scores` are left alone.
  *   scores    [batch][score_stride] fp32, score_stride >= nb_capacity:

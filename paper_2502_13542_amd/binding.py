@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libactqkv.so")
 
 ACTQKV_F32, ACTQKV_BF16 = 0, 1
-STATS_UPDATE, PROBE_MEAN_POOLING = 1, 2      # bits of build_probe's update_stats
+STATS_UPDATE, PROBE_MEAN_POOLING, PROBE_WINDOW_CHAIN = 1, 2, 4   # bits of build_probe's update_stats
 ERROR_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EALIGN", -4: "EWORKSPACE", -5: "EHIP"}
 
 

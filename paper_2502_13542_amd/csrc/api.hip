@@ -145,7 +145,7 @@ int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* 
 
 size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap) {
   (void)nb_capacity;
-  size_t probe = size_t(batch) * probe_scratch_floats(sh, m) * sizeof(float);
+  size_t probe = probe_call_floats(sh, batch, m) * sizeof(float);
   const PfSplits splits = prefill_splits(sh, batch, m, k_cap);
   size_t attn = 0;
   if (decode_mfma_supported(sh, m)) attn = decode_mfma_scratch_floats(sh, batch, k_cap) * sizeof(float);
@@ -222,9 +222,13 @@ int actqkv_build_probe(const actqkv_shape* shape, int batch, int m, const void* 
   ACTQKV_REQUIRE_SMALL(probe_norm, 4);
   ACTQKV_OPTIONAL_SMALL(weights, 4);
   if (m > 1 || update_stats) ACTQKV_REQUIRE_PTR(stats);
+  if (update_stats & ~(ACTQKV_STATS_UPDATE | ACTQKV_PROBE_MEAN_POOLING | ACTQKV_PROBE_WINDOW_CHAIN))
+    return set_error(ACTQKV_EINVAL, "update_stats has unknown bits: %d", update_stats);
+  if ((update_stats & ACTQKV_PROBE_WINDOW_CHAIN) && (!(update_stats & ACTQKV_STATS_UPDATE) || m < 2))
+    return set_error(ACTQKV_EINVAL, "consecutive windows need ACTQKV_STATS_UPDATE and m >= 2");
   if (workspace == nullptr || !aligned16(workspace))
     return set_error(ACTQKV_EWORKSPACE, "workspace is NULL or not 16-byte aligned");
-  size_t need = kCounterBytes + size_t(batch) * probe_scratch_floats(*shape, m) * sizeof(float);
+  size_t need = kCounterBytes + probe_call_floats(*shape, batch, m) * sizeof(float);
   if (ws_bytes < need)
     return set_error(ACTQKV_EWORKSPACE, "workspace has %zu bytes, build_probe needs %zu", ws_bytes, need);
   Workspace ws{workspace, ws_bytes};
@@ -248,7 +252,7 @@ int actqkv_score_blocks(const actqkv_shape* shape, int batch, const float* probe
     return set_error(ACTQKV_EINVAL, "score_stride %lld < nb_capacity %d", (long long)score_stride,
                      nb_capacity);
   const int64_t per_seq = int64_t(nb_capacity) * shape->n_rep * shape->n_kv_heads * shape->head_dim;
-  if (batch > 1 && seq_stride < per_seq)
+  if (batch > 1 && seq_stride != 0 && seq_stride < per_seq)
     return set_error(ACTQKV_EINVAL, "seq_stride %lld < one sequence's representative keys %lld",
                      (long long)seq_stride, (long long)per_seq);
   if (seq_stride % 8 != 0) return set_error(ACTQKV_EALIGN, "seq_stride must be a multiple of 8 elements");

@@ -222,10 +222,12 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
     const char* kt = uniform_ptr(kc + off);
     const char* vt = uniform_ptr(vc + off);
     char* dst = lds_b + stage * 2 * kSlotBytes + wave_s * (16 * kRowPad * 2);
+    const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kt), 0, kTileBytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vt), 0, kTileBytes, 0x00020000);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      __builtin_amdgcn_global_load_lds(kt + go[i], dst + i * 4 * (kRowPad * 2), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(vt + go[i], dst + kSlotBytes + i * 4 * (kRowPad * 2), 16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(kr, (__attribute__((address_space(3))) void*)(dst + i * 4 * (kRowPad * 2)), 16, go[i], 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(vr, (__attribute__((address_space(3))) void*)(dst + kSlotBytes + i * 4 * (kRowPad * 2)), 16, go[i], 0, 0, 0);
     }
   };
 
@@ -234,21 +236,21 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
   __syncthreads();
 
   const int a_row = perm_row(n);
-  // byte offsets of this lane's MFMA A operands inside a K / V^T slot; the 32-row blocks
-  // (kb, db) add a compile-time constant.  K: row perm(n), chunk 2*ks + half, swizzle key
-  // perm(n) % 16.  V^T: row n, chunk c = 4*kb + 2*s2 + half, swizzle key n % 16.
-  uint32_t a_off[8], v_off[8];
-#pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    a_off[c] = uint32_t(a_row) * (kRowPad * 2) + (uint32_t((2 * c + half) ^ (a_row & 15)) << 4);
-    v_off[c] = uint32_t(n) * (kRowPad * 2) + (uint32_t((2 * c + half) ^ (n & 15)) << 4);
-  }
+  // Byte offsets of this lane's MFMA A operands inside a K / V^T slot.  K: row perm(n), chunk
+  // 2*ks + half, swizzle key perm(n) % 16; V^T: row n, chunk c = 4*kb + 2*s2 + half, swizzle
+  // key n % 16.  A row is 256 bytes, so the offset of chunk pair c is that of pair 0 with
+  // c << 5 XOR-ed in: one register per operand kind and one XOR per read, instead of eight
+  // registers each.  The 32-row blocks (kb, db) add a compile-time constant.
+  uint32_t a_off0 = uint32_t(a_row) * (kRowPad * 2) + (uint32_t(half ^ (a_row & 15)) << 4);
+  uint32_t v_off0 = uint32_t(n) * (kRowPad * 2) + (uint32_t(half ^ (n & 15)) << 4);
   const bf16x8 ones = as_bf16x8(u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
   f32x16 acc_l;                                // every register: the running sum of the lane's query row
 #pragma unroll
   for (int j = 0; j < 16; ++j) acc_l[j] = 0.f;
   for (int t = t_begin; t < t_end; ++t) {
     const int u = t - t_begin, stage = u & 1;
+    // (opaque per iteration: the XOR-ed offsets are recomputed, not kept across the loop)
+    asm volatile("" : "+v"(a_off0), "+v"(v_off0));
 
     const int block = __builtin_amdgcn_readfirstlane(tile_tab[3 * u]);
     const int lo = __builtin_amdgcn_readfirstlane(tile_tab[3 * u + 1]);
@@ -267,13 +269,18 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
       // the four key groups take turns, so that an MFMA never waits for the one just before it
       // (a dependent 32x32x16 MFMA issues only about 90 cycles after its producer, an
       // independent one after 32)
+      // (written in the order it should issue: a ring of 8 operands, each read 8 MFMAs ahead)
+      auto k_read = [&](int i) {
+        return *reinterpret_cast<const u32x4*>(ks_ + (a_off0 ^ (uint32_t(i >> 2) << 5)) + (i & 3) * 32 * (kRowPad * 2));
+      };
+      u32x4 ring[8];
 #pragma unroll
-      for (int ks = 0; ks < kPfD / 16; ++ks) {
+      for (int i = 0; i < 8; ++i) ring[i] = k_read(i);
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
-          bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(ks_ + a_off[ks] + kb * 32 * (kRowPad * 2)));
-          acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], ks == 0 ? zero16 : acc_s[kb], 0, 0, 0);
-        }
+      for (int i = 0; i < 32; ++i) {
+        const int ks = i >> 2, kb = i & 3;
+        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ring[i & 7]), qreg[ks], ks == 0 ? zero16 : acc_s[kb], 0, 0, 0);
+        if (i + 8 < 32) ring[i & 7] = k_read(i + 8);
       }
       // issue order: 8 operand reads ahead of the first MFMA, then one read per MFMA, so that an
       // operand is requested about 8 MFMAs before it is needed (0x100 = LDS read, 0x008 = MFMA)
@@ -305,6 +312,14 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
           }
       }
       // ---- online softmax, one query per lane (two lanes share a query: n and n+32)
+      // the first V^T operands are requested now and land during the max reduction;
+      // operand j = 4 * (2*kb + s2) + db belongs to keys kb*32 + s2*16 .. +15, rows db*32 .. +31
+      auto v_read = [&](int j) {
+        return *reinterpret_cast<const u32x4*>(vs_ + (v_off0 ^ (uint32_t(j >> 2) << 5)) + (j & 3) * 32 * (kRowPad * 2));
+      };
+      u32x4 vring[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) vring[i] = v_read(i);
       float mx = acc_s[0][0];
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb)
@@ -319,11 +334,6 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
       const float m_safe = m_new == -INFINITY ? 0.f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
       m_run = m_new;
-#pragma unroll
-      for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          acc_s[kb][i] = __builtin_amdgcn_exp2f(acc_s[kb][i] * p.scale_log2e - m_safe);
       if (!__all(alpha == 1.f)) {
 #pragma unroll
         for (int db = 0; db < 4; ++db)
@@ -332,22 +342,33 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc_l[i] *= alpha;
       }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc_s[0][i] = __builtin_amdgcn_exp2f(acc_s[0][i] * p.scale_log2e - m_safe);
+      __builtin_amdgcn_sched_barrier(0);
       // ---- O^T += V^T P^T; the row sums of P come from one more MFMA per 16 keys against an
       // all-ones A operand (64 additions per tile less on the vector ALU, and exactly the
-      // bf16 probabilities that multiply V are summed)
+      // bf16 probabilities that multiply V are summed).  Written in issue order: the
+      // exponentials of the next 32 keys sit between the MFMAs of these 32 (the vector ALU works
+      // while the matrix pipe does), and every V^T operand is read 8 MFMAs ahead.
 #pragma unroll
-      for (int kb = 0; kb < 4; ++kb) {
+      for (int g8 = 0; g8 < 8; ++g8) {
+        const int kb = g8 >> 1, s2 = g8 & 1;
+        const bf16x8 pb = pack8(acc_s[kb][8 * s2 + 0], acc_s[kb][8 * s2 + 1], acc_s[kb][8 * s2 + 2],
+                                acc_s[kb][8 * s2 + 3], acc_s[kb][8 * s2 + 4], acc_s[kb][8 * s2 + 5],
+                                acc_s[kb][8 * s2 + 6], acc_s[kb][8 * s2 + 7]);
+        __builtin_amdgcn_sched_barrier(0);
+        acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pb, acc_l, 0, 0, 0);
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          const bf16x8 pb = pack8(acc_s[kb][8 * s2 + 0], acc_s[kb][8 * s2 + 1], acc_s[kb][8 * s2 + 2],
-                                  acc_s[kb][8 * s2 + 3], acc_s[kb][8 * s2 + 4], acc_s[kb][8 * s2 + 5],
-                                  acc_s[kb][8 * s2 + 6], acc_s[kb][8 * s2 + 7]);
-          acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pb, acc_l, 0, 0, 0);
+        for (int db = 0; db < 4; ++db) {
+          if (kb < 3) {
 #pragma unroll
-          for (int db = 0; db < 4; ++db) {
-            bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(vs_ + v_off[2 * kb + s2] + db * 32 * (kRowPad * 2)));
-            acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, acc_o[db], 0, 0, 0);
+            for (int i = 8 * s2 + 2 * db; i < 8 * s2 + 2 * db + 2; ++i)
+              acc_s[kb + 1][i] = __builtin_amdgcn_exp2f(acc_s[kb + 1][i] * p.scale_log2e - m_safe);
           }
+          __builtin_amdgcn_sched_barrier(0);
+          const int j = 4 * g8 + db;
+          acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vring[j & 7]), pb, acc_o[db], 0, 0, 0);
+          if (j + 8 < 32) vring[j & 7] = v_read(j + 8);
         }
       }
     }

@@ -31,6 +31,12 @@ inline size_t probe_a_floats(int m) { return (size_t(m) + 15) / 16 * 16; }
 inline size_t probe_scratch_floats(const actqkv_shape& sh, int m) {
   return size_t(probe_slabs(sh)) * probe_a_floats(m);
 }
+// the whole call: the partials of every entry, and behind them what a call over consecutive
+// windows of one sequence keeps: (mean, M2) [batch][2][d] and a copy of the old statistics
+inline size_t probe_call_floats(const actqkv_shape& sh, int batch, int m) {
+  return size_t(batch) * probe_scratch_floats(sh, m) +
+         (size_t(batch) + 1) * 2 * sh.n_q_heads * sh.head_dim + 4;
+}
 
 // Key-tile splits of the prefill attention.
 // The first n_qtiles - rem query tiles of a sequence are cut into s_lo pieces, the last rem

@@ -11,6 +11,13 @@
 //               slab of probe = sum_j w_j q_j of Eq. (9);
 //   finish      norm of the probe and its per-KV-head sum.
 // All sums are fp32 and are taken in a fixed order, so results are reproducible.
+//
+// Consecutive windows of one sequence can be taken in one call: Eq. (8) merges the windows
+// into the running statistics one after the other, but the merge is a function of each
+// window's own (mean, M2) only.  So window_moments computes those for all windows at once,
+// chain_bias (one workgroup per window and slab) replays the merges up to its window -
+// a few operations per channel - and takes the bias partials of its window, and weigh and
+// finish run once for all windows.  Four launches for n windows instead of 3 n.
 #include "common.h"
 #include "launch.h"
 
@@ -20,6 +27,50 @@ constexpr int kColLanes = 8;      // 16-byte column lanes of a slab
 constexpr int kRowsPerThread = 16;   // 16-byte loads a thread keeps in flight
 constexpr int kStatsRowLanes = 32;
 constexpr int kStatsRowsPerPass = kStatsRowLanes * kRowsPerThread;
+
+// apart[j] = sum over the slab's channels of (q_jc - mean_c)^2 / var_c for the rows of the
+// window (Eq. (7) summed over a slab); x holds pass 0 of the rows when there is one pass only.
+template <typename T, typename LoadPass>
+__device__ __forceinline__ void bias_partials(typename Vec<T>::raw (&x)[kRowsPerThread], LoadPass&& load_pass,
+                                              const float* mu_lds, const float* iv_lds,
+                                              float* __restrict__ apart, int m, int m_pad, int n_pass,
+                                              int cl, int rl) {
+  constexpr int V = Vec<T>::N;
+  float mu[V], iv[V];
+#pragma unroll
+  for (int v = 0; v < V; ++v) {
+    mu[v] = mu_lds[cl * V + v];
+    iv[v] = iv_lds[cl * V + v];
+  }
+  for (int pass = 0; pass < n_pass; ++pass) {
+    if (n_pass > 1) load_pass(pass);
+    const int r0 = pass * kStatsRowsPerPass + rl * kRowsPerThread;
+    float a[kRowsPerThread];
+#pragma unroll
+    for (int i = 0; i < kRowsPerThread; ++i) {
+      float f[V];
+      Vec<T>::widen(x[i], f);
+      float t = 0.f;
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        float e = f[v] - mu[v];
+        t += e * e * iv[v];
+      }
+      // the 8 column lanes of a row are neighbouring lanes of one wave
+      t += __shfl_xor(t, 1, 64);
+      t += __shfl_xor(t, 2, 64);
+      t += __shfl_xor(t, 4, 64);
+      a[i] = r0 + i < m ? t : 0.f;
+    }
+    if (cl == 0 && r0 < m_pad) {
+#pragma unroll
+      for (int i = 0; i < kRowsPerThread; i += 4) {
+        f32x4 o = {a[i], a[i + 1], a[i + 2], a[i + 3]};
+        *reinterpret_cast<f32x4*>(apart + r0 + i) = o;
+      }
+    }
+  }
+}
 
 // grid (column slabs of 8*V channels, batch); 256 threads = 8 column lanes x 32 row lanes;
 // row lane rl takes rows rl*16 .. rl*16+15 of every pass of 512 rows.
@@ -132,40 +183,158 @@ __global__ __launch_bounds__(256) void probe_stats_bias_kernel(const T* __restri
   if (m == 1) return;   // a single token is its own probe: no weights needed
   __syncthreads();
 
-  float mu[V], iv[V];
+  bias_partials<T>(x, load_pass, mu_lds, iv_lds, apart, m, m_pad, n_pass, cl, rl);
+}
+
+// ---- consecutive windows of one sequence in one call
+// Scratch behind the bias partials: mom[n][2][d] = (mean, M2) of every window on its own,
+// then base[4 + 2 d] = the running statistics as they were before the call.
+//
+// grid (column slabs, n windows); threads as in probe_stats_bias_kernel.  The sums are taken
+// about the window's first query (no cancellation in the squares).  The workgroups of window
+// 0 also copy their slab of the old statistics to `base`, which chain_bias reads: it
+// overwrites the statistics themselves while other workgroups still need the old ones.
+template <typename T>
+__global__ __launch_bounds__(256) void probe_window_moments_kernel(const T* __restrict__ q_win,
+                                                                   const float* __restrict__ stats,
+                                                                   float* __restrict__ mom,
+                                                                   float* __restrict__ base, int m, int d) {
+  constexpr int V = Vec<T>::N;
+  constexpr int SLAB = kColLanes * V;
+  typedef typename Vec<T>::raw raw_t;
+  __shared__ float red[2][kStatsRowLanes][SLAB];
+  const int w = blockIdx.y;
+  const T* q = q_win + size_t(w) * m * d;
+  const int cl = threadIdx.x % kColLanes, rl = threadIdx.x / kColLanes;
+  const int ch0 = blockIdx.x * SLAB + cl * V;
+  const bool col_ok = ch0 < d;
+  const int n_pass = (m + kStatsRowsPerPass - 1) / kStatsRowsPerPass;
+  float c[V], s1[V], s2[V];
 #pragma unroll
-  for (int v = 0; v < V; ++v) {
-    mu[v] = mu_lds[cl * V + v];
-    iv[v] = iv_lds[cl * V + v];
-  }
+  for (int v = 0; v < V; ++v) c[v] = s1[v] = s2[v] = 0.f;
+  if (col_ok) Vec<T>::load(q + ch0, c);
   for (int pass = 0; pass < n_pass; ++pass) {
-    if (n_pass > 1) load_pass(pass);
-    const int r0 = pass * kStatsRowsPerPass + rl * kRowsPerThread;
-    float a[kRowsPerThread];
+    raw_t x[kRowsPerThread];
+#pragma unroll
+    for (int i = 0; i < kRowsPerThread; ++i) {   // all loads first: they overlap
+      const int r = pass * kStatsRowsPerPass + rl * kRowsPerThread + i;
+      x[i] = Vec<T>::load_raw(q + size_t(r < m ? r : 0) * d + (col_ok ? ch0 : 0));
+    }
 #pragma unroll
     for (int i = 0; i < kRowsPerThread; ++i) {
-      float f[V];
-      Vec<T>::widen(x[i], f);
-      float t = 0.f;
+      if (pass * kStatsRowsPerPass + rl * kRowsPerThread + i < m) {
+        float f[V];
+        Vec<T>::widen(x[i], f);
 #pragma unroll
-      for (int v = 0; v < V; ++v) {
-        float e = f[v] - mu[v];
-        t += e * e * iv[v];
-      }
-      // the 8 column lanes of a row are neighbouring lanes of one wave
-      t += __shfl_xor(t, 1, 64);
-      t += __shfl_xor(t, 2, 64);
-      t += __shfl_xor(t, 4, 64);
-      a[i] = r0 + i < m ? t : 0.f;
-    }
-    if (cl == 0 && r0 < m_pad) {
-#pragma unroll
-      for (int i = 0; i < kRowsPerThread; i += 4) {
-        f32x4 o = {a[i], a[i + 1], a[i + 2], a[i + 3]};
-        *reinterpret_cast<f32x4*>(apart + r0 + i) = o;
+        for (int v = 0; v < V; ++v) {
+          float t = f[v] - c[v];
+          s1[v] += t;
+          s2[v] += t * t;
+        }
       }
     }
   }
+#pragma unroll
+  for (int v = 0; v < V; ++v) {
+    red[0][rl][cl * V + v] = s1[v];
+    red[1][rl][cl * V + v] = s2[v];
+  }
+  __syncthreads();
+  const int col = threadIdx.x, ch = blockIdx.x * SLAB + col;
+  if (col < SLAB && ch < d) {
+    float t1 = 0.f, t2 = 0.f;
+#pragma unroll
+    for (int k = 0; k < kStatsRowLanes; ++k) {
+      t1 += red[0][k][col];
+      t2 += red[1][k][col];
+    }
+    const float nb = float(m);
+    mom[(size_t(w) * 2 + 0) * d + ch] = to_f32(q[ch]) + t1 / nb;
+    mom[(size_t(w) * 2 + 1) * d + ch] = fmaxf(t2 - t1 * t1 / nb, 0.f);
+    if (w == 0) {
+      base[4 + ch] = stats[4 + ch];
+      base[4 + d + ch] = stats[4 + d + ch];
+      if (ch == 0) base[0] = stats[0];
+    }
+  }
+}
+
+constexpr int kChainBatch = 16;   // window moments a thread requests together
+
+// grid (column slabs, n windows), 256 threads.  Merges the windows 0 .. w into the old
+// statistics in window order (the merge of Eq. (8), as in probe_stats_bias_kernel), which
+// gives the statistics window w sees; the workgroups of the last window store them.  Then
+// the bias partials of window w, whose rows were requested first and arrive meanwhile.
+template <typename T>
+__global__ __launch_bounds__(256) void probe_chain_bias_kernel(const T* __restrict__ q_win,
+                                                               float* __restrict__ stats,
+                                                               const float* __restrict__ mom,
+                                                               const float* __restrict__ base,
+                                                               float* __restrict__ scratch, int m,
+                                                               int m_pad, int d, float eps,
+                                                               size_t scratch_stride) {
+  constexpr int V = Vec<T>::N;
+  constexpr int SLAB = kColLanes * V;
+  typedef typename Vec<T>::raw raw_t;
+  __shared__ float mu_lds[SLAB], iv_lds[SLAB];
+  const int w = blockIdx.y, n_win = gridDim.y;
+  const T* q = q_win + size_t(w) * m * d;
+  float* apart = scratch + size_t(w) * scratch_stride + size_t(blockIdx.x) * m_pad;
+  const int cl = threadIdx.x % kColLanes, rl = threadIdx.x / kColLanes;
+  const int ch0 = blockIdx.x * SLAB + cl * V;
+  const bool col_ok = ch0 < d;
+  const int n_pass = (m + kStatsRowsPerPass - 1) / kStatsRowsPerPass;
+  raw_t x[kRowsPerThread];
+  auto load_pass = [&](int pass) {
+#pragma unroll
+    for (int i = 0; i < kRowsPerThread; ++i) {
+      const int r = pass * kStatsRowsPerPass + rl * kRowsPerThread + i;
+      x[i] = Vec<T>::load_raw(q + size_t(r < m ? r : 0) * d + (col_ok ? ch0 : 0));
+    }
+  };
+  load_pass(0);
+  {
+    const int col = threadIdx.x, ch = blockIdx.x * SLAB + col;
+    if (col < SLAB && ch >= d) mu_lds[col] = iv_lds[col] = 0.f;
+    if (col < SLAB && ch < d) {
+      float n_run = base[0], mean = base[4 + ch], m2 = base[4 + d + ch];
+      const float nb = float(m);
+      for (int u0 = 0; u0 <= w; u0 += kChainBatch) {
+        float mean_b[kChainBatch], m2_b[kChainBatch];
+#pragma unroll
+        for (int i = 0; i < kChainBatch; ++i) {   // all loads first: they overlap
+          const int u = min(u0 + i, w);
+          mean_b[i] = mom[(size_t(u) * 2 + 0) * d + ch];
+          m2_b[i] = mom[(size_t(u) * 2 + 1) * d + ch];
+        }
+#pragma unroll
+        for (int i = 0; i < kChainBatch; ++i) {
+          if (u0 + i <= w) {
+            const float n_new = n_run + nb;
+            if (n_run > 0.f) {
+              const float delta = mean_b[i] - mean;
+              mean += delta * (nb / n_new);
+              m2 += m2_b[i] + delta * delta * (n_run * nb / n_new);
+            } else {
+              mean = mean_b[i];
+              m2 = m2_b[i];
+            }
+            n_run = n_new;
+          }
+        }
+      }
+      if (w == n_win - 1) {
+        stats[4 + ch] = mean;
+        stats[4 + d + ch] = m2;
+        if (ch == 0) stats[0] = n_run;
+      }
+      const float var = n_run > 1.f ? m2 / (n_run - 1.f) : 0.f;
+      mu_lds[col] = mean;
+      iv_lds[col] = 1.f / fmaxf(var, eps);
+    }
+  }
+  __syncthreads();
+  bias_partials<T>(x, load_pass, mu_lds, iv_lds, apart, m, m_pad, n_pass, cl, rl);
 }
 
 // probe_kv and the norm of the probe; run by one workgroup that sees the whole probe.
@@ -362,6 +531,21 @@ static int launch_probe_t(const actqkv_shape& sh, int batch, int m, const T* q_w
   static_assert(kColLanes * 8 == kProbeSlabBytes / 2 && kColLanes * 4 == kProbeSlabBytes / 4, "slab width");
   float* scratch = ws.scratch_f32();
   const int mean_pooling = (update_stats & ACTQKV_PROBE_MEAN_POOLING) != 0;
+  if (update_stats & ACTQKV_PROBE_WINDOW_CHAIN) {
+    // the batch entries are consecutive windows of one sequence with one set of statistics
+    float* mom = scratch + size_t(batch) * scratch_stride;
+    float* base = mom + size_t(batch) * 2 * d;
+    hipLaunchKernelGGL(probe_window_moments_kernel<T>, dim3(n_slabs, batch), dim3(256), 0, stream, q_win,
+                       stats, mom, base, m, d);
+    hipLaunchKernelGGL(probe_chain_bias_kernel<T>, dim3(n_slabs, batch), dim3(256), 0, stream, q_win, stats,
+                       mom, base, scratch, m, m_pad, d, eps, scratch_stride);
+    hipLaunchKernelGGL(probe_weigh_kernel<T>, dim3(n_slabs, batch), dim3(512), 0, stream, q_win, scratch,
+                       stats, 0, mean_pooling, probe, weights, m, m_pad, n_slabs, d, scratch_stride,
+                       size_t(0));
+    hipLaunchKernelGGL(probe_finish_kernel, dim3(batch), dim3(1024), 0, stream, probe, probe_kv,
+                       probe_norm, sh.n_q_heads, sh.n_kv_heads, sh.head_dim);
+    return hip_status("probe");
+  }
   update_stats &= ACTQKV_STATS_UPDATE;
   if (update_stats || (m > 1 && !mean_pooling)) {
     hipLaunchKernelGGL(probe_stats_bias_kernel<T>, dim3(n_slabs, batch), dim3(256), 0, stream, q_win,

@@ -186,9 +186,15 @@ class PrefillPipeline:
         self.probe_kv = torch.empty(plan.n_windows, dk, dtype=torch.float32, device=dev)
         self.probe_norm = torch.empty(plan.n_windows, dtype=torch.float32, device=dev)
         self.side_score = torch.cuda.Stream(device=dev)
+        # the chunk-at-a-time schedule: probes and scores of up to MAX_CHUNK windows per call
+        self.probe_chunk = torch.empty(self.MAX_CHUNK, runner.shape.n_q_heads * runner.shape.head_dim,
+                                       dtype=torch.float32, device=dev)
+        self.scores_chunk = torch.zeros(self.MAX_CHUNK, runner.score_stride, dtype=torch.float32, device=dev)
+        self.ws_probe = torch.zeros(B.workspace_bytes(runner.cs, self.MAX_CHUNK, runner.m, runner.nb_capacity,
+                                                      runner.k_cap), dtype=torch.uint8, device=dev)
 
     def run(self, q: torch.Tensor, k_cache, v_cache, rep_keys, out: torch.Tensor, overlap: bool = True,
-            events=None, chunk: int = 16, score_chunk: int = 16) -> None:
+            events=None, chunk: int = 16, score_chunk: int = 16, batched: bool = False) -> None:
         """q, out [N][H][D].  events: optional per-window (start, end) event pairs recorded around
         the attention call of a window; with overlap, the pair of a chunk's first window brackets
         the chunk's one call, on the stream it runs on.  chunk: with overlap, the second stream picks up
@@ -203,6 +209,8 @@ class PrefillPipeline:
         nb_begin = sh.n_init // sh.block_size
         cur = torch.cuda.current_stream()
         chunk = max(1, min(chunk, self.MAX_CHUNK))
+        if overlap and batched:
+            return self._run_batched(q, k_cache, v_cache, rep_keys, out, events, chunk)
         if overlap and score_chunk > 0:
             return self._run_three_streams(q, k_cache, v_cache, rep_keys, out, events, chunk, score_chunk)
 
@@ -259,6 +267,69 @@ class PrefillPipeline:
                 pending = []
         if overlap:
             cur.wait_stream(self.side)
+
+    def _run_batched(self, q, k_cache, v_cache, rep_keys, out, events, chunk) -> None:
+        """A chunk of windows per call, for every step of the path.  The running statistics of
+        Eq. (8) are the only thing a window hands to the next one within a layer, and merging a
+        window into them needs nothing but that window's own moments; scores, density, budget
+        and selection of a window depend on its probe alone.  So `chunk` consecutive full
+        windows go through one build_probe call (ACTQKV_PROBE_WINDOW_CHAIN), one score_blocks
+        and one select call on the current stream, and one attention call on the second stream,
+        which works on chunk c while the current stream prepares chunk c + 1.  A ragged last
+        window goes through calls of its own."""
+        r, plan = self.runner, self.plan
+        sh, cs = r.shape, r.cs
+        nb_begin = sh.n_init // sh.block_size
+        cur, last = torch.cuda.current_stream(), self.side
+        last.wait_stream(cur)
+        self.chunk_starts = []
+
+        def single(u):
+            w0, rows = plan.w0[u], plan.rows[u]
+            bud = None if plan.budget is None else plan.budget[u:u + 1]
+            rest = None if plan.rest is None else plan.rest[u:u + 1]
+            nb_cap = min(max(plan.nb_end_host[u], nb_begin), r.nb_capacity)
+            B.build_probe(cs, 1, rows, q[w0:w0 + rows], r.stats, True, r.probe, self.probe_kv[u],
+                          self.probe_norm[u:u + 1], None, r.workspace)
+            B.score_blocks(cs, 1, self.probe_kv[u], self.probe_norm[u:u + 1], rep_keys, 0, nb_cap,
+                           nb_begin, plan.nb_end[u:u + 1], r.scores, r.score_stride)
+            B.select(1, r.scores, r.score_stride, nb_cap, nb_begin, plan.nb_end[u:u + 1], r.k_cap, bud,
+                     rest, self.idx[u], self.n_sel[u:u + 1], None, None)
+
+        t0 = 0
+        while t0 < plan.n_windows:
+            n_p = 0
+            while t0 + n_p < plan.n_windows and n_p < chunk and plan.rows[t0 + n_p] == r.m:
+                n_p += 1
+            if n_p >= 2:
+                w0, t1 = plan.w0[t0], t0 + n_p
+                B.build_probe(cs, n_p, r.m, q[w0:w0 + n_p * r.m], r.stats,
+                              B.STATS_UPDATE | B.PROBE_WINDOW_CHAIN, self.probe_chunk, self.probe_kv[t0:t1],
+                              self.probe_norm[t0:t1], None, self.ws_probe)
+                nb_cap = min(max(plan.nb_end_host[t1 - 1], nb_begin), r.nb_capacity)
+                B.score_blocks(cs, n_p, self.probe_kv[t0:t1], self.probe_norm[t0:t1], rep_keys, 0, nb_cap,
+                               nb_begin, plan.nb_end[t0:t1], self.scores_chunk, r.score_stride)
+                B.select(n_p, self.scores_chunk, r.score_stride, nb_cap, nb_begin, plan.nb_end[t0:t1],
+                         r.k_cap, None if plan.budget is None else plan.budget[t0:t1],
+                         None if plan.rest is None else plan.rest[t0:t1], self.idx[t0:t1],
+                         self.n_sel[t0:t1], None, None)
+            else:
+                n_p = 1
+                single(t0)
+            selected = torch.cuda.Event()
+            selected.record(cur)
+            last.wait_event(selected)
+            self.chunk_starts.append(t0)
+            if events is not None:
+                events[t0][0].record(last)
+            w0, rows = plan.w0[t0], plan.rows[t0]
+            B.retrieval_attention(cs, n_p, rows, q[w0:w0 + n_p * rows], k_cache, v_cache, 0, r.nb_capacity,
+                                  plan.n_ctx[t0:t0 + n_p], self.idx[t0:t0 + n_p], self.n_sel[t0:t0 + n_p],
+                                  r.k_cap, out[w0:w0 + n_p * rows], None, self.ws_attn, last)
+            if events is not None:
+                events[t0][1].record(last)
+            t0 += n_p
+        cur.wait_stream(last)
 
     def _run_three_streams(self, q, k_cache, v_cache, rep_keys, out, events, chunk, score_chunk) -> None:
         """The selection chain cut in two as well.  The probe of a window (statistics, bias,

@@ -63,6 +63,10 @@ def test_build_probe_rejects(lib):
     assert _probe(lib, cs, ws=None) == -4
     assert _probe(lib, cs, wsb=100) == -4 and b"needs" in lib.actqkv_last_error()
     assert lib.actqkv_build_probe(None, 1, 1, A16, A16, 0, A16, A16, A16, None, A16, 1 << 20, None) == -1
+    # consecutive windows of one sequence: need the update bit and m >= 2; unknown bits
+    assert _probe(lib, cs, batch=4, upd=B.PROBE_WINDOW_CHAIN) == -1 and b"ACTQKV_STATS_UPDATE" in lib.actqkv_last_error()
+    assert _probe(lib, cs, batch=4, m=1, upd=B.PROBE_WINDOW_CHAIN | B.STATS_UPDATE) == -1
+    assert _probe(lib, cs, upd=8) == -1 and b"unknown bits" in lib.actqkv_last_error()
 
 
 @pytest.mark.parametrize("field,value,code", [("head_dim", 96, -2), ("n_kv_heads", 5, -2),

@@ -169,6 +169,28 @@ def test_c3_128k_two_stream_pipeline_as_benchmarked():
     diff = (out_two.float() - out_order.float()).abs().max().item()
     scale = out_order.float().abs().max().item()
     assert diff <= TOL_OUT["bf16"] * scale, f"two streams vs window order: {diff}"
+    # the benchmarked schedule: one probe, one score, one select and one attention call per 16
+    # windows.  The statistics are merged from per-window moments, so probes differ from the
+    # window-order ones in rounding; selections may differ only where blocks all but tie.
+    out_c = torch.zeros_like(qd)
+    runner.reset()
+    plan.budget.copy_(bud0)
+    pipe.idx.fill_(-1)
+    B.set_attention_cus(224)
+    try:
+        pipe.run(qd, kc, vc, repd, out_c, overlap=True, batched=True)
+        torch.cuda.synchronize()
+    finally:
+        B.set_attention_cus(256)
+    assert torch.equal(pipe.n_sel, nsel_order)
+    differ = [t for t in range(w.n_windows) if not torch.equal(pipe.idx[t], idx_order[t])]
+    assert len(differ) <= w.n_windows // 50, f"{len(differ)} windows select differently: {differ[:8]}"
+    same_rows = torch.ones(w.n_ctx, dtype=torch.bool)
+    for t in differ:
+        same_rows[plan.w0[t]:plan.w0[t] + plan.rows[t]] = False
+    diff_c = (out_c.float() - out_order.float()).abs().amax(dim=(1, 2)).cpu()[same_rows].max().item()
+    assert diff_c <= TOL_OUT["bf16"] * scale, f"chunked calls vs window order: {diff_c}"
+    out_two = out_c
     attend = [3, 130, 255]
     want = oracle_windows(q, k, v, rep, sh, w.window, w.k_cap, cutoffs, attend)
     worst = 0.0
@@ -183,7 +205,8 @@ def test_c3_128k_two_stream_pipeline_as_benchmarked():
         err = out_error(out_two[res["w0"]:res["w0"] + ref.shape[0]], ref)
         worst = max(worst, err)
         assert err < TOL_OUT["bf16"], f"attention output, window {t}: {err}"
-    _say(f"[case] {w.name} two streams: selections equal, max |two - order| {diff:.3e}, worst out err {worst:.3e}")
+    _say(f"[case] {w.name} two streams: selections equal, max |two - order| {diff:.3e}; chunked calls: "
+         f"{len(differ)} windows with a near-tie swap, max |chunked - order| {diff_c:.3e}, worst out err {worst:.3e}")
 
 
 @pytest.mark.parametrize("hq,hkv,d,dtype", [(28, 4, 128, "bf16"), (6, 2, 64, "fp32"), (12, 4, 128, "bf16")])
@@ -575,20 +598,22 @@ def test_pipeline_with_ragged_last_window_and_short_context():
         bud0 = plan.budget.clone()
         pipe = H.PrefillPipeline(runner, plan)
         outs = []
-        for overlap in (False, True):
+        for overlap, batched in ((False, False), (True, False), (True, True)):
             runner.reset()
             plan.budget.copy_(bud0)
             out = torch.zeros_like(qd)
             B.set_attention_cus(224 if overlap else 256)
             try:
-                pipe.run(qd, kc, vc, repd, out, overlap=overlap, chunk=4, score_chunk=4)
+                pipe.run(qd, kc, vc, repd, out, overlap=overlap, chunk=4, score_chunk=4, batched=batched)
                 torch.cuda.synchronize()
             finally:
                 B.set_attention_cus(256)
             outs.append((out, pipe.idx.clone(), pipe.n_sel.clone()))
-        assert torch.equal(outs[0][1], outs[1][1]) and torch.equal(outs[0][2], outs[1][2])
-        diff = (outs[0][0].float() - outs[1][0].float()).abs().max().item()
-        assert diff <= TOL_OUT["bf16"] * outs[0][0].float().abs().max().item()
+        for other in outs[1:]:
+            assert torch.equal(outs[0][1], other[1]) and torch.equal(outs[0][2], other[2])
+            diff = (outs[0][0].float() - other[0].float()).abs().max().item()
+            assert diff <= TOL_OUT["bf16"] * outs[0][0].float().abs().max().item()
+        outs[1] = outs[2]
         want = oracle_windows(q, k, v, rep, sh, w.window, w.k_cap, cutoffs, [w.n_windows - 1])
         res = want[w.n_windows - 1]
         err = out_error(outs[1][0][res["w0"]:res["w0"] + res["out"].shape[0]], res["out"])
@@ -620,3 +645,56 @@ def test_mean_pooling_probe_variant():
         kv = want.reshape(8, 4, 128).sum(axis=1).reshape(-1)
         assert rel_to_max(runs["mean"][1][s], kv) < TOL_PROBE
         assert rel_to_max(runs["probe"][0][s], want) > 10 * TOL_PROBE   # the activation-aware probe differs
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d,m,calls", [
+    ("bf16", 32, 8, 128, 512, (3, 5)),      # the benchmarked shape; a second call continues the first
+    ("fp32", 6, 2, 64, 96, (1, 4)),         # fp32 storage, group size 3; a call of one window
+    ("bf16", 8, 8, 128, 1100, (19,)),       # more than one pass of rows, more windows than a merge batch
+])
+def test_probe_of_consecutive_windows_in_one_call(dtype, hq, hkv, d, m, calls):
+    """ACTQKV_PROBE_WINDOW_CHAIN: n consecutive windows of one sequence in one build_probe call
+    give, window by window, the probe, weights and norm of Eq. (7)-(9) with the statistics of
+    Eq. (8) over every query up to and including that window, and leave those of the last."""
+    sh = LayerShape(hq, hkv, d, 128, 4, 128, 512, dtype)
+    cs = B.c_shape(sh)
+    dd = hq * d
+    n_total = sum(calls)
+    _say(f"[case] probe chain {dtype} H{hq}/Hk{hkv}/D{d} m={m} calls={calls}")
+    g = torch.Generator().manual_seed(99 + m)
+    # a drifting mean and scale, so that the statistics of later windows differ from the first
+    drift = torch.linspace(-0.5, 0.8, n_total).view(n_total, 1, 1, 1)
+    q = torch.randn(n_total, m, hq, d, generator=g) * (1.0 + drift.abs()) + drift
+    q[:, :, :, 5] *= 4.0                                  # a few loud channels
+    q = q.to(torch.bfloat16 if dtype == "bf16" else torch.float32)
+    qd = q.to(DEV)
+    n_max = max(calls)
+    stats = torch.zeros(B.stats_floats(cs), device=DEV)
+    ws = torch.zeros(B.workspace_bytes(cs, n_max, m, 8, 4), dtype=torch.uint8, device=DEV)
+    probe = torch.zeros(n_total, dd, device=DEV)
+    probe_kv = torch.zeros(n_total, hkv * d, device=DEV)
+    norm = torch.zeros(n_total, device=DEV)
+    wts = torch.zeros(n_total, m, device=DEV)
+    t0 = 0
+    for n in calls:
+        B.build_probe(cs, n, m, qd[t0:t0 + n], stats, B.STATS_UPDATE | B.PROBE_WINDOW_CHAIN, probe[t0:t0 + n],
+                      probe_kv[t0:t0 + n], norm[t0:t0 + n], wts[t0:t0 + n], ws)
+        t0 += n
+    torch.cuda.synchronize()
+    rs = orc.RunningStats(dd)
+    for t in range(n_total):
+        qw = f64(q[t]).reshape(m, dd)
+        z_bar, sigma2 = rs.update(qw)
+        want, w_want = orc.probe_query(qw, orc.activation_bias(qw, z_bar, sigma2))
+        assert rel_to_max(probe[t], want) < TOL_PROBE, f"probe, window {t}"
+        assert rel_to_max(wts[t], w_want) < TOL_WEIGHT, f"weights, window {t}"
+        assert abs(float(norm[t]) - np.linalg.norm(want)) < TOL_PROBE * np.linalg.norm(want)
+        kv = want.reshape(hkv, hq // hkv, d).sum(axis=1).reshape(-1)
+        assert rel_to_max(probe_kv[t], kv) < TOL_PROBE, f"probe_kv, window {t}"
+    st = f64(stats)
+    assert st[0] == n_total * m
+    assert rel_to_max(st[4:4 + dd], rs.mean) < 1e-5
+    assert rel_to_max(st[4 + dd:4 + 2 * dd], rs.m2) < 1e-4
+    # the flag needs the update bit and a window of more than one token
+    with pytest.raises(B.ActQKVError):
+        B.build_probe(cs, 2, m, qd[:2], stats, B.PROBE_WINDOW_CHAIN, probe[:2], probe_kv[:2], norm[:2], None, ws)
