@@ -435,7 +435,7 @@ def main() -> int:
     ap.add_argument("--decode-layers", type=int, default=0, help="override the layer count (testing)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="prefill: one stream, strictly in window order")
-    ap.add_argument("--chunk", type=int, default=16,
+    ap.add_argument("--chunk", type=int, default=32,
                     help="prefill, two streams: windows per hand-over between the streams")
     ap.add_argument("--score-chunk", type=int, default=16,
                     help="prefill: > 0 puts scoring and selection on a stream of their own, this many "

@@ -194,7 +194,7 @@ class PrefillPipeline:
                                                       runner.k_cap), dtype=torch.uint8, device=dev)
 
     def run(self, q: torch.Tensor, k_cache, v_cache, rep_keys, out: torch.Tensor, overlap: bool = True,
-            events=None, chunk: int = 16, score_chunk: int = 16, batched: bool = False) -> None:
+            events=None, chunk: int = 32, score_chunk: int = 16, batched: bool = False) -> None:
         """q, out [N][H][D].  events: optional per-window (start, end) event pairs recorded around
         the attention call of a window; with overlap, the pair of a chunk's first window brackets
         the chunk's one call, on the stream it runs on.  chunk: with overlap, the second stream picks up

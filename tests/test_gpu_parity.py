@@ -118,11 +118,13 @@ def test_c3_128k_full_size_sampled_windows():
 
 
 def test_c3_128k_two_stream_pipeline_as_benchmarked():
-    """configs[2] at full size the way bench.py times it: the probes on one stream, scoring and
-    selection 16 windows behind them on a second, the attention of 16 windows per launch on a
-    third with 224 of the 256 compute units.  Every window's selection must equal the one found
-    in window order; the attention of sampled windows is checked against the oracle and all
-    rows against the window-order result.  The two-stream schedule is checked the same way."""
+    """configs[2] at full size in the schedules of PrefillPipeline, the last one being the one
+    bench.py times: (1) three streams, calls of one window each: probes, then scoring and
+    selection 16 windows behind them, then the attention of up to 32 windows per launch with 224
+    of the 256 compute units; (2) the same with scoring and selection on the probes' stream;
+    (3) one probe, one score, one select and one attention call per 32 windows.  Every window's
+    selection must equal the one found in window order; the attention of sampled windows is
+    checked against the oracle and all rows against the window-order result."""
     w = synth.WORKLOADS["c3_128k"]
     sh = w.shape
     _say(f"[case] {w.name} two streams N={w.n_ctx} seed={w.seed}")
@@ -169,7 +171,7 @@ def test_c3_128k_two_stream_pipeline_as_benchmarked():
     diff = (out_two.float() - out_order.float()).abs().max().item()
     scale = out_order.float().abs().max().item()
     assert diff <= TOL_OUT["bf16"] * scale, f"two streams vs window order: {diff}"
-    # the benchmarked schedule: one probe, one score, one select and one attention call per 16
+    # the benchmarked schedule: one probe, one score, one select and one attention call per 32
     # windows.  The statistics are merged from per-window moments, so probes differ from the
     # window-order ones in rounding; selections may differ only where blocks all but tie.
     out_c = torch.zeros_like(qd)
