@@ -50,7 +50,7 @@
 extern "C" {
 #endif
 
-#define ACTQKV_VERSION 100
+#define ACTQKV_VERSION 101
 
 enum {
   ACTQKV_OK = 0,
@@ -68,6 +68,11 @@ enum {
   ACTQKV_STATS_UPDATE = 1,        /* merge the window into the running statistics first */
   ACTQKV_PROBE_MEAN_POOLING = 2,  /* ablation baseline (Sec. 5.3): every token weighs 1/m */
   ACTQKV_PROBE_WINDOW_CHAIN = 4   /* the batch entries are consecutive windows of ONE sequence */
+};
+
+/* Bits of the flags argument of actqkv_select. */
+enum {
+  ACTQKV_SELECT_ENTROPY_TOPK = 1  /* density over the k_cap best blocks only (see actqkv_select) */
 };
 
 /* Limits checked by every call (ACTQKV_ESHAPE otherwise):
@@ -146,6 +151,10 @@ int actqkv_score_blocks(const actqkv_shape* shape, int batch, const float* probe
 /* Information density, budget and selection (Eq. (11), (12), Alg. 1) over the
  * eligible blocks nb_begin <= b < nb_end[s] of each sequence.
  *   theta = entropy (natural log) of softmax(scores over the eligible blocks).
+ *           flags & ACTQKV_SELECT_ENTROPY_TOPK: of softmax(scores over the min(k_cap,
+ *           n_eligible) best blocks) instead - the other way to read Eq. (11), whose
+ *           Fig. 3 values (a perplexity near the number of retrieved chunks) fit a
+ *           distribution over the candidates rather than over the whole cache.
  *   Dynamic cut-off state (device memory, Sec. 4.2), both pointers or neither:
  *     budget_remaining [batch] fp32  B_kv, in blocks; B^l is subtracted from it, so the same
  *                                    array is handed from layer to layer within a step
@@ -158,10 +167,10 @@ int actqkv_score_blocks(const actqkv_shape* shape, int batch, const float* probe
  *   n_sel   [batch] int32 = E (0 when nothing is eligible; theta and budget are 0 then
  *           and budget_remaining is left alone).
  *   theta, budget  [batch] fp32, may be NULL.
- * Errors: EINVAL (null, one cut-off pointer without the other), ESHAPE (k_cap, more than
- * 8192 blocks), EALIGN. */
+ * Errors: EINVAL (null, one cut-off pointer without the other, unknown flag bits), ESHAPE
+ * (k_cap, more than 8192 blocks), EALIGN. */
 int actqkv_select(int batch, const float* scores, int64_t score_stride, int nb_capacity,
-                  int nb_begin, const int32_t* nb_end, int k_cap, float* budget_remaining,
+                  int nb_begin, const int32_t* nb_end, int k_cap, int flags, float* budget_remaining,
                   const float* theta_rest_sum, int32_t* idx, int32_t* n_sel, float* theta,
                   float* budget, void* stream);
 
@@ -235,6 +244,28 @@ int actqkv_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_p
  * under one setting may be too small under a larger one, which the calls report as
  * ACTQKV_EWORKSPACE).  Results do not depend on it beyond the order of floating-point sums. */
 int actqkv_set_attention_cus(int cus);
+
+/* Selected blocks from a block store into a working cache (Sec. 3.1: the cache may be kept
+ * in CPU memory).
+ *   k_store, v_store  the whole context in the blocked cache layouts,
+ *            [batch][nb_store][Hk][Bs][D] and [batch][nb_store][Hk][D][Bs]; any memory the
+ *            device can read in place: pinned host memory (hipHostMalloc) or device memory.
+ *            store_seq_stride = elements between two sequences.
+ *   idx, n_sel, k_cap  as written by actqkv_select (device memory).
+ *   k_cache, v_cache   device working cache of nb_capacity blocks; block idx[s][j], j < n_sel[s],
+ *            is copied to block slot0 + j (slot0 + k_cap <= nb_capacity).  The caller keeps the
+ *            initial tokens in the blocks before slot0 and the local span and the window in the
+ *            blocks from slot0 + k_cap on, i.e. at positions shifted by a multiple of Bs, and
+ *            passes n_ctx in those shifted positions to actqkv_retrieval_attention.
+ *   idx_slots [batch][k_cap] int32, device, may be NULL: slot0 + j for j < n_sel[s], else -1 -
+ *            the selection actqkv_retrieval_attention takes on the working cache.
+ * Entries of idx outside [0, nb_store) are skipped (their idx_slots entry is -1).
+ * Errors: EINVAL (null, slots outside the cache), ESHAPE, EALIGN. */
+int actqkv_gather_blocks(const actqkv_shape* shape, int batch, const void* k_store,
+                         const void* v_store, int64_t store_seq_stride, int nb_store,
+                         const int32_t* idx, const int32_t* n_sel, int k_cap, void* k_cache,
+                         void* v_cache, int64_t cache_seq_stride, int nb_capacity, int slot0,
+                         int32_t* idx_slots, void* stream);
 
 /* Measurement aid, not a step of the method: a plain copy of `bytes` bytes (a multiple
  * of 16; both pointers device memory, 16-byte aligned, not overlapping) done by one

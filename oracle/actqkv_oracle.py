@@ -164,6 +164,14 @@ def information_density(scores) -> float:
     return float(-(p * np.log(p)).sum())
 
 
+def information_density_topk(scores, k: int) -> float:
+    """The other reading of Eq. (11) (its domain is stated as the whole cache, while the
+    perplexities Fig. 3 shows are close to the number of retrieved chunks): the same entropy
+    over the k highest scores only."""
+    s = np.sort(_f64(scores))[::-1][:k]
+    return information_density(s)
+
+
 def layer_budget(theta: float, rest: float, b_kv: float) -> float:
     """Eq. (12): B^l = Theta^l / (Theta^l + R) * B_kv, R = the summed mean
     densities of the layers still to come.  0/0 (one eligible block, nothing

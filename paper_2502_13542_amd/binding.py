@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libactqkv.so")
 
 ACTQKV_F32, ACTQKV_BF16 = 0, 1
 STATS_UPDATE, PROBE_MEAN_POOLING, PROBE_WINDOW_CHAIN = 1, 2, 4   # bits of build_probe's update_stats
+SELECT_ENTROPY_TOPK = 1                                           # bit of select's flags
 ERROR_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EALIGN", -4: "EWORKSPACE", -5: "EHIP"}
 
 
@@ -51,13 +52,14 @@ SIGNATURES = {
     "actqkv_workspace_bytes": (_sz, [_shp, _i, _i, _i, _i]),
     "actqkv_build_probe": (_i, [_shp, _i, _i, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "actqkv_score_blocks": (_i, [_shp, _i, _vp, _vp, _vp, _i64, _i, _i, _vp, _vp, _i64, _vp]),
-    "actqkv_select": (_i, [_i, _vp, _i64, _i, _i, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "actqkv_select": (_i, [_i, _vp, _i64, _i, _i, _vp, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_retrieval_attention": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
                                         _vp, _vp, _vp, _sz, _vp]),
     "actqkv_append_kv": (_i, [_shp, _i, _i, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _vp]),
     "actqkv_cutoff_next_step": (_i, [_i, _i, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_set_attention_cus": (_i, [_i]),
     "actqkv_copy_bytes": (_i, [_vp, _vp, _sz, _vp]),
+    "actqkv_gather_blocks": (_i, [_shp, _i, _vp, _vp, _i64, _i, _vp, _vp, _i, _vp, _vp, _i64, _i, _i, _vp, _vp]),
     "actqkv_last_error": (ctypes.c_char_p, []),
     "actqkv_version": (_i, []),
 }
@@ -92,6 +94,17 @@ def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
         return None
     if not t.is_cuda:
         raise ActQKVError(-1, "tensor is not on the GPU")
+    if not t.is_contiguous():
+        raise ActQKVError(-1, "tensor is not contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ActQKVError(-1, f"tensor dtype {t.dtype}, expected {dtype}")
+    return t.data_ptr()
+
+
+def _ptr_readable(t: torch.Tensor, dtype=None) -> int:
+    """A tensor a kernel may read in place: device memory or pinned host memory."""
+    if not (t.is_cuda or t.is_pinned()):
+        raise ActQKVError(-1, "tensor is neither on the GPU nor in pinned host memory")
     if not t.is_contiguous():
         raise ActQKVError(-1, "tensor is not contiguous")
     if dtype is not None and t.dtype != dtype:
@@ -164,6 +177,17 @@ def build_probe(shape: CShape, batch: int, m: int, q_win, stats, update_stats, p
         workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
+def gather_blocks(shape: CShape, batch: int, k_store, v_store, store_seq_stride: int, nb_store: int,
+                  idx, n_sel, k_cap: int, k_cache, v_cache, cache_seq_stride: int, nb_capacity: int,
+                  slot0: int, idx_slots, stream=None) -> None:
+    st = torch.float32 if shape.dtype == ACTQKV_F32 else torch.bfloat16
+    _check(load_library().actqkv_gather_blocks(
+        ctypes.byref(shape), batch, _ptr_readable(k_store, st), _ptr_readable(v_store, st),
+        store_seq_stride, nb_store, _ptr(idx, torch.int32), _ptr(n_sel, torch.int32), k_cap,
+        _ptr(k_cache, st), _ptr(v_cache, st), cache_seq_stride, nb_capacity, slot0,
+        _ptr(idx_slots, torch.int32), _stream(stream)))
+
+
 def score_blocks(shape: CShape, batch: int, probe_kv, probe_norm, rep_keys, seq_stride: int,
                  nb_capacity: int, nb_begin: int, nb_end, scores, score_stride: int,
                  stream=None) -> None:
@@ -176,10 +200,10 @@ def score_blocks(shape: CShape, batch: int, probe_kv, probe_norm, rep_keys, seq_
 
 def select(batch: int, scores, score_stride: int, nb_capacity: int, nb_begin: int, nb_end,
            k_cap: int, budget_remaining, theta_rest_sum, idx, n_sel, theta=None, budget=None,
-           stream=None) -> None:
+           stream=None, flags: int = 0) -> None:
     _check(load_library().actqkv_select(
         batch, _ptr(scores, torch.float32), score_stride, nb_capacity, nb_begin,
-        _ptr(nb_end, torch.int32), k_cap, _ptr(budget_remaining, torch.float32),
+        _ptr(nb_end, torch.int32), k_cap, int(flags), _ptr(budget_remaining, torch.float32),
         _ptr(theta_rest_sum, torch.float32), _ptr(idx, torch.int32),
         _ptr(n_sel, torch.int32), _ptr(theta, torch.float32), _ptr(budget, torch.float32),
         _stream(stream)))

@@ -261,9 +261,10 @@ int actqkv_score_blocks(const actqkv_shape* shape, int batch, const float* probe
 }
 
 int actqkv_select(int batch, const float* scores, int64_t score_stride, int nb_capacity, int nb_begin,
-                  const int32_t* nb_end, int k_cap, float* budget_remaining,
+                  const int32_t* nb_end, int k_cap, int flags, float* budget_remaining,
                   const float* theta_rest_sum, int32_t* idx, int32_t* n_sel, float* theta,
                   float* budget, void* stream) {
+  if (flags & ~ACTQKV_SELECT_ENTROPY_TOPK) return set_error(ACTQKV_EINVAL, "select: unknown flag bits: %d", flags);
   ACTQKV_TRY(check_batch(batch));
   ACTQKV_TRY(check_blocks(nb_capacity, nb_begin, k_cap, true));
   ACTQKV_REQUIRE_SMALL(scores, 4);
@@ -279,8 +280,9 @@ int actqkv_select(int batch, const float* scores, int64_t score_stride, int nb_c
   if (score_stride < nb_capacity)
     return set_error(ACTQKV_EINVAL, "score_stride %lld < nb_capacity %d", (long long)score_stride,
                      nb_capacity);
-  return launch_select(batch, scores, score_stride, nb_capacity, nb_begin, nb_end, k_cap, budget_remaining,
-                       theta_rest_sum, idx, n_sel, theta, budget, static_cast<hipStream_t>(stream));
+  return launch_select(batch, scores, score_stride, nb_capacity, nb_begin, nb_end, k_cap, flags,
+                       budget_remaining, theta_rest_sum, idx, n_sel, theta, budget,
+                       static_cast<hipStream_t>(stream));
 }
 
 int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, const void* q,
@@ -334,6 +336,33 @@ int actqkv_copy_bytes(void* dst, const void* src, size_t bytes, void* stream) {
   hipLaunchKernelGGL(copy_bytes_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n);
   return hip_status("copy_bytes");
+}
+
+int actqkv_gather_blocks(const actqkv_shape* shape, int batch, const void* k_store, const void* v_store,
+                         int64_t store_seq_stride, int nb_store, const int32_t* idx, const int32_t* n_sel,
+                         int k_cap, void* k_cache, void* v_cache, int64_t cache_seq_stride,
+                         int nb_capacity, int slot0, int32_t* idx_slots, void* stream) {
+  ACTQKV_TRY(check_shape(shape));
+  ACTQKV_TRY(check_batch(batch));
+  if (k_cap < 1 || k_cap > 64) return set_error(ACTQKV_ESHAPE, "k_cap %d outside 1..64", k_cap);
+  if (nb_store < 1 || nb_capacity < 1) return set_error(ACTQKV_EINVAL, "gather_blocks: empty store or cache");
+  if (slot0 < 0 || int64_t(slot0) + k_cap > nb_capacity)
+    return set_error(ACTQKV_EINVAL, "gather_blocks: slots %d .. %d outside the cache of %d blocks", slot0,
+                     slot0 + k_cap - 1, nb_capacity);
+  ACTQKV_REQUIRE_PTR(k_store);
+  ACTQKV_REQUIRE_PTR(v_store);
+  ACTQKV_REQUIRE_PTR(k_cache);
+  ACTQKV_REQUIRE_PTR(v_cache);
+  ACTQKV_REQUIRE_SMALL(idx, 4);
+  ACTQKV_REQUIRE_SMALL(n_sel, 4);
+  ACTQKV_OPTIONAL_SMALL(idx_slots, 4);
+  const int64_t block_elems = int64_t(shape->n_kv_heads) * shape->block_size * shape->head_dim;
+  if (batch > 1 && (store_seq_stride < nb_store * block_elems || cache_seq_stride < nb_capacity * block_elems))
+    return set_error(ACTQKV_EINVAL, "gather_blocks: a sequence stride is smaller than one sequence");
+  if (store_seq_stride % 8 != 0 || cache_seq_stride % 8 != 0)
+    return set_error(ACTQKV_EALIGN, "sequence strides must be multiples of 8 elements");
+  return launch_gather(*shape, batch, k_store, v_store, store_seq_stride, nb_store, idx, n_sel, k_cap, k_cache,
+                       v_cache, cache_seq_stride, slot0, idx_slots, static_cast<hipStream_t>(stream));
 }
 
 int actqkv_append_kv(const actqkv_shape* shape, int batch, int m, const void* k_new, const void* v_new,

@@ -75,7 +75,7 @@ int launch_score(const actqkv_shape& sh, int batch, const float* probe_kv, const
                  const void* rep_keys, int64_t seq_stride, int nb_capacity, int nb_begin,
                  const int32_t* nb_end, float* scores, int64_t score_stride, hipStream_t stream);
 int launch_select(int batch, const float* scores, int64_t score_stride, int nb_capacity, int nb_begin,
-                  const int32_t* nb_end, int k_cap, float* budget_remaining,
+                  const int32_t* nb_end, int k_cap, int flags, float* budget_remaining,
                   const float* theta_rest_sum, int32_t* idx, int32_t* n_sel, float* theta,
                   float* budget, hipStream_t stream);
 int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
@@ -86,6 +86,11 @@ int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, co
 int launch_append(const actqkv_shape& sh, int batch, int m, const void* k_new, const void* v_new,
                   const int32_t* pos0, void* k_cache, void* v_cache, int64_t cache_stride,
                   void* rep_keys, int64_t rep_stride, int nb_capacity, hipStream_t stream);
+
+int launch_gather(const actqkv_shape& sh, int batch, const void* k_store, const void* v_store,
+                  int64_t store_stride, int nb_store, const int32_t* idx, const int32_t* n_sel, int k_cap,
+                  void* k_cache, void* v_cache, int64_t cache_stride, int slot0, int32_t* idx_slots,
+                  hipStream_t stream);
 
 int launch_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_prior,
                             const float* theta_prev, float* theta_sum, float* n_steps,

@@ -2,7 +2,8 @@
 // (Sec. 4.2, Eq. (11), Eq. (12); Alg. 1, second and third loop).
 //
 // One workgroup of 16 wavefronts per sequence.  The density is a two-pass softmax
-// entropy over the eligible scores.  The E best blocks come from a tournament:
+// entropy over the eligible scores (or, as a variant, over the scores of the k_cap best
+// blocks once the tournament has found them).  The E best blocks come from a tournament:
 // every wavefront bitonic-sorts 64 (score, index) keys at a time across its lanes
 // with shuffles and keeps a running sorted top-64; the 16 lists are then merged
 // pairwise through LDS, each merge keeping the better 64.  Keys are 64-bit:
@@ -55,9 +56,41 @@ __device__ __forceinline__ unsigned long long bitonic_sort_desc(unsigned long lo
   return v;
 }
 
+// Eq. (12), the budget update that follows it, and E^l (Alg. 1); called by one thread.
+__device__ __forceinline__ int cutoff_count(float theta, int s, int n, int k_cap,
+                                            float* __restrict__ budget_remaining,
+                                            const float* __restrict__ theta_rest_sum,
+                                            int32_t* __restrict__ n_sel, float* __restrict__ theta_out,
+                                            float* __restrict__ budget_out) {
+  float b_l;
+  int e;
+  if (budget_remaining != nullptr) {
+    float b_kv = budget_remaining[s], rest = theta_rest_sum[s];
+    float den = theta + rest;
+    b_l = den > 0.f ? theta / den * b_kv : b_kv;
+    float r = fminf(fmaxf(floorf(b_l + 0.5f), 1.f), float(k_cap));
+    e = min(int(r), n);
+    budget_remaining[s] = b_kv - b_l;
+  } else {
+    e = min(k_cap, n);
+    b_l = float(e);
+  }
+  n_sel[s] = e;
+  if (theta_out) theta_out[s] = theta;
+  if (budget_out) budget_out[s] = b_l;
+  return e;
+}
+
+// the score a tournament key was made from
+__device__ __forceinline__ float key_score(unsigned long long key) {
+  uint32_t u = uint32_t(key >> 32);
+  u ^= (u >> 31) ? 0x80000000u : 0xffffffffu;
+  return __uint_as_float(u);
+}
+
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     const float* __restrict__ scores, int64_t score_stride, int nb_capacity, int nb_begin,
-    const int32_t* __restrict__ nb_end, int k_cap, float* __restrict__ budget_remaining,
+    const int32_t* __restrict__ nb_end, int k_cap, int entropy_topk, float* __restrict__ budget_remaining,
     const float* __restrict__ theta_rest_sum, int32_t* __restrict__ idx, int32_t* __restrict__ n_sel, float* __restrict__ theta_out,
     float* __restrict__ budget_out) {
   __shared__ float red[32];
@@ -78,38 +111,22 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     }
     return;
   }
-  // Eq. (11): theta = -sum P ln P with P = softmax(s) = ln Z + max - sum P s
-  float mx = -INFINITY;
-  for (int i = tid; i < n; i += kSelectThreads) mx = fmaxf(mx, sc[i]);
-  mx = block_max(mx, red);
-  float z = 0.f, t = 0.f;
-  for (int i = tid; i < n; i += kSelectThreads) {
-    float v = sc[i], e = __expf(v - mx);
-    z += e;
-    t += e * v;
-  }
-  z = block_sum(z, red);
-  t = block_sum(t, red);
-  if (tid == 0) {
-    float theta = fmaxf(logf(z) + mx - t / z, 0.f);
-    float b_l;
-    int e;
-    if (budget_remaining != nullptr) {
-      // Eq. (12) and the budget update that follows it
-      float b_kv = budget_remaining[s], rest = theta_rest_sum[s];
-      float den = theta + rest;
-      b_l = den > 0.f ? theta / den * b_kv : b_kv;
-      float r = fminf(fmaxf(floorf(b_l + 0.5f), 1.f), float(k_cap));
-      e = min(int(r), n);
-      budget_remaining[s] = b_kv - b_l;
-    } else {
-      e = min(k_cap, n);
-      b_l = float(e);
+  if (!entropy_topk) {
+    // Eq. (11): theta = -sum P ln P with P = softmax(s) = ln Z + max - sum P s
+    float mx = -INFINITY;
+    for (int i = tid; i < n; i += kSelectThreads) mx = fmaxf(mx, sc[i]);
+    mx = block_max(mx, red);
+    float z = 0.f, t = 0.f;
+    for (int i = tid; i < n; i += kSelectThreads) {
+      float v = sc[i], e = __expf(v - mx);
+      z += e;
+      t += e * v;
     }
-    e_shared = e;
-    n_sel[s] = e;
-    if (theta_out) theta_out[s] = theta;
-    if (budget_out) budget_out[s] = b_l;
+    z = block_sum(z, red);
+    t = block_sum(t, red);
+    if (tid == 0)
+      e_shared = cutoff_count(fmaxf(logf(z) + mx - t / z, 0.f), s, n, k_cap, budget_remaining, theta_rest_sum,
+                              n_sel, theta_out, budget_out);
   }
   // Alg. 1, third loop: the best blocks, best first
   unsigned long long run = 0ull;
@@ -133,6 +150,23 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
       lists[wave][lane] = run;
     }
   }
+  if (entropy_topk && wave == 0) {
+    // the same entropy over the scores of the min(k_cap, n) best blocks, which sit in lanes
+    // 0 .. of wavefront 0, best first (lane 0 holds the maximum)
+    const bool in = lane < min(k_cap, n);
+    const float v = in ? key_score(run) : 0.f;
+    const float mx = __shfl(v, 0, 64);
+    const float e = in ? __expf(v - mx) : 0.f;
+    float z = e, t = e * v;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      z += __shfl_xor(z, o, 64);
+      t += __shfl_xor(t, o, 64);
+    }
+    if (lane == 0)
+      e_shared = cutoff_count(fmaxf(logf(z) + mx - t / z, 0.f), s, n, k_cap, budget_remaining, theta_rest_sum,
+                              n_sel, theta_out, budget_out);
+  }
   __syncthreads();
   if (wave == 0 && lane < k_cap) {
     int e = e_shared;
@@ -141,11 +175,12 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
 }
 
 int launch_select(int batch, const float* scores, int64_t score_stride, int nb_capacity, int nb_begin,
-                  const int32_t* nb_end, int k_cap, float* budget_remaining,
+                  const int32_t* nb_end, int k_cap, int flags, float* budget_remaining,
                   const float* theta_rest_sum, int32_t* idx, int32_t* n_sel, float* theta,
                   float* budget, hipStream_t stream) {
   hipLaunchKernelGGL(select_kernel, dim3(batch), dim3(kSelectThreads), 0, stream, scores,
-                     score_stride, nb_capacity, nb_begin, nb_end, k_cap, budget_remaining, theta_rest_sum, idx,
+                     score_stride, nb_capacity, nb_begin, nb_end, k_cap,
+                     (flags & ACTQKV_SELECT_ENTROPY_TOPK) != 0, budget_remaining, theta_rest_sum, idx,
                      n_sel, theta, budget);
   return hip_status("select");
 }

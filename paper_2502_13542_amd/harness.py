@@ -395,3 +395,101 @@ class PrefillPipeline:
             to_attend = []
         cur.wait_stream(mid)
         cur.wait_stream(last)
+
+
+class HostCachePrefill:
+    """Single-sequence prefill of one layer with the key-value cache in pinned host memory
+    (Sec. 3.1: the cache may be kept in CPU memory).  HBM holds the representative keys of all
+    blocks (scoring never touches the cache) and a working cache of n_init/Bs + k_cap +
+    (n_local + m)/Bs + 1 blocks: the initial tokens, k_cap slots that `actqkv_gather_blocks`
+    fills from the host store with the blocks a window selects, then the local span and the
+    window itself.  The attention runs on the working cache as on any cache: the local span and
+    the window sit at positions shifted by a multiple of the block size (only the order of the
+    positions matters to the kernel), the selection it is given are the slot numbers.
+
+    Per window: the window's keys and values (token-major, as a model hands them over) are
+    appended behind the local span (`actqkv_append_kv`); the local span moves with the window,
+    so two working caches alternate and the span's blocks are carried over with
+    `actqkv_copy_bytes`.  While the context is still shorter than n_init + n_local the working
+    cache simply holds it whole at its true positions.  Needs m, n_init, n_local multiples of
+    the block size (only the last window may be ragged)."""
+
+    def __init__(self, runner: LayerRunner, plan: PrefillPlan):
+        sh = runner.shape
+        bs = sh.block_size
+        assert runner.batch == 1 and runner.m % bs == 0 and sh.n_init % bs == 0 and sh.n_local % bs == 0
+        self.runner, self.plan = runner, plan
+        dev = runner.device
+        self.slot0 = sh.n_init // bs
+        self.tail0 = self.slot0 + runner.k_cap
+        self.nb_work = self.tail0 + (sh.n_local + runner.m) // bs + 1
+        st = torch.float32 if sh.dtype == "fp32" else torch.bfloat16
+        shape_k = (self.nb_work, sh.n_kv_heads, bs, sh.head_dim)
+        shape_v = (self.nb_work, sh.n_kv_heads, sh.head_dim, bs)
+        self.k_work = [torch.zeros(shape_k, dtype=st, device=dev) for _ in range(2)]
+        self.v_work = [torch.zeros(shape_v, dtype=st, device=dev) for _ in range(2)]
+        self.idx_slots = torch.full((1, runner.k_cap), -1, dtype=torch.int32, device=dev)
+        self.n_ctx_work = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.pos0_work = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.workspace = torch.zeros(B.workspace_bytes(runner.cs, 1, runner.m, self.nb_work, runner.k_cap),
+                                     dtype=torch.uint8, device=dev)
+        self.gathered_blocks = 0
+
+    def _copy_blocks(self, src, dst, src_block: int, dst_block: int, n: int) -> None:
+        if n > 0:
+            B.copy_bytes(dst[dst_block:dst_block + n], src[src_block:src_block + n])
+
+    def run(self, q: torch.Tensor, k_tok: torch.Tensor, v_tok: torch.Tensor, k_store: torch.Tensor,
+            v_store: torch.Tensor, rep_keys: torch.Tensor, out: torch.Tensor,
+            record: Optional[Sequence[int]] = None) -> Dict[int, Dict[str, torch.Tensor]]:
+        """q, out [N][H][D]; k_tok, v_tok [N][Hk][D] on the device (the windows' new keys and
+        values); k_store, v_store: the blocked cache of the whole context in pinned host memory
+        (already holding every block a window can select, i.e. everything older than its local
+        span); rep_keys [nb][r][Hk][D] on the device."""
+        r, plan = self.runner, self.plan
+        sh, cs, bs = r.shape, r.cs, r.shape.block_size
+        nb_begin = sh.n_init // bs
+        nb_store = k_store.shape[0]
+        rec: Dict[int, Dict[str, torch.Tensor]] = {}
+        cur, delta, has_init = 0, 0, [True, False]     # cache in use, real block - working block of its tail
+        self.gathered_blocks = 0
+        for t in range(plan.n_windows):
+            w0, rows = plan.w0[t], plan.rows[t]
+            l0 = local_start(sh, w0)
+            if l0 <= sh.n_init:
+                # the whole context fits: true positions, nothing is eligible for retrieval
+                new, pos0, new_delta = 0, w0, 0
+                assert cur == 0 and w0 + rows <= self.nb_work * bs
+            else:
+                new = 1 - cur
+                n_loc = (w0 - l0) // bs
+                if not has_init[new]:
+                    self._copy_blocks(self.k_work[cur], self.k_work[new], 0, 0, self.slot0)
+                    self._copy_blocks(self.v_work[cur], self.v_work[new], 0, 0, self.slot0)
+                    has_init[new] = True
+                self._copy_blocks(self.k_work[cur], self.k_work[new], l0 // bs - delta, self.tail0, n_loc)
+                self._copy_blocks(self.v_work[cur], self.v_work[new], l0 // bs - delta, self.tail0, n_loc)
+                pos0 = (self.tail0 + n_loc) * bs
+                new_delta = l0 // bs - self.tail0
+            self.pos0_work.fill_(pos0)
+            self.n_ctx_work.fill_(pos0 + rows)
+            B.append_kv(cs, 1, rows, k_tok[w0:w0 + rows], v_tok[w0:w0 + rows], self.pos0_work, self.k_work[new],
+                        self.v_work[new], 0, None, 0, self.nb_work)
+            bud = None if plan.budget is None else plan.budget[t:t + 1]
+            rest = None if plan.rest is None else plan.rest[t:t + 1]
+            nb_cap = min(max(plan.nb_end_host[t], nb_begin), r.nb_capacity)
+            qw = q[w0:w0 + rows]
+            B.build_probe(cs, 1, rows, qw, r.stats, True, r.probe, r.probe_kv, r.probe_norm, None, r.workspace)
+            B.score_blocks(cs, 1, r.probe_kv, r.probe_norm, rep_keys, 0, nb_cap, nb_begin, plan.nb_end[t:t + 1],
+                           r.scores, r.score_stride)
+            B.select(1, r.scores, r.score_stride, nb_cap, nb_begin, plan.nb_end[t:t + 1], r.k_cap, bud, rest,
+                     r.idx, r.n_sel, r.theta, r.budget)
+            B.gather_blocks(cs, 1, k_store, v_store, 0, nb_store, r.idx, r.n_sel, r.k_cap, self.k_work[new],
+                            self.v_work[new], 0, self.nb_work, self.slot0, self.idx_slots)
+            B.retrieval_attention(cs, 1, rows, qw, self.k_work[new], self.v_work[new], 0, self.nb_work,
+                                  self.n_ctx_work, self.idx_slots, r.n_sel, r.k_cap, out[w0:w0 + rows], None,
+                                  self.workspace)
+            if record is not None and t in record:
+                rec[t] = dict(idx=r.idx[0].clone(), n_sel=r.n_sel[0].clone(), idx_slots=self.idx_slots[0].clone())
+            cur, delta = new, new_delta
+        return rec

@@ -87,9 +87,9 @@ def test_score_select_attention_reject(lib):
                                              A16, A16, k.get("ss", 64), None)
     assert sb(rep=None) == -1 and sb(rep=A16 + 8) == -3 and sb(ss=10) == -1 and sb(cap=-1) == -1
     assert sb(batch=2, stride=8) == -1 and sb(stride=4) == -3 and sb(cap=9000, ss=9000) == -2
-    se = lambda **k: lib.actqkv_select(1, A16, 64, 64, 1, A16, k.get("k_cap", 32), k.get("bud"),
-                                       k.get("rest"), k.get("idx", A16), A16, None, None, None)
-    assert se(k_cap=0) == -2 and se(k_cap=65) == -2 and se(idx=None) == -1
+    se = lambda **k: lib.actqkv_select(1, A16, 64, 64, 1, A16, k.get("k_cap", 32), k.get("flags", 0),
+                                       k.get("bud"), k.get("rest"), k.get("idx", A16), A16, None, None, None)
+    assert se(k_cap=0) == -2 and se(k_cap=65) == -2 and se(idx=None) == -1 and se(flags=2) == -1
     assert se(bud=A16 + 2, rest=A16) == -3 and se(bud=A16) == -1 and se(rest=A16) == -1
     at = lambda **k: lib.actqkv_retrieval_attention(ctypes.byref(cs), 1, k.get("m", 512), A16,
                                                     k.get("kc", A16), A16, 0, k.get("cap", 64), A16, A16,
@@ -97,6 +97,11 @@ def test_score_select_attention_reject(lib):
                                                     k.get("wsb", 1 << 30), None)
     assert at(kc=None) == -1 and at(out=A16 + 2) == -3 and at(ws=None) == -4 and at(wsb=8) == -4
     assert at(m=0) == -1 and at(cap=2) == -1 and at(cap=0) == -1
+    ga = lambda **k: lib.actqkv_gather_blocks(ctypes.byref(cs), 1, k.get("ks", A16), A16, 0, k.get("nbs", 64), A16,
+                                              A16, k.get("k_cap", 32), k.get("kc", A16), A16, 0, k.get("cap", 64),
+                                              k.get("slot0", 1), None, None)
+    assert ga(ks=None) == -1 and ga(kc=A16 + 4) == -3 and ga(k_cap=65) == -2 and ga(nbs=0) == -1
+    assert ga(slot0=40) == -1 and b"outside the cache" in lib.actqkv_last_error() and ga(slot0=-1) == -1
     with pytest.raises(B.ActQKVError):
         B._check(at(wsb=8))
 

@@ -244,7 +244,7 @@ def test_copy_bytes():
 
 
 # ---------------------------------------------------------------- select alone: ties, cut-off, sizes
-def _select_case(scores: np.ndarray, nb_begin: int, k_cap: int, cutoff):
+def _select_case(scores: np.ndarray, nb_begin: int, k_cap: int, cutoff, topk: bool = False):
     n = len(scores)
     sc = torch.zeros(1, n + nb_begin, dtype=torch.float32, device=DEV)
     sc[0, nb_begin:] = torch.from_numpy(scores.astype(np.float32)).to(DEV)
@@ -257,11 +257,11 @@ def _select_case(scores: np.ndarray, nb_begin: int, k_cap: int, cutoff):
     bud = None if cut is None else cut[0, 0:1]
     rest = None if cut is None else cut[0, 1:2]
     B.select(1, sc, n + nb_begin, n + nb_begin, nb_begin, nb_end, k_cap, bud, rest, idx, n_sel, theta,
-             budget)
+             budget, flags=B.SELECT_ENTROPY_TOPK if topk else 0)
     torch.cuda.synchronize()
     s32 = scores.astype(np.float32).astype(np.float64)
     ids = list(range(nb_begin, nb_begin + n))
-    th = orc.information_density(s32) if n else 0.0
+    th = (orc.information_density_topk(s32, k_cap) if topk else orc.information_density(s32)) if n else 0.0
     if cutoff is None:
         count = min(k_cap, n)
     else:
@@ -297,6 +297,26 @@ def test_select_cutoff_bookkeeping_and_monotonicity():
     # nothing eligible: nothing selected, budget untouched
     got, n_sel, theta, budget, want, th, cut = _select_case(np.zeros(0), 2, 8, (50.0, 10.0))
     assert n_sel == 0 and got == [-1] * 8 and float(cut[0, 0]) == 50.0
+
+
+@pytest.mark.parametrize("n,k_cap", [(1, 4), (5, 8), (64, 64), (65, 32), (1000, 32), (1025, 16), (5000, 64)])
+def test_select_density_over_the_best_blocks(n, k_cap):
+    """ACTQKV_SELECT_ENTROPY_TOPK: the density of Eq. (11) over the k_cap best blocks only, then
+    the same budget, count and selection; without cut-off state the selection does not change."""
+    rng = np.random.default_rng(n * 17 + k_cap)
+    scores = np.clip(rng.normal(size=n) * 0.2, -1, 1)
+    _say(f"[select, density over the best] n={n} k_cap={k_cap}")
+    cut = (3.0 * k_cap, 2.5 * math.log(max(min(n, k_cap), 2)))
+    got, n_sel, theta, budget, want, th, state = _select_case(scores, 2, k_cap, cut, topk=True)
+    assert abs(theta - th) < TOL_THETA
+    b = orc.layer_budget(th, cut[1], cut[0])
+    assert abs(budget - b) <= TOL_BUDGET * max(1.0, b) and abs(float(state[0, 0]) - (cut[0] - b)) < 1e-2
+    assert n_sel == len(want) and got[:n_sel] == want and all(x == -1 for x in got[n_sel:])
+    plain = _select_case(scores, 2, k_cap, None)
+    top = _select_case(scores, 2, k_cap, None, topk=True)
+    assert plain[0] == top[0] and plain[1] == top[1]
+    if n > k_cap:
+        assert top[2] < plain[2]            # fewer terms, lower entropy
 
 
 def test_scores_zero_norms_and_determinism():
@@ -700,3 +720,87 @@ def test_probe_of_consecutive_windows_in_one_call(dtype, hq, hkv, d, m, calls):
     # the flag needs the update bit and a window of more than one token
     with pytest.raises(B.ActQKVError):
         B.build_probe(cs, 2, m, qd[:2], stats, B.PROBE_WINDOW_CHAIN, probe[:2], probe_kv[:2], norm[:2], None, ws)
+
+
+def test_gather_blocks_from_pinned_host_memory():
+    """actqkv_gather_blocks: the selected blocks of a store in pinned host memory land in the
+    slots of the working cache, bit for bit; entries beyond n_sel and indices outside the store
+    are skipped and reported as -1."""
+    sh = LayerShape(32, 8, 128, 128, 4, 128, 512, "bf16")
+    cs = B.c_shape(sh)
+    g = torch.Generator().manual_seed(77)
+    nb_store, nb_work, k_cap, slot0 = 40, 16, 8, 2
+    ks = torch.randn(2, nb_store, 8, 128, 128, generator=g).to(torch.bfloat16).pin_memory()
+    vs = torch.randn(2, nb_store, 8, 128, 128, generator=g).to(torch.bfloat16).pin_memory()
+    kw = torch.full((2, nb_work, 8, 128, 128), 7.0, dtype=torch.bfloat16, device=DEV)
+    vw = torch.full((2, nb_work, 8, 128, 128), 7.0, dtype=torch.bfloat16, device=DEV)
+    idx = torch.tensor([[5, 39, 0, 17, -1, 3, 3, 3], [12, 40, 11, 1, 2, 3, 4, 5]], dtype=torch.int32, device=DEV)
+    n_sel = torch.tensor([4, 3], dtype=torch.int32, device=DEV)
+    slots = torch.zeros(2, k_cap, dtype=torch.int32, device=DEV)
+    B.gather_blocks(cs, 2, ks, vs, ks.stride(0), nb_store, idx, n_sel, k_cap, kw, vw, kw.stride(0), nb_work, slot0,
+                    slots)
+    torch.cuda.synchronize()
+    want_slots = [[2, 3, 4, 5, -1, -1, -1, -1], [2, -1, 4, -1, -1, -1, -1, -1]]     # 40 is outside the store
+    assert slots.cpu().tolist() == want_slots
+    kw_c, vw_c = kw.cpu(), vw.cpu()
+    for s in range(2):
+        touched = set()
+        for j, slot in enumerate(want_slots[s]):
+            if slot >= 0:
+                b = int(idx[s, j])
+                assert torch.equal(kw_c[s, slot], ks[s, b]) and torch.equal(vw_c[s, slot], vs[s, b])
+                touched.add(slot)
+        for blk in range(nb_work):
+            if blk not in touched:
+                assert bool((kw_c[s, blk] == 7.0).all()) and bool((vw_c[s, blk] == 7.0).all())
+
+
+def test_prefill_with_the_cache_in_host_memory():
+    """The cache of the whole context in pinned host memory, a working cache of a few dozen
+    blocks in HBM (HostCachePrefill): selections and attention outputs must equal those of the
+    HBM-resident run, bit for bit (the same tiles go through the same kernel in the same order),
+    and sampled windows are checked against the oracle."""
+    w = synth.scaled(synth.WORKLOADS["c3_128k"], n_ctx=512 * 11 + 200, k_cap=8, name="host_cache")
+    sh = w.shape
+    _say(f"[case] {w.name} N={w.n_ctx} m={w.window} k_cap={w.k_cap}")
+    q, k, v = synth.gen_layer(w, "cpu", 0)
+    rep = synth.pick_rep_keys(k, sh.block_size, sh.n_rep)
+    cutoffs = []
+    for t in range(w.n_windows):
+        b, e = H.eligible_range(sh, t * w.window)
+        cutoffs.append(synth.cutoff_state(w, e - b, t, 0))
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    kc, vc = H.blocked_k(kd, sh, w.n_blocks), H.blocked_vt(vd, sh, w.n_blocks)
+    repd = torch.zeros(w.n_blocks, sh.n_rep, sh.n_kv_heads, sh.head_dim, dtype=rep.dtype, device=DEV)
+    repd[: rep.shape[0]] = rep.to(DEV)
+    runner = H.LayerRunner(sh, 1, w.window, w.n_blocks, w.k_cap, DEV)
+    plan = H.make_prefill_plan(sh, w.n_ctx, w.window, cutoffs, DEV)
+    bud0 = plan.budget.clone()
+    out_hbm = torch.zeros_like(qd)
+    rec_hbm = H.prefill_layer(runner, plan, qd, kc, vc, repd, out_hbm, record=range(w.n_windows))
+    torch.cuda.synchronize()
+    k_store, v_store = kc.cpu().pin_memory(), vc.cpu().pin_memory()
+    runner.reset()
+    plan.budget.copy_(bud0)
+    host = H.HostCachePrefill(runner, plan)
+    assert host.nb_work < w.n_blocks // 2
+    out_host = torch.zeros_like(qd)
+    rec = host.run(qd, kd, vd, k_store, v_store, repd, out_host, record=range(w.n_windows))
+    torch.cuda.synchronize()
+    n_retrieving = 0
+    for t in range(w.n_windows):
+        assert torch.equal(rec[t]["idx"], rec_hbm[t]["idx"]) and int(rec[t]["n_sel"]) == int(rec_hbm[t]["n_sel"])
+        n_retrieving += int(rec[t]["n_sel"]) > 0
+    assert n_retrieving >= w.n_windows - 3
+    assert torch.equal(out_host, out_hbm)
+    attend = [2, 7, w.n_windows - 1]
+    want = oracle_windows(q, k, v, rep, sh, w.window, w.k_cap, cutoffs, attend)
+    for t in attend:
+        res = want[t]
+        gi, gn = rec[t]["idx"].cpu().tolist(), int(rec[t]["n_sel"])
+        ref = res["out"]
+        if not check_selection(gi, gn, res, w.k_cap):
+            ref = orc.retrieval_attention_window(f64(q[res["w0"]:res["w0"] + w.window]), f64(k), f64(v), res["w0"],
+                                                 gi[:gn], sh.n_init, sh.n_local, sh.block_size, sh.group)
+        err = out_error(out_host[res["w0"]:res["w0"] + ref.shape[0]], ref)
+        assert err < TOL_OUT["bf16"], f"attention output, window {t}: {err}"

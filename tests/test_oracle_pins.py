@@ -177,6 +177,32 @@ def test_p8_budgets_telescope():
         b_kv -= b
 
 
+def test_p7b_information_density_over_the_best_blocks():
+    """The variant reading of Eq. (11): entropy over the k highest scores.  Closed forms: k equal
+    scores on top give ln k whatever lies below; with k >= n it is the plain density; it never
+    exceeds ln k; two scores a and a - d on top give the binary entropy of 1 / (1 + e^-d)."""
+    rng = np.random.default_rng(5)
+    low = rng.uniform(-3.0, -1.0, size=40)
+    s = np.concatenate([low, np.full(7, 0.5)])
+    rng.shuffle(s)
+    assert math.isclose(orc.information_density_topk(s, 7), math.log(7), rel_tol=1e-13)
+    assert orc.information_density_topk(s, 8) < math.log(8)
+    assert math.isclose(orc.information_density_topk(s, 100), orc.information_density(s), rel_tol=1e-13)
+    assert math.isclose(orc.information_density_topk(s, len(s)), orc.information_density(s), rel_tol=1e-13)
+    d = 0.75
+    two = np.concatenate([low, [1.0, 1.0 - d]])
+    p = 1.0 / (1.0 + math.exp(-d))
+    assert math.isclose(orc.information_density_topk(two, 2), -(p * math.log(p) + (1 - p) * math.log(1 - p)),
+                        rel_tol=1e-12)
+    assert orc.information_density_topk(np.array([0.3]), 4) == 0.0
+    # brute force on a tiny case: every subset of size k has at most the entropy bound, and the
+    # function picks the subset of the k largest
+    t = rng.normal(size=6)
+    best = sorted(t)[-3:]
+    e = np.exp(np.array(best) - max(best)); q = e / e.sum()
+    assert math.isclose(orc.information_density_topk(t, 3), float(-(q * np.log(q)).sum()), rel_tol=1e-12)
+
+
 def test_p9_budget_monotone_in_density():
     thetas = np.linspace(0.01, 7.0, 200)
     b = [orc.layer_budget(float(t), 90.0, 640.0) for t in thetas]
