@@ -268,6 +268,61 @@ def bench_prefill(args, torch, B, H, synth):
     return res
 
 
+def bench_prefill_host_cache(args, torch, B, H, synth):
+    """The same layer pass with the cache of the whole context in pinned host memory and a
+    working cache of a few dozen blocks in HBM (harness.HostCachePrefill): what the blocks a
+    window selects cost when they come over the host link.  Window order, one stream, eager."""
+    dev = "cuda:0"
+    w = synth.WORKLOADS[args.workload]
+    if args.n_ctx:
+        w = synth.scaled(w, n_ctx=args.n_ctx)
+    sh = w.shape
+    log(f"prefill {w.name}, cache in pinned host memory: generating inputs")
+    q, k, v = synth.gen_layer(w, dev)
+    rep = synth.pick_rep_keys(k, sh.block_size, sh.n_rep)
+    repd = torch.zeros(w.n_blocks, sh.n_rep, sh.n_kv_heads, sh.head_dim, dtype=rep.dtype, device=dev)
+    repd[: rep.shape[0]] = rep
+    k_store = H.blocked_k(k, sh, w.n_blocks).cpu().pin_memory()
+    v_store = H.blocked_vt(v, sh, w.n_blocks).cpu().pin_memory()
+    cutoffs = None
+    if w.cutoff:
+        cutoffs = []
+        for t in range(w.n_windows):
+            b, e = H.eligible_range(sh, t * w.window)
+            cutoffs.append(synth.cutoff_state(w, e - b, t, 0))
+    runner = H.LayerRunner(sh, 1, w.window, w.n_blocks, w.k_cap, dev)
+    plan = H.make_prefill_plan(sh, w.n_ctx, w.window, cutoffs, dev)
+    bud0 = None if plan.budget is None else plan.budget.clone()
+    host = H.HostCachePrefill(runner, plan)
+    out = torch.zeros_like(q)
+
+    def one_pass():
+        runner.stats.zero_()
+        if bud0 is not None:
+            plan.budget.copy_(bud0)
+        return host.run(q, k, v, k_store, v_store, repd, out, record=range(plan.n_windows))
+
+    rec = one_pass()
+    torch.cuda.synchronize()
+    blocks = sum(int(r["n_sel"]) for r in rec.values())
+    steps = min(args.steps, 3)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        host.run(q, k, v, k_store, v_store, repd, out)
+        runner.stats.zero_()
+        if bud0 is not None:
+            plan.budget.copy_(bud0)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    block_bytes = 2 * sh.n_kv_heads * sh.block_size * sh.head_dim * (4 if sh.dtype == "fp32" else 2)
+    return {"metric": "prefill retrieval-attn tokens/s per layer, cache in pinned host memory",
+            "value": w.n_ctx / dt, "unit": "tokens/s", "ms_per_step": dt * 1e3, "steps": steps,
+            "config": {"workload": w.name, "working_cache_blocks": host.nb_work, "context_blocks": w.n_blocks,
+                       "launch": "eager, one stream, window order"},
+            "host_link": {"blocks_gathered_per_pass": blocks, "bytes_per_pass": blocks * block_bytes,
+                          "GBps_if_the_pass_were_only_the_gather": blocks * block_bytes / dt / 1e9}}
+
+
 def bench_decode(args, torch, B, H, synth):
     """configs[3]: batch 16 x 32 layers x 64K cached tokens, `decode_steps` steps."""
     dev = "cuda:0"
@@ -445,6 +500,9 @@ def main() -> int:
                          "streams) instead of one call per chunk of windows")
     ap.add_argument("--attention-cus", type=int, default=224,
                     help="prefill, two streams: compute units the attention may fill")
+    ap.add_argument("--host-cache", action="store_true",
+                    help="also time the prefill pass with the cache in pinned host memory (reported as "
+                         "\"host_cache\" beside the headline line)")
     ap.add_argument("--pmc-pass", action="store_true",
                     help="one calibration copy and one eager pass, for a rocprofv3 --pmc run")
     args = ap.parse_args()
@@ -467,6 +525,13 @@ def main() -> int:
     if not args.skip_prefill:
         res = bench_prefill(args, torch, B, H, synth)
         torch.cuda.empty_cache()
+    if args.host_cache and not args.pmc_pass:
+        hc = bench_prefill_host_cache(args, torch, B, H, synth)
+        torch.cuda.empty_cache()
+        if res:
+            res["host_cache"] = hc
+        else:
+            res = hc
     if not args.skip_decode:
         dec = bench_decode(args, torch, B, H, synth)
         if res:
