@@ -268,6 +268,72 @@ def bench_prefill(args, torch, B, H, synth):
     return res
 
 
+def bench_prefill_layers(args, torch, B, H, synth):
+    """configs[4]-style run: all `--layers` layers of one sequence, every layer with its own
+    seeded inputs, outlier rate, statistics and cut-off profile, in the benchmarked schedule
+    (one call per step and chunk of windows, attention on a second stream), layer after layer
+    in one HIP graph.  Reported in token-layers per second, i.e. the per-layer rate."""
+    dev = "cuda:0"
+    w = synth.WORKLOADS[args.workload]
+    if args.n_ctx:
+        w = synth.scaled(w, n_ctx=args.n_ctx)
+    sh, L = w.shape, args.layers
+    layers = []
+    out = None
+    for l in range(L):
+        log(f"prefill {w.name}: generating layer {l + 1} of {L} on the device")
+        q, k, v = synth.gen_layer(w, dev, l)
+        rep = synth.pick_rep_keys(k, sh.block_size, sh.n_rep)
+        kc, vc = H.blocked_k(k, sh, w.n_blocks), H.blocked_vt(v, sh, w.n_blocks)
+        del k, v
+        repd = torch.zeros(w.n_blocks, sh.n_rep, sh.n_kv_heads, sh.head_dim, dtype=rep.dtype, device=dev)
+        repd[: rep.shape[0]] = rep
+        cutoffs = None
+        if w.cutoff:
+            cutoffs = []
+            for t in range(w.n_windows):
+                b, e = H.eligible_range(sh, t * w.window)
+                cutoffs.append(synth.cutoff_state(w, e - b, t, l))
+        runner = H.LayerRunner(sh, 1, w.window, w.n_blocks, w.k_cap, dev)
+        plan = H.make_prefill_plan(sh, w.n_ctx, w.window, cutoffs, dev)
+        bud0 = None if plan.budget is None else plan.budget.clone()
+        if out is None:
+            out = torch.zeros_like(q)          # one output buffer: the layers run one after the other
+        layers.append((q, kc, vc, repd, runner, plan, bud0, H.PrefillPipeline(runner, plan)))
+    torch.cuda.empty_cache()
+
+    def one_step():
+        for q, kc, vc, repd, runner, plan, bud0, pipe in layers:
+            runner.stats.zero_()
+            if bud0 is not None:
+                plan.budget.copy_(bud0)
+            pipe.run(q, kc, vc, repd, out, True, None, args.chunk, args.score_chunk, True)
+
+    B.set_attention_cus(args.attention_cus)
+    graph = None if args.eager else capture_graph(torch, one_step, out, f"prefill ({L} layers)")
+    run = graph.replay if graph is not None else one_step
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    B.set_attention_cus(256)
+    n_sel = [sum(pipe.n_sel.cpu().tolist()) / plan.n_windows for *_, plan, _, pipe in layers]
+    return {"metric": f"prefill retrieval-attn tokens/s per layer ({w.name}, {L} layers)",
+            "value": w.n_ctx * L / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": sh.dtype, "data": "synthetic",
+            "config": {"workload": f"{w.name}: 1 sequence, {L} layers, {w.n_ctx} tokens, window {w.window}, "
+                                   f"k_cap {w.k_cap}, cut-off {'on' if w.cutoff else 'off'}, per-layer outlier "
+                                   f"rates {synth.layer_outlier_rate(w, 0):.3f} .. {synth.layer_outlier_rate(w, L - 1):.3f}",
+                       "ms_per_layer": dt * 1e3 / L, "mean_blocks_selected_per_layer": n_sel,
+                       "launch": ("hip graph replay" if graph is not None else "eager") +
+                                 f", {args.chunk} windows per call, attention on {args.attention_cus} of 256 CUs"}}
+
+
 def bench_prefill_host_cache(args, torch, B, H, synth):
     """The same layer pass with the cache of the whole context in pinned host memory and a
     working cache of a few dozen blocks in HBM (harness.HostCachePrefill): what the blocks a
@@ -500,6 +566,9 @@ def main() -> int:
                          "streams) instead of one call per chunk of windows")
     ap.add_argument("--attention-cus", type=int, default=224,
                     help="prefill, two streams: compute units the attention may fill")
+    ap.add_argument("--layers", type=int, default=1,
+                    help="prefill: > 1 runs that many layers of the workload (configs[4]: --workload c5_200k "
+                         "--layers 32), each with its own inputs, and reports only that run")
     ap.add_argument("--host-cache", action="store_true",
                     help="also time the prefill pass with the cache in pinned host memory (reported as "
                          "\"host_cache\" beside the headline line)")
@@ -522,6 +591,9 @@ def main() -> int:
     B.load_library()
     torch.cuda.set_device(0)
     res = {}
+    if args.layers > 1:
+        print(json.dumps(bench_prefill_layers(args, torch, B, H, synth)))
+        return 0
     if not args.skip_prefill:
         res = bench_prefill(args, torch, B, H, synth)
         torch.cuda.empty_cache()

@@ -117,6 +117,12 @@ def test_c3_128k_full_size_sampled_windows():
     run_prefill_case(synth.WORKLOADS["c3_128k"], attend=[2, 64, 255])
 
 
+def test_c5_200k_full_size_sampled_windows():
+    # configs[4] at full size, its last layer (3 % outlier tokens): every window's probe, scores,
+    # density, budget and selection, and the attention of a spread of windows
+    run_prefill_case(synth.WORKLOADS["c5_200k"], attend=[5, 211, 399], layer=31)
+
+
 def test_c3_128k_two_stream_pipeline_as_benchmarked():
     """configs[2] at full size in the schedules of PrefillPipeline, the last one being the one
     bench.py times: (1) three streams, calls of one window each: probes, then scoring and
