@@ -243,10 +243,7 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
   // registers each.  The 32-row blocks (kb, db) add a compile-time constant.
   uint32_t a_off0 = uint32_t(a_row) * (kRowPad * 2) + (uint32_t(half ^ (a_row & 15)) << 4);
   uint32_t v_off0 = uint32_t(n) * (kRowPad * 2) + (uint32_t(half ^ (n & 15)) << 4);
-  const bf16x8 ones = as_bf16x8(u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
-  f32x16 acc_l;                                // every register: the running sum of the lane's query row
-#pragma unroll
-  for (int j = 0; j < 16; ++j) acc_l[j] = 0.f;
+  float l_run = 0.f;                           // this lane's share of the running sum of its query row
   for (int t = t_begin; t < t_end; ++t) {
     const int u = t - t_begin, stage = u & 1;
     // (opaque per iteration: the XOR-ed offsets are recomputed, not kept across the loop)
@@ -339,17 +336,20 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
         for (int db = 0; db < 4; ++db)
 #pragma unroll
           for (int i = 0; i < 16; ++i) acc_o[db][i] *= alpha;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc_l[i] *= alpha;
+        l_run *= alpha;
       }
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc_s[0][i] = __builtin_amdgcn_exp2f(acc_s[0][i] * p.scale_log2e - m_safe);
+      for (int i = 0; i < 16; ++i) {
+        acc_s[0][i] = __builtin_amdgcn_exp2f(acc_s[0][i] * p.scale_log2e - m_safe);
+        l_run += acc_s[0][i];
+      }
       __builtin_amdgcn_sched_barrier(0);
-      // ---- O^T += V^T P^T; the row sums of P come from one more MFMA per 16 keys against an
-      // all-ones A operand (64 additions per tile less on the vector ALU, and exactly the
-      // bf16 probabilities that multiply V are summed).  Written in issue order: the
-      // exponentials of the next 32 keys sit between the MFMAs of these 32 (the vector ALU works
-      // while the matrix pipe does), and every V^T operand is read 8 MFMAs ahead.
+      // ---- O^T += V^T P^T.  Written in issue order: the exponentials of the next 32 keys sit
+      // between the MFMAs of these 32 (the vector ALU works while the matrix pipe does), and every
+      // V^T operand is read 8 MFMAs ahead.  The row sums are plain additions of the fp32
+      // probabilities, each lane summing its own 64 keys of the tile (an extra MFMA per 16 keys
+      // against an all-ones operand summed the bf16-rounded probabilities instead and spared
+      // the vector ALU, but the matrix pipe and the LDS are the busier units: 3.5 % slower).
 #pragma unroll
       for (int g8 = 0; g8 < 8; ++g8) {
         const int kb = g8 >> 1, s2 = g8 & 1;
@@ -357,13 +357,14 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
                                 acc_s[kb][8 * s2 + 3], acc_s[kb][8 * s2 + 4], acc_s[kb][8 * s2 + 5],
                                 acc_s[kb][8 * s2 + 6], acc_s[kb][8 * s2 + 7]);
         __builtin_amdgcn_sched_barrier(0);
-        acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pb, acc_l, 0, 0, 0);
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
           if (kb < 3) {
 #pragma unroll
-            for (int i = 8 * s2 + 2 * db; i < 8 * s2 + 2 * db + 2; ++i)
+            for (int i = 8 * s2 + 2 * db; i < 8 * s2 + 2 * db + 2; ++i) {
               acc_s[kb + 1][i] = __builtin_amdgcn_exp2f(acc_s[kb + 1][i] * p.scale_log2e - m_safe);
+              l_run += acc_s[kb + 1][i];
+            }
           }
           __builtin_amdgcn_sched_barrier(0);
           const int j = 4 * g8 + db;
@@ -377,7 +378,7 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
   }
 
   // ---- epilogue
-  const float l_tot = acc_l[0];
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (splits == 1) {
     if (row_ok) store_rows(p, acc_o, m_run, l_tot, s, my_row, head, half);
     return;
