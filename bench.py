@@ -465,10 +465,8 @@ def bench_decode(args, torch, B, H, synth):
         # folds the step before into the history; B_kv = L * k again; R^l for every layer
         B.cutoff_next_step(bt, L, k_mean, theta_prior, theta_step, theta_sum, hist_steps, budget, rest_all)
         for l in range(L):
-            B.append_kv(runner.cs, bt, 1, k_step[l], v_step[l], pos_cur, kc[l], vc[l], cache_stride,
-                        rep[l], rep_stride, nb_cap)
-            B.build_probe(runner.cs, bt, 1, q_step[l], None, False, runner.probe, runner.probe_kv,
-                          runner.probe_norm, None, runner.workspace)
+            B.append_kv_probe(runner.cs, bt, q_step[l], k_step[l], v_step[l], pos_cur, kc[l], vc[l], cache_stride,
+                              rep[l], rep_stride, nb_cap, runner.probe, runner.probe_kv, runner.probe_norm)
             B.score_blocks(runner.cs, bt, runner.probe_kv, runner.probe_norm, rep[l], rep_stride,
                            nb_end_host[-1], nb_begin, nb_end_cur, runner.scores, runner.score_stride)
             B.select(bt, runner.scores, runner.score_stride, nb_end_host[-1], nb_begin, nb_end_cur,

@@ -245,6 +245,18 @@ int actqkv_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_p
  * ACTQKV_EWORKSPACE).  Results do not depend on it beyond the order of floating-point sums. */
 int actqkv_set_attention_cus(int cus);
 
+/* The first launch of a decode step: actqkv_append_kv with m = 1 and the probe of the step's
+ * one-token window (actqkv_build_probe with m = 1 and no statistics: probe = the query,
+ * Sec. 4.2) in ONE launch; the two are independent, and each is a few microseconds of work
+ * behind a launch of its own.
+ *   q_tok  [batch][H][D], storage dtype; probe, probe_kv, probe_norm as in actqkv_build_probe.
+ *   The other arguments, and the errors, as in actqkv_append_kv. */
+int actqkv_append_kv_probe(const actqkv_shape* shape, int batch, const void* q_tok, const void* k_new,
+                           const void* v_new, const int32_t* pos0, void* k_cache, void* v_cache,
+                           int64_t cache_seq_stride, void* rep_keys, int64_t rep_seq_stride,
+                           int nb_capacity, float* probe, float* probe_kv, float* probe_norm,
+                           void* stream);
+
 /* Selected blocks from a block store into a working cache (Sec. 3.1: the cache may be kept
  * in CPU memory).
  *   k_store, v_store  the whole context in the blocked cache layouts,

@@ -58,6 +58,7 @@ SIGNATURES = {
     "actqkv_append_kv": (_i, [_shp, _i, _i, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _vp]),
     "actqkv_cutoff_next_step": (_i, [_i, _i, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_set_attention_cus": (_i, [_i]),
+    "actqkv_append_kv_probe": (_i, [_shp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _vp, _vp, _vp, _vp]),
     "actqkv_copy_bytes": (_i, [_vp, _vp, _sz, _vp]),
     "actqkv_gather_blocks": (_i, [_shp, _i, _vp, _vp, _i64, _i, _vp, _vp, _i, _vp, _vp, _i64, _i, _i, _vp, _vp]),
     "actqkv_last_error": (ctypes.c_char_p, []),
@@ -144,6 +145,17 @@ def append_kv(shape: CShape, batch: int, m: int, k_new, v_new, pos0, k_cache, v_
         ctypes.byref(shape), batch, m, _ptr(k_new, st), _ptr(v_new, st), _ptr(pos0, torch.int32),
         _ptr(k_cache, st), _ptr(v_cache, st), cache_seq_stride, _ptr(rep_keys, st), rep_seq_stride,
         nb_capacity, _stream(stream)))
+
+
+def append_kv_probe(shape: CShape, batch: int, q_tok, k_new, v_new, pos0, k_cache, v_cache,
+                    cache_seq_stride: int, rep_keys, rep_seq_stride: int, nb_capacity: int, probe, probe_kv,
+                    probe_norm, stream=None) -> None:
+    st = torch.float32 if shape.dtype == ACTQKV_F32 else torch.bfloat16
+    f = torch.float32
+    _check(load_library().actqkv_append_kv_probe(
+        ctypes.byref(shape), batch, _ptr(q_tok, st), _ptr(k_new, st), _ptr(v_new, st), _ptr(pos0, torch.int32),
+        _ptr(k_cache, st), _ptr(v_cache, st), cache_seq_stride, _ptr(rep_keys, st), rep_seq_stride,
+        nb_capacity, _ptr(probe, f), _ptr(probe_kv, f), _ptr(probe_norm, f), _stream(stream)))
 
 
 def cutoff_next_step(batch: int, n_layers: int, k_mean: float, theta_prior: float, theta_prev,

@@ -365,9 +365,10 @@ int actqkv_gather_blocks(const actqkv_shape* shape, int batch, const void* k_sto
                        v_cache, cache_seq_stride, slot0, idx_slots, static_cast<hipStream_t>(stream));
 }
 
-int actqkv_append_kv(const actqkv_shape* shape, int batch, int m, const void* k_new, const void* v_new,
-                     const int32_t* pos0, void* k_cache, void* v_cache, int64_t cache_seq_stride,
-                     void* rep_keys, int64_t rep_seq_stride, int nb_capacity, void* stream) {
+static int append_checked(const actqkv_shape* shape, int batch, int m, const void* k_new, const void* v_new,
+                          const int32_t* pos0, void* k_cache, void* v_cache, int64_t cache_seq_stride,
+                          void* rep_keys, int64_t rep_seq_stride, int nb_capacity, const void* q_tok,
+                          float* probe, float* probe_kv, float* probe_norm, void* stream) {
   ACTQKV_TRY(check_shape(shape));
   ACTQKV_TRY(check_batch(batch));
   if (m < 1) return set_error(ACTQKV_EINVAL, "m %d < 1", m);
@@ -392,7 +393,28 @@ int actqkv_append_kv(const actqkv_shape* shape, int batch, int m, const void* k_
   if (cache_seq_stride % 8 != 0 || rep_seq_stride % 8 != 0)
     return set_error(ACTQKV_EALIGN, "sequence strides must be multiples of 8 elements");
   return launch_append(*shape, batch, m, k_new, v_new, pos0, k_cache, v_cache, cache_seq_stride, rep_keys,
-                       rep_seq_stride, nb_capacity, static_cast<hipStream_t>(stream));
+                       rep_seq_stride, nb_capacity, q_tok, probe, probe_kv, probe_norm,
+                       static_cast<hipStream_t>(stream));
+}
+
+int actqkv_append_kv(const actqkv_shape* shape, int batch, int m, const void* k_new, const void* v_new,
+                     const int32_t* pos0, void* k_cache, void* v_cache, int64_t cache_seq_stride,
+                     void* rep_keys, int64_t rep_seq_stride, int nb_capacity, void* stream) {
+  return append_checked(shape, batch, m, k_new, v_new, pos0, k_cache, v_cache, cache_seq_stride, rep_keys,
+                        rep_seq_stride, nb_capacity, nullptr, nullptr, nullptr, nullptr, stream);
+}
+
+int actqkv_append_kv_probe(const actqkv_shape* shape, int batch, const void* q_tok, const void* k_new,
+                           const void* v_new, const int32_t* pos0, void* k_cache, void* v_cache,
+                           int64_t cache_seq_stride, void* rep_keys, int64_t rep_seq_stride,
+                           int nb_capacity, float* probe, float* probe_kv, float* probe_norm,
+                           void* stream) {
+  ACTQKV_REQUIRE_PTR(q_tok);
+  ACTQKV_REQUIRE_PTR(probe);
+  ACTQKV_REQUIRE_PTR(probe_kv);
+  ACTQKV_REQUIRE_SMALL(probe_norm, 4);
+  return append_checked(shape, batch, 1, k_new, v_new, pos0, k_cache, v_cache, cache_seq_stride, rep_keys,
+                        rep_seq_stride, nb_capacity, q_tok, probe, probe_kv, probe_norm, stream);
 }
 
 int actqkv_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_prior,

@@ -85,7 +85,8 @@ int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, co
 
 int launch_append(const actqkv_shape& sh, int batch, int m, const void* k_new, const void* v_new,
                   const int32_t* pos0, void* k_cache, void* v_cache, int64_t cache_stride,
-                  void* rep_keys, int64_t rep_stride, int nb_capacity, hipStream_t stream);
+                  void* rep_keys, int64_t rep_stride, int nb_capacity, const void* q_tok, float* probe,
+                  float* probe_kv, float* probe_norm, hipStream_t stream);   // q_tok: fused one-token probe, or NULL
 
 int launch_gather(const actqkv_shape& sh, int batch, const void* k_store, const void* v_store,
                   int64_t store_stride, int nb_store, const int32_t* idx, const int32_t* n_sel, int k_cap,

@@ -20,6 +20,7 @@
 // finish run once for all windows.  Four launches for n windows instead of 3 n.
 #include "common.h"
 #include "launch.h"
+#include "probe_identity.h"
 
 namespace actqkv {
 
@@ -471,8 +472,7 @@ __global__ __launch_bounds__(1024) void probe_finish_kernel(const float* __restr
                n_kv_heads, head_dim, red);
 }
 
-// A window of one token (decode): Eq. (9) has a single weight, 1, so the probe is the query.
-// One workgroup of 1024 threads per sequence; a thread owns up to 4 groups of 4 channels.
+// A window of one token (decode): the probe is the query (probe_identity.h).
 template <typename T>
 __global__ __launch_bounds__(1024) void probe_identity_kernel(
     const T* __restrict__ q_win, float* __restrict__ stats, int add_count, size_t stats_stride,
@@ -480,41 +480,13 @@ __global__ __launch_bounds__(1024) void probe_identity_kernel(
     float* __restrict__ weights_out, int n_q_heads, int n_kv_heads, int head_dim) {
   __shared__ float red[32];
   extern __shared__ __attribute__((aligned(16))) float probe_lds[];   // [d]
-  const int d = n_q_heads * head_dim, g = n_q_heads / n_kv_heads;
+  const int d = n_q_heads * head_dim;
   const int s = blockIdx.x;
-  const T* q = q_win + size_t(s) * d;
-  float* probe = probe_out + size_t(s) * d;
   if (add_count && threadIdx.x == 0) stats[size_t(s) * stats_stride] += 1.f;
-  float x[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {                  // all loads first: they overlap
-    const int ch = (threadIdx.x + 1024 * i) * 4;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) x[i][v] = ch < d ? to_f32(q[ch + v]) : 0.f;
-  }
-  float ss = 0.f;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int ch = (threadIdx.x + 1024 * i) * 4;
-    if (ch < d) {
-      f32x4 v = {x[i][0], x[i][1], x[i][2], x[i][3]};
-      *reinterpret_cast<f32x4*>(probe + ch) = v;
-      *reinterpret_cast<f32x4*>(probe_lds + ch) = v;
-      ss += x[i][0] * x[i][0] + x[i][1] * x[i][1] + x[i][2] * x[i][2] + x[i][3] * x[i][3];
-    }
-  }
-  ss = block_sum(ss, red);                       // also orders the LDS writes before the reads below
-  if (threadIdx.x == 0) {
-    probe_norm_out[s] = sqrtf(ss);
-    if (weights_out != nullptr) weights_out[s] = 1.f;
-  }
-  float* probe_kv = probe_kv_out + size_t(s) * n_kv_heads * head_dim;
-  for (int e = threadIdx.x; e < n_kv_heads * head_dim; e += 1024) {
-    const int hk = e / head_dim, dd = e - hk * head_dim;
-    float t = 0.f;
-    for (int i = 0; i < g; ++i) t += probe_lds[(hk * g + i) * head_dim + dd];
-    probe_kv[e] = t;
-  }
+  probe_identity_body<T>(q_win + size_t(s) * d, probe_out + size_t(s) * d,
+                         probe_kv_out + size_t(s) * n_kv_heads * head_dim, probe_norm_out + s,
+                         weights_out != nullptr ? weights_out + s : nullptr, n_q_heads, n_kv_heads, head_dim,
+                         probe_lds, red);
 }
 
 template <typename T>

@@ -97,6 +97,10 @@ def test_score_select_attention_reject(lib):
                                                     k.get("wsb", 1 << 30), None)
     assert at(kc=None) == -1 and at(out=A16 + 2) == -3 and at(ws=None) == -4 and at(wsb=8) == -4
     assert at(m=0) == -1 and at(cap=2) == -1 and at(cap=0) == -1
+    ap = lambda **k: lib.actqkv_append_kv_probe(ctypes.byref(cs), 1, k.get("q", A16), A16, A16, A16, A16, A16, 0, None,
+                                                0, k.get("cap", 64), k.get("probe", A16), A16, A16, None)
+    assert ap(q=None) == -1 and b"q_tok" in lib.actqkv_last_error() and ap(probe=None) == -1
+    assert ap(cap=0) == -1 and ap(q=A16 + 2) == -3
     ga = lambda **k: lib.actqkv_gather_blocks(ctypes.byref(cs), 1, k.get("ks", A16), A16, 0, k.get("nbs", 64), A16,
                                               A16, k.get("k_cap", 32), k.get("kc", A16), A16, 0, k.get("cap", 64),
                                               k.get("slot0", 1), None, None)

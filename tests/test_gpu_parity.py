@@ -550,6 +550,42 @@ def test_append_kv_batch_of_decode_steps():
                 assert not rep[i, b].any()
 
 
+@pytest.mark.parametrize("dtype,hq,hkv,d", [("bf16", 32, 8, 128), ("fp32", 6, 2, 64)])
+def test_append_and_probe_in_one_launch(dtype, hq, hkv, d):
+    """actqkv_append_kv_probe = actqkv_append_kv (m = 1) + actqkv_build_probe (m = 1), bit for
+    bit, including a token that completes a block (its representatives are picked)."""
+    sh = LayerShape(hq, hkv, d, 128, 4, 128, 256, dtype)
+    cs = B.c_shape(sh)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    bt, nb = 3, 6
+    g = torch.Generator().manual_seed(5 + d)
+    kc0 = torch.randn(bt, nb, hkv, 128, d, generator=g).to(td).to(DEV)
+    vc0 = torch.randn(bt, nb, hkv, d, 128, generator=g).to(td).to(DEV)
+    rep0 = torch.randn(bt, nb, 4, hkv, d, generator=g).to(td).to(DEV)
+    q = torch.randn(bt, hq, d, generator=g).to(td).to(DEV)
+    kn = torch.randn(bt, 1, hkv, d, generator=g).to(td).to(DEV)
+    vn = torch.randn(bt, 1, hkv, d, generator=g).to(td).to(DEV)
+    pos0 = torch.tensor([300, 383, 5], dtype=torch.int32, device=DEV)      # 383 completes block 2
+    res = []
+    for fused in (False, True):
+        kc, vc, rep = kc0.clone(), vc0.clone(), rep0.clone()
+        probe = torch.zeros(bt, hq * d, device=DEV)
+        pkv = torch.zeros(bt, hkv * d, device=DEV)
+        pn = torch.zeros(bt, device=DEV)
+        if fused:
+            B.append_kv_probe(cs, bt, q, kn, vn, pos0, kc, vc, kc.stride(0), rep, rep.stride(0), nb, probe, pkv, pn)
+        else:
+            ws = torch.zeros(B.workspace_bytes(cs, bt, 1, nb, 4), dtype=torch.uint8, device=DEV)
+            B.append_kv(cs, bt, 1, kn, vn, pos0, kc, vc, kc.stride(0), rep, rep.stride(0), nb)
+            B.build_probe(cs, bt, 1, q, None, False, probe, pkv, pn, None, ws)
+        torch.cuda.synchronize()
+        res.append((kc, vc, rep, probe, pkv, pn))
+    for a, b in zip(*res):
+        assert torch.equal(a, b)
+    assert not torch.equal(res[1][2][1, 2], rep0[1, 2])                     # the representatives of block 2 were written
+    assert torch.equal(res[1][3], q.float().reshape(bt, -1))                # the probe is the query
+
+
 def test_append_kv_drops_tokens_behind_the_capacity():
     sh = LayerShape(8, 2, 64, 128, 4, 128, 256, "fp32")
     cs = B.c_shape(sh)
