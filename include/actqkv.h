@@ -245,6 +245,29 @@ int actqkv_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_p
  * ACTQKV_EWORKSPACE).  Results do not depend on it beyond the order of floating-point sums. */
 int actqkv_set_attention_cus(int cus);
 
+/* Retrieval per KV head - the alternative to the head-merged reading of the method, in which
+ * every KV head, with the G query heads it serves, scores, cuts off and selects for itself.
+ *
+ * actqkv_score_blocks_per_head: scores [batch][Hk][score_stride]; row hk is the score of
+ *   actqkv_score_blocks for the model cut down to KV head hk: mean_j <probe_kv[hk], k_j[hk]> /
+ *   (|probe of group hk| * sqrt(G) * |k_j[hk]|).  probe [batch][H*D] as written by
+ *   actqkv_build_probe; nb_end device int32 [batch][Hk] (one entry per row); the other
+ *   arguments as in actqkv_score_blocks.
+ * actqkv_select then runs on batch * Hk rows (cut-off state, idx, n_sel, theta, budget all
+ *   [batch][Hk]...).
+ * actqkv_retrieval_attention_per_head: as actqkv_retrieval_attention with idx [batch][Hk][k_cap]
+ *   and n_sel [batch][Hk]: the query heads of group hk attend over the blocks of row hk. */
+int actqkv_score_blocks_per_head(const actqkv_shape* shape, int batch, const float* probe,
+                                 const void* rep_keys, int64_t seq_stride, int nb_capacity,
+                                 int nb_begin, const int32_t* nb_end, float* scores,
+                                 int64_t score_stride, void* stream);
+int actqkv_retrieval_attention_per_head(const actqkv_shape* shape, int batch, int m, const void* q,
+                                        const void* k_cache, const void* v_cache,
+                                        int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
+                                        const int32_t* idx, const int32_t* n_sel, int k_cap,
+                                        void* out, float* lse, void* workspace, size_t ws_bytes,
+                                        void* stream);
+
 /* The first launch of a decode step: actqkv_append_kv with m = 1 and the probe of the step's
  * one-token window (actqkv_build_probe with m = 1 and no statistics: probe = the query,
  * Sec. 4.2) in ONE launch; the two are independent, and each is a few microseconds of work

@@ -156,6 +156,16 @@ def block_scores(q_probe, rep_keys, group: int) -> np.ndarray:
     return s
 
 
+def block_scores_per_head(q_probe, rep_keys, group: int) -> np.ndarray:
+    """The variant of the head-merged reading in which every KV head retrieves for itself:
+    scores [Hk][NB], row hk being block_scores of the model cut down to KV head hk and its
+    `group` query heads (the probe restricted to those heads, the keys of that head)."""
+    rep_keys = _f64(rep_keys)
+    hk_n, d = rep_keys.shape[2], rep_keys.shape[3]
+    probe = _f64(q_probe).reshape(hk_n, group * d)
+    return np.stack([block_scores(probe[hk], rep_keys[:, :, hk:hk + 1], group) for hk in range(hk_n)])
+
+
 def information_density(scores) -> float:
     """Eq. (11): entropy (natural log) of softmax(scores)."""
     s = _f64(scores)
@@ -292,6 +302,20 @@ def retrieval_attention_window(q_win, k_all, v_all, w0: int, selected: Sequence[
     return out
 
 
+def retrieval_attention_per_head(q_win, k_all, v_all, w0: int, selected_per_head: Sequence[Sequence[int]],
+                                 n_init: int, n_local: int, block: int, group: int) -> np.ndarray:
+    """Eq. (2) with a selection of its own for every KV head: the query heads of group hk attend
+    over the blocks selected_per_head[hk]."""
+    q_win = np.asarray(q_win)
+    out = np.zeros(q_win.shape)
+    for hk, sel in enumerate(selected_per_head):
+        hs = slice(hk * group, (hk + 1) * group)
+        out[:, hs] = retrieval_attention_window(q_win[:, hs], np.asarray(k_all)[:, hk:hk + 1],
+                                                np.asarray(v_all)[:, hk:hk + 1], w0, sel, n_init, n_local,
+                                                block, group)
+    return out
+
+
 # --------------------------------------------------------------------------
 # one retrieval step and the window loop
 # --------------------------------------------------------------------------
@@ -320,6 +344,17 @@ def retrieve(q_probe, rep_keys, w0: int, n_init: int, n_local: int, block: int, 
     res.update(scores=s, theta=theta, budget=b_l, count=count,
                idx=select_blocks(s, elig, count))
     return res
+
+
+def retrieve_per_head(q_probe, rep_keys, w0: int, n_init: int, n_local: int, block: int, group: int,
+                      k_cap: int, cutoffs: Optional[Sequence[Tuple[float, float]]] = None) -> List[Dict]:
+    """`retrieve` run for every KV head on its own (scores, density, budget, count and
+    selection per head); cutoffs[hk] = (B_kv, R) of that head, or None."""
+    rep_keys = _f64(rep_keys)
+    hk_n, d = rep_keys.shape[2], rep_keys.shape[3]
+    probe = _f64(q_probe).reshape(hk_n, group * d)
+    return [retrieve(probe[hk], rep_keys[:, :, hk:hk + 1], w0, n_init, n_local, block, group, k_cap,
+                     None if cutoffs is None else cutoffs[hk]) for hk in range(hk_n)]
 
 
 def prefill_layer(q, k, v, rep_keys, m: int, n_init: int, n_local: int, block: int,

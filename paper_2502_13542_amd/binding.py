@@ -55,6 +55,9 @@ SIGNATURES = {
     "actqkv_select": (_i, [_i, _vp, _i64, _i, _i, _vp, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_retrieval_attention": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
                                         _vp, _vp, _vp, _sz, _vp]),
+    "actqkv_retrieval_attention_per_head": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
+                                                 _vp, _vp, _vp, _sz, _vp]),
+    "actqkv_score_blocks_per_head": (_i, [_shp, _i, _vp, _vp, _i64, _i, _i, _vp, _vp, _i64, _vp]),
     "actqkv_append_kv": (_i, [_shp, _i, _i, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _vp]),
     "actqkv_cutoff_next_step": (_i, [_i, _i, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_set_attention_cus": (_i, [_i]),
@@ -210,6 +213,14 @@ def score_blocks(shape: CShape, batch: int, probe_kv, probe_norm, rep_keys, seq_
         _ptr(scores, torch.float32), score_stride, _stream(stream)))
 
 
+def score_blocks_per_head(shape: CShape, batch: int, probe, rep_keys, seq_stride: int, nb_capacity: int,
+                          nb_begin: int, nb_end, scores, score_stride: int, stream=None) -> None:
+    st = torch.float32 if shape.dtype == ACTQKV_F32 else torch.bfloat16
+    _check(load_library().actqkv_score_blocks_per_head(
+        ctypes.byref(shape), batch, _ptr(probe, torch.float32), _ptr(rep_keys, st), seq_stride, nb_capacity,
+        nb_begin, _ptr(nb_end, torch.int32), _ptr(scores, torch.float32), score_stride, _stream(stream)))
+
+
 def select(batch: int, scores, score_stride: int, nb_capacity: int, nb_begin: int, nb_end,
            k_cap: int, budget_remaining, theta_rest_sum, idx, n_sel, theta=None, budget=None,
            stream=None, flags: int = 0) -> None:
@@ -223,9 +234,11 @@ def select(batch: int, scores, score_stride: int, nb_capacity: int, nb_begin: in
 
 def retrieval_attention(shape: CShape, batch: int, m: int, q, k_cache, v_cache, seq_stride: int,
                         nb_capacity: int, n_ctx, idx, n_sel, k_cap: int, out, lse, workspace,
-                        stream=None) -> None:
+                        stream=None, per_head: bool = False) -> None:
+    """per_head: idx [batch][Hk][k_cap], n_sel [batch][Hk] (actqkv_retrieval_attention_per_head)."""
     st = torch.float32 if shape.dtype == ACTQKV_F32 else torch.bfloat16
-    _check(load_library().actqkv_retrieval_attention(
+    lib = load_library()
+    _check((lib.actqkv_retrieval_attention_per_head if per_head else lib.actqkv_retrieval_attention)(
         ctypes.byref(shape), batch, m, _ptr(q, st), _ptr(k_cache, st), _ptr(v_cache, st),
         seq_stride, nb_capacity, _ptr(n_ctx, torch.int32), _ptr(idx, torch.int32),
         _ptr(n_sel, torch.int32), k_cap, _ptr(out, st), _ptr(lse, torch.float32),

@@ -108,7 +108,7 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
                                   int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
                                   const int32_t* n_sel, int k_cap, void* out, float* lse,
                                   const PfSplits& splits, float* scratch, unsigned int* counters,
-                                  float scale, hipStream_t stream);
+                                  float scale, int sel_per_head, hipStream_t stream);
 
 // Compute units the prefill attention may fill (actqkv_set_attention_cus).
 static std::atomic<int> g_attention_cus{256};
@@ -141,7 +141,7 @@ int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* 
                                  const void* v_cache, int64_t seq_stride, int nb_capacity,
                                  const int32_t* n_ctx, const int32_t* idx, const int32_t* n_sel,
                                  int k_cap, void* out, float* lse, float* scratch,
-                                 unsigned int* counters, float scale, hipStream_t stream);
+                                 unsigned int* counters, float scale, int sel_per_head, hipStream_t stream);
 
 size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap) {
   (void)nb_capacity;
@@ -160,24 +160,24 @@ size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity
 int launch_attention_rows(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
                           const void* v_cache, int64_t seq_stride, int nb_capacity,
                           const int32_t* n_ctx, const int32_t* idx, const int32_t* n_sel, int k_cap,
-                          void* out, float* lse, float scale, hipStream_t stream);
+                          void* out, float* lse, float scale, int sel_per_head, hipStream_t stream);
 
 int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
                      const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
                      const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
-                     const Workspace& ws, hipStream_t stream) {
+                     const Workspace& ws, int sel_per_head, hipStream_t stream) {
   const float scale = sh.softmax_scale > 0.f ? sh.softmax_scale : 1.f / std::sqrt(float(sh.head_dim));
   if (decode_mfma_supported(sh, m))
     return launch_attention_decode_mfma(sh, batch, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx,
                                         idx, n_sel, k_cap, out, lse, ws.scratch_f32(), ws.counters(), scale,
-                                        stream);
+                                        sel_per_head, stream);
   if (prefill_mfma_supported(sh, m))
     return launch_attention_prefill_mfma(sh, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity,
                                          n_ctx, idx, n_sel, k_cap, out, lse,
                                          prefill_splits(sh, batch, m, k_cap), ws.scratch_f32(),
-                                         ws.counters(), scale, stream);
+                                         ws.counters(), scale, sel_per_head, stream);
   return launch_attention_rows(sh, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx,
-                               n_sel, k_cap, out, lse, scale, stream);
+                               n_sel, k_cap, out, lse, scale, sel_per_head, stream);
 }
 
 }  // namespace actqkv
@@ -285,11 +285,10 @@ int actqkv_select(int batch, const float* scores, int64_t score_stride, int nb_c
                        static_cast<hipStream_t>(stream));
 }
 
-int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, const void* q,
-                               const void* k_cache, const void* v_cache, int64_t seq_stride,
-                               int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
-                               const int32_t* n_sel, int k_cap, void* out, float* lse, void* workspace,
-                               size_t ws_bytes, void* stream) {
+static int attention_checked(const actqkv_shape* shape, int batch, int m, const void* q, const void* k_cache,
+                             const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
+                             const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
+                             void* workspace, size_t ws_bytes, int sel_per_head, void* stream) {
   ACTQKV_TRY(check_shape(shape));
   ACTQKV_TRY(check_batch(batch));
   if (m < 1) return set_error(ACTQKV_EINVAL, "m %d < 1", m);
@@ -322,7 +321,47 @@ int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, cons
                      need);
   Workspace ws{workspace, ws_bytes};
   return launch_attention(*shape, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx,
-                          n_sel, k_cap, out, lse, ws, static_cast<hipStream_t>(stream));
+                          n_sel, k_cap, out, lse, ws, sel_per_head, static_cast<hipStream_t>(stream));
+}
+
+int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, const void* q,
+                               const void* k_cache, const void* v_cache, int64_t seq_stride,
+                               int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
+                               const int32_t* n_sel, int k_cap, void* out, float* lse, void* workspace,
+                               size_t ws_bytes, void* stream) {
+  return attention_checked(shape, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx, n_sel,
+                           k_cap, out, lse, workspace, ws_bytes, 0, stream);
+}
+
+int actqkv_retrieval_attention_per_head(const actqkv_shape* shape, int batch, int m, const void* q,
+                                        const void* k_cache, const void* v_cache, int64_t seq_stride,
+                                        int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
+                                        const int32_t* n_sel, int k_cap, void* out, float* lse,
+                                        void* workspace, size_t ws_bytes, void* stream) {
+  return attention_checked(shape, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx, n_sel,
+                           k_cap, out, lse, workspace, ws_bytes, 1, stream);
+}
+
+int actqkv_score_blocks_per_head(const actqkv_shape* shape, int batch, const float* probe, const void* rep_keys,
+                                 int64_t seq_stride, int nb_capacity, int nb_begin, const int32_t* nb_end,
+                                 float* scores, int64_t score_stride, void* stream) {
+  ACTQKV_TRY(check_shape(shape));
+  ACTQKV_TRY(check_batch(batch));
+  ACTQKV_TRY(check_blocks(nb_capacity, nb_begin, 1, false));
+  ACTQKV_REQUIRE_PTR(probe);
+  ACTQKV_REQUIRE_PTR(rep_keys);
+  ACTQKV_REQUIRE_SMALL(nb_end, 4);
+  ACTQKV_REQUIRE_SMALL(scores, 4);
+  if (score_stride < nb_capacity)
+    return set_error(ACTQKV_EINVAL, "score_stride %lld < nb_capacity %d", (long long)score_stride,
+                     nb_capacity);
+  const int64_t per_seq = int64_t(nb_capacity) * shape->n_rep * shape->n_kv_heads * shape->head_dim;
+  if (batch > 1 && seq_stride != 0 && seq_stride < per_seq)
+    return set_error(ACTQKV_EINVAL, "seq_stride %lld < one sequence's representative keys %lld",
+                     (long long)seq_stride, (long long)per_seq);
+  if (seq_stride % 8 != 0) return set_error(ACTQKV_EALIGN, "seq_stride must be a multiple of 8 elements");
+  return launch_score_per_head(*shape, batch, probe, rep_keys, seq_stride, nb_capacity, nb_begin, nb_end,
+                               scores, score_stride, static_cast<hipStream_t>(stream));
 }
 
 int actqkv_copy_bytes(void* dst, const void* src, size_t bytes, void* stream) {

@@ -40,6 +40,7 @@ struct DcParams {
   unsigned int* counters;   // one ticket counter per (sequence, KV head), zero between launches
   int n_q_heads, n_kv_heads, n_init, n_local;
   int n_wg;     // workgroups per (sequence, KV head); 1: the workgroup writes the output itself
+  int sel_per_head;   // 1: idx and n_sel have a row per (sequence, KV head), 0: per sequence
   float scale_log2e;
 };
 
@@ -58,7 +59,8 @@ __global__ __launch_bounds__(kDcMaxWaves * 64) void attn_decode_kernel(DcParams 
 
   const int n_ctx = min(max(p.n_ctx[s], 1), p.nb_capacity * kBlock);
   const WindowGeom g = window_geom(n_ctx, 1, p.n_init, p.n_local);
-  const TileList tl = make_tile_list(g, n_ctx - 1, p.idx + size_t(s) * p.k_cap, p.n_sel[s], p.k_cap,
+  const size_t sel_row = p.sel_per_head ? size_t(s) * p.n_kv_heads + hk : size_t(s);
+  const TileList tl = make_tile_list(g, n_ctx - 1, p.idx + sel_row * p.k_cap, p.n_sel[sel_row], p.k_cap,
                                      p.nb_capacity);
   const int n_tiles = tl.count();
 
@@ -272,7 +274,7 @@ int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* 
                                  const void* v_cache, int64_t seq_stride, int nb_capacity,
                                  const int32_t* n_ctx, const int32_t* idx, const int32_t* n_sel,
                                  int k_cap, void* out, float* lse, float* scratch,
-                                 unsigned int* counters, float scale, hipStream_t stream) {
+                                 unsigned int* counters, float scale, int sel_per_head, hipStream_t stream) {
   DcParams p;
   p.q = static_cast<const uint16_t*>(q);
   p.k_cache = static_cast<const uint16_t*>(k_cache);
@@ -282,6 +284,7 @@ int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* 
   p.n_ctx = n_ctx;
   p.idx = idx;
   p.n_sel = n_sel;
+  p.sel_per_head = sel_per_head;
   p.k_cap = k_cap;
   p.out = static_cast<uint16_t*>(out);
   p.lse = lse;

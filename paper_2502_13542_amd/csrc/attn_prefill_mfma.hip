@@ -88,6 +88,7 @@ struct PfParams {
   int m, n_q_heads, n_kv_heads, n_init, n_local;
   int s_lo, rem, slots, n_qtiles;   // pieces per query tile (PfSplits)
   int items_per_head, wgs_per_head; // work items and workgroups of one KV head
+  int sel_per_head;                 // 1: idx and n_sel have a row per (sequence, KV head), 0: per sequence
   unsigned int* queue;              // per KV head: items handed out beyond the first round; [kPfQueueDone]: workgroups that left
   float scale_log2e;
 };
@@ -144,8 +145,9 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
   // the selected block indices are requested together with the two scalars they are used
   // with, not after them (one memory round trip less before the first tile can be fetched)
   __shared__ int32_t idx_lds[64];
-  const int32_t my_idx = tid < p.k_cap ? p.idx[size_t(s) * p.k_cap + tid] : -1;
-  const int n_ctx_raw = p.n_ctx[s], n_sel_raw = p.n_sel[s];
+  const size_t sel_row = p.sel_per_head ? size_t(s) * p.n_kv_heads + hk : size_t(s);
+  const int32_t my_idx = tid < p.k_cap ? p.idx[sel_row * p.k_cap + tid] : -1;
+  const int n_ctx_raw = p.n_ctx[s], n_sel_raw = p.n_sel[sel_row];
   if (tid < 64) idx_lds[tid] = my_idx;
   __syncthreads();
   const int n_ctx = min(max(n_ctx_raw, p.m), p.nb_capacity * kBlock);
@@ -530,7 +532,7 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
                                   int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
                                   const int32_t* n_sel, int k_cap, void* out, float* lse,
                                   const PfSplits& splits, float* scratch, unsigned int* counters,
-                                  float scale, hipStream_t stream) {
+                                  float scale, int sel_per_head, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_mfma_kernel),
@@ -550,6 +552,7 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
   p.n_ctx = n_ctx;
   p.idx = idx;
   p.n_sel = n_sel;
+  p.sel_per_head = sel_per_head;
   p.k_cap = k_cap;
   p.out = static_cast<uint16_t*>(out);
   p.lse = lse;

@@ -17,7 +17,7 @@ __global__ __launch_bounds__(kRowsPerWG) void attn_rows_kernel(
     int64_t seq_stride, int nb_capacity, const int32_t* __restrict__ n_ctx_arr,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ n_sel, int k_cap,
     T* __restrict__ out, float* __restrict__ lse, int m, int n_q_heads, int n_kv_heads, int n_init,
-    int n_local, float scale) {
+    int n_local, float scale, int sel_per_head) {
   __shared__ float ks[kSub][D];
   __shared__ float vs[D][kSub];
   const int s = blockIdx.z, h = blockIdx.y, hk = h / (n_q_heads / n_kv_heads);
@@ -27,7 +27,8 @@ __global__ __launch_bounds__(kRowsPerWG) void attn_rows_kernel(
   const WindowGeom g = window_geom(n_ctx, m, n_init, n_local);
   const int p = g.w0 + row;  // this thread's query position
   const int q_hi = g.w0 + min(m, (int(blockIdx.x) + 1) * kRowsPerWG) - 1;
-  const TileList tl = make_tile_list(g, q_hi, idx + size_t(s) * k_cap, n_sel[s], k_cap, nb_capacity);
+  const size_t sel_row = sel_per_head ? size_t(s) * n_kv_heads + hk : size_t(s);
+  const TileList tl = make_tile_list(g, q_hi, idx + sel_row * k_cap, n_sel[sel_row], k_cap, nb_capacity);
   const T* kc = k_cache + size_t(s) * seq_stride;
   const T* vc = v_cache + size_t(s) * seq_stride;
 
@@ -102,22 +103,22 @@ template <typename T, int D>
 static void launch_rows_t(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
                           const void* v_cache, int64_t seq_stride, int nb_capacity,
                           const int32_t* n_ctx, const int32_t* idx, const int32_t* n_sel, int k_cap,
-                          void* out, float* lse, float scale, hipStream_t stream) {
+                          void* out, float* lse, float scale, int sel_per_head, hipStream_t stream) {
   dim3 grid((m + kRowsPerWG - 1) / kRowsPerWG, sh.n_q_heads, batch);
   hipLaunchKernelGGL((attn_rows_kernel<T, D>), grid, dim3(kRowsPerWG), 0, stream,
                      static_cast<const T*>(q), static_cast<const T*>(k_cache),
                      static_cast<const T*>(v_cache), seq_stride, nb_capacity, n_ctx, idx, n_sel, k_cap,
                      static_cast<T*>(out), lse, m, sh.n_q_heads, sh.n_kv_heads, sh.n_init, sh.n_local,
-                     scale);
+                     scale, sel_per_head);
 }
 
 int launch_attention_rows(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
                           const void* v_cache, int64_t seq_stride, int nb_capacity,
                           const int32_t* n_ctx, const int32_t* idx, const int32_t* n_sel, int k_cap,
-                          void* out, float* lse, float scale, hipStream_t stream) {
+                          void* out, float* lse, float scale, int sel_per_head, hipStream_t stream) {
 #define ACTQKV_ROWS(T, D)                                                                         \
   launch_rows_t<T, D>(sh, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx, n_sel, \
-                      k_cap, out, lse, scale, stream)
+                      k_cap, out, lse, scale, sel_per_head, stream)
   if (sh.dtype == ACTQKV_F32) {
     if (sh.head_dim == 64) ACTQKV_ROWS(float, 64); else ACTQKV_ROWS(float, 128);
   } else {

@@ -81,7 +81,10 @@ int launch_select(int batch, const float* scores, int64_t score_stride, int nb_c
 int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
                      const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
                      const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
-                     const Workspace& ws, hipStream_t stream);
+                     const Workspace& ws, int sel_per_head, hipStream_t stream);
+int launch_score_per_head(const actqkv_shape& sh, int batch, const float* probe, const void* rep_keys,
+                          int64_t seq_stride, int nb_capacity, int nb_begin, const int32_t* nb_end,
+                          float* scores, int64_t score_stride, hipStream_t stream);
 
 int launch_append(const actqkv_shape& sh, int batch, int m, const void* k_new, const void* v_new,
                   const int32_t* pos0, void* k_cache, void* v_cache, int64_t cache_stride,

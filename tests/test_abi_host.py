@@ -97,6 +97,11 @@ def test_score_select_attention_reject(lib):
                                                     k.get("wsb", 1 << 30), None)
     assert at(kc=None) == -1 and at(out=A16 + 2) == -3 and at(ws=None) == -4 and at(wsb=8) == -4
     assert at(m=0) == -1 and at(cap=2) == -1 and at(cap=0) == -1
+    sp = lambda **k: lib.actqkv_score_blocks_per_head(ctypes.byref(cs), 1, k.get("probe", A16), k.get("rep", A16), 0,
+                                                      k.get("cap", 64), 1, A16, A16, k.get("ss", 64), None)
+    assert sp(probe=None) == -1 and sp(rep=A16 + 8) == -3 and sp(ss=10) == -1 and sp(cap=9000, ss=9000) == -2
+    assert lib.actqkv_retrieval_attention_per_head(ctypes.byref(cs), 1, 512, A16, None, A16, 0, 64, A16, A16, A16, 32,
+                                                   A16, None, A16, 1 << 30, None) == -1
     ap = lambda **k: lib.actqkv_append_kv_probe(ctypes.byref(cs), 1, k.get("q", A16), A16, A16, A16, A16, A16, 0, None,
                                                 0, k.get("cap", 64), k.get("probe", A16), A16, A16, None)
     assert ap(q=None) == -1 and b"q_tok" in lib.actqkv_last_error() and ap(probe=None) == -1

@@ -118,9 +118,10 @@ def test_c3_128k_full_size_sampled_windows():
 
 
 def test_c5_200k_full_size_sampled_windows():
-    # configs[4] at full size, its last layer (3 % outlier tokens): every window's probe, scores,
-    # density, budget and selection, and the attention of a spread of windows
-    run_prefill_case(synth.WORKLOADS["c5_200k"], attend=[5, 211, 399], layer=31)
+    # configs[4] at full size in its ragged form (200,000 tokens: the last window has 320 rows),
+    # its last layer (3 % outlier tokens): every window's probe, scores, density, budget and
+    # selection, and the attention of a spread of windows
+    run_prefill_case(synth.scaled(synth.WORKLOADS["c5_200k"], n_ctx=200000), attend=[5, 211, 390], layer=31)
 
 
 def test_c3_128k_two_stream_pipeline_as_benchmarked():
@@ -846,3 +847,83 @@ def test_prefill_with_the_cache_in_host_memory():
                                                  gi[:gn], sh.n_init, sh.n_local, sh.block_size, sh.group)
         err = out_error(out_host[res["w0"]:res["w0"] + ref.shape[0]], ref)
         assert err < TOL_OUT["bf16"], f"attention output, window {t}: {err}"
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d,m,n_ctx", [("bf16", 32, 8, 128, 512, 512 * 7 + 130),
+                                                   ("fp32", 8, 2, 64, 256, 256 * 9 + 40),
+                                                   ("bf16", 32, 8, 128, 1, 2200)])
+def test_retrieval_per_kv_head(dtype, hq, hkv, d, m, n_ctx):
+    """The per-KV-head variant: actqkv_score_blocks_per_head, actqkv_select on batch * Hk rows
+    (with a cut-off state per row) and actqkv_retrieval_attention_per_head against the oracle's
+    retrieve_per_head / retrieval_attention_per_head, for a prefill window (matrix-core and
+    row kernels) and a decode step."""
+    sh = LayerShape(hq, hkv, d, 128, 4, 128, 256, dtype)
+    cs = B.c_shape(sh)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    g = torch.Generator().manual_seed(3 * d + m)
+    k_cap, G = 6, hq // hkv
+    _say(f"[case] per-KV-head retrieval {dtype} H{hq}/Hk{hkv}/D{d} m={m} N={n_ctx}")
+    q_all = (torch.randn(n_ctx, hq, d, generator=g) * 1.2).to(td)
+    k = torch.randn(n_ctx, hkv, d, generator=g).to(td)
+    v = torch.randn(n_ctx, hkv, d, generator=g).to(td)
+    nb = (n_ctx + 127) // 128
+    # a few blocks every head likes, and one block only head 1 likes
+    u = torch.randn(hkv, d, generator=g)
+    for b in (3, 9):
+        k[b * 128:(b + 1) * 128] = (k[b * 128:(b + 1) * 128].float() + 0.8 * u).to(td)
+    k[5 * 128:6 * 128, 1] = (k[5 * 128:6 * 128, 1].float() + 1.5 * u[1]).to(td)
+    w0 = n_ctx - m
+    q = q_all[w0:].clone()
+    q = (q.float() + 2.0 * u.repeat_interleave(G, dim=0)).to(td)
+    rep = synth.pick_rep_keys(k, 128, 4)
+    repd = torch.zeros(nb, 4, hkv, d, dtype=td, device=DEV)
+    repd[: rep.shape[0]] = rep.to(DEV)
+    kc, vc = H.blocked_k(k.to(DEV), sh, nb), H.blocked_vt(v.to(DEV), sh, nb)
+    qd = q.to(DEV)
+    runner = H.LayerRunner(sh, 1, m, nb, k_cap, DEV)
+    B.build_probe(cs, 1, m, qd, runner.stats, True, runner.probe, runner.probe_kv, runner.probe_norm, None,
+                  runner.workspace)
+    nb_begin, nb_e = H.eligible_range(sh, w0)
+    stride = runner.score_stride
+    scores = torch.zeros(1, hkv, stride, device=DEV)
+    nb_end = torch.full((1, hkv), nb_e, dtype=torch.int32, device=DEV)
+    B.score_blocks_per_head(cs, 1, runner.probe, repd, 0, nb_e, nb_begin, nb_end, scores, stride)
+    cut = [(2.0 * k_cap + 0.37 * hk, 1.5 * math.log(max(nb_e - nb_begin, 2))) for hk in range(hkv)]
+    bud = torch.tensor([c[0] for c in cut], dtype=torch.float32, device=DEV)
+    rest = torch.tensor([c[1] for c in cut], dtype=torch.float32, device=DEV)
+    idx = torch.zeros(hkv, k_cap, dtype=torch.int32, device=DEV)
+    n_sel = torch.zeros(hkv, dtype=torch.int32, device=DEV)
+    theta = torch.zeros(hkv, device=DEV)
+    budget = torch.zeros(hkv, device=DEV)
+    B.select(hkv, scores.view(hkv, stride), stride, nb_e, nb_begin, nb_end.view(hkv), k_cap, bud, rest, idx, n_sel,
+             theta, budget)
+    out = torch.zeros_like(qd)
+    n_ctx_d = torch.tensor([n_ctx], dtype=torch.int32, device=DEV)
+    B.retrieval_attention(cs, 1, m, qd, kc, vc, 0, nb, n_ctx_d, idx, n_sel, k_cap, out, None, runner.workspace,
+                          per_head=True)
+    torch.cuda.synchronize()
+    probe64 = f64(runner.probe[0])                      # the GPU's probe (its own parity is tested elsewhere)
+    want = orc.retrieve_per_head(probe64, f64(rep), w0, sh.n_init, sh.n_local, 128, G, k_cap, cut)
+    sel = []
+    for hk in range(hkv):
+        res = want[hk]
+        gs = f64(scores[0, hk])[res["eligible"]]
+        assert np.abs(gs - res["scores"]).max() < TOL_SCORE, f"scores, head {hk}"
+        assert abs(float(theta[hk]) - res["theta"]) < TOL_THETA
+        gi, gn = idx[hk].cpu().tolist(), int(n_sel[hk])
+        check_selection(gi, gn, res, k_cap)
+        sel.append(gi[:gn])
+    assert len({tuple(x) for x in sel}) > 1, "the heads should not all select the same blocks here"
+    ref = orc.retrieval_attention_per_head(f64(q), f64(k), f64(v), w0, sel, sh.n_init, sh.n_local, 128, G)
+    err = out_error(out, ref)
+    assert err < TOL_OUT[dtype], f"attention output: {err}"
+    # the same selection for every head through the per-head call = the shared call
+    idx_same = idx[0:1].repeat(hkv, 1).contiguous()
+    n_same = n_sel[0:1].repeat(hkv).contiguous()
+    out_a, out_b = torch.zeros_like(qd), torch.zeros_like(qd)
+    B.retrieval_attention(cs, 1, m, qd, kc, vc, 0, nb, n_ctx_d, idx_same, n_same, k_cap, out_a, None,
+                          runner.workspace, per_head=True)
+    B.retrieval_attention(cs, 1, m, qd, kc, vc, 0, nb, n_ctx_d, idx[0:1], n_sel[0:1], k_cap, out_b, None,
+                          runner.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(out_a, out_b)

@@ -203,6 +203,50 @@ def test_p7b_information_density_over_the_best_blocks():
     assert math.isclose(orc.information_density_topk(t, 3), float(-(q * np.log(q)).sum()), rel_tol=1e-12)
 
 
+def test_p8b_scores_and_attention_per_kv_head():
+    """Per-KV-head retrieval (the alternative to the head-merged reading).  Closed forms: a
+    block whose key of head hk is parallel to that head's share of the probe scores exactly 1 in
+    row hk and what the other heads' keys give elsewhere; with one KV head the rows are the
+    merged scores; exchanging two KV heads exchanges the rows; giving every head the same
+    selection reproduces the merged attention; a head's output depends on its own selection only."""
+    rng = np.random.default_rng(21)
+    hk_n, g, d, nb, r = 3, 2, 8, 6, 2
+    probe = rng.normal(size=(hk_n * g, d))
+    rep = rng.normal(size=(nb, r, hk_n, d))
+    share = probe.reshape(hk_n, g, d)
+    # head 1 of block 4: every representative key parallel to the SUM of the group's probe rows
+    # is not enough for cosine 1 (the key is repeated to both heads); make the group's rows equal
+    probe[2] = probe[3]
+    rep[4, :, 1] = 2.5 * probe[2]
+    s = orc.block_scores_per_head(probe.reshape(-1), rep, g)
+    assert s.shape == (hk_n, nb) and math.isclose(s[1, 4], 1.0, rel_tol=1e-12)
+    assert abs(s[0, 4]) < 1.0 and abs(s[2, 4]) < 1.0
+    one = orc.block_scores_per_head(probe[:g].reshape(-1), rep[:, :, :1], g)
+    assert np.allclose(one[0], orc.block_scores(probe[:g].reshape(-1), rep[:, :, :1], g), rtol=1e-13)
+    perm = [2, 1, 0]
+    probe_p = probe.reshape(hk_n, g, d)[perm].reshape(hk_n * g, d)
+    s_p = orc.block_scores_per_head(probe_p.reshape(-1), rep[:, :, perm], g)
+    assert np.allclose(s_p, s[perm], rtol=1e-13)
+    # the merged score is NOT the mean of the rows (the norms differ per head): a real variant
+    assert not np.allclose(orc.block_scores(probe.reshape(-1), rep, g), s.mean(axis=0))
+    # attention
+    n, m, block = 6 * 4 + 3, 4, 4
+    q = rng.normal(size=(m, hk_n * g, d))
+    k = rng.normal(size=(n, hk_n, d))
+    v = rng.normal(size=(n, hk_n, d))
+    w0 = n - m
+    same = orc.retrieval_attention_per_head(q, k, v, w0, [[1, 3]] * hk_n, 4, 4, block, g)
+    assert np.allclose(same, orc.retrieval_attention(q, k, v, w0, [1, 3], 4, 4, block, g), rtol=1e-12, atol=1e-14)
+    a = orc.retrieval_attention_per_head(q, k, v, w0, [[1], [2, 3], []], 4, 4, block, g)
+    b = orc.retrieval_attention_per_head(q, k, v, w0, [[1], [3], [2]], 4, 4, block, g)
+    assert np.allclose(a[:, :g], b[:, :g], rtol=1e-13) and not np.allclose(a[:, g:2 * g], b[:, g:2 * g])
+    # the per-head retrieval is `retrieve` on the cut-down model
+    res = orc.retrieve_per_head(probe.reshape(-1), rep, 5 * block, block, block, block, g, 2, None)
+    elig = orc.eligible_blocks(5 * block, block, block, block)
+    for hk in range(hk_n):
+        assert res[hk]["idx"] == orc.select_blocks(s[hk][elig], elig, 2)
+
+
 def test_p9_budget_monotone_in_density():
     thetas = np.linspace(0.01, 7.0, 200)
     b = [orc.layer_budget(float(t), 90.0, 640.0) for t in thetas]
