@@ -465,12 +465,20 @@ def bench_decode(args, torch, B, H, synth):
         # folds the step before into the history; B_kv = L * k again; R^l for every layer
         B.cutoff_next_step(bt, L, k_mean, theta_prior, theta_step, theta_sum, hist_steps, budget, rest_all)
         for l in range(L):
-            B.append_kv_probe(runner.cs, bt, q_step[l], k_step[l], v_step[l], pos_cur, kc[l], vc[l], cache_stride,
-                              rep[l], rep_stride, nb_cap, runner.probe, runner.probe_kv, runner.probe_norm)
-            B.score_blocks(runner.cs, bt, runner.probe_kv, runner.probe_norm, rep[l], rep_stride,
-                           nb_end_host[-1], nb_begin, nb_end_cur, runner.scores, runner.score_stride)
-            B.select(bt, runner.scores, runner.score_stride, nb_end_host[-1], nb_begin, nb_end_cur,
-                     w.k_cap, budget, rest_all[l], runner.idx, nsel_log[l], theta_step[l], None)
+            if args.decode_launches == 3:
+                # cache update, probe and scores in one launch, then the selection
+                B.decode_retrieve(runner.cs, bt, q_step[l], k_step[l], v_step[l], pos_cur, kc[l], vc[l],
+                                  cache_stride, rep[l], rep_stride, nb_cap, nb_begin, nb_end_cur, None, None,
+                                  None, runner.scores, runner.score_stride, w.k_cap, budget, rest_all[l],
+                                  runner.idx, nsel_log[l], theta_step[l], None)
+            else:
+                B.append_kv_probe(runner.cs, bt, q_step[l], k_step[l], v_step[l], pos_cur, kc[l], vc[l],
+                                  cache_stride, rep[l], rep_stride, nb_cap, runner.probe, runner.probe_kv,
+                                  runner.probe_norm)
+                B.score_blocks(runner.cs, bt, runner.probe_kv, runner.probe_norm, rep[l], rep_stride,
+                               nb_end_host[-1], nb_begin, nb_end_cur, runner.scores, runner.score_stride)
+                B.select(bt, runner.scores, runner.score_stride, nb_end_host[-1], nb_begin, nb_end_cur,
+                         w.k_cap, budget, rest_all[l], runner.idx, nsel_log[l], theta_step[l], None)
             if events is not None:
                 events[l][0].record()
             B.retrieval_attention(runner.cs, bt, 1, q_step[l], kc[l], vc[l], cache_stride, nb_cap,
@@ -528,7 +536,8 @@ def bench_decode(args, torch, B, H, synth):
         "config": {"workload": f"{w.name}: batch {bt}, {L} layers, {n0} cached tokens, k_cap {w.k_cap}, "
                                f"dynamic cut-off with the density history on the device, new token appended per layer, KV cache {gb:.0f} GB bf16 in HBM",
                    "mean_blocks_selected": float(n_sel.float().mean()),
-                   "launch": "hip graph replay" if graph is not None else "eager"},
+                   "launch": "hip graph replay" if graph is not None else "eager",
+                   "launches_per_layer": args.decode_launches},
         "algorithmic_bytes_per_step": byt + score_bytes,
         "hbm_frac_of_step": (byt + score_bytes) / (mean_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -552,6 +561,9 @@ def main() -> int:
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--decode-layers", type=int, default=0, help="override the layer count (testing)")
+    ap.add_argument("--decode-launches", type=int, default=3, choices=(3, 4),
+                    help="launches per layer of a decode step: 3 = (cache update + probe + scores), selection, "
+                         "attention; 4 = (cache update + probe), scores, selection, attention")
     ap.add_argument("--no-overlap", action="store_true",
                     help="prefill: one stream, strictly in window order")
     ap.add_argument("--chunk", type=int, default=32,

@@ -50,7 +50,7 @@
 extern "C" {
 #endif
 
-#define ACTQKV_VERSION 101
+#define ACTQKV_VERSION 102
 
 enum {
   ACTQKV_OK = 0,
@@ -279,6 +279,34 @@ int actqkv_append_kv_probe(const actqkv_shape* shape, int batch, const void* q_t
                            int64_t cache_seq_stride, void* rep_keys, int64_t rep_seq_stride,
                            int nb_capacity, float* probe, float* probe_kv, float* probe_norm,
                            void* stream);
+
+/* Everything of a decode step that comes before the attention, in ONE call of two launches
+ * instead of four: the cache update (Sec. 3.1, Eq. (4); actqkv_append_kv with m = 1), the probe
+ * of the one-token window (the query itself, Sec. 4.2; actqkv_build_probe with m = 1 and no
+ * statistics) and the block scores (Eq. (10); actqkv_score_blocks) in the first, the selection
+ * with the cut-off (Eq. (11), Eq. (12), Alg. 1; actqkv_select) in the second.  Same results as
+ * the four calls (the probe's norm, and with it the scores, up to the order of an fp32 sum);
+ * what is saved is launch and drain time, which exceeds the work of the update and the probe.
+ *   q_tok  [batch][H][D], storage dtype.
+ *   k_new, v_new, pos0  as in actqkv_append_kv with m = 1; k_new = v_new = pos0 = NULL: no cache
+ *            update (k_cache, v_cache may then be NULL too).  nb_end[s] must not reach block
+ *            pos0[s] / Bs: the block that receives the token lies in the local span, and a block
+ *            has representatives only once it is full.
+ *   k_cache, v_cache, cache_seq_stride, rep_keys, rep_seq_stride, nb_capacity (>= 1)
+ *            as in actqkv_append_kv; rep_keys is required (it is what gets scored).
+ *   nb_begin, nb_end, scores, score_stride  as in actqkv_score_blocks.
+ *   probe, probe_kv, probe_norm  optional outputs (NULL: not written) as in actqkv_build_probe.
+ *   k_cap, flags, budget_remaining, theta_rest_sum, idx, n_sel, theta, budget
+ *            as in actqkv_select.
+ * Errors: as in the four calls. */
+int actqkv_decode_retrieve(const actqkv_shape* shape, int batch, const void* q_tok, const void* k_new,
+                           const void* v_new, const int32_t* pos0, void* k_cache, void* v_cache,
+                           int64_t cache_seq_stride, void* rep_keys, int64_t rep_seq_stride,
+                           int nb_capacity, int nb_begin, const int32_t* nb_end, float* probe,
+                           float* probe_kv, float* probe_norm, float* scores, int64_t score_stride,
+                           int k_cap, int flags, float* budget_remaining,
+                           const float* theta_rest_sum, int32_t* idx, int32_t* n_sel, float* theta,
+                           float* budget, void* stream);
 
 /* Selected blocks from a block store into a working cache (Sec. 3.1: the cache may be kept
  * in CPU memory).

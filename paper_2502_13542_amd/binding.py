@@ -62,6 +62,8 @@ SIGNATURES = {
     "actqkv_cutoff_next_step": (_i, [_i, _i, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_set_attention_cus": (_i, [_i]),
     "actqkv_append_kv_probe": (_i, [_shp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _vp, _vp, _vp, _vp]),
+    "actqkv_decode_retrieve": (_i, [_shp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _i, _vp, _vp, _vp,
+                                    _vp, _vp, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_copy_bytes": (_i, [_vp, _vp, _sz, _vp]),
     "actqkv_gather_blocks": (_i, [_shp, _i, _vp, _vp, _i64, _i, _vp, _vp, _i, _vp, _vp, _i64, _i, _i, _vp, _vp]),
     "actqkv_last_error": (ctypes.c_char_p, []),
@@ -159,6 +161,22 @@ def append_kv_probe(shape: CShape, batch: int, q_tok, k_new, v_new, pos0, k_cach
         ctypes.byref(shape), batch, _ptr(q_tok, st), _ptr(k_new, st), _ptr(v_new, st), _ptr(pos0, torch.int32),
         _ptr(k_cache, st), _ptr(v_cache, st), cache_seq_stride, _ptr(rep_keys, st), rep_seq_stride,
         nb_capacity, _ptr(probe, f), _ptr(probe_kv, f), _ptr(probe_norm, f), _stream(stream)))
+
+
+def decode_retrieve(shape: CShape, batch: int, q_tok, k_new, v_new, pos0, k_cache, v_cache,
+                    cache_seq_stride: int, rep_keys, rep_seq_stride: int, nb_capacity: int, nb_begin: int,
+                    nb_end, probe, probe_kv, probe_norm, scores, score_stride: int, k_cap: int,
+                    budget_remaining, theta_rest_sum, idx, n_sel, theta, budget, stream=None,
+                    flags: int = 0) -> None:
+    """Cache update, probe, scores and selection of a decode step in one call; see the header."""
+    st = torch.float32 if shape.dtype == ACTQKV_F32 else torch.bfloat16
+    f, i32 = torch.float32, torch.int32
+    _check(load_library().actqkv_decode_retrieve(
+        ctypes.byref(shape), batch, _ptr(q_tok, st), _ptr(k_new, st), _ptr(v_new, st), _ptr(pos0, i32),
+        _ptr(k_cache, st), _ptr(v_cache, st), cache_seq_stride, _ptr(rep_keys, st), rep_seq_stride,
+        nb_capacity, nb_begin, _ptr(nb_end, i32), _ptr(probe, f), _ptr(probe_kv, f), _ptr(probe_norm, f),
+        _ptr(scores, f), score_stride, k_cap, int(flags), _ptr(budget_remaining, f), _ptr(theta_rest_sum, f),
+        _ptr(idx, i32), _ptr(n_sel, i32), _ptr(theta, f), _ptr(budget, f), _stream(stream)))
 
 
 def cutoff_next_step(batch: int, n_layers: int, k_mean: float, theta_prior: float, theta_prev,

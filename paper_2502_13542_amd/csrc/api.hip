@@ -456,6 +456,64 @@ int actqkv_append_kv_probe(const actqkv_shape* shape, int batch, const void* q_t
                         rep_seq_stride, nb_capacity, q_tok, probe, probe_kv, probe_norm, stream);
 }
 
+int actqkv_decode_retrieve(const actqkv_shape* shape, int batch, const void* q_tok, const void* k_new,
+                           const void* v_new, const int32_t* pos0, void* k_cache, void* v_cache,
+                           int64_t cache_seq_stride, void* rep_keys, int64_t rep_seq_stride,
+                           int nb_capacity, int nb_begin, const int32_t* nb_end, float* probe,
+                           float* probe_kv, float* probe_norm, float* scores, int64_t score_stride,
+                           int k_cap, int flags, float* budget_remaining,
+                           const float* theta_rest_sum, int32_t* idx, int32_t* n_sel, float* theta,
+                           float* budget, void* stream) {
+  ACTQKV_TRY(check_shape(shape));
+  ACTQKV_TRY(check_batch(batch));
+  if (flags & ~ACTQKV_SELECT_ENTROPY_TOPK)
+    return set_error(ACTQKV_EINVAL, "decode_retrieve: unknown flag bits: %d", flags);
+  if (nb_capacity < 1) return set_error(ACTQKV_EINVAL, "nb_capacity %d < 1", nb_capacity);
+  if (int64_t(nb_capacity) * shape->block_size > (int64_t(1) << 30))
+    return set_error(ACTQKV_ESHAPE, "cache of %d blocks exceeds 2^30 tokens", nb_capacity);
+  ACTQKV_TRY(check_blocks(nb_capacity, nb_begin, k_cap, true));
+  ACTQKV_REQUIRE_PTR(q_tok);
+  const bool update = k_new != nullptr || v_new != nullptr || pos0 != nullptr;
+  if (update) {
+    ACTQKV_REQUIRE_PTR(k_new);
+    ACTQKV_REQUIRE_PTR(v_new);
+    ACTQKV_REQUIRE_SMALL(pos0, 4);
+    ACTQKV_REQUIRE_PTR(k_cache);
+    ACTQKV_REQUIRE_PTR(v_cache);
+  }
+  ACTQKV_REQUIRE_PTR(rep_keys);
+  ACTQKV_REQUIRE_SMALL(nb_end, 4);
+  ACTQKV_OPTIONAL_PTR(probe);
+  ACTQKV_OPTIONAL_PTR(probe_kv);
+  ACTQKV_OPTIONAL_SMALL(probe_norm, 4);
+  ACTQKV_REQUIRE_SMALL(scores, 4);
+  ACTQKV_REQUIRE_SMALL(idx, 4);
+  ACTQKV_REQUIRE_SMALL(n_sel, 4);
+  if ((budget_remaining == nullptr) != (theta_rest_sum == nullptr))
+    return set_error(ACTQKV_EINVAL, "budget_remaining and theta_rest_sum must be given together");
+  ACTQKV_OPTIONAL_SMALL(budget_remaining, 4);
+  ACTQKV_OPTIONAL_SMALL(theta_rest_sum, 4);
+  ACTQKV_OPTIONAL_SMALL(theta, 4);
+  ACTQKV_OPTIONAL_SMALL(budget, 4);
+  if (score_stride < nb_capacity)
+    return set_error(ACTQKV_EINVAL, "score_stride %lld < nb_capacity %d", (long long)score_stride,
+                     nb_capacity);
+  const int64_t per_seq = int64_t(nb_capacity) * shape->n_kv_heads * shape->block_size * shape->head_dim;
+  const int64_t rep_per_seq = int64_t(nb_capacity) * shape->n_rep * shape->n_kv_heads * shape->head_dim;
+  if (batch > 1 && update && cache_seq_stride < per_seq)
+    return set_error(ACTQKV_EINVAL, "cache_seq_stride %lld < one sequence's cache %lld",
+                     (long long)cache_seq_stride, (long long)per_seq);
+  if (batch > 1 && rep_seq_stride < rep_per_seq)
+    return set_error(ACTQKV_EINVAL, "rep_seq_stride %lld < one sequence's representative keys %lld",
+                     (long long)rep_seq_stride, (long long)rep_per_seq);
+  if (cache_seq_stride % 8 != 0 || rep_seq_stride % 8 != 0)
+    return set_error(ACTQKV_EALIGN, "sequence strides must be multiples of 8 elements");
+  return launch_decode_retrieve(*shape, batch, q_tok, k_new, v_new, pos0, k_cache, v_cache, cache_seq_stride,
+                                rep_keys, rep_seq_stride, nb_capacity, nb_begin, nb_end, probe, probe_kv,
+                                probe_norm, scores, score_stride, k_cap, flags, budget_remaining,
+                                theta_rest_sum, idx, n_sel, theta, budget, static_cast<hipStream_t>(stream));
+}
+
 int actqkv_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_prior,
                             const float* theta_prev, float* theta_sum, float* n_steps,
                             float* budget_remaining, float* theta_rest_sum, void* stream) {

@@ -91,6 +91,15 @@ int launch_append(const actqkv_shape& sh, int batch, int m, const void* k_new, c
                   void* rep_keys, int64_t rep_stride, int nb_capacity, const void* q_tok, float* probe,
                   float* probe_kv, float* probe_norm, hipStream_t stream);   // q_tok: fused one-token probe, or NULL
 
+int launch_decode_retrieve(const actqkv_shape& sh, int batch, const void* q_tok, const void* k_new,
+                           const void* v_new, const int32_t* pos0, void* k_cache, void* v_cache,
+                           int64_t cache_stride, void* rep_keys, int64_t rep_stride, int nb_capacity,
+                           int nb_begin, const int32_t* nb_end, float* probe, float* probe_kv,
+                           float* probe_norm, float* scores, int64_t score_stride, int k_cap, int flags,
+                           float* budget_remaining, const float* theta_rest_sum, int32_t* idx,
+                           int32_t* n_sel, float* theta, float* budget,
+                           hipStream_t stream);   // k_new NULL: no cache update
+
 int launch_gather(const actqkv_shape& sh, int batch, const void* k_store, const void* v_store,
                   int64_t store_stride, int nb_store, const int32_t* idx, const int32_t* n_sel, int k_cap,
                   void* k_cache, void* v_cache, int64_t cache_stride, int slot0, int32_t* idx_slots,

@@ -7,10 +7,9 @@
 // wavefront keeps four keys in flight.  The group-summed probe sits in LDS.
 #include "common.h"
 #include "launch.h"
+#include "score_body.h"
 
 namespace actqkv {
-
-constexpr int kScoreBatch = 8;  // 16-byte loads a lane keeps in flight
 
 template <typename T>
 __global__ __launch_bounds__(1024) void score_blocks_kernel(
@@ -18,55 +17,16 @@ __global__ __launch_bounds__(1024) void score_blocks_kernel(
     const T* __restrict__ rep_keys, int64_t seq_stride, int nb_capacity, int nb_begin,
     const int32_t* __restrict__ nb_end, float* __restrict__ scores, int64_t score_stride, int n_rep,
     int key_len, float inv_sqrt_g) {
-  constexpr int V = Vec<T>::N;
   extern __shared__ __attribute__((aligned(16))) float probe_lds[];  // [key_len]
   const int s = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int gq = lane >> 4, l16 = lane & 15;
-  const int chunks = key_len / V;
   const int end = min(nb_end[s], nb_capacity);
   const int b = nb_begin + blockIdx.x * int(blockDim.x >> 6) + wave;
   const bool live = b < end;
-  const T* block_keys = rep_keys + size_t(s) * seq_stride + size_t(live ? b : nb_begin) * n_rep * key_len;
-
-  // kScoreBatch chunks of key j, starting at chunk c0: all loads are issued before any is used
-  auto load_batch = [&](int j, int c0, float (&k)[kScoreBatch][V]) {
-    const T* key = block_keys + size_t(j < n_rep ? j : 0) * key_len;
-#pragma unroll
-    for (int i = 0; i < kScoreBatch; ++i) {
-      const int c = c0 + 16 * i;
-      Vec<T>::load(key + (c < chunks ? c : l16) * V, k[i]);
-    }
-  };
-  auto accumulate = [&](int j, int c0, const float (&k)[kScoreBatch][V], float& dot, float& nrm) {
-#pragma unroll
-    for (int i = 0; i < kScoreBatch; ++i) {
-      const int c = c0 + 16 * i;
-      if (c < chunks && j < n_rep) {
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-          dot += probe_lds[c * V + v] * k[i][v];
-          nrm += k[i][v] * k[i][v];
-        }
-      }
-    }
-  };
-  // cosine of the probe with key j repeated to the G query heads, summed over the 4 lane groups
-  auto finish_keys = [&](int j, float dot, float nrm, float pn) {
-#pragma unroll
-    for (int o = 8; o > 0; o >>= 1) {
-      dot += __shfl_xor(dot, o, 64);
-      nrm += __shfl_xor(nrm, o, 64);
-    }
-    float c = (j < n_rep && nrm > 0.f && pn > 0.f) ? dot * inv_sqrt_g / (pn * sqrtf(nrm)) : 0.f;
-    c += __shfl_xor(c, 16, 64);
-    c += __shfl_xor(c, 32, 64);
-    return c;
-  };
-
   // the first batch of key loads is in flight while the probe goes to LDS
-  float k0[kScoreBatch][V];
-  load_batch(gq, l16, k0);
+  BlockScorer<T> scorer;
+  scorer.start(rep_keys + size_t(s) * seq_stride + size_t(live ? b : nb_begin) * n_rep * key_len, n_rep,
+               key_len, lane);
   {
     const float* src = probe_kv + size_t(s) * key_len;
     for (int i = threadIdx.x * 4; i < key_len; i += int(blockDim.x) * 4)
@@ -74,29 +34,8 @@ __global__ __launch_bounds__(1024) void score_blocks_kernel(
   }
   __syncthreads();
   if (!live) return;
-  const float pn = probe_norm[s];
-  float total = 0.f;
-  {
-    float dot = 0.f, nrm = 0.f;
-    accumulate(gq, l16, k0, dot, nrm);
-    for (int c0 = l16 + 16 * kScoreBatch; c0 < chunks; c0 += 16 * kScoreBatch) {
-      float kk[kScoreBatch][V];
-      load_batch(gq, c0, kk);
-      accumulate(gq, c0, kk, dot, nrm);
-    }
-    total += finish_keys(gq, dot, nrm, pn);
-  }
-  for (int j0 = 4; j0 < n_rep; j0 += 4) {
-    const int j = j0 + gq;
-    float dot = 0.f, nrm = 0.f;
-    for (int c0 = l16; c0 < chunks; c0 += 16 * kScoreBatch) {
-      float kk[kScoreBatch][V];
-      load_batch(j, c0, kk);
-      accumulate(j, c0, kk, dot, nrm);
-    }
-    total += finish_keys(j, dot, nrm, pn);
-  }
-  if (lane == 0) scores[size_t(s) * score_stride + b] = total / float(n_rep);
+  const float total = scorer.finish(probe_lds, probe_norm[s], inv_sqrt_g);
+  if (lane == 0) scores[size_t(s) * score_stride + b] = total;
 }
 
 // The same score for every KV head on its own (the alternative to the head-merged reading):

@@ -108,6 +108,27 @@ class LayerRunner:
         B.retrieval_attention(cs, bt, m, q_win, k_cache, v_cache, cache_stride, self.nb_capacity, n_ctx,
                               self.idx, self.n_sel, self.k_cap, out, lse, self.workspace, stream)
 
+    def decode_step(self, q_tok: torch.Tensor, k_cache, v_cache, rep_keys, n_ctx: torch.Tensor,
+                    nb_end: torch.Tensor, nb_end_max: int, out: torch.Tensor,
+                    budget_remaining: Optional[torch.Tensor] = None,
+                    theta_rest_sum: Optional[torch.Tensor] = None, k_new=None, v_new=None, pos0=None,
+                    lse=None, stream=None) -> None:
+        """A decode step in two calls (three launches): (cache update,) probe, scores and selection
+        (actqkv_decode_retrieve), then the attention.  k_new, v_new, pos0: the new
+        token's key, value and position per sequence, or None if the cache already holds it."""
+        sh, cs, bt = self.shape, self.cs, self.batch
+        nb_begin = sh.n_init // sh.block_size
+        cache_stride = k_cache.stride(0) if k_cache.dim() == 5 else 0
+        rep_stride = rep_keys.stride(0) if rep_keys.dim() == 5 else 0
+        nb_cap = min(max(nb_end_max, nb_begin, 1), self.nb_capacity)
+        B.decode_retrieve(cs, bt, q_tok, k_new, v_new, pos0, k_cache, v_cache, cache_stride, rep_keys,
+                          rep_stride, nb_cap if k_new is None else self.nb_capacity, nb_begin, nb_end,
+                          self.probe, self.probe_kv, self.probe_norm, self.scores, self.score_stride,
+                          self.k_cap, budget_remaining, theta_rest_sum, self.idx, self.n_sel, self.theta,
+                          self.budget, stream)
+        B.retrieval_attention(cs, bt, 1, q_tok, k_cache, v_cache, cache_stride, self.nb_capacity, n_ctx,
+                              self.idx, self.n_sel, self.k_cap, out, lse, self.workspace, stream)
+
 
 @dataclass
 class PrefillPlan:

@@ -149,6 +149,22 @@ def test_append_kv_rejects(lib):
     assert call(batch=2, cs=8) == -1                       # stride smaller than one sequence's cache
 
 
+def test_decode_retrieve_rejects(lib):
+    cs = B.c_shape(LLAMA)
+    call = lambda **k: lib.actqkv_decode_retrieve(
+        ctypes.byref(cs), k.get("batch", 1), k.get("q", A16), k.get("kn", A16), k.get("vn", A16),
+        k.get("pos0", A16), k.get("kc", A16), A16, k.get("cs", 0), k.get("rep", A16), k.get("rs", 0),
+        k.get("cap", 64), 1, k.get("nb_end", A16), None, None, None, k.get("scores", A16), k.get("ss", 64),
+        k.get("k_cap", 32), k.get("flags", 0), k.get("bud"), k.get("rest"), k.get("idx", A16), A16, None, None, None)
+    assert call(q=None) == -1 and b"q_tok" in lib.actqkv_last_error() and call(q=A16 + 2) == -3
+    assert call(kn=None) == -1 and call(pos0=None) == -1 and call(kc=None) == -1     # a partial cache update
+    assert call(rep=None) == -1 and call(nb_end=None) == -1 and call(scores=None) == -1 and call(idx=None) == -1
+    assert call(cap=0) == -1 and call(cap=9000, ss=9000) == -2 and call(ss=10) == -1
+    assert call(k_cap=0) == -2 and call(k_cap=65) == -2 and call(flags=2) == -1
+    assert call(bud=A16) == -1 and call(bud=A16 + 2, rest=A16) == -3
+    assert call(batch=2, cs=8) == -1 and call(batch=2, cs=1 << 40, rs=8) == -1 and call(cs=12) == -3
+
+
 def test_cutoff_next_step_rejects(lib):
     f = ctypes.c_float
     call = lambda batch=2, L=32, k=8.0, prior=6.0, prev=A16, ts=A16, ns=A16, b=A16, r=A16: \

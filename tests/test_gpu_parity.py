@@ -361,7 +361,9 @@ def test_scores_zero_norms_and_determinism():
     ("bf16", 32, 8, [2900, 2817, 1100, 700, 3000, 129, 2048, 1]),  # 64 pairs: one workgroup per pair
     ("bf16", 28, 4, [2900, 1100, 129]),                       # 7 query heads per KV head
 ])
-def test_decode_step_batch(dtype, hq, hkv, n_ctxs):
+@pytest.mark.parametrize("one_launch", [False, True])
+def test_decode_step_batch(dtype, hq, hkv, n_ctxs, one_launch):
+    """one_launch: probe, scores and selection through actqkv_decode_retrieve (the probe formed inside the scoring launch) instead of three calls."""
     sh = LayerShape(hq, hkv, 128 if dtype == "bf16" else 64, 128, 4, 128, 256, dtype)
     w = synth.Workload("decode_small", sh, 3000, 1, 6, True, 2024, n_planted=4, batch=len(n_ctxs))
     nb_cap = 24
@@ -383,9 +385,13 @@ def test_decode_step_batch(dtype, hq, hkv, n_ctxs):
     bud = torch.tensor([c[0] for c in cuts], dtype=torch.float32, device=DEV)
     rest = torch.tensor([c[1] for c in cuts], dtype=torch.float32, device=DEV)
     out = torch.zeros_like(qd)
-    runner.step(qd, kc, vc, repd, torch.tensor(n_ctxs, dtype=torch.int32, device=DEV),
-                torch.tensor(nb_ends, dtype=torch.int32, device=DEV), max(nb_ends), out, bud, rest,
-                update_stats=False, m=1)
+    if one_launch:
+        runner.decode_step(qd, kc, vc, repd, torch.tensor(n_ctxs, dtype=torch.int32, device=DEV),
+                           torch.tensor(nb_ends, dtype=torch.int32, device=DEV), max(nb_ends), out, bud, rest)
+    else:
+        runner.step(qd, kc, vc, repd, torch.tensor(n_ctxs, dtype=torch.int32, device=DEV),
+                    torch.tensor(nb_ends, dtype=torch.int32, device=DEV), max(nb_ends), out, bud, rest,
+                    update_stats=False, m=1)
     torch.cuda.synchronize()
     for s, n in enumerate(n_ctxs):
         res = orc.decode_step(f64(qs[s]), f64(ks[s]), f64(vs[s]), f64(reps[s]), n, sh.n_init, sh.n_local,
@@ -441,11 +447,17 @@ def test_decode_full_size_layer_as_benchmarked():
         bud = torch.full((bt,), cut[0], dtype=torch.float32, device=DEV)
         rest = torch.full((bt,), cut[1], dtype=torch.float32, device=DEV)
         out = torch.zeros_like(q)
-        B.append_kv(cs, bt, 1, k_new, v_new, pos0, kc, vc, kc.stride(0), rep, rep.stride(0), nb_cap)
-        runner.step(q, kc, vc, rep, n_ctx, nb_end, nb_end_h, out, bud, rest, update_stats=False, m=1)
+        if rep_run == 0:      # five launches: update, probe, scores, selection, attention
+            B.append_kv(cs, bt, 1, k_new, v_new, pos0, kc, vc, kc.stride(0), rep, rep.stride(0), nb_cap)
+            runner.step(q, kc, vc, rep, n_ctx, nb_end, nb_end_h, out, bud, rest, update_stats=False, m=1)
+        else:                 # three launches, as benchmarked
+            runner.decode_step(q, kc, vc, rep, n_ctx, nb_end, nb_end_h, out, bud, rest, k_new, v_new, pos0)
         torch.cuda.synchronize()
-        outs.append(out)
-    assert torch.equal(outs[0], outs[1]) and bool(torch.isfinite(outs[0].float()).all())
+        outs.append((out, runner.idx.clone(), runner.n_sel.clone(), runner.theta.clone(), bud))
+    for i, (a, b) in enumerate(zip(*outs)):         # output, idx, n_sel bit for bit; density and budget to fp32 rounding
+        assert torch.equal(a, b) if i < 3 else torch.allclose(a, b, rtol=1e-5)
+    outs = [o[0] for o in outs]
+    assert bool(torch.isfinite(outs[0].float()).all())
     for s in (0, 7, 15):
         k_log, v_log = _logical_from_blocked(kc[s].cpu(), vc[s].cpu(), n0 + 1)
         assert torch.equal(k_log[n0], k_new[s, 0].cpu()) and torch.equal(v_log[n0], v_new[s, 0].cpu())
@@ -585,6 +597,76 @@ def test_append_and_probe_in_one_launch(dtype, hq, hkv, d):
         assert torch.equal(a, b)
     assert not torch.equal(res[1][2][1, 2], rep0[1, 2])                     # the representatives of block 2 were written
     assert torch.equal(res[1][3], q.float().reshape(bt, -1))                # the probe is the query
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d", [("bf16", 32, 8, 128), ("fp32", 6, 2, 64)])
+@pytest.mark.parametrize("update", [True, False])
+def test_decode_retrieve_equals_the_four_calls(dtype, hq, hkv, d, update):
+    """actqkv_decode_retrieve = actqkv_append_kv (m = 1) + actqkv_build_probe (m = 1) +
+    actqkv_score_blocks + actqkv_select: caches, representatives, probe and selection bit for
+    bit, norm and scores up to the order of one fp32 sum.  Ragged lengths (many scoring
+    workgroups per sequence, one sequence with no eligible block, one whose token completes a
+    block), the cut-off on, three steps in a row."""
+    sh = LayerShape(hq, hkv, d, 128, 4, 128, 256, dtype)
+    cs = B.c_shape(sh)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    pos = [9000, 5000, 300, 8831]                       # 8831 completes block 68
+    bt, nb, k_cap = len(pos), 72, 12
+    nb_begin = 1
+    ends = [H.eligible_range(sh, p)[1] for p in pos]
+    assert max(ends) - nb_begin > 48 and min(ends) <= nb_begin
+    g = torch.Generator().manual_seed(11 + d)
+    kc0 = torch.randn(bt, nb, hkv, 128, d, generator=g).to(td).to(DEV)
+    vc0 = torch.randn(bt, nb, hkv, d, 128, generator=g).to(td).to(DEV)
+    rep0 = torch.randn(bt, nb, 4, hkv, d, generator=g).to(td).to(DEV)
+    pos0 = torch.tensor(pos, dtype=torch.int32, device=DEV)
+    nb_end = torch.tensor(ends, dtype=torch.int32, device=DEV)
+    stride = nb
+    steps = []
+    for t in range(3):
+        steps.append([torch.randn(bt, hq, d, generator=g).to(td).to(DEV),
+                      torch.randn(bt, 1, hkv, d, generator=g).to(td).to(DEV),
+                      torch.randn(bt, 1, hkv, d, generator=g).to(td).to(DEV)])
+    res = []
+    for one_call in (False, True):
+        kc, vc, rep = kc0.clone(), vc0.clone(), rep0.clone()
+        ws = torch.zeros(B.workspace_bytes(cs, bt, 1, nb, k_cap), dtype=torch.uint8, device=DEV)
+        bud = torch.full((bt,), 40.0, device=DEV)
+        got = []
+        for q, kn, vn in steps:
+            probe = torch.zeros(bt, hq * d, device=DEV); pkv = torch.zeros(bt, hkv * d, device=DEV)
+            pn = torch.zeros(bt, device=DEV)
+            scores = torch.zeros(bt, stride, device=DEV)
+            idx = torch.zeros(bt, k_cap, dtype=torch.int32, device=DEV)
+            n_sel = torch.zeros(bt, dtype=torch.int32, device=DEV)
+            theta = torch.zeros(bt, device=DEV); b_l = torch.zeros(bt, device=DEV)
+            rest = torch.full((bt,), 9.0, device=DEV)
+            if one_call:
+                B.decode_retrieve(cs, bt, q, kn if update else None, vn if update else None,
+                                  pos0 if update else None, kc, vc, kc.stride(0), rep, rep.stride(0), nb,
+                                  nb_begin, nb_end, probe, pkv, pn, scores, stride, k_cap, bud, rest, idx,
+                                  n_sel, theta, b_l)
+            else:
+                if update:
+                    B.append_kv(cs, bt, 1, kn, vn, pos0, kc, vc, kc.stride(0), rep, rep.stride(0), nb)
+                B.build_probe(cs, bt, 1, q, None, False, probe, pkv, pn, None, ws)
+                B.score_blocks(cs, bt, pkv, pn, rep, rep.stride(0), nb, nb_begin, nb_end, scores, stride)
+                B.select(bt, scores, stride, nb, nb_begin, nb_end, k_cap, bud, rest, idx, n_sel, theta, b_l)
+            torch.cuda.synchronize()
+            for s_, e in enumerate(ends):
+                scores[s_, max(e, 0):] = 0
+            got += [probe, pkv, idx, n_sel, pn, scores, theta, b_l, bud.clone()]
+        res.append(got + [kc, vc, rep])
+    names = ["probe", "probe_kv", "idx", "n_sel", "probe_norm", "scores", "theta", "budget", "budget_remaining"]
+    for i, (a, b) in enumerate(zip(*res)):
+        if i >= 27 or i % 9 < 4:
+            assert torch.equal(a, b), names[i % 9] if i < 27 else "cache"
+        else:
+            assert torch.allclose(a, b, rtol=2e-6, atol=1e-7), names[i % 9]
+    n_sel = res[1][3].cpu().tolist()
+    assert n_sel[2] == 0 and min(n_sel[0], n_sel[1], n_sel[3]) >= 1
+    if update:
+        assert not torch.equal(res[1][-1][3, 68], rep0[3, 68])            # representatives of the completed block
 
 
 def test_append_kv_drops_tokens_behind_the_capacity():
