@@ -23,6 +23,10 @@ namespace actqkv {
 
 constexpr int kDcD = 128;
 constexpr int kDcMaxWaves = 8;   // 512 threads: the register budget stays at 256 per lane
+#ifndef ACTQKV_DC_ITEM_KEYS
+#define ACTQKV_DC_ITEM_KEYS 64
+#endif
+constexpr int kDcItemKeys = ACTQKV_DC_ITEM_KEYS;   // keys per work item: 64 or 128
 
 struct DcParams {
   const uint16_t* q;
@@ -83,21 +87,28 @@ __global__ __launch_bounds__(kDcMaxWaves * 64) void attn_decode_kernel(DcParams 
   const uint16_t* kc = p.k_cache + size_t(s) * p.seq_stride;
   const uint16_t* vc = p.v_cache + size_t(s) * p.seq_stride;
 
-  for (int t = wg * n_waves + wave; t < n_tiles; t += p.n_wg * n_waves) {
+  // Work items are spans of kDcItemKeys keys of a tile; item i of the list goes to wavefront i mod (all
+  // wavefronts of the pair).  Keys AND values of an item are requested before anything is computed.
+  constexpr int kSteps = kDcItemKeys / 32, kPerTile = kBlock / kDcItemKeys;
+  const int n_items = n_tiles * kPerTile;
+  for (int it = wg * n_waves + wave; it < n_items; it += p.n_wg * n_waves) {
     int block, lo, hi;
-    tl.get(t, block, lo, hi);
+    tl.get(it / kPerTile, block, lo, hi);
+    const int part = it % kPerTile;
+    const int kpos0 = block * kBlock + part * kDcItemKeys;
+    lo = max(lo, kpos0);
+    hi = min(hi, kpos0 + kDcItemKeys);
     if (hi <= lo) continue;                      // wave-uniform
-    const uint16_t* kt = kc + (size_t(block) * p.n_kv_heads + hk) * tile_elems;
-    const uint16_t* vt = vc + (size_t(block) * p.n_kv_heads + hk) * tile_elems;
-    const int kpos0 = block * kBlock;
+    const uint16_t* kt = kc + (size_t(block) * p.n_kv_heads + hk) * tile_elems + size_t(part) * kDcItemKeys * kDcD;
+    const uint16_t* vt = vc + (size_t(block) * p.n_kv_heads + hk) * tile_elems + part * kDcItemKeys;
 
     // A operands of S^T: MFMA row r of sub-tile h of 32-key step st is key 32*st + 8*(r/4) + 4*h + r%4,
     // so that lane quarter kq ends up with keys 32*st + 8*kq + 4*h + i in register i.
-    u32x4 ka[32];
+    u32x4 ka[8 * kSteps];
     {
       const uint16_t* base = kt + size_t(8 * (n >> 2) + (n & 3)) * kDcD + 8 * kq;
 #pragma unroll
-      for (int st = 0; st < 4; ++st)
+      for (int st = 0; st < kSteps; ++st)
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -105,30 +116,29 @@ __global__ __launch_bounds__(kDcMaxWaves * 64) void attn_decode_kernel(DcParams 
             ka[(st * 2 + h) * 4 + ks] =
                 *reinterpret_cast<const u32x4*>(base + size_t(32 * st + 4 * h) * kDcD + ks * 32);
     }
-    __builtin_amdgcn_sched_barrier(0);   // all 32 key loads are in flight before the first MFMA
-    f32x4 sc[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) sc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)       // the 8 sub-tiles take turns: no MFMA waits for the one before it
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        sc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dc_as_bf16x8(ka[j * 4 + ks]), qb[ks], sc[j], 0, 0, 0);
     // V^T A operands: lane (row = channel within a group of 16, kq) reads keys 32*st + 8*kq .. +7
-    u32x4 va[32];
+    u32x4 va[8 * kSteps];
     {
       const uint16_t* base = vt + size_t(n) * kBlock + 8 * kq;
 #pragma unroll
       for (int dg = 0; dg < 8; ++dg)
 #pragma unroll
-        for (int st = 0; st < 4; ++st)
-          va[dg * 4 + st] = *reinterpret_cast<const u32x4*>(base + size_t(16 * dg) * kBlock + 32 * st);
+        for (int st = 0; st < kSteps; ++st)
+          va[dg * kSteps + st] = *reinterpret_cast<const u32x4*>(base + size_t(16 * dg) * kBlock + 32 * st);
     }
-    __builtin_amdgcn_sched_barrier(0);   // all 32 value loads are in flight during the softmax
+    __builtin_amdgcn_sched_barrier(0);   // all key and value loads are in flight before the first MFMA
+    f32x4 sc[2 * kSteps];
+#pragma unroll
+    for (int j = 0; j < 2 * kSteps; ++j) sc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)       // the sub-tiles take turns: no MFMA waits for the one before it
+#pragma unroll
+      for (int j = 0; j < 2 * kSteps; ++j)
+        sc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dc_as_bf16x8(ka[j * 4 + ks]), qb[ks], sc[j], 0, 0, 0);
     // mask and online softmax: sc[2*st + h][i] is key kpos0 + 32*st + 8*kq + 4*h + i
     float mx = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < 2 * kSteps; ++j)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int kp = kpos0 + 32 * (j >> 1) + 8 * kq + 4 * (j & 1) + i;
@@ -138,12 +148,12 @@ __global__ __launch_bounds__(kDcMaxWaves * 64) void attn_decode_kernel(DcParams 
       }
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx * p.scale_log2e);   // finite: the tile has a visible key
+    const float m_new = fmaxf(m_run, mx * p.scale_log2e);   // finite: the item has a visible key
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     m_run = m_new;
     float psum = 0.f;
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < 2 * kSteps; ++j)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const float pv = __builtin_amdgcn_exp2f(sc[j][i] * p.scale_log2e - m_new);
@@ -158,13 +168,13 @@ __global__ __launch_bounds__(kDcMaxWaves * 64) void attn_decode_kernel(DcParams 
     // O^T += V^T P^T
     typedef __attribute__((ext_vector_type(8))) float f32x8;
 #pragma unroll
-    for (int st = 0; st < 4; ++st) {
+    for (int st = 0; st < kSteps; ++st) {
       f32x8 pf = {sc[2 * st][0], sc[2 * st][1], sc[2 * st][2], sc[2 * st][3],
                   sc[2 * st + 1][0], sc[2 * st + 1][1], sc[2 * st + 1][2], sc[2 * st + 1][3]};
       const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
 #pragma unroll
       for (int dg = 0; dg < 8; ++dg)
-        acc_o[dg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dc_as_bf16x8(va[dg * 4 + st]), pb, acc_o[dg], 0, 0, 0);
+        acc_o[dg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dc_as_bf16x8(va[dg * kSteps + st]), pb, acc_o[dg], 0, 0, 0);
     }
   }
 

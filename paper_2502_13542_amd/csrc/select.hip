@@ -98,9 +98,17 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
   __shared__ int e_shared;
   const int s = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* sc_mem = scores + size_t(s) * score_stride + nb_begin;
+  // The scores of the first 1024 blocks stay in registers for all three passes; their load does
+  // not wait for nb_end (the row has nb_capacity entries whatever nb_end says).
+  const float sc_first = tid < nb_capacity - nb_begin ? sc_mem[tid] : 0.f;
   int end = min(nb_end[s], nb_capacity);
   const int n = max(end - nb_begin, 0);
-  const float* sc = scores + size_t(s) * score_stride + nb_begin;
+  struct {
+    const float* mem;
+    float first;
+    __device__ __forceinline__ float operator[](int i) const { return i < kSelectThreads ? first : mem[i]; }
+  } sc{sc_mem, sc_first};                        // indexed with i = tid + c * 1024 only
   int32_t* my_idx = idx + size_t(s) * k_cap;
   if (n == 0) {
     if (tid < k_cap) my_idx[tid] = -1;
