@@ -442,6 +442,8 @@ def bench_decode(args, torch, B, H, synth):
     theta_step = torch.zeros(L, bt, dtype=torch.float32, device=dev)
     rest_all = torch.zeros(L, bt, dtype=torch.float32, device=dev)
     budget = torch.zeros(bt, dtype=torch.float32, device=dev)
+    # the launch that selects inside the attention reads B_kv from one array and writes the rest to another
+    budgets = [budget, torch.zeros(bt, dtype=torch.float32, device=dev)]
     nsel_log = torch.zeros(L, bt, dtype=torch.int32, device=dev)
     q_step = torch.zeros(L, bt, 1, sh.n_q_heads, D, dtype=torch.bfloat16, device=dev)
     step_no = torch.zeros(1, dtype=torch.int64, device=dev)
@@ -465,6 +467,22 @@ def bench_decode(args, torch, B, H, synth):
         # folds the step before into the history; B_kv = L * k again; R^l for every layer
         B.cutoff_next_step(bt, L, k_mean, theta_prior, theta_step, theta_sum, hist_steps, budget, rest_all)
         for l in range(L):
+            if args.decode_launches == 2:
+                # cache update, probe and scores in one launch, selection and attention in the other
+                B.decode_retrieve(runner.cs, bt, q_step[l], k_step[l], v_step[l], pos_cur, kc[l], vc[l],
+                                  cache_stride, rep[l], rep_stride, nb_cap, nb_begin, nb_end_cur, None, None,
+                                  None, runner.scores, runner.score_stride, w.k_cap, None, None, None, None,
+                                  None, None, None, flags=B.DECODE_SCORES_ONLY)
+                if events is not None:
+                    events[l][0].record()
+                B.decode_select_attention(runner.cs, bt, q_step[l], kc[l], vc[l], cache_stride, nb_cap,
+                                          n_ctx_cur, runner.scores, runner.score_stride, nb_begin, nb_end_cur,
+                                          w.k_cap, budgets[l % 2], rest_all[l], budgets[(l + 1) % 2],
+                                          runner.idx, nsel_log[l], theta_step[l], None, out[l], None,
+                                          runner.workspace)
+                if events is not None:
+                    events[l][1].record()
+                continue
             if args.decode_launches == 3:
                 # cache update, probe and scores in one launch, then the selection
                 B.decode_retrieve(runner.cs, bt, q_step[l], k_step[l], v_step[l], pos_cur, kc[l], vc[l],
@@ -542,7 +560,9 @@ def bench_decode(args, torch, B, H, synth):
         "hbm_frac_of_step": (byt + score_bytes) / (mean_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBS, **traffic_fields(w.name),
-                     "kernel": "actqkv_retrieval_attention launch, m = 1 (attn_decode_kernel)",
+                     "kernel": ("actqkv_decode_select_attention launch (attn_decode_select_kernel: selection + attention)"
+                                if args.decode_launches == 2 else
+                                "actqkv_retrieval_attention launch, m = 1 (attn_decode_kernel)"),
                      "avg_launch_us": attn_ms * 1e3 / L, "algorithmic_mb_per_launch": byt / L / 1e6,
                      "timing": "HIP events around every attention launch of one eager step"},
     }
@@ -561,9 +581,10 @@ def main() -> int:
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--decode-layers", type=int, default=0, help="override the layer count (testing)")
-    ap.add_argument("--decode-launches", type=int, default=3, choices=(3, 4),
-                    help="launches per layer of a decode step: 3 = (cache update + probe + scores), selection, "
-                         "attention; 4 = (cache update + probe), scores, selection, attention")
+    ap.add_argument("--decode-launches", type=int, default=2, choices=(2, 3, 4),
+                    help="launches per layer of a decode step: 2 = (cache update + probe + scores), (selection + "
+                         "attention); 3 = (cache update + probe + scores), selection, attention; "
+                         "4 = (cache update + probe), scores, selection, attention")
     ap.add_argument("--no-overlap", action="store_true",
                     help="prefill: one stream, strictly in window order")
     ap.add_argument("--chunk", type=int, default=32,

@@ -50,7 +50,7 @@
 extern "C" {
 #endif
 
-#define ACTQKV_VERSION 102
+#define ACTQKV_VERSION 103
 
 enum {
   ACTQKV_OK = 0,
@@ -70,9 +70,11 @@ enum {
   ACTQKV_PROBE_WINDOW_CHAIN = 4   /* the batch entries are consecutive windows of ONE sequence */
 };
 
-/* Bits of the flags argument of actqkv_select. */
+/* Bits of the flags argument of actqkv_select and of the decode-step calls. */
 enum {
-  ACTQKV_SELECT_ENTROPY_TOPK = 1  /* density over the k_cap best blocks only (see actqkv_select) */
+  ACTQKV_SELECT_ENTROPY_TOPK = 1, /* density over the k_cap best blocks only (see actqkv_select) */
+  ACTQKV_DECODE_SCORES_ONLY = 2   /* actqkv_decode_retrieve stops after the scores (the caller selects,
+                                     for instance inside actqkv_decode_select_attention) */
 };
 
 /* Limits checked by every call (ACTQKV_ESHAPE otherwise):
@@ -297,7 +299,8 @@ int actqkv_append_kv_probe(const actqkv_shape* shape, int batch, const void* q_t
  *   nb_begin, nb_end, scores, score_stride  as in actqkv_score_blocks.
  *   probe, probe_kv, probe_norm  optional outputs (NULL: not written) as in actqkv_build_probe.
  *   k_cap, flags, budget_remaining, theta_rest_sum, idx, n_sel, theta, budget
- *            as in actqkv_select.
+ *            as in actqkv_select; with flags & ACTQKV_DECODE_SCORES_ONLY the call ends after its
+ *            first launch and none of these but k_cap is used (idx, n_sel may be NULL).
  * Errors: as in the four calls. */
 int actqkv_decode_retrieve(const actqkv_shape* shape, int batch, const void* q_tok, const void* k_new,
                            const void* v_new, const int32_t* pos0, void* k_cache, void* v_cache,
@@ -307,6 +310,35 @@ int actqkv_decode_retrieve(const actqkv_shape* shape, int batch, const void* q_t
                            int k_cap, int flags, float* budget_remaining,
                            const float* theta_rest_sum, int32_t* idx, int32_t* n_sel, float* theta,
                            float* budget, void* stream);
+
+/* The selection and the attention of a decode step in ONE launch (actqkv_select followed by
+ * actqkv_retrieval_attention with m = 1; Sec. 4.2, Eq. (11), Eq. (12), Alg. 1; Sec. 3.1, Eq. (3)).
+ * The selection step is all latency, and an attention workgroup has that much time to spare
+ * while its first keys and values are on their way: every workgroup repeats its sequence's
+ * selection (identical in all of them) and then attends over what it selected.
+ * Supported for bf16 storage, head_dim 128 and at most 8 query heads per KV head
+ * (ACTQKV_ESHAPE otherwise: make the two calls).
+ *   q [batch][1][H][D]; k_cache, v_cache, seq_stride, nb_capacity, n_ctx, out, lse, workspace
+ *            as in actqkv_retrieval_attention with m = 1.
+ *   scores, score_stride, nb_begin, nb_end, k_cap, flags  as in actqkv_select; the scores of
+ *            blocks nb_begin .. min(nb_end[s], nb_capacity) - 1 are read.
+ *   budget_in, theta_rest_sum  the cut-off state as actqkv_select reads it (both NULL: the k_cap
+ *            best blocks); budget_after receives B_kv - B^l and must NOT be the array
+ *            budget_in points to: all workgroups of a sequence read budget_in while one of
+ *            them writes budget_after (NULL: not written).
+ *   idx, n_sel (required), theta, budget (optional)  outputs as of actqkv_select.
+ * Results: the selection is that of actqkv_select (the density up to the order of an fp32
+ * sum, since 512 instead of 1024 threads add it up); the output is that of
+ * actqkv_retrieval_attention up to fp32 summation order (the key spans are merged in another
+ * order). */
+int actqkv_decode_select_attention(const actqkv_shape* shape, int batch, const void* q,
+                                   const void* k_cache, const void* v_cache, int64_t seq_stride,
+                                   int nb_capacity, const int32_t* n_ctx, const float* scores,
+                                   int64_t score_stride, int nb_begin, const int32_t* nb_end,
+                                   int k_cap, int flags, const float* budget_in,
+                                   const float* theta_rest_sum, float* budget_after, int32_t* idx,
+                                   int32_t* n_sel, float* theta, float* budget, void* out,
+                                   float* lse, void* workspace, size_t ws_bytes, void* stream);
 
 /* Selected blocks from a block store into a working cache (Sec. 3.1: the cache may be kept
  * in CPU memory).

@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libactqkv.so")
 
 ACTQKV_F32, ACTQKV_BF16 = 0, 1
 STATS_UPDATE, PROBE_MEAN_POOLING, PROBE_WINDOW_CHAIN = 1, 2, 4   # bits of build_probe's update_stats
-SELECT_ENTROPY_TOPK = 1                                           # bit of select's flags
+SELECT_ENTROPY_TOPK = 1                                          # bit of select's flags
+DECODE_SCORES_ONLY = 2                                           # bit of decode_retrieve's flags
 ERROR_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EALIGN", -4: "EWORKSPACE", -5: "EHIP"}
 
 
@@ -64,6 +65,8 @@ SIGNATURES = {
     "actqkv_append_kv_probe": (_i, [_shp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _vp, _vp, _vp, _vp]),
     "actqkv_decode_retrieve": (_i, [_shp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _i, _vp, _vp, _vp,
                                     _vp, _vp, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "actqkv_decode_select_attention": (_i, [_shp, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _i64, _i, _vp, _i, _i,
+                                            _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "actqkv_copy_bytes": (_i, [_vp, _vp, _sz, _vp]),
     "actqkv_gather_blocks": (_i, [_shp, _i, _vp, _vp, _i64, _i, _vp, _vp, _i, _vp, _vp, _i64, _i, _i, _vp, _vp]),
     "actqkv_last_error": (ctypes.c_char_p, []),
@@ -177,6 +180,21 @@ def decode_retrieve(shape: CShape, batch: int, q_tok, k_new, v_new, pos0, k_cach
         nb_capacity, nb_begin, _ptr(nb_end, i32), _ptr(probe, f), _ptr(probe_kv, f), _ptr(probe_norm, f),
         _ptr(scores, f), score_stride, k_cap, int(flags), _ptr(budget_remaining, f), _ptr(theta_rest_sum, f),
         _ptr(idx, i32), _ptr(n_sel, i32), _ptr(theta, f), _ptr(budget, f), _stream(stream)))
+
+
+def decode_select_attention(shape: CShape, batch: int, q, k_cache, v_cache, seq_stride: int, nb_capacity: int,
+                            n_ctx, scores, score_stride: int, nb_begin: int, nb_end, k_cap: int, budget_in,
+                            theta_rest_sum, budget_after, idx, n_sel, theta, budget, out, lse, workspace,
+                            stream=None, flags: int = 0) -> None:
+    """Selection and attention of a decode step in one launch; see the header."""
+    st = torch.bfloat16
+    f, i32 = torch.float32, torch.int32
+    _check(load_library().actqkv_decode_select_attention(
+        ctypes.byref(shape), batch, _ptr(q, st), _ptr(k_cache, st), _ptr(v_cache, st), seq_stride, nb_capacity,
+        _ptr(n_ctx, i32), _ptr(scores, f), score_stride, nb_begin, _ptr(nb_end, i32), k_cap, int(flags),
+        _ptr(budget_in, f), _ptr(theta_rest_sum, f), _ptr(budget_after, f), _ptr(idx, i32), _ptr(n_sel, i32),
+        _ptr(theta, f), _ptr(budget, f), _ptr(out, st), _ptr(lse, f), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def cutoff_next_step(batch: int, n_layers: int, k_mean: float, theta_prior: float, theta_prev,

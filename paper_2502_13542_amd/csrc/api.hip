@@ -143,6 +143,14 @@ int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* 
                                  int k_cap, void* out, float* lse, float* scratch,
                                  unsigned int* counters, float scale, int sel_per_head, hipStream_t stream);
 
+int launch_attention_decode_select(const actqkv_shape& sh, int batch, const void* q, const void* k_cache,
+                                   const void* v_cache, int64_t seq_stride, int nb_capacity,
+                                   const int32_t* n_ctx, const float* scores, int64_t score_stride, int nb_begin,
+                                   const int32_t* nb_end, int k_cap, int flags, const float* budget_in,
+                                   const float* theta_rest_sum, float* budget_after, int32_t* idx,
+                                   int32_t* n_sel, float* theta, float* budget, void* out, float* lse,
+                                   float* scratch, unsigned int* counters, float scale, hipStream_t stream);
+
 size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap) {
   (void)nb_capacity;
   size_t probe = probe_call_floats(sh, batch, m) * sizeof(float);
@@ -342,6 +350,66 @@ int actqkv_retrieval_attention_per_head(const actqkv_shape* shape, int batch, in
                            k_cap, out, lse, workspace, ws_bytes, 1, stream);
 }
 
+int actqkv_decode_select_attention(const actqkv_shape* shape, int batch, const void* q,
+                                   const void* k_cache, const void* v_cache, int64_t seq_stride,
+                                   int nb_capacity, const int32_t* n_ctx, const float* scores,
+                                   int64_t score_stride, int nb_begin, const int32_t* nb_end,
+                                   int k_cap, int flags, const float* budget_in,
+                                   const float* theta_rest_sum, float* budget_after, int32_t* idx,
+                                   int32_t* n_sel, float* theta, float* budget, void* out,
+                                   float* lse, void* workspace, size_t ws_bytes, void* stream) {
+  ACTQKV_TRY(check_shape(shape));
+  ACTQKV_TRY(check_batch(batch));
+  if (!decode_mfma_supported(*shape, 1))
+    return set_error(ACTQKV_ESHAPE, "decode_select_attention: bf16, head_dim 128 and at most 8 query heads per KV head");
+  if (flags & ~ACTQKV_SELECT_ENTROPY_TOPK)
+    return set_error(ACTQKV_EINVAL, "decode_select_attention: unknown flag bits: %d", flags);
+  if (nb_capacity < 1) return set_error(ACTQKV_EINVAL, "nb_capacity %d < 1", nb_capacity);
+  if (int64_t(nb_capacity) * shape->block_size > (int64_t(1) << 30))
+    return set_error(ACTQKV_ESHAPE, "cache of %d blocks exceeds 2^30 tokens", nb_capacity);
+  ACTQKV_TRY(check_blocks(nb_capacity, nb_begin, k_cap, true));
+  ACTQKV_REQUIRE_PTR(q);
+  ACTQKV_REQUIRE_PTR(k_cache);
+  ACTQKV_REQUIRE_PTR(v_cache);
+  ACTQKV_REQUIRE_SMALL(n_ctx, 4);
+  ACTQKV_REQUIRE_SMALL(scores, 4);
+  ACTQKV_REQUIRE_SMALL(nb_end, 4);
+  ACTQKV_REQUIRE_SMALL(idx, 4);
+  ACTQKV_REQUIRE_SMALL(n_sel, 4);
+  ACTQKV_REQUIRE_PTR(out);
+  ACTQKV_OPTIONAL_SMALL(lse, 4);
+  if ((budget_in == nullptr) != (theta_rest_sum == nullptr))
+    return set_error(ACTQKV_EINVAL, "budget_in and theta_rest_sum must be given together");
+  ACTQKV_OPTIONAL_SMALL(budget_in, 4);
+  ACTQKV_OPTIONAL_SMALL(theta_rest_sum, 4);
+  ACTQKV_OPTIONAL_SMALL(budget_after, 4);
+  ACTQKV_OPTIONAL_SMALL(theta, 4);
+  ACTQKV_OPTIONAL_SMALL(budget, 4);
+  if (budget_after != nullptr && budget_after == budget_in)
+    return set_error(ACTQKV_EINVAL, "budget_after must not be the array budget_in points to");
+  if (score_stride < nb_capacity)
+    return set_error(ACTQKV_EINVAL, "score_stride %lld < nb_capacity %d", (long long)score_stride,
+                     nb_capacity);
+  const int64_t per_seq = int64_t(nb_capacity) * shape->n_kv_heads * shape->block_size * shape->head_dim;
+  if (batch > 1 && seq_stride != 0 && seq_stride < per_seq)
+    return set_error(ACTQKV_EINVAL, "seq_stride %lld < one sequence's cache %lld", (long long)seq_stride,
+                     (long long)per_seq);
+  if (seq_stride % 8 != 0) return set_error(ACTQKV_EALIGN, "seq_stride must be a multiple of 8 elements");
+  if (workspace == nullptr || !aligned16(workspace))
+    return set_error(ACTQKV_EWORKSPACE, "workspace is NULL or not 16-byte aligned");
+  const size_t need = workspace_bytes(*shape, batch, 1, nb_capacity, k_cap);
+  if (ws_bytes < need)
+    return set_error(ACTQKV_EWORKSPACE, "workspace has %zu bytes, decode_select_attention needs %zu", ws_bytes,
+                     need);
+  Workspace ws{workspace, ws_bytes};
+  const float scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.f / std::sqrt(float(shape->head_dim));
+  return launch_attention_decode_select(*shape, batch, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx,
+                                        scores, score_stride, nb_begin, nb_end, k_cap, flags, budget_in,
+                                        theta_rest_sum, budget_after, idx, n_sel, theta, budget, out, lse,
+                                        ws.scratch_f32(), ws.counters(), scale,
+                                        static_cast<hipStream_t>(stream));
+}
+
 int actqkv_score_blocks_per_head(const actqkv_shape* shape, int batch, const float* probe, const void* rep_keys,
                                  int64_t seq_stride, int nb_capacity, int nb_begin, const int32_t* nb_end,
                                  float* scores, int64_t score_stride, void* stream) {
@@ -466,8 +534,9 @@ int actqkv_decode_retrieve(const actqkv_shape* shape, int batch, const void* q_t
                            float* budget, void* stream) {
   ACTQKV_TRY(check_shape(shape));
   ACTQKV_TRY(check_batch(batch));
-  if (flags & ~ACTQKV_SELECT_ENTROPY_TOPK)
+  if (flags & ~(ACTQKV_SELECT_ENTROPY_TOPK | ACTQKV_DECODE_SCORES_ONLY))
     return set_error(ACTQKV_EINVAL, "decode_retrieve: unknown flag bits: %d", flags);
+  const bool select_too = !(flags & ACTQKV_DECODE_SCORES_ONLY);
   if (nb_capacity < 1) return set_error(ACTQKV_EINVAL, "nb_capacity %d < 1", nb_capacity);
   if (int64_t(nb_capacity) * shape->block_size > (int64_t(1) << 30))
     return set_error(ACTQKV_ESHAPE, "cache of %d blocks exceeds 2^30 tokens", nb_capacity);
@@ -487,8 +556,10 @@ int actqkv_decode_retrieve(const actqkv_shape* shape, int batch, const void* q_t
   ACTQKV_OPTIONAL_PTR(probe_kv);
   ACTQKV_OPTIONAL_SMALL(probe_norm, 4);
   ACTQKV_REQUIRE_SMALL(scores, 4);
-  ACTQKV_REQUIRE_SMALL(idx, 4);
-  ACTQKV_REQUIRE_SMALL(n_sel, 4);
+  if (select_too) {
+    ACTQKV_REQUIRE_SMALL(idx, 4);
+    ACTQKV_REQUIRE_SMALL(n_sel, 4);
+  }
   if ((budget_remaining == nullptr) != (theta_rest_sum == nullptr))
     return set_error(ACTQKV_EINVAL, "budget_remaining and theta_rest_sum must be given together");
   ACTQKV_OPTIONAL_SMALL(budget_remaining, 4);

@@ -2,9 +2,9 @@
 // over [k^t, K*]; bf16 storage, fp32 accumulation).  HBM-bound: every selected key and
 // value byte is read exactly once, by exactly one wavefront.
 //
-// A wavefront owns whole 128-key tiles of one (sequence, KV head): initial tokens, the
-// blocks chosen by actqkv_select (read from device memory) or the local span up to the new
-// token.  The G query heads of the KV head ride along as columns of a 16-wide matrix-core
+// A wavefront owns work items of 64 keys (half a block) of one (sequence, KV head): initial
+// tokens, the blocks chosen by the selection step or the local span up to the new token; the
+// keys and the values of an item are requested together, before anything is computed.  The G query heads of the KV head ride along as columns of a 16-wide matrix-core
 // tile, so a key or value byte is loaded once for all of them, straight from global memory
 // into MFMA operands (no LDS staging: nothing is shared between wavefronts):
 //   S^T[key][head] = K[key][:] Q^T        v_mfma_f32_16x16x32_bf16, A = 16 keys x 32 channels
@@ -18,15 +18,15 @@
 // otherwise the workgroups store partials and the one that finishes last merges them.
 #include "common.h"
 #include "launch.h"
+#include "select_body.h"
 
 namespace actqkv {
 
 constexpr int kDcD = 128;
 constexpr int kDcMaxWaves = 8;   // 512 threads: the register budget stays at 256 per lane
-#ifndef ACTQKV_DC_ITEM_KEYS
-#define ACTQKV_DC_ITEM_KEYS 64
-#endif
-constexpr int kDcItemKeys = ACTQKV_DC_ITEM_KEYS;   // keys per work item: 64 or 128
+constexpr int kDcThreads = kDcMaxWaves * 64;
+constexpr int kDcItemKeys = 64;  // keys per work item (half a block)
+constexpr int kDcSteps = kDcItemKeys / 32, kDcPerTile = kBlock / kDcItemKeys;
 
 struct DcParams {
   const uint16_t* q;
@@ -48,145 +48,147 @@ struct DcParams {
   float scale_log2e;
 };
 
+// What the kernel that selects for itself needs on top (the arguments of the selection step).
+struct DcSelectParams {
+  const float* scores;
+  int64_t score_stride;
+  int nb_begin;
+  const int32_t* nb_end;
+  int entropy_topk;
+  SelectIo io;              // io.write is set per workgroup by the kernel
+};
+
 __device__ __forceinline__ bf16x8 dc_as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// grid (n_wg, Hk, batch); blockDim = 64 * (wavefronts per workgroup).  Wavefront w of
-// workgroup g walks tiles g*W + w, g*W + w + n_wg*W, ...
-__global__ __launch_bounds__(kDcMaxWaves * 64) void attn_decode_kernel(DcParams p) {
-  extern __shared__ __attribute__((aligned(16))) float dc_lds[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
-  const int n = lane & 15, kq = lane >> 4;       // MFMA column (query head) and lane quarter
-  const int wg = blockIdx.x, hk = blockIdx.y, s = blockIdx.z;
-  const int group = p.n_q_heads / p.n_kv_heads;
+// Keys and values of one work item (kDcItemKeys keys of a tile of one KV head) on their way into
+// MFMA operands, and the key positions [lo, hi) of the item that the query may see.
+struct DcItem {
+  u32x4 ka[8 * kDcSteps];
+  u32x4 va[8 * kDcSteps];
+  int kpos0, lo, hi;
+};
+// Running softmax state of a wavefront: lane (n, kq) holds channels 16*dg + 4*kq + i of head n.
+struct DcAcc {
+  float m_run, l_run;
+  f32x4 acc_o[8];
+};
+
+// Item `it` of a tile list -> its block and visible span; false if the query sees none of it.
+__device__ __forceinline__ bool dc_item_span(const TileList& tl, int it, int& block, int& part, DcItem& r) {
+  int lo, hi;
+  tl.get(it / kDcPerTile, block, lo, hi);
+  part = it % kDcPerTile;
+  r.kpos0 = block * kBlock + part * kDcItemKeys;
+  r.lo = max(lo, r.kpos0);
+  r.hi = min(hi, r.kpos0 + kDcItemKeys);
+  return r.hi > r.lo;
+}
+
+// Requests the item's keys AND values (nothing is computed before both are on their way).
+// A operands of S^T: MFMA row r of sub-tile h of 32-key step st is key 32*st + 8*(r/4) + 4*h + r%4,
+// so that lane quarter kq ends up with keys 32*st + 8*kq + 4*h + i in register i.
+// V^T A operands: lane (row = channel within a group of 16, kq) reads keys 32*st + 8*kq .. +7.
+__device__ __forceinline__ void dc_issue(DcItem& r, const uint16_t* kc, const uint16_t* vc, int block, int part,
+                                         int hk, int n_kv_heads, int n, int kq) {
+  const size_t tile = (size_t(block) * n_kv_heads + hk) * size_t(kBlock) * kDcD;
+  const uint16_t* kbase = kc + tile + size_t(part) * kDcItemKeys * kDcD + size_t(8 * (n >> 2) + (n & 3)) * kDcD + 8 * kq;
+  const uint16_t* vbase = vc + tile + part * kDcItemKeys + size_t(n) * kBlock + 8 * kq;
+#pragma unroll
+  for (int st = 0; st < kDcSteps; ++st)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        r.ka[(st * 2 + h) * 4 + ks] =
+            *reinterpret_cast<const u32x4*>(kbase + size_t(32 * st + 4 * h) * kDcD + ks * 32);
+#pragma unroll
+  for (int dg = 0; dg < 8; ++dg)
+#pragma unroll
+    for (int st = 0; st < kDcSteps; ++st)
+      r.va[dg * kDcSteps + st] = *reinterpret_cast<const u32x4*>(vbase + size_t(16 * dg) * kBlock + 32 * st);
+}
+
+// Scores, mask, online softmax and O^T += V^T P^T for one item.
+__device__ __forceinline__ void dc_consume(const DcItem& r, const bf16x8 (&qb)[4], DcAcc& a, float scale_log2e,
+                                           int kq) {
+  f32x4 sc[2 * kDcSteps];
+#pragma unroll
+  for (int j = 0; j < 2 * kDcSteps; ++j) sc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)       // the sub-tiles take turns: no MFMA waits for the one before it
+#pragma unroll
+    for (int j = 0; j < 2 * kDcSteps; ++j)
+      sc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dc_as_bf16x8(r.ka[j * 4 + ks]), qb[ks], sc[j], 0, 0, 0);
+  // mask and online softmax: sc[2*st + h][i] is key kpos0 + 32*st + 8*kq + 4*h + i
+  float mx = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < 2 * kDcSteps; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int kp = r.kpos0 + 32 * (j >> 1) + 8 * kq + 4 * (j & 1) + i;
+      const float v = (kp >= r.lo && kp < r.hi) ? sc[j][i] : -INFINITY;
+      sc[j][i] = v;
+      mx = fmaxf(mx, v);
+    }
+  mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float m_new = fmaxf(a.m_run, mx * scale_log2e);   // finite: the item has a visible key
+  const float alpha = __builtin_amdgcn_exp2f(a.m_run - m_new);
+  a.m_run = m_new;
+  float psum = 0.f;
+#pragma unroll
+  for (int j = 0; j < 2 * kDcSteps; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float pv = __builtin_amdgcn_exp2f(sc[j][i] * scale_log2e - m_new);
+      sc[j][i] = pv;
+      psum += pv;
+    }
+  psum += __shfl_xor(psum, 16, 64);
+  psum += __shfl_xor(psum, 32, 64);
+  a.l_run = a.l_run * alpha + psum;
+#pragma unroll
+  for (int dg = 0; dg < 8; ++dg) a.acc_o[dg] *= alpha;
+  typedef __attribute__((ext_vector_type(8))) float f32x8;
+#pragma unroll
+  for (int st = 0; st < kDcSteps; ++st) {
+    f32x8 pf = {sc[2 * st][0], sc[2 * st][1], sc[2 * st][2], sc[2 * st][3],
+                sc[2 * st + 1][0], sc[2 * st + 1][1], sc[2 * st + 1][2], sc[2 * st + 1][3]};
+    const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
+#pragma unroll
+    for (int dg = 0; dg < 8; ++dg)
+      a.acc_o[dg] =
+          __builtin_amdgcn_mfma_f32_16x16x32_bf16(dc_as_bf16x8(r.va[dg * kDcSteps + st]), pb, a.acc_o[dg], 0, 0, 0);
+  }
+}
+
+// Q^T as B operand: lane (n, kq) holds channels ks*32 + 8*kq .. +7 of head n (zero for n >= G)
+__device__ __forceinline__ void dc_load_q(const DcParams& p, int s, int hk, int group, int n, int kq,
+                                          bf16x8 (&qb)[4]) {
+  const uint16_t* qp = p.q + (size_t(s) * p.n_q_heads + hk * group + min(n, group - 1)) * kDcD + 8 * kq;
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    u32x4 v = *reinterpret_cast<const u32x4*>(qp + ks * 32);
+    if (n >= group) v = u32x4{0u, 0u, 0u, 0u};
+    qb[ks] = dc_as_bf16x8(v);
+  }
+}
+
+// The wavefronts of a workgroup merge their (max, sum, O) through LDS.  If one workgroup covers
+// the whole (sequence, KV head) it writes the output itself; otherwise the workgroups store
+// partials and the one that finishes last merges them.  dc_lds: n_waves * G * (D + 2) floats.
+__device__ __forceinline__ void dc_finish(const DcParams& p, const DcAcc& a, float* dc_lds, int s, int hk, int wg,
+                                          int group, int n, int kq, int wave, int n_waves) {
   float* red_ml = dc_lds;                        // [n_waves][group][2]
   float* red_o = dc_lds + n_waves * group * 2;   // [n_waves][group][D]
-
-  const int n_ctx = min(max(p.n_ctx[s], 1), p.nb_capacity * kBlock);
-  const WindowGeom g = window_geom(n_ctx, 1, p.n_init, p.n_local);
-  const size_t sel_row = p.sel_per_head ? size_t(s) * p.n_kv_heads + hk : size_t(s);
-  const TileList tl = make_tile_list(g, n_ctx - 1, p.idx + sel_row * p.k_cap, p.n_sel[sel_row], p.k_cap,
-                                     p.nb_capacity);
-  const int n_tiles = tl.count();
-
-  // Q^T as B operand: lane (n, kq) holds channels ks*32 + 8*kq .. +7 of head n (zero for n >= G)
-  bf16x8 qb[4];
-  {
-    const uint16_t* qp = p.q + (size_t(s) * p.n_q_heads + hk * group + min(n, group - 1)) * kDcD + 8 * kq;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      u32x4 v = *reinterpret_cast<const u32x4*>(qp + ks * 32);
-      if (n >= group) v = u32x4{0u, 0u, 0u, 0u};
-      qb[ks] = dc_as_bf16x8(v);
-    }
-  }
-  float m_run = -INFINITY, l_run = 0.f;
-  f32x4 acc_o[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) acc_o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const size_t tile_elems = size_t(kBlock) * kDcD;
-  const uint16_t* kc = p.k_cache + size_t(s) * p.seq_stride;
-  const uint16_t* vc = p.v_cache + size_t(s) * p.seq_stride;
-
-  // Work items are spans of kDcItemKeys keys of a tile; item i of the list goes to wavefront i mod (all
-  // wavefronts of the pair).  Keys AND values of an item are requested before anything is computed.
-  constexpr int kSteps = kDcItemKeys / 32, kPerTile = kBlock / kDcItemKeys;
-  const int n_items = n_tiles * kPerTile;
-  for (int it = wg * n_waves + wave; it < n_items; it += p.n_wg * n_waves) {
-    int block, lo, hi;
-    tl.get(it / kPerTile, block, lo, hi);
-    const int part = it % kPerTile;
-    const int kpos0 = block * kBlock + part * kDcItemKeys;
-    lo = max(lo, kpos0);
-    hi = min(hi, kpos0 + kDcItemKeys);
-    if (hi <= lo) continue;                      // wave-uniform
-    const uint16_t* kt = kc + (size_t(block) * p.n_kv_heads + hk) * tile_elems + size_t(part) * kDcItemKeys * kDcD;
-    const uint16_t* vt = vc + (size_t(block) * p.n_kv_heads + hk) * tile_elems + part * kDcItemKeys;
-
-    // A operands of S^T: MFMA row r of sub-tile h of 32-key step st is key 32*st + 8*(r/4) + 4*h + r%4,
-    // so that lane quarter kq ends up with keys 32*st + 8*kq + 4*h + i in register i.
-    u32x4 ka[8 * kSteps];
-    {
-      const uint16_t* base = kt + size_t(8 * (n >> 2) + (n & 3)) * kDcD + 8 * kq;
-#pragma unroll
-      for (int st = 0; st < kSteps; ++st)
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-          for (int ks = 0; ks < 4; ++ks)
-            ka[(st * 2 + h) * 4 + ks] =
-                *reinterpret_cast<const u32x4*>(base + size_t(32 * st + 4 * h) * kDcD + ks * 32);
-    }
-    // V^T A operands: lane (row = channel within a group of 16, kq) reads keys 32*st + 8*kq .. +7
-    u32x4 va[8 * kSteps];
-    {
-      const uint16_t* base = vt + size_t(n) * kBlock + 8 * kq;
-#pragma unroll
-      for (int dg = 0; dg < 8; ++dg)
-#pragma unroll
-        for (int st = 0; st < kSteps; ++st)
-          va[dg * kSteps + st] = *reinterpret_cast<const u32x4*>(base + size_t(16 * dg) * kBlock + 32 * st);
-    }
-    __builtin_amdgcn_sched_barrier(0);   // all key and value loads are in flight before the first MFMA
-    f32x4 sc[2 * kSteps];
-#pragma unroll
-    for (int j = 0; j < 2 * kSteps; ++j) sc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)       // the sub-tiles take turns: no MFMA waits for the one before it
-#pragma unroll
-      for (int j = 0; j < 2 * kSteps; ++j)
-        sc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dc_as_bf16x8(ka[j * 4 + ks]), qb[ks], sc[j], 0, 0, 0);
-    // mask and online softmax: sc[2*st + h][i] is key kpos0 + 32*st + 8*kq + 4*h + i
-    float mx = -INFINITY;
-#pragma unroll
-    for (int j = 0; j < 2 * kSteps; ++j)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int kp = kpos0 + 32 * (j >> 1) + 8 * kq + 4 * (j & 1) + i;
-        const float v = (kp >= lo && kp < hi) ? sc[j][i] : -INFINITY;
-        sc[j][i] = v;
-        mx = fmaxf(mx, v);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx * p.scale_log2e);   // finite: the item has a visible key
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
-    float psum = 0.f;
-#pragma unroll
-    for (int j = 0; j < 2 * kSteps; ++j)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float pv = __builtin_amdgcn_exp2f(sc[j][i] * p.scale_log2e - m_new);
-        sc[j][i] = pv;
-        psum += pv;
-      }
-    psum += __shfl_xor(psum, 16, 64);
-    psum += __shfl_xor(psum, 32, 64);
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int dg = 0; dg < 8; ++dg) acc_o[dg] *= alpha;
-    // O^T += V^T P^T
-    typedef __attribute__((ext_vector_type(8))) float f32x8;
-#pragma unroll
-    for (int st = 0; st < kSteps; ++st) {
-      f32x8 pf = {sc[2 * st][0], sc[2 * st][1], sc[2 * st][2], sc[2 * st][3],
-                  sc[2 * st + 1][0], sc[2 * st + 1][1], sc[2 * st + 1][2], sc[2 * st + 1][3]};
-      const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
-#pragma unroll
-      for (int dg = 0; dg < 8; ++dg)
-        acc_o[dg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dc_as_bf16x8(va[dg * kSteps + st]), pb, acc_o[dg], 0, 0, 0);
-    }
-  }
-
-  // merge the wavefronts: lane (n < G, kq) holds channels 16*dg + 4*kq + i of head n
   if (n < group) {
     if (kq == 0) {
-      red_ml[(wave * group + n) * 2 + 0] = m_run;
-      red_ml[(wave * group + n) * 2 + 1] = l_run;
+      red_ml[(wave * group + n) * 2 + 0] = a.m_run;
+      red_ml[(wave * group + n) * 2 + 1] = a.l_run;
     }
 #pragma unroll
     for (int dg = 0; dg < 8; ++dg)
-      *reinterpret_cast<f32x4*>(&red_o[(wave * group + n) * kDcD + 16 * dg + 4 * kq]) = acc_o[dg];
+      *reinterpret_cast<f32x4*>(&red_o[(wave * group + n) * kDcD + 16 * dg + 4 * kq]) = a.acc_o[dg];
   }
   __syncthreads();
   uint32_t* pair_part = p.part + (size_t(s) * p.n_kv_heads + hk) * p.n_wg * group * (kDcD + 2);
@@ -257,6 +259,114 @@ __global__ __launch_bounds__(kDcMaxWaves * 64) void attn_decode_kernel(DcParams 
   }
 }
 
+// grid (n_wg, Hk, batch); blockDim = 64 * (wavefronts per workgroup).  Item i of the tile list
+// of a (sequence, KV head) goes to wavefront i mod (all wavefronts of the pair).
+__global__ __launch_bounds__(kDcThreads) void attn_decode_kernel(DcParams p) {
+  extern __shared__ __attribute__((aligned(16))) float dc_lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+  const int n = lane & 15, kq = lane >> 4;       // MFMA column (query head) and lane quarter
+  const int wg = blockIdx.x, hk = blockIdx.y, s = blockIdx.z;
+  const int group = p.n_q_heads / p.n_kv_heads;
+
+  const int n_ctx = min(max(p.n_ctx[s], 1), p.nb_capacity * kBlock);
+  const WindowGeom g = window_geom(n_ctx, 1, p.n_init, p.n_local);
+  const size_t sel_row = p.sel_per_head ? size_t(s) * p.n_kv_heads + hk : size_t(s);
+  const TileList tl = make_tile_list(g, n_ctx - 1, p.idx + sel_row * p.k_cap, p.n_sel[sel_row], p.k_cap,
+                                     p.nb_capacity);
+  const int n_items = tl.count() * kDcPerTile;
+  bf16x8 qb[4];
+  dc_load_q(p, s, hk, group, n, kq, qb);
+  DcAcc a;
+  a.m_run = -INFINITY;
+  a.l_run = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a.acc_o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const uint16_t* kc = p.k_cache + size_t(s) * p.seq_stride;
+  const uint16_t* vc = p.v_cache + size_t(s) * p.seq_stride;
+
+  for (int it = wg * n_waves + wave; it < n_items; it += p.n_wg * n_waves) {
+    DcItem r;
+    int block, part;
+    if (!dc_item_span(tl, it, block, part, r)) continue;   // wave-uniform
+    dc_issue(r, kc, vc, block, part, hk, p.n_kv_heads, n, kq);
+    __builtin_amdgcn_sched_barrier(0);   // all key and value loads are in flight before the first MFMA
+    dc_consume(r, qb, a, p.scale_log2e, kq);
+  }
+  dc_finish(p, a, dc_lds, s, hk, wg, group, n, kq, wave, n_waves);
+}
+
+// The same attention with the selection step (Sec. 4.2, Eq. (11), Eq. (12); Alg. 1) inside it:
+// the step needs a launch of its own only because of its latency (two memory round trips and a
+// dozen barriers for 2 KB of scores), and an attention workgroup has exactly that much time to
+// spare while its first keys and values are on their way.  Every workgroup of a sequence repeats
+// the sequence's selection (same code, same inputs: the same result in all of them) and keeps it
+// in LDS; the first workgroup of the sequence also writes it out.  Items that do not depend on
+// the selection (initial tokens, local span) come first in the list, so a wavefront's first
+// loads go out before the selection starts.
+// blockDim = kDcThreads (the selection is written for that many threads).
+__global__ __launch_bounds__(kDcThreads) void attn_decode_select_kernel(DcParams p, DcSelectParams sp) {
+  extern __shared__ __attribute__((aligned(16))) float dc_lds[];
+  __shared__ SelectLds<kDcThreads> sel_lds;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int n_waves = kDcMaxWaves;
+  const int n = lane & 15, kq = lane >> 4;
+  const int wg = blockIdx.x, hk = blockIdx.y, s = blockIdx.z;
+  const int group = p.n_q_heads / p.n_kv_heads;
+
+  // the scores of the sequence: the load of the first 512 does not wait for anything
+  const float* sc_mem = sp.scores + size_t(s) * sp.score_stride + sp.nb_begin;
+  const ScoreRow<kDcThreads> sc{sc_mem, int(threadIdx.x) < p.nb_capacity - sp.nb_begin ? sc_mem[threadIdx.x] : 0.f};
+  const int end = min(sp.nb_end[s], p.nb_capacity);
+  const int n_elig = max(end - sp.nb_begin, 0);
+  const int n_ctx = min(max(p.n_ctx[s], 1), p.nb_capacity * kBlock);
+  const WindowGeom g = window_geom(n_ctx, 1, p.n_init, p.n_local);
+  // the list without the selection: initial tokens, then the local span
+  const TileList fixed = make_tile_list(g, n_ctx - 1, nullptr, 0, p.k_cap, p.nb_capacity);
+  const int n_fixed = fixed.count() * kDcPerTile;
+  bf16x8 qb[4];
+  dc_load_q(p, s, hk, group, n, kq, qb);
+  DcAcc a;
+  a.m_run = -INFINITY;
+  a.l_run = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a.acc_o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const uint16_t* kc = p.k_cache + size_t(s) * p.seq_stride;
+  const uint16_t* vc = p.v_cache + size_t(s) * p.seq_stride;
+
+  // this wavefront's first item, if it is one that does not depend on the selection
+  const int it0 = wg * n_waves + wave, stride = p.n_wg * n_waves;
+  DcItem r0;
+  int block0, part0;
+  const bool have0 = it0 < n_fixed && dc_item_span(fixed, it0, block0, part0, r0);
+  if (have0) dc_issue(r0, kc, vc, block0, part0, hk, p.n_kv_heads, n, kq);
+  __builtin_amdgcn_sched_barrier(0);
+
+  SelectIo io = sp.io;
+  io.write = wg == 0 && hk == 0;
+  select_body<kDcThreads>(sc, s, n_elig, sp.nb_begin, p.k_cap, sp.entropy_topk, io, sel_lds);
+  __builtin_amdgcn_sched_barrier(0);
+  if (have0) dc_consume(r0, qb, a, p.scale_log2e, kq);
+
+  // the rest of the list: what is left of the fixed items, then the selected blocks
+  TileList chosen = fixed;
+  chosen.n_init_tiles = 0;
+  chosen.n_tail_tiles = 0;
+  chosen.n_sel = min(max(sel_lds.count, 0), p.k_cap);
+  chosen.idx = sel_lds.sel;
+  const int n_items = n_fixed + chosen.n_sel * kDcPerTile;
+  for (int it = it0 < n_fixed ? it0 + stride : it0; it < n_items; it += stride) {
+    DcItem r;
+    int block, part;
+    const bool ok = it < n_fixed ? dc_item_span(fixed, it, block, part, r)
+                                 : dc_item_span(chosen, it - n_fixed, block, part, r);
+    if (!ok) continue;                   // wave-uniform
+    dc_issue(r, kc, vc, block, part, hk, p.n_kv_heads, n, kq);
+    __builtin_amdgcn_sched_barrier(0);
+    dc_consume(r, qb, a, p.scale_log2e, kq);
+  }
+  dc_finish(p, a, dc_lds, s, hk, wg, group, n, kq, wave, n_waves);
+}
+
 bool decode_mfma_supported(const actqkv_shape& sh, int m) {
   const int g = sh.n_q_heads / sh.n_kv_heads;
   return sh.dtype == ACTQKV_BF16 && sh.head_dim == kDcD && m == 1 && g <= 8;
@@ -272,7 +382,7 @@ static int decode_tiles_max(const actqkv_shape& sh, int k_cap) {
 int decode_mfma_workgroups(const actqkv_shape& sh, int batch, int k_cap) {
   const int pairs = batch * sh.n_kv_heads;
   const int want = (2048 + pairs * kDcMaxWaves - 1) / (pairs * kDcMaxWaves);
-  const int most = (decode_tiles_max(sh, k_cap) + kDcMaxWaves - 1) / kDcMaxWaves;
+  const int most = (decode_tiles_max(sh, k_cap) * kDcPerTile + kDcMaxWaves - 1) / kDcMaxWaves;
   return want < 1 ? 1 : (want > most ? most : want);
 }
 
@@ -280,11 +390,10 @@ size_t decode_mfma_scratch_floats(const actqkv_shape& sh, int batch, int k_cap) 
   return size_t(batch) * sh.n_q_heads * decode_mfma_workgroups(sh, batch, k_cap) * (kDcD + 2);
 }
 
-int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* q, const void* k_cache,
-                                 const void* v_cache, int64_t seq_stride, int nb_capacity,
-                                 const int32_t* n_ctx, const int32_t* idx, const int32_t* n_sel,
-                                 int k_cap, void* out, float* lse, float* scratch,
-                                 unsigned int* counters, float scale, int sel_per_head, hipStream_t stream) {
+static DcParams decode_params(const actqkv_shape& sh, int batch, const void* q, const void* k_cache,
+                              const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
+                              const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
+                              float* scratch, unsigned int* counters, float scale, int sel_per_head) {
   DcParams p;
   p.q = static_cast<const uint16_t*>(q);
   p.k_cache = static_cast<const uint16_t*>(k_cache);
@@ -306,14 +415,47 @@ int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* 
   p.n_local = sh.n_local;
   p.n_wg = decode_mfma_workgroups(sh, batch, k_cap);
   p.scale_log2e = scale * 1.4426950408889634f;
+  return p;
+}
+
+int launch_attention_decode_mfma(const actqkv_shape& sh, int batch, const void* q, const void* k_cache,
+                                 const void* v_cache, int64_t seq_stride, int nb_capacity,
+                                 const int32_t* n_ctx, const int32_t* idx, const int32_t* n_sel,
+                                 int k_cap, void* out, float* lse, float* scratch,
+                                 unsigned int* counters, float scale, int sel_per_head, hipStream_t stream) {
+  const DcParams p = decode_params(sh, batch, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx, n_sel,
+                                   k_cap, out, lse, scratch, counters, scale, sel_per_head);
   const int group = sh.n_q_heads / sh.n_kv_heads;
-  const int n_waves = kDcMaxWaves;
-  const size_t lds = size_t(n_waves) * group * (kDcD + 2) * sizeof(float);
+  const size_t lds = size_t(kDcMaxWaves) * group * (kDcD + 2) * sizeof(float);
   if (p.n_wg > 1 && size_t(batch) * sh.n_kv_heads > kTicketCounters)
     return set_error(ACTQKV_EINVAL, "decode attention: more split (sequence, KV head) pairs than ticket counters");
-  hipLaunchKernelGGL(attn_decode_kernel, dim3(p.n_wg, sh.n_kv_heads, batch), dim3(n_waves * 64), lds,
-                     stream, p);
+  hipLaunchKernelGGL(attn_decode_kernel, dim3(p.n_wg, sh.n_kv_heads, batch), dim3(kDcThreads), lds, stream, p);
   return hip_status("attention (decode)");
+}
+
+int launch_attention_decode_select(const actqkv_shape& sh, int batch, const void* q, const void* k_cache,
+                                   const void* v_cache, int64_t seq_stride, int nb_capacity,
+                                   const int32_t* n_ctx, const float* scores, int64_t score_stride, int nb_begin,
+                                   const int32_t* nb_end, int k_cap, int flags, const float* budget_in,
+                                   const float* theta_rest_sum, float* budget_after, int32_t* idx,
+                                   int32_t* n_sel, float* theta, float* budget, void* out, float* lse,
+                                   float* scratch, unsigned int* counters, float scale, hipStream_t stream) {
+  const DcParams p = decode_params(sh, batch, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, nullptr,
+                                   nullptr, k_cap, out, lse, scratch, counters, scale, 0);
+  DcSelectParams sp;
+  sp.scores = scores;
+  sp.score_stride = score_stride;
+  sp.nb_begin = nb_begin;
+  sp.nb_end = nb_end;
+  sp.entropy_topk = (flags & ACTQKV_SELECT_ENTROPY_TOPK) != 0;
+  sp.io = SelectIo{budget_in, theta_rest_sum, budget_after, idx, n_sel, theta, budget, false};
+  const int group = sh.n_q_heads / sh.n_kv_heads;
+  const size_t lds = size_t(kDcMaxWaves) * group * (kDcD + 2) * sizeof(float);
+  if (p.n_wg > 1 && size_t(batch) * sh.n_kv_heads > kTicketCounters)
+    return set_error(ACTQKV_EINVAL, "decode attention: more split (sequence, KV head) pairs than ticket counters");
+  hipLaunchKernelGGL(attn_decode_select_kernel, dim3(p.n_wg, sh.n_kv_heads, batch), dim3(kDcThreads), lds,
+                     stream, p, sp);
+  return hip_status("attention with selection (decode)");
 }
 
 }  // namespace actqkv

@@ -213,7 +213,7 @@ int launch_decode_retrieve(const actqkv_shape& sh, int batch, const void* q_tok,
     fill(p);
     rc = launch_decode_score_t(sh, batch, p, stream);
   }
-  if (rc != ACTQKV_OK) return rc;
+  if (rc != ACTQKV_OK || (flags & ACTQKV_DECODE_SCORES_ONLY)) return rc;
   return launch_select(batch, scores, score_stride, nb_capacity, nb_begin, nb_end, k_cap, flags,
                        budget_remaining, theta_rest_sum, idx, n_sel, theta, budget, stream);
 }

@@ -129,6 +129,28 @@ class LayerRunner:
         B.retrieval_attention(cs, bt, 1, q_tok, k_cache, v_cache, cache_stride, self.nb_capacity, n_ctx,
                               self.idx, self.n_sel, self.k_cap, out, lse, self.workspace, stream)
 
+    def decode_step_two_launches(self, q_tok: torch.Tensor, k_cache, v_cache, rep_keys, n_ctx: torch.Tensor,
+                                 nb_end: torch.Tensor, out: torch.Tensor,
+                                 budget_in: Optional[torch.Tensor] = None,
+                                 theta_rest_sum: Optional[torch.Tensor] = None,
+                                 budget_after: Optional[torch.Tensor] = None, k_new=None, v_new=None,
+                                 pos0=None, lse=None, stream=None) -> None:
+        """A decode step in two launches: (cache update,) probe and scores in the first
+        (actqkv_decode_retrieve, scores only), selection and attention in the second
+        (actqkv_decode_select_attention).  bf16, head_dim 128 only."""
+        sh, cs, bt = self.shape, self.cs, self.batch
+        nb_begin = sh.n_init // sh.block_size
+        cache_stride = k_cache.stride(0) if k_cache.dim() == 5 else 0
+        rep_stride = rep_keys.stride(0) if rep_keys.dim() == 5 else 0
+        B.decode_retrieve(cs, bt, q_tok, k_new, v_new, pos0, k_cache, v_cache, cache_stride, rep_keys,
+                          rep_stride, self.nb_capacity, nb_begin, nb_end, self.probe, self.probe_kv,
+                          self.probe_norm, self.scores, self.score_stride, self.k_cap, None, None, None,
+                          None, None, None, stream, flags=B.DECODE_SCORES_ONLY)
+        B.decode_select_attention(cs, bt, q_tok, k_cache, v_cache, cache_stride, self.nb_capacity, n_ctx,
+                                  self.scores, self.score_stride, nb_begin, nb_end, self.k_cap, budget_in,
+                                  theta_rest_sum, budget_after, self.idx, self.n_sel, self.theta,
+                                  self.budget, out, lse, self.workspace, stream)
+
 
 @dataclass
 class PrefillPlan:

@@ -160,9 +160,27 @@ def test_decode_retrieve_rejects(lib):
     assert call(kn=None) == -1 and call(pos0=None) == -1 and call(kc=None) == -1     # a partial cache update
     assert call(rep=None) == -1 and call(nb_end=None) == -1 and call(scores=None) == -1 and call(idx=None) == -1
     assert call(cap=0) == -1 and call(cap=9000, ss=9000) == -2 and call(ss=10) == -1
-    assert call(k_cap=0) == -2 and call(k_cap=65) == -2 and call(flags=2) == -1
+    assert call(k_cap=0) == -2 and call(k_cap=65) == -2 and call(flags=4) == -1
     assert call(bud=A16) == -1 and call(bud=A16 + 2, rest=A16) == -3
     assert call(batch=2, cs=8) == -1 and call(batch=2, cs=1 << 40, rs=8) == -1 and call(cs=12) == -3
+
+
+def test_decode_select_attention_rejects(lib):
+    cs = B.c_shape(LLAMA)
+    call = lambda **k: lib.actqkv_decode_select_attention(
+        ctypes.byref(k.get("shape", cs)), k.get("batch", 1), k.get("q", A16), k.get("kc", A16), A16, k.get("stride", 0),
+        k.get("cap", 64), k.get("n_ctx", A16), k.get("scores", A16), k.get("ss", 64), 1, k.get("nb_end", A16),
+        k.get("k_cap", 32), k.get("flags", 0), k.get("bud"), k.get("rest"), k.get("after"), k.get("idx", A16),
+        k.get("n_sel", A16), None, None, k.get("out", A16), None, k.get("ws", A16), k.get("wsb", 1 << 30), None)
+    assert call(q=None) == -1 and call(kc=A16 + 2) == -3 and call(scores=None) == -1 and call(out=None) == -1
+    assert call(idx=None) == -1 and call(n_sel=None) == -1 and call(n_ctx=None) == -1 and call(nb_end=None) == -1
+    assert call(cap=0) == -1 and call(ss=10) == -1 and call(k_cap=65) == -2 and call(flags=2) == -1
+    assert call(bud=A16) == -1 and call(bud=A16, rest=A16, after=A16) == -1     # in place is not allowed
+    assert b"budget_after" in lib.actqkv_last_error()
+    assert call(batch=2, stride=8) == -1 and call(stride=4) == -3
+    assert call(ws=None) == -4 and call(wsb=8) == -4
+    fp32 = B.c_shape(LayerShape(8, 2, 64, 128, 4, 128, 256, "fp32"))
+    assert call(shape=fp32) == -2                                               # a bf16, head_dim 128 kernel
 
 
 def test_cutoff_next_step_rejects(lib):
