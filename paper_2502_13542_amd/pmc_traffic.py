@@ -19,7 +19,7 @@ from collections import defaultdict
 
 ATTENTION = {
     "c3_128k": ("attn_prefill_mfma_queued_kernel", ["attn_prefill_mfma_queued_kernel"]),
-    "c4_decode": ("attn_decode_kernel", ["attn_decode_kernel"]),
+    "c4_decode": ("attn_decode_select_kernel", ["attn_decode_select_kernel"]),
 }
 
 
@@ -70,7 +70,7 @@ def main() -> int:
               "| kernel | dispatches | fetch MB / dispatch | write MB / dispatch |", "|---|---|---|---|"]
     for name in sorted(set(fetch) | set(write)):
         if name == "copy_bytes_kernel" or not any(k in name for k in
-                                                  ("probe_", "score_", "select_", "attn_", "append_", "cutoff_")):
+                                                  ("probe_", "score_", "select_", "attn_", "append_", "cutoff_", "decode_")):
             continue
         fv, wv = fetch.get(name, []), write.get(name, [])
         n = max(len(fv), len(wv), 1)
