@@ -463,11 +463,12 @@ def bench_decode(args, torch, B, H, synth):
         torch.sub(n_ctx_cur, 1, out=pos_cur)
         nb_end_cur.copy_(nb_end_all[t])
 
-    def one_step(events=None):
+    def one_step(events=None, launches=None):
+        launches = args.decode_launches if launches is None else launches
         # folds the step before into the history; B_kv = L * k again; R^l for every layer
         B.cutoff_next_step(bt, L, k_mean, theta_prior, theta_step, theta_sum, hist_steps, budget, rest_all)
         for l in range(L):
-            if args.decode_launches == 2:
+            if launches == 2:
                 # cache update, probe and scores in one launch, selection and attention in the other
                 B.decode_retrieve(runner.cs, bt, q_step[l], k_step[l], v_step[l], pos_cur, kc[l], vc[l],
                                   cache_stride, rep[l], rep_stride, nb_cap, nb_begin, nb_end_cur, None, None,
@@ -483,7 +484,7 @@ def bench_decode(args, torch, B, H, synth):
                 if events is not None:
                     events[l][1].record()
                 continue
-            if args.decode_launches == 3:
+            if launches == 3:
                 # cache update, probe and scores in one launch, then the selection
                 B.decode_retrieve(runner.cs, bt, q_step[l], k_step[l], v_step[l], pos_cur, kc[l], vc[l],
                                   cache_stride, rep[l], rep_stride, nb_cap, nb_begin, nb_end_cur, None, None,
@@ -545,6 +546,13 @@ def bench_decode(args, torch, B, H, synth):
     keys = min(sh.n_init, n_ctx_last - 1) + (n_ctx_last - l0)
     byt = float(((n_sel.sum().item() * bs) + keys * L * bt) * hk * D * 2 * 2)       # K and V, bf16
     attn_ms = sum(a.elapsed_time(b) for (a, b) in ev)
+    # the attention launch without the selection inside it (selection as a launch of its own)
+    alone_ms, alone_byt = attn_ms, byt
+    if args.decode_launches == 2:
+        one_step(ev, launches=3)
+        torch.cuda.synchronize()
+        alone_ms = sum(a.elapsed_time(b) for (a, b) in ev)
+        alone_byt = float(((nsel_log.sum().item() * bs) + keys * L * bt) * hk * D * 2 * 2)
     score_bytes = float((nb_end_host[-1] - nb_begin) * sh.n_rep * hk * D * 2 * L * bt)
     achieved = byt / (attn_ms * 1e-3) / 1e9
     mean_us = sum(times) / len(times) * 1e6
@@ -564,7 +572,12 @@ def bench_decode(args, torch, B, H, synth):
                                 if args.decode_launches == 2 else
                                 "actqkv_retrieval_attention launch, m = 1 (attn_decode_kernel)"),
                      "avg_launch_us": attn_ms * 1e3 / L, "algorithmic_mb_per_launch": byt / L / 1e6,
-                     "timing": "HIP events around every attention launch of one eager step"},
+                     "timing": "HIP events around every attention launch of one eager step",
+                     "attention_alone": {"avg_launch_us": alone_ms * 1e3 / L,
+                                         "achieved": alone_byt / (alone_ms * 1e-3) / 1e9,
+                                         "frac": alone_byt / (alone_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                         "kernel": "actqkv_retrieval_attention launch, m = 1 (attn_decode_kernel), "
+                                                   "with actqkv_select as a launch of its own"}},
     }
 
 

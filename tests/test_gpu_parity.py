@@ -499,6 +499,76 @@ def test_decode_full_size_layer_as_benchmarked():
         assert err < TOL_OUT["bf16"], f"decode output, sequence {s}"
 
 
+@pytest.mark.parametrize("n,k_cap,mode", [(5, 8, "cutoff"), (511, 32, "cutoff"), (513, 32, "cutoff"), (1500, 64, "topk"),
+                                          (4000, 16, "plain"), (0, 8, "cutoff")])
+def test_decode_attention_that_selects_for_itself(n, k_cap, mode):
+    """actqkv_decode_select_attention against the oracle's selection (ties by block index,
+    density, budget, count) for more eligible blocks than the 512 threads of a workgroup, and
+    against actqkv_select + actqkv_retrieval_attention on the same inputs.  mode: cut-off on /
+    density over the best blocks (the other reading of Eq. (11)) / no cut-off."""
+    sh = LayerShape(8, 2, 128, 128, 4, 128, 256, "bf16")
+    cs = B.c_shape(sh)
+    bt, nb_begin = 2, 1
+    nb = nb_begin + n + 4                                   # the local span and the new token's block behind the eligible ones
+    n_ctx = (nb - 1) * 128 + 1
+    rng = np.random.default_rng(7 * n + k_cap)
+    g = torch.Generator().manual_seed(n + 1)
+    kc = torch.randn(bt, nb, 2, 128, 128, generator=g).to(torch.bfloat16).to(DEV)
+    vc = torch.randn(bt, nb, 2, 128, 128, generator=g).to(torch.bfloat16).to(DEV)
+    q = torch.randn(bt, 1, 8, 128, generator=g).to(torch.bfloat16).to(DEV)
+    stride = nb
+    scores = np.zeros((bt, stride), dtype=np.float32)
+    scores[0, nb_begin:nb_begin + n] = rng.integers(-6, 7, size=n) / 8.0      # many exact ties
+    scores[1, nb_begin:nb_begin + n] = rng.normal(size=n).astype(np.float32) * 0.3
+    sd = torch.from_numpy(scores).to(DEV)
+    nb_end = torch.full((bt,), nb_begin + n, dtype=torch.int32, device=DEV)
+    nctx = torch.full((bt,), n_ctx, dtype=torch.int32, device=DEV)
+    cut = (37.0, 11.0) if mode != "plain" else None
+    flags = B.SELECT_ENTROPY_TOPK if mode == "topk" else 0
+    ws = torch.zeros(B.workspace_bytes(cs, bt, 1, nb, k_cap), dtype=torch.uint8, device=DEV)
+    res = []
+    for fused in (False, True):
+        bud = torch.full((bt,), cut[0], device=DEV) if cut else None
+        rest = torch.full((bt,), cut[1], device=DEV) if cut else None
+        after = torch.full((bt,), -1.0, device=DEV)
+        idx = torch.zeros(bt, k_cap, dtype=torch.int32, device=DEV)
+        n_sel = torch.zeros(bt, dtype=torch.int32, device=DEV)
+        theta = torch.zeros(bt, device=DEV); b_l = torch.zeros(bt, device=DEV)
+        out = torch.zeros_like(q)
+        if fused:
+            B.decode_select_attention(cs, bt, q, kc, vc, kc.stride(0), nb, nctx, sd, stride, nb_begin, nb_end, k_cap,
+                                      bud, rest, after if cut else None, idx, n_sel, theta, b_l, out, None, ws,
+                                      flags=flags)
+        else:
+            B.select(bt, sd, stride, nb, nb_begin, nb_end, k_cap, bud, rest, idx, n_sel, theta, b_l, flags=flags)
+            B.retrieval_attention(cs, bt, 1, q, kc, vc, kc.stride(0), nb, nctx, idx, n_sel, k_cap, out, None, ws)
+            after = bud
+        torch.cuda.synchronize()
+        res.append((idx.cpu(), n_sel.cpu(), theta.cpu(), b_l.cpu(), after.cpu() if cut else None, out.float().cpu()))
+    a, b = res
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    assert torch.allclose(a[2], b[2], rtol=1e-5, atol=1e-6) and torch.allclose(a[3], b[3], rtol=1e-5, atol=1e-6)
+    if cut:
+        assert torch.allclose(a[4], b[4], rtol=1e-5, atol=1e-5)
+    assert float((a[5] - b[5]).abs().max()) <= 1e-2 * float(a[5].abs().max())
+    for s_ in range(bt):                                    # and the oracle
+        sc = scores[s_, nb_begin:nb_begin + n].astype(np.float64)
+        ids = list(range(nb_begin, nb_begin + n))
+        if n == 0:
+            assert int(b[1][s_]) == 0 and all(int(x) == -1 for x in b[0][s_])
+            continue
+        th = orc.information_density_topk(sc, k_cap) if mode == "topk" else orc.information_density(sc)
+        if cut:
+            bl = orc.layer_budget(th, cut[1], cut[0])
+            count = orc.cutoff_count(bl, k_cap, n)
+            assert abs(float(b[3][s_]) - bl) < TOL_BUDGET * max(bl, 1.0)
+        else:
+            count = min(k_cap, n)
+        assert abs(float(b[2][s_]) - th) < TOL_THETA
+        want = orc.select_blocks(scores[s_, nb_begin:nb_begin + n], ids, count)
+        assert int(b[1][s_]) == count and b[0][s_].tolist()[:count] == want
+
+
 # ---------------------------------------------------------------- cache update and representatives
 def _logical_from_blocked(kc, vc, n):
     """[nb][Hk][Bs][D], [nb][Hk][D][Bs] -> K, V [n][Hk][D]."""
