@@ -176,7 +176,8 @@ def bench_prefill(args, torch, B, H, synth):
         runner.stats.zero_()
         if bud0 is not None:
             plan.budget.copy_(bud0)
-        pipe.run(q, kc, vc, repd, out, overlap, events, args.chunk, args.score_chunk, not args.per_window_selection)
+        pipe.run(q, kc, vc, repd, out, overlap, events, args.chunk, args.score_chunk, not args.per_window_selection,
+                 args.attention_late_cus if overlap else 0)
 
     if args.pmc_pass:
         if not args.no_overlap:
@@ -238,7 +239,9 @@ def bench_prefill(args, torch, B, H, synth):
                    "windows": n_win, "mean_blocks_selected": sum(n_sel) / max(n_win, 1),
                    "launch": ("hip graph replay" if graph is not None else "eager") +
                              (f", two streams, {args.chunk} windows per call: probes, scores and selection of chunk "
-                              f"c + 1 beside the attention of chunk c ({args.attention_cus} of 256 CUs)"
+                              f"c + 1 beside the attention of chunk c ({args.attention_cus} of 256 CUs" +
+                              (f", {args.attention_late_cus} more once chunk c + 1 is prepared)"
+                               if args.attention_late_cus else ")")
                               if overlap and not args.per_window_selection else
                               f", three streams: probes, then scoring and selection ({args.score_chunk} windows per "
                               f"hand-over), then attention ({args.attention_cus} of 256 CUs, up to {args.chunk} "
@@ -307,7 +310,7 @@ def bench_prefill_layers(args, torch, B, H, synth):
             runner.stats.zero_()
             if bud0 is not None:
                 plan.budget.copy_(bud0)
-            pipe.run(q, kc, vc, repd, out, True, None, args.chunk, args.score_chunk, True)
+            pipe.run(q, kc, vc, repd, out, True, None, args.chunk, args.score_chunk, True, args.attention_late_cus)
 
     B.set_attention_cus(args.attention_cus)
     graph = None if args.eager else capture_graph(torch, one_step, out, f"prefill ({L} layers)")
@@ -608,6 +611,9 @@ def main() -> int:
     ap.add_argument("--per-window-selection", action="store_true",
                     help="prefill, with overlap: probe, score and select calls of one window each (three "
                          "streams) instead of one call per chunk of windows")
+    ap.add_argument("--attention-late-cus", type=int, default=32,
+                    help="compute units that join a chunk's attention once the next chunk is prepared "
+                         "(a second launch that drains the same queue); 0: none")
     ap.add_argument("--attention-cus", type=int, default=224,
                     help="prefill, two streams: compute units the attention may fill")
     ap.add_argument("--layers", type=int, default=1,

@@ -50,7 +50,7 @@
 extern "C" {
 #endif
 
-#define ACTQKV_VERSION 103
+#define ACTQKV_VERSION 104
 
 enum {
   ACTQKV_OK = 0,
@@ -269,6 +269,30 @@ int actqkv_retrieval_attention_per_head(const actqkv_shape* shape, int batch, in
                                         const int32_t* idx, const int32_t* n_sel, int k_cap,
                                         void* out, float* lse, void* workspace, size_t ws_bytes,
                                         void* stream);
+
+/* actqkv_retrieval_attention for a batch of windows (m > 1, bf16, head_dim 128) with the
+ * workgroups that drain its queue of (query tile, KV head) items coming in TWO launches, for a
+ * caller that keeps some compute units busy with other work (the next windows' probes, scores
+ * and selections) for part of the time: the first team (late = 0; as many workgroups as
+ * actqkv_set_attention_cus allows) starts at once, the second (late = 1; late_cus workgroups,
+ * n_kv_heads <= late_cus <= 256) whenever the caller's stream gets to it, typically behind that
+ * other work, and takes its share of whatever is left in the queue.  Nobody waits: if nothing
+ * is left the second team leaves at once.
+ *   BOTH calls must be made for every attention, with the same arguments apart from `late` and
+ *   the stream (the queue is put back to zero by the last workgroup of the two teams to leave;
+ *   a missing second call leaves it dirty for the next launch).  Either may run first; each
+ *   must be ordered behind the selection that wrote idx and n_sel.  The two share the
+ *   workspace (this is the one case where calls that overlap in time do); the next attention
+ *   on the same workspace must be ordered behind both.
+ *   The other arguments, the results and the errors as in actqkv_retrieval_attention.  Where
+ *   there is no queue (m = 1, fp32, or a workgroup per item in the first team already) the
+ *   first call is actqkv_retrieval_attention and the second does nothing. */
+int actqkv_retrieval_attention_teams(const actqkv_shape* shape, int batch, int m, const void* q,
+                                     const void* k_cache, const void* v_cache, int64_t seq_stride,
+                                     int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
+                                     const int32_t* n_sel, int k_cap, void* out, float* lse,
+                                     void* workspace, size_t ws_bytes, int late_cus, int late,
+                                     void* stream);
 
 /* The first launch of a decode step: actqkv_append_kv with m = 1 and the probe of the step's
  * one-token window (actqkv_build_probe with m = 1 and no statistics: probe = the query,

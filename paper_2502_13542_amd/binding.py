@@ -67,6 +67,8 @@ SIGNATURES = {
                                     _vp, _vp, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_decode_select_attention": (_i, [_shp, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _i64, _i, _vp, _i, _i,
                                             _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "actqkv_retrieval_attention_teams": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
+                                              _vp, _vp, _vp, _sz, _i, _i, _vp]),
     "actqkv_copy_bytes": (_i, [_vp, _vp, _sz, _vp]),
     "actqkv_gather_blocks": (_i, [_shp, _i, _vp, _vp, _i64, _i, _vp, _vp, _i, _vp, _vp, _i64, _i, _i, _vp, _vp]),
     "actqkv_last_error": (ctypes.c_char_p, []),
@@ -195,6 +197,19 @@ def decode_select_attention(shape: CShape, batch: int, q, k_cache, v_cache, seq_
         _ptr(budget_in, f), _ptr(theta_rest_sum, f), _ptr(budget_after, f), _ptr(idx, i32), _ptr(n_sel, i32),
         _ptr(theta, f), _ptr(budget, f), _ptr(out, st), _ptr(lse, f), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def retrieval_attention_teams(shape: CShape, batch: int, m: int, q, k_cache, v_cache, seq_stride: int,
+                              nb_capacity: int, n_ctx, idx, n_sel, k_cap: int, out, lse, workspace,
+                              late_cus: int, late: bool, stream=None) -> None:
+    """One of the two launches of a prefill attention whose queue workers come in two teams; see the header."""
+    st = torch.bfloat16
+    _check(load_library().actqkv_retrieval_attention_teams(
+        ctypes.byref(shape), batch, m, _ptr(q, st), _ptr(k_cache, st), _ptr(v_cache, st),
+        seq_stride, nb_capacity, _ptr(n_ctx, torch.int32), _ptr(idx, torch.int32),
+        _ptr(n_sel, torch.int32), k_cap, _ptr(out, st), _ptr(lse, torch.float32),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), int(late_cus), int(bool(late)),
+        _stream(stream)))
 
 
 def cutoff_next_step(batch: int, n_layers: int, k_mean: float, theta_prior: float, theta_prev,

@@ -108,7 +108,7 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
                                   int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
                                   const int32_t* n_sel, int k_cap, void* out, float* lse,
                                   const PfSplits& splits, float* scratch, unsigned int* counters,
-                                  float scale, int sel_per_head, hipStream_t stream);
+                                  float scale, int sel_per_head, int late_cus, int late, hipStream_t stream);
 
 // Compute units the prefill attention may fill (actqkv_set_attention_cus).
 static std::atomic<int> g_attention_cus{256};
@@ -173,17 +173,21 @@ int launch_attention_rows(const actqkv_shape& sh, int batch, int m, const void* 
 int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
                      const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
                      const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
-                     const Workspace& ws, int sel_per_head, hipStream_t stream) {
+                     const Workspace& ws, int sel_per_head, hipStream_t stream, int late_cus, int late) {
   const float scale = sh.softmax_scale > 0.f ? sh.softmax_scale : 1.f / std::sqrt(float(sh.head_dim));
   if (decode_mfma_supported(sh, m))
     return launch_attention_decode_mfma(sh, batch, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx,
                                         idx, n_sel, k_cap, out, lse, ws.scratch_f32(), ws.counters(), scale,
                                         sel_per_head, stream);
+  if (late_cus > 0 && (decode_mfma_supported(sh, m) || !prefill_mfma_supported(sh, m))) {
+    if (late) return ACTQKV_OK;   // these kernels have no queue: the first call does all the work
+    late_cus = 0;
+  }
   if (prefill_mfma_supported(sh, m))
     return launch_attention_prefill_mfma(sh, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity,
                                          n_ctx, idx, n_sel, k_cap, out, lse,
                                          prefill_splits(sh, batch, m, k_cap), ws.scratch_f32(),
-                                         ws.counters(), scale, sel_per_head, stream);
+                                         ws.counters(), scale, sel_per_head, late_cus, late, stream);
   return launch_attention_rows(sh, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx,
                                n_sel, k_cap, out, lse, scale, sel_per_head, stream);
 }
@@ -296,7 +300,8 @@ int actqkv_select(int batch, const float* scores, int64_t score_stride, int nb_c
 static int attention_checked(const actqkv_shape* shape, int batch, int m, const void* q, const void* k_cache,
                              const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
                              const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
-                             void* workspace, size_t ws_bytes, int sel_per_head, void* stream) {
+                             void* workspace, size_t ws_bytes, int sel_per_head, void* stream, int late_cus = 0,
+                             int late = 0) {
   ACTQKV_TRY(check_shape(shape));
   ACTQKV_TRY(check_batch(batch));
   if (m < 1) return set_error(ACTQKV_EINVAL, "m %d < 1", m);
@@ -329,7 +334,8 @@ static int attention_checked(const actqkv_shape* shape, int batch, int m, const 
                      need);
   Workspace ws{workspace, ws_bytes};
   return launch_attention(*shape, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx,
-                          n_sel, k_cap, out, lse, ws, sel_per_head, static_cast<hipStream_t>(stream));
+                          n_sel, k_cap, out, lse, ws, sel_per_head, static_cast<hipStream_t>(stream), late_cus,
+                          late);
 }
 
 int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, const void* q,
@@ -339,6 +345,19 @@ int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, cons
                                size_t ws_bytes, void* stream) {
   return attention_checked(shape, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx, n_sel,
                            k_cap, out, lse, workspace, ws_bytes, 0, stream);
+}
+
+int actqkv_retrieval_attention_teams(const actqkv_shape* shape, int batch, int m, const void* q,
+                                     const void* k_cache, const void* v_cache, int64_t seq_stride,
+                                     int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
+                                     const int32_t* n_sel, int k_cap, void* out, float* lse,
+                                     void* workspace, size_t ws_bytes, int late_cus, int late,
+                                     void* stream) {
+  if (shape != nullptr && (late_cus < shape->n_kv_heads || late_cus > 256))
+    return set_error(ACTQKV_EINVAL, "late_cus %d outside n_kv_heads..256", late_cus);
+  if (late != 0 && late != 1) return set_error(ACTQKV_EINVAL, "late must be 0 or 1");
+  return attention_checked(shape, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx, n_sel,
+                           k_cap, out, lse, workspace, ws_bytes, 0, stream, late_cus, late);
 }
 
 int actqkv_retrieval_attention_per_head(const actqkv_shape* shape, int batch, int m, const void* q,

@@ -87,7 +87,9 @@ struct PfParams {
   unsigned int* counters;  // one ticket counter per (sequence, query tile, KV head), zero between launches
   int m, n_q_heads, n_kv_heads, n_init, n_local;
   int s_lo, rem, slots, n_qtiles;   // pieces per query tile (PfSplits)
-  int items_per_head, wgs_per_head; // work items and workgroups of one KV head
+  int items_per_head, wgs_per_head; // work items and (first-team) workgroups of one KV head
+  int team_total;                   // workgroups of both teams together (the last one to leave resets the queue)
+  int late;                         // 1: this launch is the second team, which only draws from the queue
   int sel_per_head;                 // 1: idx and n_sel have a row per (sequence, KV head), 0: per sequence
   unsigned int* queue;              // per KV head: items handed out beyond the first round; [kPfQueueDone]: workgroups that left
   float scale_log2e;
@@ -487,21 +489,26 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_queued_kernel(Pf
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
   __shared__ int next_item;
   const int hk = blockIdx.x % p.n_kv_heads;
-  int item = blockIdx.x / p.n_kv_heads;
-  while (item < p.items_per_head) {
-    const int s = item / p.slots;
-    attn_prefill_item<true>(p, lds, hk, item - s * p.slots, s);
-    __syncthreads();                         // everybody is done with the LDS tiles of this item
+  auto draw = [&]() {
     if (threadIdx.x == 0)
       next_item = p.wgs_per_head + int(__hip_atomic_fetch_add(p.queue + hk, 1u, __ATOMIC_RELAXED,
                                                               __HIP_MEMORY_SCOPE_AGENT));
     __syncthreads();
-    item = next_item;
+    return next_item;
+  };
+  // A second team of workgroups (a launch of its own, on compute units that were busy with
+  // something else when the first team started) has no first-round items: it only draws.
+  int item = p.late ? draw() : int(blockIdx.x) / p.n_kv_heads;
+  while (item < p.items_per_head) {
+    const int s = item / p.slots;
+    attn_prefill_item<true>(p, lds, hk, item - s * p.slots, s);
+    __syncthreads();                         // everybody is done with the LDS tiles of this item
+    item = draw();
   }
   if (threadIdx.x == 0) {
     unsigned int* done = p.queue + kPfQueueDone;
     const unsigned int t = __hip_atomic_fetch_add(done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (t == gridDim.x - 1u) {
+    if (t == unsigned(p.team_total) - 1u) {
       for (int h = 0; h < p.n_kv_heads; ++h)
         __hip_atomic_store(p.queue + h, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -532,7 +539,7 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
                                   int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
                                   const int32_t* n_sel, int k_cap, void* out, float* lse,
                                   const PfSplits& splits, float* scratch, unsigned int* counters,
-                                  float scale, int sel_per_head, hipStream_t stream) {
+                                  float scale, int sel_per_head, int late_cus, int late, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_mfma_kernel),
@@ -577,6 +584,18 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
   p.items_per_head = splits.slots * batch;
   p.wgs_per_head = std::min(p.items_per_head, std::max(1, attention_cus() / sh.n_kv_heads));
   p.queue = counters + kTicketCounters;
+  int late_per_head = late_cus / sh.n_kv_heads;
+  if (p.items_per_head <= p.wgs_per_head) {          // a workgroup per item: no queue, nothing for a second team
+    if (late) return ACTQKV_OK;
+    late_per_head = 0;
+  }
+  p.team_total = (p.wgs_per_head + late_per_head) * sh.n_kv_heads;
+  p.late = late;
+  if (late) {
+    hipLaunchKernelGGL(attn_prefill_mfma_queued_kernel, dim3(late_per_head * sh.n_kv_heads), dim3(kPfThreads),
+                       kPfLdsBytes, stream, p);
+    return hip_status("attention (prefill, matrix cores, second team)");
+  }
   dim3 grid(p.wgs_per_head * sh.n_kv_heads);
   if (p.items_per_head > p.wgs_per_head)
     hipLaunchKernelGGL(attn_prefill_mfma_queued_kernel, grid, dim3(kPfThreads), kPfLdsBytes, stream, p);

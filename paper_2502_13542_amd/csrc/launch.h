@@ -81,7 +81,8 @@ int launch_select(int batch, const float* scores, int64_t score_stride, int nb_c
 int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
                      const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
                      const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
-                     const Workspace& ws, int sel_per_head, hipStream_t stream);
+                     const Workspace& ws, int sel_per_head, hipStream_t stream, int late_cus = 0,
+                     int late = 0);   // late_cus > 0: the queue's workgroups come in two launches
 int launch_score_per_head(const actqkv_shape& sh, int batch, const float* probe, const void* rep_keys,
                           int64_t seq_stride, int nb_capacity, int nb_begin, const int32_t* nb_end,
                           float* scores, int64_t score_stride, hipStream_t stream);

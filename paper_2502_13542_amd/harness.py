@@ -223,6 +223,7 @@ class PrefillPipeline:
         ws = max(B.workspace_bytes(runner.cs, n, runner.m, runner.nb_capacity, runner.k_cap)
                  for n in (1, 2, self.MAX_CHUNK))
         self.ws_attn = torch.zeros(ws, dtype=torch.uint8, device=dev)
+        self.ws_attn_b = torch.zeros(ws, dtype=torch.uint8, device=dev)   # two teams: chunks alternate workspaces
         self.side = torch.cuda.Stream(device=dev)
         # the probe of every window, for the schedule that scores behind the probe chain
         dk = runner.shape.n_kv_heads * runner.shape.head_dim
@@ -237,7 +238,8 @@ class PrefillPipeline:
                                                       runner.k_cap), dtype=torch.uint8, device=dev)
 
     def run(self, q: torch.Tensor, k_cache, v_cache, rep_keys, out: torch.Tensor, overlap: bool = True,
-            events=None, chunk: int = 32, score_chunk: int = 16, batched: bool = False) -> None:
+            events=None, chunk: int = 32, score_chunk: int = 16, batched: bool = False,
+            late_cus: int = 0) -> None:
         """q, out [N][H][D].  events: optional per-window (start, end) event pairs recorded around
         the attention call of a window; with overlap, the pair of a chunk's first window brackets
         the chunk's one call, on the stream it runs on.  chunk: with overlap, the second stream picks up
@@ -246,14 +248,15 @@ class PrefillPipeline:
         windows are batch entries that share the cache; with that many query tiles in a launch
         the key tiles need not be cut into pieces, so nothing has to be merged).  score_chunk > 0
         (with overlap) also moves scoring and selection to a stream of their own, that many
-        windows behind the probes (see _run_three_streams); 0 keeps them on the current stream."""
+        windows behind the probes (see _run_three_streams); 0 keeps them on the current stream.
+        late_cus > 0 (batched only): see _run_batched."""
         r, plan = self.runner, self.plan
         sh, cs = r.shape, r.cs
         nb_begin = sh.n_init // sh.block_size
         cur = torch.cuda.current_stream()
         chunk = max(1, min(chunk, self.MAX_CHUNK))
         if overlap and batched:
-            return self._run_batched(q, k_cache, v_cache, rep_keys, out, events, chunk)
+            return self._run_batched(q, k_cache, v_cache, rep_keys, out, events, chunk, late_cus)
         if overlap and score_chunk > 0:
             return self._run_three_streams(q, k_cache, v_cache, rep_keys, out, events, chunk, score_chunk)
 
@@ -311,7 +314,7 @@ class PrefillPipeline:
         if overlap:
             cur.wait_stream(self.side)
 
-    def _run_batched(self, q, k_cache, v_cache, rep_keys, out, events, chunk) -> None:
+    def _run_batched(self, q, k_cache, v_cache, rep_keys, out, events, chunk, late_cus=0) -> None:
         """A chunk of windows per call, for every step of the path.  The running statistics of
         Eq. (8) are the only thing a window hands to the next one within a layer, and merging a
         window into them needs nothing but that window's own moments; scores, density, budget
@@ -319,7 +322,15 @@ class PrefillPipeline:
         windows go through one build_probe call (ACTQKV_PROBE_WINDOW_CHAIN), one score_blocks
         and one select call on the current stream, and one attention call on the second stream,
         which works on chunk c while the current stream prepares chunk c + 1.  A ragged last
-        window goes through calls of its own."""
+        window goes through calls of its own.
+
+        late_cus > 0: the attention leaves that many compute units to the current stream (the
+        library's attention_cus setting), but the current stream needs them only while it
+        prepares the next chunk; behind that preparation it launches a second team of late_cus
+        attention workgroups for the chunk the second stream is working on
+        (actqkv_retrieval_attention_teams), which take their share of what is left in its queue.
+        Chunks alternate between two workspaces, so a chunk's queue is never touched by the
+        next chunk's launches."""
         r, plan = self.runner, self.plan
         sh, cs = r.shape, r.cs
         nb_begin = sh.n_init // sh.block_size
@@ -339,7 +350,7 @@ class PrefillPipeline:
             B.select(1, r.scores, r.score_stride, nb_cap, nb_begin, plan.nb_end[u:u + 1], r.k_cap, bud,
                      rest, self.idx[u], self.n_sel[u:u + 1], None, None)
 
-        t0 = 0
+        t0, n_chunks, pending = 0, 0, None
         while t0 < plan.n_windows:
             n_p = 0
             while t0 + n_p < plan.n_windows and n_p < chunk and plan.rows[t0 + n_p] == r.m:
@@ -361,17 +372,31 @@ class PrefillPipeline:
                 single(t0)
             selected = torch.cuda.Event()
             selected.record(cur)
+            if pending is not None:
+                # the chunk before this one is being attended to on the second stream: now that this
+                # chunk is prepared, its compute units can help there
+                B.retrieval_attention_teams(*pending, late_cus, True, cur)
+                pending = None
             last.wait_event(selected)
             self.chunk_starts.append(t0)
             if events is not None:
                 events[t0][0].record(last)
             w0, rows = plan.w0[t0], plan.rows[t0]
-            B.retrieval_attention(cs, n_p, rows, q[w0:w0 + n_p * rows], k_cache, v_cache, 0, r.nb_capacity,
-                                  plan.n_ctx[t0:t0 + n_p], self.idx[t0:t0 + n_p], self.n_sel[t0:t0 + n_p],
-                                  r.k_cap, out[w0:w0 + n_p * rows], None, self.ws_attn, last)
+            call = (cs, n_p, rows, q[w0:w0 + n_p * rows], k_cache, v_cache, 0, r.nb_capacity,
+                    plan.n_ctx[t0:t0 + n_p], self.idx[t0:t0 + n_p], self.n_sel[t0:t0 + n_p],
+                    r.k_cap, out[w0:w0 + n_p * rows], None)
+            call += (self.ws_attn if n_chunks % 2 == 0 else self.ws_attn_b,)
+            if late_cus > 0:
+                B.retrieval_attention_teams(*call, late_cus, False, last)
+                pending = call
+            else:
+                B.retrieval_attention(*call, last)
+            n_chunks += 1
             if events is not None:
                 events[t0][1].record(last)
             t0 += n_p
+        if pending is not None:
+            B.retrieval_attention_teams(*pending, late_cus, True, cur)
         cur.wait_stream(last)
 
     def _run_three_streams(self, q, k_cache, v_cache, rep_keys, out, events, chunk, score_chunk) -> None:

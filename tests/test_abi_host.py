@@ -183,6 +183,16 @@ def test_decode_select_attention_rejects(lib):
     assert call(shape=fp32) == -2                                               # a bf16, head_dim 128 kernel
 
 
+def test_retrieval_attention_teams_rejects(lib):
+    cs = B.c_shape(LLAMA)
+    call = lambda **k: lib.actqkv_retrieval_attention_teams(
+        ctypes.byref(cs), 32, 512, k.get("q", A16), A16, A16, 0, 1024, A16, A16, A16, 32, k.get("out", A16), None,
+        k.get("ws", A16), k.get("wsb", 1 << 30), k.get("late_cus", 32), k.get("late", 0), None)
+    assert call(late_cus=0) == -1 and call(late_cus=4) == -1 and call(late_cus=300) == -1 and call(late=2) == -1
+    assert call(q=None) == -1 and call(out=A16 + 2) == -3 and call(ws=None) == -4 and call(wsb=8) == -4
+    assert call(late=1, q=None) == -1                       # the second call checks its arguments too
+
+
 def test_cutoff_next_step_rejects(lib):
     f = ctypes.c_float
     call = lambda batch=2, L=32, k=8.0, prior=6.0, prev=A16, ts=A16, ns=A16, b=A16, r=A16: \

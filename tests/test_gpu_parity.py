@@ -129,7 +129,8 @@ def test_c3_128k_two_stream_pipeline_as_benchmarked():
     bench.py times: (1) three streams, calls of one window each: probes, then scoring and
     selection 16 windows behind them, then the attention of up to 32 windows per launch with 224
     of the 256 compute units; (2) the same with scoring and selection on the probes' stream;
-    (3) one probe, one score, one select and one attention call per 32 windows.  Every window's
+    (3) one probe, one score, one select and one attention call per 32 windows; (4) the same with a
+    second team of attention workgroups per chunk.  Every window's
     selection must equal the one found in window order; the attention of sampled windows is
     checked against the oracle and all rows against the window-order result."""
     w = synth.WORKLOADS["c3_128k"]
@@ -199,6 +200,24 @@ def test_c3_128k_two_stream_pipeline_as_benchmarked():
         same_rows[plan.w0[t]:plan.w0[t] + plan.rows[t]] = False
     diff_c = (out_c.float() - out_order.float()).abs().amax(dim=(1, 2)).cpu()[same_rows].max().item()
     assert diff_c <= TOL_OUT["bf16"] * scale, f"chunked calls vs window order: {diff_c}"
+    # (4) the same with a second team of 32 attention workgroups that joins each chunk's queue
+    # once the next chunk is prepared: the same items, whoever takes them, so the same bits;
+    # twice in a row, so that a queue left dirty would show
+    for rep_run in range(2):
+        out_d = torch.zeros_like(qd)
+        runner.reset()
+        plan.budget.copy_(bud0)
+        idx_c = pipe.idx.clone()
+        pipe.idx.fill_(-1)
+        B.set_attention_cus(224)
+        try:
+            pipe.run(qd, kc, vc, repd, out_d, overlap=True, batched=True, late_cus=32)
+            torch.cuda.synchronize()
+        finally:
+            B.set_attention_cus(256)
+        assert torch.equal(pipe.idx, idx_c) and torch.equal(pipe.n_sel, nsel_order)
+        assert torch.equal(out_d, out_c), f"two teams of attention workgroups, run {rep_run}"
+        assert not pipe.ws_attn[:8192].any() and not pipe.ws_attn_b[:8192].any()   # tickets and queue back at zero
     out_two = out_c
     attend = [3, 130, 255]
     want = oracle_windows(q, k, v, rep, sh, w.window, w.k_cap, cutoffs, attend)
