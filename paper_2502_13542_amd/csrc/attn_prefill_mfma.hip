@@ -43,6 +43,7 @@ constexpr int kPfLdsBytes = 2 * 2 * kTileElems * 2 + kPfMaxTiles * 12;  // 2 sta
 constexpr int kPfPartWords = 17;                     // 64-bit words per lane: 16 x 4 bf16 + (max, sum)
 constexpr int kMaxPfSplits = 8;
 constexpr float kLazyMaxLog2 = 8.f;                  // how far a tile's maximum may exceed the reference one
+constexpr int kPfOrderMax = 64;                      // batch entries the queue hands out longest first
 constexpr int kPfQueueDone = 128;                    // index of the "left" counter behind the per-head queue counters
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -496,12 +497,37 @@ __global__ __launch_bounds__(kPfThreads) void attn_prefill_mfma_queued_kernel(Pf
     __syncthreads();
     return next_item;
   };
+  // Longest items first, so that the launch does not end with a few workgroups on long items
+  // while the others have left: the batch entries in descending order of the number of blocks
+  // they retrieve (ties: ascending index), and within an entry the later query tiles, which see
+  // more of the window, before the earlier ones.
+  __shared__ int order[kPfOrderMax];
+  const int batch = p.items_per_head / p.slots;
+  const bool sorted = batch <= kPfOrderMax;
+  if (sorted) {
+    const int t = threadIdx.x;
+    if (t < batch) {
+      const size_t stride = p.sel_per_head ? p.n_kv_heads : 1, off = p.sel_per_head ? hk : 0;
+      const int mine = p.n_sel[size_t(t) * stride + off];
+      int rank = 0;
+      for (int j = 0; j < batch; ++j) {
+        const int other = p.n_sel[size_t(j) * stride + off];
+        rank += (other > mine) || (other == mine && j < t);
+      }
+      order[rank] = t;
+    }
+    __syncthreads();
+  }
   // A second team of workgroups (a launch of its own, on compute units that were busy with
   // something else when the first team started) has no first-round items: it only draws.
   int item = p.late ? draw() : int(blockIdx.x) / p.n_kv_heads;
   while (item < p.items_per_head) {
-    const int s = item / p.slots;
-    attn_prefill_item<true>(p, lds, hk, item - s * p.slots, s);
+    int s = item / p.slots, slot = item - s * p.slots;
+    if (sorted) {
+      s = order[s];
+      slot = p.slots - 1 - slot;
+    }
+    attn_prefill_item<true>(p, lds, hk, slot, s);
     __syncthreads();                         // everybody is done with the LDS tiles of this item
     item = draw();
   }
