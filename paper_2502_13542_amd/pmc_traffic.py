@@ -53,6 +53,9 @@ def main() -> int:
     ap.add_argument("--copy-bytes", type=int, default=256 << 20)
     ap.add_argument("--summary", required=True)
     ap.add_argument("--command", default="")
+    ap.add_argument("--calls", type=int, default=0,
+                    help="attention calls in the pass, if a call is more than one dispatch of the kernel "
+                         "(two teams of workgroups); default: one call per dispatch")
     args = ap.parse_args()
 
     fetch, write = per_kernel(args.fetch, "FETCH_SIZE"), per_kernel(args.write, "WRITE_SIZE")
@@ -80,9 +83,11 @@ def main() -> int:
     launches = len(fetch.get(main_kernel, []))
     if launches == 0:
         raise SystemExit(f"no {main_kernel} dispatch in the counter files")
+    if args.calls > 0:
+        launches = args.calls
     f_bytes = sum(sum(fetch.get(k, [])) for k in parts) * f_scale / launches
     w_bytes = sum(sum(write.get(k, [])) for k in parts) * w_scale / launches
-    lines += ["", f"Attention launch ({' + '.join(parts)}), mean over {launches} launches: "
+    lines += ["", f"Attention call ({' + '.join(parts)}), mean over {launches} calls: "
                   f"fetch {f_bytes / 1e6:.3f} MB, write {w_bytes / 1e6:.3f} MB."]
     os.makedirs(os.path.dirname(os.path.abspath(args.summary)), exist_ok=True)
     with open(args.summary, "w") as f:
