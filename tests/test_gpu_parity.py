@@ -859,13 +859,16 @@ def test_pipeline_with_ragged_last_window_and_short_context():
         bud0 = plan.budget.clone()
         pipe = H.PrefillPipeline(runner, plan)
         outs = []
-        for overlap, batched in ((False, False), (True, False), (True, True)):
+        # the last schedule asks for a second team of attention workgroups: with 4 windows per call
+        # there is no queue (a workgroup per item), so the second call of each pair does nothing
+        for overlap, batched, late in ((False, False, 0), (True, False, 0), (True, True, 0), (True, True, 32)):
             runner.reset()
             plan.budget.copy_(bud0)
             out = torch.zeros_like(qd)
             B.set_attention_cus(224 if overlap else 256)
             try:
-                pipe.run(qd, kc, vc, repd, out, overlap=overlap, chunk=4, score_chunk=4, batched=batched)
+                pipe.run(qd, kc, vc, repd, out, overlap=overlap, chunk=4, score_chunk=4, batched=batched,
+                         late_cus=late)
                 torch.cuda.synchronize()
             finally:
                 B.set_attention_cus(256)
