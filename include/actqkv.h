@@ -280,7 +280,8 @@ int actqkv_retrieval_attention_per_head(const actqkv_shape* shape, int batch, in
  * is left the second team leaves at once.
  *   BOTH calls must be made for every attention, with the same arguments apart from `late` and
  *   the stream (the queue is put back to zero by the last workgroup of the two teams to leave;
- *   a missing second call leaves it dirty for the next launch).  Either may run first; each
+ *   a missing second call leaves it dirty for the next launch), and with the same
+ *   actqkv_set_attention_cus setting in force.  Either may run first; each
  *   must be ordered behind the selection that wrote idx and n_sel.  The two share the
  *   workspace (this is the one case where calls that overlap in time do); the next attention
  *   on the same workspace must be ordered behind both.
