@@ -30,6 +30,20 @@ def test_exports_every_declared_symbol(lib):
     assert lib.actqkv_version() == int(re.search(r"#define ACTQKV_VERSION (\d+)", text).group(1))
 
 
+def test_header_is_plain_c(tmp_path):
+    """include/actqkv.h compiles as C99 with warnings on (no C++ or HIP types in the signatures)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "actqkv.h"\nint use(void) { return actqkv_version() > 0 ? ACTQKV_OK : ACTQKV_EINVAL; }\n')
+    res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                          "-c", str(src), "-o", str(tmp_path / "use_header.o")], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+
+
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(B.CShape) == 40
     assert B.CShape.softmax_scale.offset == 32 and B.CShape.var_eps.offset == 36
