@@ -254,7 +254,10 @@ def bench_prefill(args, torch, B, H, synth):
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, **traffic_fields(w.name),
                      "kernel": ("actqkv_retrieval_attention launches of up to %d windows "
-                                "(attn_prefill_mfma_queued_kernel)" % args.chunk) if overlap else
+                                "(attn_prefill_mfma_queued_kernel%s)" %
+                                (args.chunk, "; timed: the first team's launch of %d workgroups, with which the "
+                                             "second team of %d ends" % (args.attention_cus, args.attention_late_cus)
+                                 if args.attention_late_cus and not args.per_window_selection else "")) if overlap else
                                "actqkv_retrieval_attention launch (attn_prefill_mfma_kernel)",
                      "avg_launch_us": attn_ms * 1e3 / n_launch,
                      "windows_per_launch": n_win / n_launch,
