@@ -101,7 +101,9 @@ typedef struct actqkv_shape {
  * Zero-fill it before the first window. */
 size_t actqkv_stats_floats(const actqkv_shape* shape);
 
-/* Bytes of workspace that any of the calls below may need for these sizes.  The
+/* Bytes of workspace that any of the calls below may need for these sizes or smaller
+ * ones: every call with 1 .. batch entries and windows of 1 .. m tokens (a layer's ragged
+ * last window, a decode step) is served by a workspace of this size.  The
  * workspace must be zero-filled once after allocation (the kernels leave the
  * counters it holds at zero); calls sharing one workspace must be ordered on
  * one stream. */

@@ -151,6 +151,7 @@ int launch_attention_decode_select(const actqkv_shape& sh, int batch, const void
                                    int32_t* n_sel, float* theta, float* budget, void* out, float* lse,
                                    float* scratch, unsigned int* counters, float scale, hipStream_t stream);
 
+// what exactly this (batch, m) needs
 size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap) {
   (void)nb_capacity;
   size_t probe = probe_call_floats(sh, batch, m) * sizeof(float);
@@ -163,6 +164,21 @@ size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity
       attn = size_t(batch) * sh.n_kv_heads * splits.slots * kPfPartialFloats * sizeof(float);
   }
   return kCounterBytes + align_up(probe > attn ? probe : attn, 256);
+}
+
+// What a caller should allocate: enough for every call with 1 .. batch entries and windows of
+// 1 .. m tokens.  The need is not monotone: few short windows are cut into many pieces with
+// partial results, many long ones into none, and a window too long for the matrix-core kernel
+// needs no scratch at all; so a workspace sized for a layer's nominal window must also serve
+// its ragged last window and a decode step.
+static size_t workspace_bytes_upto(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap) {
+  size_t need = 0;
+  for (int b = 1; b <= batch; ++b) {
+    need = std::max(need, workspace_bytes(sh, b, 1, nb_capacity, k_cap));
+    for (int mm = 32; mm < m + 32; mm += 32)       // query tiles are multiples of 32 positions
+      need = std::max(need, workspace_bytes(sh, b, std::min(mm, m), nb_capacity, k_cap));
+  }
+  return need;
 }
 
 int launch_attention_rows(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
@@ -218,7 +234,7 @@ size_t actqkv_workspace_bytes(const actqkv_shape* shape, int batch, int m, int n
     set_error(ACTQKV_EINVAL, "workspace_bytes: bad batch/m/nb_capacity/k_cap");
     return 0;
   }
-  return workspace_bytes(*shape, batch, m, nb_capacity, k_cap);
+  return workspace_bytes_upto(*shape, batch, m, nb_capacity, k_cap);
 }
 
 int actqkv_build_probe(const actqkv_shape* shape, int batch, int m, const void* q_win, float* stats,

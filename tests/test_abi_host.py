@@ -68,6 +68,19 @@ def _probe(lib, cs, **kw):
                                   a["probe"], a["pkv"], a["pn"], a["w"], a["ws"], a["wsb"], None)
 
 
+def test_workspace_serves_smaller_calls(lib):
+    """A workspace sized for (batch, m) is at least what any call with fewer entries or shorter
+    windows asks for: few short windows need partial results, many long ones none, and a
+    window too long for the matrix-core kernel needs no attention scratch at all."""
+    for sh in (LLAMA, LayerShape(8, 2, 128, 128, 4, 128, 256, "bf16"), LayerShape(8, 2, 64, 128, 4, 128, 256, "fp32")):
+        cs = B.c_shape(sh)
+        for batch, m in ((32, 512), (1, 4096), (4, 2048), (16, 1)):
+            big = B.workspace_bytes(cs, batch, m, 1024, 32)
+            for b2 in sorted({1, 2, batch // 2 or 1, batch}):
+                for m2 in sorted({1, 77, 128, m // 2 or 1, m}):
+                    assert B.workspace_bytes(cs, b2, m2, 1024, 32) <= big, (sh, batch, m, b2, m2)
+
+
 def test_build_probe_rejects(lib):
     cs = B.c_shape(LLAMA)
     assert _probe(lib, cs, batch=0) == -1

@@ -1,5 +1,6 @@
 """GPU parity: every entry point of libactqkv.so against the CPU oracle, element by
 element, on the same seeded inputs.  All calls go through the C ABI (ctypes binding)."""
+import ctypes
 import math
 
 import numpy as np
@@ -253,6 +254,48 @@ def test_geometry_variants(n_init, n_local):
     w = synth.Workload(f"geom_{n_init}_{n_local}", sh, 2048 + 50, 128, 4, False, 99 + n_init + n_local,
                        outlier_rate=0.03, outlier_kind="boost", n_planted=3)
     run_prefill_case(w)
+
+
+@pytest.mark.parametrize("m,n_ctx,attend", [(2048, 3 * 2048 + 300, [1, 3]), (4096, 2 * 4096 + 128, [1, 2])])
+def test_windows_larger_than_the_benchmarked_one(m, n_ctx, attend):
+    """Windows of 2048 tokens (16 key tiles of the window itself: still the matrix-core kernel) and
+    of 4096 (more tiles than its tile table holds: the row kernel), bf16, ragged last window;
+    probes, scores and selections of every window, attention of the windows in `attend`."""
+    sh = LayerShape(8, 2, 128, 128, 4, 128, 256, "bf16")
+    w = synth.Workload(f"window_{m}", sh, n_ctx, m, 6, True, 4242 + m, n_planted=4)
+    run_prefill_case(w, attend=attend)
+
+
+def test_probe_of_the_largest_window():
+    """actqkv_build_probe with m = 8192, the largest window the library takes, against the oracle
+    (statistics of two windows, bias, weights, probe)."""
+    m, hq, hkv, d = 8192, 4, 2, 64
+    sh = LayerShape(hq, hkv, d, 128, 4, 128, 256, "fp32")
+    cs = B.c_shape(sh)
+    g = torch.Generator().manual_seed(8192)
+    q = torch.randn(2 * m, hq, d, generator=g) * 1.3 + 0.2
+    q[torch.randperm(2 * m, generator=g)[:200], :, 5] *= 9.0                    # outlier tokens
+    qd = q.to(DEV)
+    runner = H.LayerRunner(sh, 1, m, 8, 4, DEV)
+    wts = torch.zeros(1, m, device=DEV)
+    stats = orc.RunningStats(hq * d)
+    for t in range(2):
+        B.build_probe(cs, 1, m, qd[t * m:(t + 1) * m], runner.stats, True, runner.probe, runner.probe_kv,
+                      runner.probe_norm, wts, runner.workspace)
+        torch.cuda.synchronize()
+        qw = f64(q[t * m:(t + 1) * m]).reshape(m, -1)
+        z_bar, sigma2 = stats.update(qw)
+        probe, weights = orc.probe_query(qw, orc.activation_bias(qw, z_bar, sigma2))
+        assert rel_to_max(runner.probe[0], probe) < TOL_PROBE, f"probe, window {t}"
+        assert rel_to_max(wts[0], weights) < TOL_WEIGHT, f"weights, window {t}"
+        assert abs(float(wts.sum()) - 1.0) < 1e-4
+    assert lib_rejects_window(cs, m + 1)
+
+
+def lib_rejects_window(cs, m):
+    lib = B.load_library()
+    rc = lib.actqkv_build_probe(ctypes.byref(cs), 1, m, 16, 16, 1, 16, 16, 16, None, 16, 1 << 30, None)
+    return rc == -2
 
 
 def test_context_shorter_than_init():
