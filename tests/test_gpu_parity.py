@@ -631,6 +631,47 @@ def test_decode_attention_that_selects_for_itself(n, k_cap, mode):
         assert int(b[1][s_]) == count and b[0][s_].tolist()[:count] == want
 
 
+def test_largest_batch_of_a_decode_step():
+    """1024 sequences (the largest batch the library takes) through the decode step in two
+    launches: short ragged contexts, selections against the oracle's rule on the GPU's scores,
+    outputs against a plain softmax attention over the keys each sequence sees."""
+    sh = LayerShape(8, 2, 128, 128, 4, 128, 256, "bf16")
+    bt, nb, k_cap = 1024, 8, 3
+    g = torch.Generator(device=DEV).manual_seed(1024)
+    kc = torch.randn(bt, nb, 2, 128, 128, generator=g, device=DEV).to(torch.bfloat16)
+    vc = torch.randn(bt, nb, 2, 128, 128, generator=g, device=DEV).to(torch.bfloat16)
+    rep = torch.randn(bt, nb, 4, 2, 128, generator=g, device=DEV).to(torch.bfloat16)
+    q = torch.randn(bt, 1, 8, 128, generator=g, device=DEV).to(torch.bfloat16)
+    n_ctx_h = [1 + (37 * s) % (nb * 128 - 1) for s in range(bt)]
+    n_ctx = torch.tensor(n_ctx_h, dtype=torch.int32, device=DEV)
+    nb_end_h = [H.eligible_range(sh, n - 1)[1] for n in n_ctx_h]
+    nb_end = torch.tensor(nb_end_h, dtype=torch.int32, device=DEV)
+    runner = H.LayerRunner(sh, bt, 1, nb, k_cap, DEV)
+    out = torch.zeros_like(q)
+    runner.decode_step_two_launches(q, kc, vc, rep, n_ctx, nb_end, out)
+    torch.cuda.synchronize()
+    scores, idx, n_sel = runner.scores.cpu().numpy(), runner.idx.cpu().tolist(), runner.n_sel.cpu().tolist()
+    assert bool(torch.isfinite(out.float()).all())
+    for s in range(0, bt, 41):
+        n, e = n_ctx_h[s], nb_end_h[s]
+        elig = list(range(1, e))
+        want = orc.select_blocks(scores[s, 1:e], elig, min(k_cap, len(elig))) if elig else []
+        assert n_sel[s] == len(want) and idx[s][:n_sel[s]] == want, f"sequence {s}"
+        l0 = H.local_start(sh, n - 1)
+        pos = list(range(0, min(sh.n_init, n - 1)))
+        for b in want:
+            pos += list(range(b * 128, b * 128 + 128))
+        pos += list(range(l0, n))
+        pos = torch.tensor(sorted(set(pos)), device=DEV)
+        K = kc[s][pos // 128, :, pos % 128, :].float()
+        V = vc[s][pos // 128, :, :, pos % 128].float()
+        qq = q[s, 0].float().reshape(2, 4, 128)
+        p = torch.softmax(torch.einsum("hgd,nhd->hgn", qq, K) / 128 ** 0.5, dim=-1)
+        ref = torch.einsum("hgn,nhd->hgd", p, V).reshape(8, 128)
+        err = ((out[s, 0].float() - ref).abs().amax(dim=-1) / ref.abs().amax(dim=-1)).max().item()
+        assert err < TOL_OUT["bf16"], f"sequence {s}: {err}"
+
+
 # ---------------------------------------------------------------- cache update and representatives
 def _logical_from_blocked(kc, vc, n):
     """[nb][Hk][Bs][D], [nb][Hk][D][Bs] -> K, V [n][Hk][D]."""
