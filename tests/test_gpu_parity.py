@@ -298,6 +298,41 @@ def lib_rejects_window(cs, m):
     return rc == -2
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp32", 64)])
+def test_attention_over_the_largest_selection(dtype, d):
+    """A window that retrieves 64 blocks (the largest k_cap), in a batch of two windows of one
+    sequence with different selections; the second one's idx holds out-of-range and negative
+    entries, which count as empty blocks (device-side values cannot cause an access out of bounds)."""
+    sh = LayerShape(8, 2, d, 128, 4, 128, 256, dtype)
+    cs = B.c_shape(sh)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    m, k_cap, n_tok = 256, 64, 80 * 128 + 2 * 256
+    nb = n_tok // 128
+    g = torch.Generator().manual_seed(64 + d)
+    q = torch.randn(2 * m, 8, d, generator=g).to(td)
+    k = torch.randn(n_tok, 2, d, generator=g).to(td)
+    v = torch.randn(n_tok, 2, d, generator=g).to(td)
+    w0 = [n_tok - 2 * m, n_tok - m]
+    kc, vc = H.blocked_k(k.to(DEV), sh, nb), H.blocked_vt(v.to(DEV), sh, nb)
+    b, e = H.eligible_range(sh, w0[0])
+    sel = (torch.randperm(e - b, generator=g)[:k_cap] + b).tolist()
+    idx = torch.full((2, k_cap), -1, dtype=torch.int32)
+    idx[0] = torch.tensor(sel, dtype=torch.int32)
+    idx[1, :5] = torch.tensor([3, 10 ** 6, -7, 2, nb + 1], dtype=torch.int32)      # only blocks 3 and 2 exist
+    n_sel = torch.tensor([k_cap, 5], dtype=torch.int32)
+    n_ctx = torch.tensor([w0[0] + m, w0[1] + m], dtype=torch.int32)
+    out = torch.zeros(2 * m, 8, d, dtype=td, device=DEV)
+    ws = torch.zeros(B.workspace_bytes(cs, 2, m, nb, k_cap), dtype=torch.uint8, device=DEV)
+    B.retrieval_attention(cs, 2, m, q.to(DEV), kc, vc, 0, nb, n_ctx.to(DEV), idx.to(DEV), n_sel.to(DEV), k_cap, out,
+                          None, ws)
+    torch.cuda.synchronize()
+    for i, chosen in enumerate((sel, [3, 2])):
+        ref = orc.retrieval_attention_window(f64(q[i * m:(i + 1) * m]), f64(k), f64(v), w0[i], chosen, sh.n_init,
+                                             sh.n_local, 128, sh.group)
+        err = out_error(out[i * m:(i + 1) * m], ref)
+        assert err < TOL_OUT[dtype], f"window {i}: {err}"
+
+
 def test_context_shorter_than_init():
     sh = LayerShape(4, 2, 64, 128, 2, 128, 128, "fp32")
     w = synth.Workload("tiny", sh, 100, 128, 4, False, 5, outlier_kind="boost", n_planted=0)
