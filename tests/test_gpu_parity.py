@@ -737,6 +737,8 @@ def _check_reps(rep_gpu, k_all_cpu, sh, n_tokens):
     ("bf16", 32, 8, 128, [512, 512, 512, 77]),          # aligned windows and a ragged tail
     ("bf16", 32, 8, 128, [100, 1, 1, 300, 27, 1]),      # unaligned pieces, single tokens
     ("fp32", 8, 2, 64, [256, 256, 130]),
+    ("bf16", 8, 2, 128, [77, 8192, 3000]),              # the largest window, starting inside a block
+    ("fp32", 4, 2, 64, [5000, 1]),
 ])
 def test_append_kv_builds_the_cache_and_the_representatives(dtype, hq, hkv, d, chunks):
     sh = LayerShape(hq, hkv, d, 128, 4, 128, 256, dtype)
