@@ -333,6 +333,14 @@ def test_attention_over_the_largest_selection(dtype, d):
         assert err < TOL_OUT[dtype], f"window {i}: {err}"
 
 
+@pytest.mark.parametrize("dtype,d,m,n_ctx", [("bf16", 128, 2, 700), ("bf16", 128, 33, 1500), ("fp32", 64, 3, 500)])
+def test_tiny_windows(dtype, d, m, n_ctx):
+    """Windows of 2, 3 and 33 tokens (most rows of a query tile idle, a ragged last window)."""
+    sh = LayerShape(8, 2, d, 128, 4, 128, 256, dtype)
+    w = synth.Workload(f"tiny_window_{m}", sh, n_ctx, m, 2, True, 77 + m, n_planted=2)
+    run_prefill_case(w, attend=[0, w.n_windows // 2, w.n_windows - 1])
+
+
 def test_context_shorter_than_init():
     sh = LayerShape(4, 2, 64, 128, 2, 128, 128, "fp32")
     w = synth.Workload("tiny", sh, 100, 128, 4, False, 5, outlier_kind="boost", n_planted=0)
