@@ -912,6 +912,42 @@ def test_decode_retrieve_equals_the_four_calls(dtype, hq, hkv, d, update):
         assert not torch.equal(res[1][-1][3, 68], rep0[3, 68])            # representatives of the completed block
 
 
+def test_decode_step_on_a_cache_of_one_block():
+    """The first tokens of a sequence: one cache block, nothing eligible.  The two-launch step
+    writes the token, the probe and an empty selection, and attends over what is there."""
+    sh = LayerShape(8, 2, 128, 128, 4, 128, 256, "bf16")
+    cs = B.c_shape(sh)
+    bt, nb, k_cap = 3, 1, 4
+    g = torch.Generator().manual_seed(9)
+    pos = [0, 5, 127]
+    k = torch.randn(bt, 128, 2, 128, generator=g).to(torch.bfloat16)
+    v = torch.randn(bt, 128, 2, 128, generator=g).to(torch.bfloat16)
+    q = torch.randn(bt, 1, 8, 128, generator=g).to(torch.bfloat16).to(DEV)
+    kc = torch.zeros(bt, nb, 2, 128, 128, dtype=torch.bfloat16, device=DEV)
+    vc = torch.zeros(bt, nb, 2, 128, 128, dtype=torch.bfloat16, device=DEV)
+    for s, p_ in enumerate(pos):                           # the cache holds the tokens before the new one
+        kc[s] = H.blocked_k(torch.cat([k[s, :p_], torch.zeros(128 - p_, 2, 128, dtype=torch.bfloat16)]).to(DEV), sh, nb)
+        vc[s] = H.blocked_vt(torch.cat([v[s, :p_], torch.zeros(128 - p_, 2, 128, dtype=torch.bfloat16)]).to(DEV), sh, nb)
+    rep = torch.zeros(bt, nb, 4, 2, 128, dtype=torch.bfloat16, device=DEV)
+    k_new = torch.stack([k[s, p_] for s, p_ in enumerate(pos)]).unsqueeze(1).to(DEV)
+    v_new = torch.stack([v[s, p_] for s, p_ in enumerate(pos)]).unsqueeze(1).to(DEV)
+    i32 = dict(dtype=torch.int32, device=DEV)
+    runner = H.LayerRunner(sh, bt, 1, nb, k_cap, DEV)
+    out = torch.zeros_like(q)
+    runner.idx.fill_(7)
+    runner.decode_step_two_launches(q, kc, vc, rep, torch.tensor([p_ + 1 for p_ in pos], **i32),
+                                    torch.tensor([1] * bt, **i32), out, None, None, None, k_new, v_new,
+                                    torch.tensor(pos, **i32))
+    torch.cuda.synchronize()
+    assert runner.n_sel.cpu().tolist() == [0] * bt and bool((runner.idx == -1).all())
+    assert torch.equal(runner.probe.cpu(), q.float().reshape(bt, -1).cpu())
+    assert rep[2].any() and not rep[:2].any()              # position 127 completes the block: representatives picked
+    for s, p_ in enumerate(pos):
+        res = orc.decode_step(f64(q[s, 0].cpu()), f64(k[s, :p_ + 1]), f64(v[s, :p_ + 1]), np.zeros((0, 4, 2, 128)),
+                              p_ + 1, sh.n_init, sh.n_local, 128, k_cap, None)
+        assert out_error(out[s, 0], res["out"]) < TOL_OUT["bf16"], f"sequence {s}"
+
+
 def test_append_kv_drops_tokens_behind_the_capacity():
     sh = LayerShape(8, 2, 64, 128, 4, 128, 256, "fp32")
     cs = B.c_shape(sh)
