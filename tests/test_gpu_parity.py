@@ -341,6 +341,55 @@ def test_tiny_windows(dtype, d, m, n_ctx):
     run_prefill_case(w, attend=[0, w.n_windows // 2, w.n_windows - 1])
 
 
+@pytest.mark.parametrize("per_head", [False, True])
+def test_queued_attention_equals_one_call_per_window(per_head):
+    """32 windows of one sequence in ONE attention call (work items drawn from a queue, longest
+    first) against 32 calls of one window each, with a selection per sequence and with one per
+    (sequence, KV head); two runs in a row on one workspace give the same bits."""
+    sh = LayerShape(8, 2, 128, 128, 4, 128, 256, "bf16")
+    cs = B.c_shape(sh)
+    m, nw, k_cap = 512, 32, 8
+    n_tok = (nw + 1) * m
+    nb = n_tok // 128
+    g = torch.Generator().manual_seed(31 + per_head)
+    q = torch.randn(nw * m, 8, 128, generator=g).to(torch.bfloat16).to(DEV)
+    kc = torch.randn(nb, 2, 128, 128, generator=g).to(torch.bfloat16).to(DEV)
+    vc = torch.randn(nb, 2, 128, 128, generator=g).to(torch.bfloat16).to(DEV)
+    rows = nw * (2 if per_head else 1)
+    idx = torch.full((rows, k_cap), -1, dtype=torch.int32)
+    n_sel = torch.randint(0, k_cap + 1, (rows,), generator=g, dtype=torch.int32)
+    n_ctx = torch.tensor([(i + 2) * m for i in range(nw)], dtype=torch.int32)
+    for r in range(rows):
+        w0 = (r // (2 if per_head else 1) + 1) * m
+        b, e = H.eligible_range(sh, w0)
+        idx[r, : int(n_sel[r])] = (torch.randperm(e - b, generator=g)[: int(n_sel[r])] + b).int()
+    idx, n_sel, n_ctx = idx.to(DEV), n_sel.to(DEV), n_ctx.to(DEV)
+    ws = torch.zeros(B.workspace_bytes(cs, nw, m, nb, k_cap), dtype=torch.uint8, device=DEV)
+    step = 2 if per_head else 1
+    ref = torch.zeros_like(q)
+    for i in range(nw):
+        B.retrieval_attention(cs, 1, m, q[i * m:(i + 1) * m], kc, vc, 0, nb, n_ctx[i:i + 1],
+                              idx[i * step:(i + 1) * step], n_sel[i * step:(i + 1) * step], k_cap,
+                              ref[i * m:(i + 1) * m], None, ws, per_head=per_head)
+    B.set_attention_cus(192)
+    try:
+        outs = []
+        for run in range(2):
+            out = torch.zeros_like(q)
+            B.retrieval_attention(cs, nw, m, q, kc, vc, 0, nb, n_ctx, idx, n_sel, k_cap, out, None, ws,
+                                  per_head=per_head)
+            torch.cuda.synchronize()
+            # (a one-window call cuts its key tiles into pieces and merges partial results: another
+            # summation order, so the last bits of a bf16 output may differ)
+            err = ((out.float() - ref.float()).abs().amax(dim=-1) / ref.float().abs().amax(dim=-1)).max().item()
+            assert err < 1e-2, f"run {run}: {err}"
+            assert not ws[:8192].any()
+            outs.append(out)
+        assert torch.equal(outs[0], outs[1])              # whoever takes an item, the same bits
+    finally:
+        B.set_attention_cus(256)
+
+
 def test_context_shorter_than_init():
     sh = LayerShape(4, 2, 64, 128, 2, 128, 128, "fp32")
     w = synth.Workload("tiny", sh, 100, 128, 4, False, 5, outlier_kind="boost", n_planted=0)
