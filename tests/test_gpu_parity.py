@@ -390,6 +390,61 @@ def test_queued_attention_equals_one_call_per_window(per_head):
         B.set_attention_cus(256)
 
 
+def _lse_reference(q_row, k, pos, group):
+    """log sum exp of the scaled logits of one query row [H][D] over the keys at `pos`, per head."""
+    q_row, pos = f64(q_row), np.asarray(pos)
+    out = np.zeros(q_row.shape[0])
+    for h in range(q_row.shape[0]):
+        z = f64(k[pos, h // group]) @ q_row[h] / math.sqrt(q_row.shape[1])
+        out[h] = z.max() + math.log(np.exp(z - z.max()).sum())
+    return out
+
+
+@pytest.mark.parametrize("dtype,d,m,nw", [("bf16", 128, 512, 1),     # key tiles cut into pieces, merged
+                                          ("bf16", 128, 512, 8),     # whole query tiles per workgroup
+                                          ("fp32", 64, 256, 2),      # row kernel
+                                          ("bf16", 128, 1, 3),       # decode, several workgroups per pair
+                                          ("bf16", 128, 1, 200),     # decode, one workgroup per pair
+                                          ("fp32", 64, 1, 3)])       # decode, row kernel
+def test_log_sum_exp_output(dtype, d, m, nw):
+    """The optional lse output [batch][H][m] of every attention kernel: the natural-log sum of the
+    exponentials of the scaled logits over exactly the keys a row sees."""
+    sh = LayerShape(8, 2, d, 128, 4, 128, 256, dtype)
+    cs = B.c_shape(sh)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    k_cap, base = 4, 9 * 128 + 40
+    n_tok = base + nw * m
+    nb = (n_tok + 127) // 128
+    g = torch.Generator().manual_seed(m + nw)
+    q = torch.randn(nw * m, 8, d, generator=g).to(td)
+    k = torch.randn(nb * 128, 2, d, generator=g).to(td)
+    v = torch.randn(nb * 128, 2, d, generator=g).to(td)
+    kc, vc = H.blocked_k(k.to(DEV), sh, nb), H.blocked_vt(v.to(DEV), sh, nb)
+    w0 = [base + i * m for i in range(nw)]
+    idx = torch.full((nw, k_cap), -1, dtype=torch.int32)
+    n_sel = torch.zeros(nw, dtype=torch.int32)
+    for i in range(nw):
+        b, e = H.eligible_range(sh, w0[i])
+        n_sel[i] = min(k_cap, e - b, 1 + i % k_cap)
+        idx[i, : int(n_sel[i])] = (torch.randperm(e - b, generator=g)[: int(n_sel[i])] + b).int()
+    n_ctx = torch.tensor([w + m for w in w0], dtype=torch.int32)
+    out = torch.zeros(nw * m, 8, d, dtype=td, device=DEV)
+    lse = torch.full((nw, 8, m), float("nan"), device=DEV)
+    ws = torch.zeros(B.workspace_bytes(cs, nw, m, nb, k_cap), dtype=torch.uint8, device=DEV)
+    B.retrieval_attention(cs, nw, m, q.to(DEV), kc, vc, 0, nb, n_ctx.to(DEV), idx.to(DEV), n_sel.to(DEV), k_cap,
+                          out, lse, ws)
+    torch.cuda.synchronize()
+    lse = lse.cpu().numpy()
+    assert np.isfinite(lse).all()
+    tol = 2e-5 if dtype == "fp32" else 2e-3            # bf16 inputs are exact; the logits are fp32 sums either way
+    for i in range(0, nw, max(nw // 5, 1)):
+        chosen = idx[i, : int(n_sel[i])].tolist()
+        for r in sorted({0, m // 3, m - 1}):
+            pos = orc.key_positions(w0[i], w0[i] + r, chosen, sh.n_init, sh.n_local, 128)
+            ref = _lse_reference(q[i * m + r], k, pos, sh.group)
+            assert np.abs(lse[i, :, r] - ref).max() < tol * max(1.0, np.abs(ref).max()), f"window {i} row {r}"
+
+
 def test_context_shorter_than_init():
     sh = LayerShape(4, 2, 64, 128, 2, 128, 128, "fp32")
     w = synth.Workload("tiny", sh, 100, 128, 4, False, 5, outlier_kind="boost", n_planted=0)
