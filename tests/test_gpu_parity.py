@@ -266,6 +266,36 @@ def test_windows_larger_than_the_benchmarked_one(m, n_ctx, attend):
     run_prefill_case(w, attend=attend)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_probe_with_statistics_used_as_they_are(dtype):
+    """actqkv_build_probe without ACTQKV_STATS_UPDATE: the bias of a window against the statistics
+    of the windows before it only, and the record left untouched."""
+    m, hq, hkv, d = 256, 8, 2, 64
+    sh = LayerShape(hq, hkv, d, 128, 4, 128, 256, dtype)
+    cs = B.c_shape(sh)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    g = torch.Generator().manual_seed(5)
+    q = (torch.randn(2 * m, hq, d, generator=g) * 1.2 + 0.4).to(td)
+    q[m + 7, :, 3] *= 10.0
+    qd = q.to(DEV)
+    runner = H.LayerRunner(sh, 1, m, 8, 4, DEV)
+    wts = torch.zeros(1, m, device=DEV)
+    B.build_probe(cs, 1, m, qd[:m], runner.stats, True, runner.probe, runner.probe_kv, runner.probe_norm, None,
+                  runner.workspace)
+    torch.cuda.synchronize()
+    before = runner.stats.clone()
+    B.build_probe(cs, 1, m, qd[m:], runner.stats, False, runner.probe, runner.probe_kv, runner.probe_norm, wts,
+                  runner.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(runner.stats, before)
+    stats = orc.RunningStats(hq * d)
+    z_bar, sigma2 = stats.update(f64(q[:m]).reshape(m, -1))
+    qw = f64(q[m:]).reshape(m, -1)
+    probe, weights = orc.probe_query(qw, orc.activation_bias(qw, z_bar, sigma2))
+    assert rel_to_max(runner.probe[0], probe) < TOL_PROBE and rel_to_max(wts[0], weights) < TOL_WEIGHT
+    assert int(torch.argmax(wts[0])) == 7
+
+
 def test_probe_of_the_largest_window():
     """actqkv_build_probe with m = 8192, the largest window the library takes, against the oracle
     (statistics of two windows, bias, weights, probe)."""
