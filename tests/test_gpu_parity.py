@@ -475,6 +475,67 @@ def test_log_sum_exp_output(dtype, d, m, nw):
             assert np.abs(lse[i, :, r] - ref).max() < tol * max(1.0, np.abs(ref).max()), f"window {i} row {r}"
 
 
+@pytest.mark.parametrize("dtype,d,m,nw", [("bf16", 128, 256, 1), ("bf16", 128, 256, 40), ("fp32", 64, 128, 2),
+                                          ("bf16", 128, 1, 4), ("fp32", 64, 1, 2)])
+def test_softmax_scale_of_the_caller(dtype, d, m, nw):
+    """shape.softmax_scale other than 1/sqrt(D), in every attention kernel."""
+    sh = LayerShape(8, 2, d, 128, 4, 128, 256, dtype)
+    scale = 0.031
+    cs = B.c_shape(sh, softmax_scale=scale)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    k_cap, base = 3, 7 * 128 + 19
+    n_tok = base + nw * m
+    nb = (n_tok + 127) // 128
+    g = torch.Generator().manual_seed(3 * m + nw)
+    q = (torch.randn(nw * m, 8, d, generator=g) * 2.0).to(td)
+    k = torch.randn(nb * 128, 2, d, generator=g).to(td)
+    v = torch.randn(nb * 128, 2, d, generator=g).to(td)
+    kc, vc = H.blocked_k(k.to(DEV), sh, nb), H.blocked_vt(v.to(DEV), sh, nb)
+    w0 = [base + i * m for i in range(nw)]
+    idx = torch.tensor([[2, 4, 5]] * nw, dtype=torch.int32)
+    n_sel = torch.full((nw,), 3, dtype=torch.int32)
+    n_ctx = torch.tensor([w + m for w in w0], dtype=torch.int32)
+    out = torch.zeros(nw * m, 8, d, dtype=td, device=DEV)
+    ws = torch.zeros(B.workspace_bytes(cs, nw, m, nb, k_cap), dtype=torch.uint8, device=DEV)
+    B.retrieval_attention(cs, nw, m, q.to(DEV), kc, vc, 0, nb, n_ctx.to(DEV), idx.to(DEV), n_sel.to(DEV), k_cap,
+                          out, None, ws)
+    torch.cuda.synchronize()
+    for i in sorted({0, nw // 2, nw - 1}):
+        for r in sorted({0, m - 1}):
+            pos = orc.key_positions(w0[i], w0[i] + r, [2, 4, 5], sh.n_init, sh.n_local, 128)
+            ref = orc.attention_rows(f64(q[i * m + r])[None], f64(k), f64(v), pos, sh.group, scale)[0]
+            default = orc.attention_rows(f64(q[i * m + r])[None], f64(k), f64(v), pos, sh.group)[0]
+            assert out_error(out[i * m + r], ref) < TOL_OUT[dtype], f"window {i} row {r}"
+            assert out_error(default, ref) > 5 * TOL_OUT[dtype]       # the scale matters on these inputs
+
+
+def test_variance_floor_of_the_caller():
+    """shape.var_eps: a channel that never varies has variance 0, floored at var_eps (Eq. (7))."""
+    m, hq, hkv, d = 128, 4, 2, 64
+    sh = LayerShape(hq, hkv, d, 128, 4, 128, 256, "fp32")
+    eps = 0.25
+    cs = B.c_shape(sh, var_eps=eps)
+    g = torch.Generator().manual_seed(12)
+    q = torch.randn(2 * m, hq, d, generator=g)
+    q[:m, 1, 9] = 0.75                                      # constant in the first window: variance 0 after it
+    qd = q.to(DEV)
+    runner = H.LayerRunner(sh, 1, m, 8, 4, DEV)
+    wts = torch.zeros(1, m, device=DEV)
+    B.build_probe(cs, 1, m, qd[:m], runner.stats, True, runner.probe, runner.probe_kv, runner.probe_norm, None,
+                  runner.workspace)
+    B.build_probe(cs, 1, m, qd[m:], runner.stats, False, runner.probe, runner.probe_kv, runner.probe_norm, wts,
+                  runner.workspace)
+    torch.cuda.synchronize()
+    stats = orc.RunningStats(hq * d)
+    z_bar, sigma2 = stats.update(f64(q[:m]).reshape(m, -1))
+    assert sigma2[1 * d + 9] < 1e-12
+    qw = f64(q[m:]).reshape(m, -1)
+    probe, weights = orc.probe_query(qw, orc.activation_bias(qw, z_bar, sigma2, eps))
+    other, _ = orc.probe_query(qw, orc.activation_bias(qw, z_bar, sigma2, 1e-12))
+    assert rel_to_max(runner.probe[0], probe) < TOL_PROBE and rel_to_max(wts[0], weights) < TOL_WEIGHT
+    assert rel_to_max(other, probe) > 100 * TOL_PROBE       # the floor matters on these inputs
+
+
 def test_context_shorter_than_init():
     sh = LayerShape(4, 2, 64, 128, 2, 128, 128, "fp32")
     w = synth.Workload("tiny", sh, 100, 128, 4, False, 5, outlier_kind="boost", n_planted=0)
