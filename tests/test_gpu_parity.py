@@ -536,6 +536,42 @@ def test_variance_floor_of_the_caller():
     assert rel_to_max(other, probe) > 100 * TOL_PROBE       # the floor matters on these inputs
 
 
+@pytest.mark.parametrize("n_rep,dtype,d", [(1, "bf16", 128), (6, "bf16", 128), (16, "fp32", 64)])
+def test_other_numbers_of_representative_keys(n_rep, dtype, d):
+    """1, 6 and 16 representative keys per block (the scoring kernels walk them four at a time):
+    a prefill against the oracle, the decode scoring launch against the scoring kernel, and the
+    cache update's choice of representatives."""
+    sh = LayerShape(8, 2, d, 128, n_rep, 128, 256, dtype)
+    w = synth.Workload(f"rep_{n_rep}", sh, 2048 + 60, 256, 4, True, 600 + n_rep, n_planted=3)
+    run_prefill_case(w, attend=[w.n_windows - 1])
+    cs = B.c_shape(sh)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    g = torch.Generator().manual_seed(n_rep)
+    n, nb = 1000, 9
+    k = torch.randn(n, 2, d, generator=g).to(td)
+    v = torch.randn(n, 2, d, generator=g).to(td)
+    kc = torch.zeros(1, nb, 2, 128, d, dtype=td, device=DEV); vc = torch.zeros(1, nb, 2, d, 128, dtype=td, device=DEV)
+    rep = torch.zeros(1, nb, n_rep, 2, d, dtype=td, device=DEV)
+    B.append_kv(cs, 1, n, k.to(DEV), v.to(DEV), torch.zeros(1, dtype=torch.int32, device=DEV), kc, vc, 0, rep, 0, nb)
+    torch.cuda.synchronize()
+    want = orc.representative_keys(k.float().numpy(), 128, n_rep)
+    assert np.array_equal(rep[0, : want.shape[0]].float().cpu().numpy(), want)
+    q = torch.randn(1, 1, 8, d, generator=g).to(td).to(DEV)
+    nb_end = torch.tensor([7], dtype=torch.int32, device=DEV)
+    r = H.LayerRunner(sh, 1, 1, nb, 4, DEV)
+    B.build_probe(cs, 1, 1, q, None, False, r.probe, r.probe_kv, r.probe_norm, None, r.workspace)
+    B.score_blocks(cs, 1, r.probe_kv, r.probe_norm, rep, 0, nb, 1, nb_end, r.scores, r.score_stride)
+    torch.cuda.synchronize()
+    a = r.scores[0, 1:7].clone()
+    r.scores.zero_()
+    B.decode_retrieve(cs, 1, q, None, None, None, None, None, 0, rep, 0, nb, 1, nb_end, None, None, None, r.scores,
+                      r.score_stride, 4, None, None, r.idx, r.n_sel, None, None)
+    torch.cuda.synchronize()
+    assert torch.allclose(r.scores[0, 1:7], a, rtol=2e-6, atol=1e-7)
+    ref = orc.block_scores(f64(q[0, 0].cpu()).reshape(-1), want[1:7].astype(np.float64), sh.group)
+    assert np.abs(f64(a.cpu()) - ref).max() < TOL_SCORE
+
+
 def test_context_shorter_than_init():
     sh = LayerShape(4, 2, 64, 128, 2, 128, 128, "fp32")
     w = synth.Workload("tiny", sh, 100, 128, 4, False, 5, outlier_kind="boost", n_planted=0)
