@@ -572,6 +572,37 @@ def test_other_numbers_of_representative_keys(n_rep, dtype, d):
     assert np.abs(f64(a.cpu()) - ref).max() < TOL_SCORE
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("fp32", 128)])
+def test_the_other_storage_and_head_size_pairs(dtype, d):
+    """bf16 with 64 channels per head and fp32 with 128 (the benchmarked pairs are bf16 / 128 and
+    fp32 / 64): a prefill, and a decode step through the separate and the fused calls."""
+    sh = LayerShape(8, 2, d, 128, 4, 128, 256, dtype)
+    w = synth.Workload(f"{dtype}_{d}", sh, 2048 + 33, 256, 4, True, 900 + d, n_planted=3,
+                       outlier_kind="boost" if dtype == "fp32" else "student_t")
+    run_prefill_case(w, attend=[2, w.n_windows - 1])
+    n = 1500
+    q, k, v = synth.gen_layer(w, "cpu", 0, 0, n_ctx=2048)
+    rep = synth.pick_rep_keys(k[:n - 1], 128, sh.n_rep)
+    nb = 12
+    kc = H.blocked_k(k[:n - 1].to(DEV), sh, nb).unsqueeze(0).contiguous()
+    vc = H.blocked_vt(v[:n - 1].to(DEV), sh, nb).unsqueeze(0).contiguous()
+    repd = torch.zeros(1, nb, sh.n_rep, 2, d, dtype=sh.torch_dtype, device=DEV)
+    repd[0, : rep.shape[0]] = rep.to(DEV)
+    qd = q[n - 1][None, None].contiguous().to(DEV)
+    i32 = dict(dtype=torch.int32, device=DEV)
+    runner = H.LayerRunner(sh, 1, 1, nb, w.k_cap, DEV)
+    out = torch.zeros_like(qd)
+    nb_end_h = H.eligible_range(sh, n - 1)[1]
+    runner.decode_step(qd, kc, vc, repd, torch.tensor([n], **i32), torch.tensor([nb_end_h], **i32), nb_end_h, out,
+                       None, None, k[n - 1][None, None].contiguous().to(DEV), v[n - 1][None, None].contiguous().to(DEV),
+                       torch.tensor([n - 1], **i32))
+    torch.cuda.synchronize()
+    res = orc.decode_step(f64(q[n - 1]), f64(k[:n]), f64(v[:n]), f64(rep), n, sh.n_init, sh.n_local, 128, w.k_cap, None)
+    gi, gn = runner.idx[0].cpu().tolist(), int(runner.n_sel[0])
+    assert check_selection(gi, gn, res, w.k_cap)
+    assert out_error(out[0, 0], res["out"]) < TOL_OUT[dtype]
+
+
 def test_context_shorter_than_init():
     sh = LayerShape(4, 2, 64, 128, 2, 128, 128, "fp32")
     w = synth.Workload("tiny", sh, 100, 128, 4, False, 5, outlier_kind="boost", n_planted=0)
