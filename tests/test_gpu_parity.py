@@ -603,6 +603,63 @@ def test_the_other_storage_and_head_size_pairs(dtype, d):
     assert out_error(out[0, 0], res["out"]) < TOL_OUT[dtype]
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp32", 64)])
+def test_prefill_of_three_sequences_in_one_batch(dtype, d):
+    """Three independent sequences (own statistics, caches, representative keys, budgets) window by
+    window in one batch; the third is 5 windows ahead of the others, so every per-sequence
+    length (n_ctx, nb_end) differs within a call.  Every window of every sequence against the oracle."""
+    sh = LayerShape(8, 2, d, 128, 4, 128, 256, dtype)
+    cs = B.c_shape(sh)
+    m, k_cap, n_win, lead = 256, 4, 6, [0, 0, 5]
+    bt = 3
+    n_tok = (n_win + max(lead)) * m
+    nb = n_tok // 128
+    seqs = []
+    for s_ in range(bt):
+        w = synth.Workload(f"batch_seq_{s_}", sh, n_tok, m, k_cap, True, 3100 + 17 * s_, n_planted=3,
+                           outlier_kind="boost" if dtype == "fp32" else "student_t")
+        q, k, v = synth.gen_layer(w, "cpu", 0, s_)
+        seqs.append((w, q, k, v, synth.pick_rep_keys(k, 128, sh.n_rep)))
+    kc = torch.stack([H.blocked_k(x[2].to(DEV), sh, nb) for x in seqs])
+    vc = torch.stack([H.blocked_vt(x[3].to(DEV), sh, nb) for x in seqs])
+    repd = torch.stack([x[4].to(DEV) for x in seqs])
+    runner = H.LayerRunner(sh, bt, m, nb, k_cap, DEV)
+    cut = [[synth.cutoff_state(x[0], max(H.eligible_range(sh, t * m)[1] - 1, 0), t, 0) for t in range(n_win + max(lead))]
+           for x in seqs]
+    want = [oracle_windows(x[1], x[2], x[3], x[4], sh, m, k_cap, cut[s_], attend=range(n_win + lead[s_]))
+            for s_, x in enumerate(seqs)]
+    i32 = dict(dtype=torch.int32, device=DEV)
+    # the third sequence runs its first `lead` windows alone (a batch of one on the same record)
+    solo = H.LayerRunner(sh, 1, m, nb, k_cap, DEV)
+    for t in range(lead[2]):
+        o = torch.zeros(m, 8, d, dtype=sh.torch_dtype, device=DEV)
+        bud = torch.tensor([cut[2][t][0]], dtype=torch.float32, device=DEV)
+        rest = torch.tensor([cut[2][t][1]], dtype=torch.float32, device=DEV)
+        solo.step(seqs[2][1][t * m:(t + 1) * m].to(DEV), kc[2], vc[2], repd[2], torch.tensor([(t + 1) * m], **i32),
+                  torch.tensor([H.eligible_range(sh, t * m)[1]], **i32), nb, o, bud, rest, True, m)
+    runner.stats[2].copy_(solo.stats[0])
+    for t in range(n_win):
+        ts = [t + lead[s_] for s_ in range(bt)]
+        qw = torch.stack([seqs[s_][1][ts[s_] * m:(ts[s_] + 1) * m] for s_ in range(bt)]).to(DEV)
+        out = torch.zeros_like(qw)
+        bud = torch.tensor([cut[s_][ts[s_]][0] for s_ in range(bt)], dtype=torch.float32, device=DEV)
+        rest = torch.tensor([cut[s_][ts[s_]][1] for s_ in range(bt)], dtype=torch.float32, device=DEV)
+        ends = [H.eligible_range(sh, ts[s_] * m)[1] for s_ in range(bt)]
+        runner.step(qw, kc, vc, repd, torch.tensor([(x + 1) * m for x in ts], **i32), torch.tensor(ends, **i32),
+                    max(ends), out, bud, rest, True, m)
+        torch.cuda.synchronize()
+        for s_ in range(bt):
+            res = want[s_][ts[s_]]
+            assert rel_to_max(runner.probe[s_], res["probe"]) < TOL_PROBE, f"probe, sequence {s_} window {ts[s_]}"
+            gi, gn = runner.idx[s_].cpu().tolist(), int(runner.n_sel[s_])
+            ref = res["out"]
+            if not check_selection(gi, gn, res, k_cap):
+                ref = orc.retrieval_attention_window(f64(seqs[s_][1][res["w0"]:res["w0"] + m]), f64(seqs[s_][2]),
+                                                     f64(seqs[s_][3]), res["w0"], gi[:gn], sh.n_init, sh.n_local,
+                                                     128, sh.group)
+            assert out_error(out[s_], ref) < TOL_OUT[dtype], f"output, sequence {s_} window {ts[s_]}"
+
+
 def test_context_shorter_than_init():
     sh = LayerShape(4, 2, 64, 128, 2, 128, 128, "fp32")
     w = synth.Workload("tiny", sh, 100, 128, 4, False, 5, outlier_kind="boost", n_planted=0)
