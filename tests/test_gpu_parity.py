@@ -248,7 +248,7 @@ def test_group_sizes_that_do_not_divide_eight(hq, hkv, d, dtype):
     run_prefill_case(w, attend=[0, 2, 6])
 
 
-@pytest.mark.parametrize("n_init,n_local", [(0, 256), (128, 0), (256, 128)])
+@pytest.mark.parametrize("n_init,n_local", [(0, 256), (128, 0), (256, 128), (0, 0), (512, 1024)])
 def test_geometry_variants(n_init, n_local):
     sh = LayerShape(4, 2, 64, 128, 2, n_init, n_local, "fp32")
     w = synth.Workload(f"geom_{n_init}_{n_local}", sh, 2048 + 50, 128, 4, False, 99 + n_init + n_local,
@@ -658,6 +658,35 @@ def test_prefill_of_three_sequences_in_one_batch(dtype, d):
                                                      f64(seqs[s_][3]), res["w0"], gi[:gn], sh.n_init, sh.n_local,
                                                      128, sh.group)
             assert out_error(out[s_], ref) < TOL_OUT[dtype], f"output, sequence {s_} window {ts[s_]}"
+
+
+@pytest.mark.parametrize("n_init,n_local", [(0, 0), (0, 256), (384, 0), (512, 1024)])
+def test_geometry_variants_on_the_matrix_core_kernels(n_init, n_local):
+    """No initial tokens, no local span, neither, or more of both than the benchmarks use: a bf16
+    prefill (matrix-core attention) and a decode step in two launches."""
+    sh = LayerShape(8, 2, 128, 128, 4, n_init, n_local, "bf16")
+    w = synth.Workload(f"geom_bf16_{n_init}_{n_local}", sh, 3072 + 50, 256, 4, True, 5150 + n_init + n_local,
+                       n_planted=3)
+    run_prefill_case(w, attend=[0, 5, w.n_windows - 1])
+    n = 2900
+    q, k, v = synth.gen_layer(w, "cpu", 0, 1, n_ctx=3072)
+    rep = synth.pick_rep_keys(k[:n], 128, sh.n_rep)
+    nb = 24
+    kc = H.blocked_k(k[:n].to(DEV), sh, nb).unsqueeze(0).contiguous()
+    vc = H.blocked_vt(v[:n].to(DEV), sh, nb).unsqueeze(0).contiguous()
+    repd = torch.zeros(1, nb, sh.n_rep, 2, 128, dtype=torch.bfloat16, device=DEV)
+    repd[0, : rep.shape[0]] = rep.to(DEV)
+    qd = q[n - 1][None, None].contiguous().to(DEV)
+    i32 = dict(dtype=torch.int32, device=DEV)
+    runner = H.LayerRunner(sh, 1, 1, nb, w.k_cap, DEV)
+    out = torch.zeros_like(qd)
+    runner.decode_step_two_launches(qd, kc, vc, repd, torch.tensor([n], **i32),
+                                    torch.tensor([H.eligible_range(sh, n - 1)[1]], **i32), out)
+    torch.cuda.synchronize()
+    res = orc.decode_step(f64(q[n - 1]), f64(k[:n]), f64(v[:n]), f64(rep), n, n_init, n_local, 128, w.k_cap, None)
+    gi, gn = runner.idx[0].cpu().tolist(), int(runner.n_sel[0])
+    assert check_selection(gi, gn, res, w.k_cap)
+    assert out_error(out[0, 0], res["out"]) < TOL_OUT["bf16"]
 
 
 def test_context_shorter_than_init():
