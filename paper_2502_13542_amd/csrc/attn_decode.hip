@@ -316,7 +316,7 @@ __global__ __launch_bounds__(kDcThreads) void attn_decode_select_kernel(DcParams
   // the scores of the sequence: the load of the first 512 does not wait for anything
   const float* sc_mem = sp.scores + size_t(s) * sp.score_stride + sp.nb_begin;
   const ScoreRow<kDcThreads> sc{sc_mem, int(threadIdx.x) < p.nb_capacity - sp.nb_begin ? sc_mem[threadIdx.x] : 0.f};
-  const int end = min(sp.nb_end[s], p.nb_capacity);
+  const int end = min(max(sp.nb_end[s], sp.nb_begin), p.nb_capacity);   // (no wrap-around in the subtraction)
   const int n_elig = max(end - sp.nb_begin, 0);
   const int n_ctx = min(max(p.n_ctx[s], 1), p.nb_capacity * kBlock);
   const WindowGeom g = window_geom(n_ctx, 1, p.n_init, p.n_local);

@@ -19,7 +19,9 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
   const float* sc_mem = scores + size_t(s) * score_stride + nb_begin;
   // the row has nb_capacity entries whatever nb_end says
   const ScoreRow<kSelectThreads> sc{sc_mem, tid < nb_capacity - nb_begin ? sc_mem[tid] : 0.f};
-  const int end = min(nb_end[s], nb_capacity);
+  // clamped from both sides before anything is computed from it: a huge negative value in
+  // device memory must not wrap around in the subtraction
+  const int end = min(max(nb_end[s], nb_begin), nb_capacity);
   const int n = max(end - nb_begin, 0);
   const SelectIo io{budget_remaining, theta_rest_sum, budget_remaining, idx, n_sel, theta_out, budget_out, true};
   select_body<kSelectThreads>(sc, s, n, nb_begin, k_cap, entropy_topk, io, lds);

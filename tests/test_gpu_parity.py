@@ -689,6 +689,59 @@ def test_geometry_variants_on_the_matrix_core_kernels(n_init, n_local):
     assert out_error(out[0, 0], res["out"]) < TOL_OUT["bf16"]
 
 
+@pytest.mark.parametrize("dtype,d,m", [("bf16", 128, 256), ("fp32", 64, 128), ("bf16", 128, 1), ("fp32", 64, 1)])
+def test_device_side_values_are_clamped(dtype, d, m):
+    """Lengths and counts that live in device memory are clamped against the capacities the
+    host passes (every kernel does so before it forms an address): a call with absurd values
+    gives exactly what the call with the clamped values gives."""
+    sh = LayerShape(8, 2, d, 128, 4, 128, 256, dtype)
+    cs = B.c_shape(sh)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    nb, k_cap, bt = 12, 4, 3
+    big, neg = 2 ** 31 - 1, -(2 ** 31)
+    g = torch.Generator().manual_seed(77 + m)
+    q = torch.randn(bt, m, 8, d, generator=g).to(td).to(DEV)
+    kc = torch.randn(bt, nb, 2, 128, d, generator=g).to(td).to(DEV)
+    vc = torch.randn(bt, nb, 2, d, 128, generator=g).to(td).to(DEV)
+    rep = torch.randn(bt, nb, 4, 2, d, generator=g).to(td).to(DEV)
+    i32 = dict(dtype=torch.int32, device=DEV)
+    runner = H.LayerRunner(sh, bt, m, nb, k_cap, DEV)
+
+    def run(n_ctx, nb_end, n_sel_attn):
+        r = {}
+        B.build_probe(cs, bt, m, q, runner.stats.zero_(), True, runner.probe, runner.probe_kv, runner.probe_norm, None,
+                      runner.workspace)
+        scores = torch.zeros(bt, runner.score_stride, device=DEV)
+        B.score_blocks(cs, bt, runner.probe_kv, runner.probe_norm, rep, rep.stride(0), nb, 1,
+                       torch.tensor(nb_end, **i32), scores, runner.score_stride)
+        idx = torch.zeros(bt, k_cap, **i32); n_sel = torch.zeros(bt, **i32)
+        B.select(bt, scores, runner.score_stride, nb, 1, torch.tensor(nb_end, **i32), k_cap, None, None, idx, n_sel)
+        out = torch.zeros_like(q)
+        bad_idx = torch.tensor([[2, big, neg, 5]] * bt, **i32)
+        B.retrieval_attention(cs, bt, m, q, kc, vc, kc.stride(0), nb, torch.tensor(n_ctx, **i32), bad_idx,
+                              torch.tensor(n_sel_attn, **i32), k_cap, out, None, runner.workspace)
+        torch.cuda.synchronize()
+        return scores, idx, n_sel, out
+
+    cap = nb * 128
+    absurd = run([big, neg, cap + 1], [big, neg, nb + 5], [big, neg, 3])
+    clamped = run([cap, max(m, 1), cap], [nb, 1, nb], [k_cap, 0, 3])
+    for a, b in zip(absurd, clamped):
+        assert torch.equal(a, b)
+    assert bool(torch.isfinite(absurd[3].float()).all())
+    if m == 1 and dtype == "bf16":                          # the attention launch that selects for itself
+        def fused(n_ctx, nb_end):
+            idx = torch.zeros(bt, k_cap, **i32); n_sel = torch.zeros(bt, **i32)
+            out = torch.zeros_like(q)
+            B.decode_select_attention(cs, bt, q, kc, vc, kc.stride(0), nb, torch.tensor(n_ctx, **i32), clamped[0],
+                                      runner.score_stride, 1, torch.tensor(nb_end, **i32), k_cap, None, None, None,
+                                      idx, n_sel, None, None, out, None, runner.workspace)
+            torch.cuda.synchronize()
+            return idx, n_sel, out
+        for a, b in zip(fused([big, neg, cap + 1], [big, neg, nb + 5]), fused([cap, 1, cap], [nb, 1, nb])):
+            assert torch.equal(a, b)
+
+
 def test_context_shorter_than_init():
     sh = LayerShape(4, 2, 64, 128, 2, 128, 128, "fp32")
     w = synth.Workload("tiny", sh, 100, 128, 4, False, 5, outlier_kind="boost", n_planted=0)
