@@ -729,6 +729,17 @@ def test_device_side_values_are_clamped(dtype, d, m):
     for a, b in zip(absurd, clamped):
         assert torch.equal(a, b)
     assert bool(torch.isfinite(absurd[3].float()).all())
+    # a position far behind the cache: nothing is written (the cache update and the decode scoring launch)
+    kc2, vc2, rep2 = kc.clone(), vc.clone(), rep.clone()
+    k_new = torch.randn(bt, m, 2, d, generator=g).to(td).to(DEV)
+    far = torch.tensor([big, big - 5, cap], **i32)
+    B.append_kv(cs, bt, m, k_new, k_new, far, kc2, vc2, kc2.stride(0), rep2, rep2.stride(0), nb)
+    if m == 1:
+        B.decode_retrieve(cs, bt, q, k_new, k_new, far, kc2, vc2, kc2.stride(0), rep2, rep2.stride(0), nb, 1,
+                          torch.tensor([nb, nb, nb], **i32), None, None, None, torch.zeros_like(clamped[0]),
+                          runner.score_stride, k_cap, None, None, clamped[1].clone(), clamped[2].clone(), None, None)
+    torch.cuda.synchronize()
+    assert torch.equal(kc2, kc) and torch.equal(vc2, vc) and torch.equal(rep2, rep)
     if m == 1 and dtype == "bf16":                          # the attention launch that selects for itself
         def fused(n_ctx, nb_end):
             idx = torch.zeros(bt, k_cap, **i32); n_sel = torch.zeros(bt, **i32)
