@@ -1324,6 +1324,51 @@ def test_decode_retrieve_equals_the_four_calls(dtype, hq, hkv, d, update):
         assert not torch.equal(res[1][-1][3, 68], rep0[3, 68])            # representatives of the completed block
 
 
+def test_two_streams_with_a_workspace_each():
+    """Two independent batches of sequences decode at the same time on two streams, each with
+    its own buffers and workspace, ten steps each: the same bits as one after the other."""
+    sh = LayerShape(32, 8, 128, 128, 4, 128, 512, "bf16")
+    bt, nb, k_cap, steps = 4, 40, 8, 10
+    n0 = 36 * 128 + 17
+    i32 = dict(dtype=torch.int32, device=DEV)
+
+    def make(seed):
+        g = torch.Generator(device=DEV).manual_seed(seed)
+        kc = torch.randn(bt, nb, 8, 128, 128, generator=g, device=DEV).to(torch.bfloat16)
+        vc = torch.randn(bt, nb, 8, 128, 128, generator=g, device=DEV).to(torch.bfloat16)
+        rep = torch.randn(bt, nb, 4, 8, 128, generator=g, device=DEV).to(torch.bfloat16)
+        q = torch.randn(steps, bt, 1, 32, 128, generator=g, device=DEV).to(torch.bfloat16)
+        kn = torch.randn(steps, bt, 1, 8, 128, generator=g, device=DEV).to(torch.bfloat16)
+        vn = torch.randn(steps, bt, 1, 8, 128, generator=g, device=DEV).to(torch.bfloat16)
+        return dict(kc=kc, vc=vc, rep=rep, q=q, kn=kn, vn=vn, runner=H.LayerRunner(sh, bt, 1, nb, k_cap, DEV),
+                    out=torch.zeros(steps, bt, 1, 32, 128, dtype=torch.bfloat16, device=DEV),
+                    idx=torch.zeros(steps, bt, k_cap, **i32))
+
+    def run(x, stream):
+        with torch.cuda.stream(stream):
+            for t in range(steps):
+                n = n0 + t
+                x["runner"].decode_step_two_launches(
+                    x["q"][t], x["kc"], x["vc"], x["rep"], torch.full((bt,), n + 1, **i32),
+                    torch.full((bt,), H.eligible_range(sh, n)[1], **i32), x["out"][t], None, None, None,
+                    x["kn"][t], x["vn"][t], torch.full((bt,), n, **i32))
+                x["idx"][t].copy_(x["runner"].idx)
+
+    results = []
+    for concurrent in (False, True):
+        a, b = make(1), make(2)
+        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        if concurrent:
+            run(a, sa); run(b, sb)
+        else:
+            run(a, sa); torch.cuda.synchronize(); run(b, sb)
+        torch.cuda.synchronize()
+        results.append((a["out"], a["idx"], a["kc"], b["out"], b["idx"], b["kc"]))
+    for u, v_ in zip(*results):
+        assert torch.equal(u, v_)
+
+
 def test_decode_step_on_a_cache_of_one_block():
     """The first tokens of a sequence: one cache block, nothing eligible.  The two-launch step
     writes the token, the probe and an empty selection, and attends over what is there."""
