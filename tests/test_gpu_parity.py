@@ -1369,6 +1369,79 @@ def test_two_streams_with_a_workspace_each():
         assert torch.equal(u, v_)
 
 
+def _replays_equal_eager(step, outputs):
+    """Captures step() in a HIP graph; three replays, with eager runs and synchronisations in
+    between, must each leave exactly what the eager run leaves in `outputs`."""
+    step()
+    torch.cuda.synchronize()
+    want = [o.clone() for o in outputs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for i in range(3):
+        for o in outputs:
+            o.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, w_ in zip(outputs, want):
+            assert torch.equal(o, w_), f"replay {i}"
+        step()
+        torch.cuda.synchronize()
+
+
+def test_graph_replays_of_a_decode_step_and_of_a_prefill_pass():
+    """The benchmarked schedules inside HIP graphs: a decode step of two layers in two launches
+    each, and a prefill pass in chunks of windows on two streams with the second team of
+    attention workgroups."""
+    sh = LayerShape(32, 8, 128, 128, 4, 128, 512, "bf16")
+    i32 = dict(dtype=torch.int32, device=DEV)
+    bt, nb, k_cap, L = 4, 24, 8, 2
+    g = torch.Generator(device=DEV).manual_seed(3)
+    kc = torch.randn(L, bt, nb, 8, 128, 128, generator=g, device=DEV).to(torch.bfloat16)
+    vc = torch.randn(L, bt, nb, 8, 128, 128, generator=g, device=DEV).to(torch.bfloat16)
+    rep = torch.randn(L, bt, nb, 4, 8, 128, generator=g, device=DEV).to(torch.bfloat16)
+    q = torch.randn(L, bt, 1, 32, 128, generator=g, device=DEV).to(torch.bfloat16)
+    kn = torch.randn(L, bt, 1, 8, 128, generator=g, device=DEV).to(torch.bfloat16)
+    n = 20 * 128 + 5
+    n_ctx, pos0 = torch.full((bt,), n + 1, **i32), torch.full((bt,), n, **i32)
+    nb_end = torch.full((bt,), H.eligible_range(sh, n)[1], **i32)
+    runner = H.LayerRunner(sh, bt, 1, nb, k_cap, DEV)
+    out = torch.zeros(L, bt, 1, 32, 128, dtype=torch.bfloat16, device=DEV)
+    idx = torch.zeros(L, bt, k_cap, **i32)
+    buds = [torch.full((bt,), 9.0, device=DEV), torch.zeros(bt, device=DEV), torch.zeros(bt, device=DEV)]
+    rest = torch.full((bt,), 2.0, device=DEV)
+
+    def decode():
+        for l in range(L):
+            runner.decode_step_two_launches(q[l], kc[l], vc[l], rep[l], n_ctx, nb_end, out[l], buds[l], rest,
+                                            buds[l + 1], kn[l], kn[l], pos0)
+            idx[l].copy_(runner.idx)
+    _replays_equal_eager(decode, [out, idx, buds[2]])
+
+    w = synth.scaled(synth.WORKLOADS["c2_32k"], n_ctx=20 * 512 + 100, name="graph_prefill", cutoff=True, k_cap=8)
+    qp, k, v = synth.gen_layer(w, "cpu", 0)
+    rp = synth.pick_rep_keys(k, 128, 4)
+    cut = [synth.cutoff_state(w, H.eligible_range(sh, t * 512)[1] - 1, t, 0) for t in range(w.n_windows)]
+    qd, kcp, vcp = qp.to(DEV), H.blocked_k(k.to(DEV), sh, w.n_blocks), H.blocked_vt(v.to(DEV), sh, w.n_blocks)
+    repd = torch.zeros(w.n_blocks, 4, 8, 128, dtype=torch.bfloat16, device=DEV)
+    repd[: rp.shape[0]] = rp.to(DEV)
+    r2 = H.LayerRunner(sh, 1, 512, w.n_blocks, w.k_cap, DEV)
+    plan = H.make_prefill_plan(sh, w.n_ctx, 512, cut, DEV)
+    bud0 = plan.budget.clone()
+    pipe = H.PrefillPipeline(r2, plan)
+    outp = torch.zeros_like(qd)
+
+    def prefill():
+        r2.stats.zero_()
+        plan.budget.copy_(bud0)
+        pipe.run(qd, kcp, vcp, repd, outp, overlap=True, chunk=8, batched=True, late_cus=32)
+    B.set_attention_cus(224)
+    try:
+        _replays_equal_eager(prefill, [outp, pipe.idx, pipe.n_sel])
+    finally:
+        B.set_attention_cus(256)
+
+
 def test_decode_step_on_a_cache_of_one_block():
     """The first tokens of a sequence: one cache block, nothing eligible.  The two-launch step
     writes the token, the probe and an empty selection, and attends over what is there."""
