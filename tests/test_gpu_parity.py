@@ -416,6 +416,16 @@ def test_queued_attention_equals_one_call_per_window(per_head):
             assert not ws[:8192].any()
             outs.append(out)
         assert torch.equal(outs[0], outs[1])              # whoever takes an item, the same bits
+        if not per_head:
+            # two teams of workgroups, the second one launched FIRST (it then draws every item but the
+            # first team's first round), and in the documented order: the same bits, the queue at zero
+            for order in ((True, False), (False, True)):
+                out = torch.zeros_like(q)
+                for late in order:
+                    B.retrieval_attention_teams(cs, nw, m, q, kc, vc, 0, nb, n_ctx, idx, n_sel, k_cap, out, None, ws,
+                                                32, late)
+                torch.cuda.synchronize()
+                assert torch.equal(out, outs[0]) and not ws[:8192].any()
     finally:
         B.set_attention_cus(256)
 
