@@ -1452,6 +1452,88 @@ def test_graph_replays_of_a_decode_step_and_of_a_prefill_pass():
         B.set_attention_cus(256)
 
 
+@pytest.mark.parametrize("group", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_every_group_size_in_decode_and_prefill_attention(group):
+    """1 to 8 query heads per KV head, bf16: a decode step in two launches and a prefill window on
+    the matrix cores against a plain softmax attention over the keys each row sees."""
+    hkv = 2
+    sh = LayerShape(group * hkv, hkv, 128, 128, 4, 128, 256, "bf16")
+    cs = B.c_shape(sh)
+    i32 = dict(dtype=torch.int32, device=DEV)
+    g = torch.Generator().manual_seed(40 + group)
+    nb, k_cap, m = 16, 4, 192
+    n_tok = nb * 128
+    k = torch.randn(n_tok, hkv, 128, generator=g).to(torch.bfloat16)
+    v = torch.randn(n_tok, hkv, 128, generator=g).to(torch.bfloat16)
+    kc, vc = H.blocked_k(k.to(DEV), sh, nb), H.blocked_vt(v.to(DEV), sh, nb)
+    sel = [3, 7, 5]
+    idx = torch.tensor([sel + [-1]], **i32)
+    n_sel = torch.tensor([3], **i32)
+    ws = torch.zeros(B.workspace_bytes(cs, 1, m, nb, k_cap), dtype=torch.uint8, device=DEV)
+    for rows, n_ctx in ((1, 1900), (m, 1800 + m)):
+        q = torch.randn(rows, group * hkv, 128, generator=g).to(torch.bfloat16)
+        out = torch.zeros(rows, group * hkv, 128, dtype=torch.bfloat16, device=DEV)
+        B.retrieval_attention(cs, 1, rows, q.to(DEV), kc, vc, 0, nb, torch.tensor([n_ctx], **i32), idx, n_sel, k_cap,
+                              out, None, ws)
+        torch.cuda.synchronize()
+        w0 = n_ctx - rows
+        for r in sorted({0, rows // 2, rows - 1}):
+            pos = orc.key_positions(w0, w0 + r, sel, sh.n_init, sh.n_local, 128)
+            ref = orc.attention_rows(f64(q[r])[None], f64(k), f64(v), pos, group)[0]
+            assert out_error(out[r], ref) < TOL_OUT["bf16"], f"rows {rows} row {r}"
+
+
+def test_selection_on_random_cases():
+    """300 random selection problems (sizes, capacities, score scales, ties, cut-off states, both
+    density readings) in batches, every one against the oracle."""
+    rng = np.random.default_rng(2024)
+    for trial in range(10):
+        bt = 30
+        n_max = int(rng.choice([7, 64, 65, 600, 1100, 3000]))
+        k_cap = int(rng.integers(1, 65))
+        ns = rng.integers(0, n_max + 1, size=bt)
+        nb_begin = int(rng.integers(0, 3))
+        stride = nb_begin + n_max + 3
+        scores = np.zeros((bt, stride), dtype=np.float32)
+        for s_ in range(bt):
+            sc = rng.normal(size=ns[s_]) * rng.choice([0.01, 0.3, 3.0])
+            if s_ % 3 == 0:
+                sc = np.round(sc * 4) / 4                    # exact ties
+            scores[s_, nb_begin:nb_begin + ns[s_]] = sc
+        use_cut, topk = bool(trial % 2), bool(trial % 3 == 0)
+        bud_h = rng.uniform(0.5, 90.0, size=bt).astype(np.float32)
+        rest_h = rng.uniform(0.0, 40.0, size=bt).astype(np.float32)
+        bud = torch.from_numpy(bud_h.copy()).to(DEV) if use_cut else None
+        rest = torch.from_numpy(rest_h).to(DEV) if use_cut else None
+        idx = torch.zeros(bt, k_cap, dtype=torch.int32, device=DEV)
+        n_sel = torch.zeros(bt, dtype=torch.int32, device=DEV)
+        theta = torch.zeros(bt, device=DEV); b_l = torch.zeros(bt, device=DEV)
+        B.select(bt, torch.from_numpy(scores).to(DEV), stride, nb_begin + n_max, nb_begin,
+                 torch.tensor(nb_begin + ns, dtype=torch.int32, device=DEV), k_cap, bud, rest, idx, n_sel, theta, b_l,
+                 flags=B.SELECT_ENTROPY_TOPK if topk else 0)
+        torch.cuda.synchronize()
+        idx_h, n_h, th_h, bl_h = idx.cpu().tolist(), n_sel.cpu().tolist(), theta.cpu().numpy(), b_l.cpu().numpy()
+        for s_ in range(bt):
+            n = int(ns[s_])
+            if n == 0:
+                assert n_h[s_] == 0 and all(x == -1 for x in idx_h[s_])
+                continue
+            sc = scores[s_, nb_begin:nb_begin + n].astype(np.float64)
+            th = orc.information_density_topk(sc, k_cap) if topk else orc.information_density(sc)
+            assert abs(th_h[s_] - th) < TOL_THETA, (trial, s_)
+            if use_cut:
+                bl = orc.layer_budget(th, float(rest_h[s_]), float(bud_h[s_]))
+                assert abs(bl_h[s_] - bl) < TOL_BUDGET * max(bl, 1.0)
+                if abs(bl + 0.5 - round(bl + 0.5)) < 1e-3:
+                    continue                                 # B^l at a rounding boundary: either count is right
+                count = orc.cutoff_count(bl, k_cap, n)
+            else:
+                count = min(k_cap, n)
+            want = orc.select_blocks(scores[s_, nb_begin:nb_begin + n], list(range(nb_begin, nb_begin + n)), count)
+            assert n_h[s_] == count and idx_h[s_][:count] == want, (trial, s_)
+            assert all(x == -1 for x in idx_h[s_][count:])
+
+
 def test_decode_step_on_a_cache_of_one_block():
     """The first tokens of a sequence: one cache block, nothing eligible.  The two-launch step
     writes the token, the probe and an empty selection, and attends over what is there."""
