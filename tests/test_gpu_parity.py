@@ -1534,6 +1534,54 @@ def test_selection_on_random_cases():
             assert all(x == -1 for x in idx_h[s_][count:])
 
 
+def test_scores_on_random_shapes():
+    """40 random shapes (heads, group, channels, representative keys, batch, blocks, both storage
+    types; shared or per-sequence keys): block scores, head-merged and per KV head, and the
+    decode scoring launch against the oracle."""
+    rng = np.random.default_rng(77)
+    for trial in range(40):
+        hkv = int(rng.choice([1, 2, 4, 8])); group = int(rng.integers(1, 9)); d = int(rng.choice([64, 128]))
+        if hkv * group * d > 16384:
+            continue
+        n_rep = int(rng.integers(1, 17)); bt = int(rng.integers(1, 6)); nb = int(rng.integers(2, 70))
+        dtype = "bf16" if trial % 2 else "fp32"
+        td = torch.bfloat16 if dtype == "bf16" else torch.float32
+        sh = LayerShape(hkv * group, hkv, d, 128, n_rep, 128, 256, dtype)
+        cs = B.c_shape(sh)
+        shared = trial % 5 == 0
+        g = torch.Generator().manual_seed(trial)
+        rep = torch.randn(1 if shared else bt, nb, n_rep, hkv, d, generator=g).to(td)
+        q = torch.randn(bt, 1, hkv * group, d, generator=g).to(td)
+        nb_begin = 1
+        ends = rng.integers(0, nb + 1, size=bt)
+        repd, qd = rep.to(DEV), q.to(DEV)
+        nb_end = torch.tensor(ends, dtype=torch.int32, device=DEV)
+        r = H.LayerRunner(sh, bt, 1, nb, 4, DEV)
+        B.build_probe(cs, bt, 1, qd, None, False, r.probe, r.probe_kv, r.probe_norm, None, r.workspace)
+        B.score_blocks(cs, bt, r.probe_kv, r.probe_norm, repd, 0 if shared else repd.stride(0), nb, nb_begin, nb_end,
+                       r.scores, r.score_stride)
+        ph = torch.zeros(bt, hkv, r.score_stride, device=DEV)
+        B.score_blocks_per_head(cs, bt, r.probe, repd, 0 if shared else repd.stride(0), nb, nb_begin,
+                                nb_end.repeat_interleave(hkv).contiguous(), ph, r.score_stride)
+        fused = torch.zeros_like(r.scores)
+        if not shared:
+            B.decode_retrieve(cs, bt, qd, None, None, None, None, None, 0, repd, repd.stride(0), nb, nb_begin, nb_end,
+                              None, None, None, fused, r.score_stride, 4, None, None, None, None, None, None,
+                              flags=B.DECODE_SCORES_ONLY)
+        torch.cuda.synchronize()
+        for s_ in range(bt):
+            e = int(ends[s_])
+            if e <= nb_begin:
+                continue
+            keys = f64(rep[0 if shared else s_, nb_begin:e])
+            want = orc.block_scores(f64(q[s_, 0]).reshape(-1), keys, group)
+            assert np.abs(f64(r.scores[s_, nb_begin:e]) - want).max() < TOL_SCORE, (trial, s_)
+            want_ph = orc.block_scores_per_head(f64(q[s_, 0]).reshape(-1), keys, group)
+            assert np.abs(f64(ph[s_, :, nb_begin:e]) - want_ph).max() < TOL_SCORE, (trial, s_)
+            if not shared:
+                assert np.abs(f64(fused[s_, nb_begin:e]) - want).max() < TOL_SCORE, (trial, s_)
+
+
 def test_decode_step_on_a_cache_of_one_block():
     """The first tokens of a sequence: one cache block, nothing eligible.  The two-launch step
     writes the token, the probe and an empty selection, and attends over what is there."""
