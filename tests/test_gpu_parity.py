@@ -1582,6 +1582,48 @@ def test_scores_on_random_shapes():
                 assert np.abs(f64(fused[s_, nb_begin:e]) - want).max() < TOL_SCORE, (trial, s_)
 
 
+def test_probe_on_random_shapes():
+    """30 random shapes (heads, channels, window lengths from 2 to 700, batch, storage type, mean
+    pooling or not): two windows per sequence, statistics, weights, probe, its group sum and its
+    norm against the oracle."""
+    rng = np.random.default_rng(99)
+    for trial in range(30):
+        hkv = int(rng.choice([1, 2, 4, 8])); group = int(rng.integers(1, 9)); d = int(rng.choice([64, 128]))
+        if hkv * group * d > 16384:
+            continue
+        m = int(rng.choice([2, 3, 17, 64, 100, 255, 256, 513, 700])); bt = int(rng.integers(1, 5))
+        dtype = "bf16" if trial % 2 else "fp32"
+        td = torch.bfloat16 if dtype == "bf16" else torch.float32
+        pooling = trial % 7 == 0
+        hq, dd = hkv * group, hkv * group * d
+        sh = LayerShape(hq, hkv, d, 128, 4, 128, 256, dtype)
+        cs = B.c_shape(sh)
+        g = torch.Generator().manual_seed(1000 + trial)
+        q = (torch.randn(bt, 2 * m, hq, d, generator=g) * float(rng.uniform(0.3, 3.0)) + float(rng.normal())).to(td)
+        q[:, rng.integers(0, 2 * m), :, rng.integers(0, d)] *= 12.0
+        qd = q.to(DEV)
+        r = H.LayerRunner(sh, bt, m, 8, 4, DEV)
+        wts = torch.zeros(bt, m, device=DEV)
+        flags = B.STATS_UPDATE | (B.PROBE_MEAN_POOLING if pooling else 0)
+        stats = [orc.RunningStats(dd) for _ in range(bt)]
+        for t in range(2):
+            B.build_probe(cs, bt, m, qd[:, t * m:(t + 1) * m].contiguous(), r.stats, flags, r.probe, r.probe_kv,
+                          r.probe_norm, wts, r.workspace)
+            torch.cuda.synchronize()
+            for s_ in range(bt):
+                qw = f64(q[s_, t * m:(t + 1) * m]).reshape(m, dd)
+                z_bar, sigma2 = stats[s_].update(qw)
+                if pooling:
+                    probe, weights = qw.mean(axis=0), np.full(m, 1.0 / m)
+                else:
+                    probe, weights = orc.probe_query(qw, orc.activation_bias(qw, z_bar, sigma2))
+                assert rel_to_max(r.probe[s_], probe) < TOL_PROBE, (trial, t, s_)
+                assert rel_to_max(wts[s_], weights) < TOL_WEIGHT, (trial, t, s_)
+                kv = probe.reshape(hkv, group, d).sum(axis=1).reshape(-1)
+                assert rel_to_max(r.probe_kv[s_], kv) < TOL_PROBE * group, (trial, t, s_)
+                assert abs(float(r.probe_norm[s_]) - np.linalg.norm(probe)) < TOL_PROBE * np.linalg.norm(probe)
+
+
 def test_decode_step_on_a_cache_of_one_block():
     """The first tokens of a sequence: one cache block, nothing eligible.  The two-launch step
     writes the token, the probe and an empty selection, and attends over what is there."""
