@@ -1624,6 +1624,57 @@ def test_probe_on_random_shapes():
                 assert abs(float(r.probe_norm[s_]) - np.linalg.norm(probe)) < TOL_PROBE * np.linalg.norm(probe)
 
 
+def test_attention_on_random_shapes():
+    """40 random attention problems: heads, group, channels, storage type, window length (1 for a
+    decode step up to 600), context, initial tokens and local span, batch entries with their
+    own caches or sharing one, random selections; sampled rows against the oracle."""
+    rng = np.random.default_rng(4242)
+    for trial in range(40):
+        hkv = int(rng.choice([1, 2, 4, 8])); group = int(rng.integers(1, 9)); d = int(rng.choice([64, 128]))
+        dtype = "bf16" if trial % 3 else "fp32"
+        td = torch.bfloat16 if dtype == "bf16" else torch.float32
+        n_init, n_local = 128 * int(rng.integers(0, 3)), 128 * int(rng.integers(0, 4))
+        m = int(rng.choice([1, 1, 2, 31, 64, 100, 256, 257, 600])); bt = int(rng.integers(1, 4))
+        shared = bt > 1 and trial % 4 == 0
+        hq = hkv * group
+        sh = LayerShape(hq, hkv, d, 128, 4, n_init, n_local, dtype)
+        cs = B.c_shape(sh)
+        k_cap = int(rng.integers(1, 9))
+        nb = int(rng.integers((m + 127) // 128 + 1, 30))
+        g = torch.Generator().manual_seed(7000 + trial)
+        ks = [torch.randn(nb * 128, hkv, d, generator=g).to(td) for _ in range(1 if shared else bt)]
+        vs = [torch.randn(nb * 128, hkv, d, generator=g).to(td) for _ in range(1 if shared else bt)]
+        kc = torch.stack([H.blocked_k(x.to(DEV), sh, nb) for x in ks])
+        vc = torch.stack([H.blocked_vt(x.to(DEV), sh, nb) for x in vs])
+        q = torch.randn(bt, m, hq, d, generator=g).to(td)
+        n_ctx = [int(rng.integers(m, nb * 128 + 1)) for _ in range(bt)]
+        idx = torch.full((bt, k_cap), -1, dtype=torch.int32)
+        n_sel = torch.zeros(bt, dtype=torch.int32)
+        chosen = []
+        for s_ in range(bt):
+            b, e = H.eligible_range(sh, n_ctx[s_] - m)
+            cnt = int(rng.integers(0, min(k_cap, max(e - b, 0)) + 1))
+            pick = (rng.permutation(max(e - b, 0))[:cnt] + b).tolist()
+            idx[s_, :cnt] = torch.tensor(pick, dtype=torch.int32)
+            n_sel[s_] = cnt
+            chosen.append(pick)
+        out = torch.zeros(bt, m, hq, d, dtype=td, device=DEV)
+        ws = torch.zeros(B.workspace_bytes(cs, bt, m, nb, k_cap), dtype=torch.uint8, device=DEV)
+        B.retrieval_attention(cs, bt, m, q.to(DEV), kc, vc, 0 if shared else kc.stride(0), nb,
+                              torch.tensor(n_ctx, dtype=torch.int32, device=DEV), idx.to(DEV), n_sel.to(DEV), k_cap,
+                              out, None, ws)
+        torch.cuda.synchronize()
+        for s_ in range(bt):
+            kk, vv = (ks[0], vs[0]) if shared else (ks[s_], vs[s_])
+            w0 = n_ctx[s_] - m
+            for r in sorted({0, m // 2, m - 1}):
+                pos = orc.key_positions(w0, w0 + r, chosen[s_], n_init, n_local, 128)
+                ref = orc.attention_rows(f64(q[s_, r])[None], f64(kk), f64(vv), pos, group)[0]
+                err = out_error(out[s_, r], ref)
+                assert err < TOL_OUT[dtype], (trial, s_, r, err, dict(hkv=hkv, group=group, d=d, dtype=dtype, m=m,
+                                                                    n_init=n_init, n_local=n_local, n_ctx=n_ctx[s_]))
+
+
 def test_decode_step_on_a_cache_of_one_block():
     """The first tokens of a sequence: one cache block, nothing eligible.  The two-launch step
     writes the token, the probe and an empty selection, and attends over what is there."""
