@@ -1198,6 +1198,50 @@ def test_append_kv_builds_the_cache_and_the_representatives(dtype, hq, hkv, d, c
     assert not rep[n // 128:].any(), "representatives of an incomplete block were written"
 
 
+def test_append_kv_on_random_chunk_sequences():
+    """20 random shapes and sequences of chunk lengths (single tokens, pieces that end on, just
+    before and just behind block boundaries, long windows); half of the single tokens go through
+    the decode scoring launch, which also updates the cache."""
+    rng = np.random.default_rng(555)
+    for trial in range(20):
+        hkv = int(rng.choice([1, 2, 4, 8])); d = int(rng.choice([64, 128])); n_rep = int(rng.integers(1, 9))
+        dtype = "bf16" if trial % 2 else "fp32"
+        tdt = torch.float32 if dtype == "fp32" else torch.bfloat16
+        sh = LayerShape(hkv * 2, hkv, d, 128, n_rep, 128, 256, dtype)
+        cs = B.c_shape(sh)
+        chunks, total = [], 0
+        while total < 900:
+            c = int(rng.choice([1, 1, 1, 2, 127, 128, 129, 300, (128 - total % 128) or 1, int(rng.integers(1, 400))]))
+            chunks.append(c); total += c
+        n = total
+        nb_cap = (n + 127) // 128 + 1
+        g = torch.Generator().manual_seed(9000 + trial)
+        k = torch.randn(n, hkv, d, generator=g).to(tdt)
+        v = torch.randn(n, hkv, d, generator=g).to(tdt)
+        kc = torch.zeros(1, nb_cap, hkv, 128, d, dtype=tdt, device=DEV)
+        vc = torch.zeros(1, nb_cap, hkv, d, 128, dtype=tdt, device=DEV)
+        rep = torch.zeros(1, nb_cap, n_rep, hkv, d, dtype=tdt, device=DEV)
+        q = torch.zeros(1, 1, hkv * 2, d, dtype=tdt, device=DEV)
+        scores = torch.zeros(1, nb_cap + 3, device=DEV)
+        nb_end = torch.zeros(1, dtype=torch.int32, device=DEV)
+        pos = 0
+        for i, m in enumerate(chunks):
+            pos0 = torch.tensor([pos], dtype=torch.int32, device=DEV)
+            kn, vn = k[pos:pos + m][None].contiguous().to(DEV), v[pos:pos + m][None].contiguous().to(DEV)
+            if m == 1 and i % 2:
+                B.decode_retrieve(cs, 1, q, kn, vn, pos0, kc, vc, 0, rep, 0, nb_cap, 1, nb_end, None, None, None, scores,
+                                  nb_cap + 3, 4, None, None, None, None, None, None, flags=B.DECODE_SCORES_ONLY)
+            else:
+                B.append_kv(cs, 1, m, kn, vn, pos0, kc, vc, 0, rep, 0, nb_cap)
+            pos += m
+        torch.cuda.synchronize()
+        assert torch.equal(kc[0].cpu(), H.blocked_k(k, sh, nb_cap)), (trial, chunks)
+        assert torch.equal(vc[0].cpu(), H.blocked_vt(v, sh, nb_cap)), (trial, chunks)
+        want = orc.representative_keys(k.float().numpy(), 128, n_rep)
+        assert np.array_equal(rep[0, : want.shape[0]].float().cpu().numpy(), want), (trial, chunks)
+        assert not rep[0, n // 128:].any(), (trial, chunks)
+
+
 def test_append_kv_batch_of_decode_steps():
     """Three sequences at different lengths take single tokens; two of them finish a block."""
     sh = LayerShape(32, 8, 128, 128, 4, 128, 256, "bf16")
