@@ -177,11 +177,9 @@ def bench_prefill(args, torch, B, H, synth):
         if bud0 is not None:
             plan.budget.copy_(bud0)
         pipe.run(q, kc, vc, repd, out, overlap, events, args.chunk, args.score_chunk, not args.per_window_selection,
-                 args.attention_late_cus if overlap else 0)
+                 args.attention_late_cus if overlap else 0, args.attention_cus if overlap else 256)
 
     if args.pmc_pass:
-        if not args.no_overlap:
-            B.set_attention_cus(args.attention_cus)
         return pmc_pass(torch, B, lambda: one_step(overlap=not args.no_overlap),
                         {"workload": w.name, "windows": n_win, "windows_per_launch": args.chunk})
     def timed(run, steps):
@@ -199,12 +197,10 @@ def bench_prefill(args, torch, B, H, synth):
     serial_s = timed(graph_serial.replay if graph_serial is not None else one_step, min(args.steps, 3))
     overlap = not args.no_overlap
     if overlap:
-        B.set_attention_cus(args.attention_cus)     # the rest serves the chain of the next window
         step_fn = lambda: one_step(overlap=True)
         graph = None if args.eager else capture_graph(torch, step_fn, out, "prefill (two streams)")
         run = graph.replay if graph is not None else step_fn
         elapsed = timed(run, args.steps) * args.steps
-        B.set_attention_cus(256)
     else:
         graph, elapsed = graph_serial, serial_s * args.steps
         if args.steps > 3:
@@ -213,12 +209,8 @@ def bench_prefill(args, torch, B, H, synth):
     # ---- roofline of the dominant kernel: the prefill attention launches of one eager pass in
     # the schedule that was timed, events on the stream the attention runs on
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_win)]
-    if overlap:
-        B.set_attention_cus(args.attention_cus)
     one_step(ev, overlap)
     torch.cuda.synchronize()
-    if overlap:
-        B.set_attention_cus(256)
     n_sel = nsel_log.cpu().tolist()
     flops = sum(attention_flops(sh, plan.w0[t], plan.rows[t], n_sel[t], H.local_start(sh, plan.w0[t]))
                 for t in range(n_win))
@@ -313,9 +305,9 @@ def bench_prefill_layers(args, torch, B, H, synth):
             runner.stats.zero_()
             if bud0 is not None:
                 plan.budget.copy_(bud0)
-            pipe.run(q, kc, vc, repd, out, True, None, args.chunk, args.score_chunk, True, args.attention_late_cus)
+            pipe.run(q, kc, vc, repd, out, True, None, args.chunk, args.score_chunk, True, args.attention_late_cus,
+                     args.attention_cus)
 
-    B.set_attention_cus(args.attention_cus)
     graph = None if args.eager else capture_graph(torch, one_step, out, f"prefill ({L} layers)")
     run = graph.replay if graph is not None else one_step
     for _ in range(args.warmup):
@@ -326,7 +318,6 @@ def bench_prefill_layers(args, torch, B, H, synth):
         run()
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / args.steps
-    B.set_attention_cus(256)
     n_sel = [sum(pipe.n_sel.cpu().tolist()) / plan.n_windows for *_, plan, _, pipe in layers]
     return {"metric": f"prefill retrieval-attn tokens/s per layer ({w.name}, {L} layers)",
             "value": w.n_ctx * L / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

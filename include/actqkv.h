@@ -50,7 +50,7 @@
 extern "C" {
 #endif
 
-#define ACTQKV_VERSION 104
+#define ACTQKV_VERSION 105
 
 enum {
   ACTQKV_OK = 0,
@@ -103,7 +103,8 @@ size_t actqkv_stats_floats(const actqkv_shape* shape);
 
 /* Bytes of workspace that any of the calls below may need for these sizes or smaller
  * ones: every call with 1 .. batch entries and windows of 1 .. m tokens (a layer's ragged
- * last window, a decode step) is served by a workspace of this size.  The
+ * last window, a decode step), whatever launch shape it asks for, is served by a workspace of
+ * this size.  The
  * workspace must be zero-filled once after allocation (the kernels leave the
  * counters it holds at zero); calls sharing one workspace must be ordered on
  * one stream. */
@@ -239,16 +240,6 @@ int actqkv_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_p
                             const float* theta_prev, float* theta_sum, float* n_steps,
                             float* budget_remaining, float* theta_rest_sum, void* stream);
 
-/* Launch-shape hint for callers that run other kernels beside the prefill attention (for
- * instance the probe / score / select chain of the next window on a second stream, which
- * depends on the previous selection but not on the previous attention): the prefill
- * attention then cuts its key tiles into only as many pieces as fill `cus` of the chip's
- * 256 compute units and leaves the others to the concurrent work.  Process-wide, default
- * 256; takes effect for later calls, including actqkv_workspace_bytes (a workspace sized
- * under one setting may be too small under a larger one, which the calls report as
- * ACTQKV_EWORKSPACE).  Results do not depend on it beyond the order of floating-point sums. */
-int actqkv_set_attention_cus(int cus);
-
 /* Retrieval per KV head - the alternative to the head-merged reading of the method, in which
  * every KV head, with the G query heads it serves, scores, cuts off and selects for itself.
  *
@@ -272,30 +263,31 @@ int actqkv_retrieval_attention_per_head(const actqkv_shape* shape, int batch, in
                                         void* out, float* lse, void* workspace, size_t ws_bytes,
                                         void* stream);
 
-/* actqkv_retrieval_attention for a batch of windows (m > 1, bf16, head_dim 128) with the
- * workgroups that drain its queue of (query tile, KV head) items coming in TWO launches, for a
- * caller that keeps some compute units busy with other work (the next windows' probes, scores
- * and selections) for part of the time: the first team (late = 0; as many workgroups as
- * actqkv_set_attention_cus allows) starts at once, the second (late = 1; late_cus workgroups,
- * n_kv_heads <= late_cus <= 256) whenever the caller's stream gets to it, typically behind that
- * other work, and takes its share of whatever is left in the queue.  Nobody waits: if nothing
- * is left the second team leaves at once.
- *   BOTH calls must be made for every attention, with the same arguments apart from `late` and
- *   the stream (the queue is put back to zero by the last workgroup of the two teams to leave;
- *   a missing second call leaves it dirty for the next launch), and with the same
- *   actqkv_set_attention_cus setting in force.  Either may run first; each
- *   must be ordered behind the selection that wrote idx and n_sel.  The two share the
- *   workspace (this is the one case where calls that overlap in time do); the next attention
- *   on the same workspace must be ordered behind both.
- *   The other arguments, the results and the errors as in actqkv_retrieval_attention.  Where
- *   there is no queue (m = 1, fp32, or a workgroup per item in the first team already) the
- *   first call is actqkv_retrieval_attention and the second does nothing. */
+/* actqkv_retrieval_attention for a caller that runs other kernels beside the prefill attention
+ * (for instance the probes, scores and selections of the next windows on a second stream, which
+ * depend on earlier selections but on no attention): the launch shape is an argument of the call.
+ *   first_cus  1..256: the attention fills only that many of the chip's 256 compute units and
+ *            leaves the rest to the concurrent work (a single window is cut into fewer pieces;
+ *            a batch of windows (m > 1, bf16, head_dim 128), whose (query tile, KV head) items go
+ *            through a queue, gets that many persistent workgroups).
+ *   late_cus   0, or n_kv_heads..256: a second team of that many workgroups for the same queue,
+ *            launched by this call on `stream_late`, typically the stream that carries the other
+ *            work, so that the team starts once that work has drained and takes its share of
+ *            whatever is left in the queue.  Nobody waits: if nothing is left, or the call has no
+ *            queue (m = 1, fp32, a workgroup per item already), the second team leaves at once or
+ *            is not launched at all.  The output does not depend on who runs which item.
+ *   stream, stream_late  both must be ordered behind the selection that wrote idx and n_sel.  The
+ *            two launches share the workspace (the one case where work on two streams does); the
+ *            next call on the same workspace must be ordered behind both streams.
+ *   A workspace of actqkv_workspace_bytes serves every first_cus.  The other arguments, the
+ *   results and the errors as in actqkv_retrieval_attention; first_cus or late_cus out of range:
+ *   ACTQKV_EINVAL. */
 int actqkv_retrieval_attention_teams(const actqkv_shape* shape, int batch, int m, const void* q,
                                      const void* k_cache, const void* v_cache, int64_t seq_stride,
                                      int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
                                      const int32_t* n_sel, int k_cap, void* out, float* lse,
-                                     void* workspace, size_t ws_bytes, int late_cus, int late,
-                                     void* stream);
+                                     void* workspace, size_t ws_bytes, int first_cus, int late_cus,
+                                     void* stream, void* stream_late);
 
 /* The first launch of a decode step: actqkv_append_kv with m = 1 and the probe of the step's
  * one-token window (actqkv_build_probe with m = 1 and no statistics: probe = the query,

@@ -61,14 +61,13 @@ SIGNATURES = {
     "actqkv_score_blocks_per_head": (_i, [_shp, _i, _vp, _vp, _i64, _i, _i, _vp, _vp, _i64, _vp]),
     "actqkv_append_kv": (_i, [_shp, _i, _i, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _vp]),
     "actqkv_cutoff_next_step": (_i, [_i, _i, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp]),
-    "actqkv_set_attention_cus": (_i, [_i]),
     "actqkv_append_kv_probe": (_i, [_shp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _vp, _vp, _vp, _vp]),
     "actqkv_decode_retrieve": (_i, [_shp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _i, _vp, _vp, _vp,
                                     _vp, _vp, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_decode_select_attention": (_i, [_shp, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _i64, _i, _vp, _i, _i,
                                             _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "actqkv_retrieval_attention_teams": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
-                                              _vp, _vp, _vp, _sz, _i, _i, _vp]),
+                                              _vp, _vp, _vp, _sz, _i, _i, _vp, _vp]),
     "actqkv_copy_bytes": (_i, [_vp, _vp, _sz, _vp]),
     "actqkv_gather_blocks": (_i, [_shp, _i, _vp, _vp, _i64, _i, _vp, _vp, _i, _vp, _vp, _i64, _i, _i, _vp, _vp]),
     "actqkv_last_error": (ctypes.c_char_p, []),
@@ -201,15 +200,16 @@ def decode_select_attention(shape: CShape, batch: int, q, k_cache, v_cache, seq_
 
 def retrieval_attention_teams(shape: CShape, batch: int, m: int, q, k_cache, v_cache, seq_stride: int,
                               nb_capacity: int, n_ctx, idx, n_sel, k_cap: int, out, lse, workspace,
-                              late_cus: int, late: bool, stream=None) -> None:
-    """One of the two launches of a prefill attention whose queue workers come in two teams; see the header."""
-    st = torch.bfloat16
+                              first_cus: int, late_cus: int, stream=None, stream_late=None) -> None:
+    """The attention on first_cus compute units, with an optional second team of late_cus workgroups
+    launched on stream_late; see the header."""
+    st = torch.float32 if shape.dtype == ACTQKV_F32 else torch.bfloat16
     _check(load_library().actqkv_retrieval_attention_teams(
         ctypes.byref(shape), batch, m, _ptr(q, st), _ptr(k_cache, st), _ptr(v_cache, st),
         seq_stride, nb_capacity, _ptr(n_ctx, torch.int32), _ptr(idx, torch.int32),
         _ptr(n_sel, torch.int32), k_cap, _ptr(out, st), _ptr(lse, torch.float32),
-        _ptr(workspace), workspace.numel() * workspace.element_size(), int(late_cus), int(bool(late)),
-        _stream(stream)))
+        _ptr(workspace), workspace.numel() * workspace.element_size(), int(first_cus), int(late_cus),
+        _stream(stream), _stream(stream_late)))
 
 
 def cutoff_next_step(batch: int, n_layers: int, k_mean: float, theta_prior: float, theta_prev,
@@ -218,11 +218,6 @@ def cutoff_next_step(batch: int, n_layers: int, k_mean: float, theta_prior: floa
     _check(load_library().actqkv_cutoff_next_step(
         batch, n_layers, k_mean, theta_prior, _ptr(theta_prev, f), _ptr(theta_sum, f), _ptr(n_steps, f),
         _ptr(budget_remaining, f), _ptr(theta_rest_sum, f), _stream(stream)))
-
-
-def set_attention_cus(cus: int) -> None:
-    """Compute units the prefill attention may fill (256 = all); see the header."""
-    _check(load_library().actqkv_set_attention_cus(int(cus)))
 
 
 def copy_bytes(dst, src, stream=None) -> None:

@@ -1,7 +1,6 @@
 // C ABI of the library: host-side argument checks, then one launcher per entry point.
 // The checks need no GPU, so every error path can be exercised on a CPU-only machine.
 #include <algorithm>
-#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -108,21 +107,17 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
                                   int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
                                   const int32_t* n_sel, int k_cap, void* out, float* lse,
                                   const PfSplits& splits, float* scratch, unsigned int* counters,
-                                  float scale, int sel_per_head, int late_cus, int late, hipStream_t stream);
-
-// Compute units the prefill attention may fill (actqkv_set_attention_cus).
-static std::atomic<int> g_attention_cus{256};
-int attention_cus() { return g_attention_cus.load(std::memory_order_relaxed); }
+                                  float scale, int sel_per_head, int first_cus, int late_cus,
+                                  hipStream_t stream, hipStream_t stream_late);
 
 // Enough key splits to give every compute unit it may fill a workgroup, never more than 8
 // per query tile; what does not divide evenly goes to the last query tiles of the window.
-PfSplits prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap) {
+PfSplits prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap, int cus) {
   (void)k_cap;
   PfSplits r{1, 0, 1};
   if (!prefill_mfma_supported(sh, m)) return r;
   const int n_qtiles = prefill_mfma_qtiles(sh, m);
   const int pairs = batch * sh.n_kv_heads;                   // each has n_qtiles query tiles
-  const int cus = g_attention_cus.load(std::memory_order_relaxed);
   int per_pair = cus / (pairs > 0 ? pairs : 1);              // workgroups one pair may have
   if (per_pair < n_qtiles) per_pair = n_qtiles;
   r.s_lo = per_pair / n_qtiles;
@@ -151,19 +146,25 @@ int launch_attention_decode_select(const actqkv_shape& sh, int batch, const void
                                    int32_t* n_sel, float* theta, float* budget, void* out, float* lse,
                                    float* scratch, unsigned int* counters, float scale, hipStream_t stream);
 
-// what exactly this (batch, m) needs
-size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap) {
-  (void)nb_capacity;
-  size_t probe = probe_call_floats(sh, batch, m) * sizeof(float);
-  const PfSplits splits = prefill_splits(sh, batch, m, k_cap);
+// scratch of the attention alone: the ticket and queue counters, then the partial results
+size_t attention_scratch_bytes(const actqkv_shape& sh, int batch, int m, int k_cap, int cus) {
   size_t attn = 0;
   if (decode_mfma_supported(sh, m)) attn = decode_mfma_scratch_floats(sh, batch, k_cap) * sizeof(float);
   if (prefill_mfma_supported(sh, m)) {
     // partial results exist only where a query tile's key tiles are cut into pieces
+    const PfSplits splits = prefill_splits(sh, batch, m, k_cap, cus);
     if (splits.slots > prefill_mfma_qtiles(sh, m))
       attn = size_t(batch) * sh.n_kv_heads * splits.slots * kPfPartialFloats * sizeof(float);
   }
-  return kCounterBytes + align_up(probe > attn ? probe : attn, 256);
+  return kCounterBytes + align_up(attn, 256);
+}
+
+// what exactly this (batch, m) needs; the pieces a query tile is cut into, and with them the
+// partial results, only grow with the compute units the attention may fill
+size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap, int cus) {
+  (void)nb_capacity;
+  const size_t probe = kCounterBytes + align_up(probe_call_floats(sh, batch, m) * sizeof(float), 256);
+  return std::max(probe, attention_scratch_bytes(sh, batch, m, k_cap, cus));
 }
 
 // What a caller should allocate: enough for every call with 1 .. batch entries and windows of
@@ -189,23 +190,55 @@ int launch_attention_rows(const actqkv_shape& sh, int batch, int m, const void* 
 int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
                      const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
                      const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
-                     const Workspace& ws, int sel_per_head, hipStream_t stream, int late_cus, int late) {
+                     const Workspace& ws, int sel_per_head, hipStream_t stream, int first_cus, int late_cus,
+                     hipStream_t stream_late) {
   const float scale = sh.softmax_scale > 0.f ? sh.softmax_scale : 1.f / std::sqrt(float(sh.head_dim));
-  if (decode_mfma_supported(sh, m))
+  if (decode_mfma_supported(sh, m))   // (no queue: one launch does all the work)
     return launch_attention_decode_mfma(sh, batch, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx,
                                         idx, n_sel, k_cap, out, lse, ws.scratch_f32(), ws.counters(), scale,
                                         sel_per_head, stream);
-  if (late_cus > 0 && (decode_mfma_supported(sh, m) || !prefill_mfma_supported(sh, m))) {
-    if (late) return ACTQKV_OK;   // these kernels have no queue: the first call does all the work
-    late_cus = 0;
-  }
   if (prefill_mfma_supported(sh, m))
     return launch_attention_prefill_mfma(sh, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity,
                                          n_ctx, idx, n_sel, k_cap, out, lse,
-                                         prefill_splits(sh, batch, m, k_cap), ws.scratch_f32(),
-                                         ws.counters(), scale, sel_per_head, late_cus, late, stream);
+                                         prefill_splits(sh, batch, m, k_cap, first_cus), ws.scratch_f32(),
+                                         ws.counters(), scale, sel_per_head, first_cus, late_cus, stream,
+                                         stream_late);
   return launch_attention_rows(sh, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx,
                                n_sel, k_cap, out, lse, scale, sel_per_head, stream);
+}
+
+// Host-side checks of an attention call; `need` receives the scratch bytes the call uses.
+int attention_validate(const actqkv_shape* shape, int batch, int m, const void* q, const void* k_cache,
+                              const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
+                              const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
+                              int first_cus, size_t* need) {
+  ACTQKV_TRY(check_shape(shape));
+  ACTQKV_TRY(check_batch(batch));
+  if (m < 1) return set_error(ACTQKV_EINVAL, "m %d < 1", m);
+  if (m > kMaxWindow) return set_error(ACTQKV_ESHAPE, "m %d > %d", m, kMaxWindow);
+  // (the attention selects nothing: the 8192-block limit of a selection does not apply to its cache)
+  if (k_cap < 1 || k_cap > 64) return set_error(ACTQKV_ESHAPE, "k_cap %d not supported (1..64)", k_cap);
+  if (nb_capacity < 1) return set_error(ACTQKV_EINVAL, "nb_capacity %d < 1", nb_capacity);
+  if (int64_t(nb_capacity) * shape->block_size < m)
+    return set_error(ACTQKV_EINVAL, "cache of %d blocks cannot hold a window of %d tokens", nb_capacity, m);
+  if (int64_t(nb_capacity) * shape->block_size > (int64_t(1) << 30))
+    return set_error(ACTQKV_ESHAPE, "cache of %d blocks exceeds 2^30 tokens", nb_capacity);
+  ACTQKV_REQUIRE_PTR(q);
+  ACTQKV_REQUIRE_PTR(k_cache);
+  ACTQKV_REQUIRE_PTR(v_cache);
+  ACTQKV_REQUIRE_SMALL(n_ctx, 4);
+  ACTQKV_REQUIRE_SMALL(idx, 4);
+  ACTQKV_REQUIRE_SMALL(n_sel, 4);
+  ACTQKV_REQUIRE_PTR(out);
+  ACTQKV_OPTIONAL_SMALL(lse, 4);
+  const int64_t per_seq = int64_t(nb_capacity) * shape->n_kv_heads * shape->block_size * shape->head_dim;
+  // seq_stride 0: all batch entries read one cache (several windows of one sequence)
+  if (batch > 1 && seq_stride != 0 && seq_stride < per_seq)
+    return set_error(ACTQKV_EINVAL, "seq_stride %lld < one sequence's cache %lld", (long long)seq_stride,
+                     (long long)per_seq);
+  if (seq_stride % 8 != 0) return set_error(ACTQKV_EALIGN, "seq_stride must be a multiple of 8 elements");
+  *need = attention_scratch_bytes(*shape, batch, m, k_cap, first_cus);
+  return ACTQKV_OK;
 }
 
 }  // namespace actqkv
@@ -316,42 +349,20 @@ int actqkv_select(int batch, const float* scores, int64_t score_stride, int nb_c
 static int attention_checked(const actqkv_shape* shape, int batch, int m, const void* q, const void* k_cache,
                              const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
                              const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
-                             void* workspace, size_t ws_bytes, int sel_per_head, void* stream, int late_cus = 0,
-                             int late = 0) {
-  ACTQKV_TRY(check_shape(shape));
-  ACTQKV_TRY(check_batch(batch));
-  if (m < 1) return set_error(ACTQKV_EINVAL, "m %d < 1", m);
-  if (m > kMaxWindow) return set_error(ACTQKV_ESHAPE, "m %d > %d", m, kMaxWindow);
-  ACTQKV_TRY(check_blocks(nb_capacity, 0, k_cap, true));
-  if (nb_capacity < 1) return set_error(ACTQKV_EINVAL, "nb_capacity %d < 1", nb_capacity);
-  if (int64_t(nb_capacity) * shape->block_size < m)
-    return set_error(ACTQKV_EINVAL, "cache of %d blocks cannot hold a window of %d tokens", nb_capacity, m);
-  if (int64_t(nb_capacity) * shape->block_size > (int64_t(1) << 30))
-    return set_error(ACTQKV_ESHAPE, "cache of %d blocks exceeds 2^30 tokens", nb_capacity);
-  ACTQKV_REQUIRE_PTR(q);
-  ACTQKV_REQUIRE_PTR(k_cache);
-  ACTQKV_REQUIRE_PTR(v_cache);
-  ACTQKV_REQUIRE_SMALL(n_ctx, 4);
-  ACTQKV_REQUIRE_SMALL(idx, 4);
-  ACTQKV_REQUIRE_SMALL(n_sel, 4);
-  ACTQKV_REQUIRE_PTR(out);
-  ACTQKV_OPTIONAL_SMALL(lse, 4);
-  const int64_t per_seq = int64_t(nb_capacity) * shape->n_kv_heads * shape->block_size * shape->head_dim;
-  // seq_stride 0: all batch entries read one cache (several windows of one sequence)
-  if (batch > 1 && seq_stride != 0 && seq_stride < per_seq)
-    return set_error(ACTQKV_EINVAL, "seq_stride %lld < one sequence's cache %lld", (long long)seq_stride,
-                     (long long)per_seq);
-  if (seq_stride % 8 != 0) return set_error(ACTQKV_EALIGN, "seq_stride must be a multiple of 8 elements");
+                             void* workspace, size_t ws_bytes, int sel_per_head, void* stream,
+                             int first_cus = kChipCus, int late_cus = 0, void* stream_late = nullptr) {
+  size_t need = 0;
+  ACTQKV_TRY(attention_validate(shape, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx, n_sel,
+                                k_cap, out, lse, first_cus, &need));
   if (workspace == nullptr || !aligned16(workspace))
     return set_error(ACTQKV_EWORKSPACE, "workspace is NULL or not 16-byte aligned");
-  size_t need = workspace_bytes(*shape, batch, m, nb_capacity, k_cap);
   if (ws_bytes < need)
     return set_error(ACTQKV_EWORKSPACE, "workspace has %zu bytes, retrieval_attention needs %zu", ws_bytes,
                      need);
   Workspace ws{workspace, ws_bytes};
   return launch_attention(*shape, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx,
-                          n_sel, k_cap, out, lse, ws, sel_per_head, static_cast<hipStream_t>(stream), late_cus,
-                          late);
+                          n_sel, k_cap, out, lse, ws, sel_per_head, static_cast<hipStream_t>(stream), first_cus,
+                          late_cus, static_cast<hipStream_t>(stream_late));
 }
 
 int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, const void* q,
@@ -367,13 +378,14 @@ int actqkv_retrieval_attention_teams(const actqkv_shape* shape, int batch, int m
                                      const void* k_cache, const void* v_cache, int64_t seq_stride,
                                      int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
                                      const int32_t* n_sel, int k_cap, void* out, float* lse,
-                                     void* workspace, size_t ws_bytes, int late_cus, int late,
-                                     void* stream) {
-  if (shape != nullptr && (late_cus < shape->n_kv_heads || late_cus > 256))
-    return set_error(ACTQKV_EINVAL, "late_cus %d outside n_kv_heads..256", late_cus);
-  if (late != 0 && late != 1) return set_error(ACTQKV_EINVAL, "late must be 0 or 1");
+                                     void* workspace, size_t ws_bytes, int first_cus, int late_cus,
+                                     void* stream, void* stream_late) {
+  if (first_cus < 1 || first_cus > kChipCus)
+    return set_error(ACTQKV_EINVAL, "first_cus %d outside 1..%d", first_cus, kChipCus);
+  if (late_cus != 0 && shape != nullptr && (late_cus < shape->n_kv_heads || late_cus > kChipCus))
+    return set_error(ACTQKV_EINVAL, "late_cus %d neither 0 nor in n_kv_heads..%d", late_cus, kChipCus);
   return attention_checked(shape, batch, m, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, idx, n_sel,
-                           k_cap, out, lse, workspace, ws_bytes, 0, stream, late_cus, late);
+                           k_cap, out, lse, workspace, ws_bytes, 0, stream, first_cus, late_cus, stream_late);
 }
 
 int actqkv_retrieval_attention_per_head(const actqkv_shape* shape, int batch, int m, const void* q,
@@ -635,12 +647,6 @@ int actqkv_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_p
   ACTQKV_REQUIRE_SMALL(theta_rest_sum, 4);
   return launch_cutoff_next_step(batch, n_layers, k_mean, theta_prior, theta_prev, theta_sum, n_steps,
                                  budget_remaining, theta_rest_sum, static_cast<hipStream_t>(stream));
-}
-
-int actqkv_set_attention_cus(int cus) {
-  if (cus < 1 || cus > 256) return set_error(ACTQKV_EINVAL, "set_attention_cus: %d not in 1..256", cus);
-  g_attention_cus.store(cus, std::memory_order_relaxed);
-  return ACTQKV_OK;
 }
 
 const char* actqkv_last_error(void) { return g_error; }

@@ -18,6 +18,7 @@
 // microseconds of work behind a launch.  With a query given, one more role (Hk + 1, first
 // segment) forms that probe in the same launch.
 #include <algorithm>
+#include <mutex>
 
 #include "common.h"
 #include "append_body.h"
@@ -59,7 +60,9 @@ int launch_append(const actqkv_shape& sh, int batch, int m, const void* k_new, c
   size_t lds = std::max(size_t(sh.head_dim) * (kBlock + 2) * elem, size_t(2 * kBlock) * 4);
   if (q_tok != nullptr) lds = std::max(lds, size_t(sh.n_q_heads) * sh.head_dim * sizeof(float));
   if (sh.dtype == ACTQKV_F32) {
+    static std::mutex mu;       // once per process, from whichever thread comes first
     static bool attr_set = false;
+    std::lock_guard<std::mutex> lock(mu);
     if (!attr_set) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(append_kv_kernel<float>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, 128 * (kBlock + 2) * 4);

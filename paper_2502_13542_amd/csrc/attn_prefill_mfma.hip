@@ -27,6 +27,7 @@
 // undone for free because a lane's 8 consecutive accumulator registers then hold
 // 8 consecutive keys.
 #include <algorithm>
+#include <mutex>
 
 #include "common.h"
 #include "launch.h"
@@ -560,22 +561,33 @@ int prefill_mfma_workgroups(const actqkv_shape& sh, int m) {
   return prefill_mfma_qtiles(sh, m) * sh.n_kv_heads;
 }
 
+// hipFuncSetAttribute once per process, from whichever thread comes first
+static int prefill_lds_attribute() {
+  static std::mutex mu;
+  static bool attr_set = false;
+  std::lock_guard<std::mutex> lock(mu);
+  if (attr_set) return ACTQKV_OK;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_mfma_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_mfma_queued_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes);
+  if (e != hipSuccess) return set_error(ACTQKV_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+  attr_set = true;
+  return ACTQKV_OK;
+}
+
+// first_cus: compute units the first team may fill (the pieces in `splits` were chosen for it);
+// late_cus > 0: a second team of that many workgroups is launched on stream_late by the same
+// call, so that the two launches can never disagree about the queue they share.
 int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, const void* q,
                                   const void* k_cache, const void* v_cache, int64_t seq_stride,
                                   int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
                                   const int32_t* n_sel, int k_cap, void* out, float* lse,
                                   const PfSplits& splits, float* scratch, unsigned int* counters,
-                                  float scale, int sel_per_head, int late_cus, int late, hipStream_t stream) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_mfma_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_mfma_queued_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes);
-    if (e != hipSuccess) return set_error(ACTQKV_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
-    attr_set = true;
-  }
+                                  float scale, int sel_per_head, int first_cus, int late_cus,
+                                  hipStream_t stream, hipStream_t stream_late) {
+  if (int rc = prefill_lds_attribute()) return rc;
   PfParams p;
   p.q = static_cast<const uint16_t*>(q);
   p.k_cache = static_cast<const uint16_t*>(k_cache);
@@ -608,26 +620,27 @@ int launch_attention_prefill_mfma(const actqkv_shape& sh, int batch, int m, cons
   if (sh.n_kv_heads > kPfQueueDone)
     return set_error(ACTQKV_ESHAPE, "prefill attention: more than %d KV heads", kPfQueueDone);
   p.items_per_head = splits.slots * batch;
-  p.wgs_per_head = std::min(p.items_per_head, std::max(1, attention_cus() / sh.n_kv_heads));
+  p.wgs_per_head = std::min(p.items_per_head, std::max(1, first_cus / sh.n_kv_heads));
   p.queue = counters + kTicketCounters;
   int late_per_head = late_cus / sh.n_kv_heads;
-  if (p.items_per_head <= p.wgs_per_head) {          // a workgroup per item: no queue, nothing for a second team
-    if (late) return ACTQKV_OK;
-    late_per_head = 0;
-  }
+  if (p.items_per_head <= p.wgs_per_head) late_per_head = 0;   // a workgroup per item: no queue, no second team
   p.team_total = (p.wgs_per_head + late_per_head) * sh.n_kv_heads;
-  p.late = late;
-  if (late) {
-    hipLaunchKernelGGL(attn_prefill_mfma_queued_kernel, dim3(late_per_head * sh.n_kv_heads), dim3(kPfThreads),
-                       kPfLdsBytes, stream, p);
-    return hip_status("attention (prefill, matrix cores, second team)");
-  }
+  p.late = 0;
   dim3 grid(p.wgs_per_head * sh.n_kv_heads);
   if (p.items_per_head > p.wgs_per_head)
     hipLaunchKernelGGL(attn_prefill_mfma_queued_kernel, grid, dim3(kPfThreads), kPfLdsBytes, stream, p);
   else
     hipLaunchKernelGGL(attn_prefill_mfma_kernel, grid, dim3(kPfThreads), kPfLdsBytes, stream, p);
-  return hip_status("attention (prefill, matrix cores)");
+  if (int rc = hip_status("attention (prefill, matrix cores)")) return rc;
+  if (late_per_head > 0) {
+    p.late = 1;
+    hipLaunchKernelGGL(attn_prefill_mfma_queued_kernel, dim3(late_per_head * sh.n_kv_heads), dim3(kPfThreads),
+                       kPfLdsBytes, stream_late, p);
+    // (if this launch fails after the first one went out, the first team still does all the work, but
+    // the queue is not put back to zero: the workspace must be zero-filled again before its next use)
+    if (int rc = hip_status("attention (prefill, matrix cores, second team)")) return rc;
+  }
+  return ACTQKV_OK;
 }
 
 }  // namespace actqkv

@@ -44,7 +44,7 @@ inline size_t probe_call_floats(const actqkv_shape& sh, int batch, int m) {
 struct PfSplits {
   int s_lo, rem, slots;
 };
-PfSplits prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap);
+PfSplits prefill_splits(const actqkv_shape& sh, int batch, int m, int k_cap, int cus);   // cus: compute units to fill
 // prefill on the matrix cores: per workgroup and piece, 8 wavefronts x (16 eight-byte words of
 // four bf16 of normalised output + one word (max, sum)) x 64 lanes, counted in floats
 constexpr size_t kPfPartialFloats = 8 * (32 + 2) * 64;
@@ -53,10 +53,19 @@ constexpr int kMaxWindow = 8192;
 // head of the workspace: 1024 uint32 tickets, then the work queue counters of the prefill attention
 constexpr size_t kTicketCounters = 1024;
 constexpr size_t kCounterBytes = 8192;
-int attention_cus();   // compute units the prefill attention may fill (actqkv_set_attention_cus)
+constexpr int kChipCus = 256;   // compute units of the chip
 constexpr int kMaxBatch = 1024;
 
-size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap);
+// what exactly this call needs when the prefill attention may fill `cus` compute units (never more
+// than with all of them)
+size_t workspace_bytes(const actqkv_shape& sh, int batch, int m, int nb_capacity, int k_cap, int cus = kChipCus);
+
+size_t attention_scratch_bytes(const actqkv_shape& sh, int batch, int m, int k_cap, int cus);   // the attention alone
+// Host-side checks of an attention call (ACTQKV_OK or the error); *need = the scratch bytes it uses.
+int attention_validate(const actqkv_shape* shape, int batch, int m, const void* q, const void* k_cache,
+                       const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
+                       const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse, int first_cus,
+                       size_t* need);
 
 struct Workspace {
   void* base;
@@ -81,8 +90,9 @@ int launch_select(int batch, const float* scores, int64_t score_stride, int nb_c
 int launch_attention(const actqkv_shape& sh, int batch, int m, const void* q, const void* k_cache,
                      const void* v_cache, int64_t seq_stride, int nb_capacity, const int32_t* n_ctx,
                      const int32_t* idx, const int32_t* n_sel, int k_cap, void* out, float* lse,
-                     const Workspace& ws, int sel_per_head, hipStream_t stream, int late_cus = 0,
-                     int late = 0);   // late_cus > 0: the queue's workgroups come in two launches
+                     const Workspace& ws, int sel_per_head, hipStream_t stream, int first_cus = kChipCus,
+                     int late_cus = 0, hipStream_t stream_late = nullptr);   // late_cus > 0: a second team of
+                                                       // workgroups for the queue, on stream_late
 int launch_score_per_head(const actqkv_shape& sh, int batch, const float* probe, const void* rep_keys,
                           int64_t seq_stride, int nb_capacity, int nb_begin, const int32_t* nb_end,
                           float* scores, int64_t score_stride, hipStream_t stream);

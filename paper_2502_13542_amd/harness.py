@@ -237,9 +237,16 @@ class PrefillPipeline:
         self.ws_probe = torch.zeros(B.workspace_bytes(runner.cs, self.MAX_CHUNK, runner.m, runner.nb_capacity,
                                                       runner.k_cap), dtype=torch.uint8, device=dev)
 
+    def _attention(self, call, stream, late_cus: int = 0, stream_late=None) -> None:
+        """call: the arguments of actqkv_retrieval_attention up to the workspace."""
+        if self.attention_cus >= 256 and late_cus == 0:
+            B.retrieval_attention(*call, stream)
+        else:
+            B.retrieval_attention_teams(*call, self.attention_cus, late_cus, stream, stream_late)
+
     def run(self, q: torch.Tensor, k_cache, v_cache, rep_keys, out: torch.Tensor, overlap: bool = True,
             events=None, chunk: int = 32, score_chunk: int = 16, batched: bool = False,
-            late_cus: int = 0) -> None:
+            late_cus: int = 0, attention_cus: int = 256) -> None:
         """q, out [N][H][D].  events: optional per-window (start, end) event pairs recorded around
         the attention call of a window; with overlap, the pair of a chunk's first window brackets
         the chunk's one call, on the stream it runs on.  chunk: with overlap, the second stream picks up
@@ -249,12 +256,14 @@ class PrefillPipeline:
         the key tiles need not be cut into pieces, so nothing has to be merged).  score_chunk > 0
         (with overlap) also moves scoring and selection to a stream of their own, that many
         windows behind the probes (see _run_three_streams); 0 keeps them on the current stream.
-        late_cus > 0 (batched only): see _run_batched."""
+        attention_cus: compute units the attention calls on the second stream may fill (the rest
+        serves the other chain); late_cus > 0 (batched only): see _run_batched."""
         r, plan = self.runner, self.plan
         sh, cs = r.shape, r.cs
         nb_begin = sh.n_init // sh.block_size
         cur = torch.cuda.current_stream()
         chunk = max(1, min(chunk, self.MAX_CHUNK))
+        self.attention_cus = attention_cus if overlap else 256
         if overlap and batched:
             return self._run_batched(q, k_cache, v_cache, rep_keys, out, events, chunk, late_cus)
         if overlap and score_chunk > 0:
@@ -262,9 +271,9 @@ class PrefillPipeline:
 
         def attend(t, stream):
             w0, rows = plan.w0[t], plan.rows[t]
-            B.retrieval_attention(cs, 1, rows, q[w0:w0 + rows], k_cache, v_cache, 0, r.nb_capacity,
-                                  plan.n_ctx[t:t + 1], self.idx[t], self.n_sel[t:t + 1], r.k_cap,
-                                  out[w0:w0 + rows], None, self.ws_attn, stream)
+            self._attention((cs, 1, rows, q[w0:w0 + rows], k_cache, v_cache, 0, r.nb_capacity,
+                             plan.n_ctx[t:t + 1], self.idx[t], self.n_sel[t:t + 1], r.k_cap,
+                             out[w0:w0 + rows], None, self.ws_attn), stream)
 
         if overlap:
             self.side.wait_stream(cur)
@@ -301,10 +310,10 @@ class PrefillPipeline:
                     events[t0][0].record(self.side)
                 if n_p > 1 and all(plan.rows[u] == r.m for u in pending):
                     w0 = plan.w0[t0]
-                    B.retrieval_attention(cs, n_p, r.m, q[w0:w0 + n_p * r.m], k_cache, v_cache, 0,
-                                          r.nb_capacity, plan.n_ctx[t0:t0 + n_p], self.idx[t0:t0 + n_p],
-                                          self.n_sel[t0:t0 + n_p], r.k_cap, out[w0:w0 + n_p * r.m], None,
-                                          self.ws_attn, self.side)
+                    self._attention((cs, n_p, r.m, q[w0:w0 + n_p * r.m], k_cache, v_cache, 0,
+                                     r.nb_capacity, plan.n_ctx[t0:t0 + n_p], self.idx[t0:t0 + n_p],
+                                     self.n_sel[t0:t0 + n_p], r.k_cap, out[w0:w0 + n_p * r.m], None,
+                                     self.ws_attn), self.side)
                 else:
                     for u in pending:
                         attend(u, self.side)
@@ -324,11 +333,13 @@ class PrefillPipeline:
         which works on chunk c while the current stream prepares chunk c + 1.  A ragged last
         window goes through calls of its own.
 
-        late_cus > 0: the attention leaves that many compute units to the current stream (the
-        library's attention_cus setting), but the current stream needs them only while it
-        prepares the next chunk; behind that preparation it launches a second team of late_cus
-        attention workgroups for the chunk the second stream is working on
-        (actqkv_retrieval_attention_teams), which take their share of what is left in its queue.
+        late_cus > 0: the attention leaves compute units to the current stream (attention_cus of
+        256 are its own), but the current stream needs them only while it prepares the next
+        chunk; so the attention call of a chunk (actqkv_retrieval_attention_teams) is made once
+        the NEXT chunk's preparation has been enqueued: its first team goes to the second
+        stream, which has been waiting for nothing but this chunk's selection, and its second
+        team of late_cus workgroups to the current stream, behind that preparation, where it
+        takes its share of what is left in the chunk's queue.
         Chunks alternate between two workspaces, so a chunk's queue is never touched by the
         next chunk's launches."""
         r, plan = self.runner, self.plan
@@ -349,6 +360,14 @@ class PrefillPipeline:
                            nb_begin, plan.nb_end[u:u + 1], r.scores, r.score_stride)
             B.select(1, r.scores, r.score_stride, nb_cap, nb_begin, plan.nb_end[u:u + 1], r.k_cap, bud,
                      rest, self.idx[u], self.n_sel[u:u + 1], None, None)
+
+        def attend(pending):
+            t_first, call = pending
+            if events is not None:
+                events[t_first][0].record(last)
+            self._attention(call, last, late_cus, cur)
+            if events is not None:
+                events[t_first][1].record(last)
 
         t0, n_chunks, pending = 0, 0, None
         while t0 < plan.n_windows:
@@ -373,30 +392,19 @@ class PrefillPipeline:
             selected = torch.cuda.Event()
             selected.record(cur)
             if pending is not None:
-                # the chunk before this one is being attended to on the second stream: now that this
-                # chunk is prepared, its compute units can help there
-                B.retrieval_attention_teams(*pending, late_cus, True, cur)
-                pending = None
+                attend(pending)          # the chunk before this one; its second team follows this preparation
             last.wait_event(selected)
             self.chunk_starts.append(t0)
-            if events is not None:
-                events[t0][0].record(last)
             w0, rows = plan.w0[t0], plan.rows[t0]
             call = (cs, n_p, rows, q[w0:w0 + n_p * rows], k_cache, v_cache, 0, r.nb_capacity,
                     plan.n_ctx[t0:t0 + n_p], self.idx[t0:t0 + n_p], self.n_sel[t0:t0 + n_p],
                     r.k_cap, out[w0:w0 + n_p * rows], None)
             call += (self.ws_attn if n_chunks % 2 == 0 else self.ws_attn_b,)
-            if late_cus > 0:
-                B.retrieval_attention_teams(*call, late_cus, False, last)
-                pending = call
-            else:
-                B.retrieval_attention(*call, last)
+            pending = (t0, call)
             n_chunks += 1
-            if events is not None:
-                events[t0][1].record(last)
             t0 += n_p
         if pending is not None:
-            B.retrieval_attention_teams(*pending, late_cus, True, cur)
+            attend(pending)
         cur.wait_stream(last)
 
     def _run_three_streams(self, q, k_cache, v_cache, rep_keys, out, events, chunk, score_chunk) -> None:
@@ -447,17 +455,17 @@ class PrefillPipeline:
                     events[t0][0].record(last)
                 if n_p > 1 and all(plan.rows[u] == r.m for u in piece):
                     w0 = plan.w0[t0]
-                    B.retrieval_attention(cs, n_p, r.m, q[w0:w0 + n_p * r.m], k_cache, v_cache, 0,
-                                          r.nb_capacity, plan.n_ctx[t0:t0 + n_p], self.idx[t0:t0 + n_p],
-                                          self.n_sel[t0:t0 + n_p], r.k_cap, out[w0:w0 + n_p * r.m], None,
-                                          self.ws_attn, last)
+                    self._attention((cs, n_p, r.m, q[w0:w0 + n_p * r.m], k_cache, v_cache, 0,
+                                     r.nb_capacity, plan.n_ctx[t0:t0 + n_p], self.idx[t0:t0 + n_p],
+                                     self.n_sel[t0:t0 + n_p], r.k_cap, out[w0:w0 + n_p * r.m], None,
+                                     self.ws_attn), last)
                 else:
                     for u in piece:
                         w0, rows = plan.w0[u], plan.rows[u]
-                        B.retrieval_attention(cs, 1, rows, q[w0:w0 + rows], k_cache, v_cache, 0,
-                                              r.nb_capacity, plan.n_ctx[u:u + 1], self.idx[u],
-                                              self.n_sel[u:u + 1], r.k_cap, out[w0:w0 + rows], None,
-                                              self.ws_attn, last)
+                        self._attention((cs, 1, rows, q[w0:w0 + rows], k_cache, v_cache, 0,
+                                         r.nb_capacity, plan.n_ctx[u:u + 1], self.idx[u],
+                                         self.n_sel[u:u + 1], r.k_cap, out[w0:w0 + rows], None,
+                                         self.ws_attn), last)
                 if events is not None:
                     events[t0][1].record(last)
             to_attend = []

@@ -142,18 +142,30 @@ def test_score_select_attention_reject(lib):
         B._check(at(wsb=8))
 
 
-def test_set_attention_cus(lib):
+def test_workspace_serves_every_launch_shape(lib):
+    """The launch shape is an argument of the attention call, not process-wide state: a workspace
+    of actqkv_workspace_bytes is accepted with every first_cus (the host checks run up to the
+    launch, which fails without a GPU: any code but EWORKSPACE and the argument errors)."""
     cs = B.c_shape(LLAMA)
-    full = B.workspace_bytes(cs, 1, 512, 1024, 32)
-    assert lib.actqkv_set_attention_cus(0) == -1
-    assert lib.actqkv_set_attention_cus(257) == -1
-    assert "set_attention_cus" in B.last_error()
-    try:
-        assert lib.actqkv_set_attention_cus(192) == 0
-        assert B.workspace_bytes(cs, 1, 512, 1024, 32) <= full     # fewer pieces, fewer partials
-    finally:
-        assert lib.actqkv_set_attention_cus(256) == 0
-    assert B.workspace_bytes(cs, 1, 512, 1024, 32) == full
+    for batch, m in ((1, 512), (2, 512), (32, 512), (1, 96)):
+        full = B.workspace_bytes(cs, batch, m, 1024, 32)
+        for cus in (1, 8, 64, 192, 224, 256):
+            rc = lib.actqkv_retrieval_attention_teams(
+                ctypes.byref(cs), batch, m, A16, A16, A16, 0, 1024, A16, A16, A16, 32, A16, None, A16, full,
+                cus, 0, None, None)
+            assert rc in (0, -5), (batch, m, cus, B.last_error())
+
+
+def test_attention_cache_larger_than_a_selection(lib):
+    """The attention selects nothing, so the 8192-block limit of one selection does not apply to
+    its cache; the calls that select keep it."""
+    cs = B.c_shape(LLAMA)
+    att = lambda nb: lib.actqkv_retrieval_attention(
+        ctypes.byref(cs), 1, 512, A16, A16, A16, 0, nb, A16, A16, A16, 32, A16, None, A16, 1 << 30, None)
+    assert att(8193) in (0, -5) and att(1 << 20) in (0, -5)
+    assert att((1 << 23) + 1) == -2 and b"2^30" in lib.actqkv_last_error()
+    sel = lambda nb: lib.actqkv_select(1, A16, nb, nb, 0, A16, 32, 0, None, None, A16, A16, None, None, None)
+    assert sel(8193) == -2 and b"8192" in lib.actqkv_last_error()
 
 
 def test_copy_bytes_rejects(lib):
@@ -214,10 +226,11 @@ def test_retrieval_attention_teams_rejects(lib):
     cs = B.c_shape(LLAMA)
     call = lambda **k: lib.actqkv_retrieval_attention_teams(
         ctypes.byref(cs), 32, 512, k.get("q", A16), A16, A16, 0, 1024, A16, A16, A16, 32, k.get("out", A16), None,
-        k.get("ws", A16), k.get("wsb", 1 << 30), k.get("late_cus", 32), k.get("late", 0), None)
-    assert call(late_cus=0) == -1 and call(late_cus=4) == -1 and call(late_cus=300) == -1 and call(late=2) == -1
+        k.get("ws", A16), k.get("wsb", 1 << 30), k.get("first_cus", 224), k.get("late_cus", 32), None, None)
+    assert call(late_cus=4) == -1 and call(late_cus=300) == -1 and call(late_cus=-1) == -1
+    assert b"late_cus" in lib.actqkv_last_error()
+    assert call(first_cus=0) == -1 and call(first_cus=257) == -1 and b"first_cus" in lib.actqkv_last_error()
     assert call(q=None) == -1 and call(out=A16 + 2) == -3 and call(ws=None) == -4 and call(wsb=8) == -4
-    assert call(late=1, q=None) == -1                       # the second call checks its arguments too
 
 
 def test_cutoff_next_step_rejects(lib):

@@ -157,24 +157,16 @@ def test_c3_128k_two_stream_pipeline_as_benchmarked():
     runner.reset()
     plan.budget.copy_(bud0)
     pipe.idx.fill_(-1)
-    B.set_attention_cus(224)
-    try:
-        pipe.run(qd, kc, vc, repd, out_two, overlap=True)
-        torch.cuda.synchronize()
-    finally:
-        B.set_attention_cus(256)
+    pipe.run(qd, kc, vc, repd, out_two, overlap=True, attention_cus=224)
+    torch.cuda.synchronize()
     assert torch.equal(pipe.idx, idx_order) and torch.equal(pipe.n_sel, nsel_order)
     # the same with scoring and selection kept on the probes' stream
     out_b = torch.zeros_like(qd)
     runner.reset()
     plan.budget.copy_(bud0)
     pipe.idx.fill_(-1)
-    B.set_attention_cus(224)
-    try:
-        pipe.run(qd, kc, vc, repd, out_b, overlap=True, score_chunk=0)
-        torch.cuda.synchronize()
-    finally:
-        B.set_attention_cus(256)
+    pipe.run(qd, kc, vc, repd, out_b, overlap=True, score_chunk=0, attention_cus=224)
+    torch.cuda.synchronize()
     assert torch.equal(pipe.idx, idx_order) and torch.equal(pipe.n_sel, nsel_order)
     assert torch.equal(out_b, out_two)
     diff = (out_two.float() - out_order.float()).abs().max().item()
@@ -187,12 +179,8 @@ def test_c3_128k_two_stream_pipeline_as_benchmarked():
     runner.reset()
     plan.budget.copy_(bud0)
     pipe.idx.fill_(-1)
-    B.set_attention_cus(224)
-    try:
-        pipe.run(qd, kc, vc, repd, out_c, overlap=True, batched=True)
-        torch.cuda.synchronize()
-    finally:
-        B.set_attention_cus(256)
+    pipe.run(qd, kc, vc, repd, out_c, overlap=True, batched=True, attention_cus=224)
+    torch.cuda.synchronize()
     assert torch.equal(pipe.n_sel, nsel_order)
     differ = [t for t in range(w.n_windows) if not torch.equal(pipe.idx[t], idx_order[t])]
     assert len(differ) <= w.n_windows // 50, f"{len(differ)} windows select differently: {differ[:8]}"
@@ -210,12 +198,8 @@ def test_c3_128k_two_stream_pipeline_as_benchmarked():
         plan.budget.copy_(bud0)
         idx_c = pipe.idx.clone()
         pipe.idx.fill_(-1)
-        B.set_attention_cus(224)
-        try:
-            pipe.run(qd, kc, vc, repd, out_d, overlap=True, batched=True, late_cus=32)
-            torch.cuda.synchronize()
-        finally:
-            B.set_attention_cus(256)
+        pipe.run(qd, kc, vc, repd, out_d, overlap=True, batched=True, late_cus=32, attention_cus=224)
+        torch.cuda.synchronize()
         assert torch.equal(pipe.idx, idx_c) and torch.equal(pipe.n_sel, nsel_order)
         assert torch.equal(out_d, out_c), f"two teams of attention workgroups, run {rep_run}"
         assert not pipe.ws_attn[:8192].any() and not pipe.ws_attn_b[:8192].any()   # tickets and queue back at zero
@@ -401,33 +385,37 @@ def test_queued_attention_equals_one_call_per_window(per_head):
         B.retrieval_attention(cs, 1, m, q[i * m:(i + 1) * m], kc, vc, 0, nb, n_ctx[i:i + 1],
                               idx[i * step:(i + 1) * step], n_sel[i * step:(i + 1) * step], k_cap,
                               ref[i * m:(i + 1) * m], None, ws, per_head=per_head)
-    B.set_attention_cus(192)
-    try:
-        outs = []
-        for run in range(2):
-            out = torch.zeros_like(q)
+    # on 192 of the chip's compute units: the windows' items go through the queue
+    side = torch.cuda.Stream(device=DEV)
+    outs = []
+    for run in range(2):
+        out = torch.zeros_like(q)
+        if per_head:
             B.retrieval_attention(cs, nw, m, q, kc, vc, 0, nb, n_ctx, idx, n_sel, k_cap, out, None, ws,
                                   per_head=per_head)
+        else:
+            B.retrieval_attention_teams(cs, nw, m, q, kc, vc, 0, nb, n_ctx, idx, n_sel, k_cap, out, None, ws,
+                                        192, 0)
+        torch.cuda.synchronize()
+        # (a one-window call cuts its key tiles into pieces and merges partial results: another
+        # summation order, so the last bits of a bf16 output may differ)
+        err = ((out.float() - ref.float()).abs().amax(dim=-1) / ref.float().abs().amax(dim=-1)).max().item()
+        assert err < 1e-2, f"run {run}: {err}"
+        assert not ws[:8192].any()
+        outs.append(out)
+    assert torch.equal(outs[0], outs[1])              # whoever takes an item, the same bits
+    if not per_head:
+        # two teams of workgroups, the second one on the same stream (it then finds the queue empty)
+        # and on a stream of its own (it then draws beside the first team): the same bits, and the
+        # queue back at zero
+        for late_stream in (None, side):
+            out = torch.zeros_like(q)
+            if late_stream is not None:
+                late_stream.wait_stream(torch.cuda.current_stream())
+            B.retrieval_attention_teams(cs, nw, m, q, kc, vc, 0, nb, n_ctx, idx, n_sel, k_cap, out, None, ws,
+                                        192, 32, None, late_stream)
             torch.cuda.synchronize()
-            # (a one-window call cuts its key tiles into pieces and merges partial results: another
-            # summation order, so the last bits of a bf16 output may differ)
-            err = ((out.float() - ref.float()).abs().amax(dim=-1) / ref.float().abs().amax(dim=-1)).max().item()
-            assert err < 1e-2, f"run {run}: {err}"
-            assert not ws[:8192].any()
-            outs.append(out)
-        assert torch.equal(outs[0], outs[1])              # whoever takes an item, the same bits
-        if not per_head:
-            # two teams of workgroups, the second one launched FIRST (it then draws every item but the
-            # first team's first round), and in the documented order: the same bits, the queue at zero
-            for order in ((True, False), (False, True)):
-                out = torch.zeros_like(q)
-                for late in order:
-                    B.retrieval_attention_teams(cs, nw, m, q, kc, vc, 0, nb, n_ctx, idx, n_sel, k_cap, out, None, ws,
-                                                32, late)
-                torch.cuda.synchronize()
-                assert torch.equal(out, outs[0]) and not ws[:8192].any()
-    finally:
-        B.set_attention_cus(256)
+            assert torch.equal(out, outs[0]) and not ws[:8192].any()
 
 
 def _lse_reference(q_row, k, pos, group):
@@ -1488,12 +1476,8 @@ def test_graph_replays_of_a_decode_step_and_of_a_prefill_pass():
     def prefill():
         r2.stats.zero_()
         plan.budget.copy_(bud0)
-        pipe.run(qd, kcp, vcp, repd, outp, overlap=True, chunk=8, batched=True, late_cus=32)
-    B.set_attention_cus(224)
-    try:
-        _replays_equal_eager(prefill, [outp, pipe.idx, pipe.n_sel])
-    finally:
-        B.set_attention_cus(256)
+        pipe.run(qd, kcp, vcp, repd, outp, overlap=True, chunk=8, batched=True, late_cus=32, attention_cus=224)
+    _replays_equal_eager(prefill, [outp, pipe.idx, pipe.n_sel])
 
 
 @pytest.mark.parametrize("group", [1, 2, 3, 4, 5, 6, 7, 8])
@@ -1837,13 +1821,9 @@ def test_pipeline_with_ragged_last_window_and_short_context():
             runner.reset()
             plan.budget.copy_(bud0)
             out = torch.zeros_like(qd)
-            B.set_attention_cus(224 if overlap else 256)
-            try:
-                pipe.run(qd, kc, vc, repd, out, overlap=overlap, chunk=4, score_chunk=4, batched=batched,
-                         late_cus=late)
-                torch.cuda.synchronize()
-            finally:
-                B.set_attention_cus(256)
+            pipe.run(qd, kc, vc, repd, out, overlap=overlap, chunk=4, score_chunk=4, batched=batched,
+                     late_cus=late, attention_cus=224 if overlap else 256)
+            torch.cuda.synchronize()
             outs.append((out, pipe.idx.clone(), pipe.n_sel.clone()))
         for other in outs[1:]:
             assert torch.equal(outs[0][1], other[1]) and torch.equal(outs[0][2], other[2])

@@ -451,7 +451,6 @@ def test_representative_tokens_hand_example_with_tie():
 def test_representative_tokens_against_brute_force_and_torch_recipe():
     import itertools
     import torch
-    from paper_2502_13542_amd import synth
     rng = np.random.default_rng(11)
     kb = rng.standard_normal((9, 2, 4))
     norms = np.sqrt((kb ** 2).sum(axis=(1, 2)))
@@ -459,11 +458,34 @@ def test_representative_tokens_against_brute_force_and_torch_recipe():
         # the chosen set maximises the sum of norms over all r-subsets (distinct norms: unique)
         best = max(itertools.combinations(range(9), r), key=lambda c: norms[list(c)].sum())
         assert orc.representative_tokens(kb, r) == sorted(best)
-    # an independent implementation (torch stable sort) on a few blocks
+    # an independent recipe (torch: norms, stable descending sort, positions back in order) on a few
+    # blocks; the ragged tail of 17 tokens has no representatives
     k = torch.randn(3 * 128 + 17, 4, 16, generator=torch.Generator().manual_seed(3))
-    want = synth.pick_rep_keys(k, 128, 4).numpy()
+    kb3 = k[: 3 * 128].reshape(3, 128, 4, 16)
+    norm2 = kb3.double().pow(2).sum(dim=(2, 3))                                   # [block][token]
+    top = torch.sort(norm2, dim=1, descending=True, stable=True).indices[:, :4]
+    pos = torch.sort(top, dim=1).values                                           # position order
+    want = torch.stack([kb3[b, pos[b]] for b in range(3)]).numpy()
     got = orc.representative_keys(k.numpy(), 128, 4)
     assert got.shape == want.shape and np.array_equal(got, want)
+
+
+def test_small_branches_of_the_statistics_and_the_budget():
+    # Eq. (12) with nothing to divide by (one eligible block: density ln 1 = 0, and no layer to come):
+    # the layer takes the whole remaining budget
+    assert orc.layer_budget(0.0, 0.0, 7.25) == 7.25
+    assert orc.layer_budget(0.0, 3.0, 7.25) == 0.0            # a zero density beside layers to come: nothing
+    # Eq. (8) after a single query: no spread to estimate, the variance is 0 in every channel
+    st = orc.RunningStats(3)
+    z, s2 = st.update(np.array([[1.0, -2.0, 0.5]]))
+    assert np.array_equal(z, [1.0, -2.0, 0.5]) and np.array_equal(s2, [0.0, 0.0, 0.0])
+    # Eq. (7): eps is a floor under the variance, max(var, eps), not an added term.  With a
+    # variance of eps/4 the divisor is eps; with 4 eps it is 4 eps (var + eps would give 1.25 eps
+    # and 5 eps)
+    eps = 1e-6
+    q, z = np.array([[2.0, 2.0]]), np.zeros(2)
+    phi = orc.activation_bias(q, z, np.array([eps / 4, 4 * eps]), eps)
+    assert phi[0] == pytest.approx([4.0 / eps, 4.0 / (4 * eps)], rel=1e-12)
 
 
 # ---------------------------------------------------------------- Eq. (12) across layers and steps
