@@ -203,6 +203,28 @@ int actqkv_retrieval_attention(const actqkv_shape* shape, int batch, int m, cons
                                const int32_t* n_sel, int k_cap, void* out, float* lse,
                                void* workspace, size_t ws_bytes, void* stream);
 
+/* actqkv_retrieval_attention for callers that cannot allocate or bring a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch memory
+ * the attention kernels use (ticket and queue counters, partial results of query tiles whose key
+ * tiles are cut into pieces, partial results of decode sequences split over several workgroups)
+ * is an array of ACTQKV_STATIC_SCRATCH_BYTES that is part of the library's device code; every
+ * GPU the library runs on holds its own copy from the first call on it until the process ends.
+ * The call allocates and frees nothing.  The first call on a device looks the array's address up
+ * (it may load the library's code onto the device): make that one call outside graph capture.
+ *   Arguments, results and errors as in actqkv_retrieval_attention, without the workspace.
+ *   A call that would need more scratch than the array holds is refused with ACTQKV_EWORKSPACE
+ *   and a message that states both sizes (one window of up to 8192 tokens and decode batches of
+ *   up to 1024 sequences at the 32-head shape fit).
+ *   All calls on one GPU share the array: two calls that overlap in time on one GPU (two streams,
+ *   two threads) race and give wrong results; order them on one stream.  Every call first puts the
+ *   counters at the head of the array back to zero with a small kernel on `stream`. */
+#define ACTQKV_STATIC_SCRATCH_BYTES (32u << 20)
+int actqkv_retrieval_attention_static(const actqkv_shape* shape, int batch, int m, const void* q,
+                                      const void* k_cache, const void* v_cache, int64_t seq_stride,
+                                      int nb_capacity, const int32_t* n_ctx, const int32_t* idx,
+                                      const int32_t* n_sel, int k_cap, void* out, float* lse,
+                                      void* stream);
+
 /* Cache update (Sec. 3.1, Eq. (4): the cache after a step is the cache before it with the
  * step's keys and values appended), written in the blocked layouts above, and the
  * representative keys of every block the new tokens complete.

@@ -56,6 +56,8 @@ SIGNATURES = {
     "actqkv_select": (_i, [_i, _vp, _i64, _i, _i, _vp, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_retrieval_attention": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
                                         _vp, _vp, _vp, _sz, _vp]),
+    "actqkv_retrieval_attention_static": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
+                                               _vp, _vp, _vp]),
     "actqkv_retrieval_attention_per_head": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
                                                  _vp, _vp, _vp, _sz, _vp]),
     "actqkv_score_blocks_per_head": (_i, [_shp, _i, _vp, _vp, _i64, _i, _i, _vp, _vp, _i64, _vp]),
@@ -196,6 +198,16 @@ def decode_select_attention(shape: CShape, batch: int, q, k_cache, v_cache, seq_
         _ptr(budget_in, f), _ptr(theta_rest_sum, f), _ptr(budget_after, f), _ptr(idx, i32), _ptr(n_sel, i32),
         _ptr(theta, f), _ptr(budget, f), _ptr(out, st), _ptr(lse, f), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def retrieval_attention_static(shape: CShape, batch: int, m: int, q, k_cache, v_cache, seq_stride: int,
+                               nb_capacity: int, n_ctx, idx, n_sel, k_cap: int, out, lse, stream=None) -> None:
+    """The attention with the library's own scratch array instead of a workspace; see the header."""
+    st = torch.float32 if shape.dtype == ACTQKV_F32 else torch.bfloat16
+    _check(load_library().actqkv_retrieval_attention_static(
+        ctypes.byref(shape), batch, m, _ptr(q, st), _ptr(k_cache, st), _ptr(v_cache, st),
+        seq_stride, nb_capacity, _ptr(n_ctx, torch.int32), _ptr(idx, torch.int32),
+        _ptr(n_sel, torch.int32), k_cap, _ptr(out, st), _ptr(lse, torch.float32), _stream(stream)))
 
 
 def retrieval_attention_teams(shape: CShape, batch: int, m: int, q, k_cache, v_cache, seq_stride: int,

@@ -11,7 +11,7 @@ LIB = os.path.join(HERE, "libactqkv.so")
 
 SOURCES = ["api.hip", "probe.hip", "score.hip", "select.hip", "attn_rows.hip",
            "attn_prefill_mfma.hip", "attn_decode.hip", "append.hip", "cutoff.hip", "gather.hip",
-           "decode_retrieve.hip"]
+           "decode_retrieve.hip", "attn_static.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed fp32 instructions are kept out of the generated code

@@ -233,6 +233,20 @@ def test_retrieval_attention_teams_rejects(lib):
     assert call(q=None) == -1 and call(out=A16 + 2) == -3 and call(ws=None) == -4 and call(wsb=8) == -4
 
 
+def test_retrieval_attention_static_rejects(lib):
+    """The entry point that allocates nothing: argument errors as in actqkv_retrieval_attention, and
+    a call whose scratch need exceeds the library's own array is refused before anything runs."""
+    cs = B.c_shape(LLAMA)
+    call = lambda shape=cs, batch=1, m=512, **k: lib.actqkv_retrieval_attention_static(
+        ctypes.byref(shape), batch, m, k.get("q", A16), A16, A16, 0, k.get("nb", 1024), A16, A16, A16,
+        k.get("k_cap", 32), k.get("out", A16), None, None)
+    assert call(q=None) == -1 and call(out=A16 + 2) == -3 and call(k_cap=65) == -2 and call(m=0) == -1
+    big = B.c_shape(LayerShape(128, 16, 128, 128, 4, 128, 512, "bf16"))
+    assert call(shape=big, batch=1024, m=1, nb=2) == -4
+    msg = lib.actqkv_last_error().decode()
+    assert "scratch" in msg and str(32 << 20) in msg
+
+
 def test_cutoff_next_step_rejects(lib):
     f = ctypes.c_float
     call = lambda batch=2, L=32, k=8.0, prior=6.0, prev=A16, ts=A16, ns=A16, b=A16, r=A16: \
