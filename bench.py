@@ -172,12 +172,12 @@ def bench_prefill(args, torch, B, H, synth):
     pipe = H.PrefillPipeline(runner, plan)
     nsel_log = pipe.n_sel
 
-    def one_step(events=None, overlap=False):
+    def one_step(events=None, overlap=False, prelude_events=None):
         runner.stats.zero_()
         if bud0 is not None:
             plan.budget.copy_(bud0)
         pipe.run(q, kc, vc, repd, out, overlap, events, args.chunk, args.score_chunk, not args.per_window_selection,
-                 args.attention_late_cus if overlap else 0, args.attention_cus if overlap else 256)
+                 args.attention_late_cus if overlap else 0, args.attention_cus if overlap else 256, prelude_events)
 
     if args.pmc_pass:
         return pmc_pass(torch, B, lambda: one_step(overlap=not args.no_overlap),
@@ -209,7 +209,9 @@ def bench_prefill(args, torch, B, H, synth):
     # ---- roofline of the dominant kernel: the prefill attention launches of one eager pass in
     # the schedule that was timed, events on the stream the attention runs on
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_win)]
-    one_step(ev, overlap)
+    batched = overlap and not args.per_window_selection
+    pre = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_win)]
+    one_step(ev, overlap, pre if batched else None)
     torch.cuda.synchronize()
     n_sel = nsel_log.cpu().tolist()
     flops = sum(attention_flops(sh, plan.w0[t], plan.rows[t], n_sel[t], H.local_start(sh, plan.w0[t]))
@@ -257,6 +259,33 @@ def bench_prefill(args, torch, B, H, synth):
                      "timing": "HIP events, on the stream the attention runs on, around every attention "
                                "launch of one eager pass of the step in the timed schedule"},
     }
+    if batched:
+        # The other chain: probes, scores and selections of a chunk of windows (actqkv_build_probe,
+        # actqkv_score_blocks, actqkv_select: 6 launches), timed on the stream they run on, beside the
+        # attention of the chunk before.  Algorithmic bytes: every window's queries once and the
+        # representative keys of its eligible blocks once.
+        starts_all = list(pipe.chunk_starts)
+        pre_us = [pre[t][0].elapsed_time(pre[t][1]) * 1e3 for t in starts_all]
+        elem = 4 if sh.dtype == "fp32" else 2
+        pre_bytes = []
+        for i, t0 in enumerate(starts_all):
+            t1 = starts_all[i + 1] if i + 1 < len(starts_all) else n_win
+            byt = 0
+            for t in range(t0, t1):
+                b, e = H.eligible_range(sh, plan.w0[t])
+                byt += plan.rows[t] * sh.n_q_heads * sh.head_dim * elem
+                byt += (e - b) * sh.n_rep * sh.n_kv_heads * sh.head_dim * elem
+            pre_bytes.append(byt)
+        tot_us, tot_b = sum(pre_us), float(sum(pre_bytes))
+        res["prelude"] = {"bound": "hbm", "achieved": tot_b / (tot_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS,
+                          "unit": "GB/s", "frac": tot_b / (tot_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
+                          "kernels": "probe_rows_moments, probe_chain_stats, probe_rows_bias_weigh, "
+                                     "probe_chain_finish, score_blocks, select (one call of each per chunk)",
+                          "us_per_chunk": [round(u, 1) for u in pre_us],
+                          "algorithmic_mb_per_chunk": [round(b / 1e6, 1) for b in pre_bytes],
+                          "timing": "HIP events on the stream of the chain, around the three calls of every chunk, "
+                                    "in the same eager pass as the attention's; the chain shares the chip with "
+                                    "the attention of the chunk before (%d of 256 CUs)" % args.attention_cus}
     if not args.no_cpu_baseline:
         T = n_win
         stride = max(T // 48, 1)                  # about 48 windows, 10-20 s of oracle time
@@ -460,48 +489,83 @@ def bench_decode(args, torch, B, H, synth):
         torch.sub(n_ctx_cur, 1, out=pos_cur)
         nb_end_cur.copy_(nb_end_all[t])
 
-    def one_step(events=None, launches=None):
-        launches = args.decode_launches if launches is None else launches
-        # folds the step before into the history; B_kv = L * k again; R^l for every layer
-        B.cutoff_next_step(bt, L, k_mean, theta_prior, theta_step, theta_sum, hist_steps, budget, rest_all)
+    # The sequences of a batch do not depend on each other: with --decode-streams 2 the batch is cut
+    # into two halves whose layer chains run on two streams, so that one half streams keys and values
+    # while the other is in a latency-bound stretch (selection, merge of partials, launch boundary).
+    n_streams = max(1, args.decode_streams)
+    assert bt % n_streams == 0
+    hb = bt // n_streams
+    side_streams = [torch.cuda.Stream(device=dev) for _ in range(n_streams - 1)]
+    runners = [runner] + [H.LayerRunner(sh, hb, 1, nb_cap, w.k_cap, dev) for _ in range(n_streams - 1)]
+
+    def layer_chain(part, events, launches):
+        lo, hi = part * hb, (part + 1) * hb
+        r = runners[part]
+        sl = slice(lo, hi)
         for l in range(L):
+            if launches == 1:
+                # the whole layer in one launch
+                if events is not None:
+                    events[l][0].record()
+                B.decode_layer(r.cs, hb, q_step[l][sl], k_step[l][sl].view(hb, hk, D), v_step[l][sl].view(hb, hk, D),
+                               kc[l][sl], vc[l][sl], cache_stride, rep[l][sl], rep_stride, nb_cap, n_ctx_cur[sl],
+                               nb_begin, nb_end_cur[sl], r.scores, r.score_stride, w.k_cap, budgets[l % 2][sl],
+                               rest_all[l][sl], budgets[(l + 1) % 2][sl], r.idx, nsel_log[l][sl], theta_step[l][sl],
+                               None, out[l][sl], None, r.workspace)
+                if events is not None:
+                    events[l][1].record()
+                continue
             if launches == 2:
                 # cache update, probe and scores in one launch, selection and attention in the other
-                B.decode_retrieve(runner.cs, bt, q_step[l], k_step[l], v_step[l], pos_cur, kc[l], vc[l],
-                                  cache_stride, rep[l], rep_stride, nb_cap, nb_begin, nb_end_cur, None, None,
-                                  None, runner.scores, runner.score_stride, w.k_cap, None, None, None, None,
+                B.decode_retrieve(r.cs, hb, q_step[l][sl], k_step[l][sl], v_step[l][sl], pos_cur[sl], kc[l][sl],
+                                  vc[l][sl], cache_stride, rep[l][sl], rep_stride, nb_cap, nb_begin, nb_end_cur[sl],
+                                  None, None, None, r.scores, r.score_stride, w.k_cap, None, None, None, None,
                                   None, None, None, flags=B.DECODE_SCORES_ONLY)
                 if events is not None:
                     events[l][0].record()
-                B.decode_select_attention(runner.cs, bt, q_step[l], kc[l], vc[l], cache_stride, nb_cap,
-                                          n_ctx_cur, runner.scores, runner.score_stride, nb_begin, nb_end_cur,
-                                          w.k_cap, budgets[l % 2], rest_all[l], budgets[(l + 1) % 2],
-                                          runner.idx, nsel_log[l], theta_step[l], None, out[l], None,
-                                          runner.workspace)
+                B.decode_select_attention(r.cs, hb, q_step[l][sl], kc[l][sl], vc[l][sl], cache_stride, nb_cap,
+                                          n_ctx_cur[sl], r.scores, r.score_stride, nb_begin, nb_end_cur[sl],
+                                          w.k_cap, budgets[l % 2][sl], rest_all[l][sl], budgets[(l + 1) % 2][sl],
+                                          r.idx, nsel_log[l][sl], theta_step[l][sl], None, out[l][sl], None,
+                                          r.workspace)
                 if events is not None:
                     events[l][1].record()
                 continue
             if launches == 3:
                 # cache update, probe and scores in one launch, then the selection
-                B.decode_retrieve(runner.cs, bt, q_step[l], k_step[l], v_step[l], pos_cur, kc[l], vc[l],
-                                  cache_stride, rep[l], rep_stride, nb_cap, nb_begin, nb_end_cur, None, None,
-                                  None, runner.scores, runner.score_stride, w.k_cap, budget, rest_all[l],
-                                  runner.idx, nsel_log[l], theta_step[l], None)
+                B.decode_retrieve(r.cs, hb, q_step[l][sl], k_step[l][sl], v_step[l][sl], pos_cur[sl], kc[l][sl],
+                                  vc[l][sl], cache_stride, rep[l][sl], rep_stride, nb_cap, nb_begin, nb_end_cur[sl],
+                                  None, None, None, r.scores, r.score_stride, w.k_cap, budget[sl], rest_all[l][sl],
+                                  r.idx, nsel_log[l][sl], theta_step[l][sl], None)
             else:
-                B.append_kv_probe(runner.cs, bt, q_step[l], k_step[l], v_step[l], pos_cur, kc[l], vc[l],
-                                  cache_stride, rep[l], rep_stride, nb_cap, runner.probe, runner.probe_kv,
-                                  runner.probe_norm)
-                B.score_blocks(runner.cs, bt, runner.probe_kv, runner.probe_norm, rep[l], rep_stride,
-                               nb_end_host[-1], nb_begin, nb_end_cur, runner.scores, runner.score_stride)
-                B.select(bt, runner.scores, runner.score_stride, nb_end_host[-1], nb_begin, nb_end_cur,
-                         w.k_cap, budget, rest_all[l], runner.idx, nsel_log[l], theta_step[l], None)
+                B.append_kv_probe(r.cs, hb, q_step[l][sl], k_step[l][sl], v_step[l][sl], pos_cur[sl], kc[l][sl],
+                                  vc[l][sl], cache_stride, rep[l][sl], rep_stride, nb_cap, r.probe, r.probe_kv,
+                                  r.probe_norm)
+                B.score_blocks(r.cs, hb, r.probe_kv, r.probe_norm, rep[l][sl], rep_stride,
+                               nb_end_host[-1], nb_begin, nb_end_cur[sl], r.scores, r.score_stride)
+                B.select(hb, r.scores, r.score_stride, nb_end_host[-1], nb_begin, nb_end_cur[sl],
+                         w.k_cap, budget[sl], rest_all[l][sl], r.idx, nsel_log[l][sl], theta_step[l][sl], None)
             if events is not None:
                 events[l][0].record()
-            B.retrieval_attention(runner.cs, bt, 1, q_step[l], kc[l], vc[l], cache_stride, nb_cap,
-                                  n_ctx_cur, runner.idx, nsel_log[l], w.k_cap, out[l], None,
-                                  runner.workspace)
+            B.retrieval_attention(r.cs, hb, 1, q_step[l][sl], kc[l][sl], vc[l][sl], cache_stride, nb_cap,
+                                  n_ctx_cur[sl], r.idx, nsel_log[l][sl], w.k_cap, out[l][sl], None,
+                                  r.workspace)
             if events is not None:
                 events[l][1].record()
+
+    def one_step(events=None, launches=None):
+        launches = args.decode_launches if launches is None else launches
+        # folds the step before into the history; B_kv = L * k again; R^l for every layer
+        B.cutoff_next_step(bt, L, k_mean, theta_prior, theta_step, theta_sum, hist_steps, budget, rest_all)
+        cur = torch.cuda.current_stream()
+        for st in side_streams:
+            st.wait_stream(cur)
+        for part in range(n_streams - 1, 0, -1):
+            with torch.cuda.stream(side_streams[part - 1]):
+                layer_chain(part, None, launches)
+        layer_chain(0, events, launches)
+        for st in side_streams:
+            cur.wait_stream(st)
 
     load_step(0)
     # the first step has no history: the prior stands in for every layer's mean density
@@ -522,6 +586,7 @@ def bench_decode(args, torch, B, H, synth):
         run()
     torch.cuda.synchronize()
     times = []
+    nsel_sum = torch.zeros(L, bt, dtype=torch.int64, device=dev)      # blocks recalled per layer, over the steps
     t_all0 = time.perf_counter()
     for t in range(steps):
         load_step(t)
@@ -530,6 +595,7 @@ def bench_decode(args, torch, B, H, synth):
         run()
         torch.cuda.synchronize()
         times.append(time.perf_counter() - t0)
+        nsel_sum += nsel_log
     t_all = time.perf_counter() - t_all0
     times.sort()
     # roofline of the decode attention kernel: one eager step with events
@@ -545,13 +611,15 @@ def bench_decode(args, torch, B, H, synth):
     attn_ms = sum(a.elapsed_time(b) for (a, b) in ev)
     # the attention launch without the selection inside it (selection as a launch of its own)
     alone_ms, alone_byt = attn_ms, byt
-    if args.decode_launches == 2:
+    if args.decode_launches <= 2:
         one_step(ev, launches=3)
         torch.cuda.synchronize()
         alone_ms = sum(a.elapsed_time(b) for (a, b) in ev)
         alone_byt = float(((nsel_log.sum().item() * bs) + keys * L * bt) * hk * D * 2 * 2)
     score_bytes = float((nb_end_host[-1] - nb_begin) * sh.n_rep * hk * D * 2 * L * bt)
-    achieved = byt / (attn_ms * 1e-3) / 1e9
+    launch_byt = byt + score_bytes if args.decode_launches == 1 else byt    # the one launch also scores
+    achieved = launch_byt / (attn_ms * 1e-3) / 1e9
+    per_layer_e = (nsel_sum.double().sum(dim=1) / (steps * bt)).cpu().tolist()
     mean_us = sum(times) / len(times) * 1e6
     return {
         "metric": "decode step us", "value": mean_us, "unit": "us/step", "p50_us": times[len(times) // 2] * 1e6,
@@ -559,16 +627,21 @@ def bench_decode(args, torch, B, H, synth):
         "config": {"workload": f"{w.name}: batch {bt}, {L} layers, {n0} cached tokens, k_cap {w.k_cap}, "
                                f"dynamic cut-off with the density history on the device, new token appended per layer, KV cache {gb:.0f} GB bf16 in HBM",
                    "mean_blocks_selected": float(n_sel.float().mean()),
+                   # the synthetic analogue of the paper's blocks-recalled-per-layer figure (Sec. 5.4):
+                   # mean E^l over all steps and sequences, layer 0 first
+                   "mean_blocks_selected_per_layer": [round(e, 3) for e in per_layer_e],
                    "launch": "hip graph replay" if graph is not None else "eager",
                    "launches_per_layer": args.decode_launches},
         "algorithmic_bytes_per_step": byt + score_bytes,
         "hbm_frac_of_step": (byt + score_bytes) / (mean_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBS, **traffic_fields(w.name),
-                     "kernel": ("actqkv_decode_select_attention launch (attn_decode_select_kernel: selection + attention)"
+                     "kernel": ("actqkv_decode_layer launch (decode_layer_kernel: cache update + probe + scores + "
+                                "selection + attention of one layer)" if args.decode_launches == 1 else
+                                "actqkv_decode_select_attention launch (attn_decode_select_kernel: selection + attention)"
                                 if args.decode_launches == 2 else
                                 "actqkv_retrieval_attention launch, m = 1 (attn_decode_kernel)"),
-                     "avg_launch_us": attn_ms * 1e3 / L, "algorithmic_mb_per_launch": byt / L / 1e6,
+                     "avg_launch_us": attn_ms * 1e3 / L, "algorithmic_mb_per_launch": launch_byt / L / 1e6,
                      "timing": "HIP events around every attention launch of one eager step",
                      "attention_alone": {"avg_launch_us": alone_ms * 1e3 / L,
                                          "achieved": alone_byt / (alone_ms * 1e-3) / 1e9,
@@ -591,10 +664,13 @@ def main() -> int:
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--decode-layers", type=int, default=0, help="override the layer count (testing)")
-    ap.add_argument("--decode-launches", type=int, default=2, choices=(2, 3, 4),
-                    help="launches per layer of a decode step: 2 = (cache update + probe + scores), (selection + "
+    ap.add_argument("--decode-launches", type=int, default=2, choices=(1, 2, 3, 4),
+                    help="launches per layer of a decode step: 1 = the whole layer (actqkv_decode_layer); "
+                         "2 = (cache update + probe + scores), (selection + "
                          "attention); 3 = (cache update + probe + scores), selection, attention; "
                          "4 = (cache update + probe), scores, selection, attention")
+    ap.add_argument("--decode-streams", type=int, default=1,
+                    help="decode: the batch in this many parts, each part's layer chain on a stream of its own")
     ap.add_argument("--no-overlap", action="store_true",
                     help="prefill: one stream, strictly in window order")
     ap.add_argument("--chunk", type=int, default=32,

@@ -50,7 +50,7 @@
 extern "C" {
 #endif
 
-#define ACTQKV_VERSION 105
+#define ACTQKV_VERSION 106
 
 enum {
   ACTQKV_OK = 0,
@@ -73,8 +73,10 @@ enum {
 /* Bits of the flags argument of actqkv_select and of the decode-step calls. */
 enum {
   ACTQKV_SELECT_ENTROPY_TOPK = 1, /* density over the k_cap best blocks only (see actqkv_select) */
-  ACTQKV_DECODE_SCORES_ONLY = 2   /* actqkv_decode_retrieve stops after the scores (the caller selects,
+  ACTQKV_DECODE_SCORES_ONLY = 2,  /* actqkv_decode_retrieve stops after the scores (the caller selects,
                                      for instance inside actqkv_decode_select_attention) */
+  ACTQKV_DECODE_NO_WAIT = 4       /* actqkv_decode_layer: no workgroup waits for the scores of the others;
+                                     each scores its whole sequence itself (same results, slower) */
 };
 
 /* Limits checked by every call (ACTQKV_ESHAPE otherwise):
@@ -380,6 +382,38 @@ int actqkv_decode_select_attention(const actqkv_shape* shape, int batch, const v
                                    const float* theta_rest_sum, float* budget_after, int32_t* idx,
                                    int32_t* n_sel, float* theta, float* budget, void* out,
                                    float* lse, void* workspace, size_t ws_bytes, void* stream);
+
+/* A whole layer of a decode step in ONE launch: the cache update (Sec. 3.1, Eq. (4)), the probe of
+ * the one-token window (the query itself, Sec. 4.2), the block scores (Eq. (10)), density, budget
+ * and selection (Eq. (11), Eq. (12), Alg. 1) and the attention (Sec. 3.1, Eq. (3)) - what
+ * actqkv_decode_retrieve followed by actqkv_decode_select_attention do in two.  The workgroups of
+ * a sequence share its scoring, publish their scores and attend over the initial tokens and the
+ * local span; then each repeats the sequence's selection and attends over the chosen blocks.  A
+ * workgroup waits for the others' scores for a bounded time only (2 ms) and otherwise scores the
+ * whole sequence itself, so the launch ends whatever else occupies the chip.
+ * Supported for bf16 storage, head_dim 128, at most 8 query heads per KV head, batch <= 384
+ * (ACTQKV_ESHAPE otherwise).
+ *   q        [batch][1][H][D]: the step's queries.
+ *   k_new, v_new  [batch][Hk][D]: key and value of the step's token, written to position
+ *            n_ctx[s] - 1 of the caches (both NULL: the caches already hold it).
+ *   k_cache, v_cache, cache_seq_stride, rep_keys, rep_seq_stride, nb_capacity
+ *            as in actqkv_append_kv; rep_keys is required (it is what gets scored); the entries of
+ *            a block that the token completes are written.
+ *   n_ctx    device int32 [batch]: tokens in the cache including the step's token.
+ *   nb_begin, nb_end, scores, score_stride  as in actqkv_score_blocks; scores of the eligible
+ *            blocks are written.  nb_end[s] must not reach the block of position n_ctx[s] - 1.
+ *   k_cap, flags (ACTQKV_SELECT_ENTROPY_TOPK, ACTQKV_DECODE_NO_WAIT), budget_in, theta_rest_sum,
+ *   budget_after, idx, n_sel, theta, budget  as in actqkv_decode_select_attention.
+ *   out, lse, workspace  as in actqkv_retrieval_attention with m = 1.
+ * Results: scores and selection as the two calls give them; the output up to the order of fp32
+ * sums. */
+int actqkv_decode_layer(const actqkv_shape* shape, int batch, const void* q, const void* k_new,
+                        const void* v_new, void* k_cache, void* v_cache, int64_t cache_seq_stride,
+                        void* rep_keys, int64_t rep_seq_stride, int nb_capacity, const int32_t* n_ctx,
+                        int nb_begin, const int32_t* nb_end, float* scores, int64_t score_stride, int k_cap,
+                        int flags, const float* budget_in, const float* theta_rest_sum, float* budget_after,
+                        int32_t* idx, int32_t* n_sel, float* theta, float* budget, void* out, float* lse,
+                        void* workspace, size_t ws_bytes, void* stream);
 
 /* Selected blocks from a block store into a working cache (Sec. 3.1: the cache may be kept
  * in CPU memory).

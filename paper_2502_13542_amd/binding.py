@@ -21,6 +21,7 @@ ACTQKV_F32, ACTQKV_BF16 = 0, 1
 STATS_UPDATE, PROBE_MEAN_POOLING, PROBE_WINDOW_CHAIN = 1, 2, 4   # bits of build_probe's update_stats
 SELECT_ENTROPY_TOPK = 1                                          # bit of select's flags
 DECODE_SCORES_ONLY = 2                                           # bit of decode_retrieve's flags
+DECODE_NO_WAIT = 4                                               # bit of decode_layer's flags
 ERROR_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EALIGN", -4: "EWORKSPACE", -5: "EHIP"}
 
 
@@ -68,6 +69,8 @@ SIGNATURES = {
                                     _vp, _vp, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_decode_select_attention": (_i, [_shp, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _i64, _i, _vp, _i, _i,
                                             _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "actqkv_decode_layer": (_i, [_shp, _i, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _vp, _i, _vp, _vp, _i64, _i,
+                                 _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "actqkv_retrieval_attention_teams": (_i, [_shp, _i, _i, _vp, _vp, _vp, _i64, _i, _vp, _vp, _vp, _i,
                                               _vp, _vp, _vp, _sz, _i, _i, _vp, _vp]),
     "actqkv_copy_bytes": (_i, [_vp, _vp, _sz, _vp]),
@@ -197,6 +200,21 @@ def decode_select_attention(shape: CShape, batch: int, q, k_cache, v_cache, seq_
         _ptr(n_ctx, i32), _ptr(scores, f), score_stride, nb_begin, _ptr(nb_end, i32), k_cap, int(flags),
         _ptr(budget_in, f), _ptr(theta_rest_sum, f), _ptr(budget_after, f), _ptr(idx, i32), _ptr(n_sel, i32),
         _ptr(theta, f), _ptr(budget, f), _ptr(out, st), _ptr(lse, f), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def decode_layer(shape: CShape, batch: int, q, k_new, v_new, k_cache, v_cache, cache_seq_stride: int,
+                 rep_keys, rep_seq_stride: int, nb_capacity: int, n_ctx, nb_begin: int, nb_end, scores,
+                 score_stride: int, k_cap: int, budget_in, theta_rest_sum, budget_after, idx, n_sel, theta,
+                 budget, out, lse, workspace, stream=None, flags: int = 0) -> None:
+    """A whole layer of a decode step in one launch; see the header."""
+    st, f, i32 = torch.bfloat16, torch.float32, torch.int32
+    _check(load_library().actqkv_decode_layer(
+        ctypes.byref(shape), batch, _ptr(q, st), _ptr(k_new, st), _ptr(v_new, st), _ptr(k_cache, st),
+        _ptr(v_cache, st), cache_seq_stride, _ptr(rep_keys, st), rep_seq_stride, nb_capacity, _ptr(n_ctx, i32),
+        nb_begin, _ptr(nb_end, i32), _ptr(scores, f), score_stride, k_cap, int(flags), _ptr(budget_in, f),
+        _ptr(theta_rest_sum, f), _ptr(budget_after, f), _ptr(idx, i32), _ptr(n_sel, i32), _ptr(theta, f),
+        _ptr(budget, f), _ptr(out, st), _ptr(lse, f), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))
 
 

@@ -457,6 +457,78 @@ int actqkv_decode_select_attention(const actqkv_shape* shape, int batch, const v
                                         static_cast<hipStream_t>(stream));
 }
 
+int actqkv_decode_layer(const actqkv_shape* shape, int batch, const void* q, const void* k_new,
+                        const void* v_new, void* k_cache, void* v_cache, int64_t cache_seq_stride,
+                        void* rep_keys, int64_t rep_seq_stride, int nb_capacity, const int32_t* n_ctx,
+                        int nb_begin, const int32_t* nb_end, float* scores, int64_t score_stride, int k_cap,
+                        int flags, const float* budget_in, const float* theta_rest_sum, float* budget_after,
+                        int32_t* idx, int32_t* n_sel, float* theta, float* budget, void* out, float* lse,
+                        void* workspace, size_t ws_bytes, void* stream) {
+  ACTQKV_TRY(check_shape(shape));
+  ACTQKV_TRY(check_batch(batch));
+  if (!decode_mfma_supported(*shape, 1))
+    return set_error(ACTQKV_ESHAPE, "decode_layer: bf16, head_dim 128 and at most 8 query heads per KV head");
+  if (flags & ~(ACTQKV_SELECT_ENTROPY_TOPK | ACTQKV_DECODE_NO_WAIT))
+    return set_error(ACTQKV_EINVAL, "decode_layer: unknown flag bits: %d", flags);
+  if (nb_capacity < 1) return set_error(ACTQKV_EINVAL, "nb_capacity %d < 1", nb_capacity);
+  if (int64_t(nb_capacity) * shape->block_size > (int64_t(1) << 30))
+    return set_error(ACTQKV_ESHAPE, "cache of %d blocks exceeds 2^30 tokens", nb_capacity);
+  ACTQKV_TRY(check_blocks(nb_capacity, nb_begin, k_cap, true));
+  if (batch > int(kSeqCounters / 2))
+    return set_error(ACTQKV_ESHAPE, "decode_layer: batch %d > %d", batch, int(kSeqCounters / 2));
+  ACTQKV_REQUIRE_PTR(q);
+  if ((k_new == nullptr) != (v_new == nullptr))
+    return set_error(ACTQKV_EINVAL, "k_new and v_new must be given together");
+  ACTQKV_OPTIONAL_PTR(k_new);
+  ACTQKV_OPTIONAL_PTR(v_new);
+  ACTQKV_REQUIRE_PTR(k_cache);
+  ACTQKV_REQUIRE_PTR(v_cache);
+  ACTQKV_REQUIRE_PTR(rep_keys);
+  ACTQKV_REQUIRE_SMALL(n_ctx, 4);
+  ACTQKV_REQUIRE_SMALL(nb_end, 4);
+  ACTQKV_REQUIRE_SMALL(scores, 4);
+  ACTQKV_REQUIRE_SMALL(idx, 4);
+  ACTQKV_REQUIRE_SMALL(n_sel, 4);
+  ACTQKV_REQUIRE_PTR(out);
+  ACTQKV_OPTIONAL_SMALL(lse, 4);
+  if ((budget_in == nullptr) != (theta_rest_sum == nullptr))
+    return set_error(ACTQKV_EINVAL, "budget_in and theta_rest_sum must be given together");
+  ACTQKV_OPTIONAL_SMALL(budget_in, 4);
+  ACTQKV_OPTIONAL_SMALL(theta_rest_sum, 4);
+  ACTQKV_OPTIONAL_SMALL(budget_after, 4);
+  ACTQKV_OPTIONAL_SMALL(theta, 4);
+  ACTQKV_OPTIONAL_SMALL(budget, 4);
+  if (budget_after != nullptr && budget_after == budget_in)
+    return set_error(ACTQKV_EINVAL, "budget_after must not be the array budget_in points to");
+  if (score_stride < nb_capacity)
+    return set_error(ACTQKV_EINVAL, "score_stride %lld < nb_capacity %d", (long long)score_stride,
+                     nb_capacity);
+  const int64_t per_seq = int64_t(nb_capacity) * shape->n_kv_heads * shape->block_size * shape->head_dim;
+  const int64_t rep_per_seq = int64_t(nb_capacity) * shape->n_rep * shape->n_kv_heads * shape->head_dim;
+  if (batch > 1 && cache_seq_stride < per_seq)
+    return set_error(ACTQKV_EINVAL, "cache_seq_stride %lld < one sequence's cache %lld",
+                     (long long)cache_seq_stride, (long long)per_seq);
+  if (batch > 1 && rep_seq_stride < rep_per_seq)
+    return set_error(ACTQKV_EINVAL, "rep_seq_stride %lld < one sequence's representative keys %lld",
+                     (long long)rep_seq_stride, (long long)rep_per_seq);
+  if (cache_seq_stride % 8 != 0 || rep_seq_stride % 8 != 0)
+    return set_error(ACTQKV_EALIGN, "sequence strides must be multiples of 8 elements");
+  if (workspace == nullptr || !aligned16(workspace))
+    return set_error(ACTQKV_EWORKSPACE, "workspace is NULL or not 16-byte aligned");
+  const size_t need = workspace_bytes(*shape, batch, 1, nb_capacity, k_cap);
+  if (ws_bytes < need)
+    return set_error(ACTQKV_EWORKSPACE, "workspace has %zu bytes, decode_layer needs %zu", ws_bytes, need);
+  Workspace ws{workspace, ws_bytes};
+  const float scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.f / std::sqrt(float(shape->head_dim));
+  // the wait for the other workgroups' scores is bounded: 2 ms is a hundred times a whole launch
+  const int wait_us = (flags & ACTQKV_DECODE_NO_WAIT) ? 0 : 2000;
+  return launch_decode_layer(*shape, batch, q, k_new, v_new, k_cache, v_cache, cache_seq_stride, rep_keys,
+                             rep_seq_stride, nb_capacity, n_ctx, nb_begin, nb_end, scores, score_stride, k_cap,
+                             flags & ACTQKV_SELECT_ENTROPY_TOPK, budget_in, theta_rest_sum, budget_after, idx,
+                             n_sel, theta, budget, out, lse, ws.scratch_f32(), ws.counters(), scale, wait_us,
+                             static_cast<hipStream_t>(stream));
+}
+
 int actqkv_score_blocks_per_head(const actqkv_shape* shape, int batch, const float* probe, const void* rep_keys,
                                  int64_t seq_stride, int nb_capacity, int nb_begin, const int32_t* nb_end,
                                  float* scores, int64_t score_stride, void* stream) {

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(kApThreads) void append_kv_kernel(
                            n_kv_heads, head_dim, reinterpret_cast<float*>(ap_lds), red);
     return;
   }
-  append_body<T>(role, int(blockIdx.y), s, k_new, v_new, pos0_all, k_cache, v_cache, cache_stride, rep_keys,
+  append_body<T>(role, int(blockIdx.y), s, k_new, v_new, pos0_all[s], k_cache, v_cache, cache_stride, rep_keys,
                  rep_stride, nb_capacity, m, n_kv_heads, head_dim, n_rep, ap_lds);
 }
 

@@ -18,13 +18,13 @@ constexpr int kApThreads = 1024;
 template <typename T, int kThreads = kApThreads>
 __device__ __forceinline__ void append_body(int role, int seg, int s, const T* __restrict__ k_new,
                                             const T* __restrict__ v_new,
-                                            const int32_t* __restrict__ pos0_all, T* __restrict__ k_cache,
+                                            int pos0_of_s, T* __restrict__ k_cache,
                                             T* __restrict__ v_cache, int64_t cache_stride,
                                             T* __restrict__ rep_keys, int64_t rep_stride, int nb_capacity,
                                             int m, int n_kv_heads, int head_dim, int n_rep,
                                             unsigned char* ap_lds) {
   constexpr int V = Vec<T>::N;
-  const int pos0 = max(pos0_all[s], 0);
+  const int pos0 = max(pos0_of_s, 0);            // tokens already in sequence s's cache
   const int block = pos0 / kBlock + seg;
   if (block >= nb_capacity) return;
   const int lo = max(pos0, block * kBlock), hi = min(pos0 + m, block * kBlock + kBlock);

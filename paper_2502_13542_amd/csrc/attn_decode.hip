@@ -16,8 +16,13 @@
 // for the row maximum.  The 8 wavefronts of a workgroup merge their (max, sum, O) through
 // LDS.  If one workgroup covers a whole (sequence, KV head) it writes the output itself;
 // otherwise the workgroups store partials and the one that finishes last merges them.
+#include <algorithm>
+#include <mutex>
+
+#include "append_body.h"
 #include "common.h"
 #include "launch.h"
+#include "score_body.h"
 #include "select_body.h"
 
 namespace actqkv {
@@ -367,6 +372,265 @@ __global__ __launch_bounds__(kDcThreads) void attn_decode_select_kernel(DcParams
   dc_finish(p, a, dc_lds, s, hk, wg, group, n, kq, wave, n_waves);
 }
 
+// ---- a whole decode layer in ONE launch ---------------------------------------------------
+// Cache update (Sec. 3.1, Eq. (4)), the probe of the one-token window (the query itself,
+// Sec. 4.2), block scores (Eq. (10)), density, budget and selection (Eq. (11), Eq. (12),
+// Alg. 1) and the attention (Eq. (3)).  The selection of a sequence needs the scores of ALL
+// its blocks, which is what a launch boundary used to provide; here the workgroups of a
+// sequence share the scoring (block i of the sequence goes to wavefront i mod all its
+// wavefronts), publish their scores with write-through stores and a ticket, then stream the
+// items of the attention that do not depend on the selection (initial tokens, local span)
+// and only afterwards look for the others' scores.  By then these are there as a rule;
+// otherwise one thread polls the ticket counter for a bounded time, and a workgroup whose time
+// runs out scores the whole sequence for itself (same code, same bits), so every wavefront
+// reaches its end whatever the other workgroups do.  Each workgroup then repeats the
+// sequence's selection, as attn_decode_select_kernel does, and attends over the chosen blocks.
+struct DlParams {
+  const uint16_t* k_new;       // [batch][Hk][D], NULL: the cache already holds the step's token
+  const uint16_t* v_new;
+  uint16_t* k_cache;           // the same caches as DcParams', writable
+  uint16_t* v_cache;
+  uint16_t* rep_keys;          // [nb_capacity][r][Hk][D] per sequence
+  int64_t rep_stride;
+  int n_rep;
+  float* scores;               // [batch][score_stride], written for the eligible blocks
+  unsigned int* seq_counters;  // [batch][2]: workgroups that have published their scores / that have left
+  int wait_us;                 // bound of the wait for the other workgroups' scores; 0: do not wait at all
+  float inv_sqrt_g;
+};
+
+struct LdsScores {
+  const float* v;
+  __device__ __forceinline__ float operator[](int i) const { return v[i]; }
+};
+
+__global__ __launch_bounds__(kDcThreads) void decode_layer_kernel(DcParams p, DcSelectParams sp, DlParams lp) {
+  extern __shared__ __attribute__((aligned(16))) float dc_lds[];   // merge area | probe_kv | representatives step | scores
+  __shared__ SelectLds<kDcThreads> sel_lds;
+  __shared__ float red[32];
+  __shared__ int have_all;
+  constexpr int V = 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int n_waves = kDcMaxWaves;
+  const int n = lane & 15, kq = lane >> 4;
+  const int wg = blockIdx.x, hk = blockIdx.y, s = blockIdx.z;
+  const int group = p.n_q_heads / p.n_kv_heads, key_len = p.n_kv_heads * kDcD;
+  const int wgs_per_seq = p.n_wg * p.n_kv_heads, wg_in_seq = hk * p.n_wg + wg;
+  const int waves_per_seq = wgs_per_seq * n_waves, wave_in_seq = wg_in_seq * n_waves + wave;
+  float* pkv_lds = dc_lds + n_waves * group * (kDcD + 2);
+  // (an area of its own for the representatives step, whose last loop has no barrier behind it)
+  float* ap_lds = pkv_lds + key_len;
+  float* sc_lds = ap_lds + 2 * kBlock;
+
+  const int end = min(max(sp.nb_end[s], sp.nb_begin), p.nb_capacity);
+  const int n_elig = max(end - sp.nb_begin, 0);
+  const int n_ctx = min(max(p.n_ctx[s], 1), p.nb_capacity * kBlock);
+  const WindowGeom g = window_geom(n_ctx, 1, p.n_init, p.n_local);
+  const TileList fixed = make_tile_list(g, n_ctx - 1, nullptr, 0, p.k_cap, p.nb_capacity);
+  const int n_fixed = fixed.count() * kDcPerTile;
+
+  // ---- the probe: the query summed over the G heads of every KV head, and its norm.  The
+  // query loads go out before the key loads (outstanding loads are counted in order).
+  const uint16_t* __restrict__ qrow = p.q + size_t(s) * p.n_q_heads * kDcD;
+  const int n_chunks = key_len / V;
+  auto load_q = [&](int c, int g0, float (&x)[4][V]) {
+    const int h = (c * V) / kDcD, dd = c * V - h * kDcD;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) Vec<uint16_t>::load(qrow + (h * group + min(g0 + i, group - 1)) * kDcD + dd, x[i]);
+  };
+  float ss = 0.f;
+  auto add_q = [&](int g0, const float (&x)[4][V], float (&acc)[V]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (g0 + i < group) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+          acc[v] += x[i][v];
+          ss += x[i][v] * x[i][v];
+        }
+      }
+  };
+  float x0[4][V];
+  load_q(min(tid, n_chunks - 1), 0, x0);
+  bf16x8 qb[4];
+  dc_load_q(p, s, hk, group, n, kq, qb);              // Q^T operand of the attention, from the same 8 KB
+  __builtin_amdgcn_sched_barrier(0);
+  if (tid < n_chunks) {
+    float acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.f;
+    add_q(0, x0, acc);
+    for (int g0 = 4; g0 < group; g0 += 4) {
+      float x[4][V];
+      load_q(tid, g0, x);
+      add_q(g0, x, acc);
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) pkv_lds[tid * V + v] = acc[v];
+  }
+  for (int c = tid + kDcThreads; c < n_chunks; c += kDcThreads) {
+    float acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.f;
+    for (int g0 = 0; g0 < group; g0 += 4) {
+      float x[4][V];
+      load_q(c, g0, x);
+      add_q(g0, x, acc);
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) pkv_lds[c * V + v] = acc[v];
+  }
+  const float pn = sqrtf(block_sum(ss, red));            // its barriers also publish pkv_lds
+  // ---- this wavefront's first four blocks of the sequence, all requested before any is used.  (They
+  // go out behind the probe: a wavefront stalls while it issues this many loads, and the barriers
+  // of the probe would wait for the slowest one.)
+  const uint16_t* rep = lp.rep_keys + size_t(s) * lp.rep_stride;
+  const size_t block_elems = size_t(lp.n_rep) * key_len;
+  auto block_keys = [&](int i) { return rep + size_t(sp.nb_begin + i) * block_elems; };   // i < n_elig
+  BlockScorer<uint16_t> sc0, sc1, sc2, sc3;
+  const int i0 = wave_in_seq, i1 = i0 + waves_per_seq, i2 = i1 + waves_per_seq, i3 = i2 + waves_per_seq;
+  if (i0 < n_elig) sc0.start(block_keys(i0), lp.n_rep, key_len, lane);   // (wave-uniform conditions)
+  if (i1 < n_elig) sc1.start(block_keys(i1), lp.n_rep, key_len, lane);
+  if (i2 < n_elig) sc2.start(block_keys(i2), lp.n_rep, key_len, lane);
+  if (i3 < n_elig) sc3.start(block_keys(i3), lp.n_rep, key_len, lane);
+  __builtin_amdgcn_sched_barrier(0);
+  uint32_t* sc_out = reinterpret_cast<uint32_t*>(lp.scores + size_t(s) * sp.score_stride + sp.nb_begin);
+  auto finish_block = [&](BlockScorer<uint16_t>& sc, int i) {
+    if (i < n_elig) {
+      const float v = sc.finish(pkv_lds, pn, lp.inv_sqrt_g);
+      if (lane == 0) st_agent(sc_out + i, __float_as_uint(v));
+    }
+  };
+  finish_block(sc0, i0);
+  finish_block(sc1, i1);
+  finish_block(sc2, i2);
+  finish_block(sc3, i3);
+  for (int i = i3 + waves_per_seq; i < n_elig; i += 2 * waves_per_seq) {   // longer sequences: two at a time
+    sc0.start(block_keys(i), lp.n_rep, key_len, lane);
+    if (i + waves_per_seq < n_elig) sc1.start(block_keys(i + waves_per_seq), lp.n_rep, key_len, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    finish_block(sc0, i);
+    finish_block(sc1, i + waves_per_seq);
+  }
+  // ---- publish: the stores above have been acknowledged, then one ticket per workgroup
+  unsigned int* arrived = lp.seq_counters + 2 * s;
+  unsigned int* left = arrived + 1;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (tid == 0) __hip_atomic_fetch_add(arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+  // ---- the representatives of the block the step's token completes (one workgroup per sequence;
+  // reads the older tokens from the cache and the new one from k_new, so it depends on no copy)
+  const int pos_new = n_ctx - 1;
+  if (lp.k_new != nullptr && wg_in_seq == 0)
+    append_body<uint16_t, kDcThreads>(p.n_kv_heads, 0, s, lp.k_new, lp.v_new, pos_new, lp.k_cache, lp.v_cache,
+                                      p.seq_stride, lp.rep_keys, lp.rep_stride, p.nb_capacity, 1, p.n_kv_heads,
+                                      kDcD, lp.n_rep, reinterpret_cast<unsigned char*>(ap_lds));
+
+  // ---- The wavefront that owns the item holding the step's own token writes that token into the
+  // cache (its KV head's key row and value column) and waits for the stores, so that its loads
+  // of the item see it; nobody else reads those cache lines in this launch.
+  DcAcc a;
+  a.m_run = -INFINITY;
+  a.l_run = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a.acc_o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const uint16_t* kc = p.k_cache + size_t(s) * p.seq_stride;
+  const uint16_t* vc = p.v_cache + size_t(s) * p.seq_stride;
+  // item i of the list goes to wavefront i mod (all wavefronts of the pair), wavefront-major across
+  // the pair's workgroups, so that every workgroup gets its share of short lists
+  const int it0 = wave * p.n_wg + wg, stride = p.n_wg * n_waves;
+  // item of the fixed list that holds position pos_new: the last tile of the list, by construction
+  const int it_new = (fixed.count() - 1) * kDcPerTile + (pos_new % kBlock) / kDcItemKeys;
+  if (lp.k_new != nullptr && it0 == it_new % stride) {
+    const int block = pos_new / kBlock, j0 = pos_new - block * kBlock;
+    const size_t tile = size_t(s) * p.seq_stride + (size_t(block) * p.n_kv_heads + hk) * size_t(kBlock) * kDcD;
+    const uint16_t* kn = lp.k_new + (size_t(s) * p.n_kv_heads + hk) * kDcD;
+    const uint16_t* vn = lp.v_new + (size_t(s) * p.n_kv_heads + hk) * kDcD;
+    if (lane < kDcD / 8)
+      *reinterpret_cast<u32x4*>(lp.k_cache + tile + size_t(j0) * kDcD + 8 * lane) =
+          *reinterpret_cast<const u32x4*>(kn + 8 * lane);
+#pragma unroll
+    for (int r = 0; r < kDcD / 64; ++r) lp.v_cache[tile + size_t(lane + 64 * r) * kBlock + j0] = vn[lane + 64 * r];
+    __builtin_amdgcn_s_waitcnt(0);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- attention over the items that do not depend on the selection (initial tokens, local span):
+  // they stream while the other workgroups' scores and tickets become visible.  (Measured
+  // alternatives: requesting these items first and selecting while they are on their way makes
+  // the reads of the scores wait behind the items' 32 KB - loads return in order - and a
+  // wavefront set aside for those reads still shares the compute unit's load queue with the
+  // other seven: both orders were slower than this one.)
+  for (int it = it0; it < n_fixed; it += stride) {
+    DcItem r;
+    int block, part;
+    if (!dc_item_span(fixed, it, block, part, r)) continue;   // wave-uniform
+    dc_issue(r, kc, vc, block, part, hk, p.n_kv_heads, n, kq);
+    __builtin_amdgcn_sched_barrier(0);
+    dc_consume(r, qb, a, p.scale_log2e, kq);
+  }
+
+  // ---- the sequence's scores: wait (bounded) until every workgroup has published its share
+  if (tid == 0) {
+    int ok = 0;
+    if (lp.wait_us > 0) {
+      const uint64_t t_end = wall_clock64() + uint64_t(lp.wait_us) * 100u;   // the counter runs at 100 MHz
+      for (;;) {
+        ok = __hip_atomic_load(arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= unsigned(wgs_per_seq);
+        if (ok || wall_clock64() >= t_end) break;
+        __builtin_amdgcn_s_sleep(2);
+      }
+    }
+    have_all = ok;
+  }
+  __syncthreads();
+  if (have_all) {
+    for (int i = tid; i < n_elig; i += kDcThreads) sc_lds[i] = __uint_as_float(ld_agent(sc_out + i));
+  } else {
+    for (int i = wave; i < n_elig; i += n_waves) {        // the whole sequence, by this workgroup alone
+      sc0.start(block_keys(i), lp.n_rep, key_len, lane);
+      const float v0 = sc0.finish(pkv_lds, pn, lp.inv_sqrt_g);
+      if (lane == 0) sc_lds[i] = v0;
+    }
+  }
+  __syncthreads();
+
+  SelectIo io = sp.io;
+  io.write = wg_in_seq == 0;
+  select_body<kDcThreads>(LdsScores{sc_lds}, s, n_elig, sp.nb_begin, p.k_cap, sp.entropy_topk, io, sel_lds);
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- the selected blocks
+  TileList chosen = fixed;
+  chosen.n_init_tiles = 0;
+  chosen.n_tail_tiles = 0;
+  chosen.n_sel = min(max(sel_lds.count, 0), p.k_cap);
+  chosen.idx = sel_lds.sel;
+  const int n_items = n_fixed + chosen.n_sel * kDcPerTile;
+  int it = it0;
+  while (it < n_fixed) it += stride;
+  for (; it < n_items; it += stride) {
+    DcItem r;
+    int block, part;
+    if (!dc_item_span(chosen, it - n_fixed, block, part, r)) continue;   // wave-uniform
+    dc_issue(r, kc, vc, block, part, hk, p.n_kv_heads, n, kq);
+    __builtin_amdgcn_sched_barrier(0);
+    dc_consume(r, qb, a, p.scale_log2e, kq);
+  }
+  dc_finish(p, a, dc_lds, s, hk, wg, group, n, kq, wave, n_waves);
+
+  // ---- the last workgroup of the sequence to get here (nobody polls any more) resets the counters
+  if (tid == 0) {
+    const unsigned int t = __hip_atomic_fetch_add(left, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (t == unsigned(wgs_per_seq) - 1u) {
+      __hip_atomic_store(arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(left, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
 bool decode_mfma_supported(const actqkv_shape& sh, int m) {
   const int g = sh.n_q_heads / sh.n_kv_heads;
   return sh.dtype == ACTQKV_BF16 && sh.head_dim == kDcD && m == 1 && g <= 8;
@@ -456,6 +720,59 @@ int launch_attention_decode_select(const actqkv_shape& sh, int batch, const void
   hipLaunchKernelGGL(attn_decode_select_kernel, dim3(p.n_wg, sh.n_kv_heads, batch), dim3(kDcThreads), lds,
                      stream, p, sp);
   return hip_status("attention with selection (decode)");
+}
+
+int launch_decode_layer(const actqkv_shape& sh, int batch, const void* q, const void* k_new, const void* v_new,
+                        void* k_cache, void* v_cache, int64_t seq_stride, void* rep_keys, int64_t rep_stride,
+                        int nb_capacity, const int32_t* n_ctx, int nb_begin, const int32_t* nb_end, float* scores,
+                        int64_t score_stride, int k_cap, int flags, const float* budget_in,
+                        const float* theta_rest_sum, float* budget_after, int32_t* idx, int32_t* n_sel,
+                        float* theta, float* budget, void* out, float* lse, float* scratch,
+                        unsigned int* counters, float scale, int wait_us, hipStream_t stream) {
+  const DcParams p = decode_params(sh, batch, q, k_cache, v_cache, seq_stride, nb_capacity, n_ctx, nullptr,
+                                   nullptr, k_cap, out, lse, scratch, counters, scale, 0);
+  DcSelectParams sp;
+  sp.scores = scores;
+  sp.score_stride = score_stride;
+  sp.nb_begin = nb_begin;
+  sp.nb_end = nb_end;
+  sp.entropy_topk = (flags & ACTQKV_SELECT_ENTROPY_TOPK) != 0;
+  sp.io = SelectIo{budget_in, theta_rest_sum, budget_after, idx, n_sel, theta, budget, false};
+  DlParams lp;
+  lp.k_new = static_cast<const uint16_t*>(k_new);
+  lp.v_new = static_cast<const uint16_t*>(v_new);
+  lp.k_cache = static_cast<uint16_t*>(k_cache);
+  lp.v_cache = static_cast<uint16_t*>(v_cache);
+  lp.rep_keys = static_cast<uint16_t*>(rep_keys);
+  lp.rep_stride = rep_stride;
+  lp.n_rep = sh.n_rep;
+  lp.scores = scores;
+  lp.seq_counters = counters + kSeqCounterOffset;
+  lp.wait_us = wait_us;
+  const int group = sh.n_q_heads / sh.n_kv_heads;
+  lp.inv_sqrt_g = 1.f / sqrtf(float(group));
+  if (p.n_wg > 1 && size_t(batch) * sh.n_kv_heads > kTicketCounters)
+    return set_error(ACTQKV_EINVAL, "decode layer: more split (sequence, KV head) pairs than ticket counters");
+  if (2 * size_t(batch) > kSeqCounters)
+    return set_error(ACTQKV_ESHAPE, "decode layer: batch %d > %d", batch, int(kSeqCounters / 2));
+  // merge area of the wavefronts | group-summed probe | the representatives step | the sequence's scores
+  const size_t lds = (size_t(kDcMaxWaves) * group * (kDcD + 2) + size_t(sh.n_kv_heads) * kDcD + 2 * kBlock +
+                      size_t(std::max(nb_capacity - nb_begin, 1))) * sizeof(float);
+  if (lds > 150 * 1024) return set_error(ACTQKV_ESHAPE, "decode layer: %zu bytes of LDS", lds);
+  static std::mutex mu;
+  static size_t lds_set = 48 * 1024;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (lds > lds_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_layer_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+      if (e != hipSuccess) return set_error(ACTQKV_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+      lds_set = 150 * 1024;
+    }
+  }
+  hipLaunchKernelGGL(decode_layer_kernel, dim3(p.n_wg, sh.n_kv_heads, batch), dim3(kDcThreads), lds, stream, p,
+                     sp, lp);
+  return hip_status("decode layer");
 }
 
 }  // namespace actqkv

@@ -61,14 +61,48 @@ __device__ __forceinline__ void store_elem(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_elem(uint16_t* p, float v) { *p = uint16_t(f32_to_bf16_bits(v)); }
 
 // ---- wave / workgroup reductions ------------------------------------------
+// The value of lane (lane ^ J), J a power of two, without the LDS crossbar where the data-parallel
+// primitives reach: quad permutes for 1 and 2, two masked row shifts for 4 and 8 (banks of four
+// lanes take the value from J lanes above or below), a swizzle for 16; only 32 is a general shuffle.
+template <int J>
+__device__ __forceinline__ uint32_t lane_xor32(uint32_t v) {
+  if constexpr (J == 1) {
+    return __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false);          // quad_perm [1, 0, 3, 2]
+  } else if constexpr (J == 2) {
+    return __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false);          // quad_perm [2, 3, 0, 1]
+  } else if constexpr (J == 4) {
+    const uint32_t t = __builtin_amdgcn_update_dpp(v, v, 0x104, 0xF, 0x5, false);   // row_shl:4 into banks 0, 2
+    return __builtin_amdgcn_update_dpp(t, v, 0x114, 0xF, 0xA, false);               // row_shr:4 into banks 1, 3
+  } else if constexpr (J == 8) {
+    const uint32_t t = __builtin_amdgcn_update_dpp(v, v, 0x108, 0xF, 0x3, false);   // row_shl:8 into banks 0, 1
+    return __builtin_amdgcn_update_dpp(t, v, 0x118, 0xF, 0xC, false);               // row_shr:8 into banks 2, 3
+  } else if constexpr (J == 16) {
+    return uint32_t(__builtin_amdgcn_ds_swizzle(int(v), (16 << 10) | 0x1F));  // bit mode: xor 16 inside 32 lanes
+  } else {
+    static_assert(J == 32, "lane distance");
+    return uint32_t(__shfl_xor(int(v), 32, 64));
+  }
+}
+template <int J>
+__device__ __forceinline__ float lane_xor_f32(float v) {
+  return __uint_as_float(lane_xor32<J>(__float_as_uint(v)));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  v += lane_xor_f32<32>(v);
+  v += lane_xor_f32<16>(v);
+  v += lane_xor_f32<8>(v);
+  v += lane_xor_f32<4>(v);
+  v += lane_xor_f32<2>(v);
+  v += lane_xor_f32<1>(v);
   return v;
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  v = fmaxf(v, lane_xor_f32<32>(v));
+  v = fmaxf(v, lane_xor_f32<16>(v));
+  v = fmaxf(v, lane_xor_f32<8>(v));
+  v = fmaxf(v, lane_xor_f32<4>(v));
+  v = fmaxf(v, lane_xor_f32<2>(v));
+  v = fmaxf(v, lane_xor_f32<1>(v));
   return v;
 }
 // Sum over the workgroup; every thread gets the result.  `red` holds >= 32 floats of LDS.

@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kDrThreads) void decode_score_kernel(DrParams<T> p)
   }
   if (role == 1) {
     // ---- the representatives of the block, if the token completes it
-    append_body<T, kDrThreads>(p.n_kv_heads, 0, s, p.k_new, p.v_new, p.pos0, p.k_cache, p.v_cache,
+    append_body<T, kDrThreads>(p.n_kv_heads, 0, s, p.k_new, p.v_new, p.pos0[s], p.k_cache, p.v_cache,
                                p.cache_stride, p.rep_keys, p.rep_stride, p.nb_capacity, 1, p.n_kv_heads,
                                p.head_dim, p.n_rep, dr_lds);
     return;

@@ -31,11 +31,33 @@ inline size_t probe_a_floats(int m) { return (size_t(m) + 15) / 16 * 16; }
 inline size_t probe_scratch_floats(const actqkv_shape& sh, int m) {
   return size_t(probe_slabs(sh)) * probe_a_floats(m);
 }
-// the whole call: the partials of every entry, and behind them what a call over consecutive
-// windows of one sequence keeps: (mean, M2) [batch][2][d] and a copy of the old statistics
+// A call over consecutive windows of one sequence reads whole rows, kRowChunk of them per
+// workgroup, and keeps, in floats: part [n][chunks][2][d] (sums and sums of squares per chunk),
+// stat [n][3][d] (mean, 1/var, the window's own mean), pprobe [n][chunks][d] (weighted sums per
+// chunk), asum [n][chunks rounded up to 16], a [n][m rounded up to 16].
+constexpr int kRowChunk = 64;
+struct ChainScratch {
+  int n_chunks, asum_stride;
+  size_t part, stat, pprobe, asum, a;
+  size_t total() const { return part + stat + pprobe + asum + a; }
+};
+inline ChainScratch chain_scratch(const actqkv_shape& sh, int batch, int m) {
+  ChainScratch c;
+  const size_t d = size_t(sh.n_q_heads) * sh.head_dim;
+  c.n_chunks = (m + kRowChunk - 1) / kRowChunk;
+  c.asum_stride = (c.n_chunks + 15) / 16 * 16;
+  c.part = size_t(batch) * c.n_chunks * 2 * d;
+  c.stat = size_t(batch) * 3 * d;
+  c.pprobe = size_t(batch) * c.n_chunks * d;
+  c.asum = size_t(batch) * c.asum_stride;
+  c.a = size_t(batch) * probe_a_floats(m);
+  return c;
+}
+// the whole call: the slab partials of every entry, or what the row-major kernels keep
 inline size_t probe_call_floats(const actqkv_shape& sh, int batch, int m) {
-  return size_t(batch) * probe_scratch_floats(sh, m) +
-         (size_t(batch) + 1) * 2 * sh.n_q_heads * sh.head_dim + 4;
+  const size_t slabs = size_t(batch) * probe_scratch_floats(sh, m);
+  const size_t rows = chain_scratch(sh, batch, m).total();
+  return (slabs > rows ? slabs : rows) + 4;
 }
 
 // Key-tile splits of the prefill attention.
@@ -53,6 +75,8 @@ constexpr int kMaxWindow = 8192;
 // head of the workspace: 1024 uint32 tickets, then the work queue counters of the prefill attention
 constexpr size_t kTicketCounters = 1024;
 constexpr size_t kCounterBytes = 8192;
+// behind the queue counters: two counters per sequence for the decode layer in one launch
+constexpr size_t kSeqCounterOffset = kTicketCounters + 256, kSeqCounters = 768;
 constexpr int kChipCus = 256;   // compute units of the chip
 constexpr int kMaxBatch = 1024;
 
@@ -110,6 +134,15 @@ int launch_decode_retrieve(const actqkv_shape& sh, int batch, const void* q_tok,
                            float* budget_remaining, const float* theta_rest_sum, int32_t* idx,
                            int32_t* n_sel, float* theta, float* budget,
                            hipStream_t stream);   // k_new NULL: no cache update
+
+// a whole decode layer in one launch (bf16, head_dim 128); k_new NULL: no cache update
+int launch_decode_layer(const actqkv_shape& sh, int batch, const void* q, const void* k_new, const void* v_new,
+                        void* k_cache, void* v_cache, int64_t seq_stride, void* rep_keys, int64_t rep_stride,
+                        int nb_capacity, const int32_t* n_ctx, int nb_begin, const int32_t* nb_end, float* scores,
+                        int64_t score_stride, int k_cap, int flags, const float* budget_in,
+                        const float* theta_rest_sum, float* budget_after, int32_t* idx, int32_t* n_sel,
+                        float* theta, float* budget, void* out, float* lse, float* scratch,
+                        unsigned int* counters, float scale, int wait_us, hipStream_t stream);
 
 int launch_gather(const actqkv_shape& sh, int batch, const void* k_store, const void* v_store,
                   int64_t store_stride, int nb_store, const int32_t* idx, const int32_t* n_sel, int k_cap,

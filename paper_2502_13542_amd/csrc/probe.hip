@@ -13,11 +13,9 @@
 // All sums are fp32 and are taken in a fixed order, so results are reproducible.
 //
 // Consecutive windows of one sequence can be taken in one call: Eq. (8) merges the windows
-// into the running statistics one after the other, but the merge is a function of each
-// window's own (mean, M2) only.  So window_moments computes those for all windows at once,
-// chain_bias (one workgroup per window and slab) replays the merges up to its window -
-// a few operations per channel - and takes the bias partials of its window, and weigh and
-// finish run once for all windows.  Four launches for n windows instead of 3 n.
+// into the running statistics one after the other, but a merge is a function of each window's
+// own (mean, M2) only, so everything else is done for all windows at once (kernels further
+// down).  Four launches for n windows instead of 3 n.
 #include "common.h"
 #include "launch.h"
 #include "probe_identity.h"
@@ -187,157 +185,6 @@ __global__ __launch_bounds__(256) void probe_stats_bias_kernel(const T* __restri
   bias_partials<T>(x, load_pass, mu_lds, iv_lds, apart, m, m_pad, n_pass, cl, rl);
 }
 
-// ---- consecutive windows of one sequence in one call
-// Scratch behind the bias partials: mom[n][2][d] = (mean, M2) of every window on its own,
-// then base[4 + 2 d] = the running statistics as they were before the call.
-//
-// grid (column slabs, n windows); threads as in probe_stats_bias_kernel.  The sums are taken
-// about the window's first query (no cancellation in the squares).  The workgroups of window
-// 0 also copy their slab of the old statistics to `base`, which chain_bias reads: it
-// overwrites the statistics themselves while other workgroups still need the old ones.
-template <typename T>
-__global__ __launch_bounds__(256) void probe_window_moments_kernel(const T* __restrict__ q_win,
-                                                                   const float* __restrict__ stats,
-                                                                   float* __restrict__ mom,
-                                                                   float* __restrict__ base, int m, int d) {
-  constexpr int V = Vec<T>::N;
-  constexpr int SLAB = kColLanes * V;
-  typedef typename Vec<T>::raw raw_t;
-  __shared__ float red[2][kStatsRowLanes][SLAB];
-  const int w = blockIdx.y;
-  const T* q = q_win + size_t(w) * m * d;
-  const int cl = threadIdx.x % kColLanes, rl = threadIdx.x / kColLanes;
-  const int ch0 = blockIdx.x * SLAB + cl * V;
-  const bool col_ok = ch0 < d;
-  const int n_pass = (m + kStatsRowsPerPass - 1) / kStatsRowsPerPass;
-  float c[V], s1[V], s2[V];
-#pragma unroll
-  for (int v = 0; v < V; ++v) c[v] = s1[v] = s2[v] = 0.f;
-  if (col_ok) Vec<T>::load(q + ch0, c);
-  for (int pass = 0; pass < n_pass; ++pass) {
-    raw_t x[kRowsPerThread];
-#pragma unroll
-    for (int i = 0; i < kRowsPerThread; ++i) {   // all loads first: they overlap
-      const int r = pass * kStatsRowsPerPass + rl * kRowsPerThread + i;
-      x[i] = Vec<T>::load_raw(q + size_t(r < m ? r : 0) * d + (col_ok ? ch0 : 0));
-    }
-#pragma unroll
-    for (int i = 0; i < kRowsPerThread; ++i) {
-      if (pass * kStatsRowsPerPass + rl * kRowsPerThread + i < m) {
-        float f[V];
-        Vec<T>::widen(x[i], f);
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-          float t = f[v] - c[v];
-          s1[v] += t;
-          s2[v] += t * t;
-        }
-      }
-    }
-  }
-#pragma unroll
-  for (int v = 0; v < V; ++v) {
-    red[0][rl][cl * V + v] = s1[v];
-    red[1][rl][cl * V + v] = s2[v];
-  }
-  __syncthreads();
-  const int col = threadIdx.x, ch = blockIdx.x * SLAB + col;
-  if (col < SLAB && ch < d) {
-    float t1 = 0.f, t2 = 0.f;
-#pragma unroll
-    for (int k = 0; k < kStatsRowLanes; ++k) {
-      t1 += red[0][k][col];
-      t2 += red[1][k][col];
-    }
-    const float nb = float(m);
-    mom[(size_t(w) * 2 + 0) * d + ch] = to_f32(q[ch]) + t1 / nb;
-    mom[(size_t(w) * 2 + 1) * d + ch] = fmaxf(t2 - t1 * t1 / nb, 0.f);
-    if (w == 0) {
-      base[4 + ch] = stats[4 + ch];
-      base[4 + d + ch] = stats[4 + d + ch];
-      if (ch == 0) base[0] = stats[0];
-    }
-  }
-}
-
-constexpr int kChainBatch = 16;   // window moments a thread requests together
-
-// grid (column slabs, n windows), 256 threads.  Merges the windows 0 .. w into the old
-// statistics in window order (the merge of Eq. (8), as in probe_stats_bias_kernel), which
-// gives the statistics window w sees; the workgroups of the last window store them.  Then
-// the bias partials of window w, whose rows were requested first and arrive meanwhile.
-template <typename T>
-__global__ __launch_bounds__(256) void probe_chain_bias_kernel(const T* __restrict__ q_win,
-                                                               float* __restrict__ stats,
-                                                               const float* __restrict__ mom,
-                                                               const float* __restrict__ base,
-                                                               float* __restrict__ scratch, int m,
-                                                               int m_pad, int d, float eps,
-                                                               size_t scratch_stride) {
-  constexpr int V = Vec<T>::N;
-  constexpr int SLAB = kColLanes * V;
-  typedef typename Vec<T>::raw raw_t;
-  __shared__ float mu_lds[SLAB], iv_lds[SLAB];
-  const int w = blockIdx.y, n_win = gridDim.y;
-  const T* q = q_win + size_t(w) * m * d;
-  float* apart = scratch + size_t(w) * scratch_stride + size_t(blockIdx.x) * m_pad;
-  const int cl = threadIdx.x % kColLanes, rl = threadIdx.x / kColLanes;
-  const int ch0 = blockIdx.x * SLAB + cl * V;
-  const bool col_ok = ch0 < d;
-  const int n_pass = (m + kStatsRowsPerPass - 1) / kStatsRowsPerPass;
-  raw_t x[kRowsPerThread];
-  auto load_pass = [&](int pass) {
-#pragma unroll
-    for (int i = 0; i < kRowsPerThread; ++i) {
-      const int r = pass * kStatsRowsPerPass + rl * kRowsPerThread + i;
-      x[i] = Vec<T>::load_raw(q + size_t(r < m ? r : 0) * d + (col_ok ? ch0 : 0));
-    }
-  };
-  load_pass(0);
-  {
-    const int col = threadIdx.x, ch = blockIdx.x * SLAB + col;
-    if (col < SLAB && ch >= d) mu_lds[col] = iv_lds[col] = 0.f;
-    if (col < SLAB && ch < d) {
-      float n_run = base[0], mean = base[4 + ch], m2 = base[4 + d + ch];
-      const float nb = float(m);
-      for (int u0 = 0; u0 <= w; u0 += kChainBatch) {
-        float mean_b[kChainBatch], m2_b[kChainBatch];
-#pragma unroll
-        for (int i = 0; i < kChainBatch; ++i) {   // all loads first: they overlap
-          const int u = min(u0 + i, w);
-          mean_b[i] = mom[(size_t(u) * 2 + 0) * d + ch];
-          m2_b[i] = mom[(size_t(u) * 2 + 1) * d + ch];
-        }
-#pragma unroll
-        for (int i = 0; i < kChainBatch; ++i) {
-          if (u0 + i <= w) {
-            const float n_new = n_run + nb;
-            if (n_run > 0.f) {
-              const float delta = mean_b[i] - mean;
-              mean += delta * (nb / n_new);
-              m2 += m2_b[i] + delta * delta * (n_run * nb / n_new);
-            } else {
-              mean = mean_b[i];
-              m2 = m2_b[i];
-            }
-            n_run = n_new;
-          }
-        }
-      }
-      if (w == n_win - 1) {
-        stats[4 + ch] = mean;
-        stats[4 + d + ch] = m2;
-        if (ch == 0) stats[0] = n_run;
-      }
-      const float var = n_run > 1.f ? m2 / (n_run - 1.f) : 0.f;
-      mu_lds[col] = mean;
-      iv_lds[col] = 1.f / fmaxf(var, eps);
-    }
-  }
-  __syncthreads();
-  bias_partials<T>(x, load_pass, mu_lds, iv_lds, apart, m, m_pad, n_pass, cl, rl);
-}
-
 // probe_kv and the norm of the probe; run by one workgroup that sees the whole probe.
 __device__ __forceinline__ void probe_finish(const float* probe, float* probe_kv, float* probe_norm,
                                              int n_q_heads, int n_kv_heads, int head_dim,
@@ -351,6 +198,277 @@ __device__ __forceinline__ void probe_finish(const float* probe, float* probe_kv
     int hk = e / head_dim, dd = e - hk * head_dim;
     float t = 0.f;
     for (int i = 0; i < g; ++i) t += probe[(hk * g + i) * head_dim + dd];
+    probe_kv[e] = t;
+  }
+}
+
+// ---- consecutive windows of one sequence in one call
+// With many windows in a call there is enough work to read the queries the way they lie in
+// memory: a workgroup takes 64 whole rows (rows x all channels, 16-byte loads of consecutive
+// lanes are consecutive in memory), where the one-window kernels above take 128-byte column
+// slabs of all rows.  Reductions over rows leave one partial per 64-row chunk, summed in chunk
+// order by the next kernel; reductions over channels are whole-row sums inside a wavefront, so
+// the bias weight a_j of a row is complete while the row is still in registers and Eq. (9)'s
+// weighted sum is taken in the same pass: the queries are read twice, not three times.
+//   rows_moments     (chunks x windows): sums of (q - c) and (q - c)^2 per channel over the
+//                    chunk's rows, c = the window's first query;
+//   chain_stats      per channel: every window's own (mean, M2) from its chunks, then the merges
+//                    of Eq. (8) window after window, which give the (mean, 1/var) each window
+//                    sees; stores the final statistics;
+//   rows_bias_weigh  (chunks x windows): a_j = |phi_j|_1 per row, sum of a_j q_j over the chunk's
+//                    rows per channel, sum of a_j;
+//   chain_finish     per window: probe = sum over chunks / sum of a_j, norm, per-KV-head sum,
+//                    weights.
+// Scratch per call, in floats: part [n][chunks][2][d], stat [n][3][d] (mean, 1/var, the window's
+// own mean), pprobe [n][chunks][d], asum [n][chunks rounded up to 16], a [n][m rounded up to 16].
+constexpr int kRmThreads = 256;
+
+template <typename T>
+__global__ __launch_bounds__(kRmThreads) void probe_rows_moments_kernel(const T* __restrict__ q_win,
+                                                                        float* __restrict__ part, int m, int d,
+                                                                        int n_chunks) {
+  constexpr int V = Vec<T>::N;
+  constexpr int G = 2;                               // 16-byte channel groups per thread
+  constexpr int R = 8;                               // rows requested together
+  typedef typename Vec<T>::raw raw_t;
+  const int rc = blockIdx.x, w = blockIdx.y;
+  const T* q = q_win + size_t(w) * m * d;
+  int ch[G];
+  bool ok[G];
+  float c[G][V], s1[G][V], s2[G][V];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    ch[g] = ((blockIdx.z * G + g) * kRmThreads + threadIdx.x) * V;
+    ok[g] = ch[g] < d;
+    Vec<T>::load(q + (ok[g] ? ch[g] : 0), c[g]);
+#pragma unroll
+    for (int v = 0; v < V; ++v) s1[g][v] = s2[g][v] = 0.f;
+  }
+  const int r0 = rc * kRowChunk, r1 = min(r0 + kRowChunk, m);
+  for (int r = r0; r < r1; r += R) {
+    raw_t x[R][G];
+#pragma unroll
+    for (int i = 0; i < R; ++i)
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+        x[i][g] = Vec<T>::load_raw(q + size_t(min(r + i, r1 - 1)) * d + (ok[g] ? ch[g] : 0));
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      if (r + i < r1) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float f[V];
+          Vec<T>::widen(x[i][g], f);
+#pragma unroll
+          for (int v = 0; v < V; ++v) {
+            const float t = f[v] - c[g][v];
+            s1[g][v] += t;
+            s2[g][v] += t * t;
+          }
+        }
+      }
+    }
+  }
+  float* p1 = part + (size_t(w) * n_chunks + rc) * 2 * d;
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    if (ok[g]) {
+#pragma unroll
+      for (int v = 0; v < V; v += 4) {
+        *reinterpret_cast<f32x4*>(p1 + ch[g] + v) = f32x4{s1[g][v], s1[g][v + 1], s1[g][v + 2], s1[g][v + 3]};
+        *reinterpret_cast<f32x4*>(p1 + d + ch[g] + v) = f32x4{s2[g][v], s2[g][v + 1], s2[g][v + 2], s2[g][v + 3]};
+      }
+    }
+  }
+}
+
+// grid (d / 32), 1024 threads = 32 channels x 32 window lanes.  Window lane wl first turns the
+// chunk sums of windows wl, wl + 32, ... into the window's own (mean, M2) in LDS; then window
+// lane 0 merges them into the running statistics in window order (the merge of Eq. (8), as in
+// probe_stats_bias_kernel).  The count is published by the next kernel (every thread here
+// reads the old one).
+template <typename T>
+__global__ __launch_bounds__(1024) void probe_chain_stats_kernel(const T* __restrict__ q_win,
+                                                                 const float* __restrict__ part,
+                                                                 float* __restrict__ stats,
+                                                                 float* __restrict__ stat_out, int n, int m,
+                                                                 int d, int n_chunks, float eps) {
+  extern __shared__ float wm[];                      // [n][2][32]: the windows' own mean and M2
+  const int cl = threadIdx.x & 31, wl = threadIdx.x >> 5;
+  const int ch = blockIdx.x * 32 + cl;
+  const float nb = float(m);
+  if (ch < d) {
+    for (int w = wl; w < n; w += 32) {
+      const float* p1 = part + size_t(w) * n_chunks * 2 * d + ch;
+      float t1 = 0.f, t2 = 0.f;
+      for (int rc = 0; rc < n_chunks; ++rc) {
+        t1 += p1[size_t(rc) * 2 * d];
+        t2 += p1[size_t(rc) * 2 * d + d];
+      }
+      wm[(w * 2 + 0) * 32 + cl] = to_f32(q_win[size_t(w) * m * d + ch]) + t1 / nb;
+      wm[(w * 2 + 1) * 32 + cl] = fmaxf(t2 - t1 * t1 / nb, 0.f);
+    }
+  }
+  __syncthreads();
+  if (wl != 0 || ch >= d) return;
+  float n_run = stats[0], mean = stats[4 + ch], m2 = stats[4 + d + ch];
+  for (int w = 0; w < n; ++w) {
+    const float mean_b = wm[(w * 2 + 0) * 32 + cl], m2_b = wm[(w * 2 + 1) * 32 + cl];
+    const float n_new = n_run + nb;
+    if (n_run > 0.f) {
+      const float delta = mean_b - mean;
+      mean += delta * (nb / n_new);
+      m2 += m2_b + delta * delta * (n_run * nb / n_new);
+    } else {
+      mean = mean_b;
+      m2 = m2_b;
+    }
+    n_run = n_new;
+    const float var = n_run > 1.f ? m2 / (n_run - 1.f) : 0.f;
+    float* o = stat_out + size_t(w) * 3 * d + ch;
+    o[0] = mean;
+    o[d] = 1.f / fmaxf(var, eps);
+    o[2 * d] = mean_b;
+  }
+  stats[4 + ch] = mean;
+  stats[4 + d + ch] = m2;
+}
+
+// grid (chunks, windows), 4 wavefronts; wavefront v takes rows v, v + 4, ... of the chunk, a lane
+// the 16-byte groups lane, lane + 64, ... of a row (NI of them: d <= 64 * NI * V channels).
+// LDS: mean and 1/var of the window (2 d floats), reused for the sum over the 4 wavefronts.
+template <typename T>
+__global__ __launch_bounds__(kRmThreads) void probe_rows_bias_weigh_kernel(
+    const T* __restrict__ q_win, const float* __restrict__ stat_in, float* __restrict__ stats, float add_count,
+    int mean_pooling, float* __restrict__ pprobe, float* __restrict__ asum, float* __restrict__ a_rows, int m,
+    int m_pad, int d, int n_chunks, int asum_stride) {
+  constexpr int V = Vec<T>::N;
+  constexpr int NI = 64 / V;
+  typedef typename Vec<T>::raw raw_t;
+  extern __shared__ __attribute__((aligned(16))) float rw_lds[];   // [2][d]
+  __shared__ float red[4];
+  const int rc = blockIdx.x, w = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const T* q = q_win + size_t(w) * m * d;
+  float* mu = rw_lds;
+  float* iv = rw_lds + d;
+  for (int i = threadIdx.x * 4; i < d; i += kRmThreads * 4) {
+    *reinterpret_cast<f32x4*>(mu + i) = *reinterpret_cast<const f32x4*>(stat_in + size_t(w) * 3 * d + i);
+    *reinterpret_cast<f32x4*>(iv + i) = *reinterpret_cast<const f32x4*>(stat_in + size_t(w) * 3 * d + d + i);
+  }
+  if (add_count != 0.f && rc == 0 && w == 0 && threadIdx.x == 0) stats[0] += add_count;
+  __syncthreads();
+  float acc[NI][V];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[i][v] = 0.f;
+  float a_sum = 0.f;
+  const int r0 = rc * kRowChunk, r1 = min(r0 + kRowChunk, m);
+  for (int r = r0 + wave; r < r1; r += 4) {
+    raw_t x[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {                   // the whole row is requested before it is used
+      const int c = (lane + 64 * i) * V;
+      x[i] = Vec<T>::load_raw(q + size_t(r) * d + (c < d ? c : 0));
+    }
+    float f[NI][V];
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int c = (lane + 64 * i) * V;
+      Vec<T>::widen(x[i], f[i]);
+      if (c < d) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+          const float e = f[i][v] - mu[c + v];
+          t += e * e * iv[c + v];
+        }
+      }
+    }
+    float a = wave_sum(t);                           // |phi_j|_1 of Eq. (7), the row's weight before normalisation
+    if (mean_pooling) a = 1.f;
+    if (lane == 0) a_rows[size_t(w) * m_pad + r] = a;
+    a_sum += a;
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+      for (int v = 0; v < V; ++v) acc[i][v] += a * f[i][v];
+  }
+  // sum over the 4 wavefronts, in a fixed order: (0 + 2) + (1 + 3)
+  __syncthreads();                                   // mean and 1/var are no longer needed
+  if (lane == 0) red[wave] = a_sum;
+  auto put = [&](float* dst) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int c = (lane + 64 * i) * V;
+      if (c < d) {
+#pragma unroll
+        for (int v = 0; v < V; v += 4)
+          *reinterpret_cast<f32x4*>(dst + c + v) = f32x4{acc[i][v], acc[i][v + 1], acc[i][v + 2], acc[i][v + 3]};
+      }
+    }
+  };
+  auto add = [&](const float* src) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int c = (lane + 64 * i) * V;
+      if (c < d) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[i][v] += src[c + v];
+      }
+    }
+  };
+  if (wave >= 2) put(rw_lds + (wave - 2) * d);
+  __syncthreads();
+  if (wave < 2) add(rw_lds + wave * d);
+  __syncthreads();
+  if (wave == 1) put(rw_lds);
+  __syncthreads();
+  if (wave == 0) {
+    add(rw_lds);
+    put(pprobe + (size_t(w) * n_chunks + rc) * d);
+    if (lane == 0) asum[size_t(w) * asum_stride + rc] = (red[0] + red[2]) + (red[1] + red[3]);
+  }
+}
+
+// One workgroup per window: the chunk sums in chunk order, Eq. (9)'s normalisation (uniform
+// weights, i.e. the window's mean, if every bias is zero), the weights, and what probe_finish
+// computes.
+__global__ __launch_bounds__(1024) void probe_chain_finish_kernel(
+    const float* __restrict__ pprobe, const float* __restrict__ asum, const float* __restrict__ a_rows,
+    const float* __restrict__ stat_in, float* __restrict__ probe_out, float* __restrict__ probe_kv_out,
+    float* __restrict__ probe_norm_out, float* __restrict__ weights_out, int m, int m_pad, int d, int n_chunks,
+    int asum_stride, int n_q_heads, int n_kv_heads, int head_dim) {
+  __shared__ float red[32];
+  extern __shared__ __attribute__((aligned(16))) float probe_lds[];   // [d]
+  const int w = blockIdx.x;
+  float total = 0.f;
+  for (int rc = 0; rc < n_chunks; ++rc) total += asum[size_t(w) * asum_stride + rc];
+  const bool uniform = !(total > 0.f);
+  const float inv = uniform ? 0.f : 1.f / total;
+  float* probe = probe_out + size_t(w) * d;
+  float ss = 0.f;
+  for (int ch = threadIdx.x; ch < d; ch += 1024) {
+    float t = 0.f;
+    for (int rc = 0; rc < n_chunks; ++rc) t += pprobe[(size_t(w) * n_chunks + rc) * d + ch];
+    t = uniform ? stat_in[size_t(w) * 3 * d + 2 * d + ch] : t * inv;
+    probe[ch] = t;
+    probe_lds[ch] = t;
+    ss += t * t;
+  }
+  if (weights_out != nullptr) {
+    for (int j = threadIdx.x; j < m; j += 1024)
+      weights_out[size_t(w) * m + j] = uniform ? 1.f / float(m) : a_rows[size_t(w) * m_pad + j] * inv;
+  }
+  ss = block_sum(ss, red);                           // also orders the LDS writes before the reads below
+  if (threadIdx.x == 0) probe_norm_out[w] = sqrtf(ss);
+  const int g = n_q_heads / n_kv_heads;
+  float* probe_kv = probe_kv_out + size_t(w) * n_kv_heads * head_dim;
+  for (int e = threadIdx.x; e < n_kv_heads * head_dim; e += 1024) {
+    const int hk = e / head_dim, dd = e - hk * head_dim;
+    float t = 0.f;
+    for (int i = 0; i < g; ++i) t += probe_lds[(hk * g + i) * head_dim + dd];
     probe_kv[e] = t;
   }
 }
@@ -505,17 +623,36 @@ static int launch_probe_t(const actqkv_shape& sh, int batch, int m, const T* q_w
   const int mean_pooling = (update_stats & ACTQKV_PROBE_MEAN_POOLING) != 0;
   if (update_stats & ACTQKV_PROBE_WINDOW_CHAIN) {
     // the batch entries are consecutive windows of one sequence with one set of statistics
-    float* mom = scratch + size_t(batch) * scratch_stride;
-    float* base = mom + size_t(batch) * 2 * d;
-    hipLaunchKernelGGL(probe_window_moments_kernel<T>, dim3(n_slabs, batch), dim3(256), 0, stream, q_win,
-                       stats, mom, base, m, d);
-    hipLaunchKernelGGL(probe_chain_bias_kernel<T>, dim3(n_slabs, batch), dim3(256), 0, stream, q_win, stats,
-                       mom, base, scratch, m, m_pad, d, eps, scratch_stride);
-    hipLaunchKernelGGL(probe_weigh_kernel<T>, dim3(n_slabs, batch), dim3(512), 0, stream, q_win, scratch,
-                       stats, 0, mean_pooling, probe, weights, m, m_pad, n_slabs, d, scratch_stride,
-                       size_t(0));
-    hipLaunchKernelGGL(probe_finish_kernel, dim3(batch), dim3(1024), 0, stream, probe, probe_kv,
-                       probe_norm, sh.n_q_heads, sh.n_kv_heads, sh.head_dim);
+    if (d > 64 * 64) {
+      // rows wider than a wavefront of the row-major kernels holds: window after window
+      const int dk = sh.n_kv_heads * sh.head_dim;
+      for (int w = 0; w < batch; ++w) {
+        const int rc = launch_probe_t<T>(sh, 1, m, q_win + size_t(w) * m * d, stats,
+                                         update_stats & ~ACTQKV_PROBE_WINDOW_CHAIN, probe + size_t(w) * d,
+                                         probe_kv + size_t(w) * dk, probe_norm + w,
+                                         weights != nullptr ? weights + size_t(w) * m : nullptr, ws, stream);
+        if (rc != ACTQKV_OK) return rc;
+      }
+      return ACTQKV_OK;
+    }
+    const ChainScratch cl = chain_scratch(sh, batch, m);
+    float* part = scratch;
+    float* stat = part + cl.part;
+    float* pprobe = stat + cl.stat;
+    float* asum = pprobe + cl.pprobe;
+    float* a_rows = asum + cl.asum;
+    const int n_chunks = cl.n_chunks;
+    hipLaunchKernelGGL(probe_rows_moments_kernel<T>, dim3(n_chunks, batch, (d + 2 * kRmThreads * V - 1) / (2 * kRmThreads * V)),
+                       dim3(kRmThreads), 0, stream, q_win, part, m, d, n_chunks);
+    hipLaunchKernelGGL(probe_chain_stats_kernel<T>, dim3((d + 31) / 32), dim3(1024), size_t(batch) * 64 * sizeof(float),
+                       stream, q_win, part, stats, stat, batch, m, d, n_chunks, eps);
+    hipLaunchKernelGGL(probe_rows_bias_weigh_kernel<T>, dim3(n_chunks, batch), dim3(kRmThreads),
+                       size_t(2) * d * sizeof(float), stream, q_win, stat, stats, float(batch) * float(m), mean_pooling,
+                       pprobe, asum, a_rows, m, m_pad, d, n_chunks, cl.asum_stride);
+    hipLaunchKernelGGL(probe_chain_finish_kernel, dim3(batch), dim3(1024), size_t(d) * sizeof(float), stream, pprobe,
+                       asum, a_rows, stat,
+                       probe, probe_kv, probe_norm, weights, m, m_pad, d, n_chunks, cl.asum_stride, sh.n_q_heads,
+                       sh.n_kv_heads, sh.head_dim);
     return hip_status("probe");
   }
   update_stats &= ACTQKV_STATS_UPDATE;

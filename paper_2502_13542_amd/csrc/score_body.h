@@ -17,27 +17,30 @@ struct BlockScorer {
   static constexpr int V = Vec<T>::N;
   const T* block_keys;
   int n_rep, key_len, chunks, gq, l16;
-  float k0[kScoreBatch][V];
+  typedef typename Vec<T>::raw raw_t;
+  raw_t k0[kScoreBatch];          // as loaded (16 bytes each): widened only where they are used
 
   // kScoreBatch chunks of key j, starting at chunk c0: all loads are issued before any is used
-  __device__ __forceinline__ void load_batch(int j, int c0, float (&k)[kScoreBatch][V]) const {
+  __device__ __forceinline__ void load_batch(int j, int c0, raw_t (&k)[kScoreBatch]) const {
     const T* key = block_keys + size_t(j < n_rep ? j : 0) * key_len;
 #pragma unroll
     for (int i = 0; i < kScoreBatch; ++i) {
       const int c = c0 + 16 * i;
-      Vec<T>::load(key + (c < chunks ? c : l16) * V, k[i]);
+      k[i] = Vec<T>::load_raw(key + (c < chunks ? c : l16) * V);
     }
   }
   __device__ __forceinline__ void accumulate(const float* probe_lds, int j, int c0,
-                                             const float (&k)[kScoreBatch][V], float& dot, float& nrm) const {
+                                             const raw_t (&k)[kScoreBatch], float& dot, float& nrm) const {
 #pragma unroll
     for (int i = 0; i < kScoreBatch; ++i) {
       const int c = c0 + 16 * i;
       if (c < chunks && j < n_rep) {
+        float f[V];
+        Vec<T>::widen(k[i], f);
 #pragma unroll
         for (int v = 0; v < V; ++v) {
-          dot += probe_lds[c * V + v] * k[i][v];
-          nrm += k[i][v] * k[i][v];
+          dot += probe_lds[c * V + v] * f[v];
+          nrm += f[v] * f[v];
         }
       }
     }
@@ -72,7 +75,7 @@ struct BlockScorer {
       float dot = 0.f, nrm = 0.f;
       accumulate(probe_lds, gq, l16, k0, dot, nrm);
       for (int c0 = l16 + 16 * kScoreBatch; c0 < chunks; c0 += 16 * kScoreBatch) {
-        float kk[kScoreBatch][V];
+        raw_t kk[kScoreBatch];
         load_batch(gq, c0, kk);
         accumulate(probe_lds, gq, c0, kk, dot, nrm);
       }
@@ -82,7 +85,7 @@ struct BlockScorer {
       const int j = j0 + gq;
       float dot = 0.f, nrm = 0.f;
       for (int c0 = l16; c0 < chunks; c0 += 16 * kScoreBatch) {
-        float kk[kScoreBatch][V];
+        raw_t kk[kScoreBatch];
         load_batch(j, c0, kk);
         accumulate(probe_lds, j, c0, kk, dot, nrm);
       }

@@ -33,32 +33,48 @@ __device__ __forceinline__ unsigned long long shfl64(unsigned long long v, int s
   uint32_t lo = __shfl(uint32_t(v), src, 64), hi = __shfl(uint32_t(v >> 32), src, 64);
   return (static_cast<unsigned long long>(hi) << 32) | lo;
 }
+template <int J>
+__device__ __forceinline__ unsigned long long lane_xor64(unsigned long long v) {
+  const uint32_t lo = lane_xor32<J>(uint32_t(v)), hi = lane_xor32<J>(uint32_t(v >> 32));
+  return (static_cast<unsigned long long>(hi) << 32) | lo;
+}
 __device__ __forceinline__ unsigned long long umax64(unsigned long long a, unsigned long long b) {
   return a > b ? a : b;
 }
 __device__ __forceinline__ unsigned long long umin64(unsigned long long a, unsigned long long b) {
   return a < b ? a : b;
 }
+// one compare-exchange step of a bitonic network at lane distance J; keep_max per lane
+template <int J>
+__device__ __forceinline__ unsigned long long bitonic_step(unsigned long long v, bool keep_max) {
+  const unsigned long long o = lane_xor64<J>(v);
+  return keep_max ? umax64(v, o) : umin64(v, o);
+}
 // A bitonic sequence across the 64 lanes -> sorted, lane 0 largest.
 __device__ __forceinline__ unsigned long long bitonic_merge_desc(unsigned long long v, int lane) {
-#pragma unroll
-  for (int j = 32; j > 0; j >>= 1) {
-    unsigned long long o = shfl64(v, lane ^ j);
-    v = (lane & j) == 0 ? umax64(v, o) : umin64(v, o);
-  }
+  v = bitonic_step<32>(v, (lane & 32) == 0);
+  v = bitonic_step<16>(v, (lane & 16) == 0);
+  v = bitonic_step<8>(v, (lane & 8) == 0);
+  v = bitonic_step<4>(v, (lane & 4) == 0);
+  v = bitonic_step<2>(v, (lane & 2) == 0);
+  v = bitonic_step<1>(v, (lane & 1) == 0);
   return v;
 }
-// Any 64 keys across the lanes -> sorted, lane 0 largest.
+// Any 64 keys across the lanes -> sorted, lane 0 largest.  Stage k sorts runs of k lanes,
+// alternating in direction ((lane & k) == 0: descending), by steps at distances k/2 .. 1.
+template <int K, int J>
+__device__ __forceinline__ unsigned long long bitonic_stage(unsigned long long v, int lane) {
+  v = bitonic_step<J>(v, ((lane & K) == 0) == ((lane & J) == 0));
+  if constexpr (J > 1) v = bitonic_stage<K, J / 2>(v, lane);
+  return v;
+}
 __device__ __forceinline__ unsigned long long bitonic_sort_desc(unsigned long long v, int lane) {
-#pragma unroll
-  for (int k = 2; k <= 64; k <<= 1) {
-#pragma unroll
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      unsigned long long o = shfl64(v, lane ^ j);
-      bool keep_max = ((lane & k) == 0) == ((lane & j) == 0);
-      v = keep_max ? umax64(v, o) : umin64(v, o);
-    }
-  }
+  v = bitonic_stage<2, 1>(v, lane);
+  v = bitonic_stage<4, 2>(v, lane);
+  v = bitonic_stage<8, 4>(v, lane);
+  v = bitonic_stage<16, 8>(v, lane);
+  v = bitonic_stage<32, 16>(v, lane);
+  v = bitonic_stage<64, 32>(v, lane);      // (lane & 64) == 0 for every lane: descending
   return v;
 }
 

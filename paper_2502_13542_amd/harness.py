@@ -152,6 +152,24 @@ class LayerRunner:
                                   self.budget, out, lse, self.workspace, stream)
 
 
+    def decode_step_one_launch(self, q_tok: torch.Tensor, k_cache, v_cache, rep_keys, n_ctx: torch.Tensor,
+                               nb_end: torch.Tensor, out: torch.Tensor,
+                               budget_in: Optional[torch.Tensor] = None,
+                               theta_rest_sum: Optional[torch.Tensor] = None,
+                               budget_after: Optional[torch.Tensor] = None, k_new=None, v_new=None,
+                               lse=None, stream=None, flags: int = 0) -> None:
+        """A decode step in one launch (actqkv_decode_layer): the token is written at position
+        n_ctx - 1.  bf16, head_dim 128 only."""
+        sh, cs, bt = self.shape, self.cs, self.batch
+        nb_begin = sh.n_init // sh.block_size
+        cache_stride = k_cache.stride(0) if k_cache.dim() == 5 else 0
+        rep_stride = rep_keys.stride(0) if rep_keys.dim() == 5 else 0
+        B.decode_layer(cs, bt, q_tok, k_new, v_new, k_cache, v_cache, cache_stride, rep_keys, rep_stride,
+                       self.nb_capacity, n_ctx, nb_begin, nb_end, self.scores, self.score_stride, self.k_cap,
+                       budget_in, theta_rest_sum, budget_after, self.idx, self.n_sel, self.theta, self.budget,
+                       out, lse, self.workspace, stream, flags)
+
+
 @dataclass
 class PrefillPlan:
     """Per-window device scalars of a single-sequence prefill, uploaded once."""
@@ -246,7 +264,7 @@ class PrefillPipeline:
 
     def run(self, q: torch.Tensor, k_cache, v_cache, rep_keys, out: torch.Tensor, overlap: bool = True,
             events=None, chunk: int = 32, score_chunk: int = 16, batched: bool = False,
-            late_cus: int = 0, attention_cus: int = 256) -> None:
+            late_cus: int = 0, attention_cus: int = 256, prelude_events=None) -> None:
         """q, out [N][H][D].  events: optional per-window (start, end) event pairs recorded around
         the attention call of a window; with overlap, the pair of a chunk's first window brackets
         the chunk's one call, on the stream it runs on.  chunk: with overlap, the second stream picks up
@@ -257,7 +275,9 @@ class PrefillPipeline:
         (with overlap) also moves scoring and selection to a stream of their own, that many
         windows behind the probes (see _run_three_streams); 0 keeps them on the current stream.
         attention_cus: compute units the attention calls on the second stream may fill (the rest
-        serves the other chain); late_cus > 0 (batched only): see _run_batched."""
+        serves the other chain); late_cus > 0 (batched only): see _run_batched.
+        prelude_events (batched only): per-window (start, end) event pairs; the pair of a chunk's
+        first window brackets the chunk's probe, score and select calls on the current stream."""
         r, plan = self.runner, self.plan
         sh, cs = r.shape, r.cs
         nb_begin = sh.n_init // sh.block_size
@@ -265,7 +285,7 @@ class PrefillPipeline:
         chunk = max(1, min(chunk, self.MAX_CHUNK))
         self.attention_cus = attention_cus if overlap else 256
         if overlap and batched:
-            return self._run_batched(q, k_cache, v_cache, rep_keys, out, events, chunk, late_cus)
+            return self._run_batched(q, k_cache, v_cache, rep_keys, out, events, chunk, late_cus, prelude_events)
         if overlap and score_chunk > 0:
             return self._run_three_streams(q, k_cache, v_cache, rep_keys, out, events, chunk, score_chunk)
 
@@ -323,7 +343,8 @@ class PrefillPipeline:
         if overlap:
             cur.wait_stream(self.side)
 
-    def _run_batched(self, q, k_cache, v_cache, rep_keys, out, events, chunk, late_cus=0) -> None:
+    def _run_batched(self, q, k_cache, v_cache, rep_keys, out, events, chunk, late_cus=0,
+                     prelude_events=None) -> None:
         """A chunk of windows per call, for every step of the path.  The running statistics of
         Eq. (8) are the only thing a window hands to the next one within a layer, and merging a
         window into them needs nothing but that window's own moments; scores, density, budget
@@ -374,6 +395,8 @@ class PrefillPipeline:
             n_p = 0
             while t0 + n_p < plan.n_windows and n_p < chunk and plan.rows[t0 + n_p] == r.m:
                 n_p += 1
+            if prelude_events is not None:
+                prelude_events[t0][0].record(cur)
             if n_p >= 2:
                 w0, t1 = plan.w0[t0], t0 + n_p
                 B.build_probe(cs, n_p, r.m, q[w0:w0 + n_p * r.m], r.stats,
@@ -389,6 +412,8 @@ class PrefillPipeline:
             else:
                 n_p = 1
                 single(t0)
+            if prelude_events is not None:
+                prelude_events[t0][1].record(cur)
             selected = torch.cuda.Event()
             selected.record(cur)
             if pending is not None:

@@ -876,12 +876,14 @@ def test_scores_zero_norms_and_determinism():
     ("bf16", 32, 8, [2900, 2817, 1100, 700, 3000, 129, 2048, 1]),  # 64 pairs: one workgroup per pair
     ("bf16", 28, 4, [2900, 1100, 129]),                       # 7 query heads per KV head
 ])
-@pytest.mark.parametrize("launches", [4, 3, 2])
+@pytest.mark.parametrize("launches", [4, 3, 2, 1, 0])
 def test_decode_step_batch(dtype, hq, hkv, n_ctxs, launches):
     """launches 4: probe, scores, selection, attention; 3: probe and scores in one launch
     (actqkv_decode_retrieve); 2: the selection inside the attention launch as well
-    (actqkv_decode_select_attention; bf16 only)."""
-    if launches == 2 and dtype != "bf16":
+    (actqkv_decode_select_attention; bf16 only); 1: the whole layer in one launch
+    (actqkv_decode_layer); 0: the same with ACTQKV_DECODE_NO_WAIT, i.e. every workgroup takes
+    the path of a wait that ran out and scores its whole sequence itself."""
+    if launches <= 2 and dtype != "bf16":
         pytest.skip("the attention that selects for itself is a bf16 kernel")
     sh = LayerShape(hq, hkv, 128 if dtype == "bf16" else 64, 128, 4, 128, 256, dtype)
     w = synth.Workload("decode_small", sh, 3000, 1, 6, True, 2024, n_planted=4, batch=len(n_ctxs))
@@ -915,6 +917,26 @@ def test_decode_step_batch(dtype, hq, hkv, n_ctxs, launches):
         want_after = bud - runner.budget
         want_after[runner.n_sel == 0] = bud[runner.n_sel == 0]
         assert torch.allclose(after, want_after, rtol=1e-6, atol=1e-6)
+    elif launches <= 1:
+        after = torch.zeros_like(bud)
+        nb_end_d = torch.tensor(nb_ends, dtype=torch.int32, device=DEV)
+        for run in range(2):               # twice: the sequence counters must be back at zero
+            runner.decode_step_one_launch(qd, kc, vc, repd, torch.tensor(n_ctxs, dtype=torch.int32, device=DEV),
+                                          nb_end_d, out, bud, rest, after,
+                                          flags=0 if launches == 1 else B.DECODE_NO_WAIT)
+            torch.cuda.synchronize()
+            assert not runner.workspace[:8192].any(), "counters left dirty"
+        want_after = bud - runner.budget
+        want_after[runner.n_sel == 0] = bud[runner.n_sel == 0]
+        assert torch.allclose(after, want_after, rtol=1e-6, atol=1e-6)
+        # the scores are those of the scoring call
+        pkv = qd.float().reshape(bt, hkv, hq // hkv, -1).sum(dim=2).reshape(bt, -1).contiguous()
+        pn = qd.float().reshape(bt, -1).norm(dim=1).contiguous()
+        sc_ref = torch.zeros_like(runner.scores)
+        B.score_blocks(runner.cs, bt, pkv, pn, repd, repd.stride(0), nb_cap, 1, nb_end_d, sc_ref, runner.score_stride)
+        torch.cuda.synchronize()
+        for s_, e in enumerate(nb_ends):
+            assert torch.allclose(runner.scores[s_, 1:e], sc_ref[s_, 1:e], rtol=1e-5, atol=1e-6)
     else:
         runner.step(qd, kc, vc, repd, torch.tensor(n_ctxs, dtype=torch.int32, device=DEV),
                     torch.tensor(nb_ends, dtype=torch.int32, device=DEV), max(nb_ends), out, bud, rest,
@@ -930,7 +952,8 @@ def test_decode_step_batch(dtype, hq, hkv, n_ctxs, launches):
             ref = orc.retrieval_attention(f64(qs[s])[None], f64(ks[s]), f64(vs[s]), n - 1, gi[:gn],
                                           sh.n_init, sh.n_local, 128, sh.group)[0]
         assert out_error(out[s, 0], ref) < TOL_OUT[dtype], f"decode output, sequence {s}"
-        assert rel_to_max(runner.probe[s], f64(qs[s]).reshape(-1)) == 0.0   # probe is the query itself
+        if launches >= 2:      # (the one-launch layer keeps the probe to itself)
+            assert rel_to_max(runner.probe[s], f64(qs[s]).reshape(-1)) == 0.0   # probe is the query itself
 
 
 def test_decode_full_size_layer_as_benchmarked():
@@ -970,7 +993,7 @@ def test_decode_full_size_layer_as_benchmarked():
     cut = synth.cutoff_state(w, nb_end_h - nb_begin, 0, 5, 0)
     runner = H.LayerRunner(sh, bt, 1, nb_cap, w.k_cap, DEV)
     outs = []
-    for rep_run in range(3):
+    for rep_run in range(4):
         bud = torch.full((bt,), cut[0], dtype=torch.float32, device=DEV)
         rest = torch.full((bt,), cut[1], dtype=torch.float32, device=DEV)
         out = torch.zeros_like(q)
@@ -979,9 +1002,14 @@ def test_decode_full_size_layer_as_benchmarked():
             runner.step(q, kc, vc, rep, n_ctx, nb_end, nb_end_h, out, bud, rest, update_stats=False, m=1)
         elif rep_run == 1:    # three launches
             runner.decode_step(q, kc, vc, rep, n_ctx, nb_end, nb_end_h, out, bud, rest, k_new, v_new, pos0)
-        else:                 # two launches, as benchmarked
+        elif rep_run == 2:    # two launches
             after = torch.zeros_like(bud)
             runner.decode_step_two_launches(q, kc, vc, rep, n_ctx, nb_end, out, bud, rest, after, k_new, v_new, pos0)
+            bud = after
+        else:                 # one launch, as benchmarked
+            after = torch.zeros_like(bud)
+            runner.decode_step_one_launch(q, kc, vc, rep, n_ctx, nb_end, out, bud, rest, after,
+                                          k_new.squeeze(1).contiguous(), v_new.squeeze(1).contiguous())
             bud = after
         torch.cuda.synchronize()
         outs.append((runner.idx.clone(), runner.n_sel.clone(), out, runner.theta.clone(), bud))
@@ -1009,8 +1037,8 @@ def test_decode_full_size_layer_as_benchmarked():
                                           gi[:gn], sh.n_init, sh.n_local, 128, sh.group)[0]
         errs = [out_error(o[s, 0], ref) for o in outs]
         err = max(errs)
-        _say(f"[case] {w.name} sequence {s}: E = {gn}, output error {errs[0]:.3e} / {errs[1]:.3e} / {errs[2]:.3e} "
-             f"(five, three, two launches)")
+        _say(f"[case] {w.name} sequence {s}: E = {gn}, output error {errs[0]:.3e} / {errs[1]:.3e} / {errs[2]:.3e} / "
+             f"{errs[3]:.3e} (five, three, two launches, one launch)")
         assert err < TOL_OUT["bf16"], f"decode output, sequence {s}"
 
 
@@ -1364,6 +1392,76 @@ def test_decode_retrieve_equals_the_four_calls(dtype, hq, hkv, d, update):
     assert n_sel[2] == 0 and min(n_sel[0], n_sel[1], n_sel[3]) >= 1
     if update:
         assert not torch.equal(res[1][-1][3, 68], rep0[3, 68])            # representatives of the completed block
+
+
+def test_decode_layer_in_one_launch_equals_the_two_launches():
+    """actqkv_decode_layer = actqkv_decode_retrieve (scores only) + actqkv_decode_select_attention:
+    caches, representatives, scores, selection, density, budgets bit for bit, the output up to the
+    order of fp32 sums.  Ragged lengths (one sequence with no eligible block, one whose token
+    completes a block, one shorter than the initial tokens), the cut-off on, three steps in a row,
+    with the wait for the other workgroups and with every workgroup scoring for itself."""
+    sh = LayerShape(32, 8, 128, 128, 4, 128, 256, "bf16")
+    cs = B.c_shape(sh)
+    td = torch.bfloat16
+    n_tok = [9001, 5001, 301, 8832, 100]                 # 8832: the token at 8831 completes block 68
+    bt, nb, k_cap = len(n_tok), 72, 12
+    nb_begin = 1
+    ends = [H.eligible_range(sh, n - 1)[1] for n in n_tok]
+    g = torch.Generator().manual_seed(77)
+    kc0 = torch.randn(bt, nb, 8, 128, 128, generator=g).to(td).to(DEV)
+    vc0 = torch.randn(bt, nb, 8, 128, 128, generator=g).to(td).to(DEV)
+    rep0 = torch.randn(bt, nb, 4, 8, 128, generator=g).to(td).to(DEV)
+    n_ctx = torch.tensor(n_tok, dtype=torch.int32, device=DEV)
+    pos0 = n_ctx - 1
+    nb_end = torch.tensor(ends, dtype=torch.int32, device=DEV)
+    steps = [[torch.randn(bt, 1, 32, 128, generator=g).to(td).to(DEV),
+              torch.randn(bt, 1, 8, 128, generator=g).to(td).to(DEV),
+              torch.randn(bt, 1, 8, 128, generator=g).to(td).to(DEV)] for _ in range(3)]
+    res = []
+    for mode in ("two", "one", "one_no_wait"):
+        kc, vc, rep = kc0.clone(), vc0.clone(), rep0.clone()
+        runner = H.LayerRunner(sh, bt, 1, nb, k_cap, DEV)
+        bud = torch.full((bt,), 40.0, device=DEV)
+        got = []
+        for q, kn, vn in steps:
+            rest = torch.full((bt,), 9.0, device=DEV)
+            after = torch.zeros_like(bud)
+            out = torch.zeros_like(q)
+            lse = torch.zeros(bt, 32, 1, device=DEV)
+            if mode == "two":
+                runner.decode_step_two_launches(q, kc, vc, rep, n_ctx, nb_end, out, bud, rest, after, kn, vn, pos0,
+                                                lse=lse)
+            else:
+                runner.decode_step_one_launch(q, kc, vc, rep, n_ctx, nb_end, out, bud, rest, after,
+                                              kn.squeeze(1).contiguous(), vn.squeeze(1).contiguous(), lse=lse,
+                                              flags=0 if mode == "one" else B.DECODE_NO_WAIT)
+            torch.cuda.synchronize()
+            assert not runner.workspace[:8192].any(), "counters left dirty"
+            sc = runner.scores.clone()
+            for s_, e in enumerate(ends):
+                sc[s_, max(e, 0):] = 0
+                sc[s_, :nb_begin] = 0
+            got += [runner.idx.clone(), runner.n_sel.clone(), sc, runner.theta.clone(), runner.budget.clone(),
+                    after.clone(), out, lse]
+            bud = after
+        res.append(got + [kc, vc, rep])
+    names = ["idx", "n_sel", "scores", "theta", "budget", "budget_after", "out", "lse"]
+    for other in res[1:]:
+        for i, (a, b) in enumerate(zip(res[0], other)):
+            name = names[i % 8] if i < 24 else "cache"
+            if i >= 24 or i % 8 < 2:
+                assert torch.equal(a, b), name
+            elif i % 8 < 6:
+                assert torch.allclose(a, b, rtol=2e-6, atol=1e-7), name
+            else:
+                assert float((a.float() - b.float()).abs().max()) <= 1e-2 * float(a.float().abs().max()), name
+    assert torch.equal(res[1][6], res[2][6])              # waiting or not: the same bits
+    n_sel = res[1][1].cpu().tolist()
+    assert n_sel[2] == 0 and n_sel[4] == 0 and min(n_sel[0], n_sel[1], n_sel[3]) >= 1
+    assert not torch.equal(res[1][-1][3, 68], rep0[3, 68])            # representatives of the completed block
+    # the token sits in the cache where a later step will look for it
+    k_log, v_log = _logical_from_blocked(res[1][-3][4].cpu(), res[1][-2][4].cpu(), 100)
+    assert torch.equal(k_log[99], steps[-1][1][4, 0].cpu()) and torch.equal(v_log[99], steps[-1][2][4, 0].cpu())
 
 
 def test_two_streams_with_a_workspace_each():
