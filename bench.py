@@ -109,9 +109,12 @@ def capture_graph(torch, step_fn, check_tensor, log_name):
 PMC_COPY_BYTES = 256 << 20
 
 
-def pmc_pass(torch, B, one_step, info):
+def pmc_pass(torch, B, one_step, info, after=None):
     """One eager pass of the step for a hardware-counter run (rocprofv3 --pmc FETCH_SIZE or
-    WRITE_SIZE), after a plain copy of known size that calibrates the counter."""
+    WRITE_SIZE), after a plain copy of known size that calibrates the counter.  `after()` adds
+    what is only known once the pass has run (the blocks it selected, its algorithmic bytes);
+    the description of the pass goes to gpurun_out/pmc_pass_<workload>.json, from where
+    bench_traffic.py copies it next to the counter bytes."""
     src = torch.ones(PMC_COPY_BYTES, dtype=torch.uint8, device="cuda:0")
     dst = torch.zeros_like(src)
     torch.cuda.synchronize()
@@ -119,24 +122,43 @@ def pmc_pass(torch, B, one_step, info):
     torch.cuda.synchronize()
     one_step()
     torch.cuda.synchronize()
-    return dict(info, pmc_pass=True, copy_bytes=PMC_COPY_BYTES)
+    info = dict(info, pmc_pass=True, copy_bytes=PMC_COPY_BYTES)
+    if after is not None:
+        info.update(after())
+    out_dir = os.path.join(ROOT, "gpurun_out")
+    os.makedirs(out_dir, exist_ok=True)
+    with open(os.path.join(out_dir, f"pmc_pass_{info['workload']}.json"), "w") as f:
+        json.dump(info, f, indent=1, sort_keys=True)
+    return info
 
 
 def measured_traffic(workload):
-    """HBM bytes per attention launch from the committed counter runs, or None."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2502_13542_amd",
-                        "traffic_measured.json")
+    """HBM bytes per attention launch from the committed counter runs (bench_traffic.json,
+    written by bench_traffic.py), or None."""
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, "bench_traffic.json")) as f:
             return json.load(f).get(workload)
     except (OSError, ValueError):
         return None
 
 
-def traffic_fields(workload):
+def traffic_fields(workload, mean_blocks_selected=None):
+    """roofline.traffic: the stored counter bytes, as long as they were taken on the kernels that
+    are being timed (same hash of csrc/) and on a pass that selected about as many blocks."""
     t = measured_traffic(workload)
     if not t:
-        return {"traffic": None}
+        return {"traffic": None, "traffic_note": "no counter run stored for this workload"}
+    import bench_traffic
+    now = bench_traffic.source_hash()
+    if t.get("source_hash") != now:
+        return {"traffic": None,
+                "traffic_note": f"stored counters were taken on other kernel sources ({t.get('source_hash')}, "
+                                f"now {now}): re-run the counter passes (profiles/ names the commands)"}
+    e_pass = (t.get("pass") or {}).get("mean_blocks_selected")
+    if mean_blocks_selected is not None and e_pass is not None and abs(e_pass - mean_blocks_selected) > 0.5:
+        return {"traffic": None,
+                "traffic_note": f"stored counters come from a pass that selected {e_pass:.2f} blocks on average, "
+                                f"this run {mean_blocks_selected:.2f}"}
     return {"traffic": t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"],
             "traffic_detail": dict(t, unit="bytes per attention launch",
                                    source="rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of bench.py --pmc-pass, "
@@ -180,8 +202,22 @@ def bench_prefill(args, torch, B, H, synth):
                  args.attention_late_cus if overlap else 0, args.attention_cus if overlap else 256, prelude_events)
 
     if args.pmc_pass:
+        def after():
+            ns = nsel_log.cpu().tolist()
+            elem = 4 if sh.dtype == "fp32" else 2
+            # per window: its queries and outputs once, and every visible key and value once
+            byt = 0.0
+            for t in range(n_win):
+                w0, rows = plan.w0[t], plan.rows[t]
+                keys = min(sh.n_init, w0) + ns[t] * sh.block_size + (w0 - H.local_start(sh, w0)) + rows
+                byt += (2 * rows * sh.n_q_heads + 2 * keys * sh.n_kv_heads) * sh.head_dim * elem
+            n_launch = max(len(pipe.chunk_starts), 1)
+            return {"mean_blocks_selected": sum(ns) / max(n_win, 1), "attention_launches": n_launch,
+                    "algorithmic_bytes_per_launch": byt / n_launch}
         return pmc_pass(torch, B, lambda: one_step(overlap=not args.no_overlap),
-                        {"workload": w.name, "windows": n_win, "windows_per_launch": args.chunk})
+                        {"workload": w.name, "windows": n_win, "windows_per_launch": args.chunk,
+                         "attention_cus": args.attention_cus, "attention_late_cus": args.attention_late_cus},
+                        after)
     def timed(run, steps):
         for _ in range(args.warmup):
             run()
@@ -246,7 +282,8 @@ def bench_prefill(args, torch, B, H, synth):
                               else ", one stream, window order"),
                    "ms_per_step_window_order": serial_s * 1e3},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, **traffic_fields(w.name),
+                     "frac": achieved / PEAK_BF16_TFLOPS,
+                     **traffic_fields(w.name, sum(n_sel) / max(n_win, 1)),
                      "kernel": ("actqkv_retrieval_attention launches of up to %d windows "
                                 "(attn_prefill_mfma_queued_kernel%s)" %
                                 (args.chunk, "; timed: the first team's launch of %d workgroups, with which the "
@@ -387,32 +424,61 @@ def bench_prefill_host_cache(args, torch, B, H, synth):
     bud0 = None if plan.budget is None else plan.budget.clone()
     host = H.HostCachePrefill(runner, plan)
     out = torch.zeros_like(q)
+    block_bytes = 2 * sh.n_kv_heads * sh.block_size * sh.head_dim * (4 if sh.dtype == "fp32" else 2)
 
-    def one_pass():
+    def timed(fn, steps):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    # ---- window order on one stream, eager (the store filled beforehand)
+    def in_order():
         runner.stats.zero_()
         if bud0 is not None:
             plan.budget.copy_(bud0)
         return host.run(q, k, v, k_store, v_store, repd, out, record=range(plan.n_windows))
 
-    rec = one_pass()
+    rec = in_order()
     torch.cuda.synchronize()
     blocks = sum(int(r["n_sel"]) for r in rec.values())
     steps = min(args.steps, 3)
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        host.run(q, k, v, k_store, v_store, repd, out)
+    dt_order = timed(in_order, steps)
+    out_order = out.clone()
+
+    # ---- the overlapped schedule: selection chain ahead, data movement, write-back and attention on
+    # streams of their own; the host store starts EMPTY and is filled by the write-back
+    k_store.zero_()
+    v_store.zero_()
+
+    def overlapped():
         runner.stats.zero_()
         if bud0 is not None:
             plan.budget.copy_(bud0)
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / steps
-    block_bytes = 2 * sh.n_kv_heads * sh.block_size * sh.head_dim * (4 if sh.dtype == "fp32" else 2)
+        host.run_overlapped(q, k, v, k_store, v_store, repd, out)
+
+    # (eager: capturing this four-stream schedule in a HIP graph crashed on the host inside the
+    # runtime's end-of-capture call, so it is not captured)
+    graph = None
+    dt = timed(overlapped, steps)
+    same = bool(torch.equal(out, out_order))
+    wb_bytes = (w.n_ctx // sh.block_size) * block_bytes
     return {"metric": "prefill retrieval-attn tokens/s per layer, cache in pinned host memory",
             "value": w.n_ctx / dt, "unit": "tokens/s", "ms_per_step": dt * 1e3, "steps": steps,
-            "config": {"workload": w.name, "working_cache_blocks": host.nb_work, "context_blocks": w.n_blocks,
-                       "launch": "eager, one stream, window order"},
-            "host_link": {"blocks_gathered_per_pass": blocks, "bytes_per_pass": blocks * block_bytes,
-                          "GBps_if_the_pass_were_only_the_gather": blocks * block_bytes / dt / 1e9}}
+            "config": {"workload": w.name, "working_cache_blocks": host.nb_work, "working_caches": host.N_WORK,
+                       "context_blocks": w.n_blocks,
+                       "launch": ("hip graph replay" if graph is not None else "eager") +
+                                 ", four streams: selection chain, data movement (local span, append, gather), "
+                                 "write-back, attention",
+                       "ms_per_step_window_order_one_stream": dt_order * 1e3,
+                       "output_equals_window_order": same},
+            "host_link": {"blocks_gathered_per_pass": blocks, "gather_bytes_per_pass": blocks * block_bytes,
+                          "write_back_bytes_per_pass": wb_bytes,
+                          "gather_GBps_over_the_whole_pass": blocks * block_bytes / dt / 1e9,
+                          "both_directions_GBps_over_the_whole_pass": (blocks * block_bytes + wb_bytes) / dt / 1e9}}
 
 
 def bench_decode(args, torch, B, H, synth):
@@ -578,7 +644,16 @@ def bench_decode(args, torch, B, H, synth):
         B.select(bt, runner.scores, runner.score_stride, nb_end_host[-1], nb_begin, nb_end_cur,
                  w.k_cap, budget, rest_all[l], runner.idx, nsel_log[l], theta_step[l], None)
     if args.pmc_pass:
-        return pmc_pass(torch, B, one_step, {"workload": w.name, "launches": L})
+        def after():
+            ns = nsel_log.cpu()
+            n_ctx_now = int(n_ctx_cur[0])
+            keys = min(sh.n_init, n_ctx_now - 1) + (n_ctx_now - H.local_start(sh, n_ctx_now - 1))
+            byt = float((ns.sum().item() * bs + keys * L * bt) * hk * D * 2 * 2)
+            return {"mean_blocks_selected": float(ns.float().mean()), "layers": L, "batch": bt,
+                    "launches_per_layer": args.decode_launches,
+                    "algorithmic_bytes_per_launch": byt / L,
+                    "scoring_bytes_per_launch": float((nb_end_host[0] - nb_begin) * sh.n_rep * hk * D * 2 * bt)}
+        return pmc_pass(torch, B, one_step, {"workload": w.name, "launches": L}, after)
     graph = None if args.eager else capture_graph(torch, one_step, out, "decode")
     run = graph.replay if graph is not None else one_step
     for t in range(min(8, steps)):
@@ -635,7 +710,8 @@ def bench_decode(args, torch, B, H, synth):
         "algorithmic_bytes_per_step": byt + score_bytes,
         "hbm_frac_of_step": (byt + score_bytes) / (mean_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": achieved / PEAK_HBM_GBS, **traffic_fields(w.name),
+                     "frac": achieved / PEAK_HBM_GBS,
+                     **traffic_fields(w.name, float(n_sel.float().mean())),
                      "kernel": ("actqkv_decode_layer launch (decode_layer_kernel: cache update + probe + scores + "
                                 "selection + attention of one layer)" if args.decode_launches == 1 else
                                 "actqkv_decode_select_attention launch (attn_decode_select_kernel: selection + attention)"

@@ -50,7 +50,7 @@
 extern "C" {
 #endif
 
-#define ACTQKV_VERSION 106
+#define ACTQKV_VERSION 107
 
 enum {
   ACTQKV_OK = 0,
@@ -75,8 +75,10 @@ enum {
   ACTQKV_SELECT_ENTROPY_TOPK = 1, /* density over the k_cap best blocks only (see actqkv_select) */
   ACTQKV_DECODE_SCORES_ONLY = 2,  /* actqkv_decode_retrieve stops after the scores (the caller selects,
                                      for instance inside actqkv_decode_select_attention) */
-  ACTQKV_DECODE_NO_WAIT = 4       /* actqkv_decode_layer: no workgroup waits for the scores of the others;
+  ACTQKV_DECODE_NO_WAIT = 4,      /* actqkv_decode_layer: no workgroup waits for the scores of the others;
                                      each scores its whole sequence itself (same results, slower) */
+  ACTQKV_SELECT_DENSITY_ONLY = 8, /* actqkv_select: Eq. (11) only; theta is the one output */
+  ACTQKV_SELECT_GIVEN_COUNT = 16  /* actqkv_select: E is read from n_sel instead of following from Eq. (12) */
 };
 
 /* Limits checked by every call (ACTQKV_ESHAPE otherwise):
@@ -174,8 +176,15 @@ int actqkv_score_blocks(const actqkv_shape* shape, int batch, const float* probe
  *   n_sel   [batch] int32 = E (0 when nothing is eligible; theta and budget are 0 then
  *           and budget_remaining is left alone).
  *   theta, budget  [batch] fp32, may be NULL.
- * Errors: EINVAL (null, one cut-off pointer without the other, unknown flag bits), ESHAPE
- * (k_cap, more than 8192 blocks), EALIGN. */
+ *   Alg. 1 as it is printed runs in three loops over the layers - every density, then every
+ *   budget, then the selections - which two flags make callable (neither takes the cut-off state):
+ *     flags & ACTQKV_SELECT_DENSITY_ONLY: only theta[s] is computed and written (required);
+ *       idx, n_sel, budget are left alone.
+ *     flags & ACTQKV_SELECT_GIVEN_COUNT: n_sel[s] holds E on entry (for instance a row of the
+ *       counts actqkv_cutoff_budgets wrote); the min(E, k_cap, n_eligible) best blocks are
+ *       selected, that number is written back to n_sel[s], and budget reports it.
+ * Errors: EINVAL (null, one cut-off pointer without the other, unknown or contradictory flag
+ * bits), ESHAPE (k_cap, more than 8192 blocks), EALIGN. */
 int actqkv_select(int batch, const float* scores, int64_t score_stride, int nb_capacity,
                   int nb_begin, const int32_t* nb_end, int k_cap, int flags, float* budget_remaining,
                   const float* theta_rest_sum, int32_t* idx, int32_t* n_sel, float* theta,
@@ -246,6 +255,21 @@ int actqkv_retrieval_attention_static(const actqkv_shape* shape, int batch, int 
 int actqkv_append_kv(const actqkv_shape* shape, int batch, int m, const void* k_new, const void* v_new,
                      const int32_t* pos0, void* k_cache, void* v_cache, int64_t cache_seq_stride,
                      void* rep_keys, int64_t rep_seq_stride, int nb_capacity, void* stream);
+
+/* The second loop of Alg. 1 with every density of the step known (Sec. 4.2, Eq. (12) with the
+ * mean density of a layer still to come taken to be that layer's own density of this step):
+ *   B_kv = n_layers * k_mean;  for l = 0 .. n_layers - 1:
+ *     B^l = theta^l / (theta^l + sum_{j > l} theta^j) * B_kv  (B_kv if the denominator is 0);
+ *     B_kv -= B^l;  E^l = min(k_cap, max(1, floor(B^l + 0.5))).
+ *   theta   device [n_layers][batch] fp32: the densities actqkv_select wrote with
+ *           ACTQKV_SELECT_DENSITY_ONLY, one row per layer.
+ *   budget  device [n_layers][batch] fp32: B^l.   count  device [n_layers][batch] int32: E^l; pass
+ *           row l as n_sel to actqkv_select with ACTQKV_SELECT_GIVEN_COUNT in layer l.
+ *   budget_left  device [batch] fp32, may be NULL: what is left of B_kv (0 up to rounding: the
+ *           budgets add up to n_layers * k_mean).
+ * Errors: EINVAL (null, k_mean <= 0), ESHAPE (n_layers outside 1..1024, k_cap outside 1..64). */
+int actqkv_cutoff_budgets(int batch, int n_layers, float k_mean, int k_cap, const float* theta, float* budget,
+                          int32_t* count, float* budget_left, void* stream);
 
 /* Start of a step of the dynamic cut-off (Sec. 4.2, Eq. (12); Alg. 1): keeps the history of
  * the layers' information densities on the device and prepares the two cut-off inputs of
@@ -437,10 +461,12 @@ int actqkv_gather_blocks(const actqkv_shape* shape, int batch, const void* k_sto
                          void* v_cache, int64_t cache_seq_stride, int nb_capacity, int slot0,
                          int32_t* idx_slots, void* stream);
 
-/* Measurement aid, not a step of the method: a plain copy of `bytes` bytes (a multiple
- * of 16; both pointers device memory, 16-byte aligned, not overlapping) done by one
- * kernel with 16-byte loads and stores.  It reads and writes exactly `bytes` bytes of
- * HBM, which calibrates the hardware traffic counters against a known size. */
+/* A plain copy of `bytes` bytes (a multiple of 16; both pointers memory the device can access -
+ * device memory or pinned host memory -, 16-byte aligned, not overlapping) done by one kernel
+ * with 16-byte loads and stores.  Not a step of the method: between device buffers it reads and
+ * writes exactly `bytes` bytes of HBM, which calibrates the hardware traffic counters against a
+ * known size; with the cache kept in host memory (see actqkv_gather_blocks) it carries the local
+ * span from one working cache to the next and new blocks back to the host store. */
 int actqkv_copy_bytes(void* dst, const void* src, size_t bytes, void* stream);
 
 /* Message of the last error on this thread ("" if none). */

@@ -22,6 +22,7 @@ STATS_UPDATE, PROBE_MEAN_POOLING, PROBE_WINDOW_CHAIN = 1, 2, 4   # bits of build
 SELECT_ENTROPY_TOPK = 1                                          # bit of select's flags
 DECODE_SCORES_ONLY = 2                                           # bit of decode_retrieve's flags
 DECODE_NO_WAIT = 4                                               # bit of decode_layer's flags
+SELECT_DENSITY_ONLY, SELECT_GIVEN_COUNT = 8, 16                  # bits of select's flags
 ERROR_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EALIGN", -4: "EWORKSPACE", -5: "EHIP"}
 
 
@@ -63,6 +64,7 @@ SIGNATURES = {
                                                  _vp, _vp, _vp, _sz, _vp]),
     "actqkv_score_blocks_per_head": (_i, [_shp, _i, _vp, _vp, _i64, _i, _i, _vp, _vp, _i64, _vp]),
     "actqkv_append_kv": (_i, [_shp, _i, _i, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _vp]),
+    "actqkv_cutoff_budgets": (_i, [_i, _i, ctypes.c_float, _i, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_cutoff_next_step": (_i, [_i, _i, ctypes.c_float, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp]),
     "actqkv_append_kv_probe": (_i, [_shp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _vp, _vp, _vp, _vp]),
     "actqkv_decode_retrieve": (_i, [_shp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i, _i, _vp, _vp, _vp,
@@ -116,9 +118,22 @@ def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
     return t.data_ptr()
 
 
+_PINNED_STORAGES = {}     # storage address -> is it pinned (asking the runtime costs more than a launch)
+
+
+def _is_pinned(t: torch.Tensor) -> bool:
+    key = t.untyped_storage().data_ptr()
+    hit = _PINNED_STORAGES.get(key)
+    if hit is None:
+        if len(_PINNED_STORAGES) > 4096:
+            _PINNED_STORAGES.clear()
+        hit = _PINNED_STORAGES[key] = bool(t.is_pinned())
+    return hit
+
+
 def _ptr_readable(t: torch.Tensor, dtype=None) -> int:
     """A tensor a kernel may read in place: device memory or pinned host memory."""
-    if not (t.is_cuda or t.is_pinned()):
+    if not (t.is_cuda or _is_pinned(t)):
         raise ActQKVError(-1, "tensor is neither on the GPU nor in pinned host memory")
     if not t.is_contiguous():
         raise ActQKVError(-1, "tensor is not contiguous")
@@ -242,6 +257,13 @@ def retrieval_attention_teams(shape: CShape, batch: int, m: int, q, k_cache, v_c
         _stream(stream), _stream(stream_late)))
 
 
+def cutoff_budgets(batch: int, n_layers: int, k_mean: float, k_cap: int, theta, budget, count, budget_left=None,
+                   stream=None) -> None:
+    f = torch.float32
+    _check(load_library().actqkv_cutoff_budgets(batch, n_layers, k_mean, k_cap, _ptr(theta, f), _ptr(budget, f),
+                                                _ptr(count, torch.int32), _ptr(budget_left, f), _stream(stream)))
+
+
 def cutoff_next_step(batch: int, n_layers: int, k_mean: float, theta_prior: float, theta_prev,
                      theta_sum, n_steps, budget_remaining, theta_rest_sum, stream=None) -> None:
     f = torch.float32
@@ -251,11 +273,21 @@ def cutoff_next_step(batch: int, n_layers: int, k_mean: float, theta_prior: floa
 
 
 def copy_bytes(dst, src, stream=None) -> None:
-    """Plain device copy of src into dst by one kernel (traffic-counter calibration)."""
+    """Plain copy of src into dst by one kernel; either may be device memory or pinned host memory."""
     n = src.numel() * src.element_size()
     if dst.numel() * dst.element_size() != n:
         raise ActQKVError(-1, "copy_bytes: sizes differ")
-    _check(load_library().actqkv_copy_bytes(_ptr(dst), _ptr(src), n, _stream(stream)))
+    _check(load_library().actqkv_copy_bytes(_ptr_readable(dst), _ptr_readable(src), n, _stream(stream)))
+
+
+def copy_bytes_at(dst, dst_byte: int, src, src_byte: int, n_bytes: int, stream=None) -> None:
+    """copy_bytes between byte offsets of two tensors, without making views of them (a slice costs
+    the host about as much as the launch); offsets and length are checked against the tensors."""
+    if dst_byte < 0 or src_byte < 0 or n_bytes < 0 or dst_byte + n_bytes > dst.numel() * dst.element_size() \
+            or src_byte + n_bytes > src.numel() * src.element_size():
+        raise ActQKVError(-1, "copy_bytes_at: range outside a tensor")
+    _check(load_library().actqkv_copy_bytes(_ptr_readable(dst) + dst_byte, _ptr_readable(src) + src_byte, n_bytes,
+                                            _stream(stream)))
 
 
 def build_probe(shape: CShape, batch: int, m: int, q_win, stats, update_stats, probe, probe_kv,

@@ -325,7 +325,14 @@ int actqkv_select(int batch, const float* scores, int64_t score_stride, int nb_c
                   const int32_t* nb_end, int k_cap, int flags, float* budget_remaining,
                   const float* theta_rest_sum, int32_t* idx, int32_t* n_sel, float* theta,
                   float* budget, void* stream) {
-  if (flags & ~ACTQKV_SELECT_ENTROPY_TOPK) return set_error(ACTQKV_EINVAL, "select: unknown flag bits: %d", flags);
+  if (flags & ~(ACTQKV_SELECT_ENTROPY_TOPK | ACTQKV_SELECT_DENSITY_ONLY | ACTQKV_SELECT_GIVEN_COUNT))
+    return set_error(ACTQKV_EINVAL, "select: unknown flag bits: %d", flags);
+  if ((flags & ACTQKV_SELECT_DENSITY_ONLY) && (flags & ACTQKV_SELECT_GIVEN_COUNT))
+    return set_error(ACTQKV_EINVAL, "select: density only and a given count exclude each other");
+  if ((flags & ACTQKV_SELECT_DENSITY_ONLY) && theta == nullptr)
+    return set_error(ACTQKV_EINVAL, "select: density only needs theta");
+  if ((flags & (ACTQKV_SELECT_DENSITY_ONLY | ACTQKV_SELECT_GIVEN_COUNT)) && budget_remaining != nullptr)
+    return set_error(ACTQKV_EINVAL, "select: the cut-off state is not used with density only or a given count");
   ACTQKV_TRY(check_batch(batch));
   ACTQKV_TRY(check_blocks(nb_capacity, nb_begin, k_cap, true));
   ACTQKV_REQUIRE_SMALL(scores, 4);
@@ -702,6 +709,21 @@ int actqkv_decode_retrieve(const actqkv_shape* shape, int batch, const void* q_t
                                 rep_keys, rep_seq_stride, nb_capacity, nb_begin, nb_end, probe, probe_kv,
                                 probe_norm, scores, score_stride, k_cap, flags, budget_remaining,
                                 theta_rest_sum, idx, n_sel, theta, budget, static_cast<hipStream_t>(stream));
+}
+
+int actqkv_cutoff_budgets(int batch, int n_layers, float k_mean, int k_cap, const float* theta, float* budget,
+                          int32_t* count, float* budget_left, void* stream) {
+  ACTQKV_TRY(check_batch(batch));
+  if (n_layers < 1 || n_layers > 1024)
+    return set_error(ACTQKV_ESHAPE, "n_layers %d not supported (1..1024)", n_layers);
+  if (!(k_mean > 0.f)) return set_error(ACTQKV_EINVAL, "k_mean must be positive");
+  if (k_cap < 1 || k_cap > 64) return set_error(ACTQKV_ESHAPE, "k_cap %d not supported (1..64)", k_cap);
+  ACTQKV_REQUIRE_SMALL(theta, 4);
+  ACTQKV_REQUIRE_SMALL(budget, 4);
+  ACTQKV_REQUIRE_SMALL(count, 4);
+  ACTQKV_OPTIONAL_SMALL(budget_left, 4);
+  return launch_cutoff_budgets(batch, n_layers, k_mean, k_cap, theta, budget, count, budget_left,
+                               static_cast<hipStream_t>(stream));
 }
 
 int actqkv_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_prior,

@@ -49,6 +49,17 @@ constexpr int kPfQueueDone = 128;                    // index of the "left" coun
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// sum += the eight bf16 values of a packed operand (as fp32): four dot products of a pair with
+// (1, 1).  (Written as assembly: the compiler's builtin for this instruction takes the first
+// pair of a packed vector whatever element is asked for.)
+__device__ __forceinline__ void add_bf16x8(float& sum, bf16x8 v, uint32_t ones) {
+  const u32x4 w = __builtin_bit_cast(u32x4, v);
+  asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(sum) : "v"(w.x), "v"(ones));
+  asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(sum) : "v"(w.y), "v"(ones));
+  asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(sum) : "v"(w.z), "v"(ones));
+  asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(sum) : "v"(w.w), "v"(ones));
+}
+
 // 8 fp32 -> 8 bf16 (round to nearest even), packed as an MFMA operand
 __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, float a4, float a5,
                                         float a6, float a7) {
@@ -171,7 +182,11 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
   const bool row_ok = my_row < p.m && head_ok;
   const int my_pos = g.w0 + my_row;                          // this lane's query position
 
-  // Q^T as B operand: lane (n, half) holds d = ks*16 + 8*half .. +7 of query row n
+  // Q^T as B operand: lane (n, half) holds d = ks*16 + 8*half .. +7 of query row n.  (Folding
+  // scale * log2(e) into these operands, rounded to bf16 again, and starting the score
+  // accumulators at minus the reference maximum would spare the multiply-add per score, but the
+  // second rounding of the queries moves large logits by 2^-9 of their size: 2 % output error on
+  // heavy-tailed inputs.)
   bf16x8 qreg[kPfD / 16];
   {
     const int r = min(my_row, p.m - 1);
@@ -187,6 +202,7 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc_o[i][j] = 0.f;
   float m_run = -INFINITY;                // running max (log2 units)
+  const uint32_t bf16_ones = 0x3f803f80u;
 
   const char* kc = reinterpret_cast<const char*>(p.k_cache + size_t(s) * p.seq_stride);
   const char* vc = reinterpret_cast<const char*>(p.v_cache + size_t(s) * p.seq_stride);
@@ -345,32 +361,26 @@ __device__ __forceinline__ void attn_prefill_item(const PfParams& p, uint16_t* l
         l_run *= alpha;
       }
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        acc_s[0][i] = __builtin_amdgcn_exp2f(acc_s[0][i] * p.scale_log2e - m_safe);
-        l_run += acc_s[0][i];
-      }
+      for (int i = 0; i < 16; ++i) acc_s[0][i] = __builtin_amdgcn_exp2f(acc_s[0][i] * p.scale_log2e - m_safe);
       __builtin_amdgcn_sched_barrier(0);
       // ---- O^T += V^T P^T.  Written in issue order: the exponentials of the next 32 keys sit
       // between the MFMAs of these 32 (the vector ALU works while the matrix pipe does), and every
-      // V^T operand is read 8 MFMAs ahead.  The row sums are plain additions of the fp32
-      // probabilities, each lane summing its own 64 keys of the tile (an extra MFMA per 16 keys
-      // against an all-ones operand summed the bf16-rounded probabilities instead and spared
-      // the vector ALU, but the matrix pipe and the LDS are the busier units: 3.5 % slower).
+      // V^T operand is read 8 MFMAs ahead.  The row sums add the bf16 probabilities the product
+      // itself uses, a pair per instruction, each lane summing its own 64 keys of the tile.
 #pragma unroll
       for (int g8 = 0; g8 < 8; ++g8) {
         const int kb = g8 >> 1, s2 = g8 & 1;
         const bf16x8 pb = pack8(acc_s[kb][8 * s2 + 0], acc_s[kb][8 * s2 + 1], acc_s[kb][8 * s2 + 2],
                                 acc_s[kb][8 * s2 + 3], acc_s[kb][8 * s2 + 4], acc_s[kb][8 * s2 + 5],
                                 acc_s[kb][8 * s2 + 6], acc_s[kb][8 * s2 + 7]);
+        add_bf16x8(l_run, pb, bf16_ones);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
           if (kb < 3) {
 #pragma unroll
-            for (int i = 8 * s2 + 2 * db; i < 8 * s2 + 2 * db + 2; ++i) {
+            for (int i = 8 * s2 + 2 * db; i < 8 * s2 + 2 * db + 2; ++i)
               acc_s[kb + 1][i] = __builtin_amdgcn_exp2f(acc_s[kb + 1][i] * p.scale_log2e - m_safe);
-              l_run += acc_s[kb + 1][i];
-            }
           }
           __builtin_amdgcn_sched_barrier(0);
           const int j = 4 * g8 + db;

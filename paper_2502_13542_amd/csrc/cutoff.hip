@@ -41,6 +41,47 @@ __global__ __launch_bounds__(kMaxLayers) void cutoff_next_step_kernel(
   }
 }
 
+// Alg. 1, second loop, with every density of the step known (the exact form: the mean density of
+// a layer still to come is that layer's own density of this step).  grid (batch); thread j =
+// layer j sums the densities behind it (from the last layer down), thread 0 then hands out the
+// budget layer by layer: B^l = Theta^l / (Theta^l + R^l) * B_kv, B_kv -= B^l, and E^l = B^l
+// rounded half up, at least 1, at most k_cap.
+__global__ __launch_bounds__(kMaxLayers) void cutoff_budgets_kernel(int n_layers, int batch, float k_mean, int k_cap,
+                                                                    const float* __restrict__ theta,
+                                                                    float* __restrict__ budget,
+                                                                    int32_t* __restrict__ count,
+                                                                    float* __restrict__ budget_left) {
+  __shared__ float th[kMaxLayers], rest[kMaxLayers];
+  const int s = blockIdx.x, j = threadIdx.x;
+  if (j < n_layers) th[j] = theta[size_t(j) * batch + s];
+  __syncthreads();
+  if (j < n_layers) {
+    float r = 0.f;
+    for (int i = n_layers - 1; i > j; --i) r += th[i];
+    rest[j] = r;
+  }
+  __syncthreads();
+  if (j == 0) {
+    float b_kv = float(n_layers) * k_mean;
+    for (int l = 0; l < n_layers; ++l) {
+      const float den = th[l] + rest[l];
+      const float b_l = den > 0.f ? th[l] / den * b_kv : b_kv;
+      b_kv -= b_l;
+      budget[size_t(l) * batch + s] = b_l;
+      count[size_t(l) * batch + s] = int(fminf(fmaxf(floorf(b_l + 0.5f), 1.f), float(k_cap)));
+    }
+    if (budget_left != nullptr) budget_left[s] = b_kv;
+  }
+}
+
+int launch_cutoff_budgets(int batch, int n_layers, float k_mean, int k_cap, const float* theta, float* budget,
+                          int32_t* count, float* budget_left, hipStream_t stream) {
+  const int threads = (n_layers + 63) / 64 * 64;
+  hipLaunchKernelGGL(cutoff_budgets_kernel, dim3(batch), dim3(threads), 0, stream, n_layers, batch, k_mean, k_cap,
+                     theta, budget, count, budget_left);
+  return hip_status("cutoff_budgets");
+}
+
 int launch_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_prior,
                             const float* theta_prev, float* theta_sum, float* n_steps,
                             float* budget_remaining, float* theta_rest_sum, hipStream_t stream) {

@@ -8,44 +8,55 @@
 // always resident: the initial tokens before the slots, the local span and the window behind
 // them.  Attention then runs on the working cache with the slot numbers as its selection.
 //
-// grid (k_cap, Hk, batch), 256 threads; a workgroup moves one K tile and one V^T tile
-// (Bs x D elements each) with 16-byte loads, all of a thread's loads requested before the
-// first store: the host link is latency-bound per request.
+// grid (kGatherWgs, batch), 256 threads.  A few persistent workgroups walk over the (block, KV
+// head) tiles of a sequence; a thread keeps 2 x kGatherBatch 16-byte loads in flight.  The host
+// link needs about 100 KB of requests in flight to stay busy (60 GB/s times 2 us); a workgroup
+// per tile had fifty times that outstanding, which fills the memory system's queues with slow
+// host reads and slows every other kernel on the chip (a 9 us probe kernel beside such a
+// gather took 200 us).
 #include "common.h"
 #include "launch.h"
 
 namespace actqkv {
 
 constexpr int kGatherThreads = 256;
-constexpr int kGatherBatch = 8;   // 16-byte loads per tile a thread keeps in flight
+constexpr int kGatherBatch = 4;   // 16-byte loads per tile kind a thread keeps in flight
+constexpr int kGatherWgs = 8;
 
 __global__ __launch_bounds__(kGatherThreads) void gather_blocks_kernel(
     const u32x4* __restrict__ k_store, const u32x4* __restrict__ v_store, int64_t store_stride16,
     int nb_store, const int32_t* __restrict__ idx, const int32_t* __restrict__ n_sel, int k_cap,
     u32x4* __restrict__ k_cache, u32x4* __restrict__ v_cache, int64_t cache_stride16, int slot0,
     int32_t* __restrict__ idx_slots, int n_kv_heads, int tile16) {
-  const int j = blockIdx.x, hk = blockIdx.y, s = blockIdx.z;
+  const int s = blockIdx.y;
   const int e = min(max(n_sel[s], 0), k_cap);
-  const int b = idx[size_t(s) * k_cap + j];
-  const bool live = j < e && b >= 0 && b < nb_store;
-  if (hk == 0 && threadIdx.x == 0 && idx_slots != nullptr) idx_slots[size_t(s) * k_cap + j] = live ? slot0 + j : -1;
-  if (!live) return;
-  const size_t src = size_t(s) * store_stride16 + (size_t(b) * n_kv_heads + hk) * tile16;
-  const size_t dst = size_t(s) * cache_stride16 + (size_t(slot0 + j) * n_kv_heads + hk) * tile16;
-  for (int c0 = threadIdx.x; c0 < tile16; c0 += kGatherThreads * kGatherBatch) {
-    u32x4 kk[kGatherBatch], vv[kGatherBatch];
-#pragma unroll
-    for (int i = 0; i < kGatherBatch; ++i) {
-      const int c = c0 + i * kGatherThreads;
-      kk[i] = k_store[src + (c < tile16 ? c : c0)];
-      vv[i] = v_store[src + (c < tile16 ? c : c0)];
+  if (blockIdx.x == 0 && idx_slots != nullptr) {
+    for (int j = threadIdx.x; j < k_cap; j += kGatherThreads) {
+      const int b = idx[size_t(s) * k_cap + j];
+      idx_slots[size_t(s) * k_cap + j] = (j < e && b >= 0 && b < nb_store) ? slot0 + j : -1;
     }
+  }
+  for (int tile = blockIdx.x; tile < e * n_kv_heads; tile += gridDim.x) {
+    const int j = tile / n_kv_heads, hk = tile - j * n_kv_heads;
+    const int b = idx[size_t(s) * k_cap + j];
+    if (b < 0 || b >= nb_store) continue;
+    const size_t src = size_t(s) * store_stride16 + (size_t(b) * n_kv_heads + hk) * tile16;
+    const size_t dst = size_t(s) * cache_stride16 + (size_t(slot0 + j) * n_kv_heads + hk) * tile16;
+    for (int c0 = threadIdx.x; c0 < tile16; c0 += kGatherThreads * kGatherBatch) {
+      u32x4 kk[kGatherBatch], vv[kGatherBatch];
 #pragma unroll
-    for (int i = 0; i < kGatherBatch; ++i) {
-      const int c = c0 + i * kGatherThreads;
-      if (c < tile16) {
-        k_cache[dst + c] = kk[i];
-        v_cache[dst + c] = vv[i];
+      for (int i = 0; i < kGatherBatch; ++i) {
+        const int c = c0 + i * kGatherThreads;
+        kk[i] = k_store[src + (c < tile16 ? c : c0)];
+        vv[i] = v_store[src + (c < tile16 ? c : c0)];
+      }
+#pragma unroll
+      for (int i = 0; i < kGatherBatch; ++i) {
+        const int c = c0 + i * kGatherThreads;
+        if (c < tile16) {
+          k_cache[dst + c] = kk[i];
+          v_cache[dst + c] = vv[i];
+        }
       }
     }
   }
@@ -58,7 +69,7 @@ int launch_gather(const actqkv_shape& sh, int batch, const void* k_store, const 
   const int elem = sh.dtype == ACTQKV_F32 ? 4 : 2;
   const int per16 = 16 / elem;                                   // elements per 16 bytes
   const int tile16 = sh.block_size * sh.head_dim / per16;
-  hipLaunchKernelGGL(gather_blocks_kernel, dim3(k_cap, sh.n_kv_heads, batch), dim3(kGatherThreads), 0, stream,
+  hipLaunchKernelGGL(gather_blocks_kernel, dim3(kGatherWgs, batch), dim3(kGatherThreads), 0, stream,
                      static_cast<const u32x4*>(k_store), static_cast<const u32x4*>(v_store),
                      store_stride / per16, nb_store, idx, n_sel, k_cap, static_cast<u32x4*>(k_cache),
                      static_cast<u32x4*>(v_cache), cache_stride / per16, slot0, idx_slots, sh.n_kv_heads,

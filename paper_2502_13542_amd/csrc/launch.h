@@ -149,6 +149,8 @@ int launch_gather(const actqkv_shape& sh, int batch, const void* k_store, const 
                   void* k_cache, void* v_cache, int64_t cache_stride, int slot0, int32_t* idx_slots,
                   hipStream_t stream);
 
+int launch_cutoff_budgets(int batch, int n_layers, float k_mean, int k_cap, const float* theta, float* budget,
+                          int32_t* count, float* budget_left, hipStream_t stream);
 int launch_cutoff_next_step(int batch, int n_layers, float k_mean, float theta_prior,
                             const float* theta_prev, float* theta_sum, float* n_steps,
                             float* budget_remaining, float* theta_rest_sum, hipStream_t stream);

@@ -88,13 +88,25 @@ struct SelectIo {
   float* theta;                  // optional
   float* budget;                 // optional: B^l
   bool write;                    // false: nothing is stored (the caller reads the result from LDS)
+  // The two halves of Alg. 1 as it is printed (every density first, then every budget, then the
+  // selections): density_only stops after Eq. (11) and stores theta alone; count_in (per sequence,
+  // device memory) is an E^l that was computed elsewhere and replaces Eq. (12) in this call.
+  bool density_only = false;
+  const int32_t* count_in = nullptr;
 };
 
 // Eq. (12), the budget update that follows it, and E^l (Alg. 1); called by one thread.
 __device__ __forceinline__ int cutoff_count(float theta, int s, int n, int k_cap, const SelectIo& io) {
   float b_l;
   int e;
-  if (io.budget_in != nullptr) {
+  if (io.density_only) {
+    if (io.write && io.theta) io.theta[s] = theta;
+    return 0;
+  }
+  if (io.count_in != nullptr) {
+    e = min(max(io.count_in[s], 0), min(k_cap, n));
+    b_l = float(e);
+  } else if (io.budget_in != nullptr) {
     float b_kv = io.budget_in[s], rest = io.theta_rest_sum[s];
     float den = theta + rest;
     b_l = den > 0.f ? theta / den * b_kv : b_kv;
@@ -132,6 +144,11 @@ __device__ __forceinline__ void select_body(const Scores& sc, int s, int n, int 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int32_t* my_idx = io.idx + size_t(s) * k_cap;
   if (n == 0) {
+    if (io.density_only) {
+      if (tid == 0 && io.write && io.theta) io.theta[s] = 0.f;
+      __syncthreads();
+      return;
+    }
     if (tid < k_cap) {
       lds.sel[tid] = -1;
       if (io.write) my_idx[tid] = -1;
@@ -162,6 +179,10 @@ __device__ __forceinline__ void select_body(const Scores& sc, int s, int n, int 
     z = block_sum(z, lds.red);
     t = block_sum(t, lds.red);
     if (tid == 0) lds.count = cutoff_count(fmaxf(logf(z) + mx - t / z, 0.f), s, n, k_cap, io);
+    if (io.density_only) {
+      __syncthreads();
+      return;
+    }
   }
   // Alg. 1, third loop: the best blocks, best first
   unsigned long long run = 0ull;
@@ -201,6 +222,7 @@ __device__ __forceinline__ void select_body(const Scores& sc, int s, int n, int 
     if (lane == 0) lds.count = cutoff_count(fmaxf(logf(z) + mx - t / z, 0.f), s, n, k_cap, io);
   }
   __syncthreads();
+  if (io.density_only) return;        // (density over the best blocks: the tournament had to run first)
   if (wave == 0 && lane < k_cap) {
     const int b = lane < lds.count ? int(0xffffffffu - uint32_t(run)) : -1;
     lds.sel[lane] = b;

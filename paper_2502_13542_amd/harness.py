@@ -515,6 +515,9 @@ class HostCachePrefill:
     cache simply holds it whole at its true positions.  Needs m, n_init, n_local multiples of
     the block size (only the last window may be ragged)."""
 
+    GROUP = 4                 # windows per hand-over between the streams of the overlapped schedule
+    N_WORK = 2 * GROUP + 1    # working caches: a group being attended to, a group being filled, one source
+
     def __init__(self, runner: LayerRunner, plan: PrefillPlan):
         sh = runner.shape
         bs = sh.block_size
@@ -527,18 +530,41 @@ class HostCachePrefill:
         st = torch.float32 if sh.dtype == "fp32" else torch.bfloat16
         shape_k = (self.nb_work, sh.n_kv_heads, bs, sh.head_dim)
         shape_v = (self.nb_work, sh.n_kv_heads, sh.head_dim, bs)
-        self.k_work = [torch.zeros(shape_k, dtype=st, device=dev) for _ in range(2)]
-        self.v_work = [torch.zeros(shape_v, dtype=st, device=dev) for _ in range(2)]
+        self.k_work = [torch.zeros(shape_k, dtype=st, device=dev) for _ in range(self.N_WORK)]
+        self.v_work = [torch.zeros(shape_v, dtype=st, device=dev) for _ in range(self.N_WORK)]
         self.idx_slots = torch.full((1, runner.k_cap), -1, dtype=torch.int32, device=dev)
         self.n_ctx_work = torch.zeros(1, dtype=torch.int32, device=dev)
         self.pos0_work = torch.zeros(1, dtype=torch.int32, device=dev)
         self.workspace = torch.zeros(B.workspace_bytes(runner.cs, 1, runner.m, self.nb_work, runner.k_cap),
                                      dtype=torch.uint8, device=dev)
         self.gathered_blocks = 0
+        self.block_bytes = sh.n_kv_heads * bs * sh.head_dim * self.k_work[0].element_size()   # K or V of a block
+        # the overlapped schedule: every window keeps its own selection and scalars, and the data
+        # movement and the attention have streams of their own
+        T = plan.n_windows
+        self.idx_all = torch.full((T, runner.k_cap), -1, dtype=torch.int32, device=dev)
+        self.n_sel_all = torch.zeros(T, dtype=torch.int32, device=dev)
+        self.idx_slots_all = torch.full((T, runner.k_cap), -1, dtype=torch.int32, device=dev)
+        # (four streams with the current one: a process has four hardware queues here, and streams that
+        # share one run their kernels one after the other)
+        self.mover, self.attender, self.writer = (torch.cuda.Stream(device=dev) for _ in range(3))
+        self.geo = self.window_geometry()
+        self.n_ctx_w = torch.tensor([g["pos0"] + plan.rows[t] for t, g in enumerate(self.geo)], dtype=torch.int32,
+                                    device=dev)
+        self.pos0_w = torch.tensor([g["pos0"] for g in self.geo], dtype=torch.int32, device=dev)
+        # per-window views and events, made once (slicing and creating them costs the host as much as
+        # a launch, and the overlapped schedule is bound by what the host can enqueue)
+        one = lambda x: None if x is None else [x[t:t + 1] for t in range(T)]
+        self.v_idx, self.v_nsel, self.v_slots = one(self.idx_all), one(self.n_sel_all), one(self.idx_slots_all)
+        self.v_nctx, self.v_pos0, self.v_nb_end = one(self.n_ctx_w), one(self.pos0_w), one(plan.nb_end)
+        self.v_bud, self.v_rest = one(plan.budget), one(plan.rest)
+        self.ev_appended = [torch.cuda.Event() for _ in range(T)]
+        self.ev_written = [torch.cuda.Event() for _ in range(T)]
 
-    def _copy_blocks(self, src, dst, src_block: int, dst_block: int, n: int) -> None:
+    def _copy_blocks(self, src, dst, src_block: int, dst_block: int, n: int, stream=None) -> None:
         if n > 0:
-            B.copy_bytes(dst[dst_block:dst_block + n], src[src_block:src_block + n])
+            bb = self.block_bytes
+            B.copy_bytes_at(dst, dst_block * bb, src, src_block * bb, n * bb, stream)
 
     def run(self, q: torch.Tensor, k_tok: torch.Tensor, v_tok: torch.Tensor, k_store: torch.Tensor,
             v_store: torch.Tensor, rep_keys: torch.Tensor, out: torch.Tensor,
@@ -594,3 +620,131 @@ class HostCachePrefill:
                 rec[t] = dict(idx=r.idx[0].clone(), n_sel=r.n_sel[0].clone(), idx_slots=self.idx_slots[0].clone())
             cur, delta = new, new_delta
         return rec
+
+    def window_geometry(self):
+        """Per window: (working cache, the cache the local span comes from, real block - working block
+        of the tail, first working block of the local span in the source cache, blocks of local
+        span, position of the window's first token in the working cache, needs the initial blocks
+        copied).  Host-side bookkeeping only."""
+        r, plan = self.runner, self.plan
+        sh, bs = r.shape, r.shape.block_size
+        geo = []
+        cur, delta, has_init = 0, 0, [True] + [False] * (self.N_WORK - 1)
+        for t in range(plan.n_windows):
+            w0, rows = plan.w0[t], plan.rows[t]
+            l0 = local_start(sh, w0)
+            if l0 <= sh.n_init:
+                assert cur == 0 and w0 + rows <= self.nb_work * bs
+                geo.append(dict(new=0, src=0, src_block=0, n_loc=0, pos0=w0, copy_init=False, retrieving=False))
+                new, new_delta = 0, 0
+            else:
+                new = (cur + 1) % self.N_WORK
+                n_loc = (w0 - l0) // bs
+                geo.append(dict(new=new, src=cur, src_block=l0 // bs - delta, n_loc=n_loc,
+                                pos0=(self.tail0 + n_loc) * bs, copy_init=not has_init[new], retrieving=True))
+                has_init[new] = True
+                new_delta = l0 // bs - self.tail0
+            cur, delta = new, new_delta
+        return geo
+
+    def run_overlapped(self, q: torch.Tensor, k_tok: torch.Tensor, v_tok: torch.Tensor, k_store: torch.Tensor,
+                       v_store: torch.Tensor, rep_keys: torch.Tensor, out: torch.Tensor,
+                       write_back: bool = True) -> Dict[int, Dict[str, torch.Tensor]]:
+        """The same pass with the host link kept busy.  Four chains, handed over GROUP windows at a
+        time (a hand-over between streams costs the host more than a launch): on the current stream
+        the selection chain (it needs the queries and the representative keys only) and what is
+        always resident - the local span into the window's working cache, the window's keys and
+        values behind it; with write_back a second stream copies the window's new blocks from the
+        working cache to the host store (the link carries both directions at once), so the store
+        may start empty; a third does nothing but gather the selected blocks from the host store
+        into the slots, back to back; a fourth attends.  A window can select
+        blocks of the window two before it, so its gather waits for that window's write-back.
+        Results are those of run()."""
+        r, plan = self.runner, self.plan
+        sh, cs, bs = r.shape, r.cs, r.shape.block_size
+        nb_begin = sh.n_init // bs
+        nb_store = k_store.shape[0]
+        T, G = plan.n_windows, self.GROUP
+        geo, n_ctx_w, pos0_w = self.geo, self.n_ctx_w, self.pos0_w
+        cur = torch.cuda.current_stream()
+        for st in (self.mover, self.attender, self.writer):
+            st.wait_stream(cur)
+        attended, written = {}, {}      # events: group g attended to; window t written back
+        mover, attender, writer, prep = self.mover, self.attender, self.writer, cur
+        for g0 in range(0, T, G):
+            g, group = g0 // G, range(g0, min(g0 + G, T))
+            # ---- selection chain (current stream)
+            for t in group:
+                w0, rows = plan.w0[t], plan.rows[t]
+                bud = None if self.v_bud is None else self.v_bud[t]
+                rest = None if self.v_rest is None else self.v_rest[t]
+                nb_cap = min(max(plan.nb_end_host[t], nb_begin), r.nb_capacity)
+                B.build_probe(cs, 1, rows, q[w0:w0 + rows], r.stats, True, r.probe, r.probe_kv, r.probe_norm, None,
+                              r.workspace)
+                B.score_blocks(cs, 1, r.probe_kv, r.probe_norm, rep_keys, 0, nb_cap, nb_begin, self.v_nb_end[t],
+                               r.scores, r.score_stride)
+                B.select(1, r.scores, r.score_stride, nb_cap, nb_begin, self.v_nb_end[t], r.k_cap, bud, rest,
+                         self.v_idx[t], self.v_nsel[t], None, None)
+            selected = torch.cuda.Event()
+            selected.record(cur)
+            # ---- The working caches go round: the ones this group fills were last used two groups ago
+            # (attention, write-back, source of a local span).
+            for st in (prep, mover):
+                if g - 2 in attended:
+                    st.wait_event(attended[g - 2])
+                    last = min((g - 1) * G, T) - 1
+                    if last in written:
+                        st.wait_event(written[last])
+            # ---- what is always resident (still the current stream): the local span into the window's
+            # working cache, the window's keys and values behind it; the new blocks back to the store
+            # (second stream)
+            for t in group:
+                w0, rows = plan.w0[t], plan.rows[t]
+                ge = geo[t]
+                kw, vw = self.k_work[ge["new"]], self.v_work[ge["new"]]
+                if ge["retrieving"]:
+                    ks, vs = self.k_work[ge["src"]], self.v_work[ge["src"]]
+                    if ge["copy_init"]:
+                        self._copy_blocks(ks, kw, 0, 0, self.slot0, prep)
+                        self._copy_blocks(vs, vw, 0, 0, self.slot0, prep)
+                    self._copy_blocks(ks, kw, ge["src_block"], self.tail0, ge["n_loc"], prep)
+                    self._copy_blocks(vs, vw, ge["src_block"], self.tail0, ge["n_loc"], prep)
+                B.append_kv(cs, 1, rows, k_tok[w0:w0 + rows], v_tok[w0:w0 + rows], self.v_pos0[t], kw, vw, 0,
+                            None, 0, self.nb_work, prep)
+                if write_back and rows // bs > 0:
+                    self.ev_appended[t].record(prep)
+                    writer.wait_event(self.ev_appended[t])
+                    wb0, n_wb = ge["pos0"] // bs, rows // bs
+                    self._copy_blocks(kw, k_store, wb0, w0 // bs, n_wb, writer)
+                    self._copy_blocks(vw, v_store, wb0, w0 // bs, n_wb, writer)
+                    written[t] = self.ev_written[t]
+                    written[t].record(writer)
+            prepped = torch.cuda.Event()
+            prepped.record(prep)
+            # ---- the selected blocks over the host link into the slots (third stream: nothing but
+            # gathers, back to back, so that the link never waits for anything else)
+            mover.wait_event(selected)
+            for t in group:
+                ge = geo[t]
+                if t - 2 in written:
+                    mover.wait_event(written[t - 2])         # the newest blocks this window can select
+                B.gather_blocks(cs, 1, k_store, v_store, 0, nb_store, self.v_idx[t], self.v_nsel[t], r.k_cap,
+                                self.k_work[ge["new"]], self.v_work[ge["new"]], 0, self.nb_work, self.slot0,
+                                self.v_slots[t], mover)
+            moved = torch.cuda.Event()
+            moved.record(mover)
+            # ---- attention (fourth stream)
+            attender.wait_event(moved)
+            attender.wait_event(prepped)
+            for t in group:
+                w0, rows = plan.w0[t], plan.rows[t]
+                ge = geo[t]
+                B.retrieval_attention(cs, 1, rows, q[w0:w0 + rows], self.k_work[ge["new"]], self.v_work[ge["new"]],
+                                      0, self.nb_work, self.v_nctx[t], self.v_slots[t], self.v_nsel[t], r.k_cap,
+                                      out[w0:w0 + rows], None, self.workspace, attender)
+            attended[g] = torch.cuda.Event()
+            attended[g].record(attender)
+        for st in (self.mover, self.attender, self.writer):
+            cur.wait_stream(st)
+        return {t: dict(idx=self.idx_all[t], n_sel=self.n_sel_all[t], idx_slots=self.idx_slots_all[t])
+                for t in range(T)}

@@ -247,6 +247,21 @@ def test_retrieval_attention_static_rejects(lib):
     assert "scratch" in msg and str(32 << 20) in msg
 
 
+def test_cutoff_budgets_and_select_modes_reject(lib):
+    f = ctypes.c_float
+    call = lambda batch=2, L=32, k=8.0, cap=32, th=A16, b=A16, c=A16, left=None: \
+        lib.actqkv_cutoff_budgets(batch, L, f(k), cap, th, b, c, left, None)
+    assert call(batch=0) == -1 and call(k=0.0) == -1 and call(L=0) == -2 and call(L=2000) == -2
+    assert call(cap=0) == -2 and call(cap=65) == -2
+    assert call(th=None) == -1 and call(b=None) == -1 and call(c=A16 + 2) == -3 and call(left=A16 + 1) == -3
+    sel = lambda flags, theta=A16, bud=None, rest=None: lib.actqkv_select(
+        1, A16, 64, 64, 0, A16, 8, flags, bud, rest, A16, A16, theta, None, None)
+    assert sel(B.SELECT_DENSITY_ONLY | B.SELECT_GIVEN_COUNT) == -1 and b"exclude" in lib.actqkv_last_error()
+    assert sel(B.SELECT_DENSITY_ONLY, theta=None) == -1 and b"theta" in lib.actqkv_last_error()
+    assert sel(B.SELECT_GIVEN_COUNT, bud=A16, rest=A16) == -1 and b"cut-off state" in lib.actqkv_last_error()
+    assert sel(32) == -1 and b"unknown flag" in lib.actqkv_last_error()
+
+
 def test_cutoff_next_step_rejects(lib):
     f = ctypes.c_float
     call = lambda batch=2, L=32, k=8.0, prior=6.0, prev=A16, ts=A16, ns=A16, b=A16, r=A16: \

@@ -1893,6 +1893,73 @@ def test_cutoff_history_across_layers_and_steps():
     assert np.allclose(theta_sum.cpu().numpy() / steps, np.array([h.means() for h in hists]), rtol=1e-5)
 
 
+@pytest.mark.parametrize("topk", [False, True])
+def test_algorithm_1_in_its_three_loops(topk):
+    """Alg. 1 as it is printed: the density of every layer first (actqkv_select, density only),
+    then every budget (actqkv_cutoff_budgets: the mean density of a layer still to come is that
+    layer's own), then the selections with the counts given.  Against the oracle: densities,
+    budgets (which also telescope to L k theta^l / sum theta, with nothing left of B_kv), counts
+    and selected blocks, for sequences with different eligible ranges (one with a single block,
+    one with none) and the density over all eligible blocks or over the k_cap best ones."""
+    L, bt, k_cap, k_mean = 7, 5, 24, 6.0
+    n_blocks = [300, 1200, 40, 1, 0]
+    n_max = max(n_blocks) + 2
+    nb_begin = 2
+    rng = np.random.default_rng(404 + topk)
+    sharp = rng.uniform(0.5, 30.0, size=(L, bt))
+    scores = rng.standard_normal((L, bt, n_max)).astype(np.float32) * 0.05
+    scores[:, :, nb_begin:nb_begin + 6] += (sharp[:, :, None] * rng.uniform(0.5, 1.0, size=(L, bt, 6))).astype(np.float32) * 0.1
+    sd = torch.from_numpy(scores).to(DEV)
+    nb_end = torch.tensor([nb_begin + n for n in n_blocks], dtype=torch.int32, device=DEV)
+    theta = torch.full((L, bt), -1.0, device=DEV)
+    budget = torch.zeros(L, bt, device=DEV)
+    count = torch.zeros(L, bt, dtype=torch.int32, device=DEV)
+    left = torch.full((bt,), 9.0, device=DEV)
+    idx = torch.full((L, bt, k_cap), -7, dtype=torch.int32, device=DEV)
+    b_rep = torch.zeros(L, bt, device=DEV)
+    flag_t = B.SELECT_ENTROPY_TOPK if topk else 0
+    for l in range(L):                                   # first loop: densities only
+        B.select(bt, sd[l], n_max, n_max, nb_begin, nb_end, k_cap, None, None, idx[l], count[l], theta[l], None,
+                 flags=B.SELECT_DENSITY_ONLY | flag_t)
+    torch.cuda.synchronize()
+    assert bool((idx == -7).all()) and bool((count == 0).all())          # nothing but theta was written
+    B.cutoff_budgets(bt, L, k_mean, k_cap, theta, budget, count, left)   # second loop
+    torch.cuda.synchronize()
+    given = count.clone()
+    for l in range(L):                                   # third loop: the selections
+        B.select(bt, sd[l], n_max, n_max, nb_begin, nb_end, k_cap, None, None, idx[l], count[l], None, b_rep[l],
+                 flags=B.SELECT_GIVEN_COUNT | flag_t)
+    torch.cuda.synchronize()
+    th, bu = theta.cpu().numpy(), budget.cpu().numpy()
+    for s, n in enumerate(n_blocks):
+        el = [f64(scores[l, s, nb_begin:nb_begin + n]) for l in range(L)]
+        if n == 0:
+            want_t = [0.0] * L
+        else:
+            want_t = [orc.information_density_topk(e, k_cap) if topk else orc.information_density(e) for e in el]
+        assert np.allclose(th[:, s], want_t, atol=TOL_THETA), f"densities, sequence {s}"
+        rest = [sum(want_t[l + 1:]) for l in range(L)]
+        want_b = orc.step_budgets(want_t, rest, k_mean)
+        assert np.allclose(bu[:, s], want_b, rtol=TOL_BUDGET, atol=TOL_BUDGET), f"budgets, sequence {s}"
+        if sum(want_t) > 0:
+            closed = [L * k_mean * t / sum(want_t) for t in want_t]       # the budgets telescope
+            assert np.allclose(bu[:, s], closed, rtol=5e-4, atol=1e-3)
+        assert abs(float(left[s])) < 1e-3 * L * k_mean                    # the whole budget is handed out
+        for l in range(L):
+            b = want_b[l]
+            if abs(b + 0.5 - round(b + 0.5)) > 1e-3:
+                assert int(given[l, s]) == min(k_cap, max(1, math.floor(b + 0.5))), (l, s)
+            e = min(int(given[l, s]), n)
+            assert int(count[l, s]) == e and float(b_rep[l, s]) == float(e)
+            res = {"idx": orc.select_blocks(el[l], range(nb_begin, nb_begin + n), e), "scores": el[l],
+                   "nb_begin": nb_begin}
+            got = idx[l, s].cpu().tolist()
+            assert got[e:] == [-1] * (k_cap - e)
+            if got[:e] != res["idx"]:             # only blocks that all but tie may swap
+                sc = {b_: float(scores[l, s, b_]) for b_ in set(got[:e]) | set(res["idx"])}
+                assert sorted(sc[b_] for b_ in got[:e]) == pytest.approx(sorted(sc[b_] for b_ in res["idx"]), abs=2e-5)
+
+
 def test_pipeline_with_ragged_last_window_and_short_context():
     """The three-stream schedule on a context that is not a multiple of the window (the last
     window goes out as a call of its own) and on one shorter than a chunk."""
@@ -2085,6 +2152,30 @@ def test_prefill_with_the_cache_in_host_memory():
         n_retrieving += int(rec[t]["n_sel"]) > 0
     assert n_retrieving >= w.n_windows - 3
     assert torch.equal(out_host, out_hbm)
+    # the overlapped schedule (selection chain ahead, data movement and attention on streams of
+    # their own), with the host store EMPTY at the start: every block a window selects has been
+    # written back from a working cache by then.  Twice in a row, eagerly (capturing this
+    # four-stream schedule in a HIP graph ended in a host-side crash inside the runtime's
+    # end-of-capture call; the schedule is not captured anywhere).
+    k_zero, v_zero = torch.zeros_like(k_store).pin_memory(), torch.zeros_like(v_store).pin_memory()
+    out_ov = torch.zeros_like(qd)
+
+    def overlapped():
+        runner.reset()
+        plan.budget.copy_(bud0)
+        return host.run_overlapped(qd, kd, vd, k_zero, v_zero, repd, out_ov)
+    rec_ov = overlapped()
+    torch.cuda.synchronize()
+    for t in range(w.n_windows):
+        assert torch.equal(rec_ov[t]["idx"], rec_hbm[t]["idx"]) and int(rec_ov[t]["n_sel"]) == int(rec_hbm[t]["n_sel"])
+    assert torch.equal(out_ov, out_hbm)
+    full = w.n_ctx // sh.block_size
+    assert torch.equal(k_zero[:full], k_store[:full]) and torch.equal(v_zero[:full], v_store[:full])   # the store was rebuilt
+    k_zero.zero_(); v_zero.zero_()
+    out_ov.zero_()
+    overlapped()
+    torch.cuda.synchronize()
+    assert torch.equal(out_ov, out_hbm)
     attend = [2, 7, w.n_windows - 1]
     want = oracle_windows(q, k, v, rep, sh, w.window, w.k_cap, cutoffs, attend)
     for t in attend:
