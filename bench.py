@@ -32,6 +32,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
 PEAK_HBM_GBS = 8000.0
+PEAK_FP32_TFLOPS = 157.3    # fp32 vector arithmetic (the fp32 workload's attention runs in row kernels)
 
 
 def log(msg: str) -> None:
@@ -109,12 +110,12 @@ def capture_graph(torch, step_fn, check_tensor, log_name):
 PMC_COPY_BYTES = 256 << 20
 
 
-def pmc_pass(torch, B, one_step, info, after=None):
+def pmc_pass(torch, B, one_step, info, after=None, info_dir="."):
     """One eager pass of the step for a hardware-counter run (rocprofv3 --pmc FETCH_SIZE or
     WRITE_SIZE), after a plain copy of known size that calibrates the counter.  `after()` adds
     what is only known once the pass has run (the blocks it selected, its algorithmic bytes);
-    the description of the pass goes to gpurun_out/pmc_pass_<workload>.json, from where
-    bench_traffic.py copies it next to the counter bytes."""
+    the description of the pass goes to <info_dir>/pmc_pass_<workload>.json (--pmc-info-dir), from
+    where bench_traffic.py copies it next to the counter bytes."""
     src = torch.ones(PMC_COPY_BYTES, dtype=torch.uint8, device="cuda:0")
     dst = torch.zeros_like(src)
     torch.cuda.synchronize()
@@ -125,7 +126,7 @@ def pmc_pass(torch, B, one_step, info, after=None):
     info = dict(info, pmc_pass=True, copy_bytes=PMC_COPY_BYTES)
     if after is not None:
         info.update(after())
-    out_dir = os.path.join(ROOT, "gpurun_out")
+    out_dir = os.path.abspath(info_dir)
     os.makedirs(out_dir, exist_ok=True)
     with open(os.path.join(out_dir, f"pmc_pass_{info['workload']}.json"), "w") as f:
         json.dump(info, f, indent=1, sort_keys=True)
@@ -217,7 +218,7 @@ def bench_prefill(args, torch, B, H, synth):
         return pmc_pass(torch, B, lambda: one_step(overlap=not args.no_overlap),
                         {"workload": w.name, "windows": n_win, "windows_per_launch": args.chunk,
                          "attention_cus": args.attention_cus, "attention_late_cus": args.attention_late_cus},
-                        after)
+                        after, args.pmc_info_dir)
     def timed(run, steps):
         for _ in range(args.warmup):
             run()
@@ -281,8 +282,9 @@ def bench_prefill(args, torch, B, H, synth):
                               if overlap
                               else ", one stream, window order"),
                    "ms_per_step_window_order": serial_s * 1e3},
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma" if sh.dtype == "bf16" else "alu", "achieved": achieved,
+                     "peak": PEAK_BF16_TFLOPS if sh.dtype == "bf16" else PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / (PEAK_BF16_TFLOPS if sh.dtype == "bf16" else PEAK_FP32_TFLOPS),
                      **traffic_fields(w.name, sum(n_sel) / max(n_win, 1)),
                      "kernel": ("actqkv_retrieval_attention launches of up to %d windows "
                                 "(attn_prefill_mfma_queued_kernel%s)" %
@@ -330,6 +332,137 @@ def bench_prefill(args, torch, B, H, synth):
         log("cpu_baseline: timing the oracle on sampled windows")
         res["cpu_baseline"] = cpu_baseline(w, q, k, v, rep, cutoffs, sample)
     return res
+
+
+def bench_other_configs(args, torch, B, H, synth):
+    """The workloads beside the headline one, each as a short run of the same schedule, reduced to
+    the figures of a bench line: c1_8k_fp32 and c2_32k (one layer), c5_200k (32 layers, every
+    layer with its own inputs)."""
+    import copy
+    out = {}
+    for name in ("c1_8k_fp32", "c2_32k"):
+        a = copy.copy(args)
+        a.workload, a.n_ctx, a.steps, a.warmup, a.no_cpu_baseline, a.pmc_pass = name, 0, 5, 1, True, False
+        r = bench_prefill(a, torch, B, H, synth)
+        torch.cuda.empty_cache()
+        out[name] = {"metric": r["metric"], "value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"],
+                     "steps": r["steps"], "dtype": r["dtype"], "workload": r["config"]["workload"],
+                     "windows": r["config"]["windows"], "mean_blocks_selected": r["config"]["mean_blocks_selected"],
+                     "roofline": {k: r["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac",
+                                                                "avg_launch_us", "windows_per_launch")}}
+    a = copy.copy(args)
+    a.workload, a.n_ctx, a.steps, a.warmup, a.layers = "c5_200k", 0, 2, 1, synth.WORKLOADS["c5_200k"].n_layers
+    r = bench_prefill_layers(a, torch, B, H, synth)
+    torch.cuda.empty_cache()
+    out["c5_200k"] = {k: r[k] for k in ("metric", "value", "unit", "ms_per_step", "steps", "dtype")}
+    out["c5_200k"].update(workload=r["config"]["workload"], ms_per_layer=r["config"]["ms_per_layer"],
+                          mean_blocks_selected_per_layer=[round(x, 2) for x in
+                                                          r["config"]["mean_blocks_selected_per_layer"]])
+    return out
+
+
+def bench_recall(args, torch, B, H, synth, workload="c3_128k"):
+    """Synthetic stand-in for the ablation of Sec. 5.3 / Table 3: how many of the blocks that the input
+    recipe planted (keys shifted toward the direction the outlier queries carry) each variant of
+    the retrieval recalls, over every window of the workload, all through the library's calls:
+    probe-Query (Eq. 9) against mean pooling; a fixed k against the dynamic cut-off (Eq. 11, 12)
+    at the same mean number of blocks; the density over all eligible blocks against over the
+    top-k only; one selection for all heads against one per KV head."""
+    base = synth.WORKLOADS[workload]
+    out = {}
+    # the workload's own recipe, then the same with the planted keys and the outlier queries further out:
+    # where the variants part depends on how strong the planted relation is
+    for alpha, shift in ((base.alpha, base.shift), (base.alpha, 4 * base.shift), (4 * base.alpha, 4 * base.shift)):
+        w = synth.scaled(base, alpha=alpha, shift=shift)
+        r = _recall_of(w, torch, B, H, synth)
+        out[f"outlier queries + {alpha:g} u, planted keys + {shift:g} u" +
+            (" (the workload's recipe)" if (alpha, shift) == (base.alpha, base.shift) else "")] = r
+    T = base.n_ctx // base.window
+    return {"workload": base.name, "windows": T, "planted_blocks": base.n_planted, "k_cap": base.k_cap,
+            "what": "over all windows with a planted block among the eligible ones: recall = planted blocks "
+                    "selected / planted blocks eligible, precision = planted blocks selected / blocks selected; "
+                    "the cut-off rows use the workload's seeded budget per window",
+            "by_planted_signal": out}
+
+
+def _recall_of(w, torch, B, H, synth):
+    dev = "cuda:0"
+    sh = w.shape
+    cs = B.c_shape(sh)
+    q, k, _ = synth.gen_layer(w, dev)
+    rep = synth.pick_rep_keys(k, sh.block_size, sh.n_rep)
+    del k
+    repd = torch.zeros(w.n_blocks, sh.n_rep, sh.n_kv_heads, sh.head_dim, dtype=rep.dtype, device=dev)
+    repd[: rep.shape[0]] = rep
+    planted = set(synth.planted_blocks(w))
+    m, hk, kc = w.window, sh.n_kv_heads, w.k_cap
+    T = w.n_ctx // m
+    runs = {"probe": H.LayerRunner(sh, 1, m, w.n_blocks, kc, dev), "mean": H.LayerRunner(sh, 1, m, w.n_blocks, kc, dev)}
+    stride = runs["probe"].score_stride
+    nb_begin = sh.n_init // sh.block_size
+    sc = {n: torch.zeros(T, stride, device=dev) for n in ("probe", "mean")}
+    sc_ph = torch.zeros(T, hk, stride, device=dev)
+    ends = [H.eligible_range(sh, t * m)[1] for t in range(T)]
+    nb_end = torch.tensor(ends, dtype=torch.int32, device=dev)
+    nb_end_ph = nb_end[:, None].expand(T, hk).contiguous()
+    for t in range(T):
+        if ends[t] <= nb_begin:
+            continue
+        for name, r in runs.items():
+            flags = B.STATS_UPDATE | (B.PROBE_MEAN_POOLING if name == "mean" else 0)
+            B.build_probe(cs, 1, m, q[t * m:(t + 1) * m], r.stats, flags, r.probe, r.probe_kv, r.probe_norm, None,
+                          r.workspace)
+            B.score_blocks(cs, 1, r.probe_kv, r.probe_norm, repd, 0, ends[t], nb_begin, nb_end[t:t + 1],
+                           sc[name][t:t + 1], stride)
+        B.score_blocks_per_head(cs, 1, runs["probe"].probe, repd, 0, ends[t], nb_begin, nb_end_ph[t:t + 1],
+                                sc_ph[t:t + 1], stride)
+    nb_max = max(ends)
+    cut = [synth.cutoff_state(w, max(ends[t] - nb_begin, 0), t, 0) for t in range(T)]
+    bud = torch.tensor([c[0] for c in cut], dtype=torch.float32, device=dev)
+    rest = torch.tensor([c[1] for c in cut], dtype=torch.float32, device=dev)
+
+    def select(scores, rows, ends_t, k, cutoff, flags=0):
+        idx = torch.full((rows, k), -1, dtype=torch.int32, device=dev)
+        n = torch.zeros(rows, dtype=torch.int32, device=dev)
+        b = r_ = None
+        if cutoff:
+            per = rows // T
+            b = bud.repeat_interleave(per).contiguous()
+            r_ = rest.repeat_interleave(per).contiguous()
+        sc2, e2 = scores.view(rows, stride), ends_t.reshape(rows).contiguous()
+        for r0 in range(0, rows, 1024):                    # the library takes at most 1024 rows a call
+            r1 = min(r0 + 1024, rows)
+            B.select(r1 - r0, sc2[r0:r1], stride, nb_max, nb_begin, e2[r0:r1], k, None if b is None else b[r0:r1],
+                     None if r_ is None else r_[r0:r1], idx[r0:r1], n[r0:r1], None, None, None, flags)
+        return idx.cpu().tolist(), n.cpu().tolist()
+
+    def tally(idx, n, per=1):
+        hit = sel = tot = 0
+        for row in range(len(n)):
+            t = row // per
+            p = {b for b in planted if nb_begin <= b < ends[t]}
+            if not p:
+                continue
+            got = set(idx[row][:n[row]])
+            hit += len(got & p)
+            sel += n[row]
+            tot += len(p)
+        return {"recall": hit / max(tot, 1), "precision": hit / max(sel, 1),
+                "mean_blocks_selected": sel / max(sum(1 for t in range(T) if any(nb_begin <= b < ends[t]
+                                                                                  for b in planted)) * per, 1)}
+
+    out = {}
+    out["probe_query_fixed_k"] = tally(*select(sc["probe"], T, nb_end, kc, False))
+    out["mean_pooling_fixed_k"] = tally(*select(sc["mean"], T, nb_end, kc, False))
+    out["per_kv_head_fixed_k"] = tally(*select(sc_ph, T * hk, nb_end_ph, kc, False), per=hk)
+    out["probe_query_cutoff"] = tally(*select(sc["probe"], T, nb_end, kc, True))
+    out["probe_query_cutoff_density_over_top_k"] = tally(*select(sc["probe"], T, nb_end, kc, True,
+                                                                 B.SELECT_ENTROPY_TOPK))
+    out["mean_pooling_cutoff"] = tally(*select(sc["mean"], T, nb_end, kc, True))
+    k_same = max(1, min(kc, round(out["probe_query_cutoff"]["mean_blocks_selected"])))
+    out[f"probe_query_fixed_k_at_the_cutoffs_mean_of_{k_same}"] = tally(*select(sc["probe"], T, nb_end, k_same, False))
+    out[f"mean_pooling_fixed_k_of_{k_same}"] = tally(*select(sc["mean"], T, nb_end, k_same, False))
+    return {name: {k_: round(v_, 4) for k_, v_ in r.items()} for name, r in out.items()}
 
 
 def bench_prefill_layers(args, torch, B, H, synth):
@@ -653,7 +786,7 @@ def bench_decode(args, torch, B, H, synth):
                     "launches_per_layer": args.decode_launches,
                     "algorithmic_bytes_per_launch": byt / L,
                     "scoring_bytes_per_launch": float((nb_end_host[0] - nb_begin) * sh.n_rep * hk * D * 2 * bt)}
-        return pmc_pass(torch, B, one_step, {"workload": w.name, "launches": L}, after)
+        return pmc_pass(torch, B, one_step, {"workload": w.name, "launches": L}, after, args.pmc_info_dir)
     graph = None if args.eager else capture_graph(torch, one_step, out, "decode")
     run = graph.replay if graph is not None else one_step
     for t in range(min(8, steps)):
@@ -768,6 +901,12 @@ def main() -> int:
     ap.add_argument("--host-cache", action="store_true",
                     help="also time the prefill pass with the cache in pinned host memory (reported as "
                          "\"host_cache\" beside the headline line)")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="leave out the short runs of c1_8k_fp32, c2_32k and c5_200k (\"configs\" of the line)")
+    ap.add_argument("--no-recall", action="store_true",
+                    help="leave out the planted-block recall of the retrieval variants (\"recall\" of the line)")
+    ap.add_argument("--pmc-info-dir", default=".",
+                    help="--pmc-pass: folder that receives pmc_pass_<workload>.json, the description of the pass")
     ap.add_argument("--pmc-pass", action="store_true",
                     help="one calibration copy and one eager pass, for a rocprofv3 --pmc run")
     args = ap.parse_args()
@@ -802,10 +941,18 @@ def main() -> int:
             res = hc
     if not args.skip_decode:
         dec = bench_decode(args, torch, B, H, synth)
+        torch.cuda.empty_cache()
         if res:
             res["decode"] = dec
         else:
             res = dec
+    headline = args.workload == "c3_128k" and not args.n_ctx and not args.pmc_pass and not args.skip_prefill
+    if headline and not args.no_recall:
+        log("recall of planted blocks per retrieval variant")
+        res["recall"] = bench_recall(args, torch, B, H, synth)
+        torch.cuda.empty_cache()
+    if headline and not args.no_configs:
+        res["configs"] = bench_other_configs(args, torch, B, H, synth)
     print(json.dumps(res))
     return 0
 

@@ -8,7 +8,7 @@ are the ones the counters were taken with (a hash of csrc/ is stored with the by
 
     python bench_traffic.py --workload c3_128k \
         --fetch <dir>/f_counter_collection.csv --write <dir>/w_counter_collection.csv \
-        --info gpurun_out/pmc_pass_c3_128k.json --summary profiles/<name>.md \
+        --info <dir>/pmc_pass_c3_128k.json --summary profiles/<name>.md \
         --command "<how the CSVs were made>"
 
 --info is the file the counter pass itself wrote: the configuration of the pass, the mean
