@@ -33,6 +33,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
 }
 
+// acc += a.lo * b.lo + a.hi * b.hi for two packed pairs of bf16 (one instruction; written as
+// assembly because the compiler's builtin for it takes the first pair of a packed vector
+// whatever element is asked for)
+__device__ __forceinline__ void dot2_bf16(float& acc, uint32_t a, uint32_t b) {
+  asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(acc) : "v"(a), "v"(b));
+}
+
 // ---- 16-byte vector loads of VEC consecutive elements widened to fp32 ------
 template <typename T> struct Vec;  // T = float: 4 elements; T = uint16_t (bf16 bits): 8 elements
 template <> struct Vec<float> {

@@ -345,16 +345,19 @@ __global__ __launch_bounds__(kRmThreads) void probe_rows_bias_weigh_kernel(
   constexpr int V = Vec<T>::N;
   constexpr int NI = 64 / V;
   typedef typename Vec<T>::raw raw_t;
-  extern __shared__ __attribute__((aligned(16))) float rw_lds[];   // [2][d]
+  constexpr int kRowLen = 64 * NI * V;                             // channels a wavefront covers
+  extern __shared__ __attribute__((aligned(16))) float rw_lds[];   // [2][kRowLen]
   __shared__ float red[4];
   const int rc = blockIdx.x, w = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const T* q = q_win + size_t(w) * m * d;
   float* mu = rw_lds;
-  float* iv = rw_lds + d;
-  for (int i = threadIdx.x * 4; i < d; i += kRmThreads * 4) {
-    *reinterpret_cast<f32x4*>(mu + i) = *reinterpret_cast<const f32x4*>(stat_in + size_t(w) * 3 * d + i);
-    *reinterpret_cast<f32x4*>(iv + i) = *reinterpret_cast<const f32x4*>(stat_in + size_t(w) * 3 * d + d + i);
+  float* iv = rw_lds + kRowLen;
+  // channels past d (rows shorter than a wavefront's 64 * NI * V) get mean 0 and weight 0
+  for (int i = threadIdx.x * 4; i < kRowLen; i += kRmThreads * 4) {
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    *reinterpret_cast<f32x4*>(mu + i) = i < d ? *reinterpret_cast<const f32x4*>(stat_in + size_t(w) * 3 * d + i) : zero;
+    *reinterpret_cast<f32x4*>(iv + i) = i < d ? *reinterpret_cast<const f32x4*>(stat_in + size_t(w) * 3 * d + d + i) : zero;
   }
   if (add_count != 0.f && rc == 0 && w == 0 && threadIdx.x == 0) stats[0] += add_count;
   __syncthreads();
@@ -365,25 +368,36 @@ __global__ __launch_bounds__(kRmThreads) void probe_rows_bias_weigh_kernel(
     for (int v = 0; v < V; ++v) acc[i][v] = 0.f;
   float a_sum = 0.f;
   const int r0 = rc * kRowChunk, r1 = min(r0 + kRowChunk, m);
-  for (int r = r0 + wave; r < r1; r += 4) {
-    raw_t x[NI];
+  auto load_row = [&](int r, raw_t (&x)[NI]) {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {                   // the whole row is requested before it is used
+    for (int i = 0; i < NI; ++i) {
       const int c = (lane + 64 * i) * V;
       x[i] = Vec<T>::load_raw(q + size_t(r) * d + (c < d ? c : 0));
     }
-    float f[NI][V];
+  };
+  raw_t x[NI];
+  if (r0 + wave < r1) load_row(r0 + wave, x);
+  for (int r = r0 + wave; r < r1; r += 4) {
+    // the wavefront's next row is requested before this one is used: a row's worth of loads is in
+    // flight the whole time (the last row asks for itself once more, which costs nothing that matters)
+    raw_t xn[NI];
+    load_row(r + 4 < r1 ? r + 4 : r, xn);
     float t = 0.f;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const int c = (lane + 64 * i) * V;
-      Vec<T>::widen(x[i], f[i]);
-      if (c < d) {
+      float f[V];
+      Vec<T>::widen(x[i], f);
+      f32x4 mu4[V / 4], iv4[V / 4];
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-          const float e = f[i][v] - mu[c + v];
-          t += e * e * iv[c + v];
-        }
+      for (int u = 0; u < V / 4; ++u) {
+        mu4[u] = *reinterpret_cast<const f32x4*>(mu + c + 4 * u);
+        iv4[u] = *reinterpret_cast<const f32x4*>(iv + c + 4 * u);
+      }
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        const float e = f[v] - mu4[v >> 2][v & 3];
+        t += e * e * iv4[v >> 2][v & 3];
       }
     }
     float a = wave_sum(t);                           // |phi_j|_1 of Eq. (7), the row's weight before normalisation
@@ -391,9 +405,14 @@ __global__ __launch_bounds__(kRmThreads) void probe_rows_bias_weigh_kernel(
     if (lane == 0) a_rows[size_t(w) * m_pad + r] = a;
     a_sum += a;
 #pragma unroll
-    for (int i = 0; i < NI; ++i)
+    for (int i = 0; i < NI; ++i) {
+      float f[V];
+      Vec<T>::widen(x[i], f);
 #pragma unroll
-      for (int v = 0; v < V; ++v) acc[i][v] += a * f[i][v];
+      for (int v = 0; v < V; ++v) acc[i][v] += a * f[v];
+    }
+#pragma unroll
+    for (int i = 0; i < NI; ++i) x[i] = xn[i];
   }
   // sum over the 4 wavefronts, in a fixed order: (0 + 2) + (1 + 3)
   __syncthreads();                                   // mean and 1/var are no longer needed
@@ -647,7 +666,7 @@ static int launch_probe_t(const actqkv_shape& sh, int batch, int m, const T* q_w
     hipLaunchKernelGGL(probe_chain_stats_kernel<T>, dim3((d + 31) / 32), dim3(1024), size_t(batch) * 64 * sizeof(float),
                        stream, q_win, part, stats, stat, batch, m, d, n_chunks, eps);
     hipLaunchKernelGGL(probe_rows_bias_weigh_kernel<T>, dim3(n_chunks, batch), dim3(kRmThreads),
-                       size_t(2) * d * sizeof(float), stream, q_win, stat, stats, float(batch) * float(m), mean_pooling,
+                       size_t(2) * 4096 * sizeof(float), stream, q_win, stat, stats, float(batch) * float(m), mean_pooling,
                        pprobe, asum, a_rows, m, m_pad, d, n_chunks, cl.asum_stride);
     hipLaunchKernelGGL(probe_chain_finish_kernel, dim3(batch), dim3(1024), size_t(d) * sizeof(float), stream, pprobe,
                        asum, a_rows, stat,

@@ -9,6 +9,9 @@
 #include "launch.h"
 #include "score_body.h"
 
+#include <algorithm>
+#include <mutex>
+
 namespace actqkv {
 
 template <typename T>
@@ -119,6 +122,141 @@ __global__ __launch_bounds__(1024) void score_blocks_per_head_kernel(
   }
 }
 
+// ---- many windows of ONE sequence against the same representative keys ----------------------
+// The prefill pass scores 32 consecutive windows in one call (seq_stride 0: they share the keys).
+// Then the dot products of Eq. (10) are a [windows x key_len] x [key_len x keys] contraction, and
+// a kernel that walks the keys once per window reads every key 32 times from the caches.  Here a
+// wavefront loads a tile of 32 keys ONCE, straight from memory in the matrix-core operand
+// layout (lane l: key l % 32, channels 8 (l / 32) .. + 8 of each step of 16 channels), and
+// multiplies it with the probes of 32 windows, which the workgroup keeps in LDS split into two
+// bf16 halves (p = hi + lo, |p - hi - lo| <= 2^-17 |p|: the products with bf16 keys are exact in
+// fp32, so the result is that of fp32 arithmetic up to the order of the additions).
+// D[window][key]: a lane ends with one key (column l % 32) and 16 windows (rows 4 (l / 32) +
+// 8 (i / 4) + i % 4), so the key's norm is the lane's own and the r keys of a block sit in
+// adjacent lanes.  grid (workgroups that take tiles round-robin, groups of 32 windows).
+constexpr int kSsWaves = 4;
+constexpr int kSsLoads = 16;    // 16-byte key loads a lane keeps in flight
+
+__device__ __forceinline__ void ss_split(float p, uint32_t& hi, uint32_t& lo) {
+  hi = f32_to_bf16_bits(p);
+  lo = f32_to_bf16_bits(p - __uint_as_float(hi << 16));
+}
+
+__global__ __launch_bounds__(64 * kSsWaves) void score_shared_mfma_kernel(
+    const float* __restrict__ probe_kv, const float* __restrict__ probe_norm,
+    const uint16_t* __restrict__ rep_keys, int nb_capacity, int nb_begin, const int32_t* __restrict__ nb_end,
+    float* __restrict__ scores, int64_t score_stride, int batch, int n_rep, int key_len, float inv_sqrt_g) {
+  extern __shared__ __attribute__((aligned(16))) u32x4 ss_lds[];   // [hi, lo][key_len / 8][32 windows] x 8 bf16
+  const int chunks = key_len / 8;
+  const int w0 = blockIdx.y * 32;
+  u32x4* lds_hi = ss_lds;
+  u32x4* lds_lo = ss_lds + chunks * 32;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = lane >> 5, col = lane & 31;
+  const int n_keys = (nb_capacity - nb_begin) * n_rep;
+  const int n_tiles = (n_keys + 31) / 32;
+  const int steps = key_len / 16;                      // a multiple of kSsLoads (the launcher checks)
+  const uint16_t* keys0 = rep_keys + size_t(nb_begin) * n_rep * key_len + h * 8;
+  auto tile_keys = [&](int tile) {                     // the lane's key of a tile (a valid one for any tile)
+    return keys0 + size_t(min(min(tile, n_tiles - 1) * 32 + col, n_keys - 1)) * key_len;
+  };
+  // a ring of kSsLoads key loads per lane, refilled as it is used; its first round is in flight
+  // while the probes go to LDS
+  int tile = blockIdx.x * kSsWaves + wave;
+  const uint16_t* kp = tile_keys(tile);
+  u32x4 kb[kSsLoads];
+#pragma unroll
+  for (int i = 0; i < kSsLoads; ++i) kb[i] = *reinterpret_cast<const u32x4*>(kp + i * 16);
+
+  for (int e0 = threadIdx.x; e0 < chunks * 32; e0 += 4 * int(blockDim.x)) {
+    f32x4 a[4], b[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {                      // four chunks' loads before the first conversion
+      const int e = e0 + u * int(blockDim.x);
+      const int wl = e & 31, ch = e >> 5;
+      a[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+      b[u] = a[u];
+      if (e < chunks * 32 && w0 + wl < batch) {
+        const float* src = probe_kv + size_t(w0 + wl) * key_len + ch * 8;
+        a[u] = *reinterpret_cast<const f32x4*>(src);
+        b[u] = *reinterpret_cast<const f32x4*>(src + 4);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = e0 + u * int(blockDim.x);
+      if (e >= chunks * 32) break;
+      const float p[8] = {a[u].x, a[u].y, a[u].z, a[u].w, b[u].x, b[u].y, b[u].z, b[u].w};
+      uint32_t hi[8], lo[8];
+#pragma unroll
+      for (int v = 0; v < 8; ++v) ss_split(p[v], hi[v], lo[v]);
+      lds_hi[e] = u32x4{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16)};
+      lds_lo[e] = u32x4{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)};
+    }
+  }
+  // the lane's 16 windows: the probe's norm and the end of the eligible blocks
+  float pn_w[16];
+  int end_w[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int w = w0 + 4 * h + 8 * (i >> 2) + (i & 3);
+    const bool ok = w < batch;
+    pn_w[i] = ok ? probe_norm[w] : 0.f;
+    end_w[i] = ok ? min(nb_end[w], nb_capacity) : 0;
+  }
+  __syncthreads();
+  const int stride = gridDim.x * kSsWaves;
+  while (tile < n_tiles) {
+    const uint16_t* kp_next = tile_keys(tile + stride);
+    f32x16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    float nrm = 0.f;
+    for (int s0 = 0; s0 < steps; s0 += kSsLoads) {
+      const uint16_t* refill = s0 + kSsLoads < steps ? kp + size_t(s0 + kSsLoads) * 16 : kp_next;
+#pragma unroll
+      for (int i = 0; i < kSsLoads; ++i) {
+        const int at = ((s0 + i) * 2 + h) * 32 + col;
+        const bf16x8 k8 = __builtin_bit_cast(bf16x8, kb[i]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, lds_hi[at]), k8, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, lds_lo[at]), k8, acc, 0, 0, 0);
+        dot2_bf16(nrm, kb[i].x, kb[i].x);
+        dot2_bf16(nrm, kb[i].y, kb[i].y);
+        dot2_bf16(nrm, kb[i].z, kb[i].z);
+        dot2_bf16(nrm, kb[i].w, kb[i].w);
+        kb[i] = *reinterpret_cast<const u32x4*>(refill + i * 16);
+      }
+    }
+    nrm += lane_xor_f32<32>(nrm);                      // the other half of the key's channels
+    const float kn = sqrtf(nrm);
+    const int kk = tile * 32 + col;
+    const bool live = kk < n_keys && nrm > 0.f;
+    const int b = nb_begin + kk / n_rep;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      float c = (live && pn_w[i] > 0.f) ? acc[i] * inv_sqrt_g / (pn_w[i] * kn) : 0.f;
+      if (n_rep >= 2) c += lane_xor_f32<1>(c);
+      if (n_rep >= 4) c += lane_xor_f32<2>(c);
+      if (kk % n_rep == 0 && b < end_w[i])
+        scores[size_t(w0 + 4 * h + 8 * (i >> 2) + (i & 3)) * score_stride + b] = c / float(n_rep);
+    }
+    tile += stride;
+    kp = kp_next;
+  }
+}
+
+static int score_shared_lds_attribute(size_t bytes) {
+  static std::mutex mu;
+  static size_t set_for = 0;
+  std::lock_guard<std::mutex> lock(mu);
+  if (bytes <= set_for) return ACTQKV_OK;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_shared_mfma_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(bytes));
+  if (e != hipSuccess) return set_error(ACTQKV_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+  set_for = bytes;
+  return ACTQKV_OK;
+}
+
 int launch_score_per_head(const actqkv_shape& sh, int batch, const float* probe, const void* rep_keys,
                           int64_t seq_stride, int nb_capacity, int nb_begin, const int32_t* nb_end,
                           float* scores, int64_t score_stride, hipStream_t stream) {
@@ -147,6 +285,18 @@ int launch_score(const actqkv_shape& sh, int batch, const float* probe_kv, const
   if (n <= 0) return ACTQKV_OK;
   const int key_len = sh.n_kv_heads * sh.head_dim;
   const float inv_sqrt_g = 1.f / sqrtf(float(sh.n_q_heads / sh.n_kv_heads));
+  // Several windows of one sequence (they share the keys): the matrix-core kernel, which reads the keys once.
+  if (sh.dtype == ACTQKV_BF16 && batch >= 4 && seq_stride == 0 && key_len % (16 * kSsLoads) == 0 && key_len <= 1024 &&
+      (sh.n_rep == 1 || sh.n_rep == 2 || sh.n_rep == 4)) {
+    const size_t lds = size_t(key_len) * 128;          // 32 windows x key_len x (hi, lo) bf16
+    if (int rc = score_shared_lds_attribute(lds)) return rc;
+    const int n_tiles = (n * sh.n_rep + 31) / 32;
+    dim3 grid(std::min((n_tiles + kSsWaves - 1) / kSsWaves, 64), (batch + 31) / 32), block(64 * kSsWaves);
+    hipLaunchKernelGGL(score_shared_mfma_kernel, grid, block, lds, stream, probe_kv, probe_norm,
+                       static_cast<const uint16_t*>(rep_keys), nb_capacity, nb_begin, nb_end, scores, score_stride,
+                       batch, sh.n_rep, key_len, inv_sqrt_g);
+    return hip_status("score_blocks");
+  }
   // One wavefront per block.  A single long sequence (prefill) gets at most 64 workgroups,
   // so that the kernel fits beside a prefill attention that leaves 64 compute units free.
   int waves = 4;

@@ -1708,6 +1708,48 @@ def test_scores_on_random_shapes():
                 assert np.abs(f64(fused[s_, nb_begin:e]) - want).max() < TOL_SCORE, (trial, s_)
 
 
+@pytest.mark.parametrize("hkv,group,d,n_rep,bt,nb", [
+    (8, 4, 128, 4, 32, 300),     # the benchmarked shape: 32 windows of one call, more than one round of tiles
+    (8, 4, 128, 4, 37, 75),      # a second, ragged group of windows; blocks that are no multiple of a tile
+    (4, 2, 128, 2, 5, 41),       # two keys a block, fewer windows than a tile has rows
+    (2, 3, 64, 1, 9, 130),       # one key a block, short keys
+    (8, 4, 128, 4, 4, 9),        # hardly a tile
+])
+def test_scores_of_many_windows_on_shared_keys(hkv, group, d, n_rep, bt, nb):
+    """Several windows of one sequence scored in one call (seq_stride 0, bf16): the matrix-core
+    kernel, every window with its own end of the eligible blocks, against the oracle window by
+    window; blocks at and beyond a window's end keep what the buffer held."""
+    sh = LayerShape(hkv * group, hkv, d, 128, n_rep, 128, 256, "bf16")
+    cs = B.c_shape(sh)
+    _say(f"[case] shared-key scores Hk{hkv} G{group} D{d} r{n_rep} windows {bt} blocks {nb}")
+    g = torch.Generator().manual_seed(1000 * bt + nb)
+    rep = (torch.randn(nb, n_rep, hkv, d, generator=g) * 1.3).to(torch.bfloat16)
+    rep[3] = 0                                                        # a block of zero keys scores 0
+    q = (torch.randn(bt, 1, hkv * group, d, generator=g) + 0.2).to(torch.bfloat16)
+    q[bt - 1] = 0                                                     # and so does a zero probe
+    rng = np.random.default_rng(nb)
+    ends = rng.integers(0, nb + 1, size=bt)
+    ends[0] = nb
+    nb_begin = 1
+    repd, qd = rep.to(DEV), q.to(DEV)
+    nb_end = torch.tensor(ends, dtype=torch.int32, device=DEV)
+    r = H.LayerRunner(sh, bt, 1, nb, 4, DEV)
+    B.build_probe(cs, bt, 1, qd, None, False, r.probe, r.probe_kv, r.probe_norm, None, r.workspace)
+    r.scores.fill_(-7.0)
+    B.score_blocks(cs, bt, r.probe_kv, r.probe_norm, repd, 0, nb, nb_begin, nb_end, r.scores, r.score_stride)
+    torch.cuda.synchronize()
+    got = f64(r.scores)
+    for s_ in range(bt):
+        e = max(int(ends[s_]), nb_begin)
+        assert (got[s_, :nb_begin] == -7.0).all() and (got[s_, e:] == -7.0).all(), s_
+        if e > nb_begin:
+            want = orc.block_scores(f64(q[s_, 0]).reshape(-1), f64(rep[nb_begin:e]), group)
+            assert np.abs(got[s_, nb_begin:e] - want).max() < TOL_SCORE, s_
+            if nb_begin <= 3 < e:
+                assert got[s_, 3] == 0.0
+    assert (got[bt - 1, nb_begin:max(int(ends[bt - 1]), nb_begin)] == 0.0).all()
+
+
 def test_probe_on_random_shapes():
     """30 random shapes (heads, channels, window lengths from 2 to 700, batch, storage type, mean
     pooling or not): two windows per sequence, statistics, weights, probe, its group sum and its
