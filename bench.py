@@ -575,9 +575,16 @@ def bench_prefill_host_cache(args, torch, B, H, synth):
             plan.budget.copy_(bud0)
         return host.run(q, k, v, k_store, v_store, repd, out, record=range(plan.n_windows))
 
-    rec = in_order()
+    gev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(plan.n_windows)]
+    runner.stats.zero_()
+    if bud0 is not None:
+        plan.budget.copy_(bud0)
+    rec = host.run(q, k, v, k_store, v_store, repd, out, record=range(plan.n_windows), gather_events=gev)
     torch.cuda.synchronize()
     blocks = sum(int(r["n_sel"]) for r in rec.values())
+    # the gather launches on their own: HIP events around every one of them in this pass
+    g_with = [t for t in range(plan.n_windows) if int(rec[t]["n_sel"]) > 0]
+    g_us = sum(gev[t][0].elapsed_time(gev[t][1]) for t in g_with) * 1e3
     steps = min(args.steps, 3)
     dt_order = timed(in_order, steps)
     out_order = out.clone()
@@ -608,6 +615,12 @@ def bench_prefill_host_cache(args, torch, B, H, synth):
                                  "write-back, attention",
                        "ms_per_step_window_order_one_stream": dt_order * 1e3,
                        "output_equals_window_order": same},
+            "gather": {"bound": "host link (pinned host memory -> HBM)", "kernel": "gather_blocks_kernel "
+                       "(actqkv_gather_blocks: the blocks one window selected, K and V)",
+                       "achieved": blocks * block_bytes / max(g_us, 1e-9) / 1e3, "unit": "GB/s",
+                       "launches_with_blocks": len(g_with), "avg_launch_us": g_us / max(len(g_with), 1),
+                       "bytes_per_launch": blocks * block_bytes / max(len(g_with), 1),
+                       "timing": "HIP events around every gather launch of one in-order pass"},
             "host_link": {"blocks_gathered_per_pass": blocks, "gather_bytes_per_pass": blocks * block_bytes,
                           "write_back_bytes_per_pass": wb_bytes,
                           "gather_GBps_over_the_whole_pass": blocks * block_bytes / dt / 1e9,

@@ -119,8 +119,8 @@ def main() -> int:
         lines += [f"* {k}: {v}" for k, v in sorted(info.items())]
         if "algorithmic_bytes_per_launch" in info:
             a = float(info["algorithmic_bytes_per_launch"])
-            lines += ["", f"Algorithmic bytes per launch at this pass's selection: {a / 1e6:.3f} MB; fetched / "
-                          f"algorithmic = {f_bytes / a:.3f}."]
+            lines += ["", f"Algorithmic bytes per launch at this pass's selection (reads and writes): "
+                          f"{a / 1e6:.3f} MB; (fetched + written) / algorithmic = {(f_bytes + w_bytes) / a:.3f}."]
     os.makedirs(os.path.dirname(os.path.abspath(args.summary)), exist_ok=True)
     with open(args.summary, "w") as f:
         f.write("\n".join(lines) + "\n")

@@ -568,11 +568,12 @@ class HostCachePrefill:
 
     def run(self, q: torch.Tensor, k_tok: torch.Tensor, v_tok: torch.Tensor, k_store: torch.Tensor,
             v_store: torch.Tensor, rep_keys: torch.Tensor, out: torch.Tensor,
-            record: Optional[Sequence[int]] = None) -> Dict[int, Dict[str, torch.Tensor]]:
+            record: Optional[Sequence[int]] = None, gather_events=None) -> Dict[int, Dict[str, torch.Tensor]]:
         """q, out [N][H][D]; k_tok, v_tok [N][Hk][D] on the device (the windows' new keys and
         values); k_store, v_store: the blocked cache of the whole context in pinned host memory
         (already holding every block a window can select, i.e. everything older than its local
-        span); rep_keys [nb][r][Hk][D] on the device."""
+        span); rep_keys [nb][r][Hk][D] on the device.  gather_events: optional per-window
+        (start, end) event pairs recorded around the window's actqkv_gather_blocks call."""
         r, plan = self.runner, self.plan
         sh, cs, bs = r.shape, r.cs, r.shape.block_size
         nb_begin = sh.n_init // bs
@@ -611,8 +612,12 @@ class HostCachePrefill:
                            r.scores, r.score_stride)
             B.select(1, r.scores, r.score_stride, nb_cap, nb_begin, plan.nb_end[t:t + 1], r.k_cap, bud, rest,
                      r.idx, r.n_sel, r.theta, r.budget)
+            if gather_events is not None:
+                gather_events[t][0].record()
             B.gather_blocks(cs, 1, k_store, v_store, 0, nb_store, r.idx, r.n_sel, r.k_cap, self.k_work[new],
                             self.v_work[new], 0, self.nb_work, self.slot0, self.idx_slots)
+            if gather_events is not None:
+                gather_events[t][1].record()
             B.retrieval_attention(cs, 1, rows, qw, self.k_work[new], self.v_work[new], 0, self.nb_work,
                                   self.n_ctx_work, self.idx_slots, r.n_sel, r.k_cap, out[w0:w0 + rows], None,
                                   self.workspace)
