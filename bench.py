@@ -385,7 +385,8 @@ def bench_recall(args, torch, B, H, synth, workload="c3_128k"):
             "by_planted_signal": out}
 
 
-def _recall_of(w, torch, B, H, synth):
+def _recall_of(w, torch, B, H, synth, selections=None):
+    """selections: an optional dict that receives, per variant, the lists (idx rows, counts)."""
     dev = "cuda:0"
     sh = w.shape
     cs = B.c_shape(sh)
@@ -406,16 +407,17 @@ def _recall_of(w, torch, B, H, synth):
     nb_end = torch.tensor(ends, dtype=torch.int32, device=dev)
     nb_end_ph = nb_end[:, None].expand(T, hk).contiguous()
     for t in range(T):
-        if ends[t] <= nb_begin:
-            continue
         for name, r in runs.items():
             flags = B.STATS_UPDATE | (B.PROBE_MEAN_POOLING if name == "mean" else 0)
             B.build_probe(cs, 1, m, q[t * m:(t + 1) * m], r.stats, flags, r.probe, r.probe_kv, r.probe_norm, None,
-                          r.workspace)
+                          r.workspace)           # (every window enters the running statistics)
+            if ends[t] <= nb_begin:
+                continue
             B.score_blocks(cs, 1, r.probe_kv, r.probe_norm, repd, 0, ends[t], nb_begin, nb_end[t:t + 1],
                            sc[name][t:t + 1], stride)
-        B.score_blocks_per_head(cs, 1, runs["probe"].probe, repd, 0, ends[t], nb_begin, nb_end_ph[t:t + 1],
-                                sc_ph[t:t + 1], stride)
+        if ends[t] > nb_begin:
+            B.score_blocks_per_head(cs, 1, runs["probe"].probe, repd, 0, ends[t], nb_begin, nb_end_ph[t:t + 1],
+                                    sc_ph[t:t + 1], stride)
     nb_max = max(ends)
     cut = [synth.cutoff_state(w, max(ends[t] - nb_begin, 0), t, 0) for t in range(T)]
     bud = torch.tensor([c[0] for c in cut], dtype=torch.float32, device=dev)
@@ -437,6 +439,8 @@ def _recall_of(w, torch, B, H, synth):
         return idx.cpu().tolist(), n.cpu().tolist()
 
     def tally(idx, n, per=1):
+        if selections is not None:
+            selections[len(selections)] = (idx, n)
         hit = sel = tot = 0
         for row in range(len(n)):
             t = row // per

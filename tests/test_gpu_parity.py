@@ -1935,6 +1935,65 @@ def test_cutoff_history_across_layers_and_steps():
     assert np.allclose(theta_sum.cpu().numpy() / steps, np.array([h.means() for h in hists]), rtol=1e-5)
 
 
+def test_planted_block_recall_per_variant_equals_the_oracles():
+    """The recall statistic bench.py reports for the retrieval variants of the ablation (Sec. 5.3,
+    Table 3), on a reduced workload with strongly planted blocks: computed from the library's
+    selections and from the oracle's, variant by variant (probe-Query or mean pooling, fixed k or
+    cut-off, one selection or one per KV head)."""
+    import bench
+    base = synth.scaled(synth.WORKLOADS["c3_128k"], n_ctx=16384, alpha=16.0, shift=2.0, n_planted=12)
+    sh, m, kc = base.shape, base.window, base.k_cap
+    _say("[case] recall per variant, 16K tokens, strong planted signal")
+    sel_gpu = {}
+    got = bench._recall_of(base, torch, B, H, synth, sel_gpu)
+    # the order in which the bench takes its selections
+    sel_gpu = dict(zip(("probe_query_fixed_k", "mean_pooling_fixed_k", "per_kv_head_fixed_k", "probe_query_cutoff"),
+                       (sel_gpu[i] for i in range(4))))
+    q, k, _ = synth.gen_layer(base, DEV)         # the bench draws its inputs on the device: the same ones here
+    rep = f64(synth.pick_rep_keys(k, sh.block_size, sh.n_rep))
+    planted = set(synth.planted_blocks(base))
+    T = base.n_ctx // m
+    nb_begin = sh.n_init // sh.block_size
+    stats = orc.RunningStats(sh.d_model)
+    tally = {n: [0, 0, 0] for n in sel_gpu}
+    near_cut = 5e-4          # the GPU's probe is an fp32 one: blocks this close to the cut may change sides
+    for t in range(T):
+        flat = f64(q[t * m:(t + 1) * m]).reshape(m, -1)
+        z, s2 = stats.update(flat)
+        probe, _ = orc.probe_query(flat, orc.activation_bias(flat, z, s2))
+        pooled, _ = orc.probe_query(flat, np.ones_like(flat))
+        w0 = t * m
+        end = H.eligible_range(sh, w0)[1]
+        cut = synth.cutoff_state(base, max(end - nb_begin, 0), t, 0)
+        sels = {"probe_query_fixed_k": [orc.retrieve(probe, rep, w0, sh.n_init, sh.n_local, 128, sh.group, kc)],
+                "mean_pooling_fixed_k": [orc.retrieve(pooled, rep, w0, sh.n_init, sh.n_local, 128, sh.group, kc)],
+                "probe_query_cutoff": [orc.retrieve(probe, rep, w0, sh.n_init, sh.n_local, 128, sh.group, kc, cut)],
+                "per_kv_head_fixed_k": orc.retrieve_per_head(probe, rep, w0, sh.n_init, sh.n_local, 128, sh.group, kc)}
+        p = {b for b in planted if nb_begin <= b < end}
+        for name, rows in sels.items():
+            for j, res in enumerate(rows):
+                row = t * len(rows) + j
+                gi, gn = sel_gpu[name][0][row], sel_gpu[name][1][row]
+                assert gn == res["count"], (name, t, j)
+                differ = set(gi[:gn]) ^ set(res["idx"])
+                if differ:
+                    score_of = dict(zip(res["eligible"], res["scores"]))
+                    kth = sorted(res["scores"], reverse=True)[res["count"] - 1]
+                    assert all(abs(score_of[b] - kth) < near_cut for b in differ), (name, t, j, differ)
+                if p:
+                    tally[name][0] += len(set(res["idx"]) & p)
+                    tally[name][1] += len(res["idx"])
+                    tally[name][2] += len(p)
+    for name, (hit, sel, tot) in tally.items():
+        want_recall, want_prec = hit / max(tot, 1), hit / max(sel, 1)
+        _say(f"  {name}: recall {got[name]['recall']:.4f} (oracle {want_recall:.4f}), "
+             f"precision {got[name]['precision']:.4f} (oracle {want_prec:.4f})")
+        # blocks that all but tie at the cut may change sides: a few hits either way
+        assert abs(got[name]["recall"] - want_recall) <= 0.01, name
+        assert abs(got[name]["precision"] - want_prec) <= 0.01, name
+    assert got["probe_query_fixed_k"]["recall"] > got["mean_pooling_fixed_k"]["recall"]
+
+
 @pytest.mark.parametrize("topk", [False, True])
 def test_algorithm_1_in_its_three_loops(topk):
     """Alg. 1 as it is printed: the density of every layer first (actqkv_select, density only),
