@@ -656,13 +656,7 @@ def bench_decode(args, torch, B, H, synth):
         planted = torch.stack([torch.tensor(synth.planted_blocks(w, l, s)) for s in range(bt)]).to(dev)
         sidx = torch.arange(bt, device=dev)[:, None].expand_as(planted)
         kc[l][sidx, planted] += (w.shift * u)[None, None, :, None, :].to(torch.bfloat16)
-        # representative keys: the r tokens of a block with the largest key norm over all KV heads
-        norms = kc[l].float().pow(2).sum(dim=(2, 4))                      # [bt][nb][Bs]
-        top = torch.sort(norms, dim=2, descending=True, stable=True).indices[:, :, : sh.n_rep]
-        top = torch.sort(top, dim=2).values
-        src = kc[l].permute(0, 1, 3, 2, 4)                                # [bt][nb][Bs][Hk][D]
-        rep[l] = torch.gather(src, 2, top[:, :, :, None, None].expand(bt, nb_cap, sh.n_rep, hk, D))
-        del norms, top
+        rep[l] = synth.pick_rep_keys_blocked(kc[l], sh.n_rep)
     u_hat = u.repeat_interleave(sh.group, dim=0)
     q_all = torch.randn(steps, L, bt, 1, sh.n_q_heads, D, generator=gen, device=dev) + w.alpha * u_hat
     q_all = q_all.to(torch.bfloat16)

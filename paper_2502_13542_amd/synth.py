@@ -270,6 +270,17 @@ def pick_rep_keys(k: torch.Tensor, block_size: int, n_rep: int) -> torch.Tensor:
     return rep.reshape(nb, n_rep, hk, d).contiguous()
 
 
+def pick_rep_keys_blocked(kc: torch.Tensor, n_rep: int) -> torch.Tensor:
+    """The same rule on a cache in the blocked layout: kc [batch][nb][Hk][Bs][D] ->
+    [batch][nb][r][Hk][D] (every block is taken as complete)."""
+    bt, nb, hk, bs, d = kc.shape
+    norms = kc.float().pow(2).sum(dim=(2, 4))                              # [batch][nb][Bs]
+    top = torch.sort(norms, dim=2, descending=True, stable=True).indices[:, :, :n_rep]
+    top = torch.sort(top, dim=2).values                                    # position order
+    src = kc.permute(0, 1, 3, 2, 4)                                        # [batch][nb][Bs][Hk][D] view
+    return torch.gather(src, 2, top[:, :, :, None, None].expand(bt, nb, n_rep, hk, d))
+
+
 # --------------------------------------------------------------------------
 # dynamic cut-off state
 # --------------------------------------------------------------------------

@@ -222,6 +222,43 @@ def test_decode_select_attention_rejects(lib):
     assert call(shape=fp32) == -2                                               # a bf16, head_dim 128 kernel
 
 
+def test_decode_layer_rejects(lib):
+    """The whole decode layer in one launch: everything is refused on the host before a kernel runs."""
+    cs = B.c_shape(LLAMA)
+    call = lambda **k: lib.actqkv_decode_layer(
+        ctypes.byref(k.get("shape", cs)), k.get("batch", 1), k.get("q", A16), k.get("kn", A16), k.get("vn", A16),
+        k.get("kc", A16), A16, k.get("cs", 0), k.get("rep", A16), k.get("rs", 0), k.get("cap", 64),
+        k.get("n_ctx", A16), 1, k.get("nb_end", A16), k.get("scores", A16), k.get("ss", 64), k.get("k_cap", 32),
+        k.get("flags", 0), k.get("bud"), k.get("rest"), k.get("after"), k.get("idx", A16), k.get("n_sel", A16),
+        None, None, k.get("out", A16), None, k.get("ws", A16), k.get("wsb", 1 << 30), None)
+    assert call(q=None) == -1 and call(kn=None) == -1 and b"together" in lib.actqkv_last_error()
+    assert call(kc=None) == -1 and call(rep=None) == -1 and call(kc=A16 + 2) == -3
+    assert call(n_ctx=None) == -1 and call(nb_end=None) == -1 and call(scores=None) == -1
+    assert call(idx=None) == -1 and call(n_sel=None) == -1 and call(out=None) == -1
+    assert call(cap=0) == -1 and call(cap=9000, ss=9000) == -2 and call(ss=10) == -1
+    assert call(k_cap=0) == -2 and call(k_cap=65) == -2
+    assert call(flags=2) == -1 and call(flags=8) == -1 and b"unknown flag" in lib.actqkv_last_error()
+    assert call(bud=A16) == -1 and call(bud=A16, rest=A16, after=A16) == -1
+    assert b"budget_after" in lib.actqkv_last_error()
+    assert call(batch=385) == -2 and b"batch" in lib.actqkv_last_error()
+    assert call(batch=2, cs=8) == -1 and call(batch=2, cs=1 << 40, rs=8) == -1 and call(cs=12) == -3
+    assert call(ws=None) == -4 and call(wsb=8) == -4
+    fp32 = B.c_shape(LayerShape(8, 2, 64, 128, 4, 128, 256, "fp32"))
+    assert call(shape=fp32) == -2
+
+
+def test_blocked_representatives_equal_the_token_major_rule():
+    """The harness rule for the representative keys of a synthetic cache, on a blocked cache and on
+    token-major keys: the same keys (it is an input recipe; the oracle's rule is pinned on its own)."""
+    import torch
+    from paper_2502_13542_amd import synth
+    g = torch.Generator().manual_seed(5)
+    k = torch.randn(3 * 128, 2, 16, generator=g)
+    k[130] = k[131]                                       # a tie: the earlier position wins
+    blocked = k.reshape(3, 128, 2, 16).permute(0, 2, 1, 3)[None].contiguous()
+    assert torch.equal(synth.pick_rep_keys(k, 128, 4), synth.pick_rep_keys_blocked(blocked, 4)[0])
+
+
 def test_retrieval_attention_teams_rejects(lib):
     cs = B.c_shape(LLAMA)
     call = lambda **k: lib.actqkv_retrieval_attention_teams(

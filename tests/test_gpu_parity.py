@@ -975,13 +975,7 @@ def test_decode_full_size_layer_as_benchmarked():
     sidx = torch.arange(bt, device=DEV)[:, None].expand_as(planted)
     kc[sidx, planted] += (w.shift * u)[None, None, :, None, :].to(torch.bfloat16)
     cs = B.c_shape(sh)
-    # representative keys of the cached blocks: largest key norm over all KV heads, position order
-    rep = torch.zeros(bt, nb_cap, sh.n_rep, hk, D, dtype=torch.bfloat16, device=DEV)
-    src = kc.permute(0, 1, 3, 2, 4)                                   # [bt][nb][Bs][Hk][D] view
-    norms = kc.float().pow(2).sum(dim=(2, 4))                         # [bt][nb][Bs]
-    top = torch.sort(torch.sort(norms, dim=2, descending=True, stable=True).indices[:, :, : sh.n_rep], dim=2).values
-    rep.copy_(torch.gather(src, 2, top[:, :, :, None, None].expand(bt, nb_cap, sh.n_rep, hk, D)))
-    del norms, src
+    rep = synth.pick_rep_keys_blocked(kc, sh.n_rep).contiguous()      # the harness rule for synthetic caches
     q = (torch.randn(bt, 1, sh.n_q_heads, D, generator=gen, device=DEV) +
          w.alpha * u.repeat_interleave(sh.group, dim=0)).to(torch.bfloat16)
     k_new = torch.randn(bt, 1, hk, D, generator=gen, device=DEV).to(torch.bfloat16)
