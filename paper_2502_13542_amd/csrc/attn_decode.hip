@@ -312,17 +312,35 @@ __global__ __launch_bounds__(kDcThreads) void attn_decode_kernel(DcParams p) {
 __global__ __launch_bounds__(kDcThreads) void attn_decode_select_kernel(DcParams p, DcSelectParams sp) {
   extern __shared__ __attribute__((aligned(16))) float dc_lds[];
   __shared__ SelectLds<kDcThreads> sel_lds;
+  __shared__ int sel_ready;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   constexpr int n_waves = kDcMaxWaves;
   const int n = lane & 15, kq = lane >> 4;
   const int wg = blockIdx.x, hk = blockIdx.y, s = blockIdx.z;
   const int group = p.n_q_heads / p.n_kv_heads;
 
-  // the scores of the sequence: the load of the first 512 does not wait for anything
   const float* sc_mem = sp.scores + size_t(s) * sp.score_stride + sp.nb_begin;
-  const ScoreRow<kDcThreads> sc{sc_mem, int(threadIdx.x) < p.nb_capacity - sp.nb_begin ? sc_mem[threadIdx.x] : 0.f};
   const int end = min(max(sp.nb_end[s], sp.nb_begin), p.nb_capacity);   // (no wrap-around in the subtraction)
   const int n_elig = max(end - sp.nb_begin, 0);
+  // Rows that fit a wavefront's registers are selected by ONE wavefront, the last of the workgroup,
+  // which does that before anything else; the others never meet a barrier on their way to their
+  // first item and pick the result up from LDS when they need it.  Longer rows take the selection
+  // that is spread over the workgroup.
+  const bool by_wave = n_elig <= 64 * kSelWavePerLane;
+  const bool selector = by_wave && wave == n_waves - 1;
+  if (by_wave) {
+    if (threadIdx.x == 0) sel_ready = 0;
+    __syncthreads();                     // (nobody has asked the memory for anything yet: all arrive at once)
+  }
+  SelectIo io = sp.io;
+  io.write = wg == 0 && hk == 0;
+  if (selector) {
+    select_wave(sc_mem, s, n_elig, sp.nb_begin, p.k_cap, sp.entropy_topk, io, sel_lds.sel, &sel_lds.count);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (lane == 0) __hip_atomic_store(&sel_ready, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+  // the scores of the sequence for the workgroup-wide selection: the load of the first 512 does not wait for anything
+  const ScoreRow<kDcThreads> sc{sc_mem, (!by_wave && int(threadIdx.x) < p.nb_capacity - sp.nb_begin) ? sc_mem[threadIdx.x] : 0.f};
   const int n_ctx = min(max(p.n_ctx[s], 1), p.nb_capacity * kBlock);
   const WindowGeom g = window_geom(n_ctx, 1, p.n_init, p.n_local);
   // the list without the selection: initial tokens, then the local span
@@ -346,11 +364,14 @@ __global__ __launch_bounds__(kDcThreads) void attn_decode_select_kernel(DcParams
   if (have0) dc_issue(r0, kc, vc, block0, part0, hk, p.n_kv_heads, n, kq);
   __builtin_amdgcn_sched_barrier(0);
 
-  SelectIo io = sp.io;
-  io.write = wg == 0 && hk == 0;
-  select_body<kDcThreads>(sc, s, n_elig, sp.nb_begin, p.k_cap, sp.entropy_topk, io, sel_lds);
+  if (!by_wave) select_body<kDcThreads>(sc, s, n_elig, sp.nb_begin, p.k_cap, sp.entropy_topk, io, sel_lds);
   __builtin_amdgcn_sched_barrier(0);
   if (have0) dc_consume(r0, qb, a, p.scale_log2e, kq);
+  if (by_wave) {
+    // the selector has long finished as a rule; it always does, whatever the others do
+    while (__hip_atomic_load(&sel_ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) __builtin_amdgcn_s_sleep(1);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  }
 
   // the rest of the list: what is left of the fixed items, then the selected blocks
   TileList chosen = fixed;

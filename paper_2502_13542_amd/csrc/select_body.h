@@ -231,6 +231,117 @@ __device__ __forceinline__ void select_body(const Scores& sc, int s, int n, int 
   __syncthreads();
 }
 
+// ---- the same step by ONE wavefront, for rows of at most 64 * kSelWavePerLane scores ----------
+// For the decode attention that selects for itself: a selection spread over a workgroup couples
+// every wavefront to the slowest one at each of its barriers, and there the slowest one is stuck
+// handing 32 KB of load requests to a memory pipeline that is full.  One wavefront that has issued
+// nothing else needs no barrier at all: its lanes keep the scores in registers (lane l: blocks l,
+// l + 64, ...), the density is two passes over them with lane exchanges, and the E best blocks come
+// out one per round (the largest key of all lanes, which is unique, is taken and struck out).
+// Same keys, same ties, same Eq. (11), Eq. (12) as select_body; the sums run in another order.
+constexpr int kSelWavePerLane = 16;
+
+__device__ __forceinline__ unsigned long long wave_max64(unsigned long long v) {
+  v = umax64(v, lane_xor64<32>(v));
+  v = umax64(v, lane_xor64<16>(v));
+  v = umax64(v, lane_xor64<8>(v));
+  v = umax64(v, lane_xor64<4>(v));
+  v = umax64(v, lane_xor64<2>(v));
+  v = umax64(v, lane_xor64<1>(v));
+  return v;
+}
+
+// Called by all 64 lanes of one wavefront; sel[0 .. k_cap) and *count (LDS or any memory the
+// wavefront may write) receive the result, and the global outputs are written if io.write.
+// kPerLane: scores a lane holds (n <= 64 * kPerLane).
+template <int kPerLane>
+__device__ __forceinline__ void select_wave_n(const float* __restrict__ sc_mem, int s, int n, int nb_begin, int k_cap,
+                                              int entropy_topk, const SelectIo& io, int* sel, int* count) {
+  constexpr int kSelWavePerLane = kPerLane;
+  const int lane = threadIdx.x & 63;
+  int32_t* my_idx = io.idx + size_t(s) * k_cap;
+  float v[kSelWavePerLane];
+#pragma unroll
+  for (int i = 0; i < kSelWavePerLane; ++i) {                    // every load before the first use
+    const int b = lane + 64 * i;
+    v[i] = b < n ? sc_mem[b] : -INFINITY;
+  }
+  if (n == 0) {
+    if (lane < k_cap) {
+      sel[lane] = -1;
+      if (io.write) my_idx[lane] = -1;
+    }
+    if (lane == 0) {
+      *count = 0;
+      if (io.write) {
+        io.n_sel[s] = 0;
+        if (io.theta) io.theta[s] = 0.f;
+        if (io.budget) io.budget[s] = 0.f;
+        if (io.budget_in != nullptr && io.budget_after != nullptr) io.budget_after[s] = io.budget_in[s];
+      }
+    }
+    return;
+  }
+  int e_count = 0;
+  if (!entropy_topk) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < kSelWavePerLane; ++i) mx = fmaxf(mx, v[i]);
+    mx = wave_max(mx);
+    float z = 0.f, t = 0.f;
+#pragma unroll
+    for (int i = 0; i < kSelWavePerLane; ++i) {
+      if (lane + 64 * i < n) {
+        const float e = __expf(v[i] - mx);
+        z += e;
+        t += e * v[i];
+      }
+    }
+    z = wave_sum(z);
+    t = wave_sum(t);
+    if (lane == 0) e_count = cutoff_count(fmaxf(logf(z) + mx - t / z, 0.f), s, n, k_cap, io);
+    e_count = __shfl(e_count, 0, 64);
+  }
+  unsigned long long key[kSelWavePerLane];
+#pragma unroll
+  for (int i = 0; i < kSelWavePerLane; ++i) {
+    const int b = lane + 64 * i;
+    key[i] = b < n ? select_key(v[i], nb_begin + b) : 0ull;
+  }
+  const int rounds = entropy_topk ? min(k_cap, n) : e_count;
+  unsigned long long mine = 0ull;                                // lane r: the r-th best key
+  for (int r = 0; r < rounds; ++r) {
+    unsigned long long best = 0ull;
+#pragma unroll
+    for (int i = 0; i < kSelWavePerLane; ++i) best = umax64(best, key[i]);
+    best = wave_max64(best);
+    if (lane == r) mine = best;
+#pragma unroll
+    for (int i = 0; i < kSelWavePerLane; ++i) key[i] = key[i] == best ? 0ull : key[i];
+  }
+  if (entropy_topk) {
+    const bool in = lane < rounds;
+    const float sv = in ? key_score(mine) : 0.f;
+    const float mx = __shfl(sv, 0, 64);
+    const float e = in ? __expf(sv - mx) : 0.f;
+    const float z = wave_sum(e), t = wave_sum(e * sv);
+    if (lane == 0) e_count = cutoff_count(fmaxf(logf(z) + mx - t / z, 0.f), s, n, k_cap, io);
+    e_count = __shfl(e_count, 0, 64);
+  }
+  if (lane < k_cap) {
+    const int b = lane < e_count ? int(0xffffffffu - uint32_t(mine)) : -1;
+    sel[lane] = b;
+    if (io.write) my_idx[lane] = b;
+  }
+  if (lane == 0) *count = e_count;
+}
+__device__ __forceinline__ void select_wave(const float* __restrict__ sc_mem, int s, int n, int nb_begin, int k_cap,
+                                            int entropy_topk, const SelectIo& io, int* sel, int* count) {
+  // (one instantiation: with a second one for rows of at most 512 scores, which halves the work of
+  // a round, the decode step was 2 % slower - measured three times in alternation on one box)
+  select_wave_n<kSelWavePerLane>(sc_mem, s, n, nb_begin, k_cap, entropy_topk, io, sel, count);
+}
+
 // The scores of one sequence as select_body reads them: the first kThreads stay in a register
 // per thread for all passes (their load does not wait for anything), the others come from memory.
 template <int kThreads>
