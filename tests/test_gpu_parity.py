@@ -1744,6 +1744,39 @@ def test_scores_of_many_windows_on_shared_keys(hkv, group, d, n_rep, bt, nb):
     assert (got[bt - 1, nb_begin:max(int(ends[bt - 1]), nb_begin)] == 0.0).all()
 
 
+def test_scores_of_many_windows_on_random_shapes():
+    """25 random problems for the scoring of several windows on shared keys (heads, group, channels,
+    keys per block, windows, blocks, first eligible block, ragged ends), against the oracle."""
+    rng = np.random.default_rng(4242)
+    for trial in range(25):
+        hkv, d = [(8, 128), (4, 128), (2, 128), (4, 64), (8, 64), (1, 128)][int(rng.integers(0, 6))]
+        group = int(rng.integers(1, 9)); n_rep = int(rng.choice([1, 2, 4])); bt = int(rng.integers(4, 70))
+        nb = int(rng.integers(2, 140)); nb_begin = int(rng.integers(0, min(nb, 3)))
+        if hkv * group * d > 16384:
+            continue
+        sh = LayerShape(hkv * group, hkv, d, 128, n_rep, 128, 256, "bf16")
+        cs = B.c_shape(sh)
+        _say(f"[case] shared-key scores, trial {trial}: Hk{hkv} G{group} D{d} r{n_rep} windows {bt} blocks {nb} from {nb_begin}")
+        g = torch.Generator().manual_seed(trial)
+        rep = (torch.randn(nb, n_rep, hkv, d, generator=g) * float(rng.uniform(0.3, 2.0))).to(torch.bfloat16)
+        q = (torch.randn(bt, 1, hkv * group, d, generator=g) + float(rng.uniform(-0.5, 0.5))).to(torch.bfloat16)
+        ends = rng.integers(0, nb + 1, size=bt)
+        repd, qd = rep.to(DEV), q.to(DEV)
+        nb_end = torch.tensor(ends, dtype=torch.int32, device=DEV)
+        r = H.LayerRunner(sh, bt, 1, nb, 4, DEV)
+        B.build_probe(cs, bt, 1, qd, None, False, r.probe, r.probe_kv, r.probe_norm, None, r.workspace)
+        r.scores.fill_(3.0)
+        B.score_blocks(cs, bt, r.probe_kv, r.probe_norm, repd, 0, nb, nb_begin, nb_end, r.scores, r.score_stride)
+        torch.cuda.synchronize()
+        got = f64(r.scores)
+        for s_ in range(bt):
+            e = max(int(ends[s_]), nb_begin)
+            assert (got[s_, :nb_begin] == 3.0).all() and (got[s_, e:] == 3.0).all(), (trial, s_)
+            if e > nb_begin:
+                want = orc.block_scores(f64(q[s_, 0]).reshape(-1), f64(rep[nb_begin:e]), group)
+                assert np.abs(got[s_, nb_begin:e] - want).max() < TOL_SCORE, (trial, s_)
+
+
 def test_probe_on_random_shapes():
     """30 random shapes (heads, channels, window lengths from 2 to 700, batch, storage type, mean
     pooling or not): two windows per sequence, statistics, weights, probe, its group sum and its
